@@ -1,0 +1,807 @@
+// fade_api.hip — libfade's C ABI: context, device state, the step sequence and the compress / decompress loops.
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/fade.h"
+#include "fade_kernels.h"
+
+namespace {
+
+struct Dims {
+  size_t B, T, D, H, Dh, Dc, De, dl, c, k, Kc;  // Kc: K of the conv product (k * D rounded up to 64)
+};
+
+// canonical blob order (see fade.h)
+enum ParamId {
+  P_E, P_GAMMA_E, P_BETA_E, P_GAMMA_L, P_BETA_L, P_WG, P_WV, P_WM, P_LAMBDA_M, P_WCONV, P_BCONV, P_WR, P_GAMMA_C,
+  P_BETA_C, P_WDOWN, P_WU, P_WUP, P_WC, P_LAMBDA_C, P_GAMMA_F, P_BETA_F, P_WFG, P_WFV, P_WF, P_GAMMA_O, P_BETA_O,
+  P_LAMBDA_O, P_WO, P_BO, P_COUNT
+};
+
+struct Layout {
+  size_t off[P_COUNT + 1];
+};
+
+Layout make_layout(const Dims &d) {
+  const size_t n[P_COUNT] = {
+      256 * d.D, d.D, d.D, d.D, d.D, d.D * d.c, d.D * d.c, d.Dc * d.Dh, 1, d.k * d.D * d.D, d.D, d.Dh * d.Dh, d.Dh, d.Dh,
+      d.Dh * d.dl, d.B * d.dl * d.dl, d.dl * d.Dh, d.Dh * d.Dh, 1, d.Dh, d.Dh, d.Dh * d.De, d.Dh * d.De, d.De * d.Dh,
+      d.Dh, d.Dh, 1, d.Dh * 256, 256};
+  Layout L;
+  size_t o = 0;
+  for (int i = 0; i < P_COUNT; ++i) { L.off[i] = o; o += n[i]; }
+  L.off[P_COUNT] = o;
+  return L;
+}
+
+int resolve_dims(const fade_config &cfg, Dims &d, std::string *why) {
+  auto bad = [&](const char *m) { if (why) *why = m; return FADE_E_BAD_CONFIG; };
+  d.B = cfg.B; d.T = cfg.T; d.D = cfg.D; d.H = cfg.H;
+  d.Dh = d.T * d.D; d.Dc = d.H; d.De = d.H;
+  d.dl = cfg.d_low ? cfg.d_low : 64;
+  d.k = cfg.conv_k ? cfg.conv_k : 3;
+  if (!d.B || !d.T || !d.D || !d.H) return bad("B, T, D, H must be positive");
+  if (cfg.cache_chunk) d.c = cfg.cache_chunk;
+  else { if (d.H % d.T) return bad("H is not a multiple of T and cache_chunk is 0"); d.c = d.H / d.T; }
+  if (!d.c || d.Dc % d.c) return bad("H is not a multiple of cache_chunk");
+  if (cfg.dtype > FADE_BF16 || cfg.update_mode > FADE_ONLINE_ADAM) return bad("unknown dtype or update_mode");
+  d.Kc = (d.k * d.D + 63) / 64 * 64;
+  return FADE_OK;
+}
+
+// what the kernels support on top of what the model needs
+int check_kernel_limits(const fade_config &cfg, const Dims &d, std::string *why) {
+  auto bad = [&](const char *m) { if (why) *why = m; return FADE_E_BAD_CONFIG; };
+  if (d.dl != 64) return bad("kernels need d_low == 64");
+  if (d.Dh % 128) return bad("kernels need T*D to be a multiple of 128");
+  if (d.H % 64 || d.H > 1024) return bad("kernels need H to be a multiple of 64, at most 1024");
+  if (d.c > 64) return bad("kernels need cache_chunk <= 64");
+  if (d.k > 4) return bad("kernels need conv_k <= 4");
+  if (cfg.dtype == FADE_BF16 ? (d.D % 32 != 0) : (d.D % 16 != 0)) return bad("kernels need D % 32 == 0 (bf16) or D % 16 == 0 (fp32)");
+  if (d.B * d.T > 0x7fffffffull / 4 || d.B > (1u << 20)) return bad("B too large");
+  return FADE_OK;
+}
+
+uint64_t fnv1a64(const void *p, size_t n) {
+  const unsigned char *b = static_cast<const unsigned char *>(p);
+  uint64_t h = 14695981039346656037ull;
+  for (size_t i = 0; i < n; ++i) { h ^= b[i]; h *= 1099511628211ull; }
+  return h;
+}
+
+constexpr size_t kHeaderBytes = 64;
+void wr16(uint8_t *p, uint32_t v) { p[0] = v & 0xff; p[1] = (v >> 8) & 0xff; }
+void wr32(uint8_t *p, uint32_t v) { for (int i = 0; i < 4; ++i) p[i] = (v >> (8 * i)) & 0xff; }
+void wr64(uint8_t *p, uint64_t v) { for (int i = 0; i < 8; ++i) p[i] = (v >> (8 * i)) & 0xff; }
+uint32_t rd16(const uint8_t *p) { return p[0] | (uint32_t)p[1] << 8; }
+uint32_t rd32(const uint8_t *p) { uint32_t v = 0; for (int i = 3; i >= 0; --i) v = (v << 8) | p[i]; return v; }
+uint64_t rd64(const uint8_t *p) { uint64_t v = 0; for (int i = 7; i >= 0; --i) v = (v << 8) | p[i]; return v; }
+uint32_t fbits(float f) { uint32_t u; std::memcpy(&u, &f, 4); return u; }
+
+}  // namespace
+
+struct fade_ctx {
+  fade_config cfg;
+  Dims d;
+  Layout lay;
+  bool bf16 = false, online = false;
+  size_t esz = 4;  // bytes per activation element
+  hipStream_t stream = nullptr;
+  bool own_stream = false;
+  std::string err;
+  std::vector<void *> allocs;
+
+  bool have_weights = false;
+  std::vector<float> loaded;
+  uint64_t weights_hash = 0;
+
+  // parameters
+  float *master = nullptr;                                   // fp32 blob on the device
+  float *E_c = nullptr, *Wg_c = nullptr, *Wv_c = nullptr;     // fp32-resident operands (bf16-rounded in the bf16 configuration)
+  void *tabXe = nullptr, *tabXl = nullptr;
+  float *tabXe32 = nullptr;
+  void *Wm_c = nullptr, *Wconv_c = nullptr, *Wr_c = nullptr, *Wdown_c = nullptr, *WU_c = nullptr, *Wup_c = nullptr,
+       *Wc_c = nullptr, *Wfgv_c = nullptr, *Wf_c = nullptr, *Wo_c = nullptr;
+
+  // activations of the current step
+  void *X = nullptr, *XL = nullptr, *M = nullptr, *Hg = nullptr, *Hl = nullptr, *Hmix = nullptr, *Ha = nullptr,
+       *Hc = nullptr, *V = nullptr, *Hexp = nullptr, *z = nullptr;
+  float *y = nullptr, *logits = nullptr, *stats_c = nullptr, *stats_f = nullptr, *stats_o = nullptr;
+  // kept for the backward pass (online mode only)
+  void *hm = nullptr, *alpha = nullptr, *sg = nullptr, *eg = nullptr, *ev = nullptr, *cv = nullptr;
+  float *GG = nullptr, *GV = nullptr;
+
+  // coder and step bookkeeping
+  CoderBufs cb{};
+  uint8_t *payload = nullptr;
+  uint32_t *in_len = nullptr;
+  size_t payload_cap = 0;
+  StepState *st = nullptr;
+  uint8_t *ones = nullptr;
+  int *dev_err = nullptr;
+  size_t loop_n = 0, loop_next = 0;  // job size and next step of the device-resident loop in progress
+  int loop_mode = 0;
+  bool enc_complete = false;
+
+  // profiling
+  bool profiling = false;
+  struct Ev { hipEvent_t a, b; int name; };
+  std::vector<Ev> events;
+  std::vector<std::string> prof_names;
+  std::vector<double> prof_ms;
+  std::vector<uint64_t> prof_n;
+
+  const float *P(int id) const { return master + lay.off[id]; }
+};
+
+namespace {
+
+int fail(fade_ctx *c, int code, const std::string &msg) {
+  if (c) c->err = msg;
+  return code;
+}
+int hip_fail(fade_ctx *c, hipError_t e, const char *what) {
+  return fail(c, e == hipErrorOutOfMemory ? FADE_E_OOM : FADE_E_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+#define HIP_TRY(ctx, call)                                \
+  do {                                                    \
+    hipError_t e_ = (call);                               \
+    if (e_ != hipSuccess) return hip_fail(ctx, e_, #call); \
+  } while (0)
+
+template <typename T> int dev_alloc(fade_ctx *c, T **p, size_t count) {
+  void *q = nullptr;
+  hipError_t e = hipMalloc(&q, (count ? count : 1) * sizeof(T));
+  if (e != hipSuccess) return hip_fail(c, e, "hipMalloc");
+  c->allocs.push_back(q);
+  *p = static_cast<T *>(q);
+  return FADE_OK;
+}
+int dev_alloc_bytes(fade_ctx *c, void **p, size_t bytes) {
+  uint8_t *q = nullptr;
+  int rc = dev_alloc(c, &q, bytes);
+  *p = q;
+  return rc;
+}
+
+// profiling: bracket a launch with two events on the context's stream
+struct Prof {
+  fade_ctx *c; int idx = -1;
+  Prof(fade_ctx *ctx, const char *name) : c(ctx) {
+    if (!c->profiling) return;
+    int id = -1;
+    for (size_t i = 0; i < c->prof_names.size(); ++i) if (c->prof_names[i] == name) id = (int)i;
+    if (id < 0) { id = (int)c->prof_names.size(); c->prof_names.push_back(name); c->prof_ms.push_back(0); c->prof_n.push_back(0); }
+    fade_ctx::Ev ev; ev.name = id;
+    if (hipEventCreate(&ev.a) != hipSuccess || hipEventCreate(&ev.b) != hipSuccess) return;
+    (void)hipEventRecord(ev.a, c->stream);
+    c->events.push_back(ev);
+    idx = (int)c->events.size() - 1;
+  }
+  ~Prof() { if (idx >= 0) (void)hipEventRecord(c->events[idx].b, c->stream); }
+};
+
+void prof_collect(fade_ctx *c) {
+  for (auto &ev : c->events) {
+    float ms = 0;
+    if (hipEventElapsedTime(&ms, ev.a, ev.b) == hipSuccess) { c->prof_ms[ev.name] += ms; c->prof_n[ev.name] += 1; }
+    (void)hipEventDestroy(ev.a); (void)hipEventDestroy(ev.b);
+  }
+  c->events.clear();
+}
+
+// ---------------------------------------------------------------------------------------------------
+// master weights -> compute copies (runs on the stream; repeated after every online update)
+// ---------------------------------------------------------------------------------------------------
+int prepare_compute(fade_ctx *c) {
+  const Dims &d = c->d;
+  hipStream_t s = c->stream;
+  if (c->bf16) {
+    HIP_TRY(c, fade_round_bf16(c->P(P_E), c->E_c, 256 * d.D, s));
+    HIP_TRY(c, fade_round_bf16(c->P(P_WG), c->Wg_c, d.D * d.c, s));
+    HIP_TRY(c, fade_round_bf16(c->P(P_WV), c->Wv_c, d.D * d.c, s));
+    HIP_TRY(c, fade_preshuffle(c->P(P_WM), nullptr, (int)d.Dc, (int)d.Dc, (int)d.Dh, 0, c->Wm_c, s));
+    HIP_TRY(c, fade_preshuffle(c->P(P_WCONV), nullptr, (int)(d.k * d.D), (int)d.Kc, (int)d.D, 0, c->Wconv_c, s));
+    HIP_TRY(c, fade_preshuffle(c->P(P_WR), nullptr, (int)d.Dh, (int)d.Dh, (int)d.Dh, 0, c->Wr_c, s));
+    HIP_TRY(c, fade_preshuffle(c->P(P_WDOWN), nullptr, (int)d.Dh, (int)d.Dh, (int)d.dl, 0, c->Wdown_c, s));
+    HIP_TRY(c, fade_preshuffle(c->P(P_WUP), nullptr, (int)d.dl, (int)d.dl, (int)d.Dh, 0, c->Wup_c, s));
+    HIP_TRY(c, fade_preshuffle(c->P(P_WC), nullptr, (int)d.Dh, (int)d.Dh, (int)d.Dh, 0, c->Wc_c, s));
+    HIP_TRY(c, fade_preshuffle(c->P(P_WFG), c->P(P_WFV), (int)d.Dh, (int)d.Dh, (int)(2 * d.De), 1, c->Wfgv_c, s));
+    HIP_TRY(c, fade_preshuffle(c->P(P_WF), nullptr, (int)d.De, (int)d.De, (int)d.Dh, 0, c->Wf_c, s));
+    HIP_TRY(c, fade_preshuffle(c->P(P_WO), nullptr, (int)d.Dh, (int)d.Dh, 256, 0, c->Wo_c, s));
+    HIP_TRY(c, fade_convert(c->P(P_WU), c->WU_c, d.B * d.dl * d.dl, true, s));
+  } else {
+    HIP_TRY(c, fade_virtual_copy(c->P(P_WCONV), nullptr, (int)(d.k * d.D), (int)d.Kc, (int)d.D, 0, static_cast<float *>(c->Wconv_c), s));
+    HIP_TRY(c, fade_virtual_copy(c->P(P_WFG), c->P(P_WFV), (int)d.Dh, (int)d.Dh, (int)(2 * d.De), 1, static_cast<float *>(c->Wfgv_c), s));
+  }
+  HIP_TRY(c, fade_tables(c->E_c, c->P(P_GAMMA_E), c->P(P_BETA_E), c->P(P_GAMMA_L), c->P(P_BETA_L), (int)d.D, c->tabXe,
+                         c->tabXl, c->tabXe32, c->bf16, s));
+  return FADE_OK;
+}
+
+int do_reset(fade_ctx *c) {
+  const Dims &d = c->d;
+  hipStream_t s = c->stream;
+  HIP_TRY(c, hipMemsetAsync(c->M, 0, d.B * d.Dc * c->esz, s));
+  HIP_TRY(c, hipMemsetAsync(c->dev_err, 0, sizeof(int), s));
+  if (c->have_weights) {
+    HIP_TRY(c, hipMemcpyAsync(c->master, c->loaded.data(), c->loaded.size() * sizeof(float), hipMemcpyHostToDevice, s));
+    int rc = prepare_compute(c);
+    if (rc) return rc;
+  }
+  c->enc_complete = false;
+  HIP_TRY(c, hipStreamSynchronize(s));
+  return FADE_OK;
+}
+
+// ---------------------------------------------------------------------------------------------------
+// one model step: windows -> logits -> (probabilities, table, coded symbol)
+// ---------------------------------------------------------------------------------------------------
+int forward(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint16_t *freq, float *probs) {
+  const Dims &d = c->d;
+  hipStream_t s = c->stream;
+  const bool bf = c->bf16;
+  const int B = (int)d.B, Dh = (int)d.Dh, SN = (int)(d.Dh / FADE_STATS_BN);
+  {
+    Prof p(c, "embed_cache");
+    EmbedArgs a{};
+    a.ws = ws; a.T = (int)d.T; a.D = (int)d.D; a.Dh = Dh; a.Dc = (int)d.Dc; a.c = (int)d.c;
+    a.tabXe = c->tabXe; a.tabXl = c->tabXl; a.tabXe32 = c->tabXe32; a.Wg = c->Wg_c; a.Wv = c->Wv_c;
+    a.X = c->X; a.XL = c->XL; a.M = c->M; a.GG = c->GG; a.GV = c->GV;
+    HIP_TRY(c, fade_embed_cache(a, B, bf, s));
+  }
+  {  // Eq. 4
+    Prof p(c, "gemm_conv");
+    GemmArgs g{};
+    g.M = (int)(d.B * d.T); g.N = (int)d.D; g.K = (int)d.Kc;
+    g.A = c->XL; g.T = (int)d.T; g.D = (int)d.D; g.taps = (int)d.k;
+    g.W = c->Wconv_c; g.C = c->Hl; g.ldc = (int)d.D; g.C2 = c->cv; g.bias = c->P(P_BCONV);
+    HIP_TRY(c, fade_gemm(GEMM_CONV, bf, g, s));
+  }
+  {  // Eq. 3
+    Prof p(c, "gemm_global");
+    GemmArgs g{};
+    g.M = B; g.N = Dh; g.K = (int)d.Dc;
+    g.A = c->M; g.lda = (int)d.Dc; g.W = c->Wm_c; g.C = c->Hg; g.ldc = Dh; g.C2 = c->hm; g.S1 = c->X; g.lam = c->P(P_LAMBDA_M);
+    HIP_TRY(c, fade_gemm(GEMM_GLOBAL, bf, g, s));
+  }
+  {  // Eq. 5-6
+    Prof p(c, "gemm_router");
+    GemmArgs g{};
+    g.M = B; g.N = Dh; g.K = Dh;
+    g.A = c->X; g.lda = Dh; g.W = c->Wr_c; g.C = c->Hmix; g.ldc = Dh; g.C2 = c->alpha; g.S1 = c->Hg; g.S2 = c->Hl;
+    g.stats_out = c->stats_c;
+    HIP_TRY(c, fade_gemm(GEMM_ROUTER, bf, g, s));
+  }
+  {  // Eq. 7: Down(LN(H_mix))
+    Prof p(c, "gemm_down");
+    GemmArgs g{};
+    g.M = B; g.N = (int)d.dl; g.K = Dh;
+    g.A = c->Hmix; g.lda = Dh; g.stats = c->stats_c; g.stats_n = SN; g.gamma = c->P(P_GAMMA_C); g.beta = c->P(P_BETA_C);
+    g.W = c->Wdown_c; g.C = c->y; g.ldc = (int)d.dl;
+    HIP_TRY(c, fade_gemm(GEMM_DOWN, bf, g, s));
+  }
+  {  // Eq. 7: the per-stream memory
+    Prof p(c, "bmm_wu");
+    HIP_TRY(c, fade_bmm(c->y, c->WU_c, c->z, B, bf, s));
+  }
+  {  // Eq. 7: Up
+    Prof p(c, "gemm_up");
+    GemmArgs g{};
+    g.M = B; g.N = Dh; g.K = (int)d.dl;
+    g.A = c->z; g.lda = (int)d.dl; g.W = c->Wup_c; g.C = c->Ha; g.ldc = Dh;
+    HIP_TRY(c, fade_gemm(GEMM_UP, bf, g, s));
+  }
+  {  // Eq. 8
+    Prof p(c, "gemm_gate");
+    GemmArgs g{};
+    g.M = B; g.N = Dh; g.K = Dh;
+    g.A = c->Hmix; g.lda = Dh; g.W = c->Wc_c; g.C = c->Hc; g.ldc = Dh; g.C2 = c->sg; g.S1 = c->Ha; g.S2 = c->Hmix;
+    g.lam = c->P(P_LAMBDA_C); g.stats_out = c->stats_f;
+    HIP_TRY(c, fade_gemm(GEMM_GATE, bf, g, s));
+  }
+  {  // Eq. 9
+    Prof p(c, "gemm_fnr_in");
+    GemmArgs g{};
+    g.M = B; g.N = (int)(2 * d.De); g.K = Dh;
+    g.A = c->Hc; g.lda = Dh; g.stats = c->stats_f; g.stats_n = SN; g.gamma = c->P(P_GAMMA_F); g.beta = c->P(P_BETA_F);
+    g.W = c->Wfgv_c; g.C = c->Hexp; g.ldc = (int)d.De; g.C2 = c->eg; g.C3 = c->ev;
+    HIP_TRY(c, fade_gemm(GEMM_FNR_IN, bf, g, s));
+  }
+  {  // Eq. 10: H_expand W_f (+ statistics for its LayerNorm)
+    Prof p(c, "gemm_fnr_out");
+    GemmArgs g{};
+    g.M = B; g.N = Dh; g.K = (int)d.De;
+    g.A = c->Hexp; g.lda = (int)d.De; g.W = c->Wf_c; g.C = c->V; g.ldc = Dh; g.stats_out = c->stats_o;
+    HIP_TRY(c, fade_gemm(GEMM_FNR_OUT, bf, g, s));
+  }
+  {  // Eq. 10's tail fused into the head's operand load; logits = H W_o + b_o
+    Prof p(c, "gemm_head");
+    GemmArgs g{};
+    g.M = B; g.N = 256; g.K = Dh;
+    g.A = c->V; g.A2 = c->Hc; g.lda = Dh; g.stats = c->stats_o; g.stats_n = SN; g.gamma = c->P(P_GAMMA_O); g.beta = c->P(P_BETA_O);
+    g.lam = c->P(P_LAMBDA_O); g.W = c->Wo_c; g.C = c->logits; g.ldc = 256; g.bias = c->P(P_BO);
+    HIP_TRY(c, fade_gemm(GEMM_HEAD, bf, g, s));
+  }
+  {
+    Prof p(c, "softmax_quant_code");
+    SqcArgs a{};
+    a.ws = ws; a.B = B; a.logits = c->logits; a.probs = probs; a.freq = freq; a.sym_base = sym_base; a.cb = c->cb;
+    HIP_TRY(c, fade_softmax_quant_code(a, mode, s));
+  }
+  return FADE_OK;
+}
+
+int check_dev_err(fade_ctx *c) {
+  int e = 0;
+  HIP_TRY(c, hipMemcpy(&e, c->dev_err, sizeof(int), hipMemcpyDeviceToHost));
+  if (e == 1) return fail(c, FADE_E_BUFFER_TOO_SMALL, "payload buffer exhausted");
+  if (e == 2) return fail(c, FADE_E_CORRUPT_STREAM, "decoder left its interval: payload does not match the model");
+  if (e == 3) return fail(c, FADE_E_NUMERIC, "non-finite probabilities");
+  return FADE_OK;
+}
+
+size_t payload_cap_for(size_t L) { return 2 * L + 16; }
+
+int ensure_payload(fade_ctx *c, size_t L) {
+  const size_t cap = payload_cap_for(L);
+  if (c->payload && c->payload_cap >= cap) return FADE_OK;
+  // grow only: older (smaller) buffers stay owned by the context until it is destroyed
+  uint8_t *p = nullptr;
+  int rc = dev_alloc(c, &p, c->d.B * cap);
+  if (rc) return rc;
+  c->payload = p;
+  c->payload_cap = cap;
+  c->cb.out = p; c->cb.in = p; c->cb.cap = cap;
+  return FADE_OK;
+}
+
+// the loop of Algorithm 1 on device-resident bytes, steps [first, first + count); mode is CODE_ENCODE or CODE_DECODE
+int run_loop(fade_ctx *c, uint8_t *bytes_dev, size_t n, size_t first, size_t count, int mode) {
+  const Dims &d = c->d;
+  hipStream_t s = c->stream;
+  const size_t L = (n + d.B - 1) / d.B;
+  const size_t last = (count == 0 || first + count > L) ? L : first + count;
+  WinSrc ws{};
+  ws.base = bytes_dev; ws.stride = (long long)L; ws.n = (long long)n; ws.active = nullptr; ws.st = c->st;
+  HIP_TRY(c, fade_step_set(c->st, (long long)first, s));
+  for (size_t i = first; i < last; ++i) {
+    if (i < d.T) {
+      Prof p(c, "code_uniform");
+      HIP_TRY(c, fade_code_uniform(ws, bytes_dev, (int)d.B, c->cb, mode, s));
+    } else {
+      int rc = forward(c, ws, mode, bytes_dev, nullptr, nullptr);
+      if (rc) return rc;
+    }
+    HIP_TRY(c, fade_step_advance(c->st, s));
+  }
+  c->loop_next = last;
+  if (mode == CODE_ENCODE && last == L && !c->enc_complete) {
+    HIP_TRY(c, fade_coder_finish(c->cb, (int)d.B, (long long)L, (long long)n, s));
+    c->enc_complete = true;
+  }
+  HIP_TRY(c, hipStreamSynchronize(s));
+  if (c->profiling) prof_collect(c);
+  return check_dev_err(c);
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------------
+// C ABI
+// ---------------------------------------------------------------------------------------------------
+extern "C" {
+
+size_t fade_weights_nbytes(const fade_config *cfg) {
+  Dims d;
+  if (!cfg || resolve_dims(*cfg, d, nullptr)) return 0;
+  return make_layout(d).off[P_COUNT] * sizeof(float);
+}
+
+void fade_destroy(fade_ctx *c) {
+  if (!c) return;
+  if (c->stream) (void)hipStreamSynchronize(c->stream);
+  for (auto &ev : c->events) { (void)hipEventDestroy(ev.a); (void)hipEventDestroy(ev.b); }
+  for (void *p : c->allocs) (void)hipFree(p);
+  if (c->own_stream && c->stream) (void)hipStreamDestroy(c->stream);
+  delete c;
+}
+
+int fade_create(const fade_config *cfg, fade_ctx **out) {
+  if (!cfg || !out) return FADE_E_INVALID_ARG;
+  *out = nullptr;
+  if (cfg->struct_size != sizeof(fade_config) || cfg->abi_version != FADE_ABI_VERSION) return FADE_E_INVALID_ARG;
+  Dims d;
+  std::string why;
+  int rc = resolve_dims(*cfg, d, &why);
+  if (rc) return rc;
+  rc = check_kernel_limits(*cfg, d, &why);
+  if (rc) return rc;
+  if (cfg->update_mode == FADE_ONLINE_ADAM) return FADE_E_BAD_CONFIG;  // the update step is not built yet
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device < 0 || cfg->device >= ndev) return FADE_E_HIP;
+  if (hipSetDevice(cfg->device) != hipSuccess) return FADE_E_HIP;
+  fade_ctx *c = new (std::nothrow) fade_ctx();
+  if (!c) return FADE_E_OOM;
+  c->cfg = *cfg;
+  if (c->cfg.lr == 0.0f) c->cfg.lr = 1e-3f;
+  if (c->cfg.beta1 == 0.0f) c->cfg.beta1 = 0.9f;
+  if (c->cfg.beta2 == 0.0f) c->cfg.beta2 = 0.999f;
+  if (c->cfg.eps == 0.0f) c->cfg.eps = 1e-8f;
+  c->d = d;
+  c->lay = make_layout(d);
+  c->bf16 = cfg->dtype == FADE_BF16;
+  c->online = cfg->update_mode == FADE_ONLINE_ADAM;
+  c->esz = c->bf16 ? 2 : 4;
+  if (cfg->hip_stream) c->stream = static_cast<hipStream_t>(cfg->hip_stream);
+  else {
+    if (hipStreamCreate(&c->stream) != hipSuccess) { delete c; return FADE_E_HIP; }
+    c->own_stream = true;
+  }
+  const size_t np = c->lay.off[P_COUNT], BDh = d.B * d.Dh;
+  const size_t SN = d.Dh / FADE_STATS_BN;
+  auto A = [&](void **p, size_t elems) { return dev_alloc_bytes(c, p, elems * c->esz); };
+#define TRY_ALLOC(expr) do { rc = (expr); if (rc) { fade_destroy(c); return rc; } } while (0)
+  TRY_ALLOC(dev_alloc(c, &c->master, np));
+  if (c->bf16) {
+    TRY_ALLOC(dev_alloc(c, &c->E_c, 256 * d.D));
+    TRY_ALLOC(dev_alloc(c, &c->Wg_c, d.D * d.c));
+    TRY_ALLOC(dev_alloc(c, &c->Wv_c, d.D * d.c));
+    TRY_ALLOC(A(&c->Wm_c, d.Dc * d.Dh));
+    TRY_ALLOC(A(&c->Wconv_c, d.Kc * d.D));
+    TRY_ALLOC(A(&c->Wr_c, d.Dh * d.Dh));
+    TRY_ALLOC(A(&c->Wdown_c, d.Dh * d.dl));
+    TRY_ALLOC(A(&c->WU_c, d.B * d.dl * d.dl));
+    TRY_ALLOC(A(&c->Wup_c, d.dl * d.Dh));
+    TRY_ALLOC(A(&c->Wc_c, d.Dh * d.Dh));
+    TRY_ALLOC(A(&c->Wfgv_c, d.Dh * 2 * d.De));
+    TRY_ALLOC(A(&c->Wf_c, d.De * d.Dh));
+    TRY_ALLOC(A(&c->Wo_c, d.Dh * 256));
+  } else {  // fp32: most operands are used straight from the master blob
+    c->E_c = c->master + c->lay.off[P_E];
+    c->Wg_c = c->master + c->lay.off[P_WG];
+    c->Wv_c = c->master + c->lay.off[P_WV];
+    c->Wm_c = c->master + c->lay.off[P_WM];
+    c->Wr_c = c->master + c->lay.off[P_WR];
+    c->Wdown_c = c->master + c->lay.off[P_WDOWN];
+    c->WU_c = c->master + c->lay.off[P_WU];
+    c->Wup_c = c->master + c->lay.off[P_WUP];
+    c->Wc_c = c->master + c->lay.off[P_WC];
+    c->Wf_c = c->master + c->lay.off[P_WF];
+    c->Wo_c = c->master + c->lay.off[P_WO];
+    TRY_ALLOC(A(&c->Wconv_c, d.Kc * d.D));
+    TRY_ALLOC(A(&c->Wfgv_c, d.Dh * 2 * d.De));
+  }
+  TRY_ALLOC(A(&c->tabXe, 256 * d.D));
+  TRY_ALLOC(A(&c->tabXl, 256 * d.D));
+  TRY_ALLOC(dev_alloc(c, &c->tabXe32, 256 * d.D));
+  for (void **p : {&c->X, &c->XL, &c->Hg, &c->Hl, &c->Hmix, &c->Ha, &c->Hc, &c->V}) TRY_ALLOC(A(p, BDh));
+  TRY_ALLOC(A(&c->M, d.B * d.Dc));
+  TRY_ALLOC(A(&c->Hexp, d.B * d.De));
+  TRY_ALLOC(A(&c->z, d.B * d.dl));
+  TRY_ALLOC(dev_alloc(c, &c->y, d.B * d.dl));
+  TRY_ALLOC(dev_alloc(c, &c->logits, d.B * 256));
+  TRY_ALLOC(dev_alloc(c, &c->stats_c, d.B * SN * 2));
+  TRY_ALLOC(dev_alloc(c, &c->stats_f, d.B * SN * 2));
+  TRY_ALLOC(dev_alloc(c, &c->stats_o, d.B * SN * 2));
+  if (c->online) {
+    for (void **p : {&c->hm, &c->alpha, &c->sg, &c->cv}) TRY_ALLOC(A(p, BDh));
+    TRY_ALLOC(A(&c->eg, d.B * d.De));
+    TRY_ALLOC(A(&c->ev, d.B * d.De));
+    TRY_ALLOC(dev_alloc(c, &c->GG, d.B * d.c));
+    TRY_ALLOC(dev_alloc(c, &c->GV, d.B * d.c));
+  }
+  for (uint32_t **p : {&c->cb.low, &c->cb.high, &c->cb.pending, &c->cb.bitbuf, &c->cb.nbits, &c->cb.pos, &c->cb.value, &c->cb.bitpos})
+    TRY_ALLOC(dev_alloc(c, p, d.B));
+  TRY_ALLOC(dev_alloc(c, &c->in_len, d.B));
+  c->cb.in_len = c->in_len;
+  TRY_ALLOC(dev_alloc(c, &c->st, 1));
+  TRY_ALLOC(dev_alloc(c, &c->ones, d.B));
+  TRY_ALLOC(dev_alloc(c, &c->dev_err, 1));
+  c->cb.err = c->dev_err;
+#undef TRY_ALLOC
+  if (hipMemsetAsync(c->ones, 1, d.B, c->stream) != hipSuccess || hipMemsetAsync(c->dev_err, 0, sizeof(int), c->stream) != hipSuccess ||
+      hipMemsetAsync(c->M, 0, d.B * d.Dc * c->esz, c->stream) != hipSuccess || hipStreamSynchronize(c->stream) != hipSuccess) {
+    fade_destroy(c);
+    return FADE_E_HIP;
+  }
+  *out = c;
+  return FADE_OK;
+}
+
+int fade_load_weights(fade_ctx *c, const void *blob_host, size_t nbytes) {
+  if (!c || !blob_host) return FADE_E_INVALID_ARG;
+  const size_t np = c->lay.off[P_COUNT];
+  if (nbytes != np * sizeof(float)) return fail(c, FADE_E_WEIGHTS_MISMATCH, "blob size does not match the configuration");
+  const float *f = static_cast<const float *>(blob_host);
+  for (size_t i = 0; i < np; ++i)
+    if (!std::isfinite(f[i])) return fail(c, FADE_E_NUMERIC, "non-finite weight");
+  c->loaded.assign(f, f + np);
+  c->weights_hash = fnv1a64(blob_host, nbytes);
+  c->have_weights = true;
+  return do_reset(c);
+}
+
+int fade_reset(fade_ctx *c) {
+  if (!c) return FADE_E_INVALID_ARG;
+  return do_reset(c);
+}
+
+int fade_step_probs(fade_ctx *c, const uint8_t *windows_dev, const uint8_t *active_dev, uint16_t *freq_dev, float *probs_dev) {
+  if (!c || !windows_dev) return FADE_E_INVALID_ARG;
+  if (!c->have_weights) return fail(c, FADE_E_NO_WEIGHTS, "no weights loaded");
+  WinSrc ws{};
+  ws.base = windows_dev; ws.stride = (long long)c->d.T; ws.n = 0; ws.active = active_dev ? active_dev : c->ones; ws.st = c->st;
+  HIP_TRY(c, fade_step_set(c->st, (long long)c->d.T, c->stream));
+  return forward(c, ws, CODE_NONE, nullptr, freq_dev, probs_dev);
+}
+
+int fade_step_update(fade_ctx *c, const uint8_t *targets_dev, const uint8_t *active_dev) {
+  if (!c || !targets_dev) return FADE_E_INVALID_ARG;
+  (void)active_dev;
+  return fail(c, FADE_E_BAD_CONFIG, "context is frozen");
+}
+
+size_t fade_encode_bound(const fade_ctx *c, size_t n) {
+  if (!c) return 0;
+  const size_t B = c->d.B, L = (n + B - 1) / B;
+  return kHeaderBytes + 4 * B + B * (2 * L + 8);
+}
+
+int fade_encode_device(fade_ctx *c, const uint8_t *src_dev, size_t n, size_t first_step, size_t n_steps) {
+  if (!c || (!src_dev && n)) return FADE_E_INVALID_ARG;
+  if (!c->have_weights) return fail(c, FADE_E_NO_WEIGHTS, "no weights loaded");
+  if (first_step == 0) {
+    int rc = do_reset(c);
+    if (rc) return rc;
+    rc = ensure_payload(c, (n + c->d.B - 1) / c->d.B);
+    if (rc) return rc;
+    HIP_TRY(c, fade_coder_init(c->cb, (int)c->d.B, 0, c->stream));
+    c->loop_n = n; c->loop_next = 0; c->loop_mode = CODE_ENCODE;
+  } else if (c->loop_mode != CODE_ENCODE || c->loop_n != n || c->loop_next != first_step) {
+    return fail(c, FADE_E_INVALID_ARG, "first_step does not continue the encode in progress");
+  }
+  return run_loop(c, const_cast<uint8_t *>(src_dev), n, first_step, n_steps, CODE_ENCODE);
+}
+
+int fade_payloads(fade_ctx *c, uint32_t *lengths_host, uint8_t *bytes_host, size_t cap, size_t *total) {
+  if (!c || !lengths_host || !total) return FADE_E_INVALID_ARG;
+  if (!c->enc_complete) return fail(c, FADE_E_INVALID_ARG, "no completed encode to read payloads from");
+  const size_t B = c->d.B;
+  HIP_TRY(c, hipMemcpy(lengths_host, c->cb.pos, B * sizeof(uint32_t), hipMemcpyDeviceToHost));
+  size_t sum = 0;
+  for (size_t b = 0; b < B; ++b) sum += lengths_host[b];
+  *total = sum;
+  if (sum > cap || (!bytes_host && sum)) return fail(c, FADE_E_BUFFER_TOO_SMALL, "payload buffer too small");
+  size_t pos = 0;
+  for (size_t b = 0; b < B; ++b) {
+    if (lengths_host[b])
+      HIP_TRY(c, hipMemcpyAsync(bytes_host + pos, c->payload + b * c->payload_cap, lengths_host[b], hipMemcpyDeviceToHost, c->stream));
+    pos += lengths_host[b];
+  }
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return FADE_OK;
+}
+
+int fade_decode_device(fade_ctx *c, const uint32_t *lengths_host, const uint8_t *bytes_host, size_t total, uint8_t *dst_dev,
+                       size_t n, size_t first_step, size_t n_steps) {
+  if (!c || (!dst_dev && n)) return FADE_E_INVALID_ARG;
+  if (!c->have_weights) return fail(c, FADE_E_NO_WEIGHTS, "no weights loaded");
+  const size_t B = c->d.B, L = (n + B - 1) / B;
+  if (first_step != 0) {
+    if (c->loop_mode != CODE_DECODE || c->loop_n != n || c->loop_next != first_step)
+      return fail(c, FADE_E_INVALID_ARG, "first_step does not continue the decode in progress");
+    return run_loop(c, dst_dev, n, first_step, n_steps, CODE_DECODE);
+  }
+  if (!lengths_host || (!bytes_host && total)) return FADE_E_INVALID_ARG;
+  int rc = do_reset(c);
+  if (rc) return rc;
+  rc = ensure_payload(c, L);
+  if (rc) return rc;
+  size_t pos = 0;
+  for (size_t b = 0; b < B; ++b) {
+    const size_t len = lengths_host[b];
+    if (len > c->payload_cap || len > total - pos) return fail(c, FADE_E_CORRUPT_STREAM, "payload length out of range");
+    const bool empty = b * L >= n;
+    if (empty != (len == 0)) return fail(c, FADE_E_CORRUPT_STREAM, "payload length does not match the stream split");
+    if (len) HIP_TRY(c, hipMemcpyAsync(c->payload + b * c->payload_cap, bytes_host + pos, len, hipMemcpyHostToDevice, c->stream));
+    pos += len;
+  }
+  if (pos != total) return fail(c, FADE_E_CORRUPT_STREAM, "trailing payload bytes");
+  HIP_TRY(c, hipMemcpyAsync(c->in_len, lengths_host, B * sizeof(uint32_t), hipMemcpyHostToDevice, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));  // the host buffers may be reused by the caller from here on
+  HIP_TRY(c, fade_coder_init(c->cb, (int)B, 1, c->stream));
+  c->loop_n = n; c->loop_next = 0; c->loop_mode = CODE_DECODE;
+  return run_loop(c, dst_dev, n, 0, n_steps, CODE_DECODE);
+}
+
+int fade_encode(fade_ctx *c, const uint8_t *src_host, size_t n, uint8_t *dst_host, size_t dst_cap, size_t *dst_len) {
+  if (!c || (!src_host && n) || !dst_host || !dst_len) return FADE_E_INVALID_ARG;
+  if (!c->have_weights) return fail(c, FADE_E_NO_WEIGHTS, "no weights loaded");
+  const size_t B = c->d.B;
+  uint8_t *src_dev = nullptr;
+  hipError_t e = hipMalloc(reinterpret_cast<void **>(&src_dev), n ? n : 1);
+  if (e != hipSuccess) return hip_fail(c, e, "hipMalloc(src)");
+  int rc = FADE_OK;
+  std::vector<uint32_t> lens(B);
+  size_t total = 0;
+  do {
+    if (n && (e = hipMemcpy(src_dev, src_host, n, hipMemcpyHostToDevice)) != hipSuccess) { rc = hip_fail(c, e, "upload"); break; }
+    if ((rc = fade_encode_device(c, src_dev, n, 0, 0))) break;
+    if ((e = hipMemcpy(lens.data(), c->cb.pos, B * sizeof(uint32_t), hipMemcpyDeviceToHost)) != hipSuccess) { rc = hip_fail(c, e, "lengths"); break; }
+    for (size_t b = 0; b < B; ++b) total += lens[b];
+    *dst_len = kHeaderBytes + 4 * B + total;
+    if (*dst_len > dst_cap) { rc = fail(c, FADE_E_BUFFER_TOO_SMALL, "dst_cap too small"); break; }
+    uint8_t *h = dst_host;
+    std::memset(h, 0, kHeaderBytes);
+    std::memcpy(h, "FADE", 4);
+    wr16(h + 4, 1);
+    h[6] = (uint8_t)c->cfg.dtype; h[7] = (uint8_t)c->cfg.update_mode;
+    wr16(h + 8, (uint32_t)c->d.T); wr16(h + 10, (uint32_t)c->d.D); wr32(h + 12, (uint32_t)c->d.H);
+    wr16(h + 16, (uint32_t)c->d.dl); wr16(h + 18, (uint32_t)c->d.c); wr16(h + 20, (uint32_t)c->d.k);
+    wr32(h + 24, (uint32_t)B);
+    wr32(h + 28, fbits(c->cfg.lr)); wr32(h + 32, fbits(c->cfg.beta1)); wr32(h + 36, fbits(c->cfg.beta2)); wr32(h + 40, fbits(c->cfg.eps));
+    wr64(h + 48, n); wr64(h + 56, c->weights_hash);
+    for (size_t b = 0; b < B; ++b) wr32(h + kHeaderBytes + 4 * b, lens[b]);
+    size_t got = 0;
+    rc = fade_payloads(c, lens.data(), dst_host + kHeaderBytes + 4 * B, dst_cap - kHeaderBytes - 4 * B, &got);
+  } while (0);
+  (void)hipFree(src_dev);
+  return rc;
+}
+
+int fade_decode(fade_ctx *c, const uint8_t *src_host, size_t src_len, uint8_t *dst_host, size_t dst_cap, size_t *dst_len) {
+  if (!c || !src_host || !dst_len) return FADE_E_INVALID_ARG;
+  if (!c->have_weights) return fail(c, FADE_E_NO_WEIGHTS, "no weights loaded");
+  const size_t B = c->d.B;
+  if (src_len < kHeaderBytes + 4 * B) return fail(c, FADE_E_CORRUPT_STREAM, "truncated header");
+  const uint8_t *h = src_host;
+  if (std::memcmp(h, "FADE", 4) != 0 || rd16(h + 4) != 1) return fail(c, FADE_E_CORRUPT_STREAM, "bad magic or version");
+  const bool same = h[6] == c->cfg.dtype && h[7] == c->cfg.update_mode && rd16(h + 8) == c->d.T && rd16(h + 10) == c->d.D &&
+                    rd32(h + 12) == c->d.H && rd16(h + 16) == c->d.dl && rd16(h + 18) == c->d.c && rd16(h + 20) == c->d.k &&
+                    rd32(h + 24) == B && rd32(h + 28) == fbits(c->cfg.lr) && rd32(h + 32) == fbits(c->cfg.beta1) &&
+                    rd32(h + 36) == fbits(c->cfg.beta2) && rd32(h + 40) == fbits(c->cfg.eps);
+  if (!same) return fail(c, FADE_E_BAD_CONFIG, "container was written with a different configuration");
+  if (rd64(h + 56) != c->weights_hash) return fail(c, FADE_E_WEIGHTS_MISMATCH, "container was written with different weights");
+  const uint64_t n64 = rd64(h + 48);
+  const size_t n = (size_t)n64;
+  *dst_len = n;
+  if (n > dst_cap || (!dst_host && n)) return fail(c, FADE_E_BUFFER_TOO_SMALL, "dst_cap too small");
+  std::vector<uint32_t> lens(B);
+  size_t total = 0;
+  const size_t body = src_len - kHeaderBytes - 4 * B;
+  for (size_t b = 0; b < B; ++b) {
+    lens[b] = rd32(h + kHeaderBytes + 4 * b);
+    if (lens[b] > body - total) return fail(c, FADE_E_CORRUPT_STREAM, "payload runs past the end");
+    total += lens[b];
+  }
+  if (total != body) return fail(c, FADE_E_CORRUPT_STREAM, "trailing bytes");
+  uint8_t *dst_dev = nullptr;
+  hipError_t e = hipMalloc(reinterpret_cast<void **>(&dst_dev), n ? n : 1);
+  if (e != hipSuccess) return hip_fail(c, e, "hipMalloc(dst)");
+  int rc = fade_decode_device(c, lens.data(), src_host + kHeaderBytes + 4 * B, total, dst_dev, n, 0, 0);
+  if (!rc && n && (e = hipMemcpy(dst_host, dst_dev, n, hipMemcpyDeviceToHost)) != hipSuccess) rc = hip_fail(c, e, "download");
+  (void)hipFree(dst_dev);
+  return rc;
+}
+
+int fade_quantize(fade_ctx *c, const float *probs_dev, size_t rows, uint16_t *freq_dev) {
+  if (!c || !probs_dev || !freq_dev) return FADE_E_INVALID_ARG;
+  HIP_TRY(c, hipMemsetAsync(c->dev_err, 0, sizeof(int), c->stream));
+  if (rows) HIP_TRY(c, fade_quantize_rows(probs_dev, rows, freq_dev, c->dev_err, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return check_dev_err(c);
+}
+
+static int coder_tables(fade_ctx *c, const uint16_t *freq_dev, uint8_t *sym_dev, size_t n_steps, size_t n_streams, uint8_t *buf_dev,
+                        size_t cap, uint32_t *len_dev, int mode) {
+  if (!c || (!freq_dev && n_steps) || (!sym_dev && n_steps) || !buf_dev || !len_dev || n_streams == 0) return FADE_E_INVALID_ARG;
+  hipStream_t s = c->stream;
+  // private coder state for n_streams streams
+  uint32_t *state = nullptr;
+  hipError_t e = hipMalloc(reinterpret_cast<void **>(&state), 8 * n_streams * sizeof(uint32_t));
+  if (e != hipSuccess) return hip_fail(c, e, "hipMalloc(coder state)");
+  CoderBufs cb{};
+  cb.low = state; cb.high = state + n_streams; cb.pending = state + 2 * n_streams; cb.bitbuf = state + 3 * n_streams;
+  cb.nbits = state + 4 * n_streams; cb.pos = state + 5 * n_streams; cb.value = state + 6 * n_streams; cb.bitpos = state + 7 * n_streams;
+  cb.out = buf_dev; cb.in = buf_dev; cb.in_len = len_dev; cb.cap = cap; cb.err = c->dev_err;
+  int rc = FADE_OK;
+  do {
+    if ((e = hipMemsetAsync(c->dev_err, 0, sizeof(int), s)) != hipSuccess) { rc = hip_fail(c, e, "memset"); break; }
+    if ((e = fade_coder_init(cb, (int)n_streams, mode == CODE_DECODE, s)) != hipSuccess) { rc = hip_fail(c, e, "coder_init"); break; }
+    for (size_t i = 0; i < n_steps && rc == FADE_OK; ++i) {
+      e = fade_code_tables(freq_dev + i * n_streams * 256, sym_dev + i * n_streams, (int)n_streams, cb, mode, s);
+      if (e != hipSuccess) rc = hip_fail(c, e, "code_tables");
+    }
+    if (rc) break;
+    if (mode == CODE_ENCODE) {
+      // every stream coded n_steps symbols: terminate all of them when there was anything to code
+      if (n_steps && (e = fade_coder_finish(cb, (int)n_streams, 1, (long long)n_streams, s)) != hipSuccess) { rc = hip_fail(c, e, "finish"); break; }
+      if ((e = hipMemcpyAsync(len_dev, cb.pos, n_streams * sizeof(uint32_t), hipMemcpyDeviceToDevice, s)) != hipSuccess) { rc = hip_fail(c, e, "copy"); break; }
+    }
+    if ((e = hipStreamSynchronize(s)) != hipSuccess) { rc = hip_fail(c, e, "sync"); break; }
+    rc = check_dev_err(c);
+  } while (0);
+  (void)hipFree(state);
+  return rc;
+}
+
+int fade_coder_encode_tables(fade_ctx *c, const uint16_t *freq_dev, const uint8_t *sym_dev, size_t n_steps, size_t n_streams,
+                             uint8_t *out_dev, size_t cap, uint32_t *len_dev) {
+  return coder_tables(c, freq_dev, const_cast<uint8_t *>(sym_dev), n_steps, n_streams, out_dev, cap, len_dev, CODE_ENCODE);
+}
+
+int fade_coder_decode_tables(fade_ctx *c, const uint16_t *freq_dev, size_t n_steps, size_t n_streams, const uint8_t *in_dev, size_t cap,
+                             const uint32_t *len_dev, uint8_t *sym_dev) {
+  return coder_tables(c, freq_dev, sym_dev, n_steps, n_streams, const_cast<uint8_t *>(in_dev), cap, const_cast<uint32_t *>(len_dev),
+                      CODE_DECODE);
+}
+
+size_t fade_tap(fade_ctx *c, int which, float *out_host, size_t cap_floats) {
+  if (!c) return 0;
+  const Dims &d = c->d;
+  const void *src = nullptr;
+  size_t width = 0;
+  bool is_f32 = false;
+  switch (which) {
+    case FADE_TAP_X: src = c->X; width = d.Dh; break;
+    case FADE_TAP_CACHE: src = c->M; width = d.Dc; break;
+    case FADE_TAP_H_GLOBAL: src = c->Hg; width = d.Dh; break;
+    case FADE_TAP_H_LOCAL: src = c->Hl; width = d.Dh; break;
+    case FADE_TAP_ALPHA: src = c->alpha; width = d.Dh; break;
+    case FADE_TAP_H_MIX: src = c->Hmix; width = d.Dh; break;
+    case FADE_TAP_Y_DOWN: src = c->y; width = d.dl; is_f32 = true; break;
+    case FADE_TAP_Z_BMM: src = c->z; width = d.dl; break;
+    case FADE_TAP_H_A: src = c->Ha; width = d.Dh; break;
+    case FADE_TAP_H_COARSE: src = c->Hc; width = d.Dh; break;
+    case FADE_TAP_H_EXPAND: src = c->Hexp; width = d.De; break;
+    case FADE_TAP_LOGITS: src = c->logits; width = 256; is_f32 = true; break;
+    default: return 0;  // H_out is never materialised (it lives in the head product's operand load); probs are an output
+  }
+  if (!src) return 0;
+  if (!out_host) return width;
+  const size_t n = d.B * width;
+  if (cap_floats < n) return 0;
+  if (hipStreamSynchronize(c->stream) != hipSuccess) return 0;
+  if (is_f32 || !c->bf16) {
+    if (hipMemcpy(out_host, src, n * sizeof(float), hipMemcpyDeviceToHost) != hipSuccess) return 0;
+  } else {
+    std::vector<uint16_t> tmp(n);
+    if (hipMemcpy(tmp.data(), src, n * 2, hipMemcpyDeviceToHost) != hipSuccess) return 0;
+    for (size_t i = 0; i < n; ++i) { uint32_t u = (uint32_t)tmp[i] << 16; std::memcpy(&out_host[i], &u, 4); }
+  }
+  return width;
+}
+
+int fade_get_weights(fade_ctx *c, void *blob_host, size_t nbytes) {
+  if (!c || !blob_host || nbytes != c->lay.off[P_COUNT] * sizeof(float)) return FADE_E_INVALID_ARG;
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  HIP_TRY(c, hipMemcpy(blob_host, c->master, nbytes, hipMemcpyDeviceToHost));
+  return FADE_OK;
+}
+
+int fade_profile(fade_ctx *c, int enable) {
+  if (!c) return FADE_E_INVALID_ARG;
+  c->profiling = enable != 0;
+  c->prof_names.clear(); c->prof_ms.clear(); c->prof_n.clear();
+  return FADE_OK;
+}
+
+int fade_profile_read(fade_ctx *c, const char **names, double *ms, uint64_t *launches, int cap) {
+  if (!c) return 0;
+  int n = 0;
+  for (size_t i = 0; i < c->prof_names.size() && n < cap; ++i, ++n) {
+    if (names) names[n] = c->prof_names[i].c_str();
+    if (ms) ms[n] = c->prof_ms[i];
+    if (launches) launches[n] = c->prof_n[i];
+  }
+  return n;
+}
+
+const char *fade_last_error(const fade_ctx *c) { return c ? c->err.c_str() : "null context"; }
+
+}  // extern "C"

@@ -1,0 +1,484 @@
+// fade_gemm.hip — the dense products of the model step with fused prologues and epilogues (gfx950).
+//
+// bf16 path: C[M][N] = A'[M][K] * W[K][N] on the matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulate).
+//   * 256 threads = 4 wavefronts arranged WM x WN; each wavefront owns TM x TN tiles of 32 x 32.
+//   * A' is formed on the fly (LayerNorm, the Eq. 10 tail, the causal-conv row gather), converted to bf16 and
+//     staged through LDS in blocks of 64 along K, double buffered.
+//   * W never touches LDS: at load time it is rearranged into MFMA fragment order (one contiguous 1 KiB
+//     read per wavefront and 32 x 16 fragment), so each wavefront streams its own columns straight from
+//     L2 into registers, one K block ahead.
+//   * The accumulators are parked in LDS (fp32) and re-read row-wise, so that every side input and every
+//     output moves in 16-byte pieces and per-row statistics for the next LayerNorm fall out of a 16-lane
+//     butterfly. Partial statistics are stored per 128-column tile and summed by the consumer in index
+//     order: no atomics, so the result is reproducible bit for bit.
+//   * blockIdx -> tile: the chip dispatches consecutive workgroups round-robin over its 8 XCDs, each with
+//     a private L2. Tiles are numbered so that one XCD owns a contiguous range of column tiles for all
+//     row tiles: each XCD then pulls only its 1/8 of W through its L2.
+// fp32 path (small-batch configuration): same prologues/epilogues around a plain FMA core.
+#include "fade_dev.h"
+#include "fade_kernels.h"
+
+namespace {
+
+__device__ __forceinline__ float gelu_f(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
+__device__ __forceinline__ float sigmoid_f(float x) { return 1.0f / (1.0f + expf(-x)); }
+
+// 8 consecutive activations <-> registers
+__device__ __forceinline__ void load8(const bf16_t *p, float v[8]) {
+  const bf16x8 r = *reinterpret_cast<const bf16x8 *>(p);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v[i] = (float)r[i];
+}
+__device__ __forceinline__ void load8(const float *p, float v[8]) {
+  const f32x4 a = *reinterpret_cast<const f32x4 *>(p), b = *reinterpret_cast<const f32x4 *>(p + 4);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { v[i] = a[i]; v[4 + i] = b[i]; }
+}
+__device__ __forceinline__ void store8(bf16_t *p, const float v[8]) {
+  bf16x8 r;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) r[i] = (bf16_t)v[i];
+  *reinterpret_cast<bf16x8 *>(p) = r;
+}
+__device__ __forceinline__ void store8(float *p, const float v[8]) {
+  f32x4 a, b;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { a[i] = v[i]; b[i] = v[4 + i]; }
+  *reinterpret_cast<f32x4 *>(p) = a;
+  *reinterpret_cast<f32x4 *>(p + 4) = b;
+}
+
+// ---------------------------------------------------------------------------------------------------
+// A-operand staging: one thread owns one 8-wide chunk of one row per pass.
+// ---------------------------------------------------------------------------------------------------
+template <typename AT> struct Raw8 { float v[8]; };
+template <> struct Raw8<bf16_t> { bf16x8 v; };
+
+template <typename AT> __device__ __forceinline__ void raw_zero(Raw8<AT> &r);
+template <> __device__ __forceinline__ void raw_zero<bf16_t>(Raw8<bf16_t> &r) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i) r.v[i] = (bf16_t)0.0f;
+}
+template <> __device__ __forceinline__ void raw_zero<float>(Raw8<float> &r) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i) r.v[i] = 0.0f;
+}
+__device__ __forceinline__ void raw_load(Raw8<bf16_t> &r, const bf16_t *p) { r.v = *reinterpret_cast<const bf16x8 *>(p); }
+__device__ __forceinline__ void raw_load(Raw8<float> &r, const float *p) { load8(p, r.v); }
+__device__ __forceinline__ void raw_to_float(const Raw8<bf16_t> &r, float v[8]) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v[i] = (float)r.v[i];
+}
+__device__ __forceinline__ void raw_to_float(const Raw8<float> &r, float v[8]) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v[i] = r.v[i];
+}
+
+// Issue the global loads for chunk (row m, columns k..k+7) of the A operand.
+template <int PRO, typename AT>
+__device__ __forceinline__ void stage_load(const GemmArgs &g, int m, int k, Raw8<AT> &a, Raw8<AT> &a2) {
+  const AT *A = static_cast<const AT *>(g.A);
+  if (m >= g.M) { raw_zero(a); if (PRO == PRO_FINAL) raw_zero(a2); return; }
+  if (PRO == PRO_CONV) {
+    const int b = m / g.T, j = m - b * g.T;
+    const int tap = k / g.D, i = k - tap * g.D;
+    const int tok = j - (g.taps - 1) + tap;
+    if (tap < g.taps && tok >= 0) raw_load(a, A + ((size_t)b * g.T + tok) * g.D + i);
+    else raw_zero(a);
+  } else {
+    raw_load(a, A + (size_t)m * g.lda + k);
+    if (PRO == PRO_FINAL) raw_load(a2, static_cast<const AT *>(g.A2) + (size_t)m * g.lda + k);
+  }
+}
+
+// Turn the loaded chunk into operand values.
+template <int PRO, typename AT>
+__device__ __forceinline__ void stage_transform(const GemmArgs &g, int k, const Raw8<AT> &a, const Raw8<AT> &a2,
+                                                float mean, float rstd, float lam, float v[8]) {
+  raw_to_float(a, v);
+  if (PRO == PRO_LN || PRO == PRO_FINAL) {
+    float ga[8], be[8];
+    load8(g.gamma + k, ga);
+    load8(g.beta + k, be);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = (v[i] - mean) * rstd * ga[i] + be[i];
+    if (PRO == PRO_FINAL) {
+      float r[8];
+      raw_to_float(a2, r);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = gelu_f(v[i]) + lam * r[i];
+    }
+  }
+}
+
+// mean / rstd of row m from the partial sums its producer left behind (fixed summation order).
+__device__ __forceinline__ void row_moments(const GemmArgs &g, int m, float &mean, float &rstd) {
+  mean = 0.0f; rstd = 1.0f;
+  if (m >= g.M) return;
+  float s = 0.0f, q = 0.0f;
+  const float *p = g.stats + (size_t)m * g.stats_n * 2;
+  for (int j = 0; j < g.stats_n; ++j) { s += p[2 * j]; q += p[2 * j + 1]; }
+  const float inv = 1.0f / (float)g.K;
+  mean = s * inv;
+  const float var = fmaxf(q * inv - mean * mean, 0.0f);
+  rstd = 1.0f / sqrtf(var + 1e-5f);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// epilogue: the accumulator tile sits in LDS as fp32 [BM][BN + 4]; threads walk it in 8-wide row chunks
+// ---------------------------------------------------------------------------------------------------
+template <int EPI, typename AT, int BM, int BN>
+__device__ __forceinline__ void epilogue(const GemmArgs &g, const float *Cs, int m0, int n0, int nt, int tid) {
+  constexpr int LDC = BN + 4;
+  constexpr int BNO = (EPI == EPI_GEGLU) ? BN / 2 : BN;  // output columns of this tile
+  constexpr int CH = BNO / 8;                            // chunks (threads) per row
+  constexpr int RP = 256 / CH;                           // rows per pass
+  const int c8 = (tid % CH) * 8, r0 = tid / CH;
+  const int nout0 = (EPI == EPI_GEGLU) ? nt * BNO : n0;  // first output column of the tile
+  float lam = 0.0f;
+  if (EPI == EPI_GLOBAL || EPI == EPI_GATE) lam = g.lam[0];
+#pragma unroll 1
+  for (int r = r0; r < BM; r += RP) {
+    const int m = m0 + r;
+    const bool live = m < g.M;
+    float x[8], out[8];
+    load8(Cs + r * LDC + c8, x);
+    const size_t o = (size_t)m * g.ldc + nout0 + c8;
+    if (live) {
+      if (EPI == EPI_STORE) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) out[i] = x[i];
+        store8(static_cast<AT *>(g.C) + o, out);
+      } else if (EPI == EPI_STORE_F32) {
+        float bi[8];
+        if (g.bias) load8(g.bias + n0 + c8, bi);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) out[i] = g.bias ? x[i] + bi[i] : x[i];
+        store8(static_cast<float *>(g.C) + o, out);
+      } else if (EPI == EPI_GLOBAL) {
+        float s1[8];
+        load8(static_cast<const AT *>(g.S1) + o, s1);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) out[i] = gelu_f(x[i]) + lam * s1[i];
+        store8(static_cast<AT *>(g.C) + o, out);
+        if (g.C2) store8(static_cast<AT *>(g.C2) + o, x);
+      } else if (EPI == EPI_MIX) {
+        float s1[8], s2[8], al[8];
+        load8(static_cast<const AT *>(g.S1) + o, s1);
+        load8(static_cast<const AT *>(g.S2) + o, s2);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { al[i] = sigmoid_f(x[i]); out[i] = al[i] * s1[i] + (1.0f - al[i]) * s2[i]; }
+        store8(static_cast<AT *>(g.C) + o, out);
+        if (g.C2) store8(static_cast<AT *>(g.C2) + o, al);
+      } else if (EPI == EPI_GATE) {
+        float s1[8], s2[8], sg[8];
+        load8(static_cast<const AT *>(g.S1) + o, s1);
+        load8(static_cast<const AT *>(g.S2) + o, s2);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { sg[i] = sigmoid_f(x[i]); out[i] = s1[i] * sg[i] + lam * s2[i]; }
+        store8(static_cast<AT *>(g.C) + o, out);
+        if (g.C2) store8(static_cast<AT *>(g.C2) + o, sg);
+      } else if (EPI == EPI_GEGLU) {
+        float xv[8];
+        load8(Cs + r * LDC + BNO + c8, xv);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) out[i] = gelu_f(x[i]) * xv[i];
+        store8(static_cast<AT *>(g.C) + o, out);
+        if (g.C2) store8(static_cast<AT *>(g.C2) + o, x);
+        if (g.C3) store8(static_cast<AT *>(g.C3) + o, xv);
+      } else if (EPI == EPI_CONV) {
+        float bi[8], pre[8];
+        load8(g.bias + n0 + c8, bi);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { pre[i] = x[i] + bi[i]; out[i] = gelu_f(pre[i]); }
+        store8(static_cast<AT *>(g.C) + o, out);
+        if (g.C2) store8(static_cast<AT *>(g.C2) + o, pre);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) out[i] = 0.0f;
+    }
+    if (g.stats_out && (EPI == EPI_STORE || EPI == EPI_MIX || EPI == EPI_GATE)) {
+      float s = 0.0f, q = 0.0f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { s += out[i]; q += out[i] * out[i]; }
+#pragma unroll
+      for (int off = CH / 2; off > 0; off >>= 1) { s += __shfl_xor(s, off, 64); q += __shfl_xor(q, off, 64); }
+      if (live && (tid % CH) == 0) {
+        float *p = g.stats_out + ((size_t)m * (g.N / BN) + nt) * 2;
+        p[0] = s; p[1] = q;
+      }
+    }
+  }
+}
+
+__device__ __forceinline__ void tile_of_block(int bid, int ntm, int ntn, int &mt, int &nt) {
+  if ((ntn & 7) == 0) {  // one XCD (bid % 8) owns ntn / 8 consecutive column tiles, for every row tile
+    const int x = bid & 7, r = bid >> 3, per = ntn >> 3;
+    nt = x * per + r % per;
+    mt = r / per;
+  } else {
+    nt = bid % ntn;
+    mt = bid / ntn;
+  }
+  (void)ntm;
+}
+
+// ---------------------------------------------------------------------------------------------------
+// bf16 MFMA core
+// ---------------------------------------------------------------------------------------------------
+template <int WM, int WN, int TM, int TN, int PRO, int EPI>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
+  typedef bf16_t AT;
+  constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = 64, LDA = BK + 8, PASSES = BM / 32, LDC = BN + 4;
+  static_assert(WM * WN == 4, "four wavefronts per workgroup");
+  extern __shared__ __align__(16) unsigned char smem[];
+  bf16_t *As = reinterpret_cast<bf16_t *>(smem);  // [2][BM][LDA]
+  float *Cs = reinterpret_cast<float *>(smem);    // [BM][LDC], reuses the space after the K loop
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+  const int ntn = g.N / BN, ntm = (g.M + BM - 1) / BM;
+  int mt, nt;
+  tile_of_block(blockIdx.x, ntm, ntn, mt, nt);
+  const int m0 = mt * BM, n0 = nt * BN;
+
+  const int srow = tid >> 3, skc = (tid & 7) * 8;
+  float mean[PASSES], rstd[PASSES];
+  float lam = 0.0f;
+  if (PRO == PRO_LN || PRO == PRO_FINAL) {
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) row_moments(g, m0 + p * 32 + srow, mean[p], rstd[p]);
+    if (PRO == PRO_FINAL) lam = g.lam[0];
+  }
+
+  const int nkb = g.K / BK, ksteps = g.K / 16;
+  // fragment stream of this wavefront's first column tile
+  const bf16x8 *Wf = static_cast<const bf16x8 *>(g.W) + ((size_t)((n0 + wn * TN * 32) / 32) * ksteps) * 64 + lane;
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+  Raw8<AT> ra[PASSES], ra2[PASSES];
+  bf16x8 bcur[4][TN], bnext[4][TN];
+
+  // preamble: K block 0
+#pragma unroll
+  for (int p = 0; p < PASSES; ++p) stage_load<PRO, AT>(g, m0 + p * 32 + srow, skc, ra[p], ra2[p]);
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) bcur[ks][j] = Wf[((size_t)j * ksteps + ks) * 64];
+#pragma unroll
+  for (int p = 0; p < PASSES; ++p) {
+    bf16_t *dst = As + (p * 32 + srow) * LDA + skc;
+    if (PRO == PRO_PLAIN || PRO == PRO_CONV) {
+      *reinterpret_cast<bf16x8 *>(dst) = ra[p].v;
+    } else {
+      float v[8];
+      stage_transform<PRO, AT>(g, skc, ra[p], ra2[p], mean[p], rstd[p], lam, v);
+      store8(dst, v);
+    }
+  }
+
+  for (int kb = 0; kb < nkb; ++kb) {
+    const bool more = kb + 1 < nkb;
+    if (more) {
+      const int k1 = (kb + 1) * BK;
+#pragma unroll
+      for (int p = 0; p < PASSES; ++p) stage_load<PRO, AT>(g, m0 + p * 32 + srow, k1 + skc, ra[p], ra2[p]);
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bnext[ks][j] = Wf[((size_t)j * ksteps + (kb + 1) * 4 + ks) * 64];
+    }
+    __syncthreads();
+    const bf16_t *Ab = As + (kb & 1) * BM * LDA;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      bf16x8 af[TM];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+        af[i] = *reinterpret_cast<const bf16x8 *>(Ab + ((wm * TM + i) * 32 + (lane & 31)) * LDA + ks * 16 + (lane >> 5) * 8);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bcur[ks][j], acc[i][j], 0, 0, 0);
+    }
+    if (more) {
+      bf16_t *An = As + ((kb + 1) & 1) * BM * LDA;
+      const int k1 = (kb + 1) * BK;
+#pragma unroll
+      for (int p = 0; p < PASSES; ++p) {
+        bf16_t *dst = An + (p * 32 + srow) * LDA + skc;
+        if (PRO == PRO_PLAIN || PRO == PRO_CONV) {
+          *reinterpret_cast<bf16x8 *>(dst) = ra[p].v;
+        } else {
+          float v[8];
+          stage_transform<PRO, AT>(g, k1 + skc, ra[p], ra2[p], mean[p], rstd[p], lam, v);
+          store8(dst, v);
+        }
+      }
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bcur[ks][j] = bnext[ks][j];
+    }
+  }
+
+  // park the accumulators: lane l of a 32x32 tile holds column l % 32, rows (e / 4) * 8 + (l / 32) * 4 + e % 4
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int row = (wm * TM + i) * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+        const int col = (wn * TN + j) * 32 + (lane & 31);
+        Cs[row * LDC + col] = acc[i][j][e];
+      }
+  __syncthreads();
+  epilogue<EPI, AT, BM, BN>(g, Cs, m0, n0, nt, tid);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// fp32 FMA core: 256 threads, each owning 8 consecutive columns of one row; tile (2048 / BN) x BN,
+// K blocks of 32; W is plain [K][N] fp32
+// ---------------------------------------------------------------------------------------------------
+template <int BN, int PRO, int EPI>
+__global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g) {
+  typedef float AT;
+  constexpr int CHN = BN / 8, BM = 256 / CHN, BK = 32, LDC = BN + 4;
+  constexpr int NCH = (BM * 4 + 255) / 256;  // A chunks staged per thread
+  __shared__ __align__(16) float As[BM][BK + 4];
+  __shared__ __align__(16) float Ws[BK][BN];
+  __shared__ __align__(16) float Cs[BM * LDC];
+  const int tid = threadIdx.x;
+  const int ntn = g.N / BN;
+  const int nt = blockIdx.x % ntn, mt = blockIdx.x / ntn;
+  const int m0 = mt * BM, n0 = nt * BN;
+  const int r = tid / CHN, cg = (tid % CHN) * 8;  // this thread's output row and first column
+  float mean[NCH], rstd[NCH], lam = 0.0f;
+#pragma unroll
+  for (int q = 0; q < NCH; ++q) {
+    mean[q] = 0.0f; rstd[q] = 1.0f;
+    const int c = q * 256 + tid;
+    if ((PRO == PRO_LN || PRO == PRO_FINAL) && c < BM * 4) row_moments(g, m0 + (c >> 2), mean[q], rstd[q]);
+  }
+  if (PRO == PRO_FINAL) lam = g.lam[0];
+  float acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] = 0.0f;
+  const float *W = static_cast<const float *>(g.W);
+  for (int k0 = 0; k0 < g.K; k0 += BK) {
+#pragma unroll
+    for (int q = 0; q < NCH; ++q) {
+      const int c = q * 256 + tid;
+      if (c < BM * 4) {
+        const int srow = c >> 2, skc = (c & 3) * 8;
+        Raw8<AT> a, a2;
+        stage_load<PRO, AT>(g, m0 + srow, k0 + skc, a, a2);
+        float v[8];
+        stage_transform<PRO, AT>(g, k0 + skc, a, a2, mean[q], rstd[q], lam, v);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) As[srow][skc + i] = v[i];
+      }
+    }
+    for (int idx = tid; idx < BK * BN / 4; idx += 256) {
+      const int kk = idx / (BN / 4), c4 = (idx % (BN / 4)) * 4;
+      *reinterpret_cast<f32x4 *>(&Ws[kk][c4]) = *reinterpret_cast<const f32x4 *>(W + (size_t)(k0 + kk) * g.N + n0 + c4);
+    }
+    __syncthreads();
+#pragma unroll 8
+    for (int kk = 0; kk < BK; ++kk) {
+      const float a = As[r][kk];
+      const f32x4 w0 = *reinterpret_cast<const f32x4 *>(&Ws[kk][cg]), w1 = *reinterpret_cast<const f32x4 *>(&Ws[kk][cg + 4]);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { acc[i] = fmaf(a, w0[i], acc[i]); acc[4 + i] = fmaf(a, w1[i], acc[4 + i]); }
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) Cs[r * LDC + cg + i] = acc[i];
+  __syncthreads();
+  epilogue<EPI, AT, BM, BN>(g, Cs, m0, n0, nt, tid);
+}
+
+template <int WM, int WN, int TM, int TN, int PRO, int EPI>
+hipError_t launch_bf16(const GemmArgs &g, hipStream_t s) {
+  constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+  constexpr size_t lds_a = 2 * BM * (64 + 8) * sizeof(bf16_t), lds_c = (size_t)BM * (BN + 4) * sizeof(float);
+  constexpr size_t lds = lds_a > lds_c ? lds_a : lds_c;
+  static bool attr_done = false;
+  auto kern = gemm_bf16_kernel<WM, WN, TM, TN, PRO, EPI>;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  if (g.N % BN || g.K % 64 || g.M <= 0) return hipErrorInvalidValue;
+  const int grid = ((g.M + BM - 1) / BM) * (g.N / BN);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, s, g);
+  return hipGetLastError();
+}
+
+template <int BN, int PRO, int EPI>
+hipError_t launch_f32_bn(const GemmArgs &g, hipStream_t s) {
+  constexpr int BM = 256 / (BN / 8);
+  const int grid = ((g.M + BM - 1) / BM) * (g.N / BN);
+  hipLaunchKernelGGL((gemm_f32_kernel<BN, PRO, EPI>), dim3(grid), dim3(256), 0, s, g);
+  return hipGetLastError();
+}
+// wide == true: N is a multiple of 128 (required by the statistics and GeGLU layouts); otherwise N in {64, 32, 16}.
+template <int PRO, int EPI, bool WIDE>
+hipError_t launch_f32(const GemmArgs &g, hipStream_t s) {
+  if (g.K % 32 || g.M <= 0) return hipErrorInvalidValue;
+  if constexpr (WIDE) {
+    if (g.N % 128) return hipErrorInvalidValue;
+    return launch_f32_bn<128, PRO, EPI>(g, s);
+  } else {
+  if (g.N % 64 == 0) return launch_f32_bn<64, PRO, EPI>(g, s);
+  if (g.N % 32 == 0) return launch_f32_bn<32, PRO, EPI>(g, s);
+  if (g.N % 16 == 0) return launch_f32_bn<16, PRO, EPI>(g, s);
+  return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace
+
+// One entry per (shape class, prologue, epilogue) the model step uses.
+hipError_t fade_gemm(int op, bool bf16, const GemmArgs &g, hipStream_t s) {
+  if (bf16) {
+    switch (op) {
+      case GEMM_CONV:     return launch_bf16<4, 1, 1, 1, PRO_CONV, EPI_CONV>(g, s);       // 128 x 32 tiles
+      case GEMM_GLOBAL:   return launch_bf16<2, 2, 2, 2, PRO_PLAIN, EPI_GLOBAL>(g, s);    // 128 x 128
+      case GEMM_ROUTER:   return launch_bf16<2, 2, 2, 2, PRO_PLAIN, EPI_MIX>(g, s);
+      case GEMM_DOWN:     return launch_bf16<2, 2, 1, 1, PRO_LN, EPI_STORE_F32>(g, s);    // 64 x 64
+      case GEMM_UP:       return launch_bf16<2, 2, 2, 2, PRO_PLAIN, EPI_STORE>(g, s);
+      case GEMM_GATE:     return launch_bf16<2, 2, 2, 2, PRO_PLAIN, EPI_GATE>(g, s);
+      case GEMM_FNR_IN:   return launch_bf16<2, 2, 2, 2, PRO_LN, EPI_GEGLU>(g, s);
+      case GEMM_FNR_OUT:  return launch_bf16<2, 2, 2, 2, PRO_PLAIN, EPI_STORE>(g, s);
+      case GEMM_HEAD:     return launch_bf16<2, 2, 1, 1, PRO_FINAL, EPI_STORE_F32>(g, s);
+      default: return hipErrorInvalidValue;
+    }
+  }
+  switch (op) {
+    case GEMM_CONV:     return launch_f32<PRO_CONV, EPI_CONV, false>(g, s);
+    case GEMM_GLOBAL:   return launch_f32<PRO_PLAIN, EPI_GLOBAL, true>(g, s);
+    case GEMM_ROUTER:   return launch_f32<PRO_PLAIN, EPI_MIX, true>(g, s);
+    case GEMM_DOWN:     return launch_f32<PRO_LN, EPI_STORE_F32, false>(g, s);
+    case GEMM_UP:       return launch_f32<PRO_PLAIN, EPI_STORE, true>(g, s);
+    case GEMM_GATE:     return launch_f32<PRO_PLAIN, EPI_GATE, true>(g, s);
+    case GEMM_FNR_IN:   return launch_f32<PRO_LN, EPI_GEGLU, true>(g, s);
+    case GEMM_FNR_OUT:  return launch_f32<PRO_PLAIN, EPI_STORE, true>(g, s);
+    case GEMM_HEAD:     return launch_f32<PRO_FINAL, EPI_STORE_F32, true>(g, s);
+    default: return hipErrorInvalidValue;
+  }
+}

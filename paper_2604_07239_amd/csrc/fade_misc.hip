@@ -1,0 +1,516 @@
+// fade_misc.hip — everything of the step that is not a dense product: weight preparation, the embedding /
+// window gather with the rolling-cache update (Eq. 1-2), the per-stream memory product of Eq. 7, and the
+// fused softmax -> frequency table -> arithmetic coder kernel (one wavefront per stream).
+#include "fade_dev.h"
+#include "fade_kernels.h"
+
+namespace {
+
+__device__ __forceinline__ float gelu_f(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
+
+template <typename T> __device__ __forceinline__ T wave_sum(T v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+  return v;
+}
+
+// ---------------------------------------------------------------------------------------------------
+// weight preparation
+// ---------------------------------------------------------------------------------------------------
+// fp32 [k_real][N] (row-major) -> bf16 fragments for v_mfma_f32_32x32x16_bf16's B operand:
+// fragment (nt, ks) is 64 lanes x 8 values, lane l holding W[ks*16 + (l/32)*8 + i][nt*32 + l%32], i = 0..7;
+// fragments of one 32-column tile are contiguous along K. Rows >= k_real are zero (padding of K).
+// interleave = 1: the source is the pair (W0, W1) of [k_real][N/2] matrices and virtual column v maps to
+// column (v/128)*64 + v%64 of W0 when v%128 < 64, else of W1 (gate and value of Eq. 9 side by side in one tile).
+__global__ void preshuffle_kernel(const float *W0, const float *W1, int k_real, int K, int N, int interleave, bf16_t *out) {
+  const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // one thread per (fragment, lane)
+  const size_t total = (size_t)(N / 32) * (K / 16) * 64;
+  if (t >= total) return;
+  const int lane = (int)(t & 63);
+  const size_t frag = t >> 6;
+  const int ks = (int)(frag % (size_t)(K / 16)), nt = (int)(frag / (size_t)(K / 16));
+  const int v = nt * 32 + (lane & 31);
+  const float *src = W0;
+  int col = v, ld = N;
+  if (interleave) {
+    ld = N / 2;
+    col = (v / 128) * 64 + (v & 63);
+    if ((v & 127) >= 64) src = W1;
+  }
+  bf16x8 r;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int k = ks * 16 + (lane >> 5) * 8 + i;
+    r[i] = (bf16_t)(k < k_real ? src[(size_t)k * ld + col] : 0.0f);
+  }
+  reinterpret_cast<bf16x8 *>(out)[t] = r;
+}
+
+// fp32 path: the same virtual matrix, plain [K][N] fp32.
+__global__ void virtual_copy_kernel(const float *W0, const float *W1, int k_real, int K, int N, int interleave, float *out) {
+  const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= (size_t)K * N) return;
+  const int k = (int)(t / N), v = (int)(t % N);
+  const float *src = W0;
+  int col = v, ld = N;
+  if (interleave) {
+    ld = N / 2;
+    col = (v / 128) * 64 + (v & 63);
+    if ((v & 127) >= 64) src = W1;
+  }
+  out[t] = k < k_real ? src[(size_t)k * ld + col] : 0.0f;
+}
+
+template <typename AT> __global__ void convert_kernel(const float *src, AT *dst, size_t n) {
+  const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t < n) dst[t] = (AT)src[t];
+}
+// fp32 -> value rounded to bf16 and widened again (small fp32-resident operands of the bf16 configuration)
+__global__ void round_bf16_kernel(const float *src, float *dst, size_t n) {
+  const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t < n) dst[t] = (float)(bf16_t)src[t];
+}
+
+// Per-symbol tables: LN_D(E[s]) with the two affine pairs (X of the Design paragraph; LN of Eq. 4).
+template <typename AT>
+__global__ void tables_kernel(const float *E, const float *ge, const float *be, const float *gl, const float *bl, int D,
+                              AT *tabXe, AT *tabXl, float *tabXe32) {
+  const int s = blockIdx.x * blockDim.x + threadIdx.x;
+  if (s >= 256) return;
+  const float *e = E + (size_t)s * D;
+  float mean = 0.0f;
+  for (int i = 0; i < D; ++i) mean += e[i];
+  mean /= (float)D;
+  float var = 0.0f;
+  for (int i = 0; i < D; ++i) { const float d = e[i] - mean; var += d * d; }
+  var /= (float)D;
+  const float rstd = 1.0f / sqrtf(var + 1e-5f);
+  for (int i = 0; i < D; ++i) {
+    const float h = (e[i] - mean) * rstd;
+    const float xe = h * ge[i] + be[i];
+    tabXe32[(size_t)s * D + i] = xe;
+    tabXe[(size_t)s * D + i] = (AT)xe;
+    tabXl[(size_t)s * D + i] = (AT)(h * gl[i] + bl[i]);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// window gather + rolling cache (one workgroup per stream)
+// ---------------------------------------------------------------------------------------------------
+template <typename AT>
+__global__ __launch_bounds__(256) void embed_cache_kernel(EmbedArgs a) {
+  const int b = blockIdx.x, tid = threadIdx.x;
+  if (!stream_active(a.ws, b)) return;
+  const uint8_t *win = stream_window(a.ws, b, a.T);
+  const AT *tabXe = static_cast<const AT *>(a.tabXe), *tabXl = static_cast<const AT *>(a.tabXl);
+  AT *X = static_cast<AT *>(a.X) + (size_t)b * a.Dh, *XL = static_cast<AT *>(a.XL) + (size_t)b * a.Dh;
+  constexpr int V = 16 / sizeof(AT);  // elements per 16-byte piece
+  typedef f32x4 piece_t;              // 16 bytes, whatever the element type
+  for (int ch = tid; ch < a.Dh / V; ch += 256) {
+    const int e0 = ch * V, j = e0 / a.D, i = e0 - j * a.D;
+    const int s = win[j];
+    *reinterpret_cast<piece_t *>(X + e0) = *reinterpret_cast<const piece_t *>(tabXe + (size_t)s * a.D + i);
+    *reinterpret_cast<piece_t *>(XL + e0) = *reinterpret_cast<const piece_t *>(tabXl + (size_t)s * a.D + i);
+  }
+  // Eq. 2: shift the cache left by one slot (through registers, so the move is safe in place) ...
+  AT *M = static_cast<AT *>(a.M) + (size_t)b * a.Dc;
+  AT keep[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int idx = q * 256 + tid;
+    if (idx < a.Dc) keep[q] = M[idx];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int idx = q * 256 + tid;
+    if (idx < a.Dc && idx >= a.c) M[idx - a.c] = keep[q];
+  }
+  // ... and append Eq. 1's GeGLU of the newest symbol: psi(x_t W_g) * (x_t W_v)
+  if (tid < a.c) {
+    const float *xt = a.tabXe32 + (size_t)win[a.T - 1] * a.D;
+    float gg = 0.0f, gv = 0.0f;
+    for (int i = 0; i < a.D; ++i) {
+      gg = fmaf(xt[i], a.Wg[i * a.c + tid], gg);
+      gv = fmaf(xt[i], a.Wv[i * a.c + tid], gv);
+    }
+    M[a.Dc - a.c + tid] = (AT)(gelu_f(gg) * gv);
+    if (a.GG) { a.GG[(size_t)b * a.c + tid] = gg; a.GV[(size_t)b * a.c + tid] = gv; }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Eq. 7's batched product: z[b] = y[b] * W_U[b], one wavefront per stream, lane = output column (d_low = 64)
+// ---------------------------------------------------------------------------------------------------
+template <typename AT>
+__global__ __launch_bounds__(256) void bmm_kernel(const float *y, const AT *WU, AT *z, int B) {
+  const int b = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (b >= B) return;
+  const float yv = y[(size_t)b * 64 + lane];
+  const AT *W = WU + (size_t)b * 4096;
+  float acc = 0.0f;
+#pragma unroll 8
+  for (int k = 0; k < 64; ++k) acc = fmaf(__shfl(yv, k, 64), (float)W[k * 64 + lane], acc);
+  z[(size_t)b * 64 + lane] = (AT)acc;
+}
+
+// ---------------------------------------------------------------------------------------------------
+// probabilities -> frequencies (wavefront-wide, lane l owns symbols 4l .. 4l+3)
+// f_i = 1 + trunc(fp32(p_i * 65280)); the remainder 65536 - sum f goes to the lowest index of the maximum.
+// ---------------------------------------------------------------------------------------------------
+__device__ __forceinline__ bool quantize_wave(const float p[4], int lane, uint32_t q[4]) {
+  bool ok = true;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    ok = ok && (p[i] >= 0.0f) && (p[i] <= 1.0f);
+    q[i] = 1u + (uint32_t)__fmul_rn(p[i], 65280.0f);
+  }
+  const uint32_t total = wave_sum<uint32_t>(q[0] + q[1] + q[2] + q[3]);
+  uint32_t best = q[0], bi = 0;
+#pragma unroll
+  for (int i = 1; i < 4; ++i)
+    if (q[i] > best) { best = q[i]; bi = i; }
+  // order by (value, then smaller index): key = value << 10 | (1023 - index)
+  uint32_t key = (best << 10) | (1023u - (uint32_t)(4 * lane + bi));
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const uint32_t o = __shfl_xor(key, off, 64);
+    key = o > key ? o : key;
+  }
+  const int arg = 1023 - (int)(key & 1023u);
+  if ((arg >> 2) == lane) q[arg & 3] += 65536u - total;  // wraps correctly when total > 65536
+  return __all(ok);
+}
+
+// Exclusive prefix of the lane totals; cum[i] = sum of every frequency before symbol 4*lane + i.
+__device__ __forceinline__ void cumulate_wave(const uint32_t q[4], int lane, uint32_t cum[4]) {
+  const uint32_t tot = q[0] + q[1] + q[2] + q[3];
+  uint32_t inc = tot;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t o = __shfl_up(inc, off, 64);
+    if (lane >= off) inc += o;
+  }
+  const uint32_t base = inc - tot;
+  cum[0] = base; cum[1] = base + q[0]; cum[2] = cum[1] + q[1]; cum[3] = cum[2] + q[2];
+}
+
+// ---------------------------------------------------------------------------------------------------
+// arithmetic coder: 32-bit interval, totals 2^16, bit-plus-follow carries, bits MSB first
+// ---------------------------------------------------------------------------------------------------
+constexpr uint32_t kHalf = 0x80000000u, kQuarter = 0x40000000u, kThreeQ = 0xC0000000u;
+
+struct EncState {
+  uint32_t low, high, pending, bitbuf, nbits, pos;
+};
+__device__ __forceinline__ void enc_load(const CoderBufs &c, int b, EncState &e) {
+  e.low = c.low[b]; e.high = c.high[b]; e.pending = c.pending[b]; e.bitbuf = c.bitbuf[b]; e.nbits = c.nbits[b]; e.pos = c.pos[b];
+}
+__device__ __forceinline__ void enc_store(const CoderBufs &c, int b, const EncState &e) {
+  c.low[b] = e.low; c.high[b] = e.high; c.pending[b] = e.pending; c.bitbuf[b] = e.bitbuf; c.nbits[b] = e.nbits; c.pos[b] = e.pos;
+}
+__device__ __forceinline__ void put_bit(const CoderBufs &c, int b, EncState &e, uint32_t bit) {
+  e.bitbuf = (e.bitbuf << 1) | bit;
+  if (++e.nbits == 8) {
+    if (e.pos < c.cap) c.out[(size_t)b * c.cap + e.pos] = (uint8_t)e.bitbuf;
+    else *c.err = 1;  // payload buffer exhausted: flagged, never written out of bounds
+    ++e.pos; e.bitbuf = 0; e.nbits = 0;
+  }
+}
+__device__ __forceinline__ void emit(const CoderBufs &c, int b, EncState &e, uint32_t bit) {
+  put_bit(c, b, e, bit);
+  for (; e.pending > 0; --e.pending) put_bit(c, b, e, bit ^ 1u);
+}
+__device__ __forceinline__ void enc_symbol(const CoderBufs &c, int b, EncState &e, uint32_t cum_lo, uint32_t cum_hi) {
+  const uint64_t range = (uint64_t)e.high - e.low + 1;
+  e.high = e.low + (uint32_t)((range * cum_hi) >> 16) - 1;
+  e.low = e.low + (uint32_t)((range * cum_lo) >> 16);
+  for (;;) {
+    if (e.high < kHalf) emit(c, b, e, 0);
+    else if (e.low >= kHalf) emit(c, b, e, 1);
+    else if (e.low >= kQuarter && e.high < kThreeQ) { ++e.pending; e.low -= kQuarter; e.high -= kQuarter; }
+    else break;
+    e.low <<= 1;
+    e.high = (e.high << 1) | 1u;
+  }
+}
+__device__ __forceinline__ void enc_finish(const CoderBufs &c, int b, EncState &e) {
+  ++e.pending;
+  emit(c, b, e, e.low < kQuarter ? 0u : 1u);
+  while (e.nbits != 0) put_bit(c, b, e, 0);
+}
+
+struct DecState {
+  uint32_t low, high, value, bitpos;
+};
+__device__ __forceinline__ uint32_t dec_bit(const CoderBufs &c, int b, DecState &d) {
+  const uint32_t byte = d.bitpos >> 3;
+  uint32_t bit = 0;
+  if (byte < c.in_len[b]) bit = (c.in[(size_t)b * c.cap + byte] >> (7 - (d.bitpos & 7))) & 1u;
+  ++d.bitpos;  // zeros past the end
+  return bit;
+}
+__device__ __forceinline__ uint32_t dec_target(const DecState &d) {
+  const uint64_t range = (uint64_t)d.high - d.low + 1;
+  return (uint32_t)((((((uint64_t)(d.value - d.low)) + 1) << 16) - 1) / range);
+}
+__device__ __forceinline__ void dec_update(const CoderBufs &c, int b, DecState &d, uint32_t cum_lo, uint32_t cum_hi) {
+  const uint64_t range = (uint64_t)d.high - d.low + 1;
+  d.high = d.low + (uint32_t)((range * cum_hi) >> 16) - 1;
+  d.low = d.low + (uint32_t)((range * cum_lo) >> 16);
+  for (;;) {
+    if (d.high < kHalf) {
+    } else if (d.low >= kHalf) { d.value -= kHalf; d.low -= kHalf; d.high -= kHalf; }
+    else if (d.low >= kQuarter && d.high < kThreeQ) { d.value -= kQuarter; d.low -= kQuarter; d.high -= kQuarter; }
+    else break;
+    d.low <<= 1;
+    d.high = (d.high << 1) | 1u;
+    d.value = (d.value << 1) | dec_bit(c, b, d);
+  }
+}
+
+// Code one symbol of stream b under the table q (lane-distributed). mode: CODE_NONE / CODE_ENCODE / CODE_DECODE.
+template <int MODE>
+__device__ __forceinline__ void code_wave(const CoderBufs &c, int b, int lane, const uint32_t q[4], uint8_t *sym_ptr) {
+  if (MODE == CODE_NONE) return;
+  uint32_t cum[4];
+  cumulate_wave(q, lane, cum);
+  if (MODE == CODE_ENCODE) {
+    const int s = *sym_ptr;
+    const uint32_t mylo = cum[s & 3], myhi = mylo + q[s & 3];
+    const uint32_t lo = __shfl(mylo, s >> 2, 64), hi = __shfl(myhi, s >> 2, 64);
+    if (lane == 0) {
+      EncState e;
+      enc_load(c, b, e);
+      enc_symbol(c, b, e, lo, hi);
+      enc_store(c, b, e);
+    }
+  } else {
+    DecState d;
+    d.low = c.low[b]; d.high = c.high[b]; d.value = c.value[b]; d.bitpos = c.bitpos[b];
+    const uint32_t target = dec_target(d);
+    int found = -1;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (cum[i] <= target && target < cum[i] + q[i]) found = i;
+    const unsigned long long vote = __ballot(found >= 0);
+    if (vote == 0ull) {  // target outside [0, 2^16): the payload does not belong to this model
+      if (lane == 0) *c.err = 2;
+      return;
+    }
+    const int owner = __ffsll((long long)vote) - 1;
+    const int fi = found < 0 ? 0 : found;
+    const uint32_t lo = __shfl(cum[fi], owner, 64), hi = __shfl(cum[fi] + q[fi], owner, 64);
+    const int s = __shfl(4 * lane + fi, owner, 64);
+    if (lane == 0) {
+      dec_update(c, b, d, lo, hi);
+      c.low[b] = d.low; c.high[b] = d.high; c.value[b] = d.value; c.bitpos[b] = d.bitpos;
+      *sym_ptr = (uint8_t)s;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// softmax over the 256 logits of a stream, quantise, code: one wavefront per stream
+// ---------------------------------------------------------------------------------------------------
+template <int MODE>
+__global__ __launch_bounds__(256) void softmax_quant_code_kernel(SqcArgs a) {
+  const int b = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (b >= a.B) return;
+  if (!stream_active(a.ws, b)) return;
+  const f32x4 z = *reinterpret_cast<const f32x4 *>(a.logits + (size_t)b * 256 + 4 * lane);
+  const float mx = wave_max(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])));
+  float p[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) p[i] = expf(z[i] - mx);
+  const float sum = wave_sum<float>((p[0] + p[1]) + (p[2] + p[3]));
+#pragma unroll
+  for (int i = 0; i < 4; ++i) p[i] = p[i] / sum;
+  if (a.probs) {
+    f32x4 o = {p[0], p[1], p[2], p[3]};
+    *reinterpret_cast<f32x4 *>(a.probs + (size_t)b * 256 + 4 * lane) = o;
+  }
+  uint32_t q[4];
+  if (!quantize_wave(p, lane, q)) {
+    if (lane == 0) *a.cb.err = 3;  // non-finite probabilities
+    return;
+  }
+  if (a.freq) {
+    ushort4 f = make_ushort4((unsigned short)q[0], (unsigned short)q[1], (unsigned short)q[2], (unsigned short)q[3]);
+    *reinterpret_cast<ushort4 *>(a.freq + (size_t)b * 256 + 4 * lane) = f;
+  }
+  if (MODE != CODE_NONE) {
+    uint8_t *sym = a.sym_base + (long long)b * a.ws.stride + a.ws.st->i;
+    code_wave<MODE>(a.cb, b, lane, q, sym);
+  }
+}
+
+__global__ __launch_bounds__(256) void quantize_kernel(const float *probs, size_t rows, uint16_t *freq, int *err) {
+  const size_t r = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (r >= rows) return;
+  const f32x4 pv = *reinterpret_cast<const f32x4 *>(probs + r * 256 + 4 * lane);
+  const float p[4] = {pv[0], pv[1], pv[2], pv[3]};
+  uint32_t q[4];
+  if (!quantize_wave(p, lane, q)) {
+    if (lane == 0) *err = 3;
+    return;
+  }
+  ushort4 f = make_ushort4((unsigned short)q[0], (unsigned short)q[1], (unsigned short)q[2], (unsigned short)q[3]);
+  *reinterpret_cast<ushort4 *>(freq + r * 256 + 4 * lane) = f;
+}
+
+// Code one symbol per stream under explicit tables freq[stream][256] (the stand-alone coder entry points).
+template <int MODE>
+__global__ __launch_bounds__(256) void code_tables_kernel(const uint16_t *freq, uint8_t *sym, int n_streams, CoderBufs cb) {
+  const int b = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (b >= n_streams) return;
+  const ushort4 f = *reinterpret_cast<const ushort4 *>(freq + (size_t)b * 256 + 4 * lane);
+  const uint32_t q[4] = {f.x, f.y, f.z, f.w};
+  code_wave<MODE>(cb, b, lane, q, sym + b);
+}
+
+// Algorithm 1's first T symbols: every symbol has frequency 256 (p = 1/256). One thread per stream.
+template <int MODE>
+__global__ void code_uniform_kernel(WinSrc ws, uint8_t *sym_base, int B, CoderBufs cb) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B || !stream_active(ws, b)) return;
+  uint8_t *sym = sym_base + (long long)b * ws.stride + ws.st->i;
+  if (MODE == CODE_ENCODE) {
+    const uint32_t s = *sym;
+    EncState e;
+    enc_load(cb, b, e);
+    enc_symbol(cb, b, e, s * 256u, (s + 1u) * 256u);
+    enc_store(cb, b, e);
+  } else {
+    DecState d;
+    d.low = cb.low[b]; d.high = cb.high[b]; d.value = cb.value[b]; d.bitpos = cb.bitpos[b];
+    const uint32_t target = dec_target(d);
+    if (target >= 65536u) { *cb.err = 2; return; }
+    const uint32_t s = target >> 8;
+    dec_update(cb, b, d, s * 256u, (s + 1u) * 256u);
+    cb.low[b] = d.low; cb.high[b] = d.high; cb.value[b] = d.value; cb.bitpos[b] = d.bitpos;
+    *sym = (uint8_t)s;
+  }
+}
+
+// Reset coder state; for decoding also prime `value` with the first 32 payload bits.
+__global__ void coder_init_kernel(CoderBufs cb, int B, int decode) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  cb.low[b] = 0; cb.high[b] = 0xFFFFFFFFu; cb.pending[b] = 0; cb.bitbuf[b] = 0; cb.nbits[b] = 0; cb.pos[b] = 0;
+  cb.value[b] = 0; cb.bitpos[b] = 0;
+  if (decode) {
+    DecState d = {0u, 0xFFFFFFFFu, 0u, 0u};
+    for (int i = 0; i < 32; ++i) d.value = (d.value << 1) | dec_bit(cb, b, d);
+    cb.value[b] = d.value; cb.bitpos[b] = d.bitpos;
+  }
+}
+
+// Terminate every non-empty stream's payload; pos[b] becomes its byte length.
+__global__ void coder_finish_kernel(CoderBufs cb, int B, long long stride, long long n) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  if ((long long)b * stride >= n) return;  // empty stream: zero-length payload
+  EncState e;
+  enc_load(cb, b, e);
+  enc_finish(cb, b, e);
+  enc_store(cb, b, e);
+}
+
+__global__ void step_set_kernel(StepState *st, long long i) { st->i = i; }
+__global__ void step_advance_kernel(StepState *st) { st->i += 1; }
+
+inline unsigned blocks_for(size_t n, unsigned per) { return (unsigned)((n + per - 1) / per); }
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------------
+// launchers
+// ---------------------------------------------------------------------------------------------------
+hipError_t fade_preshuffle(const float *W0, const float *W1, int k_real, int K, int N, int interleave, void *out, hipStream_t s) {
+  const size_t total = (size_t)(N / 32) * (K / 16) * 64;
+  hipLaunchKernelGGL(preshuffle_kernel, dim3(blocks_for(total, 256)), dim3(256), 0, s, W0, W1, k_real, K, N, interleave,
+                     static_cast<bf16_t *>(out));
+  return hipGetLastError();
+}
+hipError_t fade_virtual_copy(const float *W0, const float *W1, int k_real, int K, int N, int interleave, float *out, hipStream_t s) {
+  hipLaunchKernelGGL(virtual_copy_kernel, dim3(blocks_for((size_t)K * N, 256)), dim3(256), 0, s, W0, W1, k_real, K, N,
+                     interleave, out);
+  return hipGetLastError();
+}
+hipError_t fade_convert(const float *src, void *dst, size_t n, bool bf16, hipStream_t s) {
+  if (bf16) hipLaunchKernelGGL(convert_kernel<bf16_t>, dim3(blocks_for(n, 256)), dim3(256), 0, s, src, static_cast<bf16_t *>(dst), n);
+  else hipLaunchKernelGGL(convert_kernel<float>, dim3(blocks_for(n, 256)), dim3(256), 0, s, src, static_cast<float *>(dst), n);
+  return hipGetLastError();
+}
+hipError_t fade_round_bf16(const float *src, float *dst, size_t n, hipStream_t s) {
+  hipLaunchKernelGGL(round_bf16_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, s, src, dst, n);
+  return hipGetLastError();
+}
+hipError_t fade_tables(const float *E, const float *ge, const float *be, const float *gl, const float *bl, int D, void *tabXe,
+                       void *tabXl, float *tabXe32, bool bf16, hipStream_t s) {
+  if (bf16)
+    hipLaunchKernelGGL(tables_kernel<bf16_t>, dim3(1), dim3(256), 0, s, E, ge, be, gl, bl, D, static_cast<bf16_t *>(tabXe),
+                       static_cast<bf16_t *>(tabXl), tabXe32);
+  else
+    hipLaunchKernelGGL(tables_kernel<float>, dim3(1), dim3(256), 0, s, E, ge, be, gl, bl, D, static_cast<float *>(tabXe),
+                       static_cast<float *>(tabXl), tabXe32);
+  return hipGetLastError();
+}
+hipError_t fade_embed_cache(const EmbedArgs &a, int B, bool bf16, hipStream_t s) {
+  if (bf16) hipLaunchKernelGGL(embed_cache_kernel<bf16_t>, dim3(B), dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(embed_cache_kernel<float>, dim3(B), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+hipError_t fade_bmm(const float *y, const void *WU, void *z, int B, bool bf16, hipStream_t s) {
+  if (bf16)
+    hipLaunchKernelGGL(bmm_kernel<bf16_t>, dim3((B + 3) / 4), dim3(256), 0, s, y, static_cast<const bf16_t *>(WU), static_cast<bf16_t *>(z), B);
+  else
+    hipLaunchKernelGGL(bmm_kernel<float>, dim3((B + 3) / 4), dim3(256), 0, s, y, static_cast<const float *>(WU), static_cast<float *>(z), B);
+  return hipGetLastError();
+}
+hipError_t fade_softmax_quant_code(const SqcArgs &a, int mode, hipStream_t s) {
+  const dim3 grid((a.B + 3) / 4), block(256);
+  if (mode == CODE_ENCODE) hipLaunchKernelGGL(softmax_quant_code_kernel<CODE_ENCODE>, grid, block, 0, s, a);
+  else if (mode == CODE_DECODE) hipLaunchKernelGGL(softmax_quant_code_kernel<CODE_DECODE>, grid, block, 0, s, a);
+  else hipLaunchKernelGGL(softmax_quant_code_kernel<CODE_NONE>, grid, block, 0, s, a);
+  return hipGetLastError();
+}
+hipError_t fade_quantize_rows(const float *probs, size_t rows, uint16_t *freq, int *err, hipStream_t s) {
+  hipLaunchKernelGGL(quantize_kernel, dim3(blocks_for(rows, 4)), dim3(256), 0, s, probs, rows, freq, err);
+  return hipGetLastError();
+}
+hipError_t fade_code_tables(const uint16_t *freq, uint8_t *sym, int n_streams, const CoderBufs &cb, int mode, hipStream_t s) {
+  const dim3 grid((n_streams + 3) / 4), block(256);
+  if (mode == CODE_ENCODE) hipLaunchKernelGGL(code_tables_kernel<CODE_ENCODE>, grid, block, 0, s, freq, sym, n_streams, cb);
+  else hipLaunchKernelGGL(code_tables_kernel<CODE_DECODE>, grid, block, 0, s, freq, sym, n_streams, cb);
+  return hipGetLastError();
+}
+hipError_t fade_code_uniform(const WinSrc &ws, uint8_t *sym_base, int B, const CoderBufs &cb, int mode, hipStream_t s) {
+  const dim3 grid((B + 63) / 64), block(64);
+  if (mode == CODE_ENCODE) hipLaunchKernelGGL(code_uniform_kernel<CODE_ENCODE>, grid, block, 0, s, ws, sym_base, B, cb);
+  else hipLaunchKernelGGL(code_uniform_kernel<CODE_DECODE>, grid, block, 0, s, ws, sym_base, B, cb);
+  return hipGetLastError();
+}
+hipError_t fade_coder_init(const CoderBufs &cb, int B, int decode, hipStream_t s) {
+  hipLaunchKernelGGL(coder_init_kernel, dim3((B + 63) / 64), dim3(64), 0, s, cb, B, decode);
+  return hipGetLastError();
+}
+hipError_t fade_coder_finish(const CoderBufs &cb, int B, long long stride, long long n, hipStream_t s) {
+  hipLaunchKernelGGL(coder_finish_kernel, dim3((B + 63) / 64), dim3(64), 0, s, cb, B, stride, n);
+  return hipGetLastError();
+}
+hipError_t fade_step_set(StepState *st, long long i, hipStream_t s) {
+  hipLaunchKernelGGL(step_set_kernel, dim3(1), dim3(1), 0, s, st, i);
+  return hipGetLastError();
+}
+hipError_t fade_step_advance(StepState *st, hipStream_t s) {
+  hipLaunchKernelGGL(step_advance_kernel, dim3(1), dim3(1), 0, s, st);
+  return hipGetLastError();
+}
