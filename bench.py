@@ -1,0 +1,173 @@
+#!/usr/bin/env python3
+"""bench.py — throughput of FADE's hot path on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch: for each of the B streams the model step
+(embedding -> DMD -> HGR -> head -> softmax -> frequency table), the arithmetic coding of the next byte
+and, in online mode, the weight update. The workload is benchmark configuration 2 (64 MiB text-like
+source, B = 1024 streams, T = 64, D = 32, H = 256, bf16 operands): the timed region codes steps
+[T + W, T + W + K) of every stream with the input already resident in HBM, first compressing, then
+decompressing the same bytes (checked byte-exact). `--full` runs the whole job end to end instead.
+
+Prints ONE JSON line (see the keys below); `roofline` describes the dominant kernel (the D_h x D_h router /
+gate product), timed with HIP events on the library's stream in a second pass over the same steps;
+`cpu_baseline` times the CPU oracle on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK = 2.5e15   # MI355X dense bf16, FLOP/s
+HBM_PEAK = 8.0e12         # B/s
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2048)
+    ap.add_argument("--warmup", type=int, default=64)
+    ap.add_argument("--config", type=int, default=2, help="benchmark configuration (1-5)")
+    ap.add_argument("--mode", choices=["frozen", "online"], default=None)
+    ap.add_argument("--full", action="store_true", help="run the whole job (all L steps) instead of K timed steps")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--oracle-streams", type=int, default=64)
+    ap.add_argument("--oracle-steps", type=int, default=24)
+    return ap.parse_args()
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    import fade_inputs as fi
+    import paper_2604_07239_amd as fa
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    spec = fi.CONFIGS[a.config]
+    B, T, D, H = spec["B"], spec["T"], spec["D"], spec["H"]
+    Dh, dl = T * D, 64
+    dtype = fa.BF16 if spec["dtype"] == "bf16" else fa.F32
+    online_ok = hasattr(fa, "ONLINE_SUPPORTED") and fa.ONLINE_SUPPORTED
+    mode = a.mode or ("online" if online_ok else "frozen")
+    K, W = a.steps, a.warmup
+
+    full = fi.config_bytes(a.config)
+    L = full.size // B
+    if a.full:
+        src = full
+        first, count = 0, 0
+    else:
+        steps_total = min(L, T + W + K)
+        K = steps_total - T - W
+        src = np.ascontiguousarray(full.reshape(B, L)[:, :steps_total]).reshape(-1)
+        first, count = T + W, K
+    n = src.size
+    blob = fi.config_blob(a.config)
+
+    g = fa.Fade(fa.make_config(B, T, D, H, dtype=dtype, update_mode=fa.ONLINE_ADAM if mode == "online" else fa.FROZEN))
+    g.load_weights(blob.data)
+    src_dev = torch.from_numpy(src).cuda()
+    dst_dev = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+
+    def timed_encode():
+        if a.full:
+            torch.cuda.synchronize(); t0 = time.perf_counter()
+            g.encode_device(src_dev, n, 0, 0)
+            torch.cuda.synchronize(); return time.perf_counter() - t0
+        g.encode_device(src_dev, n, 0, first)          # uniform warm-up symbols + W untimed model steps
+        torch.cuda.synchronize(); t0 = time.perf_counter()
+        g.encode_device(src_dev, n, first, count)      # exactly K timed steps (and the termination of each stream)
+        torch.cuda.synchronize(); return time.perf_counter() - t0
+
+    def timed_decode(lens, data):
+        if a.full:
+            torch.cuda.synchronize(); t0 = time.perf_counter()
+            g.decode_device(lens, data, dst_dev, n, 0, 0)
+            torch.cuda.synchronize(); return time.perf_counter() - t0
+        g.decode_device(lens, data, dst_dev, n, 0, first)
+        torch.cuda.synchronize(); t0 = time.perf_counter()
+        g.decode_device(None, None, dst_dev, n, first, count)
+        torch.cuda.synchronize(); return time.perf_counter() - t0
+
+    t_enc = timed_encode()
+    lens, data = g.payloads()
+    t_dec = timed_decode(lens, data)
+    ok = bool(torch.equal(dst_dev, src_dev))
+    steps_timed = L if a.full else K
+    bytes_timed = n if a.full else B * K
+    container = 64 + 4 * B + int(data.size)
+    enc_MBps = bytes_timed / t_enc / 1e6
+    dec_MBps = bytes_timed / t_dec / 1e6
+
+    # second pass over the same steps with a HIP event pair around every launch (on the library's stream)
+    prof = {}
+    if not a.full:
+        g.encode_device(src_dev, n, 0, first)
+        g.profile(True)
+        g.encode_device(src_dev, n, first, count)
+        prof = g.profile_read()
+        g.profile(False)
+    kern = {k: {"avg_us": 1e3 * ms / max(cnt, 1), "launches": int(cnt)} for k, (ms, cnt) in prof.items()}
+    fwd_flop = 2 * (2 * D * (H // T) + T * 3 * D * D + 2 * Dh * Dh + 2 * Dh * dl + dl * dl + 4 * H * Dh + 256 * Dh)
+    roofline = None
+    if "gemm_router" in kern and spec["dtype"] == "bf16":
+        # dominant kernel: alpha = sigma(X W_r) with the mix epilogue, and its twin the gate product (Eq. 5-6, 8)
+        us = 0.5 * (kern["gemm_router"]["avg_us"] + kern["gemm_gate"]["avg_us"])
+        flop = 2.0 * B * Dh * Dh
+        ach = flop / (us * 1e-6) / 1e12
+        roofline = {"bound": "mfma", "kernel": "gemm_bf16 128x128 (router / gate, M=B, N=K=D_h)", "achieved": round(ach, 2),
+                    "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s", "frac": round(ach * 1e12 / MFMA_BF16_PEAK, 4),
+                    "traffic": None, "avg_us": round(us, 2), "flop_per_launch": flop}
+    step_us_events = sum(v["avg_us"] for k, v in kern.items() if k != "code_uniform")
+
+    cpu = None
+    if not a.no_cpu_baseline:
+        import oracle as orc
+        Bo, So = min(a.oracle_streams, B), a.oracle_steps
+        sub = fi.slice_blob(blob, spec, Bo) if Bo != B else blob
+        o = orc.Oracle(orc.make_config(Bo, T, D, H, dtype=orc.BF16 if spec["dtype"] == "bf16" else orc.F32,
+                                       update_mode=orc.ONLINE_ADAM if mode == "online" else orc.FROZEN))
+        o.load_weights(sub.data)
+        osrc = np.ascontiguousarray(full.reshape(B, L)[:Bo, :T + So]).reshape(-1)
+        t0 = time.perf_counter()
+        oc = o.encode(osrc)
+        t_o = time.perf_counter() - t0
+        cpu = {"value": round(Bo * So / t_o / 1e6, 6), "unit": "MB/s", "cores": 1, "kind": "oracle",
+               "sample": f"oracle compress of the first {T}+{So} bytes of the first {Bo} streams ({Bo * So} model steps, "
+                         f"{t_o:.1f} s, single thread; box has {os.cpu_count()} logical CPUs)",
+               "container_bytes": int(oc.size)}
+
+    out = {
+        "metric": "compress MB/s (input bytes) at B streams on 1 MI355X",
+        "value": round(enc_MBps, 3), "unit": "MB/s", "n_gpus": 1, "steps": int(steps_timed), "warmup": int(W),
+        "ms_per_step": round(1e3 * t_enc / steps_timed, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": spec["dtype"], "data": "synthetic",
+        "config": {"workload": f"cfg{a.config}: {spec['nbytes'] >> 20} MiB {spec['source']} source, B={B} streams, T={T}, D={D}, "
+                               f"H={H}, d_low=64, {spec['dtype']} operands / fp32 accumulate, random-init N(0,0.02); "
+                               + ("whole job" if a.full else f"timed on steps [{first},{first + K}) of every stream"),
+                   "update_mode": mode, "B": B, "bytes_timed": int(bytes_timed)},
+        "decompress_MBps": round(dec_MBps, 3), "decompress_ms_per_step": round(1e3 * t_dec / steps_timed, 5),
+        "total_MBps": round(2 * bytes_timed / (t_enc + t_dec) / 1e6, 3),
+        "round_trip_exact": ok, "bits_per_byte": round(8.0 * container / n, 4),
+        "fwd_flop_per_byte": fwd_flop,
+        "step_fraction_of_mfma_peak": round(fwd_flop * bytes_timed / t_enc / MFMA_BF16_PEAK, 4) if mode == "frozen" else None,
+        "roofline": roofline, "cpu_baseline": cpu,
+        "kernels_us": {k: round(v["avg_us"], 2) for k, v in kern.items()}, "sum_kernels_us": round(step_us_events, 2),
+    }
+    print(json.dumps(out))
+    if not ok:
+        sys.exit(1)
+
+
+if __name__ == "__main__":
+    main()

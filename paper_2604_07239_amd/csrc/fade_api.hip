@@ -111,6 +111,11 @@ struct fade_ctx {
   void *X = nullptr, *XL = nullptr, *M = nullptr, *Hg = nullptr, *Hl = nullptr, *Hmix = nullptr, *Ha = nullptr,
        *Hc = nullptr, *V = nullptr, *Hexp = nullptr, *z = nullptr;
   float *y = nullptr, *logits = nullptr, *stats_c = nullptr, *stats_f = nullptr, *stats_o = nullptr;
+  // bf16 path: split-K partials, folded-LayerNorm vectors, the materialised H of Eq. 10
+  float *part_down = nullptr, *part_fnr = nullptr, *part_head = nullptr;
+  float *s_down = nullptr, *t_down = nullptr, *s_fnr = nullptr, *t_fnr = nullptr;
+  void *Hout = nullptr;
+  int sp_down = 1, sp_fnr = 1, sp_head = 1;
   // kept for the backward pass (online mode only)
   void *hm = nullptr, *alpha = nullptr, *sg = nullptr, *eg = nullptr, *ev = nullptr, *cv = nullptr;
   float *GG = nullptr, *GV = nullptr;
@@ -204,15 +209,18 @@ int prepare_compute(fade_ctx *c) {
     HIP_TRY(c, fade_round_bf16(c->P(P_E), c->E_c, 256 * d.D, s));
     HIP_TRY(c, fade_round_bf16(c->P(P_WG), c->Wg_c, d.D * d.c, s));
     HIP_TRY(c, fade_round_bf16(c->P(P_WV), c->Wv_c, d.D * d.c, s));
-    HIP_TRY(c, fade_preshuffle(c->P(P_WM), nullptr, (int)d.Dc, (int)d.Dc, (int)d.Dh, 0, c->Wm_c, s));
-    HIP_TRY(c, fade_preshuffle(c->P(P_WCONV), nullptr, (int)(d.k * d.D), (int)d.Kc, (int)d.D, 0, c->Wconv_c, s));
-    HIP_TRY(c, fade_preshuffle(c->P(P_WR), nullptr, (int)d.Dh, (int)d.Dh, (int)d.Dh, 0, c->Wr_c, s));
-    HIP_TRY(c, fade_preshuffle(c->P(P_WDOWN), nullptr, (int)d.Dh, (int)d.Dh, (int)d.dl, 0, c->Wdown_c, s));
-    HIP_TRY(c, fade_preshuffle(c->P(P_WUP), nullptr, (int)d.dl, (int)d.dl, (int)d.Dh, 0, c->Wup_c, s));
-    HIP_TRY(c, fade_preshuffle(c->P(P_WC), nullptr, (int)d.Dh, (int)d.Dh, (int)d.Dh, 0, c->Wc_c, s));
-    HIP_TRY(c, fade_preshuffle(c->P(P_WFG), c->P(P_WFV), (int)d.Dh, (int)d.Dh, (int)(2 * d.De), 1, c->Wfgv_c, s));
-    HIP_TRY(c, fade_preshuffle(c->P(P_WF), nullptr, (int)d.De, (int)d.De, (int)d.Dh, 0, c->Wf_c, s));
-    HIP_TRY(c, fade_preshuffle(c->P(P_WO), nullptr, (int)d.Dh, (int)d.Dh, 256, 0, c->Wo_c, s));
+    HIP_TRY(c, fade_preshuffle(c->P(P_WM), nullptr, (int)d.Dc, (int)d.Dc, (int)d.Dh, 0, nullptr, c->Wm_c, s));
+    HIP_TRY(c, fade_preshuffle(c->P(P_WCONV), nullptr, (int)(d.k * d.D), (int)d.Kc, (int)d.D, 0, nullptr, c->Wconv_c, s));
+    HIP_TRY(c, fade_preshuffle(c->P(P_WR), nullptr, (int)d.Dh, (int)d.Dh, (int)d.Dh, 0, nullptr, c->Wr_c, s));
+    HIP_TRY(c, fade_preshuffle(c->P(P_WUP), nullptr, (int)d.dl, (int)d.dl, (int)d.Dh, 0, nullptr, c->Wup_c, s));
+    HIP_TRY(c, fade_preshuffle(c->P(P_WC), nullptr, (int)d.Dh, (int)d.Dh, (int)d.Dh, 0, nullptr, c->Wc_c, s));
+    HIP_TRY(c, fade_preshuffle(c->P(P_WF), nullptr, (int)d.De, (int)d.De, (int)d.Dh, 0, nullptr, c->Wf_c, s));
+    HIP_TRY(c, fade_preshuffle(c->P(P_WO), nullptr, (int)d.Dh, (int)d.Dh, 256, 0, nullptr, c->Wo_c, s));
+    // LayerNorm gains folded into the consuming weights (Eq. 7's Down, Eq. 9's GeGLU pair) + their fix-up vectors
+    HIP_TRY(c, fade_preshuffle(c->P(P_WDOWN), nullptr, (int)d.Dh, (int)d.Dh, (int)d.dl, 0, c->P(P_GAMMA_C), c->Wdown_c, s));
+    HIP_TRY(c, fade_fold_vectors(c->P(P_WDOWN), nullptr, (int)d.Dh, (int)d.dl, 0, c->P(P_GAMMA_C), c->P(P_BETA_C), c->s_down, c->t_down, s));
+    HIP_TRY(c, fade_preshuffle(c->P(P_WFG), c->P(P_WFV), (int)d.Dh, (int)d.Dh, (int)(2 * d.De), 1, c->P(P_GAMMA_F), c->Wfgv_c, s));
+    HIP_TRY(c, fade_fold_vectors(c->P(P_WFG), c->P(P_WFV), (int)d.Dh, (int)(2 * d.De), 1, c->P(P_GAMMA_F), c->P(P_BETA_F), c->s_fnr, c->t_fnr, s));
     HIP_TRY(c, fade_convert(c->P(P_WU), c->WU_c, d.B * d.dl * d.dl, true, s));
   } else {
     HIP_TRY(c, fade_virtual_copy(c->P(P_WCONV), nullptr, (int)(d.k * d.D), (int)d.Kc, (int)d.D, 0, static_cast<float *>(c->Wconv_c), s));
@@ -241,10 +249,10 @@ int do_reset(fade_ctx *c) {
 // ---------------------------------------------------------------------------------------------------
 // one model step: windows -> logits -> (probabilities, table, coded symbol)
 // ---------------------------------------------------------------------------------------------------
-int forward(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint16_t *freq, float *probs) {
+int forward_f32(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint16_t *freq, float *probs) {
   const Dims &d = c->d;
   hipStream_t s = c->stream;
-  const bool bf = c->bf16;
+  const bool bf = false;
   const int B = (int)d.B, Dh = (int)d.Dh, SN = (int)(d.Dh / FADE_STATS_BN);
   {
     Prof p(c, "embed_cache");
@@ -334,6 +342,128 @@ int forward(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint16_t
     HIP_TRY(c, fade_softmax_quant_code(a, mode, s));
   }
   return FADE_OK;
+}
+
+// bf16 path: every product runs on raw bf16 activations through the pipelined MFMA kernel; LayerNorms are folded
+// into the weights and finished where the split-K partials are reduced.
+int pick_splits(int tiles, int k_blocks, int cap) {
+  int s = 1;
+  while (tiles * s < 192 && s * 2 <= cap && k_blocks % (s * 2) == 0 && k_blocks / (s * 2) >= 2) s *= 2;
+  return s;
+}
+
+int forward_bf16(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint16_t *freq, float *probs) {
+  const Dims &d = c->d;
+  hipStream_t s = c->stream;
+  const int B = (int)d.B, Dh = (int)d.Dh, De = (int)d.De, SN = (int)(d.Dh / FADE_STATS_BN);
+  {
+    Prof p(c, "embed_cache");
+    EmbedArgs a{};
+    a.ws = ws; a.T = (int)d.T; a.D = (int)d.D; a.Dh = Dh; a.Dc = (int)d.Dc; a.c = (int)d.c;
+    a.tabXe = c->tabXe; a.tabXl = c->tabXl; a.tabXe32 = c->tabXe32; a.Wg = c->Wg_c; a.Wv = c->Wv_c;
+    a.X = c->X; a.XL = c->XL; a.M = c->M; a.GG = c->GG; a.GV = c->GV;
+    HIP_TRY(c, fade_embed_cache(a, B, true, s));
+  }
+  {  // Eq. 4
+    Prof p(c, "gemm_conv");
+    GemmArgs g{};
+    g.M = (int)(d.B * d.T); g.N = (int)d.D; g.K = (int)d.Kc;
+    g.A = c->XL; g.T = (int)d.T; g.D = (int)d.D; g.taps = (int)d.k;
+    g.W = c->Wconv_c; g.C = c->Hl; g.ldc = (int)d.D; g.C2 = c->cv; g.bias = c->P(P_BCONV);
+    HIP_TRY(c, fade_gemm(GEMM_CONV, true, g, s));
+  }
+  {  // Eq. 3
+    Prof p(c, "gemm_global");
+    GemmArgs g{};
+    g.M = B; g.N = Dh; g.K = (int)d.Dc;
+    g.A = c->M; g.lda = (int)d.Dc; g.W = c->Wm_c; g.C = c->Hg; g.ldc = Dh; g.C2 = c->hm; g.S1 = c->X; g.lam = c->P(P_LAMBDA_M);
+    HIP_TRY(c, fade_gemm(GEMM_GLOBAL, true, g, s));
+  }
+  {  // Eq. 5-6
+    Prof p(c, "gemm_router");
+    GemmArgs g{};
+    g.M = B; g.N = Dh; g.K = Dh;
+    g.A = c->X; g.lda = Dh; g.W = c->Wr_c; g.C = c->Hmix; g.ldc = Dh; g.C2 = c->alpha; g.S1 = c->Hg; g.S2 = c->Hl;
+    g.stats_out = c->stats_c;
+    HIP_TRY(c, fade_gemm(GEMM_ROUTER, true, g, s));
+  }
+  {  // Eq. 7: H_mix W'_down as split-K partials
+    Prof p(c, "gemm_down");
+    GemmArgs g{};
+    g.M = B; g.N = (int)d.dl; g.K = Dh; g.splits = c->sp_down;
+    g.A = c->Hmix; g.lda = Dh; g.W = c->Wdown_c; g.C = c->part_down; g.ldc = (int)d.dl;
+    HIP_TRY(c, fade_gemm(GEMM_PARTIAL, true, g, s));
+  }
+  {  // Eq. 7: folded LN, then the per-stream memory
+    Prof p(c, "cci_wu");
+    CciArgs a{};
+    a.B = B; a.Dh = Dh; a.splits = c->sp_down; a.stats_n = SN; a.part = c->part_down; a.stats = c->stats_c;
+    a.s_fold = c->s_down; a.t_fold = c->t_down; a.WU = static_cast<const bf16_t *>(c->WU_c); a.y = c->y; a.z = static_cast<bf16_t *>(c->z);
+    HIP_TRY(c, fade_cci(a, s));
+  }
+  {  // Eq. 7: Up
+    Prof p(c, "gemm_up");
+    GemmArgs g{};
+    g.M = B; g.N = Dh; g.K = (int)d.dl;
+    g.A = c->z; g.lda = (int)d.dl; g.W = c->Wup_c; g.C = c->Ha; g.ldc = Dh;
+    HIP_TRY(c, fade_gemm(GEMM_UP, true, g, s));
+  }
+  {  // Eq. 8
+    Prof p(c, "gemm_gate");
+    GemmArgs g{};
+    g.M = B; g.N = Dh; g.K = Dh;
+    g.A = c->Hmix; g.lda = Dh; g.W = c->Wc_c; g.C = c->Hc; g.ldc = Dh; g.C2 = c->sg; g.S1 = c->Ha; g.S2 = c->Hmix;
+    g.lam = c->P(P_LAMBDA_C); g.stats_out = c->stats_f;
+    HIP_TRY(c, fade_gemm(GEMM_GATE, true, g, s));
+  }
+  {  // Eq. 9: H_coarse [W'_fg | W'_fv] as split-K partials
+    Prof p(c, "gemm_fnr_in");
+    GemmArgs g{};
+    g.M = B; g.N = 2 * De; g.K = Dh; g.splits = c->sp_fnr;
+    g.A = c->Hc; g.lda = Dh; g.W = c->Wfgv_c; g.C = c->part_fnr; g.ldc = 2 * De;
+    HIP_TRY(c, fade_gemm(GEMM_PARTIAL, true, g, s));
+  }
+  {
+    Prof p(c, "geglu");
+    GegluArgs a{};
+    a.B = B; a.Dh = Dh; a.De = De; a.splits = c->sp_fnr; a.stats_n = SN; a.part = c->part_fnr; a.stats = c->stats_f;
+    a.s_fold = c->s_fnr; a.t_fold = c->t_fnr; a.Hexp = static_cast<bf16_t *>(c->Hexp);
+    a.eg = static_cast<bf16_t *>(c->eg); a.ev = static_cast<bf16_t *>(c->ev);
+    HIP_TRY(c, fade_geglu(a, s));
+  }
+  {  // Eq. 10: H_expand W_f (+ statistics for its LayerNorm)
+    Prof p(c, "gemm_fnr_out");
+    GemmArgs g{};
+    g.M = B; g.N = Dh; g.K = De;
+    g.A = c->Hexp; g.lda = De; g.W = c->Wf_c; g.C = c->V; g.ldc = Dh; g.stats_out = c->stats_o;
+    HIP_TRY(c, fade_gemm(GEMM_FNR_OUT, true, g, s));
+  }
+  {  // Eq. 10's tail
+    Prof p(c, "hout");
+    HoutArgs a{};
+    a.B = B; a.Dh = Dh; a.stats_n = SN; a.V = static_cast<const bf16_t *>(c->V); a.Hc = static_cast<const bf16_t *>(c->Hc);
+    a.stats = c->stats_o; a.gamma = c->P(P_GAMMA_O); a.beta = c->P(P_BETA_O); a.lam = c->P(P_LAMBDA_O); a.Hout = static_cast<bf16_t *>(c->Hout);
+    HIP_TRY(c, fade_hout(a, s));
+  }
+  {  // head: H W_o as split-K partials; bias and reduction happen in the softmax kernel
+    Prof p(c, "gemm_head");
+    GemmArgs g{};
+    g.M = B; g.N = 256; g.K = Dh; g.splits = c->sp_head;
+    g.A = c->Hout; g.lda = Dh; g.W = c->Wo_c; g.C = c->part_head; g.ldc = 256;
+    HIP_TRY(c, fade_gemm(GEMM_PARTIAL, true, g, s));
+  }
+  {
+    Prof p(c, "softmax_quant_code");
+    SqcArgs a{};
+    a.ws = ws; a.B = B; a.splits = c->sp_head; a.bias = c->P(P_BO); a.logits_out = c->logits; a.logits = c->part_head;
+    a.probs = probs; a.freq = freq; a.sym_base = sym_base; a.cb = c->cb;
+    HIP_TRY(c, fade_softmax_quant_code(a, mode, s));
+  }
+  return FADE_OK;
+}
+
+int forward(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint16_t *freq, float *probs) {
+  return c->bf16 ? forward_bf16(c, ws, mode, sym_base, freq, probs) : forward_f32(c, ws, mode, sym_base, freq, probs);
 }
 
 int check_dev_err(fade_ctx *c) {
@@ -461,6 +591,17 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
     TRY_ALLOC(A(&c->Wfgv_c, d.Dh * 2 * d.De));
     TRY_ALLOC(A(&c->Wf_c, d.De * d.Dh));
     TRY_ALLOC(A(&c->Wo_c, d.Dh * 256));
+    TRY_ALLOC(A(&c->Hout, BDh));
+    c->sp_down = pick_splits((int)((d.B + 63) / 64), (int)(d.Dh / 64), 16);
+    c->sp_fnr = pick_splits((int)((d.B + 127) / 128 * (2 * d.De / 128)), (int)(d.Dh / 64), 8);
+    c->sp_head = pick_splits((int)((d.B + 127) / 128 * 2), (int)(d.Dh / 64), 8);
+    TRY_ALLOC(dev_alloc(c, &c->part_down, (size_t)c->sp_down * d.B * d.dl));
+    TRY_ALLOC(dev_alloc(c, &c->part_fnr, (size_t)c->sp_fnr * d.B * 2 * d.De));
+    TRY_ALLOC(dev_alloc(c, &c->part_head, (size_t)c->sp_head * d.B * 256));
+    TRY_ALLOC(dev_alloc(c, &c->s_down, d.dl));
+    TRY_ALLOC(dev_alloc(c, &c->t_down, d.dl));
+    TRY_ALLOC(dev_alloc(c, &c->s_fnr, 2 * d.De));
+    TRY_ALLOC(dev_alloc(c, &c->t_fnr, 2 * d.De));
   } else {  // fp32: most operands are used straight from the master blob
     c->E_c = c->master + c->lay.off[P_E];
     c->Wg_c = c->master + c->lay.off[P_WG];

@@ -42,7 +42,6 @@ enum {
   PRO_LN,          // (A[m][k] - mean_m) * rstd_m * gamma[k] + beta[k]          (LN of Eq. 7 / Eq. 9)
   PRO_FINAL,       // psi(LN(A)[m][k]) + lam * A2[m][k]                          (Eq. 10, feeding the head)
   PRO_CONV,        // row (b, j): concat over taps r of XL[b][j-(k-1)+r][:], zero where the index is negative (Eq. 4)
-  PRO_DGELU_LN,    // backward helper, see fade_gemm.hip
 };
 enum {
   EPI_STORE = 0,   // C = acc                                   (+ optional row statistics for a following LN)
@@ -52,10 +51,12 @@ enum {
   EPI_GATE,        // s = sigma(acc); C = S1*s + lam*S2         (Eq. 8; S1 = H_a, S2 = H_mix)
   EPI_GEGLU,       // C = psi(acc_gate) * acc_value             (Eq. 9; gate/value interleaved per 128 columns)
   EPI_CONV,        // C = psi(acc + bias[n])                    (Eq. 4)
+  EPI_PARTIAL,     // C (fp32)[split][M][N] = acc of this block's K range (summed later in split order)
 };
 
 struct GemmArgs {
   int M, N, K;            // C[M][N] = A'[M][K] * W[K][N]
+  int splits;             // EPI_PARTIAL: number of K ranges (grid.y); 0 or 1 otherwise
   // A operand
   const void *A;  int lda;
   const void *A2;         // PRO_FINAL: residual source (same leading dimension)

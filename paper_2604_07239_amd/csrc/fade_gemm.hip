@@ -15,8 +15,12 @@
 //     a private L2. Tiles are numbered so that one XCD owns a contiguous range of column tiles for all
 //     row tiles: each XCD then pulls only its 1/8 of W through its L2.
 // fp32 path (small-batch configuration): same prologues/epilogues around a plain FMA core.
+#include <cstdlib>
+
 #include "fade_dev.h"
 #include "fade_kernels.h"
+
+int fade_gemm_tune();
 
 namespace {
 
@@ -186,6 +190,8 @@ __device__ __forceinline__ void epilogue(const GemmArgs &g, const float *Cs, int
         store8(static_cast<AT *>(g.C) + o, out);
         if (g.C2) store8(static_cast<AT *>(g.C2) + o, x);
         if (g.C3) store8(static_cast<AT *>(g.C3) + o, xv);
+      } else if (EPI == EPI_PARTIAL) {
+        store8(static_cast<float *>(g.C) + ((size_t)blockIdx.y * g.M + m) * g.ldc + n0 + c8, x);
       } else if (EPI == EPI_CONV) {
         float bi[8], pre[8];
         load8(g.bias + n0 + c8, bi);
@@ -349,6 +355,126 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
 }
 
 // ---------------------------------------------------------------------------------------------------
+// bf16 MFMA core, pipelined: both operands stream global -> LDS with the asynchronous LDS-DMA loads
+// (global_load_lds_dwordx4: 16 bytes per lane land at M0-base + lane * 16, no registers involved), STAGES
+// K blocks deep. Each 1 KiB DMA is one MFMA fragment (32 rows x 16 k): the lanes gather 16-byte row pieces
+// of the row-major A (two lanes per 32-byte run) or read a ready-made fragment of W, so that the later
+// ds_read_b128 of a fragment is one contiguous, conflict-free 1 KiB read. Synchronisation is by hand:
+// s_waitcnt vmcnt(n) for this wavefront's own DMAs, then a bare s_barrier (a __syncthreads() would drain
+// every outstanding load and with it the pipeline).
+//   A: plain row-major bf16 [M][lda] (rows past M are clamped to row M-1 and never stored)
+//   W: bf16 fragments as written by the weight preparation
+//   grid.y > 1: split K, each block leaves an fp32 partial tile (EPI_PARTIAL)
+// ---------------------------------------------------------------------------------------------------
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+__device__ __forceinline__ void bare_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+__device__ __forceinline__ void dma16(const bf16_t *src, unsigned char *lds_chunk) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                   (__attribute__((address_space(3))) void *)lds_chunk, 16, 0, 0);
+}
+
+template <int BM, int BN, int BK, int STAGES, int EPI>
+__global__ __launch_bounds__(256) void gemm_pipe_kernel(GemmArgs g) {
+  typedef bf16_t AT;
+  constexpr int TM = BM / 64, TN = BN / 64;         // 32x32 tiles per wavefront (wavefronts 2 x 2)
+  constexpr int AFR = BM / 32, BFR = BN / 32, KS = BK / 16;
+  constexpr int NCH = (AFR + BFR) * KS, LPW = NCH / 4, ACH = AFR * KS / 4;  // chunks per stage, per wavefront, of A
+  constexpr int STAGE_BYTES = NCH * 1024, LDC = BN + 4;
+  static_assert(NCH % 4 == 0 && (AFR * KS) % 4 == 0, "chunk split");
+  static_assert((STAGES - 2) * LPW <= 63, "vmcnt range");
+  extern __shared__ __align__(16) unsigned char smem[];
+  float *Cs = reinterpret_cast<float *>(smem);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int ntn = g.N / BN, ntm = (g.M + BM - 1) / BM;
+  int mt, nt;
+  tile_of_block(blockIdx.x, ntm, ntn, mt, nt);
+  const int m0 = mt * BM, n0 = nt * BN;
+  const int ksplit = g.K / (int)gridDim.y, k_begin = (int)blockIdx.y * ksplit, nkb = ksplit / BK;
+  const int ksteps = g.K / 16;
+
+  // this wavefront's DMA sources for one stage; chunk c = wave + 4 q is fragment c / KS, k-step c % KS
+  const bf16_t *src[LPW];
+#pragma unroll
+  for (int q = 0; q < LPW; ++q) {
+    const int c = wave + 4 * q;
+    if (q < ACH) {
+      const int fr = c / KS, ks = c % KS;
+      int row = m0 + fr * 32 + (lane & 31);
+      row = row < g.M ? row : g.M - 1;
+      src[q] = static_cast<const bf16_t *>(g.A) + (size_t)row * g.lda + k_begin + ks * 16 + (lane >> 5) * 8;
+    } else {
+      const int cb = c - AFR * KS, fr = cb / KS, ks = cb % KS;
+      src[q] = static_cast<const bf16_t *>(g.W) + (((size_t)(n0 / 32 + fr) * ksteps + k_begin / 16 + ks) * 64 + lane) * 8;
+    }
+  }
+  auto issue = [&](int slot, int kb) {
+#pragma unroll
+    for (int q = 0; q < LPW; ++q) {
+      const size_t adv = (q < ACH) ? (size_t)kb * BK : (size_t)kb * KS * 512;
+      dma16(src[q] + adv, smem + slot * STAGE_BYTES + (wave + 4 * q) * 1024);
+    }
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+#pragma unroll
+  for (int s = 0; s < STAGES - 1; ++s)
+    if (s < nkb) issue(s, s);
+
+  for (int kb = 0; kb < nkb; ++kb) {
+    // stage kb must have landed; up to STAGES-2 younger stages may stay in flight
+    if (kb + STAGES - 2 < nkb) wait_vmcnt<(STAGES - 2) * LPW>();
+    else wait_vmcnt<0>();
+    bare_barrier();  // everyone's part of stage kb is in LDS, and everyone is done reading stage kb-1
+    if (kb + STAGES - 1 < nkb) issue((kb + STAGES - 1) % STAGES, kb + STAGES - 1);
+    const unsigned char *st = smem + (kb % STAGES) * STAGE_BYTES;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      bf16x8 af[TM], bf[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+        af[i] = *reinterpret_cast<const bf16x8 *>(st + (((wm * TM + i) * KS + ks) * 64 + lane) * 16);
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        bf[j] = *reinterpret_cast<const bf16x8 *>(st + (((AFR + wn * TN + j) * KS + ks) * 64 + lane) * 16);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+    }
+  }
+
+  wait_vmcnt<0>();
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int row = (wm * TM + i) * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+        const int col = (wn * TN + j) * 32 + (lane & 31);
+        Cs[row * LDC + col] = acc[i][j][e];
+      }
+  __syncthreads();
+  epilogue<EPI, AT, BM, BN>(g, Cs, m0, n0, nt, tid);
+}
+
+// ---------------------------------------------------------------------------------------------------
 // fp32 FMA core: 256 threads, each owning 8 consecutive columns of one row; tile (2048 / BN) x BN,
 // K blocks of 32; W is plain [K][N] fp32
 // ---------------------------------------------------------------------------------------------------
@@ -429,6 +555,33 @@ hipError_t launch_bf16(const GemmArgs &g, hipStream_t s) {
   return hipGetLastError();
 }
 
+template <int BM, int BN, int BK, int STAGES, int EPI>
+hipError_t launch_pipe(const GemmArgs &g, hipStream_t s) {
+  constexpr size_t lds_ring = (size_t)STAGES * ((BM + BN) / 32) * (BK / 16) * 1024, lds_c = (size_t)BM * (BN + 4) * sizeof(float);
+  constexpr size_t lds = lds_ring > lds_c ? lds_ring : lds_c;
+  static bool attr_done = false;
+  auto kern = gemm_pipe_kernel<BM, BN, BK, STAGES, EPI>;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const int splits = g.splits > 1 ? g.splits : 1;
+  if (g.N % BN || g.M <= 0 || g.K % (splits * BK) || (EPI != EPI_PARTIAL && splits != 1) || g.lda % 8) return hipErrorInvalidValue;
+  const dim3 grid(((g.M + BM - 1) / BM) * (g.N / BN), splits);
+  hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, g);
+  return hipGetLastError();
+}
+
+// Tile shape by problem size: 128 x 128 when that still gives every compute unit a tile, else 64 x 128.
+template <int EPI>
+hipError_t launch_pipe_auto(const GemmArgs &g, hipStream_t s) {
+  const int tiles128 = ((g.M + 127) / 128) * (g.N / 128);
+  if (fade_gemm_tune() == 1 || (fade_gemm_tune() == 0 && tiles128 >= 256)) return launch_pipe<128, 128, 64, 4, EPI>(g, s);
+  if (fade_gemm_tune() == 3) return launch_pipe<128, 128, 32, 4, EPI>(g, s);
+  return launch_pipe<64, 128, 64, 4, EPI>(g, s);
+}
+
 template <int BN, int PRO, int EPI>
 hipError_t launch_f32_bn(const GemmArgs &g, hipStream_t s) {
   constexpr int BM = 256 / (BN / 8);
@@ -453,19 +606,26 @@ hipError_t launch_f32(const GemmArgs &g, hipStream_t s) {
 
 }  // namespace
 
+// Tuning override for experiments (FADE_GEMM_TUNE: 0 automatic, 1 force 128x128, 2 force 64x128, 3 128x128 with K blocks of 32).
+int fade_gemm_tune() {
+  static int v = -1;
+  if (v < 0) { const char *e = getenv("FADE_GEMM_TUNE"); v = e ? atoi(e) : 0; }
+  return v;
+}
+
 // One entry per (shape class, prologue, epilogue) the model step uses.
 hipError_t fade_gemm(int op, bool bf16, const GemmArgs &g, hipStream_t s) {
   if (bf16) {
     switch (op) {
       case GEMM_CONV:     return launch_bf16<4, 1, 1, 1, PRO_CONV, EPI_CONV>(g, s);       // 128 x 32 tiles
-      case GEMM_GLOBAL:   return launch_bf16<2, 2, 2, 2, PRO_PLAIN, EPI_GLOBAL>(g, s);    // 128 x 128
-      case GEMM_ROUTER:   return launch_bf16<2, 2, 2, 2, PRO_PLAIN, EPI_MIX>(g, s);
-      case GEMM_DOWN:     return launch_bf16<2, 2, 1, 1, PRO_LN, EPI_STORE_F32>(g, s);    // 64 x 64
-      case GEMM_UP:       return launch_bf16<2, 2, 2, 2, PRO_PLAIN, EPI_STORE>(g, s);
-      case GEMM_GATE:     return launch_bf16<2, 2, 2, 2, PRO_PLAIN, EPI_GATE>(g, s);
-      case GEMM_FNR_IN:   return launch_bf16<2, 2, 2, 2, PRO_LN, EPI_GEGLU>(g, s);
-      case GEMM_FNR_OUT:  return launch_bf16<2, 2, 2, 2, PRO_PLAIN, EPI_STORE>(g, s);
-      case GEMM_HEAD:     return launch_bf16<2, 2, 1, 1, PRO_FINAL, EPI_STORE_F32>(g, s);
+      case GEMM_GLOBAL:   return launch_pipe_auto<EPI_GLOBAL>(g, s);
+      case GEMM_ROUTER:   return launch_pipe_auto<EPI_MIX>(g, s);
+      case GEMM_UP:       return launch_pipe_auto<EPI_STORE>(g, s);
+      case GEMM_GATE:     return launch_pipe_auto<EPI_GATE>(g, s);
+      case GEMM_FNR_OUT:  return launch_pipe_auto<EPI_STORE>(g, s);
+      case GEMM_PARTIAL:  // split-K products whose LayerNorm / bias / non-linearity follow in the reducing kernel
+        if (g.N % 128 == 0) return launch_pipe<128, 128, 64, 4, EPI_PARTIAL>(g, s);
+        return launch_pipe<64, 64, 64, 4, EPI_PARTIAL>(g, s);
       default: return hipErrorInvalidValue;
     }
   }

@@ -4,6 +4,7 @@
 
 enum {
   GEMM_CONV = 0, GEMM_GLOBAL, GEMM_ROUTER, GEMM_DOWN, GEMM_UP, GEMM_GATE, GEMM_FNR_IN, GEMM_FNR_OUT, GEMM_HEAD,
+  GEMM_PARTIAL,  // bf16 only: split-K product leaving fp32 partials [splits][M][N]
   GEMM_OP_COUNT
 };
 // Launch one of the model step's products (see fade_gemm.hip). bf16 selects the MFMA path (activations
@@ -34,17 +35,51 @@ struct EmbedArgs {
   float *GG, *GV;             // optional [B][c]: pre-activations of Eq. 1 for the backward pass
 };
 
+// arguments of the kernels that finish a split-K product with a folded LayerNorm (bf16 path)
+struct CciArgs {
+  int B, Dh, splits, stats_n;
+  const float *part;     // [splits][B][64] partials of H_mix W'_down
+  const float *stats;    // [B][stats_n][2] row sums of H_mix
+  const float *s_fold, *t_fold;  // [64]
+  const bf16_t *WU;      // [B][64][64]
+  float *y;              // [B][64] Down(LN(H_mix))
+  bf16_t *z;             // [B][64] y W_U
+};
+struct GegluArgs {
+  int B, Dh, De, splits, stats_n;
+  const float *part;     // [splits][B][2 De] partials, gate | value interleaved per 128 columns
+  const float *stats;    // row sums of H_coarse
+  const float *s_fold, *t_fold;  // [2 De] in the same interleaved order
+  bf16_t *Hexp;          // [B][De]
+  bf16_t *eg, *ev;       // optional [B][De]: pre-activations for the backward pass
+};
+struct HoutArgs {
+  int B, Dh, stats_n;
+  const bf16_t *V, *Hc;
+  const float *stats, *gamma, *beta, *lam;
+  bf16_t *Hout;
+};
+
 struct SqcArgs {
   WinSrc ws;
   int B;
-  const float *logits;  // [B][256]
+  int splits;           // 0: logits are final; > 0: [splits][B][256] partials to be summed, plus bias
+  const float *bias;    // [256] when splits > 0
+  float *logits_out;    // optional [B][256]: the reduced logits
+  const float *logits;  // [B][256] or [splits][B][256]
   float *probs;         // optional [B][256]
   uint16_t *freq;       // optional [B][256]
   uint8_t *sym_base;    // symbol of stream b at step i lives at sym_base + b * ws.stride + i
   CoderBufs cb;
 };
 
-hipError_t fade_preshuffle(const float *W0, const float *W1, int k_real, int K, int N, int interleave, void *out, hipStream_t s);
+hipError_t fade_preshuffle(const float *W0, const float *W1, int k_real, int K, int N, int interleave, const float *rowscale, void *out,
+                           hipStream_t s);
+hipError_t fade_fold_vectors(const float *W0, const float *W1, int K, int N, int interleave, const float *gamma, const float *beta,
+                             float *s_out, float *t_out, hipStream_t s);
+hipError_t fade_cci(const CciArgs &a, hipStream_t s);
+hipError_t fade_geglu(const GegluArgs &a, hipStream_t s);
+hipError_t fade_hout(const HoutArgs &a, hipStream_t s);
 hipError_t fade_virtual_copy(const float *W0, const float *W1, int k_real, int K, int N, int interleave, float *out, hipStream_t s);
 hipError_t fade_convert(const float *src, void *dst, size_t n, bool bf16, hipStream_t s);
 hipError_t fade_round_bf16(const float *src, float *dst, size_t n, hipStream_t s);

@@ -27,7 +27,10 @@ __device__ __forceinline__ float wave_max(float v) {
 // fragments of one 32-column tile are contiguous along K. Rows >= k_real are zero (padding of K).
 // interleave = 1: the source is the pair (W0, W1) of [k_real][N/2] matrices and virtual column v maps to
 // column (v/128)*64 + v%64 of W0 when v%128 < 64, else of W1 (gate and value of Eq. 9 side by side in one tile).
-__global__ void preshuffle_kernel(const float *W0, const float *W1, int k_real, int K, int N, int interleave, bf16_t *out) {
+// rowscale (optional, [k_real]): the stored value is bf16(rowscale[k] * bf16(W[k][n])): a LayerNorm gain folded into
+// the weights of the product that consumes the normalised activations.
+__global__ void preshuffle_kernel(const float *W0, const float *W1, int k_real, int K, int N, int interleave, const float *rowscale,
+                                  bf16_t *out) {
   const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // one thread per (fragment, lane)
   const size_t total = (size_t)(N / 32) * (K / 16) * 64;
   if (t >= total) return;
@@ -46,7 +49,9 @@ __global__ void preshuffle_kernel(const float *W0, const float *W1, int k_real, 
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int k = ks * 16 + (lane >> 5) * 8 + i;
-    r[i] = (bf16_t)(k < k_real ? src[(size_t)k * ld + col] : 0.0f);
+    float w = k < k_real ? src[(size_t)k * ld + col] : 0.0f;
+    if (rowscale && k < k_real) w = rowscale[k] * (float)(bf16_t)w;
+    r[i] = (bf16_t)w;
   }
   reinterpret_cast<bf16x8 *>(out)[t] = r;
 }
@@ -157,6 +162,122 @@ __global__ __launch_bounds__(256) void bmm_kernel(const float *y, const AT *WU, 
 #pragma unroll 8
   for (int k = 0; k < 64; ++k) acc = fmaf(__shfl(yv, k, 64), (float)W[k * 64 + lane], acc);
   z[(size_t)b * 64 + lane] = (AT)acc;
+}
+
+// ---------------------------------------------------------------------------------------------------
+// LayerNorm folded through a product. For u = LN(h) = (h - mean) * rstd * gamma + beta,
+//   u W = rstd * (h W' - mean * s) + t,  W' = diag(gamma) W,  s[n] = sum_k W'[k][n],  t[n] = sum_k beta[k] W[k][n],
+// so the product runs on the raw activations h and the normalisation becomes a per-row / per-column fix-up in
+// the kernel that reduces the split-K partials. s is summed from the bf16 values the matrix cores multiply.
+// ---------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void fold_vectors_kernel(const float *W0, const float *W1, int K, int N, int interleave,
+                                                           const float *gamma, const float *beta, float *s_out, float *t_out) {
+  __shared__ float ps[4][64], pt[4][64];
+  const int v = blockIdx.x * 64 + (threadIdx.x & 63), kq = threadIdx.x >> 6;
+  const float *src = W0;
+  int col = v, ld = N;
+  if (interleave) {
+    ld = N / 2;
+    col = (v / 128) * 64 + (v & 63);
+    if ((v & 127) >= 64) src = W1;
+  }
+  float sa = 0.0f, ta = 0.0f;
+  for (int k = kq; k < K; k += 4) {
+    const float w = (float)(bf16_t)src[(size_t)k * ld + col];
+    sa += (float)(bf16_t)(gamma[k] * w);
+    ta = fmaf(beta[k], w, ta);
+  }
+  ps[kq][threadIdx.x & 63] = sa;
+  pt[kq][threadIdx.x & 63] = ta;
+  __syncthreads();
+  if (kq == 0) {
+    const int c = threadIdx.x;
+    s_out[v] = (ps[0][c] + ps[1][c]) + (ps[2][c] + ps[3][c]);
+    t_out[v] = (pt[0][c] + pt[1][c]) + (pt[2][c] + pt[3][c]);
+  }
+}
+
+__device__ __forceinline__ void moments_from_partials(const float *stats, int stats_n, int width, float &mean, float &rstd) {
+  float s = 0.0f, q = 0.0f;
+  for (int j = 0; j < stats_n; ++j) { s += stats[2 * j]; q += stats[2 * j + 1]; }
+  const float inv = 1.0f / (float)width;
+  mean = s * inv;
+  rstd = 1.0f / sqrtf(fmaxf(q * inv - mean * mean, 0.0f) + 1e-5f);
+}
+
+// Eq. 7 between Down and Up (bf16 path): reduce the split-K partials of H_mix W'_down, apply the folded LayerNorm,
+// then the per-stream memory: z[b] = y[b] W_U[b]. One wavefront per stream, lane = column (d_low = 64).
+__global__ __launch_bounds__(256) void cci_kernel(CciArgs a) {
+  const int b = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (b >= a.B) return;
+  float raw = 0.0f;
+  for (int s = 0; s < a.splits; ++s) raw += a.part[((size_t)s * a.B + b) * 64 + lane];
+  float mean, rstd;
+  moments_from_partials(a.stats + (size_t)b * a.stats_n * 2, a.stats_n, a.Dh, mean, rstd);
+  const float yv = rstd * (raw - mean * a.s_fold[lane]) + a.t_fold[lane];
+  a.y[(size_t)b * 64 + lane] = yv;
+  const bf16_t *W = a.WU + (size_t)b * 4096;
+  float acc = 0.0f;
+#pragma unroll 8
+  for (int k = 0; k < 64; ++k) acc = fmaf(__shfl(yv, k, 64), (float)W[k * 64 + lane], acc);
+  a.z[(size_t)b * 64 + lane] = (bf16_t)acc;
+}
+
+// Eq. 9 (bf16 path): reduce the split-K partials of H_coarse [W'_fg | W'_fv] (gate and value interleaved per 128
+// columns), apply the folded LayerNorm, H_expand = psi(gate) * value. One thread per 8 output columns.
+__global__ __launch_bounds__(256) void geglu_kernel(GegluArgs a) {
+  const int chunks = a.De / 8;
+  const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (t >= (size_t)a.B * chunks) return;
+  const int b = (int)(t / chunks), j8 = (int)(t % chunks) * 8;
+  const int vg = (j8 / 64) * 128 + (j8 & 63), vv = vg + 64, N2 = 2 * a.De;
+  float g[8], v[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) { g[i] = 0.0f; v[i] = 0.0f; }
+  for (int s = 0; s < a.splits; ++s) {
+    const float *row = a.part + ((size_t)s * a.B + b) * N2;
+    const f32x4 g0 = *reinterpret_cast<const f32x4 *>(row + vg), g1 = *reinterpret_cast<const f32x4 *>(row + vg + 4);
+    const f32x4 v0 = *reinterpret_cast<const f32x4 *>(row + vv), v1 = *reinterpret_cast<const f32x4 *>(row + vv + 4);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { g[i] += g0[i]; g[4 + i] += g1[i]; v[i] += v0[i]; v[4 + i] += v1[i]; }
+  }
+  float mean, rstd;
+  moments_from_partials(a.stats + (size_t)b * a.stats_n * 2, a.stats_n, a.Dh, mean, rstd);
+  bf16x8 out, eg, ev;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const float gi = rstd * (g[i] - mean * a.s_fold[vg + i]) + a.t_fold[vg + i];
+    const float vi = rstd * (v[i] - mean * a.s_fold[vv + i]) + a.t_fold[vv + i];
+    out[i] = (bf16_t)(gelu_f(gi) * vi);
+    eg[i] = (bf16_t)gi;
+    ev[i] = (bf16_t)vi;
+  }
+  const size_t o = (size_t)b * a.De + j8;
+  *reinterpret_cast<bf16x8 *>(a.Hexp + o) = out;
+  if (a.eg) { *reinterpret_cast<bf16x8 *>(a.eg + o) = eg; *reinterpret_cast<bf16x8 *>(a.ev + o) = ev; }
+}
+
+// Eq. 10's tail (bf16 path): H = psi(LN(V)) + lambda_o * H_coarse. One thread per 8 columns.
+__global__ __launch_bounds__(256) void hout_kernel(HoutArgs a) {
+  const int chunks = a.Dh / 8;
+  const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (t >= (size_t)a.B * chunks) return;
+  const int b = (int)(t / chunks), c8 = (int)(t % chunks) * 8;
+  float mean, rstd;
+  moments_from_partials(a.stats + (size_t)b * a.stats_n * 2, a.stats_n, a.Dh, mean, rstd);
+  const size_t o = (size_t)b * a.Dh + c8;
+  const bf16x8 v = *reinterpret_cast<const bf16x8 *>(a.V + o), hc = *reinterpret_cast<const bf16x8 *>(a.Hc + o);
+  const f32x4 g0 = *reinterpret_cast<const f32x4 *>(a.gamma + c8), g1 = *reinterpret_cast<const f32x4 *>(a.gamma + c8 + 4);
+  const f32x4 b0 = *reinterpret_cast<const f32x4 *>(a.beta + c8), b1 = *reinterpret_cast<const f32x4 *>(a.beta + c8 + 4);
+  const float lam = a.lam[0];
+  bf16x8 out;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const float ga = i < 4 ? g0[i] : g1[i - 4], be = i < 4 ? b0[i] : b1[i - 4];
+    const float nv = ((float)v[i] - mean) * rstd * ga + be;
+    out[i] = (bf16_t)(gelu_f(nv) + lam * (float)hc[i]);
+  }
+  *reinterpret_cast<bf16x8 *>(a.Hout + o) = out;
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -323,7 +444,12 @@ __global__ __launch_bounds__(256) void softmax_quant_code_kernel(SqcArgs a) {
   const int b = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (b >= a.B) return;
   if (!stream_active(a.ws, b)) return;
-  const f32x4 z = *reinterpret_cast<const f32x4 *>(a.logits + (size_t)b * 256 + 4 * lane);
+  f32x4 z = *reinterpret_cast<const f32x4 *>(a.logits + (size_t)b * 256 + 4 * lane);
+  if (a.splits > 0) {  // logits arrive as split-K partials; the head's bias is added here
+    for (int s = 1; s < a.splits; ++s) z += *reinterpret_cast<const f32x4 *>(a.logits + ((size_t)s * a.B + b) * 256 + 4 * lane);
+    z += *reinterpret_cast<const f32x4 *>(a.bias + 4 * lane);
+    if (a.logits_out) *reinterpret_cast<f32x4 *>(a.logits_out + (size_t)b * 256 + 4 * lane) = z;
+  }
   const float mx = wave_max(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])));
   float p[4];
 #pragma unroll
@@ -433,9 +559,10 @@ inline unsigned blocks_for(size_t n, unsigned per) { return (unsigned)((n + per 
 // ---------------------------------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------------------------------
-hipError_t fade_preshuffle(const float *W0, const float *W1, int k_real, int K, int N, int interleave, void *out, hipStream_t s) {
+hipError_t fade_preshuffle(const float *W0, const float *W1, int k_real, int K, int N, int interleave, const float *rowscale, void *out,
+                           hipStream_t s) {
   const size_t total = (size_t)(N / 32) * (K / 16) * 64;
-  hipLaunchKernelGGL(preshuffle_kernel, dim3(blocks_for(total, 256)), dim3(256), 0, s, W0, W1, k_real, K, N, interleave,
+  hipLaunchKernelGGL(preshuffle_kernel, dim3(blocks_for(total, 256)), dim3(256), 0, s, W0, W1, k_real, K, N, interleave, rowscale,
                      static_cast<bf16_t *>(out));
   return hipGetLastError();
 }
@@ -473,6 +600,24 @@ hipError_t fade_bmm(const float *y, const void *WU, void *z, int B, bool bf16, h
     hipLaunchKernelGGL(bmm_kernel<bf16_t>, dim3((B + 3) / 4), dim3(256), 0, s, y, static_cast<const bf16_t *>(WU), static_cast<bf16_t *>(z), B);
   else
     hipLaunchKernelGGL(bmm_kernel<float>, dim3((B + 3) / 4), dim3(256), 0, s, y, static_cast<const float *>(WU), static_cast<float *>(z), B);
+  return hipGetLastError();
+}
+hipError_t fade_fold_vectors(const float *W0, const float *W1, int K, int N, int interleave, const float *gamma, const float *beta,
+                             float *s_out, float *t_out, hipStream_t s) {
+  if (N % 64) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(fold_vectors_kernel, dim3(N / 64), dim3(256), 0, s, W0, W1, K, N, interleave, gamma, beta, s_out, t_out);
+  return hipGetLastError();
+}
+hipError_t fade_cci(const CciArgs &a, hipStream_t s) {
+  hipLaunchKernelGGL(cci_kernel, dim3((a.B + 3) / 4), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+hipError_t fade_geglu(const GegluArgs &a, hipStream_t s) {
+  hipLaunchKernelGGL(geglu_kernel, dim3(blocks_for((size_t)a.B * (a.De / 8), 256)), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+hipError_t fade_hout(const HoutArgs &a, hipStream_t s) {
+  hipLaunchKernelGGL(hout_kernel, dim3(blocks_for((size_t)a.B * (a.Dh / 8), 256)), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 hipError_t fade_softmax_quant_code(const SqcArgs &a, int mode, hipStream_t s) {
