@@ -25,6 +25,7 @@ sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK = 2.5e15   # MI355X dense bf16, FLOP/s
 HBM_PEAK = 8.0e12         # B/s
+ROUTER_GATE_TRAFFIC_BYTES = {(2, "frozen"): int(0.5 * (52.3 + 49.7) * (1 << 20))}
 
 
 def parse():
@@ -36,6 +37,8 @@ def parse():
     ap.add_argument("--mode", choices=["frozen", "online"], default=None)
     ap.add_argument("--full", action="store_true", help="run the whole job (all L steps) instead of K timed steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 256 MiB device copy (torch) so that a counter run can be scaled against known traffic")
     ap.add_argument("--oracle-streams", type=int, default=64)
     ap.add_argument("--oracle-steps", type=int, default=24)
     return ap.parse_args()
@@ -52,6 +55,14 @@ def main():
     import paper_2604_07239_amd as fa
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if a.copy_calibration:
+        x = torch.ones(256 << 20, dtype=torch.uint8, device="cuda")
+        y = torch.empty_like(x)
+        for _ in range(4):
+            y.copy_(x)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_each_way": x.numel(), "copies": 4}))
+        return
     spec = fi.CONFIGS[a.config]
     B, T, D, H = spec["B"], spec["T"], spec["D"], spec["H"]
     Dh, dl = T * D, 64
@@ -125,9 +136,13 @@ def main():
         us = 0.5 * (kern["gemm_router"]["avg_us"] + kern["gemm_gate"]["avg_us"])
         flop = 2.0 * B * Dh * Dh
         ach = flop / (us * 1e-6) / 1e12
-        roofline = {"bound": "mfma", "kernel": "gemm_bf16 128x128 (router / gate, M=B, N=K=D_h)", "achieved": round(ach, 2),
+        # HBM bytes per launch: FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 from profiles/cfg2_frozen_pmc_counters.md (counter
+        # runs of this same program, scaled against a 256 MiB copy); only known for the configuration profiled.
+        traffic = ROUTER_GATE_TRAFFIC_BYTES.get((a.config, mode))
+        roofline = {"bound": "mfma", "kernel": "gemm_pipe_kernel (router / gate product, M=B, N=K=D_h)", "achieved": round(ach, 2),
                     "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s", "frac": round(ach * 1e12 / MFMA_BF16_PEAK, 4),
-                    "traffic": None, "avg_us": round(us, 2), "flop_per_launch": flop}
+                    "traffic": traffic, "avg_us": round(us, 2), "flop_per_launch": flop,
+                    "algorithmic_bytes_per_launch": 2 * (5 * B * Dh + Dh * Dh)}
     step_us_events = sum(v["avg_us"] for k, v in kern.items() if k != "code_uniform")
 
     cpu = None

@@ -125,7 +125,6 @@ struct fade_ctx {
   uint8_t *payload = nullptr;
   uint32_t *in_len = nullptr;
   size_t payload_cap = 0;
-  StepState *st = nullptr;
   uint8_t *ones = nullptr;
   int *dev_err = nullptr;
   size_t loop_n = 0, loop_next = 0;  // job size and next step of the device-resident loop in progress
@@ -490,6 +489,32 @@ int ensure_payload(fade_ctx *c, size_t L) {
   return FADE_OK;
 }
 
+// Payloads live strided ([B][cap]) on the device and concatenated on the host: one staging buffer, one copy, one kernel.
+// gather: device -> host after encoding (lens_host already filled); else host -> device before decoding (also uploads lengths).
+int move_payloads(fade_ctx *c, uint32_t *lens_host, uint8_t *bytes_host, size_t total, int gather) {
+  const size_t B = c->d.B;
+  std::vector<unsigned long long> off(B);
+  unsigned long long o = 0;
+  for (size_t b = 0; b < B; ++b) { off[b] = o; o += lens_host[b]; }
+  unsigned long long *off_dev = nullptr;
+  uint8_t *flat = nullptr;
+  hipError_t e = hipMalloc(reinterpret_cast<void **>(&off_dev), B * sizeof(unsigned long long));
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&flat), total ? total : 1);
+  hipStream_t s = c->stream;
+  if (e == hipSuccess) e = hipMemcpyAsync(off_dev, off.data(), B * sizeof(unsigned long long), hipMemcpyHostToDevice, s);
+  if (e == hipSuccess && !gather) {
+    e = hipMemcpyAsync(c->in_len, lens_host, B * sizeof(uint32_t), hipMemcpyHostToDevice, s);
+    if (e == hipSuccess && total) e = hipMemcpyAsync(flat, bytes_host, total, hipMemcpyHostToDevice, s);
+  }
+  if (e == hipSuccess) e = fade_payload_move(c->payload, c->payload_cap, flat, off_dev, gather ? c->cb.pos : c->in_len, (int)B, gather, s);
+  if (e == hipSuccess && gather && total) e = hipMemcpyAsync(bytes_host, flat, total, hipMemcpyDeviceToHost, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  (void)hipFree(off_dev);
+  (void)hipFree(flat);
+  if (e != hipSuccess) return hip_fail(c, e, "payload transfer");
+  return FADE_OK;
+}
+
 // the loop of Algorithm 1 on device-resident bytes, steps [first, first + count); mode is CODE_ENCODE or CODE_DECODE
 int run_loop(fade_ctx *c, uint8_t *bytes_dev, size_t n, size_t first, size_t count, int mode) {
   const Dims &d = c->d;
@@ -497,9 +522,9 @@ int run_loop(fade_ctx *c, uint8_t *bytes_dev, size_t n, size_t first, size_t cou
   const size_t L = (n + d.B - 1) / d.B;
   const size_t last = (count == 0 || first + count > L) ? L : first + count;
   WinSrc ws{};
-  ws.base = bytes_dev; ws.stride = (long long)L; ws.n = (long long)n; ws.active = nullptr; ws.st = c->st;
-  HIP_TRY(c, fade_step_set(c->st, (long long)first, s));
+  ws.base = bytes_dev; ws.stride = (long long)L; ws.n = (long long)n; ws.active = nullptr;
   for (size_t i = first; i < last; ++i) {
+    ws.i = (long long)i;
     if (i < d.T) {
       Prof p(c, "code_uniform");
       HIP_TRY(c, fade_code_uniform(ws, bytes_dev, (int)d.B, c->cb, mode, s));
@@ -507,7 +532,6 @@ int run_loop(fade_ctx *c, uint8_t *bytes_dev, size_t n, size_t first, size_t cou
       int rc = forward(c, ws, mode, bytes_dev, nullptr, nullptr);
       if (rc) return rc;
     }
-    HIP_TRY(c, fade_step_advance(c->st, s));
   }
   c->loop_next = last;
   if (mode == CODE_ENCODE && last == L && !c->enc_complete) {
@@ -640,7 +664,6 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
     TRY_ALLOC(dev_alloc(c, p, d.B));
   TRY_ALLOC(dev_alloc(c, &c->in_len, d.B));
   c->cb.in_len = c->in_len;
-  TRY_ALLOC(dev_alloc(c, &c->st, 1));
   TRY_ALLOC(dev_alloc(c, &c->ones, d.B));
   TRY_ALLOC(dev_alloc(c, &c->dev_err, 1));
   c->cb.err = c->dev_err;
@@ -676,8 +699,7 @@ int fade_step_probs(fade_ctx *c, const uint8_t *windows_dev, const uint8_t *acti
   if (!c || !windows_dev) return FADE_E_INVALID_ARG;
   if (!c->have_weights) return fail(c, FADE_E_NO_WEIGHTS, "no weights loaded");
   WinSrc ws{};
-  ws.base = windows_dev; ws.stride = (long long)c->d.T; ws.n = 0; ws.active = active_dev ? active_dev : c->ones; ws.st = c->st;
-  HIP_TRY(c, fade_step_set(c->st, (long long)c->d.T, c->stream));
+  ws.base = windows_dev; ws.stride = (long long)c->d.T; ws.n = 0; ws.active = active_dev ? active_dev : c->ones; ws.i = (long long)c->d.T;
   return forward(c, ws, CODE_NONE, nullptr, freq_dev, probs_dev);
 }
 
@@ -718,14 +740,7 @@ int fade_payloads(fade_ctx *c, uint32_t *lengths_host, uint8_t *bytes_host, size
   for (size_t b = 0; b < B; ++b) sum += lengths_host[b];
   *total = sum;
   if (sum > cap || (!bytes_host && sum)) return fail(c, FADE_E_BUFFER_TOO_SMALL, "payload buffer too small");
-  size_t pos = 0;
-  for (size_t b = 0; b < B; ++b) {
-    if (lengths_host[b])
-      HIP_TRY(c, hipMemcpyAsync(bytes_host + pos, c->payload + b * c->payload_cap, lengths_host[b], hipMemcpyDeviceToHost, c->stream));
-    pos += lengths_host[b];
-  }
-  HIP_TRY(c, hipStreamSynchronize(c->stream));
-  return FADE_OK;
+  return move_payloads(c, lengths_host, bytes_host, sum, 1);
 }
 
 int fade_decode_device(fade_ctx *c, const uint32_t *lengths_host, const uint8_t *bytes_host, size_t total, uint8_t *dst_dev,
@@ -749,12 +764,11 @@ int fade_decode_device(fade_ctx *c, const uint32_t *lengths_host, const uint8_t 
     if (len > c->payload_cap || len > total - pos) return fail(c, FADE_E_CORRUPT_STREAM, "payload length out of range");
     const bool empty = b * L >= n;
     if (empty != (len == 0)) return fail(c, FADE_E_CORRUPT_STREAM, "payload length does not match the stream split");
-    if (len) HIP_TRY(c, hipMemcpyAsync(c->payload + b * c->payload_cap, bytes_host + pos, len, hipMemcpyHostToDevice, c->stream));
     pos += len;
   }
   if (pos != total) return fail(c, FADE_E_CORRUPT_STREAM, "trailing payload bytes");
-  HIP_TRY(c, hipMemcpyAsync(c->in_len, lengths_host, B * sizeof(uint32_t), hipMemcpyHostToDevice, c->stream));
-  HIP_TRY(c, hipStreamSynchronize(c->stream));  // the host buffers may be reused by the caller from here on
+  rc = move_payloads(c, const_cast<uint32_t *>(lengths_host), const_cast<uint8_t *>(bytes_host), total, 0);
+  if (rc) return rc;
   HIP_TRY(c, fade_coder_init(c->cb, (int)B, 1, c->stream));
   c->loop_n = n; c->loop_next = 0; c->loop_mode = CODE_DECODE;
   return run_loop(c, dst_dev, n, 0, n_steps, CODE_DECODE);

@@ -9,12 +9,6 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
-// Step counter living in device memory so that a recorded launch sequence can be replayed unchanged:
-// kernels derive the window position and the activity of a stream from it.
-struct StepState {
-  long long i;  // index of the symbol being coded in every stream
-};
-
 // Where the context windows come from: stream b's window is the T bytes ending just before symbol i,
 // i.e. base + b * stride + (i - T). n is the total byte count (streams past the end are inactive).
 struct WinSrc {
@@ -22,16 +16,16 @@ struct WinSrc {
   long long stride;        // bytes between consecutive streams
   long long n;             // total bytes (stream b is active at step i iff b * stride + i < n and i < stride)
   const uint8_t *active;   // optional explicit mask [B]; overrides the rule above when non-NULL
-  const StepState *st;
+  long long i;             // index of the symbol being coded in every stream
 };
 
 __device__ __forceinline__ bool stream_active(const WinSrc &w, int b) {
   if (w.active) return w.active[b] != 0;
-  const long long i = w.st->i;
+  const long long i = w.i;
   return i < w.stride && (long long)b * w.stride + i < w.n;
 }
 __device__ __forceinline__ const uint8_t *stream_window(const WinSrc &w, int b, int T) {
-  return w.base + (long long)b * w.stride + (w.st->i - T);
+  return w.base + (long long)b * w.stride + (w.i - T);
 }
 
 // ---------------------------------------------------------------------------------------------------

@@ -379,14 +379,18 @@ __device__ __forceinline__ void dma16(const bf16_t *src, unsigned char *lds_chun
                                    (__attribute__((address_space(3))) void *)lds_chunk, 16, 0, 0);
 }
 
-template <int BM, int BN, int BK, int STAGES, int EPI>
+template <int BM, int BN, int STAGES, int EPI>
 __global__ __launch_bounds__(256) void gemm_pipe_kernel(GemmArgs g) {
   typedef bf16_t AT;
-  constexpr int TM = BM / 64, TN = BN / 64;         // 32x32 tiles per wavefront (wavefronts 2 x 2)
-  constexpr int AFR = BM / 32, BFR = BN / 32, KS = BK / 16;
-  constexpr int NCH = (AFR + BFR) * KS, LPW = NCH / 4, ACH = AFR * KS / 4;  // chunks per stage, per wavefront, of A
-  constexpr int STAGE_BYTES = NCH * 1024, LDC = BN + 4;
-  static_assert(NCH % 4 == 0 && (AFR * KS) % 4 == 0, "chunk split");
+  constexpr int BK = 64, KS = 4;
+  constexpr int TM = BM / 64, TN = BN / 64;          // 32x32 tiles per wavefront (wavefronts 2 x 2)
+  constexpr int BFR = BN / 32;
+  constexpr int A_BYTES = BM * 128;                  // A stage: BM rows of 64 k (128 bytes), 16-byte pieces XOR-swizzled
+  constexpr int ACH = BM / 8 / 4;                    // A DMAs per wavefront and stage (one DMA = 8 rows x 128 bytes)
+  constexpr int BCH = BFR * KS / 4;                  // W DMAs per wavefront and stage (one DMA = one fragment)
+  constexpr int LPW = ACH + BCH;
+  constexpr int STAGE_BYTES = A_BYTES + BFR * KS * 1024, LDC = BN + 4;
+  static_assert((BM / 8) % 4 == 0 && (BFR * KS) % 4 == 0, "chunk split");
   static_assert((STAGES - 2) * LPW <= 63, "vmcnt range");
   extern __shared__ __align__(16) unsigned char smem[];
   float *Cs = reinterpret_cast<float *>(smem);
@@ -400,27 +404,31 @@ __global__ __launch_bounds__(256) void gemm_pipe_kernel(GemmArgs g) {
   const int ksplit = g.K / (int)gridDim.y, k_begin = (int)blockIdx.y * ksplit, nkb = ksplit / BK;
   const int ksteps = g.K / 16;
 
-  // this wavefront's DMA sources for one stage; chunk c = wave + 4 q is fragment c / KS, k-step c % KS
+  // DMA sources of this wavefront for one stage.
+  // A: DMA c covers rows 8c .. 8c+7; lane i fetches row r = 8c + i/8, 16-byte piece (i % 8) ^ ((r / 2) % 8): eight lanes
+  //    read one 128-byte run of a row, and the XOR spreads the pieces that a later fragment read touches (16 rows
+  //    x one piece per quarter-wavefront) over all 64 LDS banks.
+  // W: DMA c is fragment c / 4 (32 columns), k-step c % 4, already contiguous.
   const bf16_t *src[LPW];
 #pragma unroll
-  for (int q = 0; q < LPW; ++q) {
+  for (int q = 0; q < ACH; ++q) {
     const int c = wave + 4 * q;
-    if (q < ACH) {
-      const int fr = c / KS, ks = c % KS;
-      int row = m0 + fr * 32 + (lane & 31);
-      row = row < g.M ? row : g.M - 1;
-      src[q] = static_cast<const bf16_t *>(g.A) + (size_t)row * g.lda + k_begin + ks * 16 + (lane >> 5) * 8;
-    } else {
-      const int cb = c - AFR * KS, fr = cb / KS, ks = cb % KS;
-      src[q] = static_cast<const bf16_t *>(g.W) + (((size_t)(n0 / 32 + fr) * ksteps + k_begin / 16 + ks) * 64 + lane) * 8;
-    }
+    int row = m0 + c * 8 + (lane >> 3);
+    row = row < g.M ? row : g.M - 1;
+    const int sw = ((c * 8 + (lane >> 3)) >> 1) & 7;
+    src[q] = static_cast<const bf16_t *>(g.A) + (size_t)row * g.lda + k_begin + (((lane & 7) ^ sw) << 3);
+  }
+#pragma unroll
+  for (int q = 0; q < BCH; ++q) {
+    const int c = wave + 4 * q, fr = c / KS, ks = c % KS;
+    src[ACH + q] = static_cast<const bf16_t *>(g.W) + (((size_t)(n0 / 32 + fr) * ksteps + k_begin / 16 + ks) * 64 + lane) * 8;
   }
   auto issue = [&](int slot, int kb) {
+    unsigned char *base = smem + slot * STAGE_BYTES;
 #pragma unroll
-    for (int q = 0; q < LPW; ++q) {
-      const size_t adv = (q < ACH) ? (size_t)kb * BK : (size_t)kb * KS * 512;
-      dma16(src[q] + adv, smem + slot * STAGE_BYTES + (wave + 4 * q) * 1024);
-    }
+    for (int q = 0; q < ACH; ++q) dma16(src[q] + (size_t)kb * BK, base + (wave + 4 * q) * 1024);
+#pragma unroll
+    for (int q = 0; q < BCH; ++q) dma16(src[ACH + q] + (size_t)kb * KS * 512, base + A_BYTES + (wave + 4 * q) * 1024);
   };
 
   f32x16 acc[TM][TN];
@@ -435,6 +443,12 @@ __global__ __launch_bounds__(256) void gemm_pipe_kernel(GemmArgs g) {
   for (int s = 0; s < STAGES - 1; ++s)
     if (s < nkb) issue(s, s);
 
+  // fragment read offsets inside a stage: row r, k-step ks, half h -> r * 128 + (((2 ks + h) ^ ((r / 2) & 7)) * 16)
+  int a_off[TM];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) a_off[i] = ((wm * TM + i) * 32 + (lane & 31)) * 128;
+  const int a_sw = (lane >> 1) & 7, a_half = lane >> 5;  // tile rows start at multiples of 32, so (r / 2) & 7 == (lane / 2) & 7
+
   for (int kb = 0; kb < nkb; ++kb) {
     // stage kb must have landed; up to STAGES-2 younger stages may stay in flight
     if (kb + STAGES - 2 < nkb) wait_vmcnt<(STAGES - 2) * LPW>();
@@ -442,19 +456,28 @@ __global__ __launch_bounds__(256) void gemm_pipe_kernel(GemmArgs g) {
     bare_barrier();  // everyone's part of stage kb is in LDS, and everyone is done reading stage kb-1
     if (kb + STAGES - 1 < nkb) issue((kb + STAGES - 1) % STAGES, kb + STAGES - 1);
     const unsigned char *st = smem + (kb % STAGES) * STAGE_BYTES;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      bf16x8 af[TM], bf[TN];
+    // fragments of k-step ks+1 are fetched from LDS while the matrix cores work on k-step ks
+    bf16x8 af[2][TM], bf[2][TN];
+    auto fetch = [&](int buf, int ks) {
 #pragma unroll
       for (int i = 0; i < TM; ++i)
-        af[i] = *reinterpret_cast<const bf16x8 *>(st + (((wm * TM + i) * KS + ks) * 64 + lane) * 16);
+        af[buf][i] = *reinterpret_cast<const bf16x8 *>(st + a_off[i] + (((2 * ks + a_half) ^ a_sw) << 4));
 #pragma unroll
       for (int j = 0; j < TN; ++j)
-        bf[j] = *reinterpret_cast<const bf16x8 *>(st + (((AFR + wn * TN + j) * KS + ks) * 64 + lane) * 16);
+        bf[buf][j] = *reinterpret_cast<const bf16x8 *>(st + A_BYTES + ((((wn * TN + j) * KS + ks) * 64 + lane) << 4));
+    };
+    fetch(0, 0);
+    __builtin_amdgcn_sched_barrier(0);  // keep the scheduler from sinking the reads next to their uses
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      if (ks + 1 < KS) fetch((ks + 1) & 1, ks + 1);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bf[ks & 1][j], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
 
@@ -555,12 +578,13 @@ hipError_t launch_bf16(const GemmArgs &g, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <int BM, int BN, int BK, int STAGES, int EPI>
+template <int BM, int BN, int STAGES, int EPI>
 hipError_t launch_pipe(const GemmArgs &g, hipStream_t s) {
-  constexpr size_t lds_ring = (size_t)STAGES * ((BM + BN) / 32) * (BK / 16) * 1024, lds_c = (size_t)BM * (BN + 4) * sizeof(float);
+  constexpr int BK = 64;
+  constexpr size_t lds_ring = (size_t)STAGES * (BM * 128 + (BN / 32) * 4 * 1024), lds_c = (size_t)BM * (BN + 4) * sizeof(float);
   constexpr size_t lds = lds_ring > lds_c ? lds_ring : lds_c;
   static bool attr_done = false;
-  auto kern = gemm_pipe_kernel<BM, BN, BK, STAGES, EPI>;
+  auto kern = gemm_pipe_kernel<BM, BN, STAGES, EPI>;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
@@ -577,9 +601,11 @@ hipError_t launch_pipe(const GemmArgs &g, hipStream_t s) {
 template <int EPI>
 hipError_t launch_pipe_auto(const GemmArgs &g, hipStream_t s) {
   const int tiles128 = ((g.M + 127) / 128) * (g.N / 128);
-  if (fade_gemm_tune() == 1 || (fade_gemm_tune() == 0 && tiles128 >= 256)) return launch_pipe<128, 128, 64, 4, EPI>(g, s);
-  if (fade_gemm_tune() == 3) return launch_pipe<128, 128, 32, 4, EPI>(g, s);
-  return launch_pipe<64, 128, 64, 4, EPI>(g, s);
+  if (fade_gemm_tune() == 1 || (fade_gemm_tune() == 0 && tiles128 >= 256)) return launch_pipe<128, 128, 4, EPI>(g, s);
+  if (fade_gemm_tune() == 4) return launch_pipe<64, 128, 3, EPI>(g, s);
+  if (fade_gemm_tune() == 5) return launch_pipe<64, 128, 2, EPI>(g, s);
+  if (fade_gemm_tune() == 6) return launch_pipe<64, 128, 6, EPI>(g, s);
+  return launch_pipe<64, 128, 4, EPI>(g, s);
 }
 
 template <int BN, int PRO, int EPI>
@@ -606,7 +632,7 @@ hipError_t launch_f32(const GemmArgs &g, hipStream_t s) {
 
 }  // namespace
 
-// Tuning override for experiments (FADE_GEMM_TUNE: 0 automatic, 1 force 128x128, 2 force 64x128, 3 128x128 with K blocks of 32).
+// Tuning override for experiments (FADE_GEMM_TUNE: 0 automatic, 1 force 128x128, 2 force 64x128).
 int fade_gemm_tune() {
   static int v = -1;
   if (v < 0) { const char *e = getenv("FADE_GEMM_TUNE"); v = e ? atoi(e) : 0; }
@@ -624,8 +650,8 @@ hipError_t fade_gemm(int op, bool bf16, const GemmArgs &g, hipStream_t s) {
       case GEMM_GATE:     return launch_pipe_auto<EPI_GATE>(g, s);
       case GEMM_FNR_OUT:  return launch_pipe_auto<EPI_STORE>(g, s);
       case GEMM_PARTIAL:  // split-K products whose LayerNorm / bias / non-linearity follow in the reducing kernel
-        if (g.N % 128 == 0) return launch_pipe<128, 128, 64, 4, EPI_PARTIAL>(g, s);
-        return launch_pipe<64, 64, 64, 4, EPI_PARTIAL>(g, s);
+        if (g.N % 128 == 0) return launch_pipe<128, 128, 4, EPI_PARTIAL>(g, s);
+        return launch_pipe<64, 64, 4, EPI_PARTIAL>(g, s);
       default: return hipErrorInvalidValue;
     }
   }

@@ -93,5 +93,5 @@ hipError_t fade_code_tables(const uint16_t *freq, uint8_t *sym, int n_streams, c
 hipError_t fade_code_uniform(const WinSrc &ws, uint8_t *sym_base, int B, const CoderBufs &cb, int mode, hipStream_t s);
 hipError_t fade_coder_init(const CoderBufs &cb, int B, int decode, hipStream_t s);
 hipError_t fade_coder_finish(const CoderBufs &cb, int B, long long stride, long long n, hipStream_t s);
-hipError_t fade_step_set(StepState *st, long long i, hipStream_t s);
-hipError_t fade_step_advance(StepState *st, hipStream_t s);
+hipError_t fade_payload_move(uint8_t *strided, size_t cap, uint8_t *flat, const unsigned long long *offsets, const uint32_t *lens, int B,
+                             int gather, hipStream_t s);

@@ -471,7 +471,7 @@ __global__ __launch_bounds__(256) void softmax_quant_code_kernel(SqcArgs a) {
     *reinterpret_cast<ushort4 *>(a.freq + (size_t)b * 256 + 4 * lane) = f;
   }
   if (MODE != CODE_NONE) {
-    uint8_t *sym = a.sym_base + (long long)b * a.ws.stride + a.ws.st->i;
+    uint8_t *sym = a.sym_base + (long long)b * a.ws.stride + a.ws.i;
     code_wave<MODE>(a.cb, b, lane, q, sym);
   }
 }
@@ -506,7 +506,7 @@ template <int MODE>
 __global__ void code_uniform_kernel(WinSrc ws, uint8_t *sym_base, int B, CoderBufs cb) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
   if (b >= B || !stream_active(ws, b)) return;
-  uint8_t *sym = sym_base + (long long)b * ws.stride + ws.st->i;
+  uint8_t *sym = sym_base + (long long)b * ws.stride + ws.i;
   if (MODE == CODE_ENCODE) {
     const uint32_t s = *sym;
     EncState e;
@@ -549,8 +549,18 @@ __global__ void coder_finish_kernel(CoderBufs cb, int B, long long stride, long 
   enc_store(cb, b, e);
 }
 
-__global__ void step_set_kernel(StepState *st, long long i) { st->i = i; }
-__global__ void step_advance_kernel(StepState *st) { st->i += 1; }
+// Move per-stream payloads between the strided working buffer [B][cap] and one contiguous run (offsets[b], lens[b]).
+// gather != 0: strided -> contiguous (after encoding); else contiguous -> strided (before decoding).
+__global__ __launch_bounds__(256) void payload_move_kernel(uint8_t *strided, size_t cap, uint8_t *flat, const unsigned long long *offsets,
+                                                           const uint32_t *lens, int gather) {
+  const int b = blockIdx.x;
+  const uint32_t len = lens[b];
+  uint8_t *s = strided + (size_t)b * cap, *f = flat + offsets[b];
+  for (uint32_t i = threadIdx.x; i < len; i += 256) {
+    if (gather) f[i] = s[i];
+    else s[i] = f[i];
+  }
+}
 
 inline unsigned blocks_for(size_t n, unsigned per) { return (unsigned)((n + per - 1) / per); }
 
@@ -651,11 +661,8 @@ hipError_t fade_coder_finish(const CoderBufs &cb, int B, long long stride, long 
   hipLaunchKernelGGL(coder_finish_kernel, dim3((B + 63) / 64), dim3(64), 0, s, cb, B, stride, n);
   return hipGetLastError();
 }
-hipError_t fade_step_set(StepState *st, long long i, hipStream_t s) {
-  hipLaunchKernelGGL(step_set_kernel, dim3(1), dim3(1), 0, s, st, i);
-  return hipGetLastError();
-}
-hipError_t fade_step_advance(StepState *st, hipStream_t s) {
-  hipLaunchKernelGGL(step_advance_kernel, dim3(1), dim3(1), 0, s, st);
+hipError_t fade_payload_move(uint8_t *strided, size_t cap, uint8_t *flat, const unsigned long long *offsets, const uint32_t *lens, int B,
+                             int gather, hipStream_t s) {
+  hipLaunchKernelGGL(payload_move_kernel, dim3(B), dim3(256), 0, s, strided, cap, flat, offsets, lens, gather);
   return hipGetLastError();
 }
