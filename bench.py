@@ -40,7 +40,7 @@ def parse():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 256 MiB device copy (torch) so that a counter run can be scaled against known traffic")
     ap.add_argument("--oracle-streams", type=int, default=64)
-    ap.add_argument("--oracle-steps", type=int, default=24)
+    ap.add_argument("--oracle-steps", type=int, default=None, help="model steps of the oracle sample (default 24 frozen, 8 online)")
     return ap.parse_args()
 
 
@@ -67,8 +67,7 @@ def main():
     B, T, D, H = spec["B"], spec["T"], spec["D"], spec["H"]
     Dh, dl = T * D, 64
     dtype = fa.BF16 if spec["dtype"] == "bf16" else fa.F32
-    online_ok = hasattr(fa, "ONLINE_SUPPORTED") and fa.ONLINE_SUPPORTED
-    mode = a.mode or ("online" if online_ok else "frozen")
+    mode = a.mode or "online"   # the method adapts its weights while coding (Algorithm 1); frozen is the inference-only variant
     K, W = a.steps, a.warmup
 
     full = fi.config_bytes(a.config)
@@ -148,7 +147,7 @@ def main():
     cpu = None
     if not a.no_cpu_baseline:
         import oracle as orc
-        Bo, So = min(a.oracle_streams, B), a.oracle_steps
+        Bo, So = min(a.oracle_streams, B), (a.oracle_steps or (8 if mode == "online" else 24))
         sub = fi.slice_blob(blob, spec, Bo) if Bo != B else blob
         o = orc.Oracle(orc.make_config(Bo, T, D, H, dtype=orc.BF16 if spec["dtype"] == "bf16" else orc.F32,
                                        update_mode=orc.ONLINE_ADAM if mode == "online" else orc.FROZEN))

@@ -166,6 +166,10 @@ size_t fade_tap(fade_ctx *ctx, int which, float *out_host, size_t cap_floats);
 /* Current master weights as a canonical fp32 blob (after online updates). */
 int fade_get_weights(fade_ctx *ctx, void *blob_host, size_t nbytes);
 
+/* Debug/test: the gradient of the mean NLL computed by the most recent fade_step_update, in blob layout (fp32).
+ * The W_U range is not filled: those gradients are consumed inside the kernel that applies them. */
+int fade_debug_grad(fade_ctx *ctx, void *blob_host, size_t nbytes);
+
 /* Per-kernel device time of the most recent fade_encode_device / fade_decode_device, measured with HIP
  * events on the context's stream when enabled by fade_profile(ctx, 1): names[i] / ms[i] / launches[i] for
  * i < returned count (at most cap). Profiling serialises launches and is off by default. */

@@ -7,3 +7,5 @@ calls raise.
 from .binding import (BF16, F32, FROZEN, ONLINE_ADAM, TAPS, Config, Fade, FadeError, lib, make_config,  # noqa: F401
                       weights_nbytes)
 from .buildlib import LIB, build  # noqa: F401
+
+ONLINE_SUPPORTED = True

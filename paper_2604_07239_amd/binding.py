@@ -67,6 +67,7 @@ def lib():
         L.fade_tap.restype = sz
         L.fade_tap.argtypes = [vp, C.c_int, vp, sz]
         L.fade_get_weights.argtypes = [vp, vp, sz]
+        L.fade_debug_grad.argtypes = [vp, vp, sz]
         L.fade_profile.argtypes = [vp, C.c_int]
         L.fade_profile_read.argtypes = [vp, C.POINTER(C.c_char_p), C.POINTER(C.c_double), C.POINTER(C.c_uint64), C.c_int]
         L.fade_last_error.restype = C.c_char_p
@@ -134,6 +135,12 @@ class Fade:
         n = weights_nbytes(self.cfg)
         out = np.zeros(n // 4, np.float32)
         self._chk(self.L.fade_get_weights(self.h, _hp(out), n))
+        return out
+
+    def debug_grad(self):
+        n = weights_nbytes(self.cfg)
+        out = np.zeros(n // 4, np.float32)
+        self._chk(self.L.fade_debug_grad(self.h, _hp(out), n))
         return out
 
     # -- the step --------------------------------------------------------------------------------

@@ -1,4 +1,5 @@
 // fade_api.hip — libfade's C ABI: context, device state, the step sequence and the compress / decompress loops.
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -119,6 +120,20 @@ struct fade_ctx {
   // kept for the backward pass (online mode only)
   void *hm = nullptr, *alpha = nullptr, *sg = nullptr, *eg = nullptr, *ev = nullptr, *cv = nullptr;
   float *GG = nullptr, *GV = nullptr;
+  float *probs_buf = nullptr;
+  // online update: gradients, optimiser state, backward temporaries (see backward())
+  size_t Bp = 0;  // batch rounded up to 64: leading dimension of the feature-major copies and row count of GEMM_W operands
+  float *grad = nullptr, *adam_m = nullptr, *adam_v = nullptr;
+  UpdateState *ustate = nullptr;
+  float *tabXhat = nullptr, *tabRstd = nullptr, *convt_f32 = nullptr;
+  void *WT_o = nullptr, *WT_f = nullptr, *WT_fgv = nullptr, *WT_c = nullptr, *WT_up = nullptr, *WT_down = nullptr, *WT_r = nullptr,
+       *WT_conv = nullptr;
+  void *dl = nullptr, *dHout = nullptr, *dnv = nullptr, *dV = nullptr, *dHc = nullptr, *dHexp = nullptr, *dE = nullptr, *du = nullptr,
+       *dHa = nullptr, *dac = nullptr, *dHmix1 = nullptr, *dHmix2 = nullptr, *dy_at = nullptr, *dnc = nullptr, *dar = nullptr,
+       *dhm = nullptr, *dcv = nullptr, *dX1 = nullptr, *dX2 = nullptr, *dxl = nullptr, *LT = nullptr, *RT = nullptr;
+  float *dz_part = nullptr, *dy = nullptr, *dgg = nullptr, *dgv = nullptr, *dxt = nullptr, *de = nullptr, *row_dlam = nullptr,
+        *conv_part = nullptr, *tok_part = nullptr;
+  int sp_dz = 1, conv_blocks = 256;
 
   // coder and step bookkeeping
   CoderBufs cb{};
@@ -126,6 +141,7 @@ struct fade_ctx {
   uint32_t *in_len = nullptr;
   size_t payload_cap = 0;
   uint8_t *ones = nullptr;
+  WinSrc last_ws{};
   int *dev_err = nullptr;
   size_t loop_n = 0, loop_next = 0;  // job size and next step of the device-resident loop in progress
   int loop_mode = 0;
@@ -201,7 +217,7 @@ void prof_collect(fade_ctx *c) {
 // ---------------------------------------------------------------------------------------------------
 // master weights -> compute copies (runs on the stream; repeated after every online update)
 // ---------------------------------------------------------------------------------------------------
-int prepare_compute(fade_ctx *c) {
+int prepare_compute(fade_ctx *c, bool with_wu = true) {
   const Dims &d = c->d;
   hipStream_t s = c->stream;
   if (c->bf16) {
@@ -220,13 +236,27 @@ int prepare_compute(fade_ctx *c) {
     HIP_TRY(c, fade_fold_vectors(c->P(P_WDOWN), nullptr, (int)d.Dh, (int)d.dl, 0, c->P(P_GAMMA_C), c->P(P_BETA_C), c->s_down, c->t_down, s));
     HIP_TRY(c, fade_preshuffle(c->P(P_WFG), c->P(P_WFV), (int)d.Dh, (int)d.Dh, (int)(2 * d.De), 1, c->P(P_GAMMA_F), c->Wfgv_c, s));
     HIP_TRY(c, fade_fold_vectors(c->P(P_WFG), c->P(P_WFV), (int)d.Dh, (int)(2 * d.De), 1, c->P(P_GAMMA_F), c->P(P_BETA_F), c->s_fnr, c->t_fnr, s));
-    HIP_TRY(c, fade_convert(c->P(P_WU), c->WU_c, d.B * d.dl * d.dl, true, s));
+    if (with_wu) HIP_TRY(c, fade_convert(c->P(P_WU), c->WU_c, d.B * d.dl * d.dl, true, s));
   } else {
     HIP_TRY(c, fade_virtual_copy(c->P(P_WCONV), nullptr, (int)(d.k * d.D), (int)d.Kc, (int)d.D, 0, static_cast<float *>(c->Wconv_c), s));
     HIP_TRY(c, fade_virtual_copy(c->P(P_WFG), c->P(P_WFV), (int)d.Dh, (int)d.Dh, (int)(2 * d.De), 1, static_cast<float *>(c->Wfgv_c), s));
   }
   HIP_TRY(c, fade_tables(c->E_c, c->P(P_GAMMA_E), c->P(P_BETA_E), c->P(P_GAMMA_L), c->P(P_BETA_L), (int)d.D, c->tabXe,
                          c->tabXl, c->tabXe32, c->bf16, s));
+  if (c->online) {  // operands of the backward pass
+    HIP_TRY(c, fade_tables_bwd(c->E_c, (int)d.D, c->tabXhat, c->tabRstd, s));
+    HIP_TRY(c, fade_convt_build(c->P(P_WCONV), (int)d.k, (int)d.D, (int)d.Kc, c->convt_f32, s));
+    if (c->bf16) {
+      HIP_TRY(c, fade_preshuffle(c->convt_f32, nullptr, (int)d.Kc, (int)d.Kc, (int)d.D, 0, nullptr, c->WT_conv, s));
+      HIP_TRY(c, fade_preshuffle_t(c->P(P_WO), nullptr, (int)d.Dh, 256, 0, c->WT_o, s));
+      HIP_TRY(c, fade_preshuffle_t(c->P(P_WF), nullptr, (int)d.De, (int)d.Dh, 0, c->WT_f, s));
+      HIP_TRY(c, fade_preshuffle_t(c->P(P_WFG), c->P(P_WFV), (int)d.Dh, (int)(2 * d.De), 1, c->WT_fgv, s));
+      HIP_TRY(c, fade_preshuffle_t(c->P(P_WC), nullptr, (int)d.Dh, (int)d.Dh, 0, c->WT_c, s));
+      HIP_TRY(c, fade_preshuffle_t(c->P(P_WUP), nullptr, (int)d.dl, (int)d.Dh, 0, c->WT_up, s));
+      HIP_TRY(c, fade_preshuffle_t(c->P(P_WDOWN), nullptr, (int)d.Dh, (int)d.dl, 0, c->WT_down, s));
+      HIP_TRY(c, fade_preshuffle_t(c->P(P_WR), nullptr, (int)d.Dh, (int)d.Dh, 0, c->WT_r, s));
+    }
+  }
   return FADE_OK;
 }
 
@@ -239,6 +269,12 @@ int do_reset(fade_ctx *c) {
     HIP_TRY(c, hipMemcpyAsync(c->master, c->loaded.data(), c->loaded.size() * sizeof(float), hipMemcpyHostToDevice, s));
     int rc = prepare_compute(c);
     if (rc) return rc;
+  }
+  if (c->online) {
+    const size_t np = c->lay.off[P_COUNT];
+    HIP_TRY(c, hipMemsetAsync(c->adam_m, 0, np * sizeof(float), s));
+    HIP_TRY(c, hipMemsetAsync(c->adam_v, 0, np * sizeof(float), s));
+    HIP_TRY(c, hipMemsetAsync(c->ustate, 0, sizeof(UpdateState), s));
   }
   c->enc_complete = false;
   HIP_TRY(c, hipStreamSynchronize(s));
@@ -325,6 +361,13 @@ int forward_f32(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint
     g.M = B; g.N = Dh; g.K = (int)d.De;
     g.A = c->Hexp; g.lda = (int)d.De; g.W = c->Wf_c; g.C = c->V; g.ldc = Dh; g.stats_out = c->stats_o;
     HIP_TRY(c, fade_gemm(GEMM_FNR_OUT, bf, g, s));
+  }
+  if (c->online) {  // the update needs H itself (for dW_o); frozen mode forms it only inside the head's operand load
+    Prof p(c, "hout");
+    HoutArgs a{};
+    a.B = B; a.Dh = Dh; a.stats_n = SN; a.V = c->V; a.Hc = c->Hc; a.stats = c->stats_o; a.gamma = c->P(P_GAMMA_O);
+    a.beta = c->P(P_BETA_O); a.lam = c->P(P_LAMBDA_O); a.Hout = c->Hout;
+    HIP_TRY(c, fade_hout(a, false, s));
   }
   {  // Eq. 10's tail fused into the head's operand load; logits = H W_o + b_o
     Prof p(c, "gemm_head");
@@ -440,9 +483,9 @@ int forward_bf16(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uin
   {  // Eq. 10's tail
     Prof p(c, "hout");
     HoutArgs a{};
-    a.B = B; a.Dh = Dh; a.stats_n = SN; a.V = static_cast<const bf16_t *>(c->V); a.Hc = static_cast<const bf16_t *>(c->Hc);
-    a.stats = c->stats_o; a.gamma = c->P(P_GAMMA_O); a.beta = c->P(P_BETA_O); a.lam = c->P(P_LAMBDA_O); a.Hout = static_cast<bf16_t *>(c->Hout);
-    HIP_TRY(c, fade_hout(a, s));
+    a.B = B; a.Dh = Dh; a.stats_n = SN; a.V = c->V; a.Hc = c->Hc;
+    a.stats = c->stats_o; a.gamma = c->P(P_GAMMA_O); a.beta = c->P(P_BETA_O); a.lam = c->P(P_LAMBDA_O); a.Hout = c->Hout;
+    HIP_TRY(c, fade_hout(a, true, s));
   }
   {  // head: H W_o as split-K partials; bias and reduction happen in the softmax kernel
     Prof p(c, "gemm_head");
@@ -462,7 +505,185 @@ int forward_bf16(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uin
 }
 
 int forward(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint16_t *freq, float *probs) {
-  return c->bf16 ? forward_bf16(c, ws, mode, sym_base, freq, probs) : forward_f32(c, ws, mode, sym_base, freq, probs);
+  float *p = c->online ? c->probs_buf : probs;  // the update needs the probabilities: keep them in the context
+  int rc = c->bf16 ? forward_bf16(c, ws, mode, sym_base, freq, p) : forward_f32(c, ws, mode, sym_base, freq, p);
+  if (rc) return rc;
+  if (c->online && probs)
+    HIP_TRY(c, hipMemcpyAsync(probs, c->probs_buf, c->d.B * 256 * sizeof(float), hipMemcpyDeviceToDevice, c->stream));
+  return FADE_OK;
+}
+
+// ---------------------------------------------------------------------------------------------------
+// the online update: gradient of the mean NLL (Eq. 12) through the step, then Adam on every parameter
+// ---------------------------------------------------------------------------------------------------
+// dX = dY W^T. bf16: W^T lives as a second fragment set (wt_frag); fp32: W itself, read transposed.
+int gemm_x(fade_ctx *c, const char *name, const void *dY, int Kred, int Nout, const void *wt_frag, const float *w_f32, int ld_w, void *out) {
+  Prof p(c, name);
+  GemmArgs g{};
+  g.M = (int)c->d.B; g.N = Nout; g.K = Kred; g.A = dY; g.lda = Kred; g.C = out; g.ldc = Nout;
+  if (c->bf16) g.W = wt_frag;
+  else { g.W = w_f32; g.wt = 1; g.ldb = ld_w; }
+  HIP_TRY(c, fade_gemm(GEMM_X_STORE, c->bf16, g, c->stream));
+  return FADE_OK;
+}
+// dW[Kw][N] = L^T R over the batch. L: activation [B][Kw] (optionally through a LayerNorm), R: gradient [Bp][N].
+int gemm_w(fade_ctx *c, const char *name, const void *L, int Kw, const float *ln_stats, const float *ln_gamma, const float *ln_beta,
+           const void *R, int N, float *dW, float *dW_pair) {
+  const Dims &d = c->d;
+  hipStream_t s = c->stream;
+  {
+    Prof p(c, "transpose");
+    TransposeArgs t{};
+    t.src = L; t.ld = Kw; t.dst = c->LT; t.Bp = (int)c->Bp; t.B = (int)d.B;
+    t.stats = ln_stats; t.stats_n = (int)(d.Dh / FADE_STATS_BN); t.width = Kw; t.gamma = ln_gamma; t.beta = ln_beta;
+    HIP_TRY(c, fade_transpose(t, Kw, c->bf16, s));
+    if (c->bf16) {
+      TransposeArgs r{};
+      r.src = R; r.ld = N; r.dst = c->RT; r.Bp = (int)c->Bp; r.B = (int)d.B;
+      HIP_TRY(c, fade_transpose(r, N, true, s));
+    }
+  }
+  Prof p(c, name);
+  GemmArgs g{};
+  g.M = Kw; g.N = N; g.K = (int)c->Bp; g.A = c->LT; g.lda = (int)c->Bp; g.C = dW; g.C3 = dW_pair; g.ldc = N;
+  if (c->bf16) { g.W = c->RT; g.ldb = (int)c->Bp; }
+  else g.W = R;
+  HIP_TRY(c, fade_gemm(GEMM_W, c->bf16, g, s));
+  return FADE_OK;
+}
+
+int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long tstride) {
+  const Dims &d = c->d;
+  hipStream_t s = c->stream;
+  const bool bf = c->bf16;
+  const int B = (int)d.B, Dh = (int)d.Dh, De = (int)d.De, dl = (int)d.dl, SN = (int)(d.Dh / FADE_STATS_BN);
+  float *G = c->grad;
+  auto Gp = [&](int id) { return G + c->lay.off[id]; };
+  int rc;
+  {
+    Prof p(c, "bwd_prep_dlogits");
+    HIP_TRY(c, fade_update_prep(ws, B, c->ustate, c->cfg.beta1, c->cfg.beta2, s));
+    HIP_TRY(c, fade_dlogits(ws, targets, tstride, B, c->probs_buf, c->ustate, c->dl, bf, s));
+    HIP_TRY(c, fade_colsum(B, 256, c->dl, Gp(P_BO), bf, s));
+  }
+  // head
+  if ((rc = gemm_w(c, "gemm_dW_o", c->Hout, Dh, nullptr, nullptr, nullptr, c->dl, 256, Gp(P_WO), nullptr))) return rc;
+  if ((rc = gemm_x(c, "gemm_dHout", c->dl, 256, Dh, c->WT_o, c->P(P_WO), 256, c->dHout))) return rc;
+  {  // Eq. 10
+    Prof p(c, "bwd_out");
+    BwdOutArgs a{};
+    a.Dh = Dh; a.stats_n = SN; a.dH = c->dHout; a.V = c->V; a.Hc = c->Hc; a.stats = c->stats_o; a.gamma = c->P(P_GAMMA_O);
+    a.beta = c->P(P_BETA_O); a.lam = c->P(P_LAMBDA_O); a.dnv = c->dnv; a.dV = c->dV; a.dHc = c->dHc; a.row_dlam = c->row_dlam;
+    HIP_TRY(c, fade_bwd_out(a, B, bf, s));
+    HIP_TRY(c, fade_ln_param_grad(B, Dh, SN, c->dnv, c->V, c->stats_o, Gp(P_GAMMA_O), Gp(P_BETA_O), bf, s));
+  }
+  if ((rc = gemm_w(c, "gemm_dW_f", c->Hexp, De, nullptr, nullptr, nullptr, c->dV, Dh, Gp(P_WF), nullptr))) return rc;
+  if ((rc = gemm_x(c, "gemm_dHexp", c->dV, Dh, De, c->WT_f, c->P(P_WF), Dh, c->dHexp))) return rc;
+  {  // Eq. 9
+    Prof p(c, "bwd_geglu");
+    HIP_TRY(c, fade_bwd_geglu(B, De, c->dHexp, c->eg, c->ev, c->dE, bf, s));
+  }
+  if ((rc = gemm_w(c, "gemm_dW_fgv", c->Hc, Dh, c->stats_f, c->P(P_GAMMA_F), c->P(P_BETA_F), c->dE, 2 * De, Gp(P_WFG), Gp(P_WFV)))) return rc;
+  if ((rc = gemm_x(c, "gemm_du", c->dE, 2 * De, Dh, c->WT_fgv, static_cast<const float *>(c->Wfgv_c), 2 * De, c->du))) return rc;
+  {  // LN of Eq. 9 + Eq. 8
+    Prof p(c, "bwd_gate");
+    BwdGateArgs a{};
+    a.Dh = Dh; a.stats_n = SN; a.du = c->du; a.Hc = c->Hc; a.dHc = c->dHc; a.sg = c->sg; a.Ha = c->Ha; a.Hmix = c->Hmix;
+    a.stats = c->stats_f; a.gamma = c->P(P_GAMMA_F); a.lam = c->P(P_LAMBDA_C); a.dHa = c->dHa; a.dac = c->dac; a.dHmix = c->dHmix1;
+    a.row_dlam = c->row_dlam + B;
+    HIP_TRY(c, fade_bwd_gate(a, B, bf, s));
+    HIP_TRY(c, fade_ln_param_grad(B, Dh, SN, c->du, c->Hc, c->stats_f, Gp(P_GAMMA_F), Gp(P_BETA_F), bf, s));
+  }
+  if ((rc = gemm_w(c, "gemm_dW_c", c->Hmix, Dh, nullptr, nullptr, nullptr, c->dac, Dh, Gp(P_WC), nullptr))) return rc;
+  if ((rc = gemm_x(c, "gemm_dHmix", c->dac, Dh, Dh, c->WT_c, c->P(P_WC), Dh, c->dHmix2))) return rc;
+  // Eq. 7
+  if ((rc = gemm_w(c, "gemm_dW_up", c->z, dl, nullptr, nullptr, nullptr, c->dHa, Dh, Gp(P_WUP), nullptr))) return rc;
+  {
+    Prof p(c, "gemm_dz");
+    GemmArgs g{};
+    g.M = B; g.N = dl; g.K = Dh; g.splits = c->sp_dz; g.A = c->dHa; g.lda = Dh; g.C = c->dz_part; g.ldc = dl;
+    if (bf) g.W = c->WT_up;
+    else { g.W = c->P(P_WUP); g.wt = 1; g.ldb = Dh; }
+    HIP_TRY(c, fade_gemm(GEMM_PARTIAL, bf, g, s));
+  }
+  {  // per-stream memory: dy, and Adam on W_U in place
+    Prof p(c, "bwd_cci_adam");
+    BwdCciArgs a{};
+    a.B = B; a.splits = c->sp_dz; a.dz_part = c->dz_part; a.y = c->y; a.WU_c = c->WU_c;
+    a.master = c->master + c->lay.off[P_WU]; a.m = c->adam_m + c->lay.off[P_WU]; a.v = c->adam_v + c->lay.off[P_WU];
+    a.dy = c->dy; a.dy_at = c->dy_at; a.u = c->ustate;
+    a.lr = c->cfg.lr; a.beta1 = c->cfg.beta1; a.beta2 = c->cfg.beta2; a.eps = c->cfg.eps;
+    HIP_TRY(c, fade_bwd_cci(a, bf, s));
+  }
+  if ((rc = gemm_w(c, "gemm_dW_down", c->Hmix, Dh, c->stats_c, c->P(P_GAMMA_C), c->P(P_BETA_C), c->dy_at, dl, Gp(P_WDOWN), nullptr))) return rc;
+  if ((rc = gemm_x(c, "gemm_dnc", c->dy_at, dl, Dh, c->WT_down, c->P(P_WDOWN), dl, c->dnc))) return rc;
+  {  // LN of Eq. 7 + Eq. 5-6 + branch activations
+    Prof p(c, "bwd_mix");
+    BwdMixArgs a{};
+    a.Dh = Dh; a.stats_n = SN; a.dnc = c->dnc; a.Hmix = c->Hmix; a.dHmix1 = c->dHmix1; a.dHmix2 = c->dHmix2; a.alpha = c->alpha;
+    a.Hg = c->Hg; a.Hl = c->Hl; a.hm = c->hm; a.cv = c->cv; a.X = c->X; a.stats = c->stats_c; a.gamma = c->P(P_GAMMA_C);
+    a.lam = c->P(P_LAMBDA_M); a.dar = c->dar; a.dhm = c->dhm; a.dcv = c->dcv; a.dX = c->dX1; a.row_dlam = c->row_dlam + 2 * B;
+    HIP_TRY(c, fade_bwd_mix(a, B, bf, s));
+    HIP_TRY(c, fade_ln_param_grad(B, Dh, SN, c->dnc, c->Hmix, c->stats_c, Gp(P_GAMMA_C), Gp(P_BETA_C), bf, s));
+    HIP_TRY(c, fade_scalar_sums(B, c->row_dlam, c->row_dlam + B, c->row_dlam + 2 * B, Gp(P_LAMBDA_O), Gp(P_LAMBDA_C), Gp(P_LAMBDA_M), s));
+  }
+  {  // router: X^T comes straight from the per-symbol table
+    Prof p(c, "transpose");
+    HIP_TRY(c, fade_embed_t(ws, B, (int)c->Bp, (int)d.T, (int)d.D, c->tabXe, c->LT, bf, s));
+    if (bf) {
+      TransposeArgs r{};
+      r.src = c->dar; r.ld = Dh; r.dst = c->RT; r.Bp = (int)c->Bp; r.B = B;
+      HIP_TRY(c, fade_transpose(r, Dh, true, s));
+    }
+  }
+  {
+    Prof p(c, "gemm_dW_r");
+    GemmArgs g{};
+    g.M = Dh; g.N = Dh; g.K = (int)c->Bp; g.A = c->LT; g.lda = (int)c->Bp; g.C = Gp(P_WR); g.ldc = Dh;
+    if (bf) { g.W = c->RT; g.ldb = (int)c->Bp; }
+    else g.W = c->dar;
+    HIP_TRY(c, fade_gemm(GEMM_W, bf, g, s));
+  }
+  if ((rc = gemm_x(c, "gemm_dX", c->dar, Dh, Dh, c->WT_r, c->P(P_WR), Dh, c->dX2))) return rc;
+  // global stream
+  if ((rc = gemm_w(c, "gemm_dW_m", c->M, (int)d.Dc, nullptr, nullptr, nullptr, c->dhm, Dh, Gp(P_WM), nullptr))) return rc;
+  {
+    Prof p(c, "bwd_slot");
+    BwdSlotArgs a{};
+    a.Dh = Dh; a.Dc = (int)d.Dc; a.c = (int)d.c; a.D = (int)d.D; a.round_bf16 = bf ? 1 : 0; a.dhm = c->dhm; a.Wm = c->P(P_WM);
+    a.GG = c->GG; a.GV = c->GV; a.Wg = c->Wg_c; a.Wv = c->Wv_c; a.dgg = c->dgg; a.dgv = c->dgv; a.dxt = c->dxt;
+    HIP_TRY(c, fade_bwd_slot(a, B, bf, s));
+    HIP_TRY(c, fade_slot_weight_grad(ws, B, (int)d.T, (int)d.D, (int)d.c, c->tabXe32, c->dgg, c->dgv, Gp(P_WG), Gp(P_WV), s));
+  }
+  {  // local stream
+    Prof p(c, "bwd_conv");
+    ConvGradArgs a{};
+    a.B = B; a.T = (int)d.T; a.D = (int)d.D; a.taps = (int)d.k; a.XL = c->XL; a.dcv = c->dcv; a.part = c->conv_part;
+    HIP_TRY(c, fade_conv_grad(a, c->conv_blocks, Gp(P_WCONV), Gp(P_BCONV), bf, s));
+    GemmArgs g{};
+    g.M = (int)(d.B * d.T); g.N = (int)d.D; g.K = (int)d.Kc; g.A = c->dcv; g.T = (int)d.T; g.D = (int)d.D; g.taps = (int)d.k;
+    g.W = bf ? c->WT_conv : static_cast<const void *>(c->convt_f32); g.C = c->dxl; g.ldc = (int)d.D;
+    HIP_TRY(c, fade_gemm(GEMM_CONVT, bf, g, s));
+  }
+  {  // the two per-token LayerNorms and the embedding
+    Prof p(c, "bwd_embed");
+    BwdTokenArgs a{};
+    a.ws = ws; a.B = B; a.T = (int)d.T; a.D = (int)d.D; a.dX1 = c->dX1; a.dX2 = c->dX2; a.dxl = c->dxl; a.dxt = c->dxt;
+    a.tabXhat = c->tabXhat; a.tabRstd = c->tabRstd; a.gamma_e = c->P(P_GAMMA_E); a.gamma_l = c->P(P_GAMMA_L); a.de = c->de;
+    a.part = c->tok_part;
+    HIP_TRY(c, fade_bwd_token(a, Gp(P_GAMMA_E), Gp(P_BETA_E), Gp(P_GAMMA_L), Gp(P_BETA_L), bf, s));
+    HIP_TRY(c, fade_embed_grad(ws, B, (int)d.T, (int)d.D, c->de, Gp(P_E), s));
+  }
+  {  // Adam on everything except W_U (done in place above), then refresh the compute copies
+    Prof p(c, "adam_refresh");
+    const size_t lo = c->lay.off[P_WU], hi = c->lay.off[P_WU + 1], np = c->lay.off[P_COUNT];
+    HIP_TRY(c, fade_adam(lo, c->grad, c->master, c->adam_m, c->adam_v, c->ustate, c->cfg.lr, c->cfg.beta1, c->cfg.beta2, c->cfg.eps, s));
+    HIP_TRY(c, fade_adam(np - hi, c->grad + hi, c->master + hi, c->adam_m + hi, c->adam_v + hi, c->ustate, c->cfg.lr, c->cfg.beta1,
+                         c->cfg.beta2, c->cfg.eps, s));
+    rc = prepare_compute(c, false);
+    if (rc) return rc;
+  }
+  return FADE_OK;
 }
 
 int check_dev_err(fade_ctx *c) {
@@ -531,6 +752,10 @@ int run_loop(fade_ctx *c, uint8_t *bytes_dev, size_t n, size_t first, size_t cou
     } else {
       int rc = forward(c, ws, mode, bytes_dev, nullptr, nullptr);
       if (rc) return rc;
+      if (c->online) {  // Algorithm 1: update after the symbol has been coded (the decoder has just produced it)
+        rc = backward(c, ws, bytes_dev + i, (long long)L);
+        if (rc) return rc;
+      }
     }
   }
   c->loop_next = last;
@@ -575,7 +800,6 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
   if (rc) return rc;
   rc = check_kernel_limits(*cfg, d, &why);
   if (rc) return rc;
-  if (cfg->update_mode == FADE_ONLINE_ADAM) return FADE_E_BAD_CONFIG;  // the update step is not built yet
   int ndev = 0;
   if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device < 0 || cfg->device >= ndev) return FADE_E_HIP;
   if (hipSetDevice(cfg->device) != hipSuccess) return FADE_E_HIP;
@@ -654,11 +878,53 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
   TRY_ALLOC(dev_alloc(c, &c->stats_f, d.B * SN * 2));
   TRY_ALLOC(dev_alloc(c, &c->stats_o, d.B * SN * 2));
   if (c->online) {
+    const size_t Bp = (d.B + 63) / 64 * 64, BpDh = Bp * d.Dh;
+    c->Bp = Bp;
     for (void **p : {&c->hm, &c->alpha, &c->sg, &c->cv}) TRY_ALLOC(A(p, BDh));
     TRY_ALLOC(A(&c->eg, d.B * d.De));
     TRY_ALLOC(A(&c->ev, d.B * d.De));
     TRY_ALLOC(dev_alloc(c, &c->GG, d.B * d.c));
     TRY_ALLOC(dev_alloc(c, &c->GV, d.B * d.c));
+    TRY_ALLOC(dev_alloc(c, &c->probs_buf, d.B * 256));
+    if (!c->bf16) TRY_ALLOC(A(&c->Hout, BDh));
+    TRY_ALLOC(dev_alloc(c, &c->grad, np));
+    TRY_ALLOC(dev_alloc(c, &c->adam_m, np));
+    TRY_ALLOC(dev_alloc(c, &c->adam_v, np));
+    TRY_ALLOC(dev_alloc(c, &c->ustate, 1));
+    TRY_ALLOC(dev_alloc(c, &c->tabXhat, 256 * d.D));
+    TRY_ALLOC(dev_alloc(c, &c->tabRstd, 256));
+    TRY_ALLOC(dev_alloc(c, &c->convt_f32, d.Kc * d.D));
+    if (c->bf16) {
+      TRY_ALLOC(A(&c->WT_o, d.Dh * 256));
+      TRY_ALLOC(A(&c->WT_f, d.De * d.Dh));
+      TRY_ALLOC(A(&c->WT_fgv, d.Dh * 2 * d.De));
+      TRY_ALLOC(A(&c->WT_c, d.Dh * d.Dh));
+      TRY_ALLOC(A(&c->WT_up, d.dl * d.Dh));
+      TRY_ALLOC(A(&c->WT_down, d.Dh * d.dl));
+      TRY_ALLOC(A(&c->WT_r, d.Dh * d.Dh));
+      TRY_ALLOC(A(&c->WT_conv, d.Kc * d.D));
+    }
+    // gradients that serve as the right operand of a weight-gradient product have Bp rows (padding rows stay zero)
+    struct { void **p; size_t n; } bufs[] = {
+        {&c->dl, Bp * 256}, {&c->dHout, BDh}, {&c->dnv, BDh}, {&c->dV, BpDh}, {&c->dHc, BDh}, {&c->dHexp, d.B * d.De},
+        {&c->dE, Bp * 2 * d.De}, {&c->du, BDh}, {&c->dHa, BpDh}, {&c->dac, BpDh}, {&c->dHmix1, BDh}, {&c->dHmix2, BDh},
+        {&c->dy_at, Bp * d.dl}, {&c->dnc, BDh}, {&c->dar, BpDh}, {&c->dhm, BpDh}, {&c->dcv, BDh}, {&c->dX1, BDh}, {&c->dX2, BDh},
+        {&c->dxl, BDh}, {&c->LT, d.Dh * Bp}, {&c->RT, std::max<size_t>(std::max<size_t>(d.Dh, 2 * d.De), 256) * Bp}};
+    for (auto &b : bufs) {
+      TRY_ALLOC(A(b.p, b.n));
+      if (hipMemsetAsync(*b.p, 0, b.n * c->esz, c->stream) != hipSuccess) { fade_destroy(c); return FADE_E_HIP; }
+    }
+    c->sp_dz = c->bf16 ? pick_splits((int)((d.B + 63) / 64), (int)(d.Dh / 64), 16) : 1;
+    TRY_ALLOC(dev_alloc(c, &c->dz_part, (size_t)c->sp_dz * d.B * d.dl));
+    TRY_ALLOC(dev_alloc(c, &c->dy, d.B * d.dl));
+    TRY_ALLOC(dev_alloc(c, &c->dgg, d.B * d.c));
+    TRY_ALLOC(dev_alloc(c, &c->dgv, d.B * d.c));
+    TRY_ALLOC(dev_alloc(c, &c->dxt, d.B * d.D));
+    TRY_ALLOC(dev_alloc(c, &c->de, BDh));
+    TRY_ALLOC(dev_alloc(c, &c->row_dlam, 3 * d.B));
+    TRY_ALLOC(dev_alloc(c, &c->conv_part, (size_t)c->conv_blocks * (d.k * d.D + 1) * d.D));
+    TRY_ALLOC(dev_alloc(c, &c->tok_part, (d.B * d.T + 255) / 256 * 4 * d.D));
+    if (hipMemsetAsync(c->grad, 0, np * sizeof(float), c->stream) != hipSuccess) { fade_destroy(c); return FADE_E_HIP; }
   }
   for (uint32_t **p : {&c->cb.low, &c->cb.high, &c->cb.pending, &c->cb.bitbuf, &c->cb.nbits, &c->cb.pos, &c->cb.value, &c->cb.bitpos})
     TRY_ALLOC(dev_alloc(c, p, d.B));
@@ -700,13 +966,17 @@ int fade_step_probs(fade_ctx *c, const uint8_t *windows_dev, const uint8_t *acti
   if (!c->have_weights) return fail(c, FADE_E_NO_WEIGHTS, "no weights loaded");
   WinSrc ws{};
   ws.base = windows_dev; ws.stride = (long long)c->d.T; ws.n = 0; ws.active = active_dev ? active_dev : c->ones; ws.i = (long long)c->d.T;
+  c->last_ws = ws;  // fade_step_update re-reads these windows (embedding gradient): they must stay valid until then
   return forward(c, ws, CODE_NONE, nullptr, freq_dev, probs_dev);
 }
 
 int fade_step_update(fade_ctx *c, const uint8_t *targets_dev, const uint8_t *active_dev) {
   if (!c || !targets_dev) return FADE_E_INVALID_ARG;
-  (void)active_dev;
-  return fail(c, FADE_E_BAD_CONFIG, "context is frozen");
+  if (!c->online) return fail(c, FADE_E_BAD_CONFIG, "context is frozen");
+  if (!c->have_weights) return fail(c, FADE_E_NO_WEIGHTS, "no weights loaded");
+  WinSrc ws = c->last_ws;
+  ws.active = active_dev ? active_dev : c->ones;
+  return backward(c, ws, targets_dev, 1);
 }
 
 size_t fade_encode_bound(const fade_ctx *c, size_t n) {
@@ -936,6 +1206,14 @@ int fade_get_weights(fade_ctx *c, void *blob_host, size_t nbytes) {
   if (!c || !blob_host || nbytes != c->lay.off[P_COUNT] * sizeof(float)) return FADE_E_INVALID_ARG;
   HIP_TRY(c, hipStreamSynchronize(c->stream));
   HIP_TRY(c, hipMemcpy(blob_host, c->master, nbytes, hipMemcpyDeviceToHost));
+  return FADE_OK;
+}
+
+int fade_debug_grad(fade_ctx *c, void *blob_host, size_t nbytes) {
+  if (!c || !blob_host || nbytes != c->lay.off[P_COUNT] * sizeof(float)) return FADE_E_INVALID_ARG;
+  if (!c->online) return fail(c, FADE_E_BAD_CONFIG, "context is frozen");
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  HIP_TRY(c, hipMemcpy(blob_host, c->grad, nbytes, hipMemcpyDeviceToHost));
   return FADE_OK;
 }
 

@@ -36,6 +36,7 @@ enum {
   PRO_LN,          // (A[m][k] - mean_m) * rstd_m * gamma[k] + beta[k]          (LN of Eq. 7 / Eq. 9)
   PRO_FINAL,       // psi(LN(A)[m][k]) + lam * A2[m][k]                          (Eq. 10, feeding the head)
   PRO_CONV,        // row (b, j): concat over taps r of XL[b][j-(k-1)+r][:], zero where the index is negative (Eq. 4)
+  PRO_CONVT,       // backward of Eq. 4 w.r.t. its input: row (b, j): concat over taps r of dY[b][j+(k-1)-r][:], zero past T-1
 };
 enum {
   EPI_STORE = 0,   // C = acc                                   (+ optional row statistics for a following LN)
@@ -46,6 +47,7 @@ enum {
   EPI_GEGLU,       // C = psi(acc_gate) * acc_value             (Eq. 9; gate/value interleaved per 128 columns)
   EPI_CONV,        // C = psi(acc + bias[n])                    (Eq. 4)
   EPI_PARTIAL,     // C (fp32)[split][M][N] = acc of this block's K range (summed later in split order)
+  EPI_GRAD,        // C (fp32) = acc: a weight gradient; with C3 set, columns interleaved per 128 go to the pair (C, C3)
 };
 
 struct GemmArgs {
@@ -61,6 +63,8 @@ struct GemmArgs {
   int T, D, taps;         // PRO_CONV geometry
   // B operand: bf16 fragments in MFMA order (bf16 path) or plain fp32 [K][N] (fp32 path)
   const void *W;
+  int ldb;                // pipelined kernel with a row-major B operand ([N][ldb], K contiguous); fp32 kernel with wt != 0
+  int wt;                 // fp32 kernel: W is given transposed ([N][ldb]) instead of [K][N]
   // output
   void *C;  int ldc;
   void *C2, *C3;          // optional copies of pre-activation values for the backward pass

@@ -89,6 +89,12 @@ __device__ __forceinline__ void stage_load(const GemmArgs &g, int m, int k, Raw8
     const int tok = j - (g.taps - 1) + tap;
     if (tap < g.taps && tok >= 0) raw_load(a, A + ((size_t)b * g.T + tok) * g.D + i);
     else raw_zero(a);
+  } else if (PRO == PRO_CONVT) {
+    const int b = m / g.T, j = m - b * g.T;
+    const int tap = k / g.D, i = k - tap * g.D;
+    const int tok = j + (g.taps - 1) - tap;
+    if (tap < g.taps && tok < g.T) raw_load(a, A + ((size_t)b * g.T + tok) * g.D + i);
+    else raw_zero(a);
   } else {
     raw_load(a, A + (size_t)m * g.lda + k);
     if (PRO == PRO_FINAL) raw_load(a2, static_cast<const AT *>(g.A2) + (size_t)m * g.lda + k);
@@ -190,6 +196,14 @@ __device__ __forceinline__ void epilogue(const GemmArgs &g, const float *Cs, int
         store8(static_cast<AT *>(g.C) + o, out);
         if (g.C2) store8(static_cast<AT *>(g.C2) + o, x);
         if (g.C3) store8(static_cast<AT *>(g.C3) + o, xv);
+      } else if (EPI == EPI_GRAD) {
+        if (g.C3) {
+          const int v = n0 + c8;
+          float *dstp = ((v & 127) < 64) ? static_cast<float *>(g.C) : static_cast<float *>(g.C3);
+          store8(dstp + (size_t)m * (g.N / 2) + (v / 128) * 64 + (v & 63), x);
+        } else {
+          store8(static_cast<float *>(g.C) + o, x);
+        }
       } else if (EPI == EPI_PARTIAL) {
         store8(static_cast<float *>(g.C) + ((size_t)blockIdx.y * g.M + m) * g.ldc + n0 + c8, x);
       } else if (EPI == EPI_CONV) {
@@ -283,7 +297,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
 #pragma unroll
   for (int p = 0; p < PASSES; ++p) {
     bf16_t *dst = As + (p * 32 + srow) * LDA + skc;
-    if (PRO == PRO_PLAIN || PRO == PRO_CONV) {
+    if (PRO == PRO_PLAIN || PRO == PRO_CONV || PRO == PRO_CONVT) {
       *reinterpret_cast<bf16x8 *>(dst) = ra[p].v;
     } else {
       float v[8];
@@ -323,7 +337,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
 #pragma unroll
       for (int p = 0; p < PASSES; ++p) {
         bf16_t *dst = An + (p * 32 + srow) * LDA + skc;
-        if (PRO == PRO_PLAIN || PRO == PRO_CONV) {
+        if (PRO == PRO_PLAIN || PRO == PRO_CONV || PRO == PRO_CONVT) {
           *reinterpret_cast<bf16x8 *>(dst) = ra[p].v;
         } else {
           float v[8];
@@ -379,7 +393,7 @@ __device__ __forceinline__ void dma16(const bf16_t *src, unsigned char *lds_chun
                                    (__attribute__((address_space(3))) void *)lds_chunk, 16, 0, 0);
 }
 
-template <int BM, int BN, int STAGES, int EPI>
+template <int BM, int BN, int STAGES, int EPI, bool BROW>
 __global__ __launch_bounds__(256) void gemm_pipe_kernel(GemmArgs g) {
   typedef bf16_t AT;
   constexpr int BK = 64, KS = 4;
@@ -387,10 +401,10 @@ __global__ __launch_bounds__(256) void gemm_pipe_kernel(GemmArgs g) {
   constexpr int BFR = BN / 32;
   constexpr int A_BYTES = BM * 128;                  // A stage: BM rows of 64 k (128 bytes), 16-byte pieces XOR-swizzled
   constexpr int ACH = BM / 8 / 4;                    // A DMAs per wavefront and stage (one DMA = 8 rows x 128 bytes)
-  constexpr int BCH = BFR * KS / 4;                  // W DMAs per wavefront and stage (one DMA = one fragment)
+  constexpr int BCH = BROW ? BN / 8 / 4 : BFR * KS / 4;  // W DMAs per wavefront and stage (one fragment, or 8 rows x 128 bytes)
   constexpr int LPW = ACH + BCH;
   constexpr int STAGE_BYTES = A_BYTES + BFR * KS * 1024, LDC = BN + 4;
-  static_assert((BM / 8) % 4 == 0 && (BFR * KS) % 4 == 0, "chunk split");
+  static_assert((BM / 8) % 4 == 0 && (BFR * KS) % 4 == 0 && (BN / 8) % 4 == 0, "chunk split");
   static_assert((STAGES - 2) * LPW <= 63, "vmcnt range");
   extern __shared__ __align__(16) unsigned char smem[];
   float *Cs = reinterpret_cast<float *>(smem);
@@ -420,15 +434,22 @@ __global__ __launch_bounds__(256) void gemm_pipe_kernel(GemmArgs g) {
   }
 #pragma unroll
   for (int q = 0; q < BCH; ++q) {
-    const int c = wave + 4 * q, fr = c / KS, ks = c % KS;
-    src[ACH + q] = static_cast<const bf16_t *>(g.W) + (((size_t)(n0 / 32 + fr) * ksteps + k_begin / 16 + ks) * 64 + lane) * 8;
+    const int c = wave + 4 * q;
+    if (BROW) {  // row-major [N][ldb]: same 8-rows-per-DMA, XOR-swizzled scheme as A
+      const int row = n0 + c * 8 + (lane >> 3);
+      const int sw = ((c * 8 + (lane >> 3)) >> 1) & 7;
+      src[ACH + q] = static_cast<const bf16_t *>(g.W) + (size_t)row * g.ldb + k_begin + (((lane & 7) ^ sw) << 3);
+    } else {
+      const int fr = c / KS, ks = c % KS;
+      src[ACH + q] = static_cast<const bf16_t *>(g.W) + (((size_t)(n0 / 32 + fr) * ksteps + k_begin / 16 + ks) * 64 + lane) * 8;
+    }
   }
   auto issue = [&](int slot, int kb) {
     unsigned char *base = smem + slot * STAGE_BYTES;
 #pragma unroll
     for (int q = 0; q < ACH; ++q) dma16(src[q] + (size_t)kb * BK, base + (wave + 4 * q) * 1024);
 #pragma unroll
-    for (int q = 0; q < BCH; ++q) dma16(src[ACH + q] + (size_t)kb * KS * 512, base + A_BYTES + (wave + 4 * q) * 1024);
+    for (int q = 0; q < BCH; ++q) dma16(src[ACH + q] + (BROW ? (size_t)kb * BK : (size_t)kb * KS * 512), base + A_BYTES + (wave + 4 * q) * 1024);
   };
 
   f32x16 acc[TM][TN];
@@ -444,9 +465,11 @@ __global__ __launch_bounds__(256) void gemm_pipe_kernel(GemmArgs g) {
     if (s < nkb) issue(s, s);
 
   // fragment read offsets inside a stage: row r, k-step ks, half h -> r * 128 + (((2 ks + h) ^ ((r / 2) & 7)) * 16)
-  int a_off[TM];
+  int a_off[TM], b_off[TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i) a_off[i] = ((wm * TM + i) * 32 + (lane & 31)) * 128;
+#pragma unroll
+  for (int j = 0; j < TN; ++j) b_off[j] = A_BYTES + ((wn * TN + j) * 32 + (lane & 31)) * 128;
   const int a_sw = (lane >> 1) & 7, a_half = lane >> 5;  // tile rows start at multiples of 32, so (r / 2) & 7 == (lane / 2) & 7
 
   for (int kb = 0; kb < nkb; ++kb) {
@@ -464,7 +487,8 @@ __global__ __launch_bounds__(256) void gemm_pipe_kernel(GemmArgs g) {
         af[buf][i] = *reinterpret_cast<const bf16x8 *>(st + a_off[i] + (((2 * ks + a_half) ^ a_sw) << 4));
 #pragma unroll
       for (int j = 0; j < TN; ++j)
-        bf[buf][j] = *reinterpret_cast<const bf16x8 *>(st + A_BYTES + ((((wn * TN + j) * KS + ks) * 64 + lane) << 4));
+        bf[buf][j] = BROW ? *reinterpret_cast<const bf16x8 *>(st + b_off[j] + (((2 * ks + a_half) ^ a_sw) << 4))
+                          : *reinterpret_cast<const bf16x8 *>(st + A_BYTES + ((((wn * TN + j) * KS + ks) * 64 + lane) << 4));
     };
     fetch(0, 0);
     __builtin_amdgcn_sched_barrier(0);  // keep the scheduler from sinking the reads next to their uses
@@ -540,9 +564,16 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g) {
         for (int i = 0; i < 8; ++i) As[srow][skc + i] = v[i];
       }
     }
-    for (int idx = tid; idx < BK * BN / 4; idx += 256) {
-      const int kk = idx / (BN / 4), c4 = (idx % (BN / 4)) * 4;
-      *reinterpret_cast<f32x4 *>(&Ws[kk][c4]) = *reinterpret_cast<const f32x4 *>(W + (size_t)(k0 + kk) * g.N + n0 + c4);
+    if (g.wt) {  // W given as [N][ldb]: rows are output columns, K contiguous
+      for (int idx = tid; idx < BK * BN; idx += 256) {
+        const int c = idx / BK, kk = idx % BK;
+        Ws[kk][c] = W[(size_t)(n0 + c) * g.ldb + k0 + kk];
+      }
+    } else {
+      for (int idx = tid; idx < BK * BN / 4; idx += 256) {
+        const int kk = idx / (BN / 4), c4 = (idx % (BN / 4)) * 4;
+        *reinterpret_cast<f32x4 *>(&Ws[kk][c4]) = *reinterpret_cast<const f32x4 *>(W + (size_t)(k0 + kk) * g.N + n0 + c4);
+      }
     }
     __syncthreads();
 #pragma unroll 8
@@ -578,20 +609,20 @@ hipError_t launch_bf16(const GemmArgs &g, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <int BM, int BN, int STAGES, int EPI>
+template <int BM, int BN, int STAGES, int EPI, bool BROW = false>
 hipError_t launch_pipe(const GemmArgs &g, hipStream_t s) {
   constexpr int BK = 64;
   constexpr size_t lds_ring = (size_t)STAGES * (BM * 128 + (BN / 32) * 4 * 1024), lds_c = (size_t)BM * (BN + 4) * sizeof(float);
   constexpr size_t lds = lds_ring > lds_c ? lds_ring : lds_c;
   static bool attr_done = false;
-  auto kern = gemm_pipe_kernel<BM, BN, STAGES, EPI>;
+  auto kern = gemm_pipe_kernel<BM, BN, STAGES, EPI, BROW>;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
   const int splits = g.splits > 1 ? g.splits : 1;
-  if (g.N % BN || g.M <= 0 || g.K % (splits * BK) || (EPI != EPI_PARTIAL && splits != 1) || g.lda % 8) return hipErrorInvalidValue;
+  if (g.N % BN || g.M <= 0 || g.K % (splits * BK) || (EPI != EPI_PARTIAL && splits != 1) || g.lda % 8 || (BROW && g.ldb % 8)) return hipErrorInvalidValue;
   const dim3 grid(((g.M + BM - 1) / BM) * (g.N / BN), splits);
   hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, g);
   return hipGetLastError();
@@ -652,6 +683,13 @@ hipError_t fade_gemm(int op, bool bf16, const GemmArgs &g, hipStream_t s) {
       case GEMM_PARTIAL:  // split-K products whose LayerNorm / bias / non-linearity follow in the reducing kernel
         if (g.N % 128 == 0) return launch_pipe<128, 128, 4, EPI_PARTIAL>(g, s);
         return launch_pipe<64, 64, 4, EPI_PARTIAL>(g, s);
+      case GEMM_X_STORE:  // backward dX = dY W^T: W^T is kept as a second set of fragments
+        if (g.N % 128) return launch_pipe<64, 64, 4, EPI_STORE>(g, s);
+        return launch_pipe_auto<EPI_STORE>(g, s);
+      case GEMM_W:        // backward dW = L^T R over the batch: both operands are feature-major copies [*][Bp]
+        if (g.N % 128 == 0) return launch_pipe<64, 128, 4, EPI_GRAD, true>(g, s);
+        return launch_pipe<64, 64, 4, EPI_GRAD, true>(g, s);
+      case GEMM_CONVT:    return launch_bf16<4, 1, 1, 1, PRO_CONVT, EPI_STORE>(g, s);
       default: return hipErrorInvalidValue;
     }
   }
@@ -665,6 +703,14 @@ hipError_t fade_gemm(int op, bool bf16, const GemmArgs &g, hipStream_t s) {
     case GEMM_FNR_IN:   return launch_f32<PRO_LN, EPI_GEGLU, true>(g, s);
     case GEMM_FNR_OUT:  return launch_f32<PRO_PLAIN, EPI_STORE, true>(g, s);
     case GEMM_HEAD:     return launch_f32<PRO_FINAL, EPI_STORE_F32, true>(g, s);
+    case GEMM_X_STORE:  // W passed transposed (wt = 1)
+      if (g.N % 128 == 0) return launch_f32<PRO_PLAIN, EPI_STORE, true>(g, s);
+      return launch_f32<PRO_PLAIN, EPI_STORE, false>(g, s);
+    case GEMM_PARTIAL:  return launch_f32<PRO_PLAIN, EPI_PARTIAL, false>(g, s);  // one "split": the full sum
+    case GEMM_W:
+      if (g.N % 128 == 0) return launch_f32<PRO_PLAIN, EPI_GRAD, true>(g, s);
+      return launch_f32<PRO_PLAIN, EPI_GRAD, false>(g, s);
+    case GEMM_CONVT:    return launch_f32<PRO_CONVT, EPI_STORE, false>(g, s);
     default: return hipErrorInvalidValue;
   }
 }

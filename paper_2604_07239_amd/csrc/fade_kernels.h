@@ -4,7 +4,10 @@
 
 enum {
   GEMM_CONV = 0, GEMM_GLOBAL, GEMM_ROUTER, GEMM_DOWN, GEMM_UP, GEMM_GATE, GEMM_FNR_IN, GEMM_FNR_OUT, GEMM_HEAD,
-  GEMM_PARTIAL,  // bf16 only: split-K product leaving fp32 partials [splits][M][N]
+  GEMM_PARTIAL,  // product leaving fp32 partials [splits][M][N] (fp32 path: one split)
+  GEMM_X_STORE,  // backward: dX = dY W^T, stored as activations
+  GEMM_W,        // backward: dW = L^T R, reduction over the batch, fp32 gradient out
+  GEMM_CONVT,    // backward of Eq. 4 w.r.t. its input
   GEMM_OP_COUNT
 };
 // Launch one of the model step's products (see fade_gemm.hip). bf16 selects the MFMA path (activations
@@ -55,9 +58,9 @@ struct GegluArgs {
 };
 struct HoutArgs {
   int B, Dh, stats_n;
-  const bf16_t *V, *Hc;
+  const void *V, *Hc;
   const float *stats, *gamma, *beta, *lam;
-  bf16_t *Hout;
+  void *Hout;
 };
 
 struct SqcArgs {
@@ -75,11 +78,15 @@ struct SqcArgs {
 
 hipError_t fade_preshuffle(const float *W0, const float *W1, int k_real, int K, int N, int interleave, const float *rowscale, void *out,
                            hipStream_t s);
+// fragments of the TRANSPOSE of the (possibly interleaved) matrix [K][N]: the result multiplies from the right as [N][K]
+hipError_t fade_preshuffle_t(const float *W0, const float *W1, int K, int N, int interleave, void *out, hipStream_t s);
+hipError_t fade_tables_bwd(const float *E, int D, float *tabXhat, float *tabRstd, hipStream_t s);
+hipError_t fade_convt_build(const float *Wconv, int taps, int D, int Kc, float *V, hipStream_t s);
 hipError_t fade_fold_vectors(const float *W0, const float *W1, int K, int N, int interleave, const float *gamma, const float *beta,
                              float *s_out, float *t_out, hipStream_t s);
 hipError_t fade_cci(const CciArgs &a, hipStream_t s);
 hipError_t fade_geglu(const GegluArgs &a, hipStream_t s);
-hipError_t fade_hout(const HoutArgs &a, hipStream_t s);
+hipError_t fade_hout(const HoutArgs &a, bool bf16, hipStream_t s);
 hipError_t fade_virtual_copy(const float *W0, const float *W1, int k_real, int K, int N, int interleave, float *out, hipStream_t s);
 hipError_t fade_convert(const float *src, void *dst, size_t n, bool bf16, hipStream_t s);
 hipError_t fade_round_bf16(const float *src, float *dst, size_t n, hipStream_t s);
@@ -95,3 +102,98 @@ hipError_t fade_coder_init(const CoderBufs &cb, int B, int decode, hipStream_t s
 hipError_t fade_coder_finish(const CoderBufs &cb, int B, long long stride, long long n, hipStream_t s);
 hipError_t fade_payload_move(uint8_t *strided, size_t cap, uint8_t *flat, const unsigned long long *offsets, const uint32_t *lens, int B,
                              int gather, hipStream_t s);
+
+// ---------------------------------------------------------------------------------------------------
+// online update (fade_bwd.hip)
+// ---------------------------------------------------------------------------------------------------
+struct UpdateState {
+  int na;         // active streams of this step
+  int t;          // Adam step count
+  float c1, c2;   // 1 - beta^t
+  float inv_na;
+};
+struct TransposeArgs {
+  const void *src; int ld;     // [B][ld]
+  void *dst; int Bp;           // [N][Bp]
+  int B;
+  const float *stats; int stats_n, width;  // optional LayerNorm on the way (stats == NULL: plain copy)
+  const float *gamma, *beta;
+};
+struct BwdOutArgs {
+  int Dh, stats_n;
+  const void *dH, *V, *Hc;
+  const float *stats, *gamma, *beta, *lam;
+  void *dnv, *dV, *dHc;
+  float *row_dlam;
+};
+struct BwdGateArgs {
+  int Dh, stats_n;
+  const void *du, *Hc, *dHc, *sg, *Ha, *Hmix;
+  const float *stats, *gamma, *lam;
+  void *dHa, *dac, *dHmix;
+  float *row_dlam;
+};
+struct BwdMixArgs {
+  int Dh, stats_n;
+  const void *dnc, *Hmix, *dHmix1, *dHmix2, *alpha, *Hg, *Hl, *hm, *cv, *X;
+  const float *stats, *gamma, *lam;
+  void *dar, *dhm, *dcv, *dX;
+  float *row_dlam;
+};
+struct BwdCciArgs {
+  int B, splits;
+  const float *dz_part;   // [splits][B][64]
+  const float *y;         // [B][64]
+  void *WU_c;             // [B][64][64] compute copy (read, then rewritten by Adam)
+  float *master, *m, *v;  // W_U's slice of the fp32 blob and of the two moment blobs
+  float *dy; void *dy_at; // [B][64]
+  const UpdateState *u;
+  float lr, beta1, beta2, eps;
+};
+struct BwdSlotArgs {
+  int Dh, Dc, c, D, round_bf16;
+  const void *dhm;        // [B][Dh]
+  const float *Wm;        // fp32 master W_m [Dc][Dh]
+  const float *GG, *GV;   // [B][c]
+  const float *Wg, *Wv;   // [D][c] compute values
+  float *dgg, *dgv;       // [B][c]
+  float *dxt;             // [B][D]
+};
+struct ConvGradArgs {
+  int B, T, D, taps;
+  const void *XL, *dcv;   // [B*T][D]
+  float *part;            // [blocks][taps*D + 1][D]
+};
+struct BwdTokenArgs {
+  WinSrc ws;
+  int B, T, D;
+  const void *dX1, *dX2, *dxl;   // [B*T][D]
+  const float *dxt;               // [B][D], added at the newest token
+  const float *tabXhat, *tabRstd; // [256][D], [256]
+  const float *gamma_e, *gamma_l;
+  float *de;                      // [B*T][D]
+  float *part;                    // [blocks][4][D]
+};
+
+hipError_t fade_update_prep(const WinSrc &ws, int B, UpdateState *u, float beta1, float beta2, hipStream_t s);
+hipError_t fade_dlogits(const WinSrc &ws, const uint8_t *targets, long long tstride, int B, const float *probs, const UpdateState *u,
+                        void *dl, bool bf16, hipStream_t s);
+hipError_t fade_transpose(const TransposeArgs &a, int N, bool bf16, hipStream_t s);
+hipError_t fade_embed_t(const WinSrc &ws, int B, int Bp, int T, int D, const void *tab, void *XT, bool bf16, hipStream_t s);
+hipError_t fade_bwd_out(const BwdOutArgs &a, int B, bool bf16, hipStream_t s);
+hipError_t fade_bwd_geglu(int B, int De, const void *dHexp, const void *eg, const void *ev, void *dE, bool bf16, hipStream_t s);
+hipError_t fade_bwd_gate(const BwdGateArgs &a, int B, bool bf16, hipStream_t s);
+hipError_t fade_bwd_mix(const BwdMixArgs &a, int B, bool bf16, hipStream_t s);
+hipError_t fade_ln_param_grad(int B, int width, int stats_n, const void *dn, const void *x, const float *stats, float *dgamma, float *dbeta,
+                              bool bf16, hipStream_t s);
+hipError_t fade_colsum(int B, int N, const void *src, float *out, bool bf16, hipStream_t s);
+hipError_t fade_scalar_sums(int B, const float *r0, const float *r1, const float *r2, float *o0, float *o1, float *o2, hipStream_t s);
+hipError_t fade_bwd_cci(const BwdCciArgs &a, bool bf16, hipStream_t s);
+hipError_t fade_bwd_slot(const BwdSlotArgs &a, int B, bool bf16, hipStream_t s);
+hipError_t fade_slot_weight_grad(const WinSrc &ws, int B, int T, int D, int c, const float *tabXe32, const float *dgg, const float *dgv,
+                                 float *dWg, float *dWv, hipStream_t s);
+hipError_t fade_conv_grad(const ConvGradArgs &a, int nblocks, float *dW, float *db, bool bf16, hipStream_t s);
+hipError_t fade_bwd_token(const BwdTokenArgs &a, float *dge, float *dbe, float *dgl, float *dbl, bool bf16, hipStream_t s);
+hipError_t fade_embed_grad(const WinSrc &ws, int B, int T, int D, const float *de, float *dE, hipStream_t s);
+hipError_t fade_adam(size_t n, const float *grad, float *master, float *m, float *v, const UpdateState *u, float lr, float beta1, float beta2,
+                     float eps, hipStream_t s);

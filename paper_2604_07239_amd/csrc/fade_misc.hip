@@ -257,7 +257,19 @@ __global__ __launch_bounds__(256) void geglu_kernel(GegluArgs a) {
   if (a.eg) { *reinterpret_cast<bf16x8 *>(a.eg + o) = eg; *reinterpret_cast<bf16x8 *>(a.ev + o) = ev; }
 }
 
-// Eq. 10's tail (bf16 path): H = psi(LN(V)) + lambda_o * H_coarse. One thread per 8 columns.
+// Eq. 10's tail: H = psi(LN(V)) + lambda_o * H_coarse. One thread per 8 columns.
+template <typename AT> __device__ __forceinline__ void ldv8(const AT *p, float v[8]);
+template <> __device__ __forceinline__ void ldv8<bf16_t>(const bf16_t *p, float v[8]) {
+  const bf16x8 r = *reinterpret_cast<const bf16x8 *>(p);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v[i] = (float)r[i];
+}
+template <> __device__ __forceinline__ void ldv8<float>(const float *p, float v[8]) {
+  const f32x4 a = *reinterpret_cast<const f32x4 *>(p), b = *reinterpret_cast<const f32x4 *>(p + 4);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { v[i] = a[i]; v[4 + i] = b[i]; }
+}
+template <typename AT>
 __global__ __launch_bounds__(256) void hout_kernel(HoutArgs a) {
   const int chunks = a.Dh / 8;
   const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -266,18 +278,68 @@ __global__ __launch_bounds__(256) void hout_kernel(HoutArgs a) {
   float mean, rstd;
   moments_from_partials(a.stats + (size_t)b * a.stats_n * 2, a.stats_n, a.Dh, mean, rstd);
   const size_t o = (size_t)b * a.Dh + c8;
-  const bf16x8 v = *reinterpret_cast<const bf16x8 *>(a.V + o), hc = *reinterpret_cast<const bf16x8 *>(a.Hc + o);
-  const f32x4 g0 = *reinterpret_cast<const f32x4 *>(a.gamma + c8), g1 = *reinterpret_cast<const f32x4 *>(a.gamma + c8 + 4);
-  const f32x4 b0 = *reinterpret_cast<const f32x4 *>(a.beta + c8), b1 = *reinterpret_cast<const f32x4 *>(a.beta + c8 + 4);
+  float v[8], hc[8], ga[8], be[8];
+  ldv8<AT>(static_cast<const AT *>(a.V) + o, v);
+  ldv8<AT>(static_cast<const AT *>(a.Hc) + o, hc);
+  ldv8<float>(a.gamma + c8, ga);
+  ldv8<float>(a.beta + c8, be);
   const float lam = a.lam[0];
-  bf16x8 out;
+  AT *out = static_cast<AT *>(a.Hout) + o;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) out[i] = (AT)(gelu_f((v[i] - mean) * rstd * ga[i] + be[i]) + lam * hc[i]);
+}
+
+// x-hat and rstd of the per-symbol LayerNorm (shared by both affine pairs), for the embedding's backward pass
+__global__ void tables_bwd_kernel(const float *E, int D, float *tabXhat, float *tabRstd) {
+  const int s = blockIdx.x * blockDim.x + threadIdx.x;
+  if (s >= 256) return;
+  const float *e = E + (size_t)s * D;
+  float mean = 0.0f;
+  for (int i = 0; i < D; ++i) mean += e[i];
+  mean /= (float)D;
+  float var = 0.0f;
+  for (int i = 0; i < D; ++i) { const float d = e[i] - mean; var += d * d; }
+  var /= (float)D;
+  const float rstd = 1.0f / sqrtf(var + 1e-5f);
+  tabRstd[s] = rstd;
+  for (int i = 0; i < D; ++i) tabXhat[(size_t)s * D + i] = (e[i] - mean) * rstd;
+}
+
+// Eq. 4 backward w.r.t. its input is again a (anti-causal) convolution; its weight as a product operand:
+// V[(r * D + o)][i] = W_conv[r][i][o], rows past taps * D are zero. fp32 [Kc][D].
+__global__ void convt_build_kernel(const float *Wconv, int taps, int D, int Kc, float *V) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= Kc * D) return;
+  const int row = t / D, i = t - row * D;
+  const int r = row / D, o = row - r * D;
+  V[t] = (r < taps) ? Wconv[((size_t)r * D + i) * D + o] : 0.0f;
+}
+
+// Fragments of the transpose: virtual V[k'][n'] = W[n'][k'] with W the (possibly interleaved) [K][N] matrix, so V is [N][K]:
+// reduction index k' runs over W's columns, output column n' over W's rows.
+__global__ void preshuffle_t_kernel(const float *W0, const float *W1, int K, int N, int interleave, bf16_t *out) {
+  const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // one thread per (fragment, lane)
+  const int Kv = N, Nv = K;
+  const size_t total = (size_t)(Nv / 32) * (Kv / 16) * 64;
+  if (t >= total) return;
+  const int lane = (int)(t & 63);
+  const size_t frag = t >> 6;
+  const int ks = (int)(frag % (size_t)(Kv / 16)), nt = (int)(frag / (size_t)(Kv / 16));
+  const int row = nt * 32 + (lane & 31);  // row of W
+  bf16x8 r;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    const float ga = i < 4 ? g0[i] : g1[i - 4], be = i < 4 ? b0[i] : b1[i - 4];
-    const float nv = ((float)v[i] - mean) * rstd * ga + be;
-    out[i] = (bf16_t)(gelu_f(nv) + lam * (float)hc[i]);
+    const int v = ks * 16 + (lane >> 5) * 8 + i;  // column of the virtual W
+    const float *src = W0;
+    int col = v, ld = N;
+    if (interleave) {
+      ld = N / 2;
+      col = (v / 128) * 64 + (v & 63);
+      if ((v & 127) >= 64) src = W1;
+    }
+    r[i] = (bf16_t)src[(size_t)row * ld + col];
   }
-  *reinterpret_cast<bf16x8 *>(a.Hout + o) = out;
+  reinterpret_cast<bf16x8 *>(out)[t] = r;
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -626,8 +688,23 @@ hipError_t fade_geglu(const GegluArgs &a, hipStream_t s) {
   hipLaunchKernelGGL(geglu_kernel, dim3(blocks_for((size_t)a.B * (a.De / 8), 256)), dim3(256), 0, s, a);
   return hipGetLastError();
 }
-hipError_t fade_hout(const HoutArgs &a, hipStream_t s) {
-  hipLaunchKernelGGL(hout_kernel, dim3(blocks_for((size_t)a.B * (a.Dh / 8), 256)), dim3(256), 0, s, a);
+hipError_t fade_hout(const HoutArgs &a, bool bf16, hipStream_t s) {
+  const dim3 grid(blocks_for((size_t)a.B * (a.Dh / 8), 256));
+  if (bf16) hipLaunchKernelGGL(hout_kernel<bf16_t>, grid, dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(hout_kernel<float>, grid, dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+hipError_t fade_preshuffle_t(const float *W0, const float *W1, int K, int N, int interleave, void *out, hipStream_t s) {
+  const size_t total = (size_t)(K / 32) * (N / 16) * 64;
+  hipLaunchKernelGGL(preshuffle_t_kernel, dim3(blocks_for(total, 256)), dim3(256), 0, s, W0, W1, K, N, interleave, static_cast<bf16_t *>(out));
+  return hipGetLastError();
+}
+hipError_t fade_convt_build(const float *Wconv, int taps, int D, int Kc, float *V, hipStream_t s) {
+  hipLaunchKernelGGL(convt_build_kernel, dim3(blocks_for((size_t)Kc * D, 256)), dim3(256), 0, s, Wconv, taps, D, Kc, V);
+  return hipGetLastError();
+}
+hipError_t fade_tables_bwd(const float *E, int D, float *tabXhat, float *tabRstd, hipStream_t s) {
+  hipLaunchKernelGGL(tables_bwd_kernel, dim3(1), dim3(256), 0, s, E, D, tabXhat, tabRstd);
   return hipGetLastError();
 }
 hipError_t fade_softmax_quant_code(const SqcArgs &a, int mode, hipStream_t s) {
