@@ -1,5 +1,7 @@
 // fade_api.hip — libfade's C ABI: context, device state, the step sequence and the compress / decompress loops.
 #include <algorithm>
+#include <initializer_list>
+#include <utility>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -64,6 +66,8 @@ int check_kernel_limits(const fade_config &cfg, const Dims &d, std::string *why)
   if (d.k > 4) return bad("kernels need conv_k <= 4");
   if (cfg.dtype == FADE_BF16 ? (d.D % 32 != 0) : (d.D % 16 != 0)) return bad("kernels need D % 32 == 0 (bf16) or D % 16 == 0 (fp32)");
   if (d.B * d.T > 0x7fffffffull / 4 || d.B > (1u << 20)) return bad("B too large");
+  if (cfg.update_mode == FADE_ONLINE_ADAM && (d.Dh > 2048 || d.D > 32 || 128 % d.T || 256 % d.D))
+    return bad("the update kernels need T*D <= 2048, D in {16, 32} and T a power of two up to 128");
   return FADE_OK;
 }
 
@@ -114,7 +118,7 @@ struct fade_ctx {
   float *y = nullptr, *logits = nullptr, *stats_c = nullptr, *stats_f = nullptr, *stats_o = nullptr;
   // bf16 path: split-K partials, folded-LayerNorm vectors, the materialised H of Eq. 10
   float *part_down = nullptr, *part_fnr = nullptr, *part_head = nullptr;
-  float *s_down = nullptr, *t_down = nullptr, *s_fnr = nullptr, *t_fnr = nullptr;
+  float *s_down = nullptr, *t_down = nullptr, *s_fnr = nullptr, *t_fnr = nullptr, *fold_part = nullptr;
   void *Hout = nullptr;
   int sp_down = 1, sp_fnr = 1, sp_head = 1;
   // kept for the backward pass (online mode only)
@@ -130,10 +134,12 @@ struct fade_ctx {
        *WT_conv = nullptr;
   void *dl = nullptr, *dHout = nullptr, *dnv = nullptr, *dV = nullptr, *dHc = nullptr, *dHexp = nullptr, *dE = nullptr, *du = nullptr,
        *dHa = nullptr, *dac = nullptr, *dHmix1 = nullptr, *dHmix2 = nullptr, *dy_at = nullptr, *dnc = nullptr, *dar = nullptr,
-       *dhm = nullptr, *dcv = nullptr, *dX1 = nullptr, *dX2 = nullptr, *dxl = nullptr, *LT = nullptr, *RT = nullptr;
-  float *dz_part = nullptr, *dy = nullptr, *dgg = nullptr, *dgv = nullptr, *dxt = nullptr, *de = nullptr, *row_dlam = nullptr,
+       *dhm = nullptr, *dcv = nullptr, *dX1 = nullptr, *dX2 = nullptr, *dxl = nullptr;
+  void *LT[8] = {}, *RT[8] = {};  // feature-major copies [width][Bp] of weight-gradient operands (see backward())
+  float *dz_part = nullptr, *dy = nullptr, *dgg = nullptr, *dgv = nullptr, *dxt = nullptr, *sym_sums = nullptr, *row_dlam = nullptr,
         *conv_part = nullptr, *tok_part = nullptr;
-  int sp_dz = 1, conv_blocks = 256;
+  float *ln_part = nullptr, *col_part = nullptr, *slot_part = nullptr, *emb_part = nullptr;
+  int sp_dz = 1, emb_blocks = 128;
 
   // coder and step bookkeeping
   CoderBufs cb{};
@@ -221,42 +227,46 @@ int prepare_compute(fade_ctx *c, bool with_wu = true) {
   const Dims &d = c->d;
   hipStream_t s = c->stream;
   if (c->bf16) {
-    HIP_TRY(c, fade_round_bf16(c->P(P_E), c->E_c, 256 * d.D, s));
-    HIP_TRY(c, fade_round_bf16(c->P(P_WG), c->Wg_c, d.D * d.c, s));
-    HIP_TRY(c, fade_round_bf16(c->P(P_WV), c->Wv_c, d.D * d.c, s));
-    HIP_TRY(c, fade_preshuffle(c->P(P_WM), nullptr, (int)d.Dc, (int)d.Dc, (int)d.Dh, 0, nullptr, c->Wm_c, s));
-    HIP_TRY(c, fade_preshuffle(c->P(P_WCONV), nullptr, (int)(d.k * d.D), (int)d.Kc, (int)d.D, 0, nullptr, c->Wconv_c, s));
-    HIP_TRY(c, fade_preshuffle(c->P(P_WR), nullptr, (int)d.Dh, (int)d.Dh, (int)d.Dh, 0, nullptr, c->Wr_c, s));
-    HIP_TRY(c, fade_preshuffle(c->P(P_WUP), nullptr, (int)d.dl, (int)d.dl, (int)d.Dh, 0, nullptr, c->Wup_c, s));
-    HIP_TRY(c, fade_preshuffle(c->P(P_WC), nullptr, (int)d.Dh, (int)d.Dh, (int)d.Dh, 0, nullptr, c->Wc_c, s));
-    HIP_TRY(c, fade_preshuffle(c->P(P_WF), nullptr, (int)d.De, (int)d.De, (int)d.Dh, 0, nullptr, c->Wf_c, s));
-    HIP_TRY(c, fade_preshuffle(c->P(P_WO), nullptr, (int)d.Dh, (int)d.Dh, 256, 0, nullptr, c->Wo_c, s));
-    // LayerNorm gains folded into the consuming weights (Eq. 7's Down, Eq. 9's GeGLU pair) + their fix-up vectors
-    HIP_TRY(c, fade_preshuffle(c->P(P_WDOWN), nullptr, (int)d.Dh, (int)d.Dh, (int)d.dl, 0, c->P(P_GAMMA_C), c->Wdown_c, s));
-    HIP_TRY(c, fade_fold_vectors(c->P(P_WDOWN), nullptr, (int)d.Dh, (int)d.dl, 0, c->P(P_GAMMA_C), c->P(P_BETA_C), c->s_down, c->t_down, s));
-    HIP_TRY(c, fade_preshuffle(c->P(P_WFG), c->P(P_WFV), (int)d.Dh, (int)d.Dh, (int)(2 * d.De), 1, c->P(P_GAMMA_F), c->Wfgv_c, s));
-    HIP_TRY(c, fade_fold_vectors(c->P(P_WFG), c->P(P_WFV), (int)d.Dh, (int)(2 * d.De), 1, c->P(P_GAMMA_F), c->P(P_BETA_F), c->s_fnr, c->t_fnr, s));
+    PrepBatch pb{};
+    auto add = [&](int kind, const float *W0, const float *W1, size_t k_real, size_t K, size_t N, int il, const float *scale, void *out) {
+      PrepDesc &q = pb.d[pb.count++];
+      q.kind = kind; q.W0 = W0; q.W1 = W1; q.k_real = (int)k_real; q.K = (int)K; q.N = (int)N; q.interleave = il; q.rowscale = scale;
+      q.out = out; q.taps = (int)d.k; q.D = (int)d.D;
+    };
+    add(PREP_ROUND, c->P(P_E), nullptr, 0, 0, 256 * d.D, 0, nullptr, c->E_c);
+    add(PREP_ROUND, c->P(P_WG), nullptr, 0, 0, d.D * d.c, 0, nullptr, c->Wg_c);
+    add(PREP_ROUND, c->P(P_WV), nullptr, 0, 0, d.D * d.c, 0, nullptr, c->Wv_c);
+    add(PREP_FRAG, c->P(P_WM), nullptr, d.Dc, d.Dc, d.Dh, 0, nullptr, c->Wm_c);
+    add(PREP_FRAG, c->P(P_WCONV), nullptr, d.k * d.D, d.Kc, d.D, 0, nullptr, c->Wconv_c);
+    add(PREP_FRAG, c->P(P_WR), nullptr, d.Dh, d.Dh, d.Dh, 0, nullptr, c->Wr_c);
+    add(PREP_FRAG, c->P(P_WUP), nullptr, d.dl, d.dl, d.Dh, 0, nullptr, c->Wup_c);
+    add(PREP_FRAG, c->P(P_WC), nullptr, d.Dh, d.Dh, d.Dh, 0, nullptr, c->Wc_c);
+    add(PREP_FRAG, c->P(P_WF), nullptr, d.De, d.De, d.Dh, 0, nullptr, c->Wf_c);
+    add(PREP_FRAG, c->P(P_WO), nullptr, d.Dh, d.Dh, 256, 0, nullptr, c->Wo_c);
+    // LayerNorm gains folded into the consuming weights (Eq. 7's Down, Eq. 9's GeGLU pair)
+    add(PREP_FRAG, c->P(P_WDOWN), nullptr, d.Dh, d.Dh, d.dl, 0, c->P(P_GAMMA_C), c->Wdown_c);
+    add(PREP_FRAG, c->P(P_WFG), c->P(P_WFV), d.Dh, d.Dh, 2 * d.De, 1, c->P(P_GAMMA_F), c->Wfgv_c);
+    if (c->online) {  // operands of the backward pass: transposed fragment sets, and Eq. 4's transposed taps
+      add(PREP_FRAG_CONVT, c->P(P_WCONV), nullptr, d.k * d.D, d.Kc, d.D, 0, nullptr, c->WT_conv);
+      add(PREP_FRAG_T, c->P(P_WO), nullptr, 0, d.Dh, 256, 0, nullptr, c->WT_o);
+      add(PREP_FRAG_T, c->P(P_WF), nullptr, 0, d.De, d.Dh, 0, nullptr, c->WT_f);
+      add(PREP_FRAG_T, c->P(P_WFG), c->P(P_WFV), 0, d.Dh, 2 * d.De, 1, nullptr, c->WT_fgv);
+      add(PREP_FRAG_T, c->P(P_WC), nullptr, 0, d.Dh, d.Dh, 0, nullptr, c->WT_c);
+      add(PREP_FRAG_T, c->P(P_WUP), nullptr, 0, d.dl, d.Dh, 0, nullptr, c->WT_up);
+      add(PREP_FRAG_T, c->P(P_WDOWN), nullptr, 0, d.Dh, d.dl, 0, nullptr, c->WT_down);
+      add(PREP_FRAG_T, c->P(P_WR), nullptr, 0, d.Dh, d.Dh, 0, nullptr, c->WT_r);
+    }
+    HIP_TRY(c, fade_prep_batch(pb, s));
+    HIP_TRY(c, fade_fold_vectors(c->P(P_WDOWN), nullptr, (int)d.Dh, (int)d.dl, 0, c->P(P_GAMMA_C), c->P(P_BETA_C), c->fold_part, c->s_down, s));
+    HIP_TRY(c, fade_fold_vectors(c->P(P_WFG), c->P(P_WFV), (int)d.Dh, (int)(2 * d.De), 1, c->P(P_GAMMA_F), c->P(P_BETA_F), c->fold_part, c->s_fnr, s));
     if (with_wu) HIP_TRY(c, fade_convert(c->P(P_WU), c->WU_c, d.B * d.dl * d.dl, true, s));
   } else {
     HIP_TRY(c, fade_virtual_copy(c->P(P_WCONV), nullptr, (int)(d.k * d.D), (int)d.Kc, (int)d.D, 0, static_cast<float *>(c->Wconv_c), s));
     HIP_TRY(c, fade_virtual_copy(c->P(P_WFG), c->P(P_WFV), (int)d.Dh, (int)d.Dh, (int)(2 * d.De), 1, static_cast<float *>(c->Wfgv_c), s));
+    if (c->online) HIP_TRY(c, fade_convt_build(c->P(P_WCONV), (int)d.k, (int)d.D, (int)d.Kc, c->convt_f32, s));
   }
   HIP_TRY(c, fade_tables(c->E_c, c->P(P_GAMMA_E), c->P(P_BETA_E), c->P(P_GAMMA_L), c->P(P_BETA_L), (int)d.D, c->tabXe,
-                         c->tabXl, c->tabXe32, c->bf16, s));
-  if (c->online) {  // operands of the backward pass
-    HIP_TRY(c, fade_tables_bwd(c->E_c, (int)d.D, c->tabXhat, c->tabRstd, s));
-    HIP_TRY(c, fade_convt_build(c->P(P_WCONV), (int)d.k, (int)d.D, (int)d.Kc, c->convt_f32, s));
-    if (c->bf16) {
-      HIP_TRY(c, fade_preshuffle(c->convt_f32, nullptr, (int)d.Kc, (int)d.Kc, (int)d.D, 0, nullptr, c->WT_conv, s));
-      HIP_TRY(c, fade_preshuffle_t(c->P(P_WO), nullptr, (int)d.Dh, 256, 0, c->WT_o, s));
-      HIP_TRY(c, fade_preshuffle_t(c->P(P_WF), nullptr, (int)d.De, (int)d.Dh, 0, c->WT_f, s));
-      HIP_TRY(c, fade_preshuffle_t(c->P(P_WFG), c->P(P_WFV), (int)d.Dh, (int)(2 * d.De), 1, c->WT_fgv, s));
-      HIP_TRY(c, fade_preshuffle_t(c->P(P_WC), nullptr, (int)d.Dh, (int)d.Dh, 0, c->WT_c, s));
-      HIP_TRY(c, fade_preshuffle_t(c->P(P_WUP), nullptr, (int)d.dl, (int)d.Dh, 0, c->WT_up, s));
-      HIP_TRY(c, fade_preshuffle_t(c->P(P_WDOWN), nullptr, (int)d.Dh, (int)d.dl, 0, c->WT_down, s));
-      HIP_TRY(c, fade_preshuffle_t(c->P(P_WR), nullptr, (int)d.Dh, (int)d.Dh, 0, c->WT_r, s));
-    }
-  }
+                         c->tabXl, c->tabXe32, c->tabXhat, c->tabRstd, c->bf16, s));
   return FADE_OK;
 }
 
@@ -526,29 +536,33 @@ int gemm_x(fade_ctx *c, const char *name, const void *dY, int Kred, int Nout, co
   HIP_TRY(c, fade_gemm(GEMM_X_STORE, c->bf16, g, c->stream));
   return FADE_OK;
 }
-// dW[Kw][N] = L^T R over the batch. L: activation [B][Kw] (optionally through a LayerNorm), R: gradient [Bp][N].
-int gemm_w(fade_ctx *c, const char *name, const void *L, int Kw, const float *ln_stats, const float *ln_gamma, const float *ln_beta,
-           const void *R, int N, float *dW, float *dW_pair) {
-  const Dims &d = c->d;
-  hipStream_t s = c->stream;
-  {
-    Prof p(c, "transpose");
-    TransposeArgs t{};
-    t.src = L; t.ld = Kw; t.dst = c->LT; t.Bp = (int)c->Bp; t.B = (int)d.B;
-    t.stats = ln_stats; t.stats_n = (int)(d.Dh / FADE_STATS_BN); t.width = Kw; t.gamma = ln_gamma; t.beta = ln_beta;
-    HIP_TRY(c, fade_transpose(t, Kw, c->bf16, s));
-    if (c->bf16) {
-      TransposeArgs r{};
-      r.src = R; r.ld = N; r.dst = c->RT; r.Bp = (int)c->Bp; r.B = (int)d.B;
-      HIP_TRY(c, fade_transpose(r, N, true, s));
-    }
-  }
+// dW[Kw][N] = L^T R over the batch. LT: feature-major copy [Kw][Bp] of the left operand; R: gradient [Bp][N] (fp32 path),
+// RT: its feature-major copy [N][Bp] (bf16 path).
+int gemm_w(fade_ctx *c, const char *name, const void *LT, int Kw, const void *R, const void *RT, int N, float *dW, float *dW_pair) {
   Prof p(c, name);
   GemmArgs g{};
-  g.M = Kw; g.N = N; g.K = (int)c->Bp; g.A = c->LT; g.lda = (int)c->Bp; g.C = dW; g.C3 = dW_pair; g.ldc = N;
-  if (c->bf16) { g.W = c->RT; g.ldb = (int)c->Bp; }
+  g.M = Kw; g.N = N; g.K = (int)c->Bp; g.A = LT; g.lda = (int)c->Bp; g.C = dW; g.C3 = dW_pair; g.ldc = N;
+  if (c->bf16) { g.W = RT; g.ldb = (int)c->Bp; }
   else g.W = R;
-  HIP_TRY(c, fade_gemm(GEMM_W, c->bf16, g, s));
+  HIP_TRY(c, fade_gemm(GEMM_W, c->bf16, g, c->stream));
+  return FADE_OK;
+}
+TransposeArgs tr_desc(fade_ctx *c, const void *src, int ld, void *dst, const float *stats, const float *gamma, const float *beta) {
+  TransposeArgs t{};
+  t.src = src; t.ld = ld; t.dst = dst; t.Bp = (int)c->Bp; t.B = (int)c->d.B;
+  t.stats = stats; t.stats_n = (int)(c->d.Dh / FADE_STATS_BN); t.width = ld; t.gamma = gamma; t.beta = beta;
+  return t;
+}
+// feature-major copies of freshly produced gradients (bf16 path only: the fp32 product reads them row-major)
+int transpose_grads(fade_ctx *c, std::initializer_list<std::pair<const void *, std::pair<void *, int>>> items) {
+  if (!c->bf16) return FADE_OK;
+  Prof p(c, "transpose");
+  TransposeBatch tb{};
+  for (auto &it : items) {
+    tb.t[tb.count] = tr_desc(c, it.first, it.second.second, it.second.first, nullptr, nullptr, nullptr);
+    tb.N[tb.count++] = it.second.second;
+  }
+  HIP_TRY(c, fade_transpose_batch(tb, true, c->stream));
   return FADE_OK;
 }
 
@@ -559,45 +573,67 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
   const int B = (int)d.B, Dh = (int)d.Dh, De = (int)d.De, dl = (int)d.dl, SN = (int)(d.Dh / FADE_STATS_BN);
   float *G = c->grad;
   auto Gp = [&](int id) { return G + c->lay.off[id]; };
+  const int RB = (B + fade_rows_per_block() - 1) / fade_rows_per_block();
   int rc;
   {
     Prof p(c, "bwd_prep_dlogits");
     HIP_TRY(c, fade_update_prep(ws, B, c->ustate, c->cfg.beta1, c->cfg.beta2, s));
     HIP_TRY(c, fade_dlogits(ws, targets, tstride, B, c->probs_buf, c->ustate, c->dl, bf, s));
-    HIP_TRY(c, fade_colsum(B, 256, c->dl, Gp(P_BO), bf, s));
+    HIP_TRY(c, fade_colsum(B, 256, c->dl, c->col_part, Gp(P_BO), bf, s));
+  }
+  {  // feature-major copies of every forward activation that is the left operand of a weight gradient, in one launch
+    Prof p(c, "transpose");
+    TransposeBatch tb{};
+    auto add = [&](const void *src, int width, void *dst, const float *st, const float *ga, const float *be) {
+      tb.t[tb.count] = tr_desc(c, src, width, dst, st, ga, be);
+      tb.N[tb.count++] = width;
+    };
+    add(c->Hout, Dh, c->LT[0], nullptr, nullptr, nullptr);
+    add(c->Hexp, De, c->LT[1], nullptr, nullptr, nullptr);
+    add(c->Hc, Dh, c->LT[2], c->stats_f, c->P(P_GAMMA_F), c->P(P_BETA_F));   // u = LN(H_coarse)
+    add(c->Hmix, Dh, c->LT[3], nullptr, nullptr, nullptr);
+    add(c->z, dl, c->LT[4], nullptr, nullptr, nullptr);
+    add(c->Hmix, Dh, c->LT[5], c->stats_c, c->P(P_GAMMA_C), c->P(P_BETA_C)); // LN(H_mix)
+    add(c->M, (int)d.Dc, c->LT[6], nullptr, nullptr, nullptr);
+    HIP_TRY(c, fade_transpose_batch(tb, bf, s));
+    HIP_TRY(c, fade_embed_t(ws, B, (int)c->Bp, (int)d.T, (int)d.D, c->tabXe, c->LT[7], bf, s));  // X^T straight from the table
   }
   // head
-  if ((rc = gemm_w(c, "gemm_dW_o", c->Hout, Dh, nullptr, nullptr, nullptr, c->dl, 256, Gp(P_WO), nullptr))) return rc;
+  if ((rc = transpose_grads(c, {{c->dl, {c->RT[0], 256}}}))) return rc;
+  if ((rc = gemm_w(c, "gemm_dW_o", c->LT[0], Dh, c->dl, c->RT[0], 256, Gp(P_WO), nullptr))) return rc;
   if ((rc = gemm_x(c, "gemm_dHout", c->dl, 256, Dh, c->WT_o, c->P(P_WO), 256, c->dHout))) return rc;
   {  // Eq. 10
     Prof p(c, "bwd_out");
     BwdOutArgs a{};
-    a.Dh = Dh; a.stats_n = SN; a.dH = c->dHout; a.V = c->V; a.Hc = c->Hc; a.stats = c->stats_o; a.gamma = c->P(P_GAMMA_O);
+    a.B = B; a.Dh = Dh; a.stats_n = SN; a.ln_part = c->ln_part; a.dH = c->dHout; a.V = c->V; a.Hc = c->Hc; a.stats = c->stats_o; a.gamma = c->P(P_GAMMA_O);
     a.beta = c->P(P_BETA_O); a.lam = c->P(P_LAMBDA_O); a.dnv = c->dnv; a.dV = c->dV; a.dHc = c->dHc; a.row_dlam = c->row_dlam;
-    HIP_TRY(c, fade_bwd_out(a, B, bf, s));
-    HIP_TRY(c, fade_ln_param_grad(B, Dh, SN, c->dnv, c->V, c->stats_o, Gp(P_GAMMA_O), Gp(P_BETA_O), bf, s));
+    HIP_TRY(c, fade_bwd_out(a, bf, s));
+    HIP_TRY(c, fade_reduce_rows(RB, 2 * Dh, c->ln_part, Gp(P_GAMMA_O), s));  // gamma_o then beta_o, adjacent in the blob
   }
-  if ((rc = gemm_w(c, "gemm_dW_f", c->Hexp, De, nullptr, nullptr, nullptr, c->dV, Dh, Gp(P_WF), nullptr))) return rc;
+  if ((rc = transpose_grads(c, {{c->dV, {c->RT[1], Dh}}}))) return rc;
+  if ((rc = gemm_w(c, "gemm_dW_f", c->LT[1], De, c->dV, c->RT[1], Dh, Gp(P_WF), nullptr))) return rc;
   if ((rc = gemm_x(c, "gemm_dHexp", c->dV, Dh, De, c->WT_f, c->P(P_WF), Dh, c->dHexp))) return rc;
   {  // Eq. 9
     Prof p(c, "bwd_geglu");
     HIP_TRY(c, fade_bwd_geglu(B, De, c->dHexp, c->eg, c->ev, c->dE, bf, s));
   }
-  if ((rc = gemm_w(c, "gemm_dW_fgv", c->Hc, Dh, c->stats_f, c->P(P_GAMMA_F), c->P(P_BETA_F), c->dE, 2 * De, Gp(P_WFG), Gp(P_WFV)))) return rc;
+  if ((rc = transpose_grads(c, {{c->dE, {c->RT[2], 2 * De}}}))) return rc;
+  if ((rc = gemm_w(c, "gemm_dW_fgv", c->LT[2], Dh, c->dE, c->RT[2], 2 * De, Gp(P_WFG), Gp(P_WFV)))) return rc;
   if ((rc = gemm_x(c, "gemm_du", c->dE, 2 * De, Dh, c->WT_fgv, static_cast<const float *>(c->Wfgv_c), 2 * De, c->du))) return rc;
   {  // LN of Eq. 9 + Eq. 8
     Prof p(c, "bwd_gate");
     BwdGateArgs a{};
-    a.Dh = Dh; a.stats_n = SN; a.du = c->du; a.Hc = c->Hc; a.dHc = c->dHc; a.sg = c->sg; a.Ha = c->Ha; a.Hmix = c->Hmix;
+    a.B = B; a.Dh = Dh; a.stats_n = SN; a.ln_part = c->ln_part + (size_t)RB * 2 * Dh; a.du = c->du; a.Hc = c->Hc; a.dHc = c->dHc; a.sg = c->sg; a.Ha = c->Ha; a.Hmix = c->Hmix;
     a.stats = c->stats_f; a.gamma = c->P(P_GAMMA_F); a.lam = c->P(P_LAMBDA_C); a.dHa = c->dHa; a.dac = c->dac; a.dHmix = c->dHmix1;
     a.row_dlam = c->row_dlam + B;
-    HIP_TRY(c, fade_bwd_gate(a, B, bf, s));
-    HIP_TRY(c, fade_ln_param_grad(B, Dh, SN, c->du, c->Hc, c->stats_f, Gp(P_GAMMA_F), Gp(P_BETA_F), bf, s));
+    HIP_TRY(c, fade_bwd_gate(a, bf, s));
+    HIP_TRY(c, fade_reduce_rows(RB, 2 * Dh, c->ln_part + (size_t)RB * 2 * Dh, Gp(P_GAMMA_F), s));
   }
-  if ((rc = gemm_w(c, "gemm_dW_c", c->Hmix, Dh, nullptr, nullptr, nullptr, c->dac, Dh, Gp(P_WC), nullptr))) return rc;
+  if ((rc = transpose_grads(c, {{c->dac, {c->RT[3], Dh}}, {c->dHa, {c->RT[4], Dh}}}))) return rc;
+  if ((rc = gemm_w(c, "gemm_dW_c", c->LT[3], Dh, c->dac, c->RT[3], Dh, Gp(P_WC), nullptr))) return rc;
   if ((rc = gemm_x(c, "gemm_dHmix", c->dac, Dh, Dh, c->WT_c, c->P(P_WC), Dh, c->dHmix2))) return rc;
   // Eq. 7
-  if ((rc = gemm_w(c, "gemm_dW_up", c->z, dl, nullptr, nullptr, nullptr, c->dHa, Dh, Gp(P_WUP), nullptr))) return rc;
+  if ((rc = gemm_w(c, "gemm_dW_up", c->LT[4], dl, c->dHa, c->RT[4], Dh, Gp(P_WUP), nullptr))) return rc;
   {
     Prof p(c, "gemm_dz");
     GemmArgs g{};
@@ -615,51 +651,37 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     a.lr = c->cfg.lr; a.beta1 = c->cfg.beta1; a.beta2 = c->cfg.beta2; a.eps = c->cfg.eps;
     HIP_TRY(c, fade_bwd_cci(a, bf, s));
   }
-  if ((rc = gemm_w(c, "gemm_dW_down", c->Hmix, Dh, c->stats_c, c->P(P_GAMMA_C), c->P(P_BETA_C), c->dy_at, dl, Gp(P_WDOWN), nullptr))) return rc;
+  if ((rc = transpose_grads(c, {{c->dy_at, {c->RT[5], dl}}}))) return rc;
+  if ((rc = gemm_w(c, "gemm_dW_down", c->LT[5], Dh, c->dy_at, c->RT[5], dl, Gp(P_WDOWN), nullptr))) return rc;
   if ((rc = gemm_x(c, "gemm_dnc", c->dy_at, dl, Dh, c->WT_down, c->P(P_WDOWN), dl, c->dnc))) return rc;
   {  // LN of Eq. 7 + Eq. 5-6 + branch activations
     Prof p(c, "bwd_mix");
     BwdMixArgs a{};
-    a.Dh = Dh; a.stats_n = SN; a.dnc = c->dnc; a.Hmix = c->Hmix; a.dHmix1 = c->dHmix1; a.dHmix2 = c->dHmix2; a.alpha = c->alpha;
+    a.B = B; a.Dh = Dh; a.stats_n = SN; a.ln_part = c->ln_part + (size_t)RB * 4 * Dh; a.dnc = c->dnc; a.Hmix = c->Hmix; a.dHmix1 = c->dHmix1; a.dHmix2 = c->dHmix2; a.alpha = c->alpha;
     a.Hg = c->Hg; a.Hl = c->Hl; a.hm = c->hm; a.cv = c->cv; a.X = c->X; a.stats = c->stats_c; a.gamma = c->P(P_GAMMA_C);
     a.lam = c->P(P_LAMBDA_M); a.dar = c->dar; a.dhm = c->dhm; a.dcv = c->dcv; a.dX = c->dX1; a.row_dlam = c->row_dlam + 2 * B;
-    HIP_TRY(c, fade_bwd_mix(a, B, bf, s));
-    HIP_TRY(c, fade_ln_param_grad(B, Dh, SN, c->dnc, c->Hmix, c->stats_c, Gp(P_GAMMA_C), Gp(P_BETA_C), bf, s));
+    HIP_TRY(c, fade_bwd_mix(a, bf, s));
+    HIP_TRY(c, fade_reduce_rows(RB, 2 * Dh, c->ln_part + (size_t)RB * 4 * Dh, Gp(P_GAMMA_C), s));
     HIP_TRY(c, fade_scalar_sums(B, c->row_dlam, c->row_dlam + B, c->row_dlam + 2 * B, Gp(P_LAMBDA_O), Gp(P_LAMBDA_C), Gp(P_LAMBDA_M), s));
   }
-  {  // router: X^T comes straight from the per-symbol table
-    Prof p(c, "transpose");
-    HIP_TRY(c, fade_embed_t(ws, B, (int)c->Bp, (int)d.T, (int)d.D, c->tabXe, c->LT, bf, s));
-    if (bf) {
-      TransposeArgs r{};
-      r.src = c->dar; r.ld = Dh; r.dst = c->RT; r.Bp = (int)c->Bp; r.B = B;
-      HIP_TRY(c, fade_transpose(r, Dh, true, s));
-    }
-  }
-  {
-    Prof p(c, "gemm_dW_r");
-    GemmArgs g{};
-    g.M = Dh; g.N = Dh; g.K = (int)c->Bp; g.A = c->LT; g.lda = (int)c->Bp; g.C = Gp(P_WR); g.ldc = Dh;
-    if (bf) { g.W = c->RT; g.ldb = (int)c->Bp; }
-    else g.W = c->dar;
-    HIP_TRY(c, fade_gemm(GEMM_W, bf, g, s));
-  }
+  if ((rc = transpose_grads(c, {{c->dar, {c->RT[6], Dh}}, {c->dhm, {c->RT[7], Dh}}}))) return rc;
+  if ((rc = gemm_w(c, "gemm_dW_r", c->LT[7], Dh, c->dar, c->RT[6], Dh, Gp(P_WR), nullptr))) return rc;
   if ((rc = gemm_x(c, "gemm_dX", c->dar, Dh, Dh, c->WT_r, c->P(P_WR), Dh, c->dX2))) return rc;
   // global stream
-  if ((rc = gemm_w(c, "gemm_dW_m", c->M, (int)d.Dc, nullptr, nullptr, nullptr, c->dhm, Dh, Gp(P_WM), nullptr))) return rc;
+  if ((rc = gemm_w(c, "gemm_dW_m", c->LT[6], (int)d.Dc, c->dhm, c->RT[7], Dh, Gp(P_WM), nullptr))) return rc;
   {
     Prof p(c, "bwd_slot");
     BwdSlotArgs a{};
     a.Dh = Dh; a.Dc = (int)d.Dc; a.c = (int)d.c; a.D = (int)d.D; a.round_bf16 = bf ? 1 : 0; a.dhm = c->dhm; a.Wm = c->P(P_WM);
     a.GG = c->GG; a.GV = c->GV; a.Wg = c->Wg_c; a.Wv = c->Wv_c; a.dgg = c->dgg; a.dgv = c->dgv; a.dxt = c->dxt;
     HIP_TRY(c, fade_bwd_slot(a, B, bf, s));
-    HIP_TRY(c, fade_slot_weight_grad(ws, B, (int)d.T, (int)d.D, (int)d.c, c->tabXe32, c->dgg, c->dgv, Gp(P_WG), Gp(P_WV), s));
+    HIP_TRY(c, fade_slot_weight_grad(ws, B, (int)d.T, (int)d.D, (int)d.c, c->tabXe32, c->dgg, c->dgv, c->slot_part, Gp(P_WG), s));
   }
   {  // local stream
     Prof p(c, "bwd_conv");
     ConvGradArgs a{};
     a.B = B; a.T = (int)d.T; a.D = (int)d.D; a.taps = (int)d.k; a.XL = c->XL; a.dcv = c->dcv; a.part = c->conv_part;
-    HIP_TRY(c, fade_conv_grad(a, c->conv_blocks, Gp(P_WCONV), Gp(P_BCONV), bf, s));
+    HIP_TRY(c, fade_conv_grad(a, Gp(P_WCONV), bf, s));  // W_conv then b_conv, adjacent in the blob
     GemmArgs g{};
     g.M = (int)(d.B * d.T); g.N = (int)d.D; g.K = (int)d.Kc; g.A = c->dcv; g.T = (int)d.T; g.D = (int)d.D; g.taps = (int)d.k;
     g.W = bf ? c->WT_conv : static_cast<const void *>(c->convt_f32); g.C = c->dxl; g.ldc = (int)d.D;
@@ -669,10 +691,10 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     Prof p(c, "bwd_embed");
     BwdTokenArgs a{};
     a.ws = ws; a.B = B; a.T = (int)d.T; a.D = (int)d.D; a.dX1 = c->dX1; a.dX2 = c->dX2; a.dxl = c->dxl; a.dxt = c->dxt;
-    a.tabXhat = c->tabXhat; a.tabRstd = c->tabRstd; a.gamma_e = c->P(P_GAMMA_E); a.gamma_l = c->P(P_GAMMA_L); a.de = c->de;
-    a.part = c->tok_part;
-    HIP_TRY(c, fade_bwd_token(a, Gp(P_GAMMA_E), Gp(P_BETA_E), Gp(P_GAMMA_L), Gp(P_BETA_L), bf, s));
-    HIP_TRY(c, fade_embed_grad(ws, B, (int)d.T, (int)d.D, c->de, Gp(P_E), s));
+    a.tabXhat = c->tabXhat; a.tabRstd = c->tabRstd; a.gamma_e = c->P(P_GAMMA_E); a.gamma_l = c->P(P_GAMMA_L);
+    a.part = c->emb_part;
+    // gamma_e, beta_e, gamma_l, beta_l are adjacent in the blob
+    HIP_TRY(c, fade_bwd_embed(a, c->emb_blocks, c->sym_sums, c->tok_part, Gp(P_E), Gp(P_GAMMA_E), bf, s));
   }
   {  // Adam on everything except W_U (done in place above), then refresh the compute copies
     Prof p(c, "adam_refresh");
@@ -846,10 +868,11 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
     TRY_ALLOC(dev_alloc(c, &c->part_down, (size_t)c->sp_down * d.B * d.dl));
     TRY_ALLOC(dev_alloc(c, &c->part_fnr, (size_t)c->sp_fnr * d.B * 2 * d.De));
     TRY_ALLOC(dev_alloc(c, &c->part_head, (size_t)c->sp_head * d.B * 256));
-    TRY_ALLOC(dev_alloc(c, &c->s_down, d.dl));
-    TRY_ALLOC(dev_alloc(c, &c->t_down, d.dl));
-    TRY_ALLOC(dev_alloc(c, &c->s_fnr, 2 * d.De));
-    TRY_ALLOC(dev_alloc(c, &c->t_fnr, 2 * d.De));
+    TRY_ALLOC(dev_alloc(c, &c->s_down, 2 * d.dl));
+    c->t_down = c->s_down + d.dl;
+    TRY_ALLOC(dev_alloc(c, &c->s_fnr, 4 * d.De));
+    c->t_fnr = c->s_fnr + 2 * d.De;
+    TRY_ALLOC(dev_alloc(c, &c->fold_part, 16 * 2 * std::max<size_t>(d.dl, 2 * d.De)));
   } else {  // fp32: most operands are used straight from the master blob
     c->E_c = c->master + c->lay.off[P_E];
     c->Wg_c = c->master + c->lay.off[P_WG];
@@ -909,7 +932,11 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
         {&c->dl, Bp * 256}, {&c->dHout, BDh}, {&c->dnv, BDh}, {&c->dV, BpDh}, {&c->dHc, BDh}, {&c->dHexp, d.B * d.De},
         {&c->dE, Bp * 2 * d.De}, {&c->du, BDh}, {&c->dHa, BpDh}, {&c->dac, BpDh}, {&c->dHmix1, BDh}, {&c->dHmix2, BDh},
         {&c->dy_at, Bp * d.dl}, {&c->dnc, BDh}, {&c->dar, BpDh}, {&c->dhm, BpDh}, {&c->dcv, BDh}, {&c->dX1, BDh}, {&c->dX2, BDh},
-        {&c->dxl, BDh}, {&c->LT, d.Dh * Bp}, {&c->RT, std::max<size_t>(std::max<size_t>(d.Dh, 2 * d.De), 256) * Bp}};
+        {&c->dxl, BDh},
+        {&c->LT[0], d.Dh * Bp}, {&c->LT[1], d.De * Bp}, {&c->LT[2], d.Dh * Bp}, {&c->LT[3], d.Dh * Bp}, {&c->LT[4], d.dl * Bp},
+        {&c->LT[5], d.Dh * Bp}, {&c->LT[6], d.Dc * Bp}, {&c->LT[7], d.Dh * Bp},
+        {&c->RT[0], 256 * Bp}, {&c->RT[1], d.Dh * Bp}, {&c->RT[2], 2 * d.De * Bp}, {&c->RT[3], d.Dh * Bp}, {&c->RT[4], d.Dh * Bp},
+        {&c->RT[5], d.dl * Bp}, {&c->RT[6], d.Dh * Bp}, {&c->RT[7], d.Dh * Bp}};
     for (auto &b : bufs) {
       TRY_ALLOC(A(b.p, b.n));
       if (hipMemsetAsync(*b.p, 0, b.n * c->esz, c->stream) != hipSuccess) { fade_destroy(c); return FADE_E_HIP; }
@@ -920,10 +947,16 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
     TRY_ALLOC(dev_alloc(c, &c->dgg, d.B * d.c));
     TRY_ALLOC(dev_alloc(c, &c->dgv, d.B * d.c));
     TRY_ALLOC(dev_alloc(c, &c->dxt, d.B * d.D));
-    TRY_ALLOC(dev_alloc(c, &c->de, BDh));
     TRY_ALLOC(dev_alloc(c, &c->row_dlam, 3 * d.B));
-    TRY_ALLOC(dev_alloc(c, &c->conv_part, (size_t)c->conv_blocks * (d.k * d.D + 1) * d.D));
-    TRY_ALLOC(dev_alloc(c, &c->tok_part, (d.B * d.T + 255) / 256 * 4 * d.D));
+    const size_t tokens = d.B * d.T, rb = (d.B + fade_rows_per_block() - 1) / fade_rows_per_block();
+    c->emb_blocks = (int)std::min<size_t>(256, (tokens + 127) / 128);
+    TRY_ALLOC(dev_alloc(c, &c->conv_part, (tokens + 127) / 128 * (d.k * d.D + 1) * d.D));
+    TRY_ALLOC(dev_alloc(c, &c->tok_part, 256 * 4 * d.D));
+    TRY_ALLOC(dev_alloc(c, &c->sym_sums, 2 * 256 * d.D));
+    TRY_ALLOC(dev_alloc(c, &c->ln_part, 3 * rb * 2 * d.Dh));
+    TRY_ALLOC(dev_alloc(c, &c->col_part, (d.B + 31) / 32 * 256));
+    TRY_ALLOC(dev_alloc(c, &c->slot_part, (d.B + 15) / 16 * 2 * d.D * d.c));
+    TRY_ALLOC(dev_alloc(c, &c->emb_part, (size_t)c->emb_blocks * 2 * 256 * d.D));
     if (hipMemsetAsync(c->grad, 0, np * sizeof(float), c->stream) != hipSuccess) { fade_destroy(c); return FADE_E_HIP; }
   }
   for (uint32_t **p : {&c->cb.low, &c->cb.high, &c->cb.pending, &c->cb.bitbuf, &c->cb.nbits, &c->cb.pos, &c->cb.value, &c->cb.bitpos})

@@ -125,6 +125,35 @@ __global__ __launch_bounds__(256) void transpose_kernel(TransposeArgs a) {
   }
 }
 
+template <typename AT>
+__global__ __launch_bounds__(256) void transpose_batch_kernel(TransposeBatch tb) {
+  __shared__ float tile[64][65];
+  const TransposeArgs &a = tb.t[blockIdx.z];
+  const int b0 = blockIdx.x * 64, n0 = blockIdx.y * 64;
+  if (b0 >= a.B || n0 >= tb.N[blockIdx.z]) return;  // uniform over the workgroup
+  const AT *src = static_cast<const AT *>(a.src);
+  AT *dst = static_cast<AT *>(a.dst);
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int r = ty; r < 64; r += 4) {
+    const int b = b0 + r;
+    float v = 0.0f;
+    if (b < a.B) {
+      v = (float)src[(size_t)b * a.ld + n0 + tx];
+      if (a.stats) {
+        float mean, rstd;
+        moments(a.stats + (size_t)b * a.stats_n * 2, a.stats_n, a.width, mean, rstd);
+        v = (v - mean) * rstd * a.gamma[n0 + tx] + a.beta[n0 + tx];
+      }
+    }
+    tile[r][tx] = v;
+  }
+  __syncthreads();
+  for (int r = ty; r < 64; r += 4) {
+    const int b = b0 + tx;
+    if (b < a.B) dst[(size_t)(n0 + r) * a.Bp + b] = (AT)tile[tx][r];
+  }
+}
+
 // X_T[j*D+i][b] = LN_e(E[w_{b,j}])[i] straight from the per-symbol table (X is a gather, so is its transpose)
 template <typename AT>
 __global__ __launch_bounds__(256) void embed_t_kernel(WinSrc ws, int B, int Bp, int T, int D, const AT *tab, AT *XT) {
@@ -145,56 +174,63 @@ __global__ __launch_bounds__(256) void embed_t_kernel(WinSrc ws, int B, int Bp, 
 // ---------------------------------------------------------------------------------------------------
 // row-wise backward passes (one workgroup per stream; a thread owns 8-wide chunks tid, tid+256, ...)
 // ---------------------------------------------------------------------------------------------------
-constexpr int kMaxChunks = 4;  // D_h <= 8192
+// a thread of the row kernels owns one 8-wide chunk: D_h <= 2048
+constexpr int kRowsPerBlock = 4; // rows handled by one workgroup; its LayerNorm gain / shift partial sums cover those rows
 
 // Eq. 10 backward: dnv = dH * psi'(nv), LN backward -> dV; dH_coarse = lambda_o dH; row part of d lambda_o.
 template <typename AT>
 __global__ __launch_bounds__(256) void bwd_out_kernel(BwdOutArgs a) {
   __shared__ float red[4];
-  const int b = blockIdx.x, tid = threadIdx.x, nch = a.Dh / 8;
-  float mean, rstd;
-  moments(a.stats + (size_t)b * a.stats_n * 2, a.stats_n, a.Dh, mean, rstd);
+  const int tid = threadIdx.x, nch = a.Dh / 8;
+  const bool mine = tid < nch;
   const float lam = a.lam[0];
-  const size_t base = (size_t)b * a.Dh;
-  float dh[kMaxChunks][8], xh[kMaxChunks][8];
-  float s1 = 0.0f, s2 = 0.0f, sl = 0.0f;
+  float ga[8], be[8], pg[8], pb[8];
 #pragma unroll
-  for (int q = 0; q < kMaxChunks; ++q) {
-    const int ch = q * 256 + tid;
-    if (ch < nch) {
-      float dH[8], v[8], hc[8], ga[8], be[8], dnv[8], dhc[8];
-      ld8<AT>(static_cast<const AT *>(a.dH) + base + ch * 8, dH);
-      ld8<AT>(static_cast<const AT *>(a.V) + base + ch * 8, v);
-      ld8<AT>(static_cast<const AT *>(a.Hc) + base + ch * 8, hc);
-      ld8<float>(a.gamma + ch * 8, ga);
-      ld8<float>(a.beta + ch * 8, be);
+  for (int i = 0; i < 8; ++i) { ga[i] = be[i] = pg[i] = pb[i] = 0.0f; }
+  if (mine) { ld8<float>(a.gamma + tid * 8, ga); ld8<float>(a.beta + tid * 8, be); }
+  for (int r = 0; r < kRowsPerBlock; ++r) {
+    const int b = blockIdx.x * kRowsPerBlock + r;
+    if (b >= a.B) break;  // uniform over the workgroup
+    float mean, rstd;
+    moments(a.stats + (size_t)b * a.stats_n * 2, a.stats_n, a.Dh, mean, rstd);
+    const size_t base = (size_t)b * a.Dh + tid * 8;
+    float dh[8], xh[8], s1 = 0.0f, s2 = 0.0f, sl = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { dh[i] = 0.0f; xh[i] = 0.0f; }
+    if (mine) {
+      float dH[8], v[8], hc[8], dnv[8], dhc[8];
+      ld8<AT>(static_cast<const AT *>(a.dH) + base, dH);
+      ld8<AT>(static_cast<const AT *>(a.V) + base, v);
+      ld8<AT>(static_cast<const AT *>(a.Hc) + base, hc);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        xh[q][i] = (v[i] - mean) * rstd;
-        const float nv = xh[q][i] * ga[i] + be[i];
+        xh[i] = (v[i] - mean) * rstd;
+        const float nv = xh[i] * ga[i] + be[i];
         dnv[i] = dH[i] * gelu_grad_f(nv);
-        dh[q][i] = dnv[i] * ga[i];
-        s1 += dh[q][i];
-        s2 += dh[q][i] * xh[q][i];
+        dh[i] = dnv[i] * ga[i];
+        s1 += dh[i];
+        s2 += dh[i] * xh[i];
         sl += dH[i] * hc[i];
         dhc[i] = lam * dH[i];
+        pg[i] += dnv[i] * xh[i];
+        pb[i] += dnv[i];
       }
-      st8<AT>(static_cast<AT *>(a.dnv) + base + ch * 8, dnv);
-      st8<AT>(static_cast<AT *>(a.dHc) + base + ch * 8, dhc);
+      st8<AT>(static_cast<AT *>(a.dHc) + base, dhc);
     }
-  }
-  const float m1 = block_sum(s1, red) / (float)a.Dh, m2 = block_sum(s2, red) / (float)a.Dh;
-  const float sumlam = block_sum(sl, red);
-  if (tid == 0) a.row_dlam[b] = sumlam;
-#pragma unroll
-  for (int q = 0; q < kMaxChunks; ++q) {
-    const int ch = q * 256 + tid;
-    if (ch < nch) {
+    const float m1 = block_sum(s1, red) / (float)a.Dh, m2 = block_sum(s2, red) / (float)a.Dh;
+    const float sumlam = block_sum(sl, red);
+    if (tid == 0) a.row_dlam[b] = sumlam;
+    if (mine) {
       float dv[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) dv[i] = rstd * (dh[q][i] - m1 - xh[q][i] * m2);
-      st8<AT>(static_cast<AT *>(a.dV) + base + ch * 8, dv);
+      for (int i = 0; i < 8; ++i) dv[i] = rstd * (dh[i] - m1 - xh[i] * m2);
+      st8<AT>(static_cast<AT *>(a.dV) + base, dv);
     }
+  }
+  if (mine) {
+    float *p = a.ln_part + (size_t)blockIdx.x * 2 * a.Dh;
+    st8<float>(p + tid * 8, pg);
+    st8<float>(p + a.Dh + tid * 8, pb);
   }
 }
 
@@ -222,56 +258,64 @@ __global__ __launch_bounds__(256) void bwd_geglu_kernel(int B, int De, const AT 
 template <typename AT>
 __global__ __launch_bounds__(256) void bwd_gate_kernel(BwdGateArgs a) {
   __shared__ float red[4];
-  const int b = blockIdx.x, tid = threadIdx.x, nch = a.Dh / 8;
-  float mean, rstd;
-  moments(a.stats + (size_t)b * a.stats_n * 2, a.stats_n, a.Dh, mean, rstd);
+  const int tid = threadIdx.x, nch = a.Dh / 8;
+  const bool mine = tid < nch;
   const float lam = a.lam[0];
-  const size_t base = (size_t)b * a.Dh;
-  float dh[kMaxChunks][8], xh[kMaxChunks][8];
-  float s1 = 0.0f, s2 = 0.0f;
+  float ga[8], pg[8], pb[8];
 #pragma unroll
-  for (int q = 0; q < kMaxChunks; ++q) {
-    const int ch = q * 256 + tid;
-    if (ch < nch) {
-      float du[8], hc[8], ga[8];
-      ld8<AT>(static_cast<const AT *>(a.du) + base + ch * 8, du);
-      ld8<AT>(static_cast<const AT *>(a.Hc) + base + ch * 8, hc);
-      ld8<float>(a.gamma + ch * 8, ga);
+  for (int i = 0; i < 8; ++i) { ga[i] = pg[i] = pb[i] = 0.0f; }
+  if (mine) ld8<float>(a.gamma + tid * 8, ga);
+  for (int r = 0; r < kRowsPerBlock; ++r) {
+    const int b = blockIdx.x * kRowsPerBlock + r;
+    if (b >= a.B) break;
+    float mean, rstd;
+    moments(a.stats + (size_t)b * a.stats_n * 2, a.stats_n, a.Dh, mean, rstd);
+    const size_t base = (size_t)b * a.Dh + tid * 8;
+    float dh[8], xh[8], s1 = 0.0f, s2 = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { dh[i] = 0.0f; xh[i] = 0.0f; }
+    if (mine) {
+      float du[8], hc[8];
+      ld8<AT>(static_cast<const AT *>(a.du) + base, du);
+      ld8<AT>(static_cast<const AT *>(a.Hc) + base, hc);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        xh[q][i] = (hc[i] - mean) * rstd;
-        dh[q][i] = du[i] * ga[i];
-        s1 += dh[q][i];
-        s2 += dh[q][i] * xh[q][i];
+        xh[i] = (hc[i] - mean) * rstd;
+        dh[i] = du[i] * ga[i];
+        s1 += dh[i];
+        s2 += dh[i] * xh[i];
+        pg[i] += du[i] * xh[i];
+        pb[i] += du[i];
       }
     }
-  }
-  const float m1 = block_sum(s1, red) / (float)a.Dh, m2 = block_sum(s2, red) / (float)a.Dh;
-  float sl = 0.0f;
-#pragma unroll
-  for (int q = 0; q < kMaxChunks; ++q) {
-    const int ch = q * 256 + tid;
-    if (ch < nch) {
+    const float m1 = block_sum(s1, red) / (float)a.Dh, m2 = block_sum(s2, red) / (float)a.Dh;
+    float sl = 0.0f;
+    if (mine) {
       float dhc[8], sg[8], ha[8], hm[8], dHa[8], dac[8], dmix[8];
-      ld8<AT>(static_cast<const AT *>(a.dHc) + base + ch * 8, dhc);
-      ld8<AT>(static_cast<const AT *>(a.sg) + base + ch * 8, sg);
-      ld8<AT>(static_cast<const AT *>(a.Ha) + base + ch * 8, ha);
-      ld8<AT>(static_cast<const AT *>(a.Hmix) + base + ch * 8, hm);
+      ld8<AT>(static_cast<const AT *>(a.dHc) + base, dhc);
+      ld8<AT>(static_cast<const AT *>(a.sg) + base, sg);
+      ld8<AT>(static_cast<const AT *>(a.Ha) + base, ha);
+      ld8<AT>(static_cast<const AT *>(a.Hmix) + base, hm);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        const float d = dhc[i] + rstd * (dh[q][i] - m1 - xh[q][i] * m2);
+        const float d = dhc[i] + rstd * (dh[i] - m1 - xh[i] * m2);
         dHa[i] = d * sg[i];
         dac[i] = d * ha[i] * sg[i] * (1.0f - sg[i]);
         dmix[i] = lam * d;
         sl += d * hm[i];
       }
-      st8<AT>(static_cast<AT *>(a.dHa) + base + ch * 8, dHa);
-      st8<AT>(static_cast<AT *>(a.dac) + base + ch * 8, dac);
-      st8<AT>(static_cast<AT *>(a.dHmix) + base + ch * 8, dmix);
+      st8<AT>(static_cast<AT *>(a.dHa) + base, dHa);
+      st8<AT>(static_cast<AT *>(a.dac) + base, dac);
+      st8<AT>(static_cast<AT *>(a.dHmix) + base, dmix);
     }
+    const float sumlam = block_sum(sl, red);
+    if (tid == 0) a.row_dlam[b] = sumlam;
   }
-  const float sumlam = block_sum(sl, red);
-  if (tid == 0) a.row_dlam[b] = sumlam;
+  if (mine) {
+    float *p = a.ln_part + (size_t)blockIdx.x * 2 * a.Dh;
+    st8<float>(p + tid * 8, pg);
+    st8<float>(p + a.Dh + tid * 8, pb);
+  }
 }
 
 // LN (Eq. 7) backward into dH_mix (+ the gate path's contribution), then Eq. 5-6 and the branch activations:
@@ -280,48 +324,51 @@ __global__ __launch_bounds__(256) void bwd_gate_kernel(BwdGateArgs a) {
 template <typename AT>
 __global__ __launch_bounds__(256) void bwd_mix_kernel(BwdMixArgs a) {
   __shared__ float red[4];
-  const int b = blockIdx.x, tid = threadIdx.x, nch = a.Dh / 8;
-  float mean, rstd;
-  moments(a.stats + (size_t)b * a.stats_n * 2, a.stats_n, a.Dh, mean, rstd);
+  const int tid = threadIdx.x, nch = a.Dh / 8;
+  const bool mine = tid < nch;
   const float lam = a.lam[0];
-  const size_t base = (size_t)b * a.Dh;
-  float dh[kMaxChunks][8], xh[kMaxChunks][8];
-  float s1 = 0.0f, s2 = 0.0f;
+  float ga[8], pg[8], pb[8];
 #pragma unroll
-  for (int q = 0; q < kMaxChunks; ++q) {
-    const int ch = q * 256 + tid;
-    if (ch < nch) {
-      float dn[8], hm[8], ga[8];
-      ld8<AT>(static_cast<const AT *>(a.dnc) + base + ch * 8, dn);
-      ld8<AT>(static_cast<const AT *>(a.Hmix) + base + ch * 8, hm);
-      ld8<float>(a.gamma + ch * 8, ga);
+  for (int i = 0; i < 8; ++i) { ga[i] = pg[i] = pb[i] = 0.0f; }
+  if (mine) ld8<float>(a.gamma + tid * 8, ga);
+  for (int r = 0; r < kRowsPerBlock; ++r) {
+    const int b = blockIdx.x * kRowsPerBlock + r;
+    if (b >= a.B) break;
+    float mean, rstd;
+    moments(a.stats + (size_t)b * a.stats_n * 2, a.stats_n, a.Dh, mean, rstd);
+    const size_t base = (size_t)b * a.Dh + tid * 8;
+    float dh[8], xh[8], s1 = 0.0f, s2 = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { dh[i] = 0.0f; xh[i] = 0.0f; }
+    if (mine) {
+      float dn[8], hm[8];
+      ld8<AT>(static_cast<const AT *>(a.dnc) + base, dn);
+      ld8<AT>(static_cast<const AT *>(a.Hmix) + base, hm);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        xh[q][i] = (hm[i] - mean) * rstd;
-        dh[q][i] = dn[i] * ga[i];
-        s1 += dh[q][i];
-        s2 += dh[q][i] * xh[q][i];
+        xh[i] = (hm[i] - mean) * rstd;
+        dh[i] = dn[i] * ga[i];
+        s1 += dh[i];
+        s2 += dh[i] * xh[i];
+        pg[i] += dn[i] * xh[i];
+        pb[i] += dn[i];
       }
     }
-  }
-  const float m1 = block_sum(s1, red) / (float)a.Dh, m2 = block_sum(s2, red) / (float)a.Dh;
-  float sl = 0.0f;
-#pragma unroll
-  for (int q = 0; q < kMaxChunks; ++q) {
-    const int ch = q * 256 + tid;
-    if (ch < nch) {
+    const float m1 = block_sum(s1, red) / (float)a.Dh, m2 = block_sum(s2, red) / (float)a.Dh;
+    float sl = 0.0f;
+    if (mine) {
       float d1[8], d2[8], al[8], hg[8], hl[8], pre_g[8], pre_c[8], x[8], dar[8], dhm[8], dcv[8], dX[8];
-      ld8<AT>(static_cast<const AT *>(a.dHmix1) + base + ch * 8, d1);
-      ld8<AT>(static_cast<const AT *>(a.dHmix2) + base + ch * 8, d2);
-      ld8<AT>(static_cast<const AT *>(a.alpha) + base + ch * 8, al);
-      ld8<AT>(static_cast<const AT *>(a.Hg) + base + ch * 8, hg);
-      ld8<AT>(static_cast<const AT *>(a.Hl) + base + ch * 8, hl);
-      ld8<AT>(static_cast<const AT *>(a.hm) + base + ch * 8, pre_g);
-      ld8<AT>(static_cast<const AT *>(a.cv) + base + ch * 8, pre_c);
-      ld8<AT>(static_cast<const AT *>(a.X) + base + ch * 8, x);
+      ld8<AT>(static_cast<const AT *>(a.dHmix1) + base, d1);
+      ld8<AT>(static_cast<const AT *>(a.dHmix2) + base, d2);
+      ld8<AT>(static_cast<const AT *>(a.alpha) + base, al);
+      ld8<AT>(static_cast<const AT *>(a.Hg) + base, hg);
+      ld8<AT>(static_cast<const AT *>(a.Hl) + base, hl);
+      ld8<AT>(static_cast<const AT *>(a.hm) + base, pre_g);
+      ld8<AT>(static_cast<const AT *>(a.cv) + base, pre_c);
+      ld8<AT>(static_cast<const AT *>(a.X) + base, x);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        const float d = d1[i] + d2[i] + rstd * (dh[q][i] - m1 - xh[q][i] * m2);
+        const float d = d1[i] + d2[i] + rstd * (dh[i] - m1 - xh[i] * m2);
         const float dHg = d * al[i], dHl = d * (1.0f - al[i]);
         dar[i] = d * (hg[i] - hl[i]) * al[i] * (1.0f - al[i]);
         dhm[i] = dHg * gelu_grad_f(pre_g[i]);
@@ -329,51 +376,49 @@ __global__ __launch_bounds__(256) void bwd_mix_kernel(BwdMixArgs a) {
         dX[i] = lam * dHg;
         sl += dHg * x[i];
       }
-      st8<AT>(static_cast<AT *>(a.dar) + base + ch * 8, dar);
-      st8<AT>(static_cast<AT *>(a.dhm) + base + ch * 8, dhm);
-      st8<AT>(static_cast<AT *>(a.dcv) + base + ch * 8, dcv);
-      st8<AT>(static_cast<AT *>(a.dX) + base + ch * 8, dX);
+      st8<AT>(static_cast<AT *>(a.dar) + base, dar);
+      st8<AT>(static_cast<AT *>(a.dhm) + base, dhm);
+      st8<AT>(static_cast<AT *>(a.dcv) + base, dcv);
+      st8<AT>(static_cast<AT *>(a.dX) + base, dX);
     }
+    const float sumlam = block_sum(sl, red);
+    if (tid == 0) a.row_dlam[b] = sumlam;
   }
-  const float sumlam = block_sum(sl, red);
-  if (tid == 0) a.row_dlam[b] = sumlam;
-}
-
-// d gamma[n] = sum_b dn[b][n] * xhat[b][n], d beta[n] = sum_b dn[b][n] for a row LayerNorm over `width` columns.
-// One workgroup per 64 columns; four row phases, each summing its rows in increasing order, combined in phase order.
-template <typename AT>
-__global__ __launch_bounds__(256) void ln_param_grad_kernel(int B, int width, int stats_n, const AT *dn, const AT *x, const float *stats,
-                                                            float *dgamma, float *dbeta) {
-  __shared__ float pg[4][64], pb[4][64];
-  const int n = blockIdx.x * 64 + (threadIdx.x & 63), ph = threadIdx.x >> 6;
-  float sg = 0.0f, sb = 0.0f;
-  for (int b = ph; b < B; b += 4) {
-    float mean, rstd;
-    moments(stats + (size_t)b * stats_n * 2, stats_n, width, mean, rstd);
-    const float d = (float)dn[(size_t)b * width + n];
-    sg += d * ((float)x[(size_t)b * width + n] - mean) * rstd;
-    sb += d;
-  }
-  pg[ph][threadIdx.x & 63] = sg;
-  pb[ph][threadIdx.x & 63] = sb;
-  __syncthreads();
-  if (ph == 0) {
-    const int c = threadIdx.x;
-    dgamma[n] = (pg[0][c] + pg[1][c]) + (pg[2][c] + pg[3][c]);
-    dbeta[n] = (pb[0][c] + pb[1][c]) + (pb[2][c] + pb[3][c]);
+  if (mine) {
+    float *p = a.ln_part + (size_t)blockIdx.x * 2 * a.Dh;
+    st8<float>(p + tid * 8, pg);
+    st8<float>(p + a.Dh + tid * 8, pb);
   }
 }
 
-// out[n] = sum_b src[b][n] (bias gradients). Same structure as above.
-template <typename AT>
-__global__ __launch_bounds__(256) void colsum_kernel(int B, int N, const AT *src, float *out) {
-  __shared__ float ps[4][64];
-  const int n = blockIdx.x * 64 + (threadIdx.x & 63), ph = threadIdx.x >> 6;
+// Column sums in two deterministic stages. Stage 1 (here, or inside a producer kernel) leaves partial sums per row block
+// as part[P][N]; stage 2 adds the P partials of each column in index order.
+__global__ __launch_bounds__(256) void reduce_rows_kernel(int P, int N, const float *part, float *out) {
+  // 32 columns x 8 phases: phase h adds rows h, h+8, ... in increasing order; the 8 phase sums are added in phase order
+  __shared__ float ps[8][32];
+  const int c = threadIdx.x & 31, h = threadIdx.x >> 5, n = blockIdx.x * 32 + c;
   float s = 0.0f;
-  for (int b = ph; b < B; b += 4) s += (float)src[(size_t)b * N + n];
-  ps[ph][threadIdx.x & 63] = s;
+  if (n < N) {
+#pragma unroll 4
+    for (int p = h; p < P; p += 8) s += part[(size_t)p * N + n];
+  }
+  ps[h][c] = s;
   __syncthreads();
-  if (ph == 0) out[n] = (ps[0][threadIdx.x] + ps[1][threadIdx.x]) + (ps[2][threadIdx.x] + ps[3][threadIdx.x]);
+  if (h == 0 && n < N) {
+    float t = 0.0f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) t += ps[k][c];
+    out[n] = t;
+  }
+}
+// stage 1 for a plain matrix: part[rb][n] = sum over the 32 rows of row block rb of src[b][n]
+template <typename AT>
+__global__ __launch_bounds__(256) void colsum_partial_kernel(int B, int N, const AT *src, float *part) {
+  const int n = blockIdx.y * 256 + threadIdx.x, b0 = blockIdx.x * 32;
+  if (n >= N) return;
+  float s = 0.0f;
+  for (int r = 0; r < 32 && b0 + r < B; ++r) s += (float)src[(size_t)(b0 + r) * N + n];
+  part[(size_t)blockIdx.x * N + n] = s;
 }
 
 // Sum per-row partials [B] into one scalar each (the three residual scales). One workgroup, fixed order.
@@ -397,32 +442,43 @@ __global__ __launch_bounds__(256) void scalar_sums_kernel(int B, const float *r0
 // ---------------------------------------------------------------------------------------------------
 template <typename AT>
 __global__ __launch_bounds__(256) void bwd_cci_kernel(BwdCciArgs a) {
-  const int b = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
-  if (b >= a.B) return;
-  float dz = 0.0f;
-  for (int s = 0; s < a.splits; ++s) dz += a.dz_part[((size_t)s * a.B + b) * 64 + lane];
-  const float yv = a.y[(size_t)b * 64 + lane];
-  const AT *Wc = static_cast<const AT *>(a.WU_c) + (size_t)b * 4096;
-  // dy[lane] = row `lane` of W_U[b] dot dz: walk the columns, broadcasting dz
-  float dy = 0.0f;
-  for (int n = 0; n < 64; ++n) dy = fmaf((float)Wc[lane * 64 + n], __shfl(dz, n, 64), dy);
-  a.dy[(size_t)b * 64 + lane] = dy;
-  static_cast<AT *>(a.dy_at)[(size_t)b * 64 + lane] = (AT)dy;
+  __shared__ float dz_s[64], y_s[64];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  if (tid < 64) {
+    float dz = 0.0f;
+    for (int s = 0; s < a.splits; ++s) dz += a.dz_part[((size_t)s * a.B + b) * 64 + tid];
+    dz_s[tid] = dz;
+    y_s[tid] = a.y[(size_t)b * 64 + tid];
+  }
+  __syncthreads();
+  AT *Wc = static_cast<AT *>(a.WU_c) + (size_t)b * 4096;
+  {  // dy[k] = row k of W_U[b] dot dz: four threads per row, 16 columns each, combined in a fixed butterfly
+    const int k = tid >> 2, q = tid & 3;
+    float s = 0.0f;
+#pragma unroll
+    for (int n = 0; n < 16; ++n) s = fmaf((float)Wc[k * 64 + q * 16 + n], dz_s[q * 16 + n], s);
+    s += __shfl_xor(s, 1, 64);
+    s += __shfl_xor(s, 2, 64);
+    if (q == 0) {
+      a.dy[(size_t)b * 64 + k] = s;
+      static_cast<AT *>(a.dy_at)[(size_t)b * 64 + k] = (AT)s;
+    }
+  }
   const UpdateState u = *a.u;
   if (u.na == 0) return;
-  // Adam on slice b: lane owns column `lane`, rows k = 0..63
+  __syncthreads();  // every read of the old W_U[b] is done before it is rewritten
   float *master = a.master + (size_t)b * 4096, *m = a.m + (size_t)b * 4096, *v = a.v + (size_t)b * 4096;
-  AT *Wo = static_cast<AT *>(a.WU_c) + (size_t)b * 4096;
-  for (int k = 0; k < 64; ++k) {
-    const int idx = k * 64 + lane;
-    const float g = __shfl(yv, k, 64) * dz;
+#pragma unroll 4
+  for (int e = 0; e < 16; ++e) {
+    const int idx = e * 256 + tid, k = idx >> 6, n = idx & 63;
+    const float g = y_s[k] * dz_s[n];
     const float mk = a.beta1 * m[idx] + (1.0f - a.beta1) * g;
     const float vk = a.beta2 * v[idx] + (1.0f - a.beta2) * g * g;
     m[idx] = mk;
     v[idx] = vk;
     const float w = master[idx] - a.lr * (mk / u.c1) / (sqrtf(vk / u.c2) + a.eps);
     master[idx] = w;
-    Wo[idx] = (AT)w;
+    Wc[idx] = (AT)w;
   }
 }
 
@@ -461,21 +517,22 @@ __global__ __launch_bounds__(256) void bwd_slot_kernel(BwdSlotArgs a) {
   }
 }
 
-// dW_g[i][q] = sum_b xt[b][i] d gg[b][q] (same for W_v): one thread per output, batch in increasing order.
-__global__ void slot_weight_grad_kernel(WinSrc ws, int B, int T, int D, int c, const float *tabXe32, const float *dgg, const float *dgv,
-                                        float *dWg, float *dWv) {
-  const int t = blockIdx.x * blockDim.x + threadIdx.x;
-  if (t >= D * c) return;
-  const int i = t / c, q = t - i * c;
-  float sg = 0.0f, sv = 0.0f;
-  for (int b = 0; b < B; ++b) {
-    if (!stream_active(ws, b)) continue;
-    const float xt = tabXe32[(size_t)stream_window(ws, b, T)[T - 1] * D + i];
-    sg = fmaf(xt, dgg[(size_t)b * c + q], sg);
-    sv = fmaf(xt, dgv[(size_t)b * c + q], sv);
+// dW_g[i][q] = sum_b xt[b][i] d gg[b][q] (same for W_v). Stage 1: one workgroup per 16 streams, one thread per output
+// (outputs [2][D][c] in blob order), streams in increasing order; stage 2 is reduce_rows_kernel. (16 streams per workgroup)
+__global__ __launch_bounds__(256) void slot_weight_partial_kernel(WinSrc ws, int B, int T, int D, int c, const float *tabXe32, const float *dgg,
+                                                                  const float *dgv, float *part) {
+  const int nout = 2 * D * c, b0 = blockIdx.x * 16;
+  for (int t = threadIdx.x; t < nout; t += 256) {
+    const int which = t / (D * c), r = t - which * D * c, i = r / c, q = r - i * c;
+    const float *dsrc = which ? dgv : dgg;
+    float s = 0.0f;
+    for (int k = 0; k < 16 && b0 + k < B; ++k) {
+      const int b = b0 + k;
+      if (!stream_active(ws, b)) continue;
+      s = fmaf(tabXe32[(size_t)stream_window(ws, b, T)[T - 1] * D + i], dsrc[(size_t)b * c + q], s);
+    }
+    part[(size_t)blockIdx.x * nout + t] = s;
   }
-  dWg[t] = sg;
-  dWv[t] = sv;
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -485,132 +542,123 @@ __global__ void slot_weight_grad_kernel(WinSrc ws, int B, int T, int D, int c, c
 // ---------------------------------------------------------------------------------------------------
 template <typename AT>
 __global__ __launch_bounds__(256) void conv_grad_partial_kernel(ConvGradArgs a) {
-  const int tid = threadIdx.x;
-  const int rows = a.taps * a.D;                  // (tap, i) pairs
-  const int o = tid % a.D, grp = tid / a.D, ngrp = 256 / a.D;
+  // one workgroup = 128 consecutive tokens = whole streams (T divides 128); both tiles staged in LDS as fp32
+  __shared__ float xs[128 * 32], ds[128 * 32];
+  const int tid = threadIdx.x, D = a.D;
+  const long long tokens = (long long)a.B * a.T, t0 = (long long)blockIdx.x * 128;
+  const AT *XL = static_cast<const AT *>(a.XL), *dcv = static_cast<const AT *>(a.dcv);
+  for (int e = tid; e < 128 * D; e += 256) {
+    const long long t = t0 + e / D;
+    const bool ok = t < tokens;
+    xs[e] = ok ? (float)XL[(size_t)t0 * D + e] : 0.0f;
+    ds[e] = ok ? (float)dcv[(size_t)t0 * D + e] : 0.0f;
+  }
+  __syncthreads();
+  const int rows = a.taps * D;                    // (tap, i) pairs
+  const int o = tid % D, grp = tid / D, ngrp = 256 / D;
   const int per = (rows + ngrp - 1) / ngrp;       // (tap, i) rows owned by this thread's group (<= 16)
   float acc[16], bsum = 0.0f;
+  int xoff[16], back[16];  // per owned (tap, i): offset of its input inside the tile relative to the token, and the tap's reach
 #pragma unroll
-  for (int q = 0; q < 16; ++q) acc[q] = 0.0f;
-  const long long tokens = (long long)a.B * a.T;
-  const long long per_blk = (tokens + gridDim.x - 1) / gridDim.x;
-  const long long t0 = (long long)blockIdx.x * per_blk, t1 = (t0 + per_blk < tokens) ? t0 + per_blk : tokens;
-  const AT *XL = static_cast<const AT *>(a.XL), *dcv = static_cast<const AT *>(a.dcv);
-  for (long long t = t0; t < t1; ++t) {
-    const int b = (int)(t / a.T), j = (int)(t - (long long)b * a.T);
-    const float d = (float)dcv[(size_t)t * a.D + o];
-    if (grp == 0) bsum += d;
-#pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      const int r = grp * per + q;
-      if (q < per && r < rows) {
-        const int tap = r / a.D, i = r - tap * a.D, tok = j - (a.taps - 1) + tap;
-        if (tok >= 0) acc[q] = fmaf((float)XL[((size_t)b * a.T + tok) * a.D + i], d, acc[q]);
-      }
-    }
+  for (int q = 0; q < 16; ++q) {
+    acc[q] = 0.0f;
+    const int r = grp * per + q;
+    const bool ok = q < per && r < rows;
+    const int tap = ok ? r / D : 0, i = ok ? r - tap * D : 0;
+    back[q] = ok ? (a.taps - 1) - tap : 1 << 20;  // an unreachable reach switches the slot off
+    xoff[q] = i - back[q] * D;
   }
-  float *part = a.part + (size_t)blockIdx.x * (rows + 1) * a.D;
+  const int Tm = a.T - 1;  // T is a power of two
+  for (int tl = 0; tl < 128; ++tl) {
+    const int j = tl & Tm;
+    const float d = ds[tl * D + o];
+    bsum += d;
+#pragma unroll
+    for (int q = 0; q < 16; ++q)
+      if (j >= back[q]) acc[q] = fmaf(xs[tl * D + xoff[q]], d, acc[q]);
+  }
+  float *part = a.part + (size_t)blockIdx.x * (rows + 1) * D;
 #pragma unroll
   for (int q = 0; q < 16; ++q) {
     const int r = grp * per + q;
-    if (q < per && r < rows) part[(size_t)r * a.D + o] = acc[q];
+    if (q < per && r < rows) part[(size_t)r * D + o] = acc[q];
   }
-  if (grp == 0) part[(size_t)rows * a.D + o] = bsum;
-}
-__global__ void conv_grad_reduce_kernel(int nblk, int rows, int D, const float *part, float *dW, float *db) {
-  const int t = blockIdx.x * blockDim.x + threadIdx.x;
-  if (t >= (rows + 1) * D) return;
-  float s = 0.0f;
-  for (int k = 0; k < nblk; ++k) s += part[(size_t)k * (rows + 1) * D + t];
-  if (t < rows * D) dW[t] = s;
-  else db[t - rows * D] = s;
+  if (grp == 0) part[(size_t)rows * D + o] = bsum;
 }
 
 // ---------------------------------------------------------------------------------------------------
-// the two per-token LayerNorms backward -> d(embedding row) per token, plus their gain / shift gradients
-// de[t][:] (fp32) for token t = (b, j); per-workgroup partial sums of d gamma / d beta, reduced afterwards.
-// One thread per token; a wavefront handles 64 tokens.
+// the two per-token LayerNorms and the embedding, backward. For a fixed symbol s the LayerNorm backward is a LINEAR map of
+// the incoming gradient (mean, 1/sigma and x-hat depend on E[s] only), so tokens are first summed per symbol:
+//   SX[s] = sum over tokens with symbol s of dX (router + global residual + newest-slot paths),  SL[s] likewise of dX_l,
+// and everything else happens on the 256 x D tables:
+//   dE[s] = rstd_s * ( P_s(gamma_e * SX[s]) + P_s(gamma_l * SL[s]) ),  P_s(v) = v - mean(v) - xhat_s * mean(v * xhat_s)
+//   d gamma_e = sum_s xhat_s * SX[s], d beta_e = sum_s SX[s]  (same with SL for the pair of Eq. 4's LayerNorm).
 // ---------------------------------------------------------------------------------------------------
+// Stage 1 of the per-symbol sums: blockIdx.y = 0 builds SX, 1 builds SL. Each workgroup owns a contiguous token range and a
+// private 256 x D table in LDS. Tokens are staged 128 at a time; 256 / D lane groups walk them in token order, group g
+// adding only the symbols with s % groups == g (disjoint table rows, so every row sees its tokens in order).
 template <typename AT>
-__global__ __launch_bounds__(256) void bwd_token_kernel(BwdTokenArgs a) {
-  __shared__ float red[4];
-  const long long t = (long long)blockIdx.x * 256 + threadIdx.x, tokens = (long long)a.B * a.T;
-  const int D = a.D;
-  float pge = 0.0f, pbe = 0.0f, pgl = 0.0f, pbl = 0.0f;  // this thread's contribution for the column handled below
-  // pass 1: de rows
-  if (t < tokens) {
-    const int b = (int)(t / a.T), j = (int)(t - (long long)b * a.T);
-    const bool act = stream_active(a.ws, b);
-    const int s = act ? stream_window(a.ws, b, a.T)[j] : 0;
-    const float *xh = a.tabXhat + (size_t)s * D;
-    const float rstd = a.tabRstd[s];
-    const AT *dX1 = static_cast<const AT *>(a.dX1) + (size_t)t * D, *dX2 = static_cast<const AT *>(a.dX2) + (size_t)t * D;
-    const AT *dxl = static_cast<const AT *>(a.dxl) + (size_t)t * D;
-    float m1e = 0.0f, m2e = 0.0f, m1l = 0.0f, m2l = 0.0f;
-    for (int i = 0; i < D; ++i) {
-      float de = (float)dX1[i] + (float)dX2[i];
-      if (j == a.T - 1) de += a.dxt[(size_t)b * D + i];
-      const float dhe = de * a.gamma_e[i], dhl = (float)dxl[i] * a.gamma_l[i];
-      m1e += dhe; m2e += dhe * xh[i];
-      m1l += dhl; m2l += dhl * xh[i];
-    }
-    m1e /= (float)D; m2e /= (float)D; m1l /= (float)D; m2l /= (float)D;
-    float *out = a.de + (size_t)t * D;
-    for (int i = 0; i < D; ++i) {
-      float de = (float)dX1[i] + (float)dX2[i];
-      if (j == a.T - 1) de += a.dxt[(size_t)b * D + i];
-      const float dhe = de * a.gamma_e[i], dhl = (float)dxl[i] * a.gamma_l[i];
-      out[i] = act ? rstd * ((dhe - m1e - xh[i] * m2e) + (dhl - m1l - xh[i] * m2l)) : 0.0f;
-    }
-  }
-  // pass 2: column sums over this workgroup's 256 tokens for d gamma_e, d beta_e, d gamma_l, d beta_l
-  for (int i = 0; i < D; ++i) {
-    pge = pbe = pgl = pbl = 0.0f;
-    if (t < tokens) {
-      const int b = (int)(t / a.T), j = (int)(t - (long long)b * a.T);
-      if (stream_active(a.ws, b)) {
-        const int s = stream_window(a.ws, b, a.T)[j];
-        const float xh = a.tabXhat[(size_t)s * D + i];
-        float de = (float)static_cast<const AT *>(a.dX1)[(size_t)t * D + i] + (float)static_cast<const AT *>(a.dX2)[(size_t)t * D + i];
-        if (j == a.T - 1) de += a.dxt[(size_t)b * D + i];
-        const float dl = (float)static_cast<const AT *>(a.dxl)[(size_t)t * D + i];
-        pge = de * xh; pbe = de; pgl = dl * xh; pbl = dl;
+__global__ __launch_bounds__(256) void symbol_sums_partial_kernel(BwdTokenArgs a, long long per_block) {
+  __shared__ float tab[256 * 32];
+  __shared__ float tile[128 * 32];
+  __shared__ int sym[128];
+  const int tid = threadIdx.x, D = a.D, which = blockIdx.y;
+  const int lane_i = tid % D, grp = tid / D, ngrp = 256 / D;
+  const long long tokens = (long long)a.B * a.T, t0 = (long long)blockIdx.x * per_block;
+  long long t1 = t0 + per_block;
+  if (t1 > tokens) t1 = tokens;
+  for (int e = tid; e < 256 * D; e += 256) tab[e] = 0.0f;
+  for (long long c0 = t0; c0 < t1; c0 += 128) {
+    const int cnt = (int)((t1 - c0 < 128) ? (t1 - c0) : 128);
+    __syncthreads();
+    for (int e = tid; e < cnt * D; e += 256) {
+      const long long t = c0 + e / D;
+      const size_t g = (size_t)c0 * D + e;
+      float v;
+      if (which == 0) {
+        v = (float)static_cast<const AT *>(a.dX1)[g] + (float)static_cast<const AT *>(a.dX2)[g];
+        const int b = (int)(t / a.T);
+        if ((int)(t - (long long)b * a.T) == a.T - 1) v += a.dxt[(size_t)b * D + e % D];
+      } else {
+        v = (float)static_cast<const AT *>(a.dxl)[g];
       }
+      tile[e] = v;
     }
-    const float s0 = block_sum(pge, red), s1 = block_sum(pbe, red), s2 = block_sum(pgl, red), s3 = block_sum(pbl, red);
-    if (threadIdx.x == 0) {
-      float *p = a.part + ((size_t)blockIdx.x * 4) * D;
-      p[i] = s0; p[D + i] = s1; p[2 * D + i] = s2; p[3 * D + i] = s3;
+    if (tid < cnt) {
+      const long long t = c0 + tid;
+      const int b = (int)(t / a.T), j = (int)(t - (long long)b * a.T);
+      sym[tid] = stream_active(a.ws, b) ? stream_window(a.ws, b, a.T)[j] : -1;  // inactive streams contribute nothing
+    }
+    __syncthreads();
+    for (int k = 0; k < cnt; ++k) {
+      const int s = sym[k];
+      if (s >= 0 && (s % ngrp) == grp) tab[s * D + lane_i] += tile[k * D + lane_i];
     }
   }
-}
-__global__ void token_param_reduce_kernel(int nblk, int D, const float *part, float *dge, float *dbe, float *dgl, float *dbl) {
-  const int t = blockIdx.x * blockDim.x + threadIdx.x;
-  if (t >= 4 * D) return;
-  float s = 0.0f;
-  for (int k = 0; k < nblk; ++k) s += part[(size_t)k * 4 * D + t];
-  float *outs[4] = {dge, dbe, dgl, dbl};
-  outs[t / D][t % D] = s;
+  __syncthreads();
+  float *out = a.part + ((size_t)blockIdx.x * 2 + which) * 256 * D;
+  for (int e = tid; e < 256 * D; e += 256) out[e] = tab[e];
 }
 
-// dE[s][:] = sum of de over the tokens whose symbol is s. One workgroup per symbol; eight token phases of D lanes,
-// each phase walking its tokens in increasing order; phases combined in index order.
-__global__ __launch_bounds__(256) void embed_grad_kernel(WinSrc ws, int B, int T, int D, const float *de, float *dE) {
-  __shared__ float ps[256];
-  const int s = blockIdx.x, i = threadIdx.x % D, ph = threadIdx.x / D, nph = 256 / D;
-  float acc = 0.0f;
-  for (int b = 0; b < B; ++b) {
-    if (!stream_active(ws, b)) continue;
-    const uint8_t *win = stream_window(ws, b, T);
-    for (int j = ph; j < T; j += nph)
-      if (win[j] == s) acc += de[((size_t)b * T + j) * D + i];
-  }
-  ps[threadIdx.x] = acc;
+// Finish on the tables: one workgroup per symbol, lane = channel. sums: [2][256][D] (SX then SL).
+// Writes dE[s] and this symbol's contribution to (d gamma_e, d beta_e, d gamma_l, d beta_l) as contrib[s][4][D].
+__global__ __launch_bounds__(64) void embed_finish_kernel(int D, const float *sums, const float *tabXhat, const float *tabRstd,
+                                                          const float *gamma_e, const float *gamma_l, float *dE, float *contrib) {
+  __shared__ float red[4][64];
+  const int s = blockIdx.x, i = threadIdx.x;
+  const bool on = i < D;
+  const float sx = on ? sums[(size_t)s * D + i] : 0.0f, sl = on ? sums[(size_t)(256 + s) * D + i] : 0.0f;
+  const float xh = on ? tabXhat[(size_t)s * D + i] : 0.0f;
+  const float he = on ? sx * gamma_e[i] : 0.0f, hl = on ? sl * gamma_l[i] : 0.0f;
+  red[0][i] = he; red[1][i] = he * xh; red[2][i] = hl; red[3][i] = hl * xh;
   __syncthreads();
-  if (ph == 0) {
-    float tot = 0.0f;
-    for (int k = 0; k < nph; ++k) tot += ps[k * D + i];
-    dE[(size_t)s * D + i] = tot;
+  float m[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  for (int k = 0; k < D; ++k) { m[0] += red[0][k]; m[1] += red[1][k]; m[2] += red[2][k]; m[3] += red[3][k]; }
+  if (on) {
+    const float inv = 1.0f / (float)D;
+    dE[(size_t)s * D + i] = tabRstd[s] * ((he - m[0] * inv - xh * m[1] * inv) + (hl - m[2] * inv - xh * m[3] * inv));
+    float *c = contrib + (size_t)s * 4 * D;
+    c[i] = xh * sx; c[D + i] = sx; c[2 * D + i] = xh * sl; c[3 * D + i] = sl;
   }
 }
 
@@ -656,68 +704,87 @@ hipError_t fade_transpose(const TransposeArgs &a, int N, bool bf16, hipStream_t 
   if (N % 64) return hipErrorInvalidValue;
   DISPATCH_AT(bf16, transpose_kernel, dim3((a.B + 63) / 64, N / 64), dim3(256), s, a);
 }
+hipError_t fade_transpose_batch(const TransposeBatch &tb, bool bf16, hipStream_t s) {
+  if (tb.count <= 0 || tb.count > 8) return hipErrorInvalidValue;
+  int maxB = 0, maxN = 0;
+  for (int i = 0; i < tb.count; ++i) {
+    if (tb.N[i] % 64) return hipErrorInvalidValue;
+    if (tb.t[i].B > maxB) maxB = tb.t[i].B;
+    if (tb.N[i] > maxN) maxN = tb.N[i];
+  }
+  const dim3 grid((maxB + 63) / 64, maxN / 64, tb.count);
+  if (bf16) hipLaunchKernelGGL(transpose_batch_kernel<bf16_t>, grid, dim3(256), 0, s, tb);
+  else hipLaunchKernelGGL(transpose_batch_kernel<float>, grid, dim3(256), 0, s, tb);
+  return hipGetLastError();
+}
 hipError_t fade_embed_t(const WinSrc &ws, int B, int Bp, int T, int D, const void *tab, void *XT, bool bf16, hipStream_t s) {
   const size_t n = (size_t)T * D * (Bp / 8);
   if (bf16) hipLaunchKernelGGL(embed_t_kernel<bf16_t>, dim3(nblk(n, 256)), dim3(256), 0, s, ws, B, Bp, T, D, static_cast<const bf16_t *>(tab), static_cast<bf16_t *>(XT));
   else hipLaunchKernelGGL(embed_t_kernel<float>, dim3(nblk(n, 256)), dim3(256), 0, s, ws, B, Bp, T, D, static_cast<const float *>(tab), static_cast<float *>(XT));
   return hipGetLastError();
 }
-hipError_t fade_bwd_out(const BwdOutArgs &a, int B, bool bf16, hipStream_t s) { DISPATCH_AT(bf16, bwd_out_kernel, dim3(B), dim3(256), s, a); }
+hipError_t fade_bwd_out(const BwdOutArgs &a, bool bf16, hipStream_t s) { DISPATCH_AT(bf16, bwd_out_kernel, dim3((a.B + kRowsPerBlock - 1) / kRowsPerBlock), dim3(256), s, a); }
 hipError_t fade_bwd_geglu(int B, int De, const void *dHexp, const void *eg, const void *ev, void *dE, bool bf16, hipStream_t s) {
   const size_t n = (size_t)B * (De / 8);
   if (bf16) hipLaunchKernelGGL(bwd_geglu_kernel<bf16_t>, dim3(nblk(n, 256)), dim3(256), 0, s, B, De, static_cast<const bf16_t *>(dHexp), static_cast<const bf16_t *>(eg), static_cast<const bf16_t *>(ev), static_cast<bf16_t *>(dE));
   else hipLaunchKernelGGL(bwd_geglu_kernel<float>, dim3(nblk(n, 256)), dim3(256), 0, s, B, De, static_cast<const float *>(dHexp), static_cast<const float *>(eg), static_cast<const float *>(ev), static_cast<float *>(dE));
   return hipGetLastError();
 }
-hipError_t fade_bwd_gate(const BwdGateArgs &a, int B, bool bf16, hipStream_t s) { DISPATCH_AT(bf16, bwd_gate_kernel, dim3(B), dim3(256), s, a); }
-hipError_t fade_bwd_mix(const BwdMixArgs &a, int B, bool bf16, hipStream_t s) { DISPATCH_AT(bf16, bwd_mix_kernel, dim3(B), dim3(256), s, a); }
-hipError_t fade_ln_param_grad(int B, int width, int stats_n, const void *dn, const void *x, const float *stats, float *dgamma, float *dbeta,
-                              bool bf16, hipStream_t s) {
-  if (width % 64) return hipErrorInvalidValue;
-  if (bf16) hipLaunchKernelGGL(ln_param_grad_kernel<bf16_t>, dim3(width / 64), dim3(256), 0, s, B, width, stats_n, static_cast<const bf16_t *>(dn), static_cast<const bf16_t *>(x), stats, dgamma, dbeta);
-  else hipLaunchKernelGGL(ln_param_grad_kernel<float>, dim3(width / 64), dim3(256), 0, s, B, width, stats_n, static_cast<const float *>(dn), static_cast<const float *>(x), stats, dgamma, dbeta);
+hipError_t fade_bwd_gate(const BwdGateArgs &a, bool bf16, hipStream_t s) { DISPATCH_AT(bf16, bwd_gate_kernel, dim3((a.B + kRowsPerBlock - 1) / kRowsPerBlock), dim3(256), s, a); }
+hipError_t fade_bwd_mix(const BwdMixArgs &a, bool bf16, hipStream_t s) { DISPATCH_AT(bf16, bwd_mix_kernel, dim3((a.B + kRowsPerBlock - 1) / kRowsPerBlock), dim3(256), s, a); }
+int fade_rows_per_block() { return kRowsPerBlock; }
+hipError_t fade_reduce_rows(int P, int N, const float *part, float *out, hipStream_t s) {
+  hipLaunchKernelGGL(reduce_rows_kernel, dim3(nblk((size_t)N, 32)), dim3(256), 0, s, P, N, part, out);
   return hipGetLastError();
 }
-hipError_t fade_colsum(int B, int N, const void *src, float *out, bool bf16, hipStream_t s) {
-  if (N % 64) return hipErrorInvalidValue;
-  if (bf16) hipLaunchKernelGGL(colsum_kernel<bf16_t>, dim3(N / 64), dim3(256), 0, s, B, N, static_cast<const bf16_t *>(src), out);
-  else hipLaunchKernelGGL(colsum_kernel<float>, dim3(N / 64), dim3(256), 0, s, B, N, static_cast<const float *>(src), out);
-  return hipGetLastError();
+// out[n] = sum_b src[b][n]; part must hold ceil(B / 32) * N floats
+hipError_t fade_colsum(int B, int N, const void *src, float *part, float *out, bool bf16, hipStream_t s) {
+  const int P = (B + 31) / 32;
+  const dim3 grid(P, (N + 255) / 256);
+  if (bf16) hipLaunchKernelGGL(colsum_partial_kernel<bf16_t>, grid, dim3(256), 0, s, B, N, static_cast<const bf16_t *>(src), part);
+  else hipLaunchKernelGGL(colsum_partial_kernel<float>, grid, dim3(256), 0, s, B, N, static_cast<const float *>(src), part);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return fade_reduce_rows(P, N, part, out, s);
 }
 hipError_t fade_scalar_sums(int B, const float *r0, const float *r1, const float *r2, float *o0, float *o1, float *o2, hipStream_t s) {
   hipLaunchKernelGGL(scalar_sums_kernel, dim3(1), dim3(256), 0, s, B, r0, r1, r2, o0, o1, o2);
   return hipGetLastError();
 }
-hipError_t fade_bwd_cci(const BwdCciArgs &a, bool bf16, hipStream_t s) { DISPATCH_AT(bf16, bwd_cci_kernel, dim3((a.B + 3) / 4), dim3(256), s, a); }
+hipError_t fade_bwd_cci(const BwdCciArgs &a, bool bf16, hipStream_t s) { DISPATCH_AT(bf16, bwd_cci_kernel, dim3(a.B), dim3(256), s, a); }
 hipError_t fade_bwd_slot(const BwdSlotArgs &a, int B, bool bf16, hipStream_t s) { DISPATCH_AT(bf16, bwd_slot_kernel, dim3(B), dim3(256), s, a); }
+// part must hold ceil(B / 16) * 2 * D * c floats; dWgv points at W_g's gradient (W_v's follows it in the blob)
 hipError_t fade_slot_weight_grad(const WinSrc &ws, int B, int T, int D, int c, const float *tabXe32, const float *dgg, const float *dgv,
-                                 float *dWg, float *dWv, hipStream_t s) {
-  hipLaunchKernelGGL(slot_weight_grad_kernel, dim3(nblk((size_t)D * c, 64)), dim3(64), 0, s, ws, B, T, D, c, tabXe32, dgg, dgv, dWg, dWv);
-  return hipGetLastError();
-}
-hipError_t fade_conv_grad(const ConvGradArgs &a, int nblocks, float *dW, float *db, bool bf16, hipStream_t s) {
-  if (256 % a.D || (a.taps * a.D + 256 / a.D - 1) / (256 / a.D) > 16) return hipErrorInvalidValue;
-  if (bf16) hipLaunchKernelGGL(conv_grad_partial_kernel<bf16_t>, dim3(nblocks), dim3(256), 0, s, a);
-  else hipLaunchKernelGGL(conv_grad_partial_kernel<float>, dim3(nblocks), dim3(256), 0, s, a);
+                                 float *part, float *dWgv, hipStream_t s) {
+  const int P = (B + 15) / 16;
+  hipLaunchKernelGGL(slot_weight_partial_kernel, dim3(P), dim3(256), 0, s, ws, B, T, D, c, tabXe32, dgg, dgv, part);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const int rows = a.taps * a.D;
-  hipLaunchKernelGGL(conv_grad_reduce_kernel, dim3(nblk((size_t)(rows + 1) * a.D, 256)), dim3(256), 0, s, nblocks, rows, a.D, a.part, dW, db);
-  return hipGetLastError();
+  return fade_reduce_rows(P, 2 * D * c, part, dWgv, s);
 }
-hipError_t fade_bwd_token(const BwdTokenArgs &a, float *dge, float *dbe, float *dgl, float *dbl, bool bf16, hipStream_t s) {
-  const int blocks = (int)(((long long)a.B * a.T + 255) / 256);
-  if (bf16) hipLaunchKernelGGL(bwd_token_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, a);
-  else hipLaunchKernelGGL(bwd_token_kernel<float>, dim3(blocks), dim3(256), 0, s, a);
+// a.part must hold ceil(B * T / 128) * (taps * D + 1) * D floats; dWb points at W_conv's gradient (b_conv's follows it)
+hipError_t fade_conv_grad(const ConvGradArgs &a, float *dWb, bool bf16, hipStream_t s) {
+  if (256 % a.D || a.D > 32 || 128 % a.T || (a.taps * a.D + 256 / a.D - 1) / (256 / a.D) > 16) return hipErrorInvalidValue;
+  const int P = (int)(((long long)a.B * a.T + 127) / 128);
+  if (bf16) hipLaunchKernelGGL(conv_grad_partial_kernel<bf16_t>, dim3(P), dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(conv_grad_partial_kernel<float>, dim3(P), dim3(256), 0, s, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(token_param_reduce_kernel, dim3(nblk((size_t)4 * a.D, 64)), dim3(64), 0, s, blocks, a.D, a.part, dge, dbe, dgl, dbl);
-  return hipGetLastError();
+  return fade_reduce_rows(P, (a.taps * a.D + 1) * a.D, a.part, dWb, s);
 }
-hipError_t fade_embed_grad(const WinSrc &ws, int B, int T, int D, const float *de, float *dE, hipStream_t s) {
-  if (256 % D) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(embed_grad_kernel, dim3(256), dim3(256), 0, s, ws, B, T, D, de, dE);
-  return hipGetLastError();
+// a.part: nblocks * 2 * 256 * D floats; sums: 2 * 256 * D; contrib: 256 * 4 * D.
+// dE: gradient of the embedding; dparams: gradient of gamma_e (beta_e, gamma_l, beta_l follow it in the blob).
+hipError_t fade_bwd_embed(const BwdTokenArgs &a, int nblocks, float *sums, float *contrib, float *dE, float *dparams, bool bf16, hipStream_t s) {
+  if (256 % a.D || a.D > 32) return hipErrorInvalidValue;
+  const long long tokens = (long long)a.B * a.T, per = (tokens + nblocks - 1) / nblocks;
+  if (bf16) hipLaunchKernelGGL(symbol_sums_partial_kernel<bf16_t>, dim3(nblocks, 2), dim3(256), 0, s, a, per);
+  else hipLaunchKernelGGL(symbol_sums_partial_kernel<float>, dim3(nblocks, 2), dim3(256), 0, s, a, per);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if ((e = fade_reduce_rows(nblocks, 2 * 256 * a.D, a.part, sums, s)) != hipSuccess) return e;
+  hipLaunchKernelGGL(embed_finish_kernel, dim3(256), dim3(64), 0, s, a.D, sums, a.tabXhat, a.tabRstd, a.gamma_e, a.gamma_l, dE, contrib);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  return fade_reduce_rows(256, 4 * a.D, contrib, dparams, s);
 }
 hipError_t fade_adam(size_t n, const float *grad, float *master, float *m, float *v, const UpdateState *u, float lr, float beta1, float beta2,
                      float eps, hipStream_t s) {

@@ -80,10 +80,25 @@ hipError_t fade_preshuffle(const float *W0, const float *W1, int k_real, int K, 
                            hipStream_t s);
 // fragments of the TRANSPOSE of the (possibly interleaved) matrix [K][N]: the result multiplies from the right as [N][K]
 hipError_t fade_preshuffle_t(const float *W0, const float *W1, int K, int N, int interleave, void *out, hipStream_t s);
-hipError_t fade_tables_bwd(const float *E, int D, float *tabXhat, float *tabRstd, hipStream_t s);
+// weight preparation in one launch: every descriptor is an element-wise map master -> compute copy
+enum { PREP_FRAG = 0, PREP_FRAG_T = 1, PREP_ROUND = 2, PREP_FRAG_CONVT = 3 };
+struct PrepDesc {
+  int kind;
+  const float *W0, *W1;   // source(s) in the fp32 blob
+  int k_real, K, N;       // PREP_FRAG: virtual [K][N] with rows >= k_real zero; PREP_FRAG_T: source [K][N], result for [N][K]; PREP_ROUND: N values
+  int interleave;         // gate | value interleave per 128 columns over the pair (W0, W1)
+  const float *rowscale;  // PREP_FRAG: folded LayerNorm gain or NULL
+  void *out;
+  int taps, D;            // PREP_FRAG_CONVT: W0 = W_conv [taps][D][D]; virtual [K][D] with row (r*D+o), column i = W_conv[r][i][o]
+};
+struct PrepBatch {
+  PrepDesc d[20];
+  int count;
+};
+hipError_t fade_prep_batch(const PrepBatch &pb, hipStream_t s);
 hipError_t fade_convt_build(const float *Wconv, int taps, int D, int Kc, float *V, hipStream_t s);
 hipError_t fade_fold_vectors(const float *W0, const float *W1, int K, int N, int interleave, const float *gamma, const float *beta,
-                             float *s_out, float *t_out, hipStream_t s);
+                             float *part, float *st_out, hipStream_t s);
 hipError_t fade_cci(const CciArgs &a, hipStream_t s);
 hipError_t fade_geglu(const GegluArgs &a, hipStream_t s);
 hipError_t fade_hout(const HoutArgs &a, bool bf16, hipStream_t s);
@@ -91,7 +106,7 @@ hipError_t fade_virtual_copy(const float *W0, const float *W1, int k_real, int K
 hipError_t fade_convert(const float *src, void *dst, size_t n, bool bf16, hipStream_t s);
 hipError_t fade_round_bf16(const float *src, float *dst, size_t n, hipStream_t s);
 hipError_t fade_tables(const float *E, const float *ge, const float *be, const float *gl, const float *bl, int D, void *tabXe,
-                       void *tabXl, float *tabXe32, bool bf16, hipStream_t s);
+                       void *tabXl, float *tabXe32, float *tabXhat, float *tabRstd, bool bf16, hipStream_t s);
 hipError_t fade_embed_cache(const EmbedArgs &a, int B, bool bf16, hipStream_t s);
 hipError_t fade_bmm(const float *y, const void *WU, void *z, int B, bool bf16, hipStream_t s);
 hipError_t fade_softmax_quant_code(const SqcArgs &a, int mode, hipStream_t s);
@@ -119,22 +134,31 @@ struct TransposeArgs {
   const float *stats; int stats_n, width;  // optional LayerNorm on the way (stats == NULL: plain copy)
   const float *gamma, *beta;
 };
+// several transposes in one launch (blockIdx.z picks one)
+struct TransposeBatch {
+  TransposeArgs t[8];
+  int N[8];
+  int count;
+};
 struct BwdOutArgs {
-  int Dh, stats_n;
+  int B, Dh, stats_n;
+  float *ln_part;  // [blocks][2][Dh] partial sums of d gamma, d beta over this workgroup's rows
   const void *dH, *V, *Hc;
   const float *stats, *gamma, *beta, *lam;
   void *dnv, *dV, *dHc;
   float *row_dlam;
 };
 struct BwdGateArgs {
-  int Dh, stats_n;
+  int B, Dh, stats_n;
+  float *ln_part;
   const void *du, *Hc, *dHc, *sg, *Ha, *Hmix;
   const float *stats, *gamma, *lam;
   void *dHa, *dac, *dHmix;
   float *row_dlam;
 };
 struct BwdMixArgs {
-  int Dh, stats_n;
+  int B, Dh, stats_n;
+  float *ln_part;
   const void *dnc, *Hmix, *dHmix1, *dHmix2, *alpha, *Hg, *Hl, *hm, *cv, *X;
   const float *stats, *gamma, *lam;
   void *dar, *dhm, *dcv, *dX;
@@ -162,7 +186,7 @@ struct BwdSlotArgs {
 struct ConvGradArgs {
   int B, T, D, taps;
   const void *XL, *dcv;   // [B*T][D]
-  float *part;            // [blocks][taps*D + 1][D]
+  float *part;            // [ceil(B*T/128)][taps*D + 1][D]
 };
 struct BwdTokenArgs {
   WinSrc ws;
@@ -171,29 +195,28 @@ struct BwdTokenArgs {
   const float *dxt;               // [B][D], added at the newest token
   const float *tabXhat, *tabRstd; // [256][D], [256]
   const float *gamma_e, *gamma_l;
-  float *de;                      // [B*T][D]
-  float *part;                    // [blocks][4][D]
+  float *part;                    // [blocks][2][256][D] per-symbol partial sums
 };
 
 hipError_t fade_update_prep(const WinSrc &ws, int B, UpdateState *u, float beta1, float beta2, hipStream_t s);
 hipError_t fade_dlogits(const WinSrc &ws, const uint8_t *targets, long long tstride, int B, const float *probs, const UpdateState *u,
                         void *dl, bool bf16, hipStream_t s);
 hipError_t fade_transpose(const TransposeArgs &a, int N, bool bf16, hipStream_t s);
+hipError_t fade_transpose_batch(const TransposeBatch &tb, bool bf16, hipStream_t s);
 hipError_t fade_embed_t(const WinSrc &ws, int B, int Bp, int T, int D, const void *tab, void *XT, bool bf16, hipStream_t s);
-hipError_t fade_bwd_out(const BwdOutArgs &a, int B, bool bf16, hipStream_t s);
+hipError_t fade_bwd_out(const BwdOutArgs &a, bool bf16, hipStream_t s);
 hipError_t fade_bwd_geglu(int B, int De, const void *dHexp, const void *eg, const void *ev, void *dE, bool bf16, hipStream_t s);
-hipError_t fade_bwd_gate(const BwdGateArgs &a, int B, bool bf16, hipStream_t s);
-hipError_t fade_bwd_mix(const BwdMixArgs &a, int B, bool bf16, hipStream_t s);
-hipError_t fade_ln_param_grad(int B, int width, int stats_n, const void *dn, const void *x, const float *stats, float *dgamma, float *dbeta,
-                              bool bf16, hipStream_t s);
-hipError_t fade_colsum(int B, int N, const void *src, float *out, bool bf16, hipStream_t s);
+hipError_t fade_bwd_gate(const BwdGateArgs &a, bool bf16, hipStream_t s);
+hipError_t fade_bwd_mix(const BwdMixArgs &a, bool bf16, hipStream_t s);
+int fade_rows_per_block();
+hipError_t fade_reduce_rows(int P, int N, const float *part, float *out, hipStream_t s);
+hipError_t fade_colsum(int B, int N, const void *src, float *part, float *out, bool bf16, hipStream_t s);
 hipError_t fade_scalar_sums(int B, const float *r0, const float *r1, const float *r2, float *o0, float *o1, float *o2, hipStream_t s);
 hipError_t fade_bwd_cci(const BwdCciArgs &a, bool bf16, hipStream_t s);
 hipError_t fade_bwd_slot(const BwdSlotArgs &a, int B, bool bf16, hipStream_t s);
 hipError_t fade_slot_weight_grad(const WinSrc &ws, int B, int T, int D, int c, const float *tabXe32, const float *dgg, const float *dgv,
-                                 float *dWg, float *dWv, hipStream_t s);
-hipError_t fade_conv_grad(const ConvGradArgs &a, int nblocks, float *dW, float *db, bool bf16, hipStream_t s);
-hipError_t fade_bwd_token(const BwdTokenArgs &a, float *dge, float *dbe, float *dgl, float *dbl, bool bf16, hipStream_t s);
-hipError_t fade_embed_grad(const WinSrc &ws, int B, int T, int D, const float *de, float *dE, hipStream_t s);
+                                 float *part, float *dWgv, hipStream_t s);
+hipError_t fade_conv_grad(const ConvGradArgs &a, float *dWb, bool bf16, hipStream_t s);
+hipError_t fade_bwd_embed(const BwdTokenArgs &a, int nblocks, float *sums, float *contrib, float *dE, float *dparams, bool bf16, hipStream_t s);
 hipError_t fade_adam(size_t n, const float *grad, float *master, float *m, float *v, const UpdateState *u, float lr, float beta1, float beta2,
                      float eps, hipStream_t s);

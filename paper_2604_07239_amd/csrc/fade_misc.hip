@@ -81,27 +81,35 @@ __global__ void round_bf16_kernel(const float *src, float *dst, size_t n) {
   if (t < n) dst[t] = (float)(bf16_t)src[t];
 }
 
-// Per-symbol tables: LN_D(E[s]) with the two affine pairs (X of the Design paragraph; LN of Eq. 4).
+// Per-symbol tables: LN_D(E[s]) with the two affine pairs (X of the Design paragraph; LN of Eq. 4), and, for the
+// update, the normalised row x-hat and 1/sigma. One workgroup per symbol, lane = channel (D <= 256).
 template <typename AT>
-__global__ void tables_kernel(const float *E, const float *ge, const float *be, const float *gl, const float *bl, int D,
-                              AT *tabXe, AT *tabXl, float *tabXe32) {
-  const int s = blockIdx.x * blockDim.x + threadIdx.x;
-  if (s >= 256) return;
-  const float *e = E + (size_t)s * D;
+__global__ __launch_bounds__(256) void tables_kernel(const float *E, const float *ge, const float *be, const float *gl, const float *bl, int D,
+                                                     AT *tabXe, AT *tabXl, float *tabXe32, float *tabXhat, float *tabRstd) {
+  __shared__ float red[256];
+  const int s = blockIdx.x, i = threadIdx.x;
+  const float e = i < D ? E[(size_t)s * D + i] : 0.0f;
+  red[i] = e;
+  __syncthreads();
   float mean = 0.0f;
-  for (int i = 0; i < D; ++i) mean += e[i];
+  for (int k = 0; k < D; ++k) mean += red[k];
   mean /= (float)D;
+  __syncthreads();
+  const float dlt = e - mean;
+  red[i] = i < D ? dlt * dlt : 0.0f;
+  __syncthreads();
   float var = 0.0f;
-  for (int i = 0; i < D; ++i) { const float d = e[i] - mean; var += d * d; }
+  for (int k = 0; k < D; ++k) var += red[k];
   var /= (float)D;
   const float rstd = 1.0f / sqrtf(var + 1e-5f);
-  for (int i = 0; i < D; ++i) {
-    const float h = (e[i] - mean) * rstd;
-    const float xe = h * ge[i] + be[i];
+  if (i < D) {
+    const float h = dlt * rstd, xe = h * ge[i] + be[i];
     tabXe32[(size_t)s * D + i] = xe;
     tabXe[(size_t)s * D + i] = (AT)xe;
     tabXl[(size_t)s * D + i] = (AT)(h * gl[i] + bl[i]);
+    if (tabXhat) tabXhat[(size_t)s * D + i] = h;
   }
+  if (i == 0 && tabRstd) tabRstd[s] = rstd;
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -171,9 +179,11 @@ __global__ __launch_bounds__(256) void bmm_kernel(const float *y, const AT *WU, 
 // the kernel that reduces the split-K partials. s is summed from the bf16 values the matrix cores multiply.
 // ---------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void fold_vectors_kernel(const float *W0, const float *W1, int K, int N, int interleave,
-                                                           const float *gamma, const float *beta, float *s_out, float *t_out) {
+                                                           const float *gamma, const float *beta, float *part /*[gridDim.y][2][N]*/) {
+  // workgroup (x, y): 64 columns, K range y; four row phases per range, each in increasing k, combined in phase order
   __shared__ float ps[4][64], pt[4][64];
   const int v = blockIdx.x * 64 + (threadIdx.x & 63), kq = threadIdx.x >> 6;
+  const int kper = K / (int)gridDim.y, k0 = (int)blockIdx.y * kper;
   const float *src = W0;
   int col = v, ld = N;
   if (interleave) {
@@ -182,7 +192,7 @@ __global__ __launch_bounds__(256) void fold_vectors_kernel(const float *W0, cons
     if ((v & 127) >= 64) src = W1;
   }
   float sa = 0.0f, ta = 0.0f;
-  for (int k = kq; k < K; k += 4) {
+  for (int k = k0 + kq; k < k0 + kper; k += 4) {
     const float w = (float)(bf16_t)src[(size_t)k * ld + col];
     sa += (float)(bf16_t)(gamma[k] * w);
     ta = fmaf(beta[k], w, ta);
@@ -192,9 +202,17 @@ __global__ __launch_bounds__(256) void fold_vectors_kernel(const float *W0, cons
   __syncthreads();
   if (kq == 0) {
     const int c = threadIdx.x;
-    s_out[v] = (ps[0][c] + ps[1][c]) + (ps[2][c] + ps[3][c]);
-    t_out[v] = (pt[0][c] + pt[1][c]) + (pt[2][c] + pt[3][c]);
+    float *p = part + (size_t)blockIdx.y * 2 * N;
+    p[v] = (ps[0][c] + ps[1][c]) + (ps[2][c] + ps[3][c]);
+    p[N + v] = (pt[0][c] + pt[1][c]) + (pt[2][c] + pt[3][c]);
   }
+}
+__global__ __launch_bounds__(256) void fold_reduce_kernel(int P, int N2, const float *part, float *out) {
+  const int n = blockIdx.x * 256 + threadIdx.x;
+  if (n >= N2) return;
+  float s = 0.0f;
+  for (int p = 0; p < P; ++p) s += part[(size_t)p * N2 + n];
+  out[n] = s;
 }
 
 __device__ __forceinline__ void moments_from_partials(const float *stats, int stats_n, int width, float &mean, float &rstd) {
@@ -289,20 +307,45 @@ __global__ __launch_bounds__(256) void hout_kernel(HoutArgs a) {
   for (int i = 0; i < 8; ++i) out[i] = (AT)(gelu_f((v[i] - mean) * rstd * ga[i] + be[i]) + lam * hc[i]);
 }
 
-// x-hat and rstd of the per-symbol LayerNorm (shared by both affine pairs), for the embedding's backward pass
-__global__ void tables_bwd_kernel(const float *E, int D, float *tabXhat, float *tabRstd) {
-  const int s = blockIdx.x * blockDim.x + threadIdx.x;
-  if (s >= 256) return;
-  const float *e = E + (size_t)s * D;
-  float mean = 0.0f;
-  for (int i = 0; i < D; ++i) mean += e[i];
-  mean /= (float)D;
-  float var = 0.0f;
-  for (int i = 0; i < D; ++i) { const float d = e[i] - mean; var += d * d; }
-  var /= (float)D;
-  const float rstd = 1.0f / sqrtf(var + 1e-5f);
-  tabRstd[s] = rstd;
-  for (int i = 0; i < D; ++i) tabXhat[(size_t)s * D + i] = (e[i] - mean) * rstd;
+// All element-wise weight preparation of one refresh in a single launch: blockIdx.y picks the descriptor.
+__global__ __launch_bounds__(256) void prep_batch_kernel(PrepBatch pb) {
+  const PrepDesc &d = pb.d[blockIdx.y];
+  const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (d.kind == PREP_ROUND) {
+    if (t < (size_t)d.N) static_cast<float *>(d.out)[t] = (float)(bf16_t)d.W0[t];
+    return;
+  }
+  const bool tr = d.kind == PREP_FRAG_T;
+  const int Kv = tr ? d.N : d.K, Nv = tr ? d.K : d.N;  // shape of the matrix whose fragments are written
+  const size_t total = (size_t)(Nv / 32) * (Kv / 16) * 64;
+  if (t >= total) return;
+  const int lane = (int)(t & 63);
+  const size_t frag = t >> 6;
+  const int ks = (int)(frag % (size_t)(Kv / 16)), nt = (int)(frag / (size_t)(Kv / 16));
+  const int n = nt * 32 + (lane & 31);
+  bf16x8 r;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int k = ks * 16 + (lane >> 5) * 8 + i;
+    float w;
+    if (d.kind == PREP_FRAG_CONVT) {
+      const int rr = k / d.D, o = k - rr * d.D;
+      w = rr < d.taps ? d.W0[((size_t)rr * d.D + n) * d.D + o] : 0.0f;
+    } else {
+      const int row = tr ? n : k, v = tr ? k : n;  // position in the (virtual) source [K][N]
+      const float *src = d.W0;
+      int col = v, ld = d.N;
+      if (d.interleave) {
+        ld = d.N / 2;
+        col = (v / 128) * 64 + (v & 63);
+        if ((v & 127) >= 64) src = d.W1;
+      }
+      w = (tr || row < d.k_real) ? src[(size_t)row * ld + col] : 0.0f;
+      if (!tr && d.rowscale && row < d.k_real) w = d.rowscale[row] * (float)(bf16_t)w;
+    }
+    r[i] = (bf16_t)w;
+  }
+  reinterpret_cast<bf16x8 *>(d.out)[t] = r;
 }
 
 // Eq. 4 backward w.r.t. its input is again a (anti-causal) convolution; its weight as a product operand:
@@ -653,13 +696,14 @@ hipError_t fade_round_bf16(const float *src, float *dst, size_t n, hipStream_t s
   return hipGetLastError();
 }
 hipError_t fade_tables(const float *E, const float *ge, const float *be, const float *gl, const float *bl, int D, void *tabXe,
-                       void *tabXl, float *tabXe32, bool bf16, hipStream_t s) {
+                       void *tabXl, float *tabXe32, float *tabXhat, float *tabRstd, bool bf16, hipStream_t s) {
+  if (D > 256) return hipErrorInvalidValue;
   if (bf16)
-    hipLaunchKernelGGL(tables_kernel<bf16_t>, dim3(1), dim3(256), 0, s, E, ge, be, gl, bl, D, static_cast<bf16_t *>(tabXe),
-                       static_cast<bf16_t *>(tabXl), tabXe32);
+    hipLaunchKernelGGL(tables_kernel<bf16_t>, dim3(256), dim3(256), 0, s, E, ge, be, gl, bl, D, static_cast<bf16_t *>(tabXe),
+                       static_cast<bf16_t *>(tabXl), tabXe32, tabXhat, tabRstd);
   else
-    hipLaunchKernelGGL(tables_kernel<float>, dim3(1), dim3(256), 0, s, E, ge, be, gl, bl, D, static_cast<float *>(tabXe),
-                       static_cast<float *>(tabXl), tabXe32);
+    hipLaunchKernelGGL(tables_kernel<float>, dim3(256), dim3(256), 0, s, E, ge, be, gl, bl, D, static_cast<float *>(tabXe),
+                       static_cast<float *>(tabXl), tabXe32, tabXhat, tabRstd);
   return hipGetLastError();
 }
 hipError_t fade_embed_cache(const EmbedArgs &a, int B, bool bf16, hipStream_t s) {
@@ -674,10 +718,15 @@ hipError_t fade_bmm(const float *y, const void *WU, void *z, int B, bool bf16, h
     hipLaunchKernelGGL(bmm_kernel<float>, dim3((B + 3) / 4), dim3(256), 0, s, y, static_cast<const float *>(WU), static_cast<float *>(z), B);
   return hipGetLastError();
 }
+// st_out: [2][N] (s then t); part: scratch of 16 * 2 * N floats
 hipError_t fade_fold_vectors(const float *W0, const float *W1, int K, int N, int interleave, const float *gamma, const float *beta,
-                             float *s_out, float *t_out, hipStream_t s) {
-  if (N % 64) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(fold_vectors_kernel, dim3(N / 64), dim3(256), 0, s, W0, W1, K, N, interleave, gamma, beta, s_out, t_out);
+                             float *part, float *st_out, hipStream_t s) {
+  if (N % 64 || K % 64) return hipErrorInvalidValue;
+  const int ksp = 16;
+  hipLaunchKernelGGL(fold_vectors_kernel, dim3(N / 64, ksp), dim3(256), 0, s, W0, W1, K, N, interleave, gamma, beta, part);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(fold_reduce_kernel, dim3(blocks_for((size_t)2 * N, 256)), dim3(256), 0, s, ksp, 2 * N, part, st_out);
   return hipGetLastError();
 }
 hipError_t fade_cci(const CciArgs &a, hipStream_t s) {
@@ -699,12 +748,22 @@ hipError_t fade_preshuffle_t(const float *W0, const float *W1, int K, int N, int
   hipLaunchKernelGGL(preshuffle_t_kernel, dim3(blocks_for(total, 256)), dim3(256), 0, s, W0, W1, K, N, interleave, static_cast<bf16_t *>(out));
   return hipGetLastError();
 }
-hipError_t fade_convt_build(const float *Wconv, int taps, int D, int Kc, float *V, hipStream_t s) {
-  hipLaunchKernelGGL(convt_build_kernel, dim3(blocks_for((size_t)Kc * D, 256)), dim3(256), 0, s, Wconv, taps, D, Kc, V);
+hipError_t fade_prep_batch(const PrepBatch &pb, hipStream_t s) {
+  if (pb.count <= 0 || pb.count > 20) return hipErrorInvalidValue;
+  size_t most = 0;
+  for (int i = 0; i < pb.count; ++i) {
+    const PrepDesc &d = pb.d[i];
+    size_t n;
+    if (d.kind == PREP_ROUND) n = (size_t)d.N;
+    else if (d.kind == PREP_FRAG_T) n = (size_t)(d.K / 32) * (d.N / 16) * 64;
+    else n = (size_t)(d.N / 32) * (d.K / 16) * 64;
+    if (n > most) most = n;
+  }
+  hipLaunchKernelGGL(prep_batch_kernel, dim3(blocks_for(most, 256), pb.count), dim3(256), 0, s, pb);
   return hipGetLastError();
 }
-hipError_t fade_tables_bwd(const float *E, int D, float *tabXhat, float *tabRstd, hipStream_t s) {
-  hipLaunchKernelGGL(tables_bwd_kernel, dim3(1), dim3(256), 0, s, E, D, tabXhat, tabRstd);
+hipError_t fade_convt_build(const float *Wconv, int taps, int D, int Kc, float *V, hipStream_t s) {
+  hipLaunchKernelGGL(convt_build_kernel, dim3(blocks_for((size_t)Kc * D, 256)), dim3(256), 0, s, Wconv, taps, D, Kc, V);
   return hipGetLastError();
 }
 hipError_t fade_softmax_quant_code(const SqcArgs &a, int mode, hipStream_t s) {
