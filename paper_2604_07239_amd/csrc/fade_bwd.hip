@@ -547,9 +547,9 @@ __global__ __launch_bounds__(256) void conv_grad_partial_kernel(ConvGradArgs a) 
   const int tid = threadIdx.x, D = a.D;
   const long long tokens = (long long)a.B * a.T, t0 = (long long)blockIdx.x * 128;
   const AT *XL = static_cast<const AT *>(a.XL), *dcv = static_cast<const AT *>(a.dcv);
+  const long long left = (tokens - t0) * D;  // elements of this tile that exist
   for (int e = tid; e < 128 * D; e += 256) {
-    const long long t = t0 + e / D;
-    const bool ok = t < tokens;
+    const bool ok = e < left;
     xs[e] = ok ? (float)XL[(size_t)t0 * D + e] : 0.0f;
     ds[e] = ok ? (float)dcv[(size_t)t0 * D + e] : 0.0f;
   }
@@ -573,9 +573,13 @@ __global__ __launch_bounds__(256) void conv_grad_partial_kernel(ConvGradArgs a) 
     const int j = tl & Tm;
     const float d = ds[tl * D + o];
     bsum += d;
+    // unconditional LDS reads (index clamped into the tile) and a select: a branch per slot would wait for each read in turn
 #pragma unroll
-    for (int q = 0; q < 16; ++q)
-      if (j >= back[q]) acc[q] = fmaf(xs[tl * D + xoff[q]], d, acc[q]);
+    for (int q = 0; q < 16; ++q) {
+      const int idx = tl * D + xoff[q];
+      const float x = xs[idx < 0 ? 0 : idx];
+      acc[q] = fmaf(j >= back[q] ? x : 0.0f, d, acc[q]);
+    }
   }
   float *part = a.part + (size_t)blockIdx.x * (rows + 1) * D;
 #pragma unroll
@@ -603,7 +607,8 @@ __global__ __launch_bounds__(256) void symbol_sums_partial_kernel(BwdTokenArgs a
   __shared__ float tile[128 * 32];
   __shared__ int sym[128];
   const int tid = threadIdx.x, D = a.D, which = blockIdx.y;
-  const int lane_i = tid % D, grp = tid / D, ngrp = 256 / D;
+  const int lgD = 31 - __builtin_clz(D), Tm1 = a.T - 1, lgT = 31 - __builtin_clz(a.T);  // D and T are powers of two
+  const int lane_i = tid & (D - 1), grp = tid >> lgD, gmask = (256 >> lgD) - 1;
   const long long tokens = (long long)a.B * a.T, t0 = (long long)blockIdx.x * per_block;
   long long t1 = t0 + per_block;
   if (t1 > tokens) t1 = tokens;
@@ -612,13 +617,12 @@ __global__ __launch_bounds__(256) void symbol_sums_partial_kernel(BwdTokenArgs a
     const int cnt = (int)((t1 - c0 < 128) ? (t1 - c0) : 128);
     __syncthreads();
     for (int e = tid; e < cnt * D; e += 256) {
-      const long long t = c0 + e / D;
+      const long long t = c0 + (e >> lgD);
       const size_t g = (size_t)c0 * D + e;
       float v;
       if (which == 0) {
         v = (float)static_cast<const AT *>(a.dX1)[g] + (float)static_cast<const AT *>(a.dX2)[g];
-        const int b = (int)(t / a.T);
-        if ((int)(t - (long long)b * a.T) == a.T - 1) v += a.dxt[(size_t)b * D + e % D];
+        if ((int)(t & Tm1) == Tm1) v += a.dxt[(size_t)(t >> lgT) * D + (e & (D - 1))];
       } else {
         v = (float)static_cast<const AT *>(a.dxl)[g];
       }
@@ -626,13 +630,17 @@ __global__ __launch_bounds__(256) void symbol_sums_partial_kernel(BwdTokenArgs a
     }
     if (tid < cnt) {
       const long long t = c0 + tid;
-      const int b = (int)(t / a.T), j = (int)(t - (long long)b * a.T);
+      const int b = (int)(t >> lgT), j = (int)(t & Tm1);
       sym[tid] = stream_active(a.ws, b) ? stream_window(a.ws, b, a.T)[j] : -1;  // inactive streams contribute nothing
     }
     __syncthreads();
-    for (int k = 0; k < cnt; ++k) {
-      const int s = sym[k];
-      if (s >= 0 && (s % ngrp) == grp) tab[s * D + lane_i] += tile[k * D + lane_i];
+    for (int k0 = 0; k0 < cnt; k0 += 8) {
+      int sy[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) sy[q] = (k0 + q < cnt) ? sym[k0 + q] : -1;
+#pragma unroll
+      for (int q = 0; q < 8; ++q)
+        if (sy[q] >= 0 && (sy[q] & gmask) == grp) tab[sy[q] * D + lane_i] += tile[(k0 + q) * D + lane_i];
     }
   }
   __syncthreads();
