@@ -574,12 +574,13 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
   float *G = c->grad;
   auto Gp = [&](int id) { return G + c->lay.off[id]; };
   const int RB = (B + fade_rows_per_block() - 1) / fade_rows_per_block();
+  ReduceBatch rq{};  // second-stage reductions nothing in here waits for: one launch before Adam
   int rc;
   {
     Prof p(c, "bwd_prep_dlogits");
     HIP_TRY(c, fade_update_prep(ws, B, c->ustate, c->cfg.beta1, c->cfg.beta2, s));
     HIP_TRY(c, fade_dlogits(ws, targets, tstride, B, c->probs_buf, c->ustate, c->dl, bf, s));
-    HIP_TRY(c, fade_colsum(B, 256, c->dl, c->col_part, Gp(P_BO), bf, s));
+    HIP_TRY(c, fade_colsum(B, 256, c->dl, c->col_part, Gp(P_BO), bf, rq, s));
   }
   {  // feature-major copies of every forward activation that is the left operand of a weight gradient, in one launch
     Prof p(c, "transpose");
@@ -608,7 +609,7 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     a.B = B; a.Dh = Dh; a.stats_n = SN; a.ln_part = c->ln_part; a.dH = c->dHout; a.V = c->V; a.Hc = c->Hc; a.stats = c->stats_o; a.gamma = c->P(P_GAMMA_O);
     a.beta = c->P(P_BETA_O); a.lam = c->P(P_LAMBDA_O); a.dnv = c->dnv; a.dV = c->dV; a.dHc = c->dHc; a.row_dlam = c->row_dlam;
     HIP_TRY(c, fade_bwd_out(a, bf, s));
-    HIP_TRY(c, fade_reduce_rows(RB, 2 * Dh, c->ln_part, Gp(P_GAMMA_O), s));  // gamma_o then beta_o, adjacent in the blob
+    rq.push(RB, 2 * Dh, c->ln_part, Gp(P_GAMMA_O));  // gamma_o then beta_o, adjacent in the blob
   }
   if ((rc = transpose_grads(c, {{c->dV, {c->RT[1], Dh}}}))) return rc;
   if ((rc = gemm_w(c, "gemm_dW_f", c->LT[1], De, c->dV, c->RT[1], Dh, Gp(P_WF), nullptr))) return rc;
@@ -627,7 +628,7 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     a.stats = c->stats_f; a.gamma = c->P(P_GAMMA_F); a.lam = c->P(P_LAMBDA_C); a.dHa = c->dHa; a.dac = c->dac; a.dHmix = c->dHmix1;
     a.row_dlam = c->row_dlam + B;
     HIP_TRY(c, fade_bwd_gate(a, bf, s));
-    HIP_TRY(c, fade_reduce_rows(RB, 2 * Dh, c->ln_part + (size_t)RB * 2 * Dh, Gp(P_GAMMA_F), s));
+    rq.push(RB, 2 * Dh, c->ln_part + (size_t)RB * 2 * Dh, Gp(P_GAMMA_F));
   }
   if ((rc = transpose_grads(c, {{c->dac, {c->RT[3], Dh}}, {c->dHa, {c->RT[4], Dh}}}))) return rc;
   if ((rc = gemm_w(c, "gemm_dW_c", c->LT[3], Dh, c->dac, c->RT[3], Dh, Gp(P_WC), nullptr))) return rc;
@@ -661,8 +662,10 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     a.Hg = c->Hg; a.Hl = c->Hl; a.hm = c->hm; a.cv = c->cv; a.X = c->X; a.stats = c->stats_c; a.gamma = c->P(P_GAMMA_C);
     a.lam = c->P(P_LAMBDA_M); a.dar = c->dar; a.dhm = c->dhm; a.dcv = c->dcv; a.dX = c->dX1; a.row_dlam = c->row_dlam + 2 * B;
     HIP_TRY(c, fade_bwd_mix(a, bf, s));
-    HIP_TRY(c, fade_reduce_rows(RB, 2 * Dh, c->ln_part + (size_t)RB * 4 * Dh, Gp(P_GAMMA_C), s));
-    HIP_TRY(c, fade_scalar_sums(B, c->row_dlam, c->row_dlam + B, c->row_dlam + 2 * B, Gp(P_LAMBDA_O), Gp(P_LAMBDA_C), Gp(P_LAMBDA_M), s));
+    rq.push(RB, 2 * Dh, c->ln_part + (size_t)RB * 4 * Dh, Gp(P_GAMMA_C));
+    rq.push(B, 1, c->row_dlam, Gp(P_LAMBDA_O));  // the three residual scales: per-stream terms, one column each
+    rq.push(B, 1, c->row_dlam + B, Gp(P_LAMBDA_C));
+    rq.push(B, 1, c->row_dlam + 2 * B, Gp(P_LAMBDA_M));
   }
   if ((rc = transpose_grads(c, {{c->dar, {c->RT[6], Dh}}, {c->dhm, {c->RT[7], Dh}}}))) return rc;
   if ((rc = gemm_w(c, "gemm_dW_r", c->LT[7], Dh, c->dar, c->RT[6], Dh, Gp(P_WR), nullptr))) return rc;
@@ -675,13 +678,13 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     a.Dh = Dh; a.Dc = (int)d.Dc; a.c = (int)d.c; a.D = (int)d.D; a.round_bf16 = bf ? 1 : 0; a.dhm = c->dhm; a.Wm = c->P(P_WM);
     a.GG = c->GG; a.GV = c->GV; a.Wg = c->Wg_c; a.Wv = c->Wv_c; a.dgg = c->dgg; a.dgv = c->dgv; a.dxt = c->dxt;
     HIP_TRY(c, fade_bwd_slot(a, B, bf, s));
-    HIP_TRY(c, fade_slot_weight_grad(ws, B, (int)d.T, (int)d.D, (int)d.c, c->tabXe32, c->dgg, c->dgv, c->slot_part, Gp(P_WG), s));
+    HIP_TRY(c, fade_slot_weight_grad(ws, B, (int)d.T, (int)d.D, (int)d.c, c->tabXe32, c->dgg, c->dgv, c->slot_part, Gp(P_WG), rq, s));
   }
   {  // local stream
     Prof p(c, "bwd_conv");
     ConvGradArgs a{};
     a.B = B; a.T = (int)d.T; a.D = (int)d.D; a.taps = (int)d.k; a.XL = c->XL; a.dcv = c->dcv; a.part = c->conv_part;
-    HIP_TRY(c, fade_conv_grad(a, Gp(P_WCONV), bf, s));  // W_conv then b_conv, adjacent in the blob
+    HIP_TRY(c, fade_conv_grad(a, Gp(P_WCONV), bf, rq, s));  // W_conv then b_conv, adjacent in the blob
     GemmArgs g{};
     g.M = (int)(d.B * d.T); g.N = (int)d.D; g.K = (int)d.Kc; g.A = c->dcv; g.T = (int)d.T; g.D = (int)d.D; g.taps = (int)d.k;
     g.W = bf ? c->WT_conv : static_cast<const void *>(c->convt_f32); g.C = c->dxl; g.ldc = (int)d.D;
@@ -694,11 +697,12 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     a.tabXhat = c->tabXhat; a.tabRstd = c->tabRstd; a.gamma_e = c->P(P_GAMMA_E); a.gamma_l = c->P(P_GAMMA_L);
     a.part = c->emb_part;
     // gamma_e, beta_e, gamma_l, beta_l are adjacent in the blob
-    HIP_TRY(c, fade_bwd_embed(a, c->emb_blocks, c->sym_sums, c->tok_part, Gp(P_E), Gp(P_GAMMA_E), bf, s));
+    HIP_TRY(c, fade_bwd_embed(a, c->emb_blocks, c->sym_sums, c->tok_part, Gp(P_E), Gp(P_GAMMA_E), bf, rq, s));
   }
   {  // Adam on everything except W_U (done in place above), then refresh the compute copies
     Prof p(c, "adam_refresh");
     const size_t lo = c->lay.off[P_WU], hi = c->lay.off[P_WU + 1], np = c->lay.off[P_COUNT];
+    HIP_TRY(c, fade_reduce_batch(rq, s));
     HIP_TRY(c, fade_adam(lo, c->grad, c->master, c->adam_m, c->adam_v, c->ustate, c->cfg.lr, c->cfg.beta1, c->cfg.beta2, c->cfg.eps, s));
     HIP_TRY(c, fade_adam(np - hi, c->grad + hi, c->master + hi, c->adam_m + hi, c->adam_v + hi, c->ustate, c->cfg.lr, c->cfg.beta1,
                          c->cfg.beta2, c->cfg.eps, s));

@@ -98,60 +98,64 @@ __global__ __launch_bounds__(256) void dlogits_kernel(WinSrc ws, const uint8_t *
 // the batch and therefore need batch-contiguous operands. Optional LayerNorm on the way (u = LN(H_coarse), LN(H_mix)).
 // 64 x 64 tiles through LDS; dst has leading dimension Bp (batch rounded up to 64, padding stays zero).
 // ---------------------------------------------------------------------------------------------------
+// One 64 x 64 tile: 16-byte (bf16) / 32-byte (fp32) pieces on both the read and the write side, the turn happens in LDS
+// (pitch 65 floats: the piece-wise row writes and the column reads both touch all 64 banks).
+template <typename AT>
+__device__ __forceinline__ void transpose_tile(const TransposeArgs &a, int b0, int n0, float (*tile)[65], float *mr /*[2][64]*/) {
+  const AT *src = static_cast<const AT *>(a.src);
+  AT *dst = static_cast<AT *>(a.dst);
+  const int tid = threadIdx.x;
+  if (a.stats) {
+    if (tid < 64) {
+      float mean = 0.0f, rstd = 0.0f;
+      if (b0 + tid < a.B) moments(a.stats + (size_t)(b0 + tid) * a.stats_n * 2, a.stats_n, a.width, mean, rstd);
+      mr[tid] = mean; mr[64 + tid] = rstd;
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int p = 0; p < 2; ++p) {
+    const int q = tid + 256 * p, r = q >> 3, c8 = (q & 7) * 8, b = b0 + r;
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = 0.0f;
+    if (b < a.B) {
+      ld8<AT>(src + (size_t)b * a.ld + n0 + c8, v);
+      if (a.stats) {
+        const float mean = mr[r], rstd = mr[64 + r];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = (v[i] - mean) * rstd * a.gamma[n0 + c8 + i] + a.beta[n0 + c8 + i];  // blob vectors: dword-aligned only
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) tile[r][c8 + i] = v[i];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int p = 0; p < 2; ++p) {
+    const int q = tid + 256 * p, n = q >> 3, bc = (q & 7) * 8;
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = tile[bc + i][n];
+    st8<AT>(dst + (size_t)(n0 + n) * a.Bp + b0 + bc, v);  // rows past B were staged as zeros: the padding stays zero
+  }
+}
+
 template <typename AT>
 __global__ __launch_bounds__(256) void transpose_kernel(TransposeArgs a) {
   __shared__ float tile[64][65];
-  const AT *src = static_cast<const AT *>(a.src);
-  AT *dst = static_cast<AT *>(a.dst);
-  const int b0 = blockIdx.x * 64, n0 = blockIdx.y * 64;
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  for (int r = ty; r < 64; r += 4) {
-    const int b = b0 + r;
-    float v = 0.0f;
-    if (b < a.B) {
-      v = (float)src[(size_t)b * a.ld + n0 + tx];
-      if (a.stats) {
-        float mean, rstd;
-        moments(a.stats + (size_t)b * a.stats_n * 2, a.stats_n, a.width, mean, rstd);
-        v = (v - mean) * rstd * a.gamma[n0 + tx] + a.beta[n0 + tx];
-      }
-    }
-    tile[r][tx] = v;
-  }
-  __syncthreads();
-  for (int r = ty; r < 64; r += 4) {
-    const int b = b0 + tx;
-    if (b < a.B) dst[(size_t)(n0 + r) * a.Bp + b] = (AT)tile[tx][r];
-  }
+  __shared__ float mr[128];
+  transpose_tile<AT>(a, blockIdx.x * 64, blockIdx.y * 64, tile, mr);
 }
 
 template <typename AT>
 __global__ __launch_bounds__(256) void transpose_batch_kernel(TransposeBatch tb) {
   __shared__ float tile[64][65];
+  __shared__ float mr[128];
   const TransposeArgs &a = tb.t[blockIdx.z];
   const int b0 = blockIdx.x * 64, n0 = blockIdx.y * 64;
   if (b0 >= a.B || n0 >= tb.N[blockIdx.z]) return;  // uniform over the workgroup
-  const AT *src = static_cast<const AT *>(a.src);
-  AT *dst = static_cast<AT *>(a.dst);
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  for (int r = ty; r < 64; r += 4) {
-    const int b = b0 + r;
-    float v = 0.0f;
-    if (b < a.B) {
-      v = (float)src[(size_t)b * a.ld + n0 + tx];
-      if (a.stats) {
-        float mean, rstd;
-        moments(a.stats + (size_t)b * a.stats_n * 2, a.stats_n, a.width, mean, rstd);
-        v = (v - mean) * rstd * a.gamma[n0 + tx] + a.beta[n0 + tx];
-      }
-    }
-    tile[r][tx] = v;
-  }
-  __syncthreads();
-  for (int r = ty; r < 64; r += 4) {
-    const int b = b0 + tx;
-    if (b < a.B) dst[(size_t)(n0 + r) * a.Bp + b] = (AT)tile[tx][r];
-  }
+  transpose_tile<AT>(a, b0, n0, tile, mr);
 }
 
 // X_T[j*D+i][b] = LN_e(E[w_{b,j}])[i] straight from the per-symbol table (X is a gather, so is its transpose)
@@ -411,6 +415,27 @@ __global__ __launch_bounds__(256) void reduce_rows_kernel(int P, int N, const fl
     out[n] = t;
   }
 }
+__global__ __launch_bounds__(256) void reduce_batch_kernel(ReduceBatch rb) {
+  // same arithmetic as reduce_rows_kernel, blockIdx.y picks the queued reduction
+  __shared__ float ps[8][32];
+  const int k = blockIdx.y, P = rb.P[k], N = rb.N[k];
+  if ((int)blockIdx.x * 32 >= N) return;  // uniform over the workgroup
+  const float *part = rb.part[k];
+  const int c = threadIdx.x & 31, h = threadIdx.x >> 5, n = blockIdx.x * 32 + c;
+  float s = 0.0f;
+  if (n < N) {
+#pragma unroll 4
+    for (int p = h; p < P; p += 8) s += part[(size_t)p * N + n];
+  }
+  ps[h][c] = s;
+  __syncthreads();
+  if (h == 0 && n < N) {
+    float t = 0.0f;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) t += ps[q][c];
+    rb.out[k][n] = t;
+  }
+}
 // stage 1 for a plain matrix: part[rb][n] = sum over the 32 rows of row block rb of src[b][n]
 template <typename AT>
 __global__ __launch_bounds__(256) void colsum_partial_kernel(int B, int N, const AT *src, float *part) {
@@ -419,20 +444,6 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(int B, int N, const
   float s = 0.0f;
   for (int r = 0; r < 32 && b0 + r < B; ++r) s += (float)src[(size_t)(b0 + r) * N + n];
   part[(size_t)blockIdx.x * N + n] = s;
-}
-
-// Sum per-row partials [B] into one scalar each (the three residual scales). One workgroup, fixed order.
-__global__ __launch_bounds__(256) void scalar_sums_kernel(int B, const float *r0, const float *r1, const float *r2, float *o0, float *o1,
-                                                          float *o2) {
-  __shared__ float red[4];
-  const float *rs[3] = {r0, r1, r2};
-  float *os[3] = {o0, o1, o2};
-  for (int k = 0; k < 3; ++k) {
-    float s = 0.0f;
-    for (int b = threadIdx.x; b < B; b += 256) s += rs[k][b];
-    const float tot = block_sum(s, red);
-    if (threadIdx.x == 0) os[k][0] = tot;
-  }
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -542,43 +553,57 @@ __global__ __launch_bounds__(256) void slot_weight_partial_kernel(WinSrc ws, int
 // ---------------------------------------------------------------------------------------------------
 template <typename AT>
 __global__ __launch_bounds__(256) void conv_grad_partial_kernel(ConvGradArgs a) {
-  // one workgroup = 128 consecutive tokens = whole streams (T divides 128); both tiles staged in LDS as fp32
-  __shared__ float xs[128 * 32], ds[128 * 32];
-  const int tid = threadIdx.x, D = a.D;
+  // One workgroup = 128 consecutive tokens = whole streams (T divides 128), both tiles staged in LDS as fp32. The input
+  // tile carries taps-1 zero rows in front of every stream: tap r of token j is then row j + r of the padded stream, no
+  // boundary test is left in the loop, and the (tap, i) rows a thread owns are contiguous floats.
+  constexpr int kXs = (128 + 3 * 32) * 32 + 32;  // taps <= 4, T >= 4, 16 <= D <= 32; 32 floats of slack for the over-read below
+  __shared__ __attribute__((aligned(16))) float xs[kXs];
+  __shared__ __attribute__((aligned(16))) float ds[128 * 32];
+  const int tid = threadIdx.x, D = a.D, pad = a.taps - 1;
+  const int lgD = 31 - __builtin_clz(D), lgT = 31 - __builtin_clz(a.T), Tm = a.T - 1, Tp = a.T + pad;  // D, T: powers of two
   const long long tokens = (long long)a.B * a.T, t0 = (long long)blockIdx.x * 128;
-  const AT *XL = static_cast<const AT *>(a.XL), *dcv = static_cast<const AT *>(a.dcv);
-  const long long left = (tokens - t0) * D;  // elements of this tile that exist
-  for (int e = tid; e < 128 * D; e += 256) {
-    const bool ok = e < left;
-    xs[e] = ok ? (float)XL[(size_t)t0 * D + e] : 0.0f;
-    ds[e] = ok ? (float)dcv[(size_t)t0 * D + e] : 0.0f;
+  const AT *XL = static_cast<const AT *>(a.XL) + (size_t)t0 * D, *dcv = static_cast<const AT *>(a.dcv) + (size_t)t0 * D;
+  const int used = (((128 >> lgT) * Tp) << lgD) + 32;
+  for (int e = tid; e < used; e += 256) xs[e] = 0.0f;
+  __syncthreads();
+  const int left = (int)((tokens - t0 < 128 ? tokens - t0 : 128)) << lgD;  // elements of this tile that exist
+  for (int e = tid * 8; e < (128 << lgD); e += 2048) {
+    float x[8], d[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) { x[q] = 0.0f; d[q] = 0.0f; }
+    if (e < left) { ld8<AT>(XL + e, x); ld8<AT>(dcv + e, d); }
+    const int tl = e >> lgD, at = ((((tl >> lgT) * Tp) + pad + (tl & Tm)) << lgD) + (e & (D - 1));
+#pragma unroll
+    for (int q = 0; q < 8; ++q) { xs[at + q] = x[q]; ds[e + q] = d[q]; }
   }
   __syncthreads();
   const int rows = a.taps * D;                    // (tap, i) pairs
-  const int o = tid % D, grp = tid / D, ngrp = 256 / D;
+  const int o = tid & (D - 1), grp = tid >> lgD, ngrp = 256 >> lgD;
   const int per = (rows + ngrp - 1) / ngrp;       // (tap, i) rows owned by this thread's group (<= 16)
+  const float *xp = xs + grp * per;
   float acc[16], bsum = 0.0f;
-  int xoff[16], back[16];  // per owned (tap, i): offset of its input inside the tile relative to the token, and the tap's reach
 #pragma unroll
-  for (int q = 0; q < 16; ++q) {
-    acc[q] = 0.0f;
-    const int r = grp * per + q;
-    const bool ok = q < per && r < rows;
-    const int tap = ok ? r / D : 0, i = ok ? r - tap * D : 0;
-    back[q] = ok ? (a.taps - 1) - tap : 1 << 20;  // an unreachable reach switches the slot off
-    xoff[q] = i - back[q] * D;
-  }
-  const int Tm = a.T - 1;  // T is a power of two
-  for (int tl = 0; tl < 128; ++tl) {
-    const int j = tl & Tm;
-    const float d = ds[tl * D + o];
-    bsum += d;
-    // unconditional LDS reads (index clamped into the tile) and a select: a branch per slot would wait for each read in turn
+  for (int q = 0; q < 16; ++q) acc[q] = 0.0f;
+  // rows past `per` (or past `rows`) are read and accumulated too (in bounds thanks to the slack) and dropped at the end
+  if ((per & 3) == 0) {
+    for (int tl = 0; tl < 128; ++tl) {
+      const float d = ds[(tl << lgD) + o];
+      bsum += d;
+      const f32x4 *x4 = reinterpret_cast<const f32x4 *>(xp + ((((tl >> lgT) * Tp) + (tl & Tm)) << lgD));
 #pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      const int idx = tl * D + xoff[q];
-      const float x = xs[idx < 0 ? 0 : idx];
-      acc[q] = fmaf(j >= back[q] ? x : 0.0f, d, acc[q]);
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const f32x4 x = x4[q4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[4 * q4 + i] = fmaf(x[i], d, acc[4 * q4 + i]);
+      }
+    }
+  } else {
+    for (int tl = 0; tl < 128; ++tl) {
+      const float d = ds[(tl << lgD) + o];
+      bsum += d;
+      const float *x = xp + ((((tl >> lgT) * Tp) + (tl & Tm)) << lgD);
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc[q] = fmaf(x[q], d, acc[q]);
     }
   }
   float *part = a.part + (size_t)blockIdx.x * (rows + 1) * D;
@@ -616,17 +641,26 @@ __global__ __launch_bounds__(256) void symbol_sums_partial_kernel(BwdTokenArgs a
   for (long long c0 = t0; c0 < t1; c0 += 128) {
     const int cnt = (int)((t1 - c0 < 128) ? (t1 - c0) : 128);
     __syncthreads();
-    for (int e = tid; e < cnt * D; e += 256) {
+    for (int e = tid * 8; e < (cnt << lgD); e += 2048) {  // 8 channels of one token per thread and pass
       const long long t = c0 + (e >> lgD);
-      const size_t g = (size_t)c0 * D + e;
-      float v;
+      const size_t g = ((size_t)c0 << lgD) + e;
+      float v[8];
       if (which == 0) {
-        v = (float)static_cast<const AT *>(a.dX1)[g] + (float)static_cast<const AT *>(a.dX2)[g];
-        if ((int)(t & Tm1) == Tm1) v += a.dxt[(size_t)(t >> lgT) * D + (e & (D - 1))];
+        float w[8];
+        ld8<AT>(static_cast<const AT *>(a.dX1) + g, v);
+        ld8<AT>(static_cast<const AT *>(a.dX2) + g, w);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) v[q] += w[q];
+        if ((int)(t & Tm1) == Tm1) {
+          ld8<float>(a.dxt + (((size_t)(t >> lgT)) << lgD) + (e & (D - 1)), w);
+#pragma unroll
+          for (int q = 0; q < 8; ++q) v[q] += w[q];
+        }
       } else {
-        v = (float)static_cast<const AT *>(a.dxl)[g];
+        ld8<AT>(static_cast<const AT *>(a.dxl) + g, v);
       }
-      tile[e] = v;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) tile[e + q] = v[q];
     }
     if (tid < cnt) {
       const long long t = c0 + tid;
@@ -745,45 +779,49 @@ hipError_t fade_reduce_rows(int P, int N, const float *part, float *out, hipStre
   hipLaunchKernelGGL(reduce_rows_kernel, dim3(nblk((size_t)N, 32)), dim3(256), 0, s, P, N, part, out);
   return hipGetLastError();
 }
+hipError_t fade_reduce_batch(const ReduceBatch &rb, hipStream_t s) {
+  if (rb.count <= 0) return hipSuccess;
+  int maxN = 0;
+  for (int i = 0; i < rb.count; ++i) maxN = rb.N[i] > maxN ? rb.N[i] : maxN;
+  hipLaunchKernelGGL(reduce_batch_kernel, dim3(nblk((size_t)maxN, 32), rb.count), dim3(256), 0, s, rb);
+  return hipGetLastError();
+}
 // out[n] = sum_b src[b][n]; part must hold ceil(B / 32) * N floats
-hipError_t fade_colsum(int B, int N, const void *src, float *part, float *out, bool bf16, hipStream_t s) {
+hipError_t fade_colsum(int B, int N, const void *src, float *part, float *out, bool bf16, ReduceBatch &rb, hipStream_t s) {
   const int P = (B + 31) / 32;
   const dim3 grid(P, (N + 255) / 256);
   if (bf16) hipLaunchKernelGGL(colsum_partial_kernel<bf16_t>, grid, dim3(256), 0, s, B, N, static_cast<const bf16_t *>(src), part);
   else hipLaunchKernelGGL(colsum_partial_kernel<float>, grid, dim3(256), 0, s, B, N, static_cast<const float *>(src), part);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  return fade_reduce_rows(P, N, part, out, s);
-}
-hipError_t fade_scalar_sums(int B, const float *r0, const float *r1, const float *r2, float *o0, float *o1, float *o2, hipStream_t s) {
-  hipLaunchKernelGGL(scalar_sums_kernel, dim3(1), dim3(256), 0, s, B, r0, r1, r2, o0, o1, o2);
-  return hipGetLastError();
+  return rb.push(P, N, part, out) ? hipSuccess : hipErrorInvalidValue;
 }
 hipError_t fade_bwd_cci(const BwdCciArgs &a, bool bf16, hipStream_t s) { DISPATCH_AT(bf16, bwd_cci_kernel, dim3(a.B), dim3(256), s, a); }
 hipError_t fade_bwd_slot(const BwdSlotArgs &a, int B, bool bf16, hipStream_t s) { DISPATCH_AT(bf16, bwd_slot_kernel, dim3(B), dim3(256), s, a); }
 // part must hold ceil(B / 16) * 2 * D * c floats; dWgv points at W_g's gradient (W_v's follows it in the blob)
 hipError_t fade_slot_weight_grad(const WinSrc &ws, int B, int T, int D, int c, const float *tabXe32, const float *dgg, const float *dgv,
-                                 float *part, float *dWgv, hipStream_t s) {
+                                 float *part, float *dWgv, ReduceBatch &rb, hipStream_t s) {
   const int P = (B + 15) / 16;
   hipLaunchKernelGGL(slot_weight_partial_kernel, dim3(P), dim3(256), 0, s, ws, B, T, D, c, tabXe32, dgg, dgv, part);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  return fade_reduce_rows(P, 2 * D * c, part, dWgv, s);
+  return rb.push(P, 2 * D * c, part, dWgv) ? hipSuccess : hipErrorInvalidValue;
 }
 // a.part must hold ceil(B * T / 128) * (taps * D + 1) * D floats; dWb points at W_conv's gradient (b_conv's follows it)
-hipError_t fade_conv_grad(const ConvGradArgs &a, float *dWb, bool bf16, hipStream_t s) {
-  if (256 % a.D || a.D > 32 || 128 % a.T || (a.taps * a.D + 256 / a.D - 1) / (256 / a.D) > 16) return hipErrorInvalidValue;
+hipError_t fade_conv_grad(const ConvGradArgs &a, float *dWb, bool bf16, ReduceBatch &rb, hipStream_t s) {
+  if (256 % a.D || a.D > 32 || a.D < 16 || 128 % a.T || a.T < 4 || a.taps > 4 || (a.taps * a.D + 256 / a.D - 1) / (256 / a.D) > 16) return hipErrorInvalidValue;
   const int P = (int)(((long long)a.B * a.T + 127) / 128);
   if (bf16) hipLaunchKernelGGL(conv_grad_partial_kernel<bf16_t>, dim3(P), dim3(256), 0, s, a);
   else hipLaunchKernelGGL(conv_grad_partial_kernel<float>, dim3(P), dim3(256), 0, s, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  return fade_reduce_rows(P, (a.taps * a.D + 1) * a.D, a.part, dWb, s);
+  return rb.push(P, (a.taps * a.D + 1) * a.D, a.part, dWb) ? hipSuccess : hipErrorInvalidValue;
 }
 // a.part: nblocks * 2 * 256 * D floats; sums: 2 * 256 * D; contrib: 256 * 4 * D.
 // dE: gradient of the embedding; dparams: gradient of gamma_e (beta_e, gamma_l, beta_l follow it in the blob).
-hipError_t fade_bwd_embed(const BwdTokenArgs &a, int nblocks, float *sums, float *contrib, float *dE, float *dparams, bool bf16, hipStream_t s) {
-  if (256 % a.D || a.D > 32) return hipErrorInvalidValue;
+hipError_t fade_bwd_embed(const BwdTokenArgs &a, int nblocks, float *sums, float *contrib, float *dE, float *dparams, bool bf16, ReduceBatch &rb,
+                          hipStream_t s) {
+  if (256 % a.D || a.D > 32 || a.D % 8) return hipErrorInvalidValue;
   const long long tokens = (long long)a.B * a.T, per = (tokens + nblocks - 1) / nblocks;
   if (bf16) hipLaunchKernelGGL(symbol_sums_partial_kernel<bf16_t>, dim3(nblocks, 2), dim3(256), 0, s, a, per);
   else hipLaunchKernelGGL(symbol_sums_partial_kernel<float>, dim3(nblocks, 2), dim3(256), 0, s, a, per);
@@ -792,7 +830,7 @@ hipError_t fade_bwd_embed(const BwdTokenArgs &a, int nblocks, float *sums, float
   if ((e = fade_reduce_rows(nblocks, 2 * 256 * a.D, a.part, sums, s)) != hipSuccess) return e;
   hipLaunchKernelGGL(embed_finish_kernel, dim3(256), dim3(64), 0, s, a.D, sums, a.tabXhat, a.tabRstd, a.gamma_e, a.gamma_l, dE, contrib);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  return fade_reduce_rows(256, 4 * a.D, contrib, dparams, s);
+  return rb.push(256, 4 * a.D, contrib, dparams) ? hipSuccess : hipErrorInvalidValue;
 }
 hipError_t fade_adam(size_t n, const float *grad, float *master, float *m, float *v, const UpdateState *u, float lr, float beta1, float beta2,
                      float eps, hipStream_t s) {

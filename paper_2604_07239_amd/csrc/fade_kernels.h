@@ -210,13 +210,27 @@ hipError_t fade_bwd_gate(const BwdGateArgs &a, bool bf16, hipStream_t s);
 hipError_t fade_bwd_mix(const BwdMixArgs &a, bool bf16, hipStream_t s);
 int fade_rows_per_block();
 hipError_t fade_reduce_rows(int P, int N, const float *part, float *out, hipStream_t s);
-hipError_t fade_colsum(int B, int N, const void *src, float *part, float *out, bool bf16, hipStream_t s);
-hipError_t fade_scalar_sums(int B, const float *r0, const float *r1, const float *r2, float *o0, float *o1, float *o2, hipStream_t s);
+// Second stages (out[n] = sum over p < P of part[p][n], rows added in a fixed order) that nothing inside the backward pass
+// waits for are queued here and run as ONE launch just before Adam. The stage-1 launchers below take the queue.
+struct ReduceBatch {
+  int count;
+  int P[16], N[16];
+  const float *part[16];
+  float *out[16];
+  bool push(int p, int n, const float *src, float *dst) {
+    if (count >= 16) return false;
+    P[count] = p; N[count] = n; part[count] = src; out[count] = dst; ++count;
+    return true;
+  }
+};
+hipError_t fade_reduce_batch(const ReduceBatch &rb, hipStream_t s);
+hipError_t fade_colsum(int B, int N, const void *src, float *part, float *out, bool bf16, ReduceBatch &rb, hipStream_t s);
 hipError_t fade_bwd_cci(const BwdCciArgs &a, bool bf16, hipStream_t s);
 hipError_t fade_bwd_slot(const BwdSlotArgs &a, int B, bool bf16, hipStream_t s);
 hipError_t fade_slot_weight_grad(const WinSrc &ws, int B, int T, int D, int c, const float *tabXe32, const float *dgg, const float *dgv,
-                                 float *part, float *dWgv, hipStream_t s);
-hipError_t fade_conv_grad(const ConvGradArgs &a, float *dWb, bool bf16, hipStream_t s);
-hipError_t fade_bwd_embed(const BwdTokenArgs &a, int nblocks, float *sums, float *contrib, float *dE, float *dparams, bool bf16, hipStream_t s);
+                                 float *part, float *dWgv, ReduceBatch &rb, hipStream_t s);
+hipError_t fade_conv_grad(const ConvGradArgs &a, float *dWb, bool bf16, ReduceBatch &rb, hipStream_t s);
+hipError_t fade_bwd_embed(const BwdTokenArgs &a, int nblocks, float *sums, float *contrib, float *dE, float *dparams, bool bf16, ReduceBatch &rb,
+                          hipStream_t s);
 hipError_t fade_adam(size_t n, const float *grad, float *master, float *m, float *v, const UpdateState *u, float lr, float beta1, float beta2,
                      float eps, hipStream_t s);
