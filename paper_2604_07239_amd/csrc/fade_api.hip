@@ -4,6 +4,7 @@
 #include <utility>
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -97,6 +98,11 @@ struct fade_ctx {
   size_t esz = 4;  // bytes per activation element
   hipStream_t stream = nullptr;
   bool own_stream = false;
+  // online mode: the weight-gradient products (and the operand copies they need) feed nothing but Adam, so they run on a
+  // second stream beside the chain of activation gradients; fork_ev[k] hands a finished gradient over, join_ev closes the step
+  hipStream_t side = nullptr;
+  bool one_stream = false;
+  hipEvent_t fork_ev[8] = {}, join_ev = nullptr;
   std::string err;
   std::vector<void *> allocs;
 
@@ -185,6 +191,11 @@ template <typename T> int dev_alloc(fade_ctx *c, T **p, size_t count) {
   if (e != hipSuccess) return hip_fail(c, e, "hipMalloc");
   c->allocs.push_back(q);
   *p = static_cast<T *>(q);
+  // Every buffer starts at zero. Rows of streams that are never active (a ragged last stream, an explicit mask) are never
+  // written by the window gather, yet the dense products and the backward pass run over all B rows: their contribution is
+  // (zero gradient) x (activation), which must not be 0 x NaN from recycled memory.
+  e = hipMemsetAsync(q, 0, (count ? count : 1) * sizeof(T), c->stream);
+  if (e != hipSuccess) return hip_fail(c, e, "hipMemsetAsync");
   return FADE_OK;
 }
 int dev_alloc_bytes(fade_ctx *c, void **p, size_t bytes) {
@@ -196,19 +207,19 @@ int dev_alloc_bytes(fade_ctx *c, void **p, size_t bytes) {
 
 // profiling: bracket a launch with two events on the context's stream
 struct Prof {
-  fade_ctx *c; int idx = -1;
-  Prof(fade_ctx *ctx, const char *name) : c(ctx) {
+  fade_ctx *c; int idx = -1; hipStream_t st;
+  Prof(fade_ctx *ctx, const char *name, hipStream_t on = nullptr) : c(ctx), st(on ? on : ctx->stream) {
     if (!c->profiling) return;
     int id = -1;
     for (size_t i = 0; i < c->prof_names.size(); ++i) if (c->prof_names[i] == name) id = (int)i;
     if (id < 0) { id = (int)c->prof_names.size(); c->prof_names.push_back(name); c->prof_ms.push_back(0); c->prof_n.push_back(0); }
     fade_ctx::Ev ev; ev.name = id;
     if (hipEventCreate(&ev.a) != hipSuccess || hipEventCreate(&ev.b) != hipSuccess) return;
-    (void)hipEventRecord(ev.a, c->stream);
+    (void)hipEventRecord(ev.a, st);
     c->events.push_back(ev);
     idx = (int)c->events.size() - 1;
   }
-  ~Prof() { if (idx >= 0) (void)hipEventRecord(c->events[idx].b, c->stream); }
+  ~Prof() { if (idx >= 0) (void)hipEventRecord(c->events[idx].b, st); }
 };
 
 void prof_collect(fade_ctx *c) {
@@ -538,13 +549,13 @@ int gemm_x(fade_ctx *c, const char *name, const void *dY, int Kred, int Nout, co
 }
 // dW[Kw][N] = L^T R over the batch. LT: feature-major copy [Kw][Bp] of the left operand; R: gradient [Bp][N] (fp32 path),
 // RT: its feature-major copy [N][Bp] (bf16 path).
-int gemm_w(fade_ctx *c, const char *name, const void *LT, int Kw, const void *R, const void *RT, int N, float *dW, float *dW_pair) {
-  Prof p(c, name);
+int gemm_w(fade_ctx *c, hipStream_t st, const char *name, const void *LT, int Kw, const void *R, const void *RT, int N, float *dW, float *dW_pair) {
+  Prof p(c, name, st);
   GemmArgs g{};
   g.M = Kw; g.N = N; g.K = (int)c->Bp; g.A = LT; g.lda = (int)c->Bp; g.C = dW; g.C3 = dW_pair; g.ldc = N;
   if (c->bf16) { g.W = RT; g.ldb = (int)c->Bp; }
   else g.W = R;
-  HIP_TRY(c, fade_gemm(GEMM_W, c->bf16, g, c->stream));
+  HIP_TRY(c, fade_gemm(GEMM_W, c->bf16, g, st));
   return FADE_OK;
 }
 TransposeArgs tr_desc(fade_ctx *c, const void *src, int ld, void *dst, const float *stats, const float *gamma, const float *beta) {
@@ -554,21 +565,28 @@ TransposeArgs tr_desc(fade_ctx *c, const void *src, int ld, void *dst, const flo
   return t;
 }
 // feature-major copies of freshly produced gradients (bf16 path only: the fp32 product reads them row-major)
-int transpose_grads(fade_ctx *c, std::initializer_list<std::pair<const void *, std::pair<void *, int>>> items) {
+int transpose_grads(fade_ctx *c, hipStream_t st, std::initializer_list<std::pair<const void *, std::pair<void *, int>>> items) {
   if (!c->bf16) return FADE_OK;
-  Prof p(c, "transpose");
+  Prof p(c, "transpose", st);
   TransposeBatch tb{};
   for (auto &it : items) {
     tb.t[tb.count] = tr_desc(c, it.first, it.second.second, it.second.first, nullptr, nullptr, nullptr);
     tb.N[tb.count++] = it.second.second;
   }
-  HIP_TRY(c, fade_transpose_batch(tb, true, c->stream));
+  HIP_TRY(c, fade_transpose_batch(tb, true, st));
+  return FADE_OK;
+}
+// everything enqueued on the main stream so far is visible to what is enqueued on the side stream from here on
+int fork_side(fade_ctx *c, int k) {
+  if (c->one_stream) return FADE_OK;
+  HIP_TRY(c, hipEventRecord(c->fork_ev[k], c->stream));
+  HIP_TRY(c, hipStreamWaitEvent(c->side, c->fork_ev[k], 0));
   return FADE_OK;
 }
 
 int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long tstride) {
   const Dims &d = c->d;
-  hipStream_t s = c->stream;
+  hipStream_t s = c->stream, w = c->one_stream ? c->stream : c->side;  // s: chain of activation gradients; w: weight-gradient products beside it
   const bool bf = c->bf16;
   const int B = (int)d.B, Dh = (int)d.Dh, De = (int)d.De, dl = (int)d.dl, SN = (int)(d.Dh / FADE_STATS_BN);
   float *G = c->grad;
@@ -582,8 +600,9 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     HIP_TRY(c, fade_dlogits(ws, targets, tstride, B, c->probs_buf, c->ustate, c->dl, bf, s));
     HIP_TRY(c, fade_colsum(B, 256, c->dl, c->col_part, Gp(P_BO), bf, rq, s));
   }
+  if ((rc = fork_side(c, 0))) return rc;
   {  // feature-major copies of every forward activation that is the left operand of a weight gradient, in one launch
-    Prof p(c, "transpose");
+    Prof p(c, "transpose", w);
     TransposeBatch tb{};
     auto add = [&](const void *src, int width, void *dst, const float *st, const float *ga, const float *be) {
       tb.t[tb.count] = tr_desc(c, src, width, dst, st, ga, be);
@@ -596,12 +615,13 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     add(c->z, dl, c->LT[4], nullptr, nullptr, nullptr);
     add(c->Hmix, Dh, c->LT[5], c->stats_c, c->P(P_GAMMA_C), c->P(P_BETA_C)); // LN(H_mix)
     add(c->M, (int)d.Dc, c->LT[6], nullptr, nullptr, nullptr);
-    HIP_TRY(c, fade_transpose_batch(tb, bf, s));
-    HIP_TRY(c, fade_embed_t(ws, B, (int)c->Bp, (int)d.T, (int)d.D, c->tabXe, c->LT[7], bf, s));  // X^T straight from the table
+    HIP_TRY(c, fade_transpose_batch(tb, bf, w));
+    HIP_TRY(c, fade_embed_t(ws, B, (int)c->Bp, (int)d.T, (int)d.D, c->tabXe, c->LT[7], bf, w));  // X^T straight from the table
   }
   // head
-  if ((rc = transpose_grads(c, {{c->dl, {c->RT[0], 256}}}))) return rc;
-  if ((rc = gemm_w(c, "gemm_dW_o", c->LT[0], Dh, c->dl, c->RT[0], 256, Gp(P_WO), nullptr))) return rc;
+  if ((rc = fork_side(c, 1))) return rc;
+  if ((rc = transpose_grads(c, w, {{c->dl, {c->RT[0], 256}}}))) return rc;
+  if ((rc = gemm_w(c, w, "gemm_dW_o", c->LT[0], Dh, c->dl, c->RT[0], 256, Gp(P_WO), nullptr))) return rc;
   if ((rc = gemm_x(c, "gemm_dHout", c->dl, 256, Dh, c->WT_o, c->P(P_WO), 256, c->dHout))) return rc;
   {  // Eq. 10
     Prof p(c, "bwd_out");
@@ -611,15 +631,17 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     HIP_TRY(c, fade_bwd_out(a, bf, s));
     rq.push(RB, 2 * Dh, c->ln_part, Gp(P_GAMMA_O));  // gamma_o then beta_o, adjacent in the blob
   }
-  if ((rc = transpose_grads(c, {{c->dV, {c->RT[1], Dh}}}))) return rc;
-  if ((rc = gemm_w(c, "gemm_dW_f", c->LT[1], De, c->dV, c->RT[1], Dh, Gp(P_WF), nullptr))) return rc;
+  if ((rc = fork_side(c, 2))) return rc;
+  if ((rc = transpose_grads(c, w, {{c->dV, {c->RT[1], Dh}}}))) return rc;
+  if ((rc = gemm_w(c, w, "gemm_dW_f", c->LT[1], De, c->dV, c->RT[1], Dh, Gp(P_WF), nullptr))) return rc;
   if ((rc = gemm_x(c, "gemm_dHexp", c->dV, Dh, De, c->WT_f, c->P(P_WF), Dh, c->dHexp))) return rc;
   {  // Eq. 9
     Prof p(c, "bwd_geglu");
     HIP_TRY(c, fade_bwd_geglu(B, De, c->dHexp, c->eg, c->ev, c->dE, bf, s));
   }
-  if ((rc = transpose_grads(c, {{c->dE, {c->RT[2], 2 * De}}}))) return rc;
-  if ((rc = gemm_w(c, "gemm_dW_fgv", c->LT[2], Dh, c->dE, c->RT[2], 2 * De, Gp(P_WFG), Gp(P_WFV)))) return rc;
+  if ((rc = fork_side(c, 3))) return rc;
+  if ((rc = transpose_grads(c, w, {{c->dE, {c->RT[2], 2 * De}}}))) return rc;
+  if ((rc = gemm_w(c, w, "gemm_dW_fgv", c->LT[2], Dh, c->dE, c->RT[2], 2 * De, Gp(P_WFG), Gp(P_WFV)))) return rc;
   if ((rc = gemm_x(c, "gemm_du", c->dE, 2 * De, Dh, c->WT_fgv, static_cast<const float *>(c->Wfgv_c), 2 * De, c->du))) return rc;
   {  // LN of Eq. 9 + Eq. 8
     Prof p(c, "bwd_gate");
@@ -630,11 +652,12 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     HIP_TRY(c, fade_bwd_gate(a, bf, s));
     rq.push(RB, 2 * Dh, c->ln_part + (size_t)RB * 2 * Dh, Gp(P_GAMMA_F));
   }
-  if ((rc = transpose_grads(c, {{c->dac, {c->RT[3], Dh}}, {c->dHa, {c->RT[4], Dh}}}))) return rc;
-  if ((rc = gemm_w(c, "gemm_dW_c", c->LT[3], Dh, c->dac, c->RT[3], Dh, Gp(P_WC), nullptr))) return rc;
+  if ((rc = fork_side(c, 4))) return rc;
+  if ((rc = transpose_grads(c, w, {{c->dac, {c->RT[3], Dh}}, {c->dHa, {c->RT[4], Dh}}}))) return rc;
+  if ((rc = gemm_w(c, w, "gemm_dW_c", c->LT[3], Dh, c->dac, c->RT[3], Dh, Gp(P_WC), nullptr))) return rc;
   if ((rc = gemm_x(c, "gemm_dHmix", c->dac, Dh, Dh, c->WT_c, c->P(P_WC), Dh, c->dHmix2))) return rc;
   // Eq. 7
-  if ((rc = gemm_w(c, "gemm_dW_up", c->LT[4], dl, c->dHa, c->RT[4], Dh, Gp(P_WUP), nullptr))) return rc;
+  if ((rc = gemm_w(c, w, "gemm_dW_up", c->LT[4], dl, c->dHa, c->RT[4], Dh, Gp(P_WUP), nullptr))) return rc;
   {
     Prof p(c, "gemm_dz");
     GemmArgs g{};
@@ -652,8 +675,9 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     a.lr = c->cfg.lr; a.beta1 = c->cfg.beta1; a.beta2 = c->cfg.beta2; a.eps = c->cfg.eps;
     HIP_TRY(c, fade_bwd_cci(a, bf, s));
   }
-  if ((rc = transpose_grads(c, {{c->dy_at, {c->RT[5], dl}}}))) return rc;
-  if ((rc = gemm_w(c, "gemm_dW_down", c->LT[5], Dh, c->dy_at, c->RT[5], dl, Gp(P_WDOWN), nullptr))) return rc;
+  if ((rc = fork_side(c, 5))) return rc;
+  if ((rc = transpose_grads(c, w, {{c->dy_at, {c->RT[5], dl}}}))) return rc;
+  if ((rc = gemm_w(c, w, "gemm_dW_down", c->LT[5], Dh, c->dy_at, c->RT[5], dl, Gp(P_WDOWN), nullptr))) return rc;
   if ((rc = gemm_x(c, "gemm_dnc", c->dy_at, dl, Dh, c->WT_down, c->P(P_WDOWN), dl, c->dnc))) return rc;
   {  // LN of Eq. 7 + Eq. 5-6 + branch activations
     Prof p(c, "bwd_mix");
@@ -667,11 +691,12 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     rq.push(B, 1, c->row_dlam + B, Gp(P_LAMBDA_C));
     rq.push(B, 1, c->row_dlam + 2 * B, Gp(P_LAMBDA_M));
   }
-  if ((rc = transpose_grads(c, {{c->dar, {c->RT[6], Dh}}, {c->dhm, {c->RT[7], Dh}}}))) return rc;
-  if ((rc = gemm_w(c, "gemm_dW_r", c->LT[7], Dh, c->dar, c->RT[6], Dh, Gp(P_WR), nullptr))) return rc;
+  if ((rc = fork_side(c, 6))) return rc;
+  if ((rc = transpose_grads(c, w, {{c->dar, {c->RT[6], Dh}}, {c->dhm, {c->RT[7], Dh}}}))) return rc;
+  if ((rc = gemm_w(c, w, "gemm_dW_r", c->LT[7], Dh, c->dar, c->RT[6], Dh, Gp(P_WR), nullptr))) return rc;
   if ((rc = gemm_x(c, "gemm_dX", c->dar, Dh, Dh, c->WT_r, c->P(P_WR), Dh, c->dX2))) return rc;
   // global stream
-  if ((rc = gemm_w(c, "gemm_dW_m", c->LT[6], (int)d.Dc, c->dhm, c->RT[7], Dh, Gp(P_WM), nullptr))) return rc;
+  if ((rc = gemm_w(c, w, "gemm_dW_m", c->LT[6], (int)d.Dc, c->dhm, c->RT[7], Dh, Gp(P_WM), nullptr))) return rc;
   {
     Prof p(c, "bwd_slot");
     BwdSlotArgs a{};
@@ -702,6 +727,10 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
   {  // Adam on everything except W_U (done in place above), then refresh the compute copies
     Prof p(c, "adam_refresh");
     const size_t lo = c->lay.off[P_WU], hi = c->lay.off[P_WU + 1], np = c->lay.off[P_COUNT];
+    if (!c->one_stream) {
+      HIP_TRY(c, hipEventRecord(c->join_ev, w));
+      HIP_TRY(c, hipStreamWaitEvent(s, c->join_ev, 0));
+    }
     HIP_TRY(c, fade_reduce_batch(rq, s));
     HIP_TRY(c, fade_adam(lo, c->grad, c->master, c->adam_m, c->adam_v, c->ustate, c->cfg.lr, c->cfg.beta1, c->cfg.beta2, c->cfg.eps, s));
     HIP_TRY(c, fade_adam(np - hi, c->grad + hi, c->master + hi, c->adam_m + hi, c->adam_v + hi, c->ustate, c->cfg.lr, c->cfg.beta1,
@@ -810,8 +839,12 @@ size_t fade_weights_nbytes(const fade_config *cfg) {
 void fade_destroy(fade_ctx *c) {
   if (!c) return;
   if (c->stream) (void)hipStreamSynchronize(c->stream);
+  if (c->side) (void)hipStreamSynchronize(c->side);
   for (auto &ev : c->events) { (void)hipEventDestroy(ev.a); (void)hipEventDestroy(ev.b); }
   for (void *p : c->allocs) (void)hipFree(p);
+  for (hipEvent_t e : c->fork_ev) if (e) (void)hipEventDestroy(e);
+  if (c->join_ev) (void)hipEventDestroy(c->join_ev);
+  if (c->side) (void)hipStreamDestroy(c->side);
   if (c->own_stream && c->stream) (void)hipStreamDestroy(c->stream);
   delete c;
 }
@@ -845,6 +878,14 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
   else {
     if (hipStreamCreate(&c->stream) != hipSuccess) { delete c; return FADE_E_HIP; }
     c->own_stream = true;
+  }
+  if (c->online) {
+    const char *one = getenv("FADE_ONE_STREAM");  // debugging aid: run the weight-gradient branch on the main stream
+    c->one_stream = one && one[0] == '1';
+    bool ok = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) == hipSuccess;
+    for (int k = 0; k < 8 && ok; ++k) ok = hipEventCreateWithFlags(&c->fork_ev[k], hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&c->join_ev, hipEventDisableTiming) == hipSuccess;
+    if (!ok) { fade_destroy(c); return FADE_E_HIP; }
   }
   const size_t np = c->lay.off[P_COUNT], BDh = d.B * d.Dh;
   const size_t SN = d.Dh / FADE_STATS_BN;
