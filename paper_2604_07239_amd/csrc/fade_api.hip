@@ -1,5 +1,6 @@
 // fade_api.hip — libfade's C ABI: context, device state, the step sequence and the compress / decompress loops.
 #include <algorithm>
+#include <chrono>
 #include <initializer_list>
 #include <utility>
 #include <cmath>
@@ -98,11 +99,6 @@ struct fade_ctx {
   size_t esz = 4;  // bytes per activation element
   hipStream_t stream = nullptr;
   bool own_stream = false;
-  // online mode: the weight-gradient products (and the operand copies they need) feed nothing but Adam, so they run on a
-  // second stream beside the chain of activation gradients; fork_ev[k] hands a finished gradient over, join_ev closes the step
-  hipStream_t side = nullptr;
-  bool one_stream = false;
-  hipEvent_t fork_ev[8] = {}, join_ev = nullptr;
   std::string err;
   std::vector<void *> allocs;
 
@@ -576,17 +572,11 @@ int transpose_grads(fade_ctx *c, hipStream_t st, std::initializer_list<std::pair
   HIP_TRY(c, fade_transpose_batch(tb, true, st));
   return FADE_OK;
 }
-// everything enqueued on the main stream so far is visible to what is enqueued on the side stream from here on
-int fork_side(fade_ctx *c, int k) {
-  if (c->one_stream) return FADE_OK;
-  HIP_TRY(c, hipEventRecord(c->fork_ev[k], c->stream));
-  HIP_TRY(c, hipStreamWaitEvent(c->side, c->fork_ev[k], 0));
-  return FADE_OK;
-}
-
 int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long tstride) {
   const Dims &d = c->d;
-  hipStream_t s = c->stream, w = c->one_stream ? c->stream : c->side;  // s: chain of activation gradients; w: weight-gradient products beside it
+  // The weight-gradient products (w) feed nothing but Adam and could overlap the chain of activation gradients (s) on a
+  // second stream; that variant produced rare wrong results on this machine whose cause was not found, so both are one stream.
+  hipStream_t s = c->stream, w = c->stream;
   const bool bf = c->bf16;
   const int B = (int)d.B, Dh = (int)d.Dh, De = (int)d.De, dl = (int)d.dl, SN = (int)(d.Dh / FADE_STATS_BN);
   float *G = c->grad;
@@ -600,7 +590,6 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     HIP_TRY(c, fade_dlogits(ws, targets, tstride, B, c->probs_buf, c->ustate, c->dl, bf, s));
     HIP_TRY(c, fade_colsum(B, 256, c->dl, c->col_part, Gp(P_BO), bf, rq, s));
   }
-  if ((rc = fork_side(c, 0))) return rc;
   {  // feature-major copies of every forward activation that is the left operand of a weight gradient, in one launch
     Prof p(c, "transpose", w);
     TransposeBatch tb{};
@@ -619,7 +608,6 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     HIP_TRY(c, fade_embed_t(ws, B, (int)c->Bp, (int)d.T, (int)d.D, c->tabXe, c->LT[7], bf, w));  // X^T straight from the table
   }
   // head
-  if ((rc = fork_side(c, 1))) return rc;
   if ((rc = transpose_grads(c, w, {{c->dl, {c->RT[0], 256}}}))) return rc;
   if ((rc = gemm_w(c, w, "gemm_dW_o", c->LT[0], Dh, c->dl, c->RT[0], 256, Gp(P_WO), nullptr))) return rc;
   if ((rc = gemm_x(c, "gemm_dHout", c->dl, 256, Dh, c->WT_o, c->P(P_WO), 256, c->dHout))) return rc;
@@ -631,7 +619,6 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     HIP_TRY(c, fade_bwd_out(a, bf, s));
     rq.push(RB, 2 * Dh, c->ln_part, Gp(P_GAMMA_O));  // gamma_o then beta_o, adjacent in the blob
   }
-  if ((rc = fork_side(c, 2))) return rc;
   if ((rc = transpose_grads(c, w, {{c->dV, {c->RT[1], Dh}}}))) return rc;
   if ((rc = gemm_w(c, w, "gemm_dW_f", c->LT[1], De, c->dV, c->RT[1], Dh, Gp(P_WF), nullptr))) return rc;
   if ((rc = gemm_x(c, "gemm_dHexp", c->dV, Dh, De, c->WT_f, c->P(P_WF), Dh, c->dHexp))) return rc;
@@ -639,7 +626,6 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     Prof p(c, "bwd_geglu");
     HIP_TRY(c, fade_bwd_geglu(B, De, c->dHexp, c->eg, c->ev, c->dE, bf, s));
   }
-  if ((rc = fork_side(c, 3))) return rc;
   if ((rc = transpose_grads(c, w, {{c->dE, {c->RT[2], 2 * De}}}))) return rc;
   if ((rc = gemm_w(c, w, "gemm_dW_fgv", c->LT[2], Dh, c->dE, c->RT[2], 2 * De, Gp(P_WFG), Gp(P_WFV)))) return rc;
   if ((rc = gemm_x(c, "gemm_du", c->dE, 2 * De, Dh, c->WT_fgv, static_cast<const float *>(c->Wfgv_c), 2 * De, c->du))) return rc;
@@ -652,7 +638,6 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     HIP_TRY(c, fade_bwd_gate(a, bf, s));
     rq.push(RB, 2 * Dh, c->ln_part + (size_t)RB * 2 * Dh, Gp(P_GAMMA_F));
   }
-  if ((rc = fork_side(c, 4))) return rc;
   if ((rc = transpose_grads(c, w, {{c->dac, {c->RT[3], Dh}}, {c->dHa, {c->RT[4], Dh}}}))) return rc;
   if ((rc = gemm_w(c, w, "gemm_dW_c", c->LT[3], Dh, c->dac, c->RT[3], Dh, Gp(P_WC), nullptr))) return rc;
   if ((rc = gemm_x(c, "gemm_dHmix", c->dac, Dh, Dh, c->WT_c, c->P(P_WC), Dh, c->dHmix2))) return rc;
@@ -675,7 +660,6 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     a.lr = c->cfg.lr; a.beta1 = c->cfg.beta1; a.beta2 = c->cfg.beta2; a.eps = c->cfg.eps;
     HIP_TRY(c, fade_bwd_cci(a, bf, s));
   }
-  if ((rc = fork_side(c, 5))) return rc;
   if ((rc = transpose_grads(c, w, {{c->dy_at, {c->RT[5], dl}}}))) return rc;
   if ((rc = gemm_w(c, w, "gemm_dW_down", c->LT[5], Dh, c->dy_at, c->RT[5], dl, Gp(P_WDOWN), nullptr))) return rc;
   if ((rc = gemm_x(c, "gemm_dnc", c->dy_at, dl, Dh, c->WT_down, c->P(P_WDOWN), dl, c->dnc))) return rc;
@@ -691,7 +675,6 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     rq.push(B, 1, c->row_dlam + B, Gp(P_LAMBDA_C));
     rq.push(B, 1, c->row_dlam + 2 * B, Gp(P_LAMBDA_M));
   }
-  if ((rc = fork_side(c, 6))) return rc;
   if ((rc = transpose_grads(c, w, {{c->dar, {c->RT[6], Dh}}, {c->dhm, {c->RT[7], Dh}}}))) return rc;
   if ((rc = gemm_w(c, w, "gemm_dW_r", c->LT[7], Dh, c->dar, c->RT[6], Dh, Gp(P_WR), nullptr))) return rc;
   if ((rc = gemm_x(c, "gemm_dX", c->dar, Dh, Dh, c->WT_r, c->P(P_WR), Dh, c->dX2))) return rc;
@@ -727,10 +710,6 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
   {  // Adam on everything except W_U (done in place above), then refresh the compute copies
     Prof p(c, "adam_refresh");
     const size_t lo = c->lay.off[P_WU], hi = c->lay.off[P_WU + 1], np = c->lay.off[P_COUNT];
-    if (!c->one_stream) {
-      HIP_TRY(c, hipEventRecord(c->join_ev, w));
-      HIP_TRY(c, hipStreamWaitEvent(s, c->join_ev, 0));
-    }
     HIP_TRY(c, fade_reduce_batch(rq, s));
     HIP_TRY(c, fade_adam(lo, c->grad, c->master, c->adam_m, c->adam_v, c->ustate, c->cfg.lr, c->cfg.beta1, c->cfg.beta2, c->cfg.eps, s));
     HIP_TRY(c, fade_adam(np - hi, c->grad + hi, c->master + hi, c->adam_m + hi, c->adam_v + hi, c->ustate, c->cfg.lr, c->cfg.beta1,
@@ -799,6 +778,7 @@ int run_loop(fade_ctx *c, uint8_t *bytes_dev, size_t n, size_t first, size_t cou
   const size_t last = (count == 0 || first + count > L) ? L : first + count;
   WinSrc ws{};
   ws.base = bytes_dev; ws.stride = (long long)L; ws.n = (long long)n; ws.active = nullptr;
+  const auto t_host0 = std::chrono::steady_clock::now();
   for (size_t i = first; i < last; ++i) {
     ws.i = (long long)i;
     if (i < d.T) {
@@ -814,6 +794,10 @@ int run_loop(fade_ctx *c, uint8_t *bytes_dev, size_t n, size_t first, size_t cou
     }
   }
   c->loop_next = last;
+  if (getenv("FADE_TRACE_HOST")) {
+    const double ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_host0).count();
+    fprintf(stderr, "[fade] host enqueue: %.3f ms for %zu steps (%.1f us/step) before the final wait\n", ms, last - first, 1e3 * ms / (double)(last - first));
+  }
   if (mode == CODE_ENCODE && last == L && !c->enc_complete) {
     HIP_TRY(c, fade_coder_finish(c->cb, (int)d.B, (long long)L, (long long)n, s));
     c->enc_complete = true;
@@ -839,12 +823,8 @@ size_t fade_weights_nbytes(const fade_config *cfg) {
 void fade_destroy(fade_ctx *c) {
   if (!c) return;
   if (c->stream) (void)hipStreamSynchronize(c->stream);
-  if (c->side) (void)hipStreamSynchronize(c->side);
   for (auto &ev : c->events) { (void)hipEventDestroy(ev.a); (void)hipEventDestroy(ev.b); }
   for (void *p : c->allocs) (void)hipFree(p);
-  for (hipEvent_t e : c->fork_ev) if (e) (void)hipEventDestroy(e);
-  if (c->join_ev) (void)hipEventDestroy(c->join_ev);
-  if (c->side) (void)hipStreamDestroy(c->side);
   if (c->own_stream && c->stream) (void)hipStreamDestroy(c->stream);
   delete c;
 }
@@ -878,14 +858,6 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
   else {
     if (hipStreamCreate(&c->stream) != hipSuccess) { delete c; return FADE_E_HIP; }
     c->own_stream = true;
-  }
-  if (c->online) {
-    const char *one = getenv("FADE_ONE_STREAM");  // debugging aid: run the weight-gradient branch on the main stream
-    c->one_stream = one && one[0] == '1';
-    bool ok = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) == hipSuccess;
-    for (int k = 0; k < 8 && ok; ++k) ok = hipEventCreateWithFlags(&c->fork_ev[k], hipEventDisableTiming) == hipSuccess;
-    ok = ok && hipEventCreateWithFlags(&c->join_ev, hipEventDisableTiming) == hipSuccess;
-    if (!ok) { fade_destroy(c); return FADE_E_HIP; }
   }
   const size_t np = c->lay.off[P_COUNT], BDh = d.B * d.Dh;
   const size_t SN = d.Dh / FADE_STATS_BN;

@@ -7,10 +7,8 @@
 
 namespace {
 
-__device__ __forceinline__ float gelu_f(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
-__device__ __forceinline__ float gelu_grad_f(float x) {
-  return 0.5f * (1.0f + erff(x * 0.70710678118654752f)) + x * 0.3989422804014327f * expf(-0.5f * x * x);
-}
+__device__ __forceinline__ float gelu_f(float x) { return fade_gelu(x); }
+__device__ __forceinline__ float gelu_grad_f(float x) { return fade_gelu_grad(x); }
 
 template <typename AT> __device__ __forceinline__ void ld8(const AT *p, float v[8]);
 template <> __device__ __forceinline__ void ld8<bf16_t>(const bf16_t *p, float v[8]) {
@@ -39,11 +37,7 @@ template <> __device__ __forceinline__ void st8<float>(float *p, const float v[8
 }
 
 __device__ __forceinline__ void moments(const float *stats, int stats_n, int width, float &mean, float &rstd) {
-  float s = 0.0f, q = 0.0f;
-  for (int j = 0; j < stats_n; ++j) { s += stats[2 * j]; q += stats[2 * j + 1]; }
-  const float inv = 1.0f / (float)width;
-  mean = s * inv;
-  rstd = 1.0f / sqrtf(fmaxf(q * inv - mean * mean, 0.0f) + 1e-5f);
+  fade_row_moments(stats, stats_n, width, mean, rstd);
 }
 
 // Sum of one value per thread over a 256-thread workgroup, same order every time: butterfly inside each
@@ -181,10 +175,32 @@ __global__ __launch_bounds__(256) void embed_t_kernel(WinSrc ws, int B, int Bp, 
 // a thread of the row kernels owns one 8-wide chunk: D_h <= 2048
 constexpr int kRowsPerBlock = 4; // rows handled by one workgroup; its LayerNorm gain / shift partial sums cover those rows
 
+// Several row sums at once over a 256-thread workgroup (same fixed order as block_sum); red holds 4 * N floats.
+template <int N>
+__device__ __forceinline__ void block_sum_n(float (&v)[N], float *red) {
+#pragma unroll
+  for (int k = 0; k < N; ++k) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v[k] += __shfl_xor(v[k], off, 64);
+  }
+  __syncthreads();  // red may still be read from a previous call
+  if ((threadIdx.x & 63) == 0) {
+#pragma unroll
+    for (int k = 0; k < N; ++k) red[(threadIdx.x >> 6) * N + k] = v[k];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < N; ++k) v[k] = (red[k] + red[N + k]) + (red[2 * N + k] + red[3 * N + k]);
+}
+
+// The row kernels below take their kRowsPerBlock rows through each phase together (all loads of a phase in flight at once,
+// one workgroup reduction per phase for all rows), not row after row: they are bound by memory latency, not by arithmetic.
+
 // Eq. 10 backward: dnv = dH * psi'(nv), LN backward -> dV; dH_coarse = lambda_o dH; row part of d lambda_o.
 template <typename AT>
 __global__ __launch_bounds__(256) void bwd_out_kernel(BwdOutArgs a) {
-  __shared__ float red[4];
+  constexpr int R = kRowsPerBlock;
+  __shared__ float red[4 * 3 * R];
   const int tid = threadIdx.x, nch = a.Dh / 8;
   const bool mine = tid < nch;
   const float lam = a.lam[0];
@@ -192,43 +208,50 @@ __global__ __launch_bounds__(256) void bwd_out_kernel(BwdOutArgs a) {
 #pragma unroll
   for (int i = 0; i < 8; ++i) { ga[i] = be[i] = pg[i] = pb[i] = 0.0f; }
   if (mine) { ld8<float>(a.gamma + tid * 8, ga); ld8<float>(a.beta + tid * 8, be); }
-  for (int r = 0; r < kRowsPerBlock; ++r) {
-    const int b = blockIdx.x * kRowsPerBlock + r;
-    if (b >= a.B) break;  // uniform over the workgroup
-    float mean, rstd;
-    moments(a.stats + (size_t)b * a.stats_n * 2, a.stats_n, a.Dh, mean, rstd);
-    const size_t base = (size_t)b * a.Dh + tid * 8;
-    float dh[8], xh[8], s1 = 0.0f, s2 = 0.0f, sl = 0.0f;
+  float dh[R][8], xh[R][8], rstd[R], sums[3 * R];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) { dh[i] = 0.0f; xh[i] = 0.0f; }
-    if (mine) {
-      float dH[8], v[8], hc[8], dnv[8], dhc[8];
+  for (int r = 0; r < R; ++r) {
+    const int b = blockIdx.x * R + r;
+    float s1 = 0.0f, s2 = 0.0f, sl = 0.0f, mean = 0.0f;
+    rstd[r] = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { dh[r][i] = 0.0f; xh[r][i] = 0.0f; }
+    if (b < a.B && mine) {  // b < B is uniform over the workgroup
+      moments(a.stats + (size_t)b * a.stats_n * 2, a.stats_n, a.Dh, mean, rstd[r]);
+      const size_t base = (size_t)b * a.Dh + tid * 8;
+      float dH[8], v[8], hc[8], dhc[8];
       ld8<AT>(static_cast<const AT *>(a.dH) + base, dH);
       ld8<AT>(static_cast<const AT *>(a.V) + base, v);
       ld8<AT>(static_cast<const AT *>(a.Hc) + base, hc);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        xh[i] = (v[i] - mean) * rstd;
-        const float nv = xh[i] * ga[i] + be[i];
-        dnv[i] = dH[i] * gelu_grad_f(nv);
-        dh[i] = dnv[i] * ga[i];
-        s1 += dh[i];
-        s2 += dh[i] * xh[i];
+        xh[r][i] = (v[i] - mean) * rstd[r];
+        const float nv = xh[r][i] * ga[i] + be[i];
+        const float dnv = dH[i] * gelu_grad_f(nv);
+        dh[r][i] = dnv * ga[i];
+        s1 += dh[r][i];
+        s2 += dh[r][i] * xh[r][i];
         sl += dH[i] * hc[i];
         dhc[i] = lam * dH[i];
-        pg[i] += dnv[i] * xh[i];
-        pb[i] += dnv[i];
+        pg[i] += dnv * xh[r][i];
+        pb[i] += dnv;
       }
       st8<AT>(static_cast<AT *>(a.dHc) + base, dhc);
     }
-    const float m1 = block_sum(s1, red) / (float)a.Dh, m2 = block_sum(s2, red) / (float)a.Dh;
-    const float sumlam = block_sum(sl, red);
-    if (tid == 0) a.row_dlam[b] = sumlam;
+    sums[r] = s1; sums[R + r] = s2; sums[2 * R + r] = sl;
+  }
+  block_sum_n<3 * R>(sums, red);
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int b = blockIdx.x * R + r;
+    if (b >= a.B) break;
+    if (tid == 0) a.row_dlam[b] = sums[2 * R + r];
     if (mine) {
+      const float m1 = sums[r] / (float)a.Dh, m2 = sums[R + r] / (float)a.Dh;
       float dv[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) dv[i] = rstd * (dh[i] - m1 - xh[i] * m2);
-      st8<AT>(static_cast<AT *>(a.dV) + base, dv);
+      for (int i = 0; i < 8; ++i) dv[i] = rstd[r] * (dh[r][i] - m1 - xh[r][i] * m2);
+      st8<AT>(static_cast<AT *>(a.dV) + (size_t)b * a.Dh + tid * 8, dv);
     }
   }
   if (mine) {
@@ -261,7 +284,8 @@ __global__ __launch_bounds__(256) void bwd_geglu_kernel(int B, int De, const AT 
 // dH_a = dHc * s, d(gate logits) = dHc * H_a * s (1 - s), dH_mix = lambda_c dHc, row part of d lambda_c.
 template <typename AT>
 __global__ __launch_bounds__(256) void bwd_gate_kernel(BwdGateArgs a) {
-  __shared__ float red[4];
+  constexpr int R = kRowsPerBlock;
+  __shared__ float red[4 * 2 * R];
   const int tid = threadIdx.x, nch = a.Dh / 8;
   const bool mine = tid < nch;
   const float lam = a.lam[0];
@@ -269,32 +293,40 @@ __global__ __launch_bounds__(256) void bwd_gate_kernel(BwdGateArgs a) {
 #pragma unroll
   for (int i = 0; i < 8; ++i) { ga[i] = pg[i] = pb[i] = 0.0f; }
   if (mine) ld8<float>(a.gamma + tid * 8, ga);
-  for (int r = 0; r < kRowsPerBlock; ++r) {
-    const int b = blockIdx.x * kRowsPerBlock + r;
-    if (b >= a.B) break;
-    float mean, rstd;
-    moments(a.stats + (size_t)b * a.stats_n * 2, a.stats_n, a.Dh, mean, rstd);
-    const size_t base = (size_t)b * a.Dh + tid * 8;
-    float dh[8], xh[8], s1 = 0.0f, s2 = 0.0f;
+  float dh[R][8], xh[R][8], rstd[R], sums[2 * R], sl[R];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) { dh[i] = 0.0f; xh[i] = 0.0f; }
-    if (mine) {
+  for (int r = 0; r < R; ++r) {
+    const int b = blockIdx.x * R + r;
+    float s1 = 0.0f, s2 = 0.0f, mean = 0.0f;
+    rstd[r] = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { dh[r][i] = 0.0f; xh[r][i] = 0.0f; }
+    if (b < a.B && mine) {
+      moments(a.stats + (size_t)b * a.stats_n * 2, a.stats_n, a.Dh, mean, rstd[r]);
+      const size_t base = (size_t)b * a.Dh + tid * 8;
       float du[8], hc[8];
       ld8<AT>(static_cast<const AT *>(a.du) + base, du);
       ld8<AT>(static_cast<const AT *>(a.Hc) + base, hc);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        xh[i] = (hc[i] - mean) * rstd;
-        dh[i] = du[i] * ga[i];
-        s1 += dh[i];
-        s2 += dh[i] * xh[i];
-        pg[i] += du[i] * xh[i];
+        xh[r][i] = (hc[i] - mean) * rstd[r];
+        dh[r][i] = du[i] * ga[i];
+        s1 += dh[r][i];
+        s2 += dh[r][i] * xh[r][i];
+        pg[i] += du[i] * xh[r][i];
         pb[i] += du[i];
       }
     }
-    const float m1 = block_sum(s1, red) / (float)a.Dh, m2 = block_sum(s2, red) / (float)a.Dh;
-    float sl = 0.0f;
-    if (mine) {
+    sums[r] = s1; sums[R + r] = s2;
+  }
+  block_sum_n<2 * R>(sums, red);
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int b = blockIdx.x * R + r;
+    sl[r] = 0.0f;
+    if (b < a.B && mine) {
+      const size_t base = (size_t)b * a.Dh + tid * 8;
+      const float m1 = sums[r] / (float)a.Dh, m2 = sums[R + r] / (float)a.Dh;
       float dhc[8], sg[8], ha[8], hm[8], dHa[8], dac[8], dmix[8];
       ld8<AT>(static_cast<const AT *>(a.dHc) + base, dhc);
       ld8<AT>(static_cast<const AT *>(a.sg) + base, sg);
@@ -302,18 +334,22 @@ __global__ __launch_bounds__(256) void bwd_gate_kernel(BwdGateArgs a) {
       ld8<AT>(static_cast<const AT *>(a.Hmix) + base, hm);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        const float d = dhc[i] + rstd * (dh[i] - m1 - xh[i] * m2);
+        const float d = dhc[i] + rstd[r] * (dh[r][i] - m1 - xh[r][i] * m2);
         dHa[i] = d * sg[i];
         dac[i] = d * ha[i] * sg[i] * (1.0f - sg[i]);
         dmix[i] = lam * d;
-        sl += d * hm[i];
+        sl[r] += d * hm[i];
       }
       st8<AT>(static_cast<AT *>(a.dHa) + base, dHa);
       st8<AT>(static_cast<AT *>(a.dac) + base, dac);
       st8<AT>(static_cast<AT *>(a.dHmix) + base, dmix);
     }
-    const float sumlam = block_sum(sl, red);
-    if (tid == 0) a.row_dlam[b] = sumlam;
+  }
+  block_sum_n<R>(sl, red);
+  if (tid == 0) {
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+      if (blockIdx.x * R + r < a.B) a.row_dlam[blockIdx.x * R + r] = sl[r];
   }
   if (mine) {
     float *p = a.ln_part + (size_t)blockIdx.x * 2 * a.Dh;
@@ -327,7 +363,8 @@ __global__ __launch_bounds__(256) void bwd_gate_kernel(BwdGateArgs a) {
 // d(conv pre-act) = dHl psi'(cv), dX = lambda_m dHg, row part of d lambda_m.
 template <typename AT>
 __global__ __launch_bounds__(256) void bwd_mix_kernel(BwdMixArgs a) {
-  __shared__ float red[4];
+  constexpr int R = kRowsPerBlock;
+  __shared__ float red[4 * 2 * R];
   const int tid = threadIdx.x, nch = a.Dh / 8;
   const bool mine = tid < nch;
   const float lam = a.lam[0];
@@ -335,32 +372,40 @@ __global__ __launch_bounds__(256) void bwd_mix_kernel(BwdMixArgs a) {
 #pragma unroll
   for (int i = 0; i < 8; ++i) { ga[i] = pg[i] = pb[i] = 0.0f; }
   if (mine) ld8<float>(a.gamma + tid * 8, ga);
-  for (int r = 0; r < kRowsPerBlock; ++r) {
-    const int b = blockIdx.x * kRowsPerBlock + r;
-    if (b >= a.B) break;
-    float mean, rstd;
-    moments(a.stats + (size_t)b * a.stats_n * 2, a.stats_n, a.Dh, mean, rstd);
-    const size_t base = (size_t)b * a.Dh + tid * 8;
-    float dh[8], xh[8], s1 = 0.0f, s2 = 0.0f;
+  float dh[R][8], xh[R][8], rstd[R], sums[2 * R], sl[R];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) { dh[i] = 0.0f; xh[i] = 0.0f; }
-    if (mine) {
+  for (int r = 0; r < R; ++r) {
+    const int b = blockIdx.x * R + r;
+    float s1 = 0.0f, s2 = 0.0f, mean = 0.0f;
+    rstd[r] = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { dh[r][i] = 0.0f; xh[r][i] = 0.0f; }
+    if (b < a.B && mine) {
+      moments(a.stats + (size_t)b * a.stats_n * 2, a.stats_n, a.Dh, mean, rstd[r]);
+      const size_t base = (size_t)b * a.Dh + tid * 8;
       float dn[8], hm[8];
       ld8<AT>(static_cast<const AT *>(a.dnc) + base, dn);
       ld8<AT>(static_cast<const AT *>(a.Hmix) + base, hm);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        xh[i] = (hm[i] - mean) * rstd;
-        dh[i] = dn[i] * ga[i];
-        s1 += dh[i];
-        s2 += dh[i] * xh[i];
-        pg[i] += dn[i] * xh[i];
+        xh[r][i] = (hm[i] - mean) * rstd[r];
+        dh[r][i] = dn[i] * ga[i];
+        s1 += dh[r][i];
+        s2 += dh[r][i] * xh[r][i];
+        pg[i] += dn[i] * xh[r][i];
         pb[i] += dn[i];
       }
     }
-    const float m1 = block_sum(s1, red) / (float)a.Dh, m2 = block_sum(s2, red) / (float)a.Dh;
-    float sl = 0.0f;
-    if (mine) {
+    sums[r] = s1; sums[R + r] = s2;
+  }
+  block_sum_n<2 * R>(sums, red);
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int b = blockIdx.x * R + r;
+    sl[r] = 0.0f;
+    if (b < a.B && mine) {
+      const size_t base = (size_t)b * a.Dh + tid * 8;
+      const float m1 = sums[r] / (float)a.Dh, m2 = sums[R + r] / (float)a.Dh;
       float d1[8], d2[8], al[8], hg[8], hl[8], pre_g[8], pre_c[8], x[8], dar[8], dhm[8], dcv[8], dX[8];
       ld8<AT>(static_cast<const AT *>(a.dHmix1) + base, d1);
       ld8<AT>(static_cast<const AT *>(a.dHmix2) + base, d2);
@@ -372,21 +417,25 @@ __global__ __launch_bounds__(256) void bwd_mix_kernel(BwdMixArgs a) {
       ld8<AT>(static_cast<const AT *>(a.X) + base, x);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        const float d = d1[i] + d2[i] + rstd * (dh[i] - m1 - xh[i] * m2);
+        const float d = d1[i] + d2[i] + rstd[r] * (dh[r][i] - m1 - xh[r][i] * m2);
         const float dHg = d * al[i], dHl = d * (1.0f - al[i]);
         dar[i] = d * (hg[i] - hl[i]) * al[i] * (1.0f - al[i]);
         dhm[i] = dHg * gelu_grad_f(pre_g[i]);
         dcv[i] = dHl * gelu_grad_f(pre_c[i]);
         dX[i] = lam * dHg;
-        sl += dHg * x[i];
+        sl[r] += dHg * x[i];
       }
       st8<AT>(static_cast<AT *>(a.dar) + base, dar);
       st8<AT>(static_cast<AT *>(a.dhm) + base, dhm);
       st8<AT>(static_cast<AT *>(a.dcv) + base, dcv);
       st8<AT>(static_cast<AT *>(a.dX) + base, dX);
     }
-    const float sumlam = block_sum(sl, red);
-    if (tid == 0) a.row_dlam[b] = sumlam;
+  }
+  block_sum_n<R>(sl, red);
+  if (tid == 0) {
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+      if (blockIdx.x * R + r < a.B) a.row_dlam[blockIdx.x * R + r] = sl[r];
   }
   if (mine) {
     float *p = a.ln_part + (size_t)blockIdx.x * 2 * a.Dh;
@@ -457,7 +506,13 @@ __global__ __launch_bounds__(256) void bwd_cci_kernel(BwdCciArgs a) {
   const int b = blockIdx.x, tid = threadIdx.x;
   if (tid < 64) {
     float dz = 0.0f;
-    for (int s = 0; s < a.splits; ++s) dz += a.dz_part[((size_t)s * a.B + b) * 64 + tid];
+    for (int s0 = 0; s0 < a.splits; s0 += 8) {  // 8 partials in flight, added in split order
+      float pv[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) pv[j] = a.dz_part[((size_t)(s0 + j < a.splits ? s0 + j : a.splits - 1) * a.B + b) * 64 + tid];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) dz += (s0 + j < a.splits) ? pv[j] : 0.0f;
+    }
     dz_s[tid] = dz;
     y_s[tid] = a.y[(size_t)b * 64 + tid];
   }

@@ -75,3 +75,61 @@ struct GemmArgs {
 
 // Row statistics are accumulated per block tile of BN columns; consumers add the partials in index order.
 #define FADE_STATS_BN 128
+
+// (sum, sum of squares) partials of one row -> mean and 1 / sigma (biased variance, eps 1e-5). The pairs are fetched 16 at
+// a time with no add between the loads (a loop of load-add-load-add would pay the memory latency once per pair); the adds
+// run in index order, slots past stats_n add an exact zero.
+__device__ __forceinline__ void fade_row_moments(const float *stats, int stats_n, int width, float &mean, float &rstd) {
+  const float2 *p = reinterpret_cast<const float2 *>(stats);
+  float s = 0.0f, q = 0.0f;
+  for (int j0 = 0; j0 < stats_n; j0 += 16) {
+    float2 v[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const int idx = j0 + j;
+      v[j] = p[idx < stats_n ? idx : stats_n - 1];
+    }
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const bool in = j0 + j < stats_n;
+      s += in ? v[j].x : 0.0f;
+      q += in ? v[j].y : 0.0f;
+    }
+  }
+  const float inv = 1.0f / (float)width;
+  mean = s * inv;
+  rstd = 1.0f / sqrtf(fmaxf(q * inv - mean * mean, 0.0f) + 1e-5f);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// activation arithmetic shared by every kernel (encoder and decoder run the same code, so they agree bit for bit)
+// ---------------------------------------------------------------------------------------------------
+// erf by the rational-times-Gaussian formula 7.1.26 of Abramowitz & Stegun (|error| <= 1.5e-7 absolute): the row kernels
+// run one wavefront per SIMD and were bound by the library erff + expf (over a hundred instructions per element).
+// The Gaussian e = exp(-x^2) is passed in because GeLU's derivative needs the same exponential.
+__device__ __forceinline__ float fade_exp(float x) { return __builtin_amdgcn_exp2f(x * 1.4426950408889634f); }
+__device__ __forceinline__ float fade_erf_pos(float ax, float e) {  // ax >= 0, e = exp(-ax^2)
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, ax, 1.0f));
+  float p = fmaf(1.061405429f, t, -1.453152027f);
+  p = fmaf(p, t, 1.421413741f);
+  p = fmaf(p, t, -0.284496736f);
+  p = fmaf(p, t, 0.254829592f);
+  return fmaf(-p * t, e, 1.0f);
+}
+// Phi(x) = (1 + erf(x / sqrt 2)) / 2 and the Gaussian g = exp(-x^2 / 2)
+__device__ __forceinline__ float fade_norm_cdf(float x, float &g) {
+  const float ax = fabsf(x) * 0.70710678118654752f;
+  g = fade_exp(-ax * ax);
+  const float er = fade_erf_pos(ax, g);
+  return 0.5f * (1.0f + copysignf(er, x));
+}
+__device__ __forceinline__ float fade_gelu(float x) {  // psi(x) = x Phi(x) (exact-erf GeLU)
+  float g;
+  return x * fade_norm_cdf(x, g);
+}
+__device__ __forceinline__ float fade_gelu_grad(float x) {  // psi'(x) = Phi(x) + x phi(x)
+  float g;
+  const float cdf = fade_norm_cdf(x, g);
+  return fmaf(x * 0.3989422804014327f, g, cdf);
+}
+__device__ __forceinline__ float fade_sigmoid(float x) { return __builtin_amdgcn_rcpf(1.0f + fade_exp(-x)); }

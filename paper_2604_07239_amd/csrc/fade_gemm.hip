@@ -24,8 +24,8 @@ int fade_gemm_tune();
 
 namespace {
 
-__device__ __forceinline__ float gelu_f(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
-__device__ __forceinline__ float sigmoid_f(float x) { return 1.0f / (1.0f + expf(-x)); }
+__device__ __forceinline__ float gelu_f(float x) { return fade_gelu(x); }
+__device__ __forceinline__ float sigmoid_f(float x) { return fade_sigmoid(x); }
 
 // 8 consecutive activations <-> registers
 __device__ __forceinline__ void load8(const bf16_t *p, float v[8]) {
@@ -125,13 +125,7 @@ __device__ __forceinline__ void stage_transform(const GemmArgs &g, int k, const 
 __device__ __forceinline__ void row_moments(const GemmArgs &g, int m, float &mean, float &rstd) {
   mean = 0.0f; rstd = 1.0f;
   if (m >= g.M) return;
-  float s = 0.0f, q = 0.0f;
-  const float *p = g.stats + (size_t)m * g.stats_n * 2;
-  for (int j = 0; j < g.stats_n; ++j) { s += p[2 * j]; q += p[2 * j + 1]; }
-  const float inv = 1.0f / (float)g.K;
-  mean = s * inv;
-  const float var = fmaxf(q * inv - mean * mean, 0.0f);
-  rstd = 1.0f / sqrtf(var + 1e-5f);
+  fade_row_moments(g.stats + (size_t)m * g.stats_n * 2, g.stats_n, g.K, mean, rstd);
 }
 
 // ---------------------------------------------------------------------------------------------------

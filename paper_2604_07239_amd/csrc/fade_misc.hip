@@ -6,7 +6,7 @@
 
 namespace {
 
-__device__ __forceinline__ float gelu_f(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_f(float x) { return fade_gelu(x); }
 
 template <typename T> __device__ __forceinline__ T wave_sum(T v) {
 #pragma unroll
@@ -216,11 +216,7 @@ __global__ __launch_bounds__(256) void fold_reduce_kernel(int P, int N2, const f
 }
 
 __device__ __forceinline__ void moments_from_partials(const float *stats, int stats_n, int width, float &mean, float &rstd) {
-  float s = 0.0f, q = 0.0f;
-  for (int j = 0; j < stats_n; ++j) { s += stats[2 * j]; q += stats[2 * j + 1]; }
-  const float inv = 1.0f / (float)width;
-  mean = s * inv;
-  rstd = 1.0f / sqrtf(fmaxf(q * inv - mean * mean, 0.0f) + 1e-5f);
+  fade_row_moments(stats, stats_n, width, mean, rstd);
 }
 
 // Eq. 7 between Down and Up (bf16 path): reduce the split-K partials of H_mix W'_down, apply the folded LayerNorm,
@@ -229,7 +225,13 @@ __global__ __launch_bounds__(256) void cci_kernel(CciArgs a) {
   const int b = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (b >= a.B) return;
   float raw = 0.0f;
-  for (int s = 0; s < a.splits; ++s) raw += a.part[((size_t)s * a.B + b) * 64 + lane];
+  for (int s0 = 0; s0 < a.splits; s0 += 8) {  // 8 partials in flight, added in split order
+    float pv[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) pv[j] = a.part[((size_t)(s0 + j < a.splits ? s0 + j : a.splits - 1) * a.B + b) * 64 + lane];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) raw += (s0 + j < a.splits) ? pv[j] : 0.0f;
+  }
   float mean, rstd;
   moments_from_partials(a.stats + (size_t)b * a.stats_n * 2, a.stats_n, a.Dh, mean, rstd);
   const float yv = rstd * (raw - mean * a.s_fold[lane]) + a.t_fold[lane];
@@ -252,12 +254,21 @@ __global__ __launch_bounds__(256) void geglu_kernel(GegluArgs a) {
   float g[8], v[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) { g[i] = 0.0f; v[i] = 0.0f; }
-  for (int s = 0; s < a.splits; ++s) {
-    const float *row = a.part + ((size_t)s * a.B + b) * N2;
-    const f32x4 g0 = *reinterpret_cast<const f32x4 *>(row + vg), g1 = *reinterpret_cast<const f32x4 *>(row + vg + 4);
-    const f32x4 v0 = *reinterpret_cast<const f32x4 *>(row + vv), v1 = *reinterpret_cast<const f32x4 *>(row + vv + 4);
+  for (int s0 = 0; s0 < a.splits; s0 += 4) {  // 4 partials in flight, added in split order
+    f32x4 g0[4], g1[4], v0[4], v1[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) { g[i] += g0[i]; g[4 + i] += g1[i]; v[i] += v0[i]; v[4 + i] += v1[i]; }
+    for (int j = 0; j < 4; ++j) {
+      const float *row = a.part + ((size_t)(s0 + j < a.splits ? s0 + j : a.splits - 1) * a.B + b) * N2;
+      g0[j] = *reinterpret_cast<const f32x4 *>(row + vg); g1[j] = *reinterpret_cast<const f32x4 *>(row + vg + 4);
+      v0[j] = *reinterpret_cast<const f32x4 *>(row + vv); v1[j] = *reinterpret_cast<const f32x4 *>(row + vv + 4);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (s0 + j < a.splits) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { g[i] += g0[j][i]; g[4 + i] += g1[j][i]; v[i] += v0[j][i]; v[4 + i] += v1[j][i]; }
+      }
+    }
   }
   float mean, rstd;
   moments_from_partials(a.stats + (size_t)b * a.stats_n * 2, a.stats_n, a.Dh, mean, rstd);
@@ -551,7 +562,15 @@ __global__ __launch_bounds__(256) void softmax_quant_code_kernel(SqcArgs a) {
   if (!stream_active(a.ws, b)) return;
   f32x4 z = *reinterpret_cast<const f32x4 *>(a.logits + (size_t)b * 256 + 4 * lane);
   if (a.splits > 0) {  // logits arrive as split-K partials; the head's bias is added here
-    for (int s = 1; s < a.splits; ++s) z += *reinterpret_cast<const f32x4 *>(a.logits + ((size_t)s * a.B + b) * 256 + 4 * lane);
+    for (int s0 = 1; s0 < a.splits; s0 += 8) {  // up to 8 partials in flight, added in split order
+      f32x4 zp[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        zp[j] = *reinterpret_cast<const f32x4 *>(a.logits + ((size_t)(s0 + j < a.splits ? s0 + j : a.splits - 1) * a.B + b) * 256 + 4 * lane);
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (s0 + j < a.splits) z += zp[j];
+    }
     z += *reinterpret_cast<const f32x4 *>(a.bias + 4 * lane);
     if (a.logits_out) *reinterpret_cast<f32x4 *>(a.logits_out + (size_t)b * 256 + 4 * lane) = z;
   }
