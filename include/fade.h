@@ -82,8 +82,8 @@ size_t fade_weights_nbytes(const fade_config *cfg);
 /* Create a context: validates the configuration and allocates all device state (compute weights, rolling
  * caches M [B][H], per-stream memories W_U, activations, coder state; optimiser state in online mode).
  * Supported shapes: D % 32 == 0 (FADE_BF16) or D % 16 == 0 (FADE_F32), (T*D) % 128 == 0, H % 64 == 0 and
- * H <= 1024, d_low == 64, conv_k <= 4, H % cache_chunk == 0, cache_chunk <= 64; anything else is
- * FADE_E_BAD_CONFIG. No device, or a device ordinal out of range: FADE_E_HIP. *out is NULL on failure. */
+ * H <= 1024, d_low == 64, conv_k <= 4, H % cache_chunk == 0, cache_chunk <= 64; with FADE_ONLINE_ADAM also
+ * T*D <= 2048, D <= 32, T a divisor of 128 and D a divisor of 256; anything else is FADE_E_BAD_CONFIG. No device, or a device ordinal out of range: FADE_E_HIP. *out is NULL on failure. */
 int fade_create(const fade_config *cfg, fade_ctx **out);
 
 /* Load the canonical fp32 blob from host memory (copied; rounded to bf16 for FADE_BF16 matrix operands) and
