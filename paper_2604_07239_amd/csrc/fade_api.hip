@@ -137,7 +137,7 @@ struct fade_ctx {
   void *dl = nullptr, *dHout = nullptr, *dnv = nullptr, *dV = nullptr, *dHc = nullptr, *dHexp = nullptr, *dE = nullptr, *du = nullptr,
        *dHa = nullptr, *dac = nullptr, *dHmix1 = nullptr, *dHmix2 = nullptr, *dy_at = nullptr, *dnc = nullptr, *dar = nullptr,
        *dhm = nullptr, *dcv = nullptr, *dX1 = nullptr, *dX2 = nullptr, *dxl = nullptr;
-  void *LT[8] = {}, *RT[8] = {};  // feature-major copies [width][Bp] of weight-gradient operands (see backward())
+  void *LT[8] = {};  // left operands of the weight gradients that need a copy: LN(H_coarse), LN(H_mix) row-major (bf16 path); feature-major copies [width][Bp] of all eight (fp32 path)
   float *dz_part = nullptr, *dy = nullptr, *dgg = nullptr, *dgv = nullptr, *dxt = nullptr, *sym_sums = nullptr, *row_dlam = nullptr,
         *conv_part = nullptr, *tok_part = nullptr;
   float *ln_part = nullptr, *col_part = nullptr, *slot_part = nullptr, *emb_part = nullptr;
@@ -534,24 +534,40 @@ int forward(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint16_t
 // the online update: gradient of the mean NLL (Eq. 12) through the step, then Adam on every parameter
 // ---------------------------------------------------------------------------------------------------
 // dX = dY W^T. bf16: W^T lives as a second fragment set (wt_frag); fp32: W itself, read transposed.
-int gemm_x(fade_ctx *c, const char *name, const void *dY, int Kred, int Nout, const void *wt_frag, const float *w_f32, int ld_w, void *out) {
-  Prof p(c, name);
+GemmArgs args_x(fade_ctx *c, const void *dY, int Kred, int Nout, const void *wt_frag, const float *w_f32, int ld_w, void *out) {
   GemmArgs g{};
   g.M = (int)c->d.B; g.N = Nout; g.K = Kred; g.A = dY; g.lda = Kred; g.C = out; g.ldc = Nout;
   if (c->bf16) g.W = wt_frag;
   else { g.W = w_f32; g.wt = 1; g.ldb = ld_w; }
-  HIP_TRY(c, fade_gemm(GEMM_X_STORE, c->bf16, g, c->stream));
-  return FADE_OK;
+  return g;
 }
-// dW[Kw][N] = L^T R over the batch. LT: feature-major copy [Kw][Bp] of the left operand; R: gradient [Bp][N] (fp32 path),
-// RT: its feature-major copy [N][Bp] (bf16 path).
-int gemm_w(fade_ctx *c, hipStream_t st, const char *name, const void *LT, int Kw, const void *R, const void *RT, int N, float *dW, float *dW_pair) {
-  Prof p(c, name, st);
+// dW[Kw][N] = L^T R over the batch. bf16 path: both operands row-major as the forward / backward kernels left them
+// (L [B][ldL], R [Bp][N] with zero rows past the batch), turned on the way out of LDS. fp32 path: LT is a feature-major
+// copy [Kw][Bp] of L, R is read row-major.
+GemmArgs args_w(fade_ctx *c, const void *L, int ldL, const void *LT, int Kw, const void *R, int N, float *dW, float *dW_pair) {
   GemmArgs g{};
-  g.M = Kw; g.N = N; g.K = (int)c->Bp; g.A = LT; g.lda = (int)c->Bp; g.C = dW; g.C3 = dW_pair; g.ldc = N;
-  if (c->bf16) { g.W = RT; g.ldb = (int)c->Bp; }
-  else g.W = R;
-  HIP_TRY(c, fade_gemm(GEMM_W, c->bf16, g, st));
+  g.M = Kw; g.N = N; g.K = (int)c->Bp; g.C = dW; g.C3 = dW_pair; g.ldc = N; g.W = R;
+  if (c->bf16) { g.A = L; g.lda = ldL; g.a_rows = (int)c->d.B; g.ldb = N; }
+  else { g.A = LT; g.lda = (int)c->Bp; }
+  return g;
+}
+// The products of one backward phase consume the same gradient and are independent: one grouped launch (bf16 path), or
+// one launch each (fp32 path).
+struct PhaseGemms {
+  int n = 0;
+  int op[4];
+  GemmArgs g[4];
+  void add(int o, const GemmArgs &a) { op[n] = o; g[n++] = a; }
+};
+int run_phase(fade_ctx *c, const char *name, const PhaseGemms &ph) {
+  Prof p(c, name);
+  if (c->bf16) {
+    GemmGroup gg{};
+    for (int i = 0; i < ph.n; ++i) HIP_TRY(c, fade_gemm_group_add(gg, ph.op[i], ph.g[i]));
+    HIP_TRY(c, fade_gemm_group_launch(gg, c->stream));
+  } else {
+    for (int i = 0; i < ph.n; ++i) HIP_TRY(c, fade_gemm(ph.op[i] == GEMM_W_TN ? GEMM_W : ph.op[i], false, ph.g[i], c->stream));
+  }
   return FADE_OK;
 }
 TransposeArgs tr_desc(fade_ctx *c, const void *src, int ld, void *dst, const float *stats, const float *gamma, const float *beta) {
@@ -559,18 +575,6 @@ TransposeArgs tr_desc(fade_ctx *c, const void *src, int ld, void *dst, const flo
   t.src = src; t.ld = ld; t.dst = dst; t.Bp = (int)c->Bp; t.B = (int)c->d.B;
   t.stats = stats; t.stats_n = (int)(c->d.Dh / FADE_STATS_BN); t.width = ld; t.gamma = gamma; t.beta = beta;
   return t;
-}
-// feature-major copies of freshly produced gradients (bf16 path only: the fp32 product reads them row-major)
-int transpose_grads(fade_ctx *c, hipStream_t st, std::initializer_list<std::pair<const void *, std::pair<void *, int>>> items) {
-  if (!c->bf16) return FADE_OK;
-  Prof p(c, "transpose", st);
-  TransposeBatch tb{};
-  for (auto &it : items) {
-    tb.t[tb.count] = tr_desc(c, it.first, it.second.second, it.second.first, nullptr, nullptr, nullptr);
-    tb.N[tb.count++] = it.second.second;
-  }
-  HIP_TRY(c, fade_transpose_batch(tb, true, st));
-  return FADE_OK;
 }
 int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long tstride) {
   const Dims &d = c->d;
@@ -590,7 +594,14 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     HIP_TRY(c, fade_dlogits(ws, targets, tstride, B, c->probs_buf, c->ustate, c->dl, bf, s));
     HIP_TRY(c, fade_colsum(B, 256, c->dl, c->col_part, Gp(P_BO), bf, rq, s));
   }
-  {  // feature-major copies of every forward activation that is the left operand of a weight gradient, in one launch
+  if (bf) {  // the two left operands the forward pass never stores: LN(H_coarse), LN(H_mix), row-major
+    Prof p(c, "ln_apply", w);
+    LnApplyBatch lb{};
+    lb.count = 2; lb.B = B; lb.Dh = Dh; lb.stats_n = SN;
+    lb.a[0] = {c->Hc, c->LT[2], c->stats_f, c->P(P_GAMMA_F), c->P(P_BETA_F)};
+    lb.a[1] = {c->Hmix, c->LT[5], c->stats_c, c->P(P_GAMMA_C), c->P(P_BETA_C)};
+    HIP_TRY(c, fade_ln_apply(lb, true, w));
+  } else {  // fp32 path: feature-major copies of every forward activation that is the left operand of a weight gradient
     Prof p(c, "transpose", w);
     TransposeBatch tb{};
     auto add = [&](const void *src, int width, void *dst, const float *st, const float *ga, const float *be) {
@@ -604,13 +615,16 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     add(c->z, dl, c->LT[4], nullptr, nullptr, nullptr);
     add(c->Hmix, Dh, c->LT[5], c->stats_c, c->P(P_GAMMA_C), c->P(P_BETA_C)); // LN(H_mix)
     add(c->M, (int)d.Dc, c->LT[6], nullptr, nullptr, nullptr);
-    HIP_TRY(c, fade_transpose_batch(tb, bf, w));
-    HIP_TRY(c, fade_embed_t(ws, B, (int)c->Bp, (int)d.T, (int)d.D, c->tabXe, c->LT[7], bf, w));  // X^T straight from the table
+    HIP_TRY(c, fade_transpose_batch(tb, false, w));
+    HIP_TRY(c, fade_embed_t(ws, B, (int)c->Bp, (int)d.T, (int)d.D, c->tabXe, c->LT[7], false, w));  // X^T straight from the table
   }
   // head
-  if ((rc = transpose_grads(c, w, {{c->dl, {c->RT[0], 256}}}))) return rc;
-  if ((rc = gemm_w(c, w, "gemm_dW_o", c->LT[0], Dh, c->dl, c->RT[0], 256, Gp(P_WO), nullptr))) return rc;
-  if ((rc = gemm_x(c, "gemm_dHout", c->dl, 256, Dh, c->WT_o, c->P(P_WO), 256, c->dHout))) return rc;
+  {
+    PhaseGemms ph;
+    ph.add(GEMM_W_TN, args_w(c, c->Hout, Dh, c->LT[0], Dh, c->dl, 256, Gp(P_WO), nullptr));
+    ph.add(GEMM_X_STORE, args_x(c, c->dl, 256, Dh, c->WT_o, c->P(P_WO), 256, c->dHout));
+    if ((rc = run_phase(c, "gemms_head", ph))) return rc;
+  }
   {  // Eq. 10
     Prof p(c, "bwd_out");
     BwdOutArgs a{};
@@ -619,16 +633,22 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     HIP_TRY(c, fade_bwd_out(a, bf, s));
     rq.push(RB, 2 * Dh, c->ln_part, Gp(P_GAMMA_O));  // gamma_o then beta_o, adjacent in the blob
   }
-  if ((rc = transpose_grads(c, w, {{c->dV, {c->RT[1], Dh}}}))) return rc;
-  if ((rc = gemm_w(c, w, "gemm_dW_f", c->LT[1], De, c->dV, c->RT[1], Dh, Gp(P_WF), nullptr))) return rc;
-  if ((rc = gemm_x(c, "gemm_dHexp", c->dV, Dh, De, c->WT_f, c->P(P_WF), Dh, c->dHexp))) return rc;
+  {
+    PhaseGemms ph;
+    ph.add(GEMM_W_TN, args_w(c, c->Hexp, De, c->LT[1], De, c->dV, Dh, Gp(P_WF), nullptr));
+    ph.add(GEMM_X_STORE, args_x(c, c->dV, Dh, De, c->WT_f, c->P(P_WF), Dh, c->dHexp));
+    if ((rc = run_phase(c, "gemms_fnr_out", ph))) return rc;
+  }
   {  // Eq. 9
     Prof p(c, "bwd_geglu");
     HIP_TRY(c, fade_bwd_geglu(B, De, c->dHexp, c->eg, c->ev, c->dE, bf, s));
   }
-  if ((rc = transpose_grads(c, w, {{c->dE, {c->RT[2], 2 * De}}}))) return rc;
-  if ((rc = gemm_w(c, w, "gemm_dW_fgv", c->LT[2], Dh, c->dE, c->RT[2], 2 * De, Gp(P_WFG), Gp(P_WFV)))) return rc;
-  if ((rc = gemm_x(c, "gemm_du", c->dE, 2 * De, Dh, c->WT_fgv, static_cast<const float *>(c->Wfgv_c), 2 * De, c->du))) return rc;
+  {
+    PhaseGemms ph;
+    ph.add(GEMM_W_TN, args_w(c, c->LT[2], Dh, c->LT[2], Dh, c->dE, 2 * De, Gp(P_WFG), Gp(P_WFV)));
+    ph.add(GEMM_X_STORE, args_x(c, c->dE, 2 * De, Dh, c->WT_fgv, static_cast<const float *>(c->Wfgv_c), 2 * De, c->du));
+    if ((rc = run_phase(c, "gemms_fnr_in", ph))) return rc;
+  }
   {  // LN of Eq. 9 + Eq. 8
     Prof p(c, "bwd_gate");
     BwdGateArgs a{};
@@ -638,18 +658,17 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     HIP_TRY(c, fade_bwd_gate(a, bf, s));
     rq.push(RB, 2 * Dh, c->ln_part + (size_t)RB * 2 * Dh, Gp(P_GAMMA_F));
   }
-  if ((rc = transpose_grads(c, w, {{c->dac, {c->RT[3], Dh}}, {c->dHa, {c->RT[4], Dh}}}))) return rc;
-  if ((rc = gemm_w(c, w, "gemm_dW_c", c->LT[3], Dh, c->dac, c->RT[3], Dh, Gp(P_WC), nullptr))) return rc;
-  if ((rc = gemm_x(c, "gemm_dHmix", c->dac, Dh, Dh, c->WT_c, c->P(P_WC), Dh, c->dHmix2))) return rc;
-  // Eq. 7
-  if ((rc = gemm_w(c, w, "gemm_dW_up", c->LT[4], dl, c->dHa, c->RT[4], Dh, Gp(P_WUP), nullptr))) return rc;
-  {
-    Prof p(c, "gemm_dz");
+  {  // Eq. 8's gate product and Eq. 7's Up
+    PhaseGemms ph;
+    ph.add(GEMM_W_TN, args_w(c, c->Hmix, Dh, c->LT[3], Dh, c->dac, Dh, Gp(P_WC), nullptr));
+    ph.add(GEMM_X_STORE, args_x(c, c->dac, Dh, Dh, c->WT_c, c->P(P_WC), Dh, c->dHmix2));
+    ph.add(GEMM_W_TN, args_w(c, c->z, dl, c->LT[4], dl, c->dHa, Dh, Gp(P_WUP), nullptr));
     GemmArgs g{};
     g.M = B; g.N = dl; g.K = Dh; g.splits = c->sp_dz; g.A = c->dHa; g.lda = Dh; g.C = c->dz_part; g.ldc = dl;
     if (bf) g.W = c->WT_up;
     else { g.W = c->P(P_WUP); g.wt = 1; g.ldb = Dh; }
-    HIP_TRY(c, fade_gemm(GEMM_PARTIAL, bf, g, s));
+    ph.add(GEMM_PARTIAL, g);
+    if ((rc = run_phase(c, "gemms_gate_up", ph))) return rc;
   }
   {  // per-stream memory: dy, and Adam on W_U in place
     Prof p(c, "bwd_cci_adam");
@@ -660,9 +679,12 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     a.lr = c->cfg.lr; a.beta1 = c->cfg.beta1; a.beta2 = c->cfg.beta2; a.eps = c->cfg.eps;
     HIP_TRY(c, fade_bwd_cci(a, bf, s));
   }
-  if ((rc = transpose_grads(c, w, {{c->dy_at, {c->RT[5], dl}}}))) return rc;
-  if ((rc = gemm_w(c, w, "gemm_dW_down", c->LT[5], Dh, c->dy_at, c->RT[5], dl, Gp(P_WDOWN), nullptr))) return rc;
-  if ((rc = gemm_x(c, "gemm_dnc", c->dy_at, dl, Dh, c->WT_down, c->P(P_WDOWN), dl, c->dnc))) return rc;
+  {
+    PhaseGemms ph;
+    ph.add(GEMM_W_TN, args_w(c, c->LT[5], Dh, c->LT[5], Dh, c->dy_at, dl, Gp(P_WDOWN), nullptr));
+    ph.add(GEMM_X_STORE, args_x(c, c->dy_at, dl, Dh, c->WT_down, c->P(P_WDOWN), dl, c->dnc));
+    if ((rc = run_phase(c, "gemms_down", ph))) return rc;
+  }
   {  // LN of Eq. 7 + Eq. 5-6 + branch activations
     Prof p(c, "bwd_mix");
     BwdMixArgs a{};
@@ -675,11 +697,13 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     rq.push(B, 1, c->row_dlam + B, Gp(P_LAMBDA_C));
     rq.push(B, 1, c->row_dlam + 2 * B, Gp(P_LAMBDA_M));
   }
-  if ((rc = transpose_grads(c, w, {{c->dar, {c->RT[6], Dh}}, {c->dhm, {c->RT[7], Dh}}}))) return rc;
-  if ((rc = gemm_w(c, w, "gemm_dW_r", c->LT[7], Dh, c->dar, c->RT[6], Dh, Gp(P_WR), nullptr))) return rc;
-  if ((rc = gemm_x(c, "gemm_dX", c->dar, Dh, Dh, c->WT_r, c->P(P_WR), Dh, c->dX2))) return rc;
-  // global stream
-  if ((rc = gemm_w(c, w, "gemm_dW_m", c->LT[6], (int)d.Dc, c->dhm, c->RT[7], Dh, Gp(P_WM), nullptr))) return rc;
+  {  // router and global stream
+    PhaseGemms ph;
+    ph.add(GEMM_W_TN, args_w(c, c->X, Dh, c->LT[7], Dh, c->dar, Dh, Gp(P_WR), nullptr));
+    ph.add(GEMM_X_STORE, args_x(c, c->dar, Dh, Dh, c->WT_r, c->P(P_WR), Dh, c->dX2));
+    ph.add(GEMM_W_TN, args_w(c, c->M, (int)d.Dc, c->LT[6], (int)d.Dc, c->dhm, Dh, Gp(P_WM), nullptr));
+    if ((rc = run_phase(c, "gemms_router_global", ph))) return rc;
+  }
   {
     Prof p(c, "bwd_slot");
     BwdSlotArgs a{};
@@ -950,13 +974,15 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
         {&c->dE, Bp * 2 * d.De}, {&c->du, BDh}, {&c->dHa, BpDh}, {&c->dac, BpDh}, {&c->dHmix1, BDh}, {&c->dHmix2, BDh},
         {&c->dy_at, Bp * d.dl}, {&c->dnc, BDh}, {&c->dar, BpDh}, {&c->dhm, BpDh}, {&c->dcv, BDh}, {&c->dX1, BDh}, {&c->dX2, BDh},
         {&c->dxl, BDh},
-        {&c->LT[0], d.Dh * Bp}, {&c->LT[1], d.De * Bp}, {&c->LT[2], d.Dh * Bp}, {&c->LT[3], d.Dh * Bp}, {&c->LT[4], d.dl * Bp},
-        {&c->LT[5], d.Dh * Bp}, {&c->LT[6], d.Dc * Bp}, {&c->LT[7], d.Dh * Bp},
-        {&c->RT[0], 256 * Bp}, {&c->RT[1], d.Dh * Bp}, {&c->RT[2], 2 * d.De * Bp}, {&c->RT[3], d.Dh * Bp}, {&c->RT[4], d.Dh * Bp},
-        {&c->RT[5], d.dl * Bp}, {&c->RT[6], d.Dh * Bp}, {&c->RT[7], d.Dh * Bp}};
+        {&c->LT[2], d.Dh * Bp}, {&c->LT[5], d.Dh * Bp}};
     for (auto &b : bufs) {
       TRY_ALLOC(A(b.p, b.n));
       if (hipMemsetAsync(*b.p, 0, b.n * c->esz, c->stream) != hipSuccess) { fade_destroy(c); return FADE_E_HIP; }
+    }
+    if (!c->bf16) {  // fp32 path: feature-major copies [width][Bp] of the remaining left operands
+      struct { void **p; size_t n; } lts[] = {{&c->LT[0], d.Dh * Bp}, {&c->LT[1], d.De * Bp}, {&c->LT[3], d.Dh * Bp}, {&c->LT[4], d.dl * Bp},
+                                               {&c->LT[6], d.Dc * Bp}, {&c->LT[7], d.Dh * Bp}};
+      for (auto &b : lts) TRY_ALLOC(A(b.p, b.n));
     }
     c->sp_dz = c->bf16 ? pick_splits((int)((d.B + 63) / 64), (int)(d.Dh / 64), 16) : 1;
     TRY_ALLOC(dev_alloc(c, &c->dz_part, (size_t)c->sp_dz * d.B * d.dl));

@@ -152,6 +152,21 @@ __global__ __launch_bounds__(256) void transpose_batch_kernel(TransposeBatch tb)
   transpose_tile<AT>(a, b0, n0, tile, mr);
 }
 
+template <typename AT>
+__global__ __launch_bounds__(256) void ln_apply_kernel(LnApplyBatch lb) {
+  const LnApplyArgs &a = lb.a[blockIdx.y];
+  const int chunks = lb.Dh / 8;
+  const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (t >= (size_t)lb.B * chunks) return;
+  const int b = (int)(t / chunks), c8 = (int)(t % chunks) * 8;
+  float mean, rstd, v[8];
+  moments(a.stats + (size_t)b * lb.stats_n * 2, lb.stats_n, lb.Dh, mean, rstd);
+  ld8<AT>(static_cast<const AT *>(a.src) + (size_t)b * lb.Dh + c8, v);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v[i] = (v[i] - mean) * rstd * a.gamma[c8 + i] + a.beta[c8 + i];
+  st8<AT>(static_cast<AT *>(a.dst) + (size_t)b * lb.Dh + c8, v);
+}
+
 // X_T[j*D+i][b] = LN_e(E[w_{b,j}])[i] straight from the per-symbol table (X is a gather, so is its transpose)
 template <typename AT>
 __global__ __launch_bounds__(256) void embed_t_kernel(WinSrc ws, int B, int Bp, int T, int D, const AT *tab, AT *XT) {
@@ -800,6 +815,13 @@ hipError_t fade_dlogits(const WinSrc &ws, const uint8_t *targets, long long tstr
 hipError_t fade_transpose(const TransposeArgs &a, int N, bool bf16, hipStream_t s) {
   if (N % 64) return hipErrorInvalidValue;
   DISPATCH_AT(bf16, transpose_kernel, dim3((a.B + 63) / 64, N / 64), dim3(256), s, a);
+}
+hipError_t fade_ln_apply(const LnApplyBatch &lb, bool bf16, hipStream_t s) {
+  if (lb.count <= 0 || lb.count > 2 || lb.Dh % 8) return hipErrorInvalidValue;
+  const dim3 grid(nblk((size_t)lb.B * (lb.Dh / 8), 256), lb.count);
+  if (bf16) hipLaunchKernelGGL(ln_apply_kernel<bf16_t>, grid, dim3(256), 0, s, lb);
+  else hipLaunchKernelGGL(ln_apply_kernel<float>, grid, dim3(256), 0, s, lb);
+  return hipGetLastError();
 }
 hipError_t fade_transpose_batch(const TransposeBatch &tb, bool bf16, hipStream_t s) {
   if (tb.count <= 0 || tb.count > 8) return hipErrorInvalidValue;

@@ -55,6 +55,7 @@ struct GemmArgs {
   int splits;             // EPI_PARTIAL: number of K ranges (grid.y); 0 or 1 otherwise
   // A operand
   const void *A;  int lda;
+  int a_rows;             // row-major weight-gradient product: rows of A that exist (rows up to K are clamped to the last one)
   const void *A2;         // PRO_FINAL: residual source (same leading dimension)
   const float *stats;     // PRO_LN / PRO_FINAL: [M][stats_n][2] partial (sum, sum of squares) of A's rows
   int stats_n;
@@ -71,6 +72,15 @@ struct GemmArgs {
   const void *S1, *S2;    // side inputs [M][N] (leading dimension ldc)
   const float *bias;
   float *stats_out;       // optional [M][N / BN][2]
+};
+
+// A grouped launch: up to 4 independent products, each with the kernel body named by kind[]; blocks [first_block[p],
+// first_block[p + 1]) work on problem p (tiles[p] output tiles x splits[p] ranges of K).
+enum { GK_STORE_64x128 = 0, GK_STORE_64x64, GK_PARTIAL_64x64, GK_TN_64x128, GK_TN_128x128, GK_TN_64x64 };
+struct GemmGroup {
+  int count;
+  int kind[4], tiles[4], splits[4], first_block[5];
+  GemmArgs g[4];
 };
 
 // Row statistics are accumulated per block tile of BN columns; consumers add the partials in index order.

@@ -132,7 +132,7 @@ __device__ __forceinline__ void row_moments(const GemmArgs &g, int m, float &mea
 // epilogue: the accumulator tile sits in LDS as fp32 [BM][BN + 4]; threads walk it in 8-wide row chunks
 // ---------------------------------------------------------------------------------------------------
 template <int EPI, typename AT, int BM, int BN>
-__device__ __forceinline__ void epilogue(const GemmArgs &g, const float *Cs, int m0, int n0, int nt, int tid) {
+__device__ __forceinline__ void epilogue(const GemmArgs &g, const float *Cs, int m0, int n0, int nt, int tid, int split = 0) {
   constexpr int LDC = BN + 4;
   constexpr int BNO = (EPI == EPI_GEGLU) ? BN / 2 : BN;  // output columns of this tile
   constexpr int CH = BNO / 8;                            // chunks (threads) per row
@@ -199,7 +199,7 @@ __device__ __forceinline__ void epilogue(const GemmArgs &g, const float *Cs, int
           store8(static_cast<float *>(g.C) + o, x);
         }
       } else if (EPI == EPI_PARTIAL) {
-        store8(static_cast<float *>(g.C) + ((size_t)blockIdx.y * g.M + m) * g.ldc + n0 + c8, x);
+        store8(static_cast<float *>(g.C) + ((size_t)split * g.M + m) * g.ldc + n0 + c8, x);
       } else if (EPI == EPI_CONV) {
         float bi[8], pre[8];
         load8(g.bias + n0 + c8, bi);
@@ -388,7 +388,7 @@ __device__ __forceinline__ void dma16(const bf16_t *src, unsigned char *lds_chun
 }
 
 template <int BM, int BN, int STAGES, int EPI, bool BROW>
-__global__ __launch_bounds__(256) void gemm_pipe_kernel(GemmArgs g) {
+__device__ __forceinline__ void pipe_body(const GemmArgs &g, int bid, int split, int nsplit) {
   typedef bf16_t AT;
   constexpr int BK = 64, KS = 4;
   constexpr int TM = BM / 64, TN = BN / 64;          // 32x32 tiles per wavefront (wavefronts 2 x 2)
@@ -407,9 +407,9 @@ __global__ __launch_bounds__(256) void gemm_pipe_kernel(GemmArgs g) {
   const int wm = wave >> 1, wn = wave & 1;
   const int ntn = g.N / BN, ntm = (g.M + BM - 1) / BM;
   int mt, nt;
-  tile_of_block(blockIdx.x, ntm, ntn, mt, nt);
+  tile_of_block(bid, ntm, ntn, mt, nt);
   const int m0 = mt * BM, n0 = nt * BN;
-  const int ksplit = g.K / (int)gridDim.y, k_begin = (int)blockIdx.y * ksplit, nkb = ksplit / BK;
+  const int ksplit = g.K / nsplit, k_begin = split * ksplit, nkb = ksplit / BK;
   const int ksteps = g.K / 16;
 
   // DMA sources of this wavefront for one stage.
@@ -512,8 +512,192 @@ __global__ __launch_bounds__(256) void gemm_pipe_kernel(GemmArgs g) {
         Cs[row * LDC + col] = acc[i][j][e];
       }
   __syncthreads();
-  epilogue<EPI, AT, BM, BN>(g, Cs, m0, n0, nt, tid);
+  epilogue<EPI, AT, BM, BN>(g, Cs, m0, n0, nt, tid, split);
 }
+template <int BM, int BN, int STAGES, int EPI, bool BROW>
+__global__ __launch_bounds__(256) void gemm_pipe_kernel(GemmArgs g) {
+  pipe_body<BM, BN, STAGES, EPI, BROW>(g, (int)blockIdx.x, (int)blockIdx.y, (int)gridDim.y);
+}
+
+
+// ---------------------------------------------------------------------------------------------------
+// Weight gradients from ROW-MAJOR operands: C[M][N] = sum over rows b < K of A[b][m] * W[b][n]  (dW = L^T R over the batch;
+// A = a forward activation [a_rows][lda], W = a gradient [K][ldb] whose rows past the batch are zero).
+// The contraction index is the row index, which the matrix cores want contiguous per lane; instead of keeping transposed
+// copies of all sixteen operands in HBM, the turn happens on the way out of LDS. A stage holds 64 rows of BM (BN) columns
+// as they are in memory (LDS-DMA, 1 KiB = 8 rows x 128 bytes or 4 rows x 256 bytes per instruction), and fragments are
+// read with gfx950's transposing LDS load (ds_read_b64_tr_b16): within each group of 16 lanes, lane s supplies the
+// address of 4 consecutive 16-bit values, and lane i receives value (i % 4) of the lanes i / 4, i / 4 + 4, i / 4 + 8,
+// i / 4 + 12 (layout checked on the hardware). Pointing lane s at row s / 4, columns 4 (s % 4) .. + 3 of a 4 x 16 block
+// therefore hands lane i column i of the block with its 4 rows in order: two such loads give a lane the 8 contraction
+// rows of its column, which is the operand layout of v_mfma_f32_32x32x16_bf16.
+// Bank conflicts: one load touches 4 rows x 64 contiguous bytes per 32 lanes; with a row pitch of 128 (256) bytes those
+// rows would share banks, so the 16-byte pieces of a row are XOR-permuted by a function of the row (below) such that
+// 4 consecutive rows land in 4 different quarter-ranges of the 64 banks.
+// ---------------------------------------------------------------------------------------------------
+typedef __attribute__((ext_vector_type(4))) short i16x4;
+typedef __attribute__((ext_vector_type(8))) short i16x8;
+// piece permutation of row r in a stage whose rows are PITCH bytes long
+template <int PITCH> __device__ __forceinline__ int tn_swizzle(int r) {
+  static_assert(PITCH == 128 || PITCH == 256, "row pitch");
+  return PITCH == 256 ? ((r & 3) << 2) : (((r >> 1) & 1) << 2);
+}
+
+template <int BM, int BN, int STAGES>
+__device__ __forceinline__ void tn_body(const GemmArgs &g, int bid) {
+  typedef bf16_t AT;
+  constexpr int BK = 64, KS = 4;
+  constexpr int TM = BM / 64, TN = BN / 64;
+  constexpr int PA = BM / 8, PB = BN / 8;          // 16-byte pieces per row
+  constexpr int RA = 64 / PA, RB = 64 / PB;        // rows per DMA
+  constexpr int A_BYTES = BK * BM * 2, B_BYTES = BK * BN * 2;
+  constexpr int ACH = BK / RA / 4, BCH = BK / RB / 4;  // DMAs per wavefront and stage
+  constexpr int LPW = ACH + BCH, STAGE_BYTES = A_BYTES + B_BYTES, LDC = BN + 4;
+  static_assert(PA >= 8 && PB >= 8 && (BK / RA) % 4 == 0 && (BK / RB) % 4 == 0, "tile shape");
+  static_assert((STAGES - 2) * LPW <= 63, "vmcnt range");
+  extern __shared__ __align__(16) unsigned char smem[];
+  float *Cs = reinterpret_cast<float *>(smem);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int ntn = g.N / BN, ntm = g.M / BM;
+  int mt, nt;
+  tile_of_block(bid, ntm, ntn, mt, nt);
+  const int m0 = mt * BM, n0 = nt * BN;
+  const int nkb = g.K / BK;
+
+  // DMA c of an operand covers rows c * R .. c * R + R - 1 of the stage; lane i lands at byte 16 i of that KiB, i.e. at
+  // (row, piece) = (c * R + i / P, i % P), and fetches the piece whose index is XORed as described above.
+  int a_row[ACH], b_row[BCH];
+  const bf16_t *a_col[ACH], *b_src[BCH];
+#pragma unroll
+  for (int q = 0; q < ACH; ++q) {
+    const int row = (wave + 4 * q) * RA + lane / PA, piece = (lane % PA) ^ tn_swizzle<BM * 2>(row);
+    a_row[q] = row;
+    a_col[q] = static_cast<const bf16_t *>(g.A) + m0 + piece * 8;
+  }
+#pragma unroll
+  for (int q = 0; q < BCH; ++q) {
+    const int row = (wave + 4 * q) * RB + lane / PB, piece = (lane % PB) ^ tn_swizzle<BN * 2>(row);
+    b_row[q] = row;
+    b_src[q] = static_cast<const bf16_t *>(g.W) + (size_t)row * g.ldb + n0 + piece * 8;
+  }
+  const int last_a = g.a_rows - 1;
+  auto issue = [&](int slot, int kb) {
+    unsigned char *base = smem + slot * STAGE_BYTES;
+#pragma unroll
+    for (int q = 0; q < ACH; ++q) {
+      int r = kb * BK + a_row[q];
+      r = r < last_a ? r : last_a;  // past the batch: any finite row, its partner row of W is zero
+      dma16(a_col[q] + (size_t)r * g.lda, base + (wave + 4 * q) * 1024);
+    }
+#pragma unroll
+    for (int q = 0; q < BCH; ++q) dma16(b_src[q] + (size_t)kb * BK * g.ldb, base + A_BYTES + (wave + 4 * q) * 1024);
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+#pragma unroll
+  for (int s = 0; s < STAGES - 1; ++s)
+    if (s < nkb) issue(s, s);
+
+  // address this lane supplies to the transposing loads of k-step 0 (first of the two loads; the second is 4 rows on):
+  // row 8 * (lane / 32) + (lane % 16) / 4, columns tile * 32 + 16 * ((lane / 16) % 2) + 4 * (lane % 4) .. + 3
+  const int s16 = lane & 15, r0 = (lane >> 5) * 8 + (s16 >> 2), mh = (lane >> 4) & 1;
+  int a_off[TM], b_off[TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+    a_off[i] = r0 * (BM * 2) + ((((wm * TM + i) * 4 + 2 * mh + ((s16 & 3) >> 1)) ^ tn_swizzle<BM * 2>(r0)) << 4) + (s16 & 1) * 8;
+#pragma unroll
+  for (int j = 0; j < TN; ++j)
+    b_off[j] = A_BYTES + r0 * (BN * 2) + ((((wn * TN + j) * 4 + 2 * mh + ((s16 & 3) >> 1)) ^ tn_swizzle<BN * 2>(r0)) << 4) + (s16 & 1) * 8;
+  // rows 4 and 16 further on have the same (r & 3) and the same ((r >> 1) & 1): the permutation term does not change
+
+  for (int kb = 0; kb < nkb; ++kb) {
+    if (kb + STAGES - 2 < nkb) wait_vmcnt<(STAGES - 2) * LPW>();
+    else wait_vmcnt<0>();
+    bare_barrier();
+    if (kb + STAGES - 1 < nkb) issue((kb + STAGES - 1) % STAGES, kb + STAGES - 1);
+    const unsigned char *st = smem + (kb % STAGES) * STAGE_BYTES;
+    i16x8 af[2][TM], bf[2][TN];
+    auto tr_load = [&](const unsigned char *p) {
+      return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)p);
+    };
+    auto fetch = [&](int buf, int ks) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const unsigned char *p = st + a_off[i] + ks * 16 * (BM * 2);
+        const i16x4 lo = tr_load(p), hi = tr_load(p + 4 * (BM * 2));
+        af[buf][i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      }
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const unsigned char *p = st + b_off[j] + ks * 16 * (BN * 2);
+        const i16x4 lo = tr_load(p), hi = tr_load(p + 4 * (BN * 2));
+        bf[buf][j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      }
+    };
+    fetch(0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      if (ks + 1 < KS) fetch((ks + 1) & 1, ks + 1);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[ks & 1][i]), __builtin_bit_cast(bf16x8, bf[ks & 1][j]),
+                                                              acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+
+  wait_vmcnt<0>();
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int row = (wm * TM + i) * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+        const int col = (wn * TN + j) * 32 + (lane & 31);
+        Cs[row * LDC + col] = acc[i][j][e];
+      }
+  __syncthreads();
+  epilogue<EPI_GRAD, AT, BM, BN>(g, Cs, m0, n0, nt, tid);
+}
+template <int BM, int BN, int STAGES>
+__global__ __launch_bounds__(256) void gemm_tn_kernel(GemmArgs g) {
+  tn_body<BM, BN, STAGES>(g, (int)blockIdx.x);
+}
+
+// Several independent products in ONE launch (a block-uniform switch picks the problem and its kernel body): the products
+// of one backward phase (dX = dY W^T, dW = L^T dY, ...) consume the same gradient and do not depend on each other, and at
+// B = 1024 none of them fills the chip alone.
+__global__ __launch_bounds__(256) void gemm_group_kernel(GemmGroup gg) {
+  int p = 0;
+  while (p + 1 < gg.count && (int)blockIdx.x >= gg.first_block[p + 1]) ++p;
+  const int local = (int)blockIdx.x - gg.first_block[p], tiles = gg.tiles[p];
+  const GemmArgs &g = gg.g[p];
+  switch (gg.kind[p]) {
+    case GK_STORE_64x128:   pipe_body<64, 128, 4, EPI_STORE, false>(g, local, 0, 1); break;
+    case GK_STORE_64x64:    pipe_body<64, 64, 4, EPI_STORE, false>(g, local, 0, 1); break;
+    case GK_PARTIAL_64x64:  pipe_body<64, 64, 4, EPI_PARTIAL, false>(g, local % tiles, local / tiles, gg.splits[p]); break;
+    case GK_TN_64x128:      tn_body<64, 128, 4>(g, local); break;
+    case GK_TN_128x128:     tn_body<128, 128, 4>(g, local); break;
+    case GK_TN_64x64:       tn_body<64, 64, 4>(g, local); break;
+    default: break;
+  }
+}
+
 
 // ---------------------------------------------------------------------------------------------------
 // fp32 FMA core: 256 threads, each owning 8 consecutive columns of one row; tile (2048 / BN) x BN,
@@ -622,6 +806,22 @@ hipError_t launch_pipe(const GemmArgs &g, hipStream_t s) {
   return hipGetLastError();
 }
 
+template <int BM, int BN, int STAGES>
+hipError_t launch_tn(const GemmArgs &g, hipStream_t s) {
+  constexpr size_t lds_ring = (size_t)STAGES * 64 * (BM + BN) * 2, lds_c = (size_t)BM * (BN + 4) * sizeof(float);
+  constexpr size_t lds = lds_ring > lds_c ? lds_ring : lds_c;
+  static bool attr_done = false;
+  auto kern = gemm_tn_kernel<BM, BN, STAGES>;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  if (g.M % BM || g.N % BN || g.K % 64 || g.K <= 0 || g.a_rows <= 0 || g.a_rows > g.K || g.lda % 8 || g.ldb % 8) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(kern, dim3((g.M / BM) * (g.N / BN)), dim3(256), lds, s, g);
+  return hipGetLastError();
+}
+
 // Tile shape by problem size: 128 x 128 when that still gives every compute unit a tile, else 64 x 128.
 template <int EPI>
 hipError_t launch_pipe_auto(const GemmArgs &g, hipStream_t s) {
@@ -657,6 +857,68 @@ hipError_t launch_f32(const GemmArgs &g, hipStream_t s) {
 
 }  // namespace
 
+// ---------------------------------------------------------------------------------------------------
+// grouped launches (bf16 path)
+// ---------------------------------------------------------------------------------------------------
+namespace {
+size_t group_kind_lds(int kind) {
+  switch (kind) {
+    case GK_STORE_64x128: case GK_TN_64x128: return 4 * (8192 + 16384);
+    case GK_TN_128x128: return 4 * (16384 + 16384);
+    default: return 4 * (8192 + 8192);  // the 64 x 64 kinds
+  }
+}
+}  // namespace
+
+// Append one product to a group; the kernel body is chosen from the operation and the shape. op is one of GEMM_X_STORE
+// (C = A W, W as fragments), GEMM_PARTIAL (split-K partials, N = 64) and GEMM_W_TN (dW from row-major operands).
+hipError_t fade_gemm_group_add(GemmGroup &gg, int op, const GemmArgs &g) {
+  if (gg.count >= 4 || g.M <= 0 || g.K <= 0 || g.K % 64 || g.lda % 8) return hipErrorInvalidValue;
+  int kind, bm, bn, splits = 1;
+  if (op == GEMM_X_STORE) {
+    if (g.N % 128 == 0 && ((g.M + 63) / 64) * (g.N / 128) >= 128) { kind = GK_STORE_64x128; bn = 128; }
+    else if (g.N % 64 == 0) { kind = GK_STORE_64x64; bn = 64; }
+    else return hipErrorInvalidValue;
+    bm = 64;
+  } else if (op == GEMM_PARTIAL) {
+    if (g.N % 64) return hipErrorInvalidValue;
+    kind = GK_PARTIAL_64x64; bm = 64; bn = 64;
+    splits = g.splits > 1 ? g.splits : 1;
+    if (g.K % (splits * 64)) return hipErrorInvalidValue;
+  } else if (op == GEMM_W_TN) {
+    if (g.a_rows <= 0 || g.a_rows > g.K || g.ldb % 8 || g.M % 64) return hipErrorInvalidValue;
+    if (g.N % 128 == 0) {
+      const bool big = g.M % 128 == 0 && (g.M / 128) * (g.N / 128) >= 256 && fade_gemm_tune() != 8;
+      kind = big ? GK_TN_128x128 : GK_TN_64x128; bm = big ? 128 : 64; bn = 128;
+    } else if (g.N % 64 == 0) { kind = GK_TN_64x64; bm = 64; bn = 64; }
+    else return hipErrorInvalidValue;
+  } else {
+    return hipErrorInvalidValue;
+  }
+  const int p = gg.count;
+  if (p == 0) gg.first_block[0] = 0;
+  gg.kind[p] = kind;
+  gg.tiles[p] = ((g.M + bm - 1) / bm) * (g.N / bn);
+  gg.splits[p] = splits;
+  gg.first_block[p + 1] = gg.first_block[p] + gg.tiles[p] * splits;
+  gg.g[p] = g;
+  gg.count = p + 1;
+  return hipSuccess;
+}
+hipError_t fade_gemm_group_launch(const GemmGroup &gg, hipStream_t s) {
+  if (gg.count <= 0) return hipSuccess;
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_group_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * (16384 + 16384));
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  size_t lds = 0;
+  for (int p = 0; p < gg.count; ++p) lds = group_kind_lds(gg.kind[p]) > lds ? group_kind_lds(gg.kind[p]) : lds;
+  hipLaunchKernelGGL(gemm_group_kernel, dim3(gg.first_block[gg.count]), dim3(256), lds, s, gg);
+  return hipGetLastError();
+}
+
 // Tuning override for experiments (FADE_GEMM_TUNE: 0 automatic, 1 force 128x128, 2 force 64x128).
 int fade_gemm_tune() {
   static int v = -1;
@@ -683,6 +945,12 @@ hipError_t fade_gemm(int op, bool bf16, const GemmArgs &g, hipStream_t s) {
       case GEMM_W:        // backward dW = L^T R over the batch: both operands are feature-major copies [*][Bp]
         if (g.N % 128 == 0) return launch_pipe<64, 128, 4, EPI_GRAD, true>(g, s);
         return launch_pipe<64, 64, 4, EPI_GRAD, true>(g, s);
+      case GEMM_W_TN:     // the same from row-major operands (no copies): A = L [a_rows][lda], W = R [K][ldb]
+        if (g.N % 128 == 0) {
+          if (fade_gemm_tune() == 7 && g.M % 128 == 0) return launch_tn<128, 128, 4>(g, s);
+          return launch_tn<64, 128, 4>(g, s);
+        }
+        return launch_tn<64, 64, 4>(g, s);
       case GEMM_CONVT:    return launch_bf16<4, 1, 1, 1, PRO_CONVT, EPI_STORE>(g, s);
       default: return hipErrorInvalidValue;
     }

@@ -7,12 +7,15 @@ enum {
   GEMM_PARTIAL,  // product leaving fp32 partials [splits][M][N] (fp32 path: one split)
   GEMM_X_STORE,  // backward: dX = dY W^T, stored as activations
   GEMM_W,        // backward: dW = L^T R, reduction over the batch, fp32 gradient out
+  GEMM_W_TN,     // the same from row-major operands (bf16 path): A = L [a_rows][lda], W = R [K][ldb], K = padded batch
   GEMM_CONVT,    // backward of Eq. 4 w.r.t. its input
   GEMM_OP_COUNT
 };
 // Launch one of the model step's products (see fade_gemm.hip). bf16 selects the MFMA path (activations
 // bf16, W in fragment order) or the fp32 path (activations fp32, W plain [K][N]).
 hipError_t fade_gemm(int op, bool bf16, const GemmArgs &g, hipStream_t s);
+hipError_t fade_gemm_group_add(GemmGroup &gg, int op, const GemmArgs &g);
+hipError_t fade_gemm_group_launch(const GemmGroup &gg, hipStream_t s);
 
 enum { CODE_NONE = 0, CODE_ENCODE = 1, CODE_DECODE = 2 };
 
@@ -134,6 +137,11 @@ struct TransposeArgs {
   const float *stats; int stats_n, width;  // optional LayerNorm on the way (stats == NULL: plain copy)
   const float *gamma, *beta;
 };
+// u = LN(h) written out row-major (the forward pass folds these LayerNorms into the following product and never stores u;
+// the weight gradients of Eq. 7's Down and Eq. 9's pair need it as their left operand)
+struct LnApplyArgs { const void *src; void *dst; const float *stats, *gamma, *beta; };
+struct LnApplyBatch { LnApplyArgs a[2]; int count, B, Dh, stats_n; };
+hipError_t fade_ln_apply(const LnApplyBatch &lb, bool bf16, hipStream_t s);
 // several transposes in one launch (blockIdx.z picks one)
 struct TransposeBatch {
   TransposeArgs t[8];
