@@ -29,16 +29,19 @@ enum ParamId {
 
 struct Layout {
   size_t off[P_COUNT + 1];
+  size_t len[P_COUNT];
 };
 
-Layout make_layout(const Dims &d) {
+// canonical: the blob of the C ABI, tensors back to back. Device arrays (master, gradient, Adam moments) start every tensor on
+// a 16-byte boundary instead (only the three scalar residual scales get padding), so that kernels can use 16-byte accesses.
+Layout make_layout(const Dims &d, bool canonical) {
   const size_t n[P_COUNT] = {
       256 * d.D, d.D, d.D, d.D, d.D, d.D * d.c, d.D * d.c, d.Dc * d.Dh, 1, d.k * d.D * d.D, d.D, d.Dh * d.Dh, d.Dh, d.Dh,
       d.Dh * d.dl, d.B * d.dl * d.dl, d.dl * d.Dh, d.Dh * d.Dh, 1, d.Dh, d.Dh, d.Dh * d.De, d.Dh * d.De, d.De * d.Dh,
       d.Dh, d.Dh, 1, d.Dh * 256, 256};
   Layout L;
   size_t o = 0;
-  for (int i = 0; i < P_COUNT; ++i) { L.off[i] = o; o += n[i]; }
+  for (int i = 0; i < P_COUNT; ++i) { L.off[i] = o; o += canonical ? n[i] : (n[i] + 3) / 4 * 4; L.len[i] = n[i]; }
   L.off[P_COUNT] = o;
   return L;
 }
@@ -121,6 +124,7 @@ struct fade_ctx {
   // bf16 path: split-K partials, folded-LayerNorm vectors, the materialised H of Eq. 10
   float *part_down = nullptr, *part_fnr = nullptr, *part_head = nullptr;
   float *s_down = nullptr, *t_down = nullptr, *s_fnr = nullptr, *t_fnr = nullptr, *fold_part = nullptr;
+  float *fold_down = nullptr, *fold_fnr = nullptr;  // per 64-row block partials of those vectors, written by the Adam + refresh kernel
   void *Hout = nullptr;
   int sp_down = 1, sp_fnr = 1, sp_head = 1;
   // kept for the backward pass (online mode only)
@@ -163,6 +167,7 @@ struct fade_ctx {
   std::vector<double> prof_ms;
   std::vector<uint64_t> prof_n;
 
+  Layout blob;  // canonical layout of the C ABI's blob (lay: the device arrays)
   const float *P(int id) const { return master + lay.off[id]; }
 };
 
@@ -230,43 +235,67 @@ void prof_collect(fade_ctx *c) {
 // ---------------------------------------------------------------------------------------------------
 // master weights -> compute copies (runs on the stream; repeated after every online update)
 // ---------------------------------------------------------------------------------------------------
+// The nine big matrices: (online: one Adam step, then) both bf16 fragment copies and the partial sums of the folded-LayerNorm
+// vectors, one pass over 64 x 64 blocks. fp32 path: the Adam step only (operands are the master weights themselves).
+int refresh_matrices(fade_ctx *c, bool adam) {
+  const Dims &d = c->d;
+  const bool bf = c->bf16;
+  AdamRefreshBatch ab{};
+  ab.refresh_only = adam ? 0 : 1;
+  ab.opt = AdamArrays{c->grad, c->master, c->adam_m, c->adam_v, c->ustate, c->cfg.lr, c->cfg.beta1, c->cfg.beta2, c->cfg.eps};
+  auto add = [&](int id, size_t K, size_t N, int vcol0, int vstride, size_t VN, void *frag, void *fragT, const float *ga, const float *be, float *fp) {
+    AdamMat &m = ab.m[ab.count++];
+    m.off = c->lay.off[id]; m.K = (int)K; m.N = (int)N; m.vcol0 = vcol0; m.vstride = vstride; m.VN = (int)VN;
+    m.frag = bf ? frag : nullptr; m.fragT = (bf && c->online) ? fragT : nullptr; m.gamma = bf ? ga : nullptr; m.beta = bf ? be : nullptr; m.fold_part = fp;
+    m.first_block = ab.total_blocks;
+    ab.total_blocks += (int)((K / 64) * (N / 64));
+  };
+  add(P_WR, d.Dh, d.Dh, 0, 64, d.Dh, c->Wr_c, c->WT_r, nullptr, nullptr, nullptr);
+  add(P_WC, d.Dh, d.Dh, 0, 64, d.Dh, c->Wc_c, c->WT_c, nullptr, nullptr, nullptr);
+  add(P_WFG, d.Dh, d.De, 0, 128, 2 * d.De, c->Wfgv_c, c->WT_fgv, c->P(P_GAMMA_F), c->P(P_BETA_F), c->fold_fnr);
+  add(P_WFV, d.Dh, d.De, 64, 128, 2 * d.De, c->Wfgv_c, c->WT_fgv, c->P(P_GAMMA_F), c->P(P_BETA_F), c->fold_fnr);
+  add(P_WM, d.Dc, d.Dh, 0, 64, d.Dh, c->Wm_c, nullptr, nullptr, nullptr, nullptr);
+  add(P_WF, d.De, d.Dh, 0, 64, d.Dh, c->Wf_c, c->WT_f, nullptr, nullptr, nullptr);
+  add(P_WO, d.Dh, 256, 0, 64, 256, c->Wo_c, c->WT_o, nullptr, nullptr, nullptr);
+  add(P_WUP, d.dl, d.Dh, 0, 64, d.Dh, c->Wup_c, c->WT_up, nullptr, nullptr, nullptr);
+  add(P_WDOWN, d.Dh, d.dl, 0, 64, d.dl, c->Wdown_c, c->WT_down, c->P(P_GAMMA_C), c->P(P_BETA_C), c->fold_down);
+  HIP_TRY(c, fade_adam_refresh(ab, c->stream));
+  return FADE_OK;
+}
+// bf16 path, after the matrices: the small operands (embedding, slot pair, conv taps in both orientations), the folded-LayerNorm
+// vectors from their per-block partials, the per-symbol tables
+int refresh_small(fade_ctx *c) {
+  const Dims &d = c->d;
+  hipStream_t s = c->stream;
+  PrepBatch pb{};
+  auto padd = [&](int kind, const float *W0, size_t k_real, size_t K, size_t N, void *out) {
+    PrepDesc &q = pb.d[pb.count++];
+    q.kind = kind; q.W0 = W0; q.W1 = nullptr; q.k_real = (int)k_real; q.K = (int)K; q.N = (int)N; q.interleave = 0; q.rowscale = nullptr;
+    q.out = out; q.taps = (int)d.k; q.D = (int)d.D;
+  };
+  padd(PREP_ROUND, c->P(P_E), 0, 0, 256 * d.D, c->E_c);
+  padd(PREP_ROUND, c->P(P_WG), 0, 0, d.D * d.c, c->Wg_c);
+  padd(PREP_ROUND, c->P(P_WV), 0, 0, d.D * d.c, c->Wv_c);
+  padd(PREP_FRAG, c->P(P_WCONV), d.k * d.D, d.Kc, d.D, c->Wconv_c);
+  if (c->online) padd(PREP_FRAG_CONVT, c->P(P_WCONV), d.k * d.D, d.Kc, d.D, c->WT_conv);
+  HIP_TRY(c, fade_prep_batch(pb, s));
+  ReduceBatch fr{};  // s then t, adjacent
+  fr.push_plain((int)(d.Dh / 64), (int)(2 * d.dl), c->fold_down, c->s_down);
+  fr.push_plain((int)(d.Dh / 64), (int)(4 * d.De), c->fold_fnr, c->s_fnr);
+  HIP_TRY(c, fade_reduce_batch(fr, s));
+  HIP_TRY(c, fade_tables(c->E_c, c->P(P_GAMMA_E), c->P(P_BETA_E), c->P(P_GAMMA_L), c->P(P_BETA_L), (int)d.D, c->tabXe, c->tabXl, c->tabXe32,
+                         c->tabXhat, c->tabRstd, true, s));
+  return FADE_OK;
+}
+
 int prepare_compute(fade_ctx *c, bool with_wu = true) {
   const Dims &d = c->d;
   hipStream_t s = c->stream;
   if (c->bf16) {
-    PrepBatch pb{};
-    auto add = [&](int kind, const float *W0, const float *W1, size_t k_real, size_t K, size_t N, int il, const float *scale, void *out) {
-      PrepDesc &q = pb.d[pb.count++];
-      q.kind = kind; q.W0 = W0; q.W1 = W1; q.k_real = (int)k_real; q.K = (int)K; q.N = (int)N; q.interleave = il; q.rowscale = scale;
-      q.out = out; q.taps = (int)d.k; q.D = (int)d.D;
-    };
-    add(PREP_ROUND, c->P(P_E), nullptr, 0, 0, 256 * d.D, 0, nullptr, c->E_c);
-    add(PREP_ROUND, c->P(P_WG), nullptr, 0, 0, d.D * d.c, 0, nullptr, c->Wg_c);
-    add(PREP_ROUND, c->P(P_WV), nullptr, 0, 0, d.D * d.c, 0, nullptr, c->Wv_c);
-    add(PREP_FRAG, c->P(P_WM), nullptr, d.Dc, d.Dc, d.Dh, 0, nullptr, c->Wm_c);
-    add(PREP_FRAG, c->P(P_WCONV), nullptr, d.k * d.D, d.Kc, d.D, 0, nullptr, c->Wconv_c);
-    add(PREP_FRAG, c->P(P_WR), nullptr, d.Dh, d.Dh, d.Dh, 0, nullptr, c->Wr_c);
-    add(PREP_FRAG, c->P(P_WUP), nullptr, d.dl, d.dl, d.Dh, 0, nullptr, c->Wup_c);
-    add(PREP_FRAG, c->P(P_WC), nullptr, d.Dh, d.Dh, d.Dh, 0, nullptr, c->Wc_c);
-    add(PREP_FRAG, c->P(P_WF), nullptr, d.De, d.De, d.Dh, 0, nullptr, c->Wf_c);
-    add(PREP_FRAG, c->P(P_WO), nullptr, d.Dh, d.Dh, 256, 0, nullptr, c->Wo_c);
-    // LayerNorm gains folded into the consuming weights (Eq. 7's Down, Eq. 9's GeGLU pair)
-    add(PREP_FRAG, c->P(P_WDOWN), nullptr, d.Dh, d.Dh, d.dl, 0, c->P(P_GAMMA_C), c->Wdown_c);
-    add(PREP_FRAG, c->P(P_WFG), c->P(P_WFV), d.Dh, d.Dh, 2 * d.De, 1, c->P(P_GAMMA_F), c->Wfgv_c);
-    if (c->online) {  // operands of the backward pass: transposed fragment sets, and Eq. 4's transposed taps
-      add(PREP_FRAG_CONVT, c->P(P_WCONV), nullptr, d.k * d.D, d.Kc, d.D, 0, nullptr, c->WT_conv);
-      add(PREP_FRAG_T, c->P(P_WO), nullptr, 0, d.Dh, 256, 0, nullptr, c->WT_o);
-      add(PREP_FRAG_T, c->P(P_WF), nullptr, 0, d.De, d.Dh, 0, nullptr, c->WT_f);
-      add(PREP_FRAG_T, c->P(P_WFG), c->P(P_WFV), 0, d.Dh, 2 * d.De, 1, nullptr, c->WT_fgv);
-      add(PREP_FRAG_T, c->P(P_WC), nullptr, 0, d.Dh, d.Dh, 0, nullptr, c->WT_c);
-      add(PREP_FRAG_T, c->P(P_WUP), nullptr, 0, d.dl, d.Dh, 0, nullptr, c->WT_up);
-      add(PREP_FRAG_T, c->P(P_WDOWN), nullptr, 0, d.Dh, d.dl, 0, nullptr, c->WT_down);
-      add(PREP_FRAG_T, c->P(P_WR), nullptr, 0, d.Dh, d.Dh, 0, nullptr, c->WT_r);
-    }
-    HIP_TRY(c, fade_prep_batch(pb, s));
-    HIP_TRY(c, fade_fold_vectors(c->P(P_WDOWN), nullptr, (int)d.Dh, (int)d.dl, 0, c->P(P_GAMMA_C), c->P(P_BETA_C), c->fold_part, c->s_down, s));
-    HIP_TRY(c, fade_fold_vectors(c->P(P_WFG), c->P(P_WFV), (int)d.Dh, (int)(2 * d.De), 1, c->P(P_GAMMA_F), c->P(P_BETA_F), c->fold_part, c->s_fnr, s));
+    int rc = refresh_matrices(c, false);
+    if (rc) return rc;
     if (with_wu) HIP_TRY(c, fade_convert(c->P(P_WU), c->WU_c, d.B * d.dl * d.dl, true, s));
+    return refresh_small(c);
   } else {
     HIP_TRY(c, fade_virtual_copy(c->P(P_WCONV), nullptr, (int)(d.k * d.D), (int)d.Kc, (int)d.D, 0, static_cast<float *>(c->Wconv_c), s));
     HIP_TRY(c, fade_virtual_copy(c->P(P_WFG), c->P(P_WFV), (int)d.Dh, (int)d.Dh, (int)(2 * d.De), 1, static_cast<float *>(c->Wfgv_c), s));
@@ -731,14 +760,15 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     // gamma_e, beta_e, gamma_l, beta_l are adjacent in the blob
     HIP_TRY(c, fade_bwd_embed(a, c->emb_blocks, c->sym_sums, c->tok_part, Gp(P_E), Gp(P_GAMMA_E), bf, rq, s));
   }
-  {  // Adam on everything except W_U (done in place above), then refresh the compute copies
+  {  // Adam on everything except W_U (done in place above) and the refresh of every compute copy
     Prof p(c, "adam_refresh");
-    const size_t lo = c->lay.off[P_WU], hi = c->lay.off[P_WU + 1], np = c->lay.off[P_COUNT];
+    const AdamArrays opt{c->grad, c->master, c->adam_m, c->adam_v, c->ustate, c->cfg.lr, c->cfg.beta1, c->cfg.beta2, c->cfg.eps};
+    // vectors, scalars, biases and the small tensors: Adam right where their gradient sums are finished
+    rq.opt = opt;
+    rq.push(1, (int)(256 * d.D), Gp(P_E), Gp(P_E));  // dE is complete already: a one-row "sum" that only adds the Adam step
     HIP_TRY(c, fade_reduce_batch(rq, s));
-    HIP_TRY(c, fade_adam(lo, c->grad, c->master, c->adam_m, c->adam_v, c->ustate, c->cfg.lr, c->cfg.beta1, c->cfg.beta2, c->cfg.eps, s));
-    HIP_TRY(c, fade_adam(np - hi, c->grad + hi, c->master + hi, c->adam_m + hi, c->adam_v + hi, c->ustate, c->cfg.lr, c->cfg.beta1,
-                         c->cfg.beta2, c->cfg.eps, s));
-    rc = prepare_compute(c, false);
+    if ((rc = refresh_matrices(c, true))) return rc;
+    rc = bf ? refresh_small(c) : prepare_compute(c, false);
     if (rc) return rc;
   }
   return FADE_OK;
@@ -841,7 +871,7 @@ extern "C" {
 size_t fade_weights_nbytes(const fade_config *cfg) {
   Dims d;
   if (!cfg || resolve_dims(*cfg, d, nullptr)) return 0;
-  return make_layout(d).off[P_COUNT] * sizeof(float);
+  return make_layout(d, true).off[P_COUNT] * sizeof(float);
 }
 
 void fade_destroy(fade_ctx *c) {
@@ -874,7 +904,8 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
   if (c->cfg.beta2 == 0.0f) c->cfg.beta2 = 0.999f;
   if (c->cfg.eps == 0.0f) c->cfg.eps = 1e-8f;
   c->d = d;
-  c->lay = make_layout(d);
+  c->lay = make_layout(d, false);
+  c->blob = make_layout(d, true);
   c->bf16 = cfg->dtype == FADE_BF16;
   c->online = cfg->update_mode == FADE_ONLINE_ADAM;
   c->esz = c->bf16 ? 2 : 4;
@@ -914,6 +945,8 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
     TRY_ALLOC(dev_alloc(c, &c->s_fnr, 4 * d.De));
     c->t_fnr = c->s_fnr + 2 * d.De;
     TRY_ALLOC(dev_alloc(c, &c->fold_part, 16 * 2 * std::max<size_t>(d.dl, 2 * d.De)));
+    TRY_ALLOC(dev_alloc(c, &c->fold_down, d.Dh / 64 * 2 * d.dl));
+    TRY_ALLOC(dev_alloc(c, &c->fold_fnr, d.Dh / 64 * 2 * 2 * d.De));
   } else {  // fp32: most operands are used straight from the master blob
     c->E_c = c->master + c->lay.off[P_E];
     c->Wg_c = c->master + c->lay.off[P_WG];
@@ -1021,12 +1054,13 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
 
 int fade_load_weights(fade_ctx *c, const void *blob_host, size_t nbytes) {
   if (!c || !blob_host) return FADE_E_INVALID_ARG;
-  const size_t np = c->lay.off[P_COUNT];
+  const size_t np = c->blob.off[P_COUNT];
   if (nbytes != np * sizeof(float)) return fail(c, FADE_E_WEIGHTS_MISMATCH, "blob size does not match the configuration");
   const float *f = static_cast<const float *>(blob_host);
   for (size_t i = 0; i < np; ++i)
     if (!std::isfinite(f[i])) return fail(c, FADE_E_NUMERIC, "non-finite weight");
-  c->loaded.assign(f, f + np);
+  c->loaded.assign(c->lay.off[P_COUNT], 0.0f);  // kept in the device layout
+  for (int t = 0; t < P_COUNT; ++t) std::memcpy(c->loaded.data() + c->lay.off[t], f + c->blob.off[t], c->blob.len[t] * sizeof(float));
   c->weights_hash = fnv1a64(blob_host, nbytes);
   c->have_weights = true;
   return do_reset(c);
@@ -1278,19 +1312,25 @@ size_t fade_tap(fade_ctx *c, int which, float *out_host, size_t cap_floats) {
   return width;
 }
 
-int fade_get_weights(fade_ctx *c, void *blob_host, size_t nbytes) {
-  if (!c || !blob_host || nbytes != c->lay.off[P_COUNT] * sizeof(float)) return FADE_E_INVALID_ARG;
+// device array (device layout) -> canonical blob on the host
+static int read_blob(fade_ctx *c, const float *dev, void *blob_host) {
   HIP_TRY(c, hipStreamSynchronize(c->stream));
-  HIP_TRY(c, hipMemcpy(blob_host, c->master, nbytes, hipMemcpyDeviceToHost));
+  std::vector<float> tmp(c->lay.off[P_COUNT]);
+  HIP_TRY(c, hipMemcpy(tmp.data(), dev, tmp.size() * sizeof(float), hipMemcpyDeviceToHost));
+  for (int t = 0; t < P_COUNT; ++t)
+    std::memcpy(static_cast<float *>(blob_host) + c->blob.off[t], tmp.data() + c->lay.off[t], c->blob.len[t] * sizeof(float));
   return FADE_OK;
 }
 
+int fade_get_weights(fade_ctx *c, void *blob_host, size_t nbytes) {
+  if (!c || !blob_host || nbytes != c->blob.off[P_COUNT] * sizeof(float)) return FADE_E_INVALID_ARG;
+  return read_blob(c, c->master, blob_host);
+}
+
 int fade_debug_grad(fade_ctx *c, void *blob_host, size_t nbytes) {
-  if (!c || !blob_host || nbytes != c->lay.off[P_COUNT] * sizeof(float)) return FADE_E_INVALID_ARG;
+  if (!c || !blob_host || nbytes != c->blob.off[P_COUNT] * sizeof(float)) return FADE_E_INVALID_ARG;
   if (!c->online) return fail(c, FADE_E_BAD_CONFIG, "context is frozen");
-  HIP_TRY(c, hipStreamSynchronize(c->stream));
-  HIP_TRY(c, hipMemcpy(blob_host, c->grad, nbytes, hipMemcpyDeviceToHost));
-  return FADE_OK;
+  return read_blob(c, c->grad, blob_host);
 }
 
 int fade_profile(fade_ctx *c, int enable) {

@@ -40,6 +40,19 @@ __device__ __forceinline__ void moments(const float *stats, int stats_n, int wid
   fade_row_moments(stats, stats_n, width, mean, rstd);
 }
 
+// One Adam step (bias-corrected, no weight decay) on element idx of the blob, given its gradient; returns the new weight.
+__device__ __forceinline__ float adam_element(const AdamArrays &o, size_t idx, float g) {
+  const UpdateState us = *o.u;
+  if (us.na == 0) return o.master[idx];  // no active stream: no update
+  const float mk = o.beta1 * o.m[idx] + (1.0f - o.beta1) * g;
+  const float vk = o.beta2 * o.v[idx] + (1.0f - o.beta2) * g * g;
+  o.m[idx] = mk;
+  o.v[idx] = vk;
+  const float w = o.master[idx] - o.lr * (mk / us.c1) / (sqrtf(vk / us.c2) + o.eps);
+  o.master[idx] = w;
+  return w;
+}
+
 // Sum of one value per thread over a 256-thread workgroup, same order every time: butterfly inside each
 // wavefront, then the four wavefront sums added in index order. Every thread gets the result.
 __device__ __forceinline__ float block_sum(float v, float *red /*[4]*/) {
@@ -498,6 +511,7 @@ __global__ __launch_bounds__(256) void reduce_batch_kernel(ReduceBatch rb) {
 #pragma unroll
     for (int q = 0; q < 8; ++q) t += ps[q][c];
     rb.out[k][n] = t;
+    if (rb.adam[k]) adam_element(rb.opt, (size_t)(rb.out[k] - rb.opt.grad_base) + n, t);
   }
 }
 // stage 1 for a plain matrix: part[rb][n] = sum over the 32 rows of row block rb of src[b][n]
@@ -791,6 +805,101 @@ __global__ __launch_bounds__(256) void adam_kernel(size_t n, const float *grad, 
   master[t] = master[t] - lr * (mk / us.c1) / (sqrtf(vk / us.c2) + eps);
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Adam on the big matrices + refresh of their bf16 operand copies, one 64 x 64 block per workgroup
+// ---------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void adam_refresh_kernel(AdamRefreshBatch ab) {
+  __shared__ float tile[64][65];
+  __shared__ float gb[2][64];
+  UpdateState us{};
+  if (!ab.refresh_only) {
+    us = *ab.opt.u;
+    if (us.na == 0) return;  // nothing was updated, every copy is still valid
+  }
+  int p = 0;
+  while (p + 1 < ab.count && (int)blockIdx.x >= ab.m[p + 1].first_block) ++p;
+  const AdamMat &M = ab.m[p];
+  const int local = (int)blockIdx.x - M.first_block, nbn = M.N / 64;
+  const int kb = local / nbn, nb = local - kb * nbn, k0 = kb * 64, n0 = nb * 64;
+  const int tid = threadIdx.x;
+  const float b1 = ab.opt.beta1, b2 = ab.opt.beta2, lr = ab.opt.lr, eps = ab.opt.eps;
+  {  // Adam: thread = 4 consecutive columns of rows r, r + 16, r + 32, r + 48
+    const int c4 = (tid & 15) * 4;
+    f32x4 g[4], mm[4], vv[4], w[4];
+    size_t idx[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      idx[q] = M.off + (size_t)(k0 + (tid >> 4) + 16 * q) * M.N + n0 + c4;
+      w[q] = *reinterpret_cast<const f32x4 *>(ab.opt.master + idx[q]);
+      if (!ab.refresh_only) {
+        g[q] = *reinterpret_cast<const f32x4 *>(ab.opt.grad_base + idx[q]);
+        mm[q] = *reinterpret_cast<const f32x4 *>(ab.opt.m + idx[q]);
+        vv[q] = *reinterpret_cast<const f32x4 *>(ab.opt.v + idx[q]);
+      }
+    }
+    if (ab.refresh_only) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) tile[(tid >> 4) + 16 * q][c4 + i] = w[q][i];
+    } else
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float mk = b1 * mm[q][i] + (1.0f - b1) * g[q][i];
+        const float vk = b2 * vv[q][i] + (1.0f - b2) * g[q][i] * g[q][i];
+        mm[q][i] = mk;
+        vv[q][i] = vk;
+        w[q][i] = w[q][i] - lr * (mk / us.c1) / (sqrtf(vk / us.c2) + eps);
+        tile[(tid >> 4) + 16 * q][c4 + i] = w[q][i];
+      }
+      *reinterpret_cast<f32x4 *>(ab.opt.m + idx[q]) = mm[q];
+      *reinterpret_cast<f32x4 *>(ab.opt.v + idx[q]) = vv[q];
+      *reinterpret_cast<f32x4 *>(ab.opt.master + idx[q]) = w[q];
+    }
+  }
+  if (M.gamma && tid < 64) { gb[0][tid] = M.gamma[k0 + tid]; gb[1][tid] = M.beta[k0 + tid]; }
+  __syncthreads();
+  const int vbase = (n0 >> 6) * M.vstride + M.vcol0;  // virtual column of this block's first column (64 columns stay together)
+  // 8 fragments of each kind per block, 64 lanes each: two (fragment, lane) pairs per thread
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    const int id = tid + 256 * q, fl = id >> 6, lane = id & 63, t2 = fl >> 2, s4 = fl & 3;
+    if (M.frag) {  // forward operand: lane = column, 8 consecutive rows
+      const int n = t2 * 32 + (lane & 31), kk = s4 * 16 + (lane >> 5) * 8;
+      bf16x8 r;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        float x = tile[kk + i][n];
+        if (M.gamma) x = gb[0][kk + i] * (float)(bf16_t)x;
+        r[i] = (bf16_t)x;
+      }
+      const size_t f = (size_t)(vbase / 32 + t2) * (M.K / 16) + (k0 / 16 + s4);
+      reinterpret_cast<bf16x8 *>(M.frag)[f * 64 + lane] = r;
+    }
+    if (M.fragT) {  // operand of dX = dY W^T: lane = row of W, 8 consecutive (virtual) columns
+      const int k = t2 * 32 + (lane & 31), nn = s4 * 16 + (lane >> 5) * 8;
+      bf16x8 r;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) r[i] = (bf16_t)tile[k][nn + i];
+      const size_t f = (size_t)(k0 / 32 + t2) * (M.VN / 16) + (vbase / 16 + s4);
+      reinterpret_cast<bf16x8 *>(M.fragT)[f * 64 + lane] = r;
+    }
+  }
+  if (M.gamma && tid < 64) {  // this block's part of the folded-LayerNorm vectors: s = column sums of W', t = beta^T W
+    float sa = 0.0f, ta = 0.0f;
+    for (int k = 0; k < 64; ++k) {
+      const float w = (float)(bf16_t)tile[k][tid];
+      sa += (float)(bf16_t)(gb[0][k] * w);
+      ta = fmaf(gb[1][k], w, ta);
+    }
+    float *pp = M.fold_part + (size_t)kb * 2 * M.VN;
+    pp[vbase + tid] = sa;
+    pp[M.VN + vbase + tid] = ta;
+  }
+}
+
 inline unsigned nblk(size_t n, unsigned per) { return (unsigned)((n + per - 1) / per); }
 
 }  // namespace
@@ -908,6 +1017,13 @@ hipError_t fade_bwd_embed(const BwdTokenArgs &a, int nblocks, float *sums, float
   hipLaunchKernelGGL(embed_finish_kernel, dim3(256), dim3(64), 0, s, a.D, sums, a.tabXhat, a.tabRstd, a.gamma_e, a.gamma_l, dE, contrib);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   return rb.push(256, 4 * a.D, contrib, dparams) ? hipSuccess : hipErrorInvalidValue;
+}
+hipError_t fade_adam_refresh(const AdamRefreshBatch &ab, hipStream_t s) {
+  if (ab.count <= 0 || ab.count > 10) return hipErrorInvalidValue;
+  for (int i = 0; i < ab.count; ++i)
+    if (ab.m[i].K % 64 || ab.m[i].N % 64 || ab.m[i].off % 4 || ab.m[i].vstride % 64 || ab.m[i].vcol0 % 64) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(adam_refresh_kernel, dim3(ab.total_blocks), dim3(256), 0, s, ab);
+  return hipGetLastError();
 }
 hipError_t fade_adam(size_t n, const float *grad, float *master, float *m, float *v, const UpdateState *u, float lr, float beta1, float beta2,
                      float eps, hipStream_t s) {

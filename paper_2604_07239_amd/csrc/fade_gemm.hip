@@ -689,6 +689,7 @@ __global__ __launch_bounds__(256) void gemm_group_kernel(GemmGroup gg) {
   const GemmArgs &g = gg.g[p];
   switch (gg.kind[p]) {
     case GK_STORE_64x128:   pipe_body<64, 128, 4, EPI_STORE, false>(g, local, 0, 1); break;
+    case GK_STORE_128x128:  pipe_body<128, 128, 4, EPI_STORE, false>(g, local, 0, 1); break;
     case GK_STORE_64x64:    pipe_body<64, 64, 4, EPI_STORE, false>(g, local, 0, 1); break;
     case GK_PARTIAL_64x64:  pipe_body<64, 64, 4, EPI_PARTIAL, false>(g, local % tiles, local / tiles, gg.splits[p]); break;
     case GK_TN_64x128:      tn_body<64, 128, 4>(g, local); break;
@@ -864,7 +865,7 @@ namespace {
 size_t group_kind_lds(int kind) {
   switch (kind) {
     case GK_STORE_64x128: case GK_TN_64x128: return 4 * (8192 + 16384);
-    case GK_TN_128x128: return 4 * (16384 + 16384);
+    case GK_TN_128x128: case GK_STORE_128x128: return 4 * (16384 + 16384);
     default: return 4 * (8192 + 8192);  // the 64 x 64 kinds
   }
 }
@@ -876,10 +877,11 @@ hipError_t fade_gemm_group_add(GemmGroup &gg, int op, const GemmArgs &g) {
   if (gg.count >= 4 || g.M <= 0 || g.K <= 0 || g.K % 64 || g.lda % 8) return hipErrorInvalidValue;
   int kind, bm, bn, splits = 1;
   if (op == GEMM_X_STORE) {
-    if (g.N % 128 == 0 && ((g.M + 63) / 64) * (g.N / 128) >= 128) { kind = GK_STORE_64x128; bn = 128; }
+    bm = 64;
+    if (g.N % 128 == 0 && ((g.M + 127) / 128) * (g.N / 128) >= 128 && fade_gemm_tune() != 9) { kind = GK_STORE_128x128; bm = 128; bn = 128; }
+    else if (g.N % 128 == 0 && ((g.M + 63) / 64) * (g.N / 128) >= 128) { kind = GK_STORE_64x128; bn = 128; }
     else if (g.N % 64 == 0) { kind = GK_STORE_64x64; bn = 64; }
     else return hipErrorInvalidValue;
-    bm = 64;
   } else if (op == GEMM_PARTIAL) {
     if (g.N % 64) return hipErrorInvalidValue;
     kind = GK_PARTIAL_64x64; bm = 64; bn = 64;

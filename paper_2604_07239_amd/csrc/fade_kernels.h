@@ -220,18 +220,51 @@ int fade_rows_per_block();
 hipError_t fade_reduce_rows(int P, int N, const float *part, float *out, hipStream_t s);
 // Second stages (out[n] = sum over p < P of part[p][n], rows added in a fixed order) that nothing inside the backward pass
 // waits for are queued here and run as ONE launch just before Adam. The stage-1 launchers below take the queue.
+// Adam's hyper-parameters and state arrays (device layout; gradient, master weights and both moments share the offsets)
+struct AdamArrays {
+  const float *grad_base;
+  float *master, *m, *v;
+  const UpdateState *u;
+  float lr, beta1, beta2, eps;
+};
 struct ReduceBatch {
   int count;
+  int adam[16];          // item's output is a parameter gradient: apply Adam to the parameter right after the sum
+  AdamArrays opt;        // used when any adam[] is set
   int P[16], N[16];
   const float *part[16];
   float *out[16];
   bool push(int p, int n, const float *src, float *dst) {
     if (count >= 16) return false;
-    P[count] = p; N[count] = n; part[count] = src; out[count] = dst; ++count;
+    P[count] = p; N[count] = n; part[count] = src; out[count] = dst; adam[count] = 1; ++count;
+    return true;
+  }
+  bool push_plain(int p, int n, const float *src, float *dst) {  // a sum that is not a parameter gradient
+    if (!push(p, n, src, dst)) return false;
+    adam[count - 1] = 0;
     return true;
   }
 };
 hipError_t fade_reduce_batch(const ReduceBatch &rb, hipStream_t s);
+// Adam on a [K][N] matrix of the blob in 64 x 64 blocks, writing the refreshed bf16 operand copies in the same pass: the
+// forward fragments (optionally with a LayerNorm gain folded in, plus the partial column sums of its fix-up vectors) and the
+// fragments of the transpose. A matrix may be one half of the interleaved GeGLU pair (virtual column mapping).
+struct AdamMat {
+  unsigned long long off;  // offset in the blob
+  int K, N;
+  int vcol0, vstride, VN;  // virtual column of column n: (n / 64) * vstride + (n % 64) + vcol0; VN = width of the virtual matrix
+  void *frag, *fragT;      // may be NULL
+  const float *gamma, *beta;
+  float *fold_part;        // [K / 64][2][VN] when gamma is set
+  int first_block;
+};
+struct AdamRefreshBatch {
+  int count, total_blocks;
+  int refresh_only;        // no Adam step: rebuild the copies from the master weights as they are (load / reset)
+  AdamMat m[10];
+  AdamArrays opt;
+};
+hipError_t fade_adam_refresh(const AdamRefreshBatch &ab, hipStream_t s);
 hipError_t fade_colsum(int B, int N, const void *src, float *part, float *out, bool bf16, ReduceBatch &rb, hipStream_t s);
 hipError_t fade_bwd_cci(const BwdCciArgs &a, bool bf16, hipStream_t s);
 hipError_t fade_bwd_slot(const BwdSlotArgs &a, int B, bool bf16, hipStream_t s);
