@@ -619,9 +619,7 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
   int rc;
   {
     Prof p(c, "bwd_prep_dlogits");
-    HIP_TRY(c, fade_update_prep(ws, B, c->ustate, c->cfg.beta1, c->cfg.beta2, s));
-    HIP_TRY(c, fade_dlogits(ws, targets, tstride, B, c->probs_buf, c->ustate, c->dl, bf, s));
-    HIP_TRY(c, fade_colsum(B, 256, c->dl, c->col_part, Gp(P_BO), bf, rq, s));
+    HIP_TRY(c, fade_loss_grad(ws, targets, tstride, B, c->probs_buf, c->ustate, c->cfg.beta1, c->cfg.beta2, c->dl, c->col_part, Gp(P_BO), bf, rq, s));
   }
   if (bf) {  // the two left operands the forward pass never stores: LN(H_coarse), LN(H_mix), row-major
     Prof p(c, "ln_apply", w);
@@ -738,8 +736,8 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     BwdSlotArgs a{};
     a.Dh = Dh; a.Dc = (int)d.Dc; a.c = (int)d.c; a.D = (int)d.D; a.round_bf16 = bf ? 1 : 0; a.dhm = c->dhm; a.Wm = c->P(P_WM);
     a.GG = c->GG; a.GV = c->GV; a.Wg = c->Wg_c; a.Wv = c->Wv_c; a.dgg = c->dgg; a.dgv = c->dgv; a.dxt = c->dxt;
-    HIP_TRY(c, fade_bwd_slot(a, B, bf, s));
-    HIP_TRY(c, fade_slot_weight_grad(ws, B, (int)d.T, (int)d.D, (int)d.c, c->tabXe32, c->dgg, c->dgv, c->slot_part, Gp(P_WG), rq, s));
+    a.ws = ws; a.B = B; a.T = (int)d.T; a.tabXe32 = c->tabXe32; a.part = c->slot_part;
+    HIP_TRY(c, fade_bwd_slot(a, Gp(P_WG), bf, rq, s));
   }
   {  // local stream
     Prof p(c, "bwd_conv");
@@ -1025,13 +1023,13 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
     TRY_ALLOC(dev_alloc(c, &c->dxt, d.B * d.D));
     TRY_ALLOC(dev_alloc(c, &c->row_dlam, 3 * d.B));
     const size_t tokens = d.B * d.T, rb = (d.B + fade_rows_per_block() - 1) / fade_rows_per_block();
-    c->emb_blocks = (int)std::min<size_t>(256, (tokens + 127) / 128);
+    c->emb_blocks = (int)std::min<size_t>(128, (tokens + 127) / 128);
     TRY_ALLOC(dev_alloc(c, &c->conv_part, (tokens + 127) / 128 * (d.k * d.D + 1) * d.D));
     TRY_ALLOC(dev_alloc(c, &c->tok_part, 256 * 4 * d.D));
     TRY_ALLOC(dev_alloc(c, &c->sym_sums, 2 * 256 * d.D));
     TRY_ALLOC(dev_alloc(c, &c->ln_part, 3 * rb * 2 * d.Dh));
     TRY_ALLOC(dev_alloc(c, &c->col_part, (d.B + 31) / 32 * 256));
-    TRY_ALLOC(dev_alloc(c, &c->slot_part, (d.B + 15) / 16 * 2 * d.D * d.c));
+    TRY_ALLOC(dev_alloc(c, &c->slot_part, (d.B + 3) / 4 * 2 * d.D * d.c));
     TRY_ALLOC(dev_alloc(c, &c->emb_part, (size_t)c->emb_blocks * 2 * 256 * d.D));
     if (hipMemsetAsync(c->grad, 0, np * sizeof(float), c->stream) != hipSuccess) { fade_destroy(c); return FADE_E_HIP; }
   }

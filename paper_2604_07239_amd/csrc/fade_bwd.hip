@@ -36,6 +36,33 @@ template <> __device__ __forceinline__ void st8<float>(float *p, const float v[8
   *reinterpret_cast<f32x4 *>(p + 4) = b;
 }
 
+// 8 values as loaded (no conversion: nothing waits for the load until cvt() is called)
+template <typename AT> struct Raw8B;
+template <> struct Raw8B<bf16_t> {
+  bf16x8 r;
+  __device__ __forceinline__ void load(const bf16_t *p) { r = *reinterpret_cast<const bf16x8 *>(p); }
+  __device__ __forceinline__ void zero() {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) r[i] = (bf16_t)0.0f;
+  }
+  __device__ __forceinline__ void cvt(float v[8]) const {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = (float)r[i];
+  }
+};
+template <> struct Raw8B<float> {
+  f32x4 a, b;
+  __device__ __forceinline__ void load(const float *p) { a = *reinterpret_cast<const f32x4 *>(p); b = *reinterpret_cast<const f32x4 *>(p + 4); }
+  __device__ __forceinline__ void zero() {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { a[i] = 0.0f; b[i] = 0.0f; }
+  }
+  __device__ __forceinline__ void cvt(float v[8]) const {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { v[i] = a[i]; v[4 + i] = b[i]; }
+  }
+};
+
 __device__ __forceinline__ void moments(const float *stats, int stats_n, int width, float &mean, float &rstd) {
   fade_row_moments(stats, stats_n, width, mean, rstd);
 }
@@ -65,39 +92,55 @@ __device__ __forceinline__ float block_sum(float v, float *red /*[4]*/) {
 }
 
 // ---------------------------------------------------------------------------------------------------
-// step bookkeeping: number of active streams, Adam's step count and bias corrections (one thread)
+// Start of the update, one launch: the number of active streams (every workgroup counts for itself), Adam's step count
+// and bias corrections (workgroup 0 records them for the kernels that follow), the loss gradient
+//   dlogits = (p - onehot(target)) / n_active for active streams, 0 otherwise   (gradient of the mean NLL, Eq. 12)
+// and the first stage of db_o (column sums over this workgroup's 32 streams). Thread = one of the 256 symbols.
 // ---------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void update_prep_kernel(WinSrc ws, int B, UpdateState *u, float beta1, float beta2) {
-  __shared__ int cnt[256];
-  int mine = 0;
-  for (int b = threadIdx.x; b < B; b += 256) mine += stream_active(ws, b) ? 1 : 0;
-  cnt[threadIdx.x] = mine;
-  __syncthreads();
-  if (threadIdx.x != 0) return;
-  int na = 0;
-  for (int k = 0; k < 256; ++k) na += cnt[k];
-  u->na = na;
-  if (na > 0) {
-    u->t += 1;
-    u->c1 = 1.0f - powf(beta1, (float)u->t);
-    u->c2 = 1.0f - powf(beta2, (float)u->t);
-    u->inv_na = 1.0f / (float)na;
-  }
-}
-
-// dlogits = (p - onehot(target)) / n_active for active streams, 0 otherwise (gradient of the mean NLL, Eq. 12)
 template <typename AT>
-__global__ __launch_bounds__(256) void dlogits_kernel(WinSrc ws, const uint8_t *targets, long long tstride, int B, const float *probs,
-                                                      const UpdateState *u, AT *dl) {
-  const int b = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
-  if (b >= B) return;
-  const bool act = stream_active(ws, b);
-  const f32x4 p = *reinterpret_cast<const f32x4 *>(probs + (size_t)b * 256 + 4 * lane);
-  const int x = act ? targets[(long long)b * tstride] : -1;
-  const float sc = u->inv_na;
-  AT *o = dl + (size_t)b * 256 + 4 * lane;
+__global__ __launch_bounds__(256) void loss_grad_kernel(WinSrc ws, const uint8_t *targets, long long tstride, int B, const float *probs,
+                                                        UpdateState *u, float beta1, float beta2, AT *dl, float *col_part) {
+  __shared__ int cnt[4];
+  const int tid = threadIdx.x;
+  int mine = 0;
+  for (int b = tid; b < B; b += 256) mine += stream_active(ws, b) ? 1 : 0;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) o[i] = (AT)(act ? sc * (p[i] - ((4 * lane + i) == x ? 1.0f : 0.0f)) : 0.0f);
+  for (int off = 32; off > 0; off >>= 1) mine += __shfl_xor(mine, off, 64);
+  if ((tid & 63) == 0) cnt[tid >> 6] = mine;
+  __syncthreads();
+  const int na = cnt[0] + cnt[1] + cnt[2] + cnt[3];
+  const float sc = na > 0 ? 1.0f / (float)na : 0.0f;
+  if (blockIdx.x == 0 && tid == 0) {
+    u->na = na;
+    if (na > 0) {
+      u->t += 1;
+      u->c1 = 1.0f - powf(beta1, (float)u->t);
+      u->c2 = 1.0f - powf(beta2, (float)u->t);
+      u->inv_na = sc;
+    }
+  }
+  const int b0 = blockIdx.x * 32;
+  float colsum = 0.0f;
+  // targets and flags of the 32 streams first, then the probabilities (all loads in flight together)
+  float p[32];
+  int x[32];
+#pragma unroll
+  for (int r = 0; r < 32; ++r) {
+    const int b = b0 + r;
+    const bool act = b < B && stream_active(ws, b);
+    x[r] = act ? (int)targets[(long long)b * tstride] : -1;
+    p[r] = b < B ? probs[(size_t)b * 256 + tid] : 0.0f;
+  }
+#pragma unroll
+  for (int r = 0; r < 32; ++r) {
+    const int b = b0 + r;
+    if (b >= B) break;
+    const float g = x[r] >= 0 ? sc * (p[r] - (tid == x[r] ? 1.0f : 0.0f)) : 0.0f;
+    const AT gq = (AT)g;
+    dl[(size_t)b * 256 + tid] = gq;
+    colsum += (float)gq;  // db_o is the column sum of the gradient the products see
+  }
+  col_part[(size_t)blockIdx.x * 256 + tid] = colsum;
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -578,55 +621,71 @@ __global__ __launch_bounds__(256) void bwd_cci_kernel(BwdCciArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Eq. 1-3 backward through the newest cache slot (one workgroup per stream):
+// Eq. 1-3 backward through the newest cache slot, one wavefront per stream (4 streams per workgroup):
 //   dg[q] = sum_n d(hm)[n] W_m[Dc-c+q][n];  d gg = dg gv psi'(gg);  d gv = dg psi(gg);  dxt = W_g d gg + W_v d gv
+// and the first stage of dW_g[i][q] = sum_b xt[b][i] d gg[b][q] (same for W_v): the workgroup's 4 streams, in order,
+// as part[workgroup][2][D][c] (blob order); the second stage adds the workgroups in index order.
 // ---------------------------------------------------------------------------------------------------
 template <typename AT>
 __global__ __launch_bounds__(256) void bwd_slot_kernel(BwdSlotArgs a) {
-  __shared__ float red[4];
-  __shared__ float dgg_s[64], dgv_s[64];
-  const int b = blockIdx.x, tid = threadIdx.x;
-  const AT *dhm = static_cast<const AT *>(a.dhm) + (size_t)b * a.Dh;
+  __shared__ float dg_s[4][2][64];
+  __shared__ int sym_s[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, b = blockIdx.x * 4 + wave;
+  const bool live = b < a.B;
+  const int nch = a.Dh / 8;  // 8-wide chunks of a row: lane owns chunks lane, lane + 64, ... (D_h <= 2048: at most 4)
+  float dh[4][8];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) dh[k][i] = 0.0f;
+    const int ch = lane + 64 * k;
+    if (live && ch < nch) ld8<AT>(static_cast<const AT *>(a.dhm) + (size_t)b * a.Dh + ch * 8, dh[k]);
+  }
+  float mine = 0.0f;  // lane q ends up with dg[q]
   for (int q = 0; q < a.c; ++q) {
     const float *wrow = a.Wm + (size_t)(a.Dc - a.c + q) * a.Dh;
     float s = 0.0f;
-    for (int n = tid; n < a.Dh; n += 256) {
-      float w = wrow[n];
-      if (a.round_bf16) w = (float)(bf16_t)w;
-      s = fmaf((float)dhm[n], w, s);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int ch = lane + 64 * k;
+      if (ch < nch) {
+        float w[8];
+        ld8<float>(wrow + ch * 8, w);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) s = fmaf(dh[k][i], a.round_bf16 ? (float)(bf16_t)w[i] : w[i], s);
+      }
     }
-    const float dg = block_sum(s, red);
-    if (tid == 0) {
-      const float gg = a.GG[(size_t)b * a.c + q], gv = a.GV[(size_t)b * a.c + q];
-      dgg_s[q] = dg * gv * gelu_grad_f(gg);
-      dgv_s[q] = dg * gelu_f(gg);
-      a.dgg[(size_t)b * a.c + q] = dgg_s[q];
-      a.dgv[(size_t)b * a.c + q] = dgv_s[q];
-    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    if (lane == q) mine = s;
   }
+  if (lane < a.c) {
+    float dgg = 0.0f, dgv = 0.0f;
+    if (live) {
+      const float gg = a.GG[(size_t)b * a.c + lane], gv = a.GV[(size_t)b * a.c + lane];
+      dgg = mine * gv * gelu_grad_f(gg);
+      dgv = mine * gelu_f(gg);
+      a.dgg[(size_t)b * a.c + lane] = dgg;
+      a.dgv[(size_t)b * a.c + lane] = dgv;
+    }
+    dg_s[wave][0][lane] = dgg;
+    dg_s[wave][1][lane] = dgv;
+  }
+  if (lane == 0) sym_s[wave] = (live && stream_active(a.ws, b)) ? (int)stream_window(a.ws, b, a.T)[a.T - 1] : -1;
   __syncthreads();
-  if (tid < a.D) {
+  if (live && lane < a.D) {
     float s = 0.0f;
-    for (int q = 0; q < a.c; ++q) s += a.Wg[tid * a.c + q] * dgg_s[q] + a.Wv[tid * a.c + q] * dgv_s[q];
-    a.dxt[(size_t)b * a.D + tid] = s;
+    for (int q = 0; q < a.c; ++q) s += a.Wg[lane * a.c + q] * dg_s[wave][0][q] + a.Wv[lane * a.c + q] * dg_s[wave][1][q];
+    a.dxt[(size_t)b * a.D + lane] = s;
   }
-}
-
-// dW_g[i][q] = sum_b xt[b][i] d gg[b][q] (same for W_v). Stage 1: one workgroup per 16 streams, one thread per output
-// (outputs [2][D][c] in blob order), streams in increasing order; stage 2 is reduce_rows_kernel. (16 streams per workgroup)
-__global__ __launch_bounds__(256) void slot_weight_partial_kernel(WinSrc ws, int B, int T, int D, int c, const float *tabXe32, const float *dgg,
-                                                                  const float *dgv, float *part) {
-  const int nout = 2 * D * c, b0 = blockIdx.x * 16;
-  for (int t = threadIdx.x; t < nout; t += 256) {
-    const int which = t / (D * c), r = t - which * D * c, i = r / c, q = r - i * c;
-    const float *dsrc = which ? dgv : dgg;
+  const int nout = 2 * a.D * a.c;
+  for (int t = tid; t < nout; t += 256) {
+    const int which = t / (a.D * a.c), r = t - which * a.D * a.c, i = r / a.c, q = r - i * a.c;
     float s = 0.0f;
-    for (int k = 0; k < 16 && b0 + k < B; ++k) {
-      const int b = b0 + k;
-      if (!stream_active(ws, b)) continue;
-      s = fmaf(tabXe32[(size_t)stream_window(ws, b, T)[T - 1] * D + i], dsrc[(size_t)b * c + q], s);
-    }
-    part[(size_t)blockIdx.x * nout + t] = s;
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      if (sym_s[k] >= 0) s = fmaf(a.tabXe32[(size_t)sym_s[k] * a.D + i], dg_s[k][which][q], s);  // inactive streams contribute nothing
+    a.part[(size_t)blockIdx.x * nout + t] = s;
   }
 }
 
@@ -707,63 +766,129 @@ __global__ __launch_bounds__(256) void conv_grad_partial_kernel(ConvGradArgs a) 
 //   dE[s] = rstd_s * ( P_s(gamma_e * SX[s]) + P_s(gamma_l * SL[s]) ),  P_s(v) = v - mean(v) - xhat_s * mean(v * xhat_s)
 //   d gamma_e = sum_s xhat_s * SX[s], d beta_e = sum_s SX[s]  (same with SL for the pair of Eq. 4's LayerNorm).
 // ---------------------------------------------------------------------------------------------------
-// Stage 1 of the per-symbol sums: blockIdx.y = 0 builds SX, 1 builds SL. Each workgroup owns a contiguous token range and a
-// private 256 x D table in LDS. Tokens are staged 128 at a time; 256 / D lane groups walk them in token order, group g
-// adding only the symbols with s % groups == g (disjoint table rows, so every row sees its tokens in order).
-template <typename AT>
-__global__ __launch_bounds__(256) void symbol_sums_partial_kernel(BwdTokenArgs a, long long per_block) {
-  __shared__ float tab[256 * 32];
-  __shared__ float tile[128 * 32];
-  __shared__ int sym[128];
-  const int tid = threadIdx.x, D = a.D, which = blockIdx.y;
-  const int lgD = 31 - __builtin_clz(D), Tm1 = a.T - 1, lgT = 31 - __builtin_clz(a.T);  // D and T are powers of two
-  const int lane_i = tid & (D - 1), grp = tid >> lgD, gmask = (256 >> lgD) - 1;
-  const long long tokens = (long long)a.B * a.T, t0 = (long long)blockIdx.x * per_block;
-  long long t1 = t0 + per_block;
-  if (t1 > tokens) t1 = tokens;
-  for (int e = tid; e < 256 * D; e += 256) tab[e] = 0.0f;
-  for (long long c0 = t0; c0 < t1; c0 += 128) {
-    const int cnt = (int)((t1 - c0 < 128) ? (t1 - c0) : 128);
-    __syncthreads();
-    for (int e = tid * 8; e < (cnt << lgD); e += 2048) {  // 8 channels of one token per thread and pass
-      const long long t = c0 + (e >> lgD);
-      const size_t g = ((size_t)c0 << lgD) + e;
-      float v[8];
-      if (which == 0) {
-        float w[8];
-        ld8<AT>(static_cast<const AT *>(a.dX1) + g, v);
-        ld8<AT>(static_cast<const AT *>(a.dX2) + g, w);
+// Stage 1 of the per-symbol sums, on the matrix cores: S[s][n] = sum over tokens t of onehot[t][s] * V[t][n], with V = [dX paths | dX_l]
+// (2 D columns). The one-hot operand is exact in bf16; V is split into three bf16 terms (hi + mid + lo carries 24 mantissa
+// bits), so the result is an fp32-accurate sum in a fixed order. One workgroup owns a contiguous token range and leaves a
+// partial table [2][256][D]; wavefront w owns symbols 64 w .. 64 w + 63. V is staged row-major (16-byte pieces, permuted as
+// in the weight-gradient kernel) and read with the transposing LDS load.
+template <typename AT, int D>
+__global__ __launch_bounds__(256) void symbol_sums_mfma_kernel(BwdTokenArgs a, int per_block) {
+  typedef __attribute__((ext_vector_type(4))) short i16x4;
+  typedef __attribute__((ext_vector_type(8))) short i16x8;
+  typedef __attribute__((ext_vector_type(8))) unsigned short u16x8;
+  constexpr int W2 = 2 * D, PITCH = W2 * 2, NT = W2 / 32, PPR = W2 / 8, CH = 128;
+  __shared__ __attribute__((aligned(16))) unsigned char vs[3][CH * PITCH];
+  __shared__ __attribute__((aligned(16))) unsigned short sym[CH];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lgT = 31 - __builtin_clz(a.T), Tm1 = a.T - 1;
+  const long long tokens = (long long)a.B * a.T, t_begin = (long long)blockIdx.x * per_block;
+  long long t_end = t_begin + per_block;
+  if (t_end > tokens) t_end = tokens;
+  auto swz = [](int r) { return PITCH == 128 ? (((r >> 1) & 1) << 2) : 0; };
+  f32x16 acc[2][NT];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) v[q] += w[q];
-        if ((int)(t & Tm1) == Tm1) {
-          ld8<float>(a.dxt + (((size_t)(t >> lgT)) << lgD) + (e & (D - 1)), w);
+  for (int i = 0; i < 2; ++i)
 #pragma unroll
-          for (int q = 0; q < 8; ++q) v[q] += w[q];
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+  // addresses this lane supplies to the transposing loads (k-step 0, first of the two loads), per column tile
+  const int s16 = lane & 15, r0 = (lane >> 5) * 8 + (s16 >> 2), mh = (lane >> 4) & 1;
+  int b_off[NT];
+#pragma unroll
+  for (int j = 0; j < NT; ++j) b_off[j] = r0 * PITCH + (((j * 4 + 2 * mh + ((s16 & 3) >> 1)) ^ swz(r0)) << 4) + (s16 & 1) * 8;
+  const bf16_t one = (bf16_t)1.0f, zero = (bf16_t)0.0f;
+
+  // global loads of chunk c + 1 are issued before the matrix work on chunk c (values wait in registers)
+  constexpr int ITEMS = CH * PPR / 256;
+  Raw8B<AT> ra[ITEMS], rb[ITEMS];
+  Raw8B<float> rc[ITEMS];
+  unsigned short psym = 0xFFFF;
+  auto fetch = [&](long long c0) {
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it) {
+      const int item = tid + 256 * it, tl = item / PPR, col = (item % PPR) * 8;
+      const long long t = c0 + tl;
+      ra[it].zero(); rb[it].zero(); rc[it].zero();
+      if (t < t_end) {
+        if (col < D) {
+          const size_t g = (size_t)t * D + col;
+          ra[it].load(static_cast<const AT *>(a.dX1) + g);
+          rb[it].load(static_cast<const AT *>(a.dX2) + g);
+          // newest token of its stream: the cache-slot path ends here too
+          if ((int)(t & Tm1) == Tm1) rc[it].load(a.dxt + (size_t)(t >> lgT) * D + col);
+        } else {
+          ra[it].load(static_cast<const AT *>(a.dxl) + (size_t)t * D + (col - D));
         }
-      } else {
-        ld8<AT>(static_cast<const AT *>(a.dxl) + g, v);
+      }
+    }
+    psym = 0xFFFF;  // matches no symbol: tokens past the range and inactive streams contribute nothing
+    if (tid < CH) {
+      const long long t = c0 + tid;
+      if (t < t_end) {
+        const int b = (int)(t >> lgT), j = (int)(t & Tm1);
+        if (stream_active(a.ws, b)) psym = stream_window(a.ws, b, a.T)[j];
+      }
+    }
+  };
+  if (t_begin < t_end) fetch(t_begin);
+  for (long long c0 = t_begin; c0 < t_end; c0 += CH) {
+    __syncthreads();  // the previous chunk has been consumed
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it) {
+      const int item = tid + 256 * it, tl = item / PPR, pc = item % PPR;
+      float v[8], w[8], x[8];
+      ra[it].cvt(v); rb[it].cvt(w); rc[it].cvt(x);
+      bf16x8 hi, mid, lo;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const float val = (v[q] + w[q]) + x[q];
+        hi[q] = (bf16_t)val;
+        const float r1 = val - (float)hi[q];
+        mid[q] = (bf16_t)r1;
+        lo[q] = (bf16_t)(r1 - (float)mid[q]);
+      }
+      const int pos = tl * PITCH + ((pc ^ swz(tl)) << 4);
+      *reinterpret_cast<bf16x8 *>(&vs[0][pos]) = hi;
+      *reinterpret_cast<bf16x8 *>(&vs[1][pos]) = mid;
+      *reinterpret_cast<bf16x8 *>(&vs[2][pos]) = lo;
+    }
+    if (tid < CH) sym[tid] = psym;
+    __syncthreads();
+    if (c0 + CH < t_end) fetch(c0 + CH);
+#pragma unroll 2
+    for (int ks = 0; ks < CH / 16; ++ks) {
+      const u16x8 sy = *reinterpret_cast<const u16x8 *>(sym + ks * 16 + (lane >> 5) * 8);
+      bf16x8 af[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const unsigned short s = (unsigned short)((wave * 2 + i) * 32 + (lane & 31));
+#pragma unroll
+        for (int q = 0; q < 8; ++q) af[i][q] = sy[q] == s ? one : zero;
       }
 #pragma unroll
-      for (int q = 0; q < 8; ++q) tile[e + q] = v[q];
-    }
-    if (tid < cnt) {
-      const long long t = c0 + tid;
-      const int b = (int)(t >> lgT), j = (int)(t & Tm1);
-      sym[tid] = stream_active(a.ws, b) ? stream_window(a.ws, b, a.T)[j] : -1;  // inactive streams contribute nothing
-    }
-    __syncthreads();
-    for (int k0 = 0; k0 < cnt; k0 += 8) {
-      int sy[8];
+      for (int j = 0; j < NT; ++j)
 #pragma unroll
-      for (int q = 0; q < 8; ++q) sy[q] = (k0 + q < cnt) ? sym[k0 + q] : -1;
+        for (int sp = 0; sp < 3; ++sp) {
+          const unsigned char *p = &vs[sp][0] + b_off[j] + ks * 16 * PITCH;
+          const i16x4 l4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)p);
+          const i16x4 h4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)(p + 4 * PITCH));
+          const bf16x8 bfr = __builtin_bit_cast(bf16x8, (i16x8)__builtin_shufflevector(l4, h4, 0, 1, 2, 3, 4, 5, 6, 7));
 #pragma unroll
-      for (int q = 0; q < 8; ++q)
-        if (sy[q] >= 0 && (sy[q] & gmask) == grp) tab[sy[q] * D + lane_i] += tile[(k0 + q) * D + lane_i];
+          for (int i = 0; i < 2; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr, acc[i][j], 0, 0, 0);
+        }
     }
   }
-  __syncthreads();
-  float *out = a.part + ((size_t)blockIdx.x * 2 + which) * 256 * D;
-  for (int e = tid; e < 256 * D; e += 256) out[e] = tab[e];
+  float *out = a.part + (size_t)blockIdx.x * 2 * 256 * D;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int s = (wave * 2 + i) * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3), n = j * 32 + (lane & 31);
+        out[((size_t)(n / D) * 256 + s) * D + (n % D)] = acc[i][j][e];
+      }
 }
 
 // Finish on the tables: one workgroup per symbol, lane = channel. sums: [2][256][D] (SX then SL).
@@ -911,15 +1036,15 @@ inline unsigned nblk(size_t n, unsigned per) { return (unsigned)((n + per - 1) /
     return hipGetLastError();                                                                     \
   } while (0)
 
-hipError_t fade_update_prep(const WinSrc &ws, int B, UpdateState *u, float beta1, float beta2, hipStream_t s) {
-  hipLaunchKernelGGL(update_prep_kernel, dim3(1), dim3(256), 0, s, ws, B, u, beta1, beta2);
-  return hipGetLastError();
-}
-hipError_t fade_dlogits(const WinSrc &ws, const uint8_t *targets, long long tstride, int B, const float *probs, const UpdateState *u,
-                        void *dl, bool bf16, hipStream_t s) {
-  if (bf16) hipLaunchKernelGGL(dlogits_kernel<bf16_t>, dim3((B + 3) / 4), dim3(256), 0, s, ws, targets, tstride, B, probs, u, static_cast<bf16_t *>(dl));
-  else hipLaunchKernelGGL(dlogits_kernel<float>, dim3((B + 3) / 4), dim3(256), 0, s, ws, targets, tstride, B, probs, u, static_cast<float *>(dl));
-  return hipGetLastError();
+// col_part must hold ceil(B / 32) * 256 floats; db_o's second stage is queued in rb
+hipError_t fade_loss_grad(const WinSrc &ws, const uint8_t *targets, long long tstride, int B, const float *probs, UpdateState *u, float beta1,
+                          float beta2, void *dl, float *col_part, float *dbo, bool bf16, ReduceBatch &rb, hipStream_t s) {
+  const int P = (B + 31) / 32;
+  if (bf16) hipLaunchKernelGGL(loss_grad_kernel<bf16_t>, dim3(P), dim3(256), 0, s, ws, targets, tstride, B, probs, u, beta1, beta2, static_cast<bf16_t *>(dl), col_part);
+  else hipLaunchKernelGGL(loss_grad_kernel<float>, dim3(P), dim3(256), 0, s, ws, targets, tstride, B, probs, u, beta1, beta2, static_cast<float *>(dl), col_part);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return rb.push(P, 256, col_part, dbo) ? hipSuccess : hipErrorInvalidValue;
 }
 hipError_t fade_transpose(const TransposeArgs &a, int N, bool bf16, hipStream_t s) {
   if (N % 64) return hipErrorInvalidValue;
@@ -983,15 +1108,15 @@ hipError_t fade_colsum(int B, int N, const void *src, float *part, float *out, b
   return rb.push(P, N, part, out) ? hipSuccess : hipErrorInvalidValue;
 }
 hipError_t fade_bwd_cci(const BwdCciArgs &a, bool bf16, hipStream_t s) { DISPATCH_AT(bf16, bwd_cci_kernel, dim3(a.B), dim3(256), s, a); }
-hipError_t fade_bwd_slot(const BwdSlotArgs &a, int B, bool bf16, hipStream_t s) { DISPATCH_AT(bf16, bwd_slot_kernel, dim3(B), dim3(256), s, a); }
-// part must hold ceil(B / 16) * 2 * D * c floats; dWgv points at W_g's gradient (W_v's follows it in the blob)
-hipError_t fade_slot_weight_grad(const WinSrc &ws, int B, int T, int D, int c, const float *tabXe32, const float *dgg, const float *dgv,
-                                 float *part, float *dWgv, ReduceBatch &rb, hipStream_t s) {
-  const int P = (B + 15) / 16;
-  hipLaunchKernelGGL(slot_weight_partial_kernel, dim3(P), dim3(256), 0, s, ws, B, T, D, c, tabXe32, dgg, dgv, part);
+// a.part must hold ceil(B / 4) * 2 * D * c floats; dWgv points at W_g's gradient (W_v's follows it in the blob)
+hipError_t fade_bwd_slot(const BwdSlotArgs &a, float *dWgv, bool bf16, ReduceBatch &rb, hipStream_t s) {
+  if (a.Dh > 2048 || a.Dh % 8 || a.c > 64 || a.D > 64) return hipErrorInvalidValue;
+  const int P = (a.B + 3) / 4;
+  if (bf16) hipLaunchKernelGGL(bwd_slot_kernel<bf16_t>, dim3(P), dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(bwd_slot_kernel<float>, dim3(P), dim3(256), 0, s, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  return rb.push(P, 2 * D * c, part, dWgv) ? hipSuccess : hipErrorInvalidValue;
+  return rb.push(P, 2 * a.D * a.c, a.part, dWgv) ? hipSuccess : hipErrorInvalidValue;
 }
 // a.part must hold ceil(B * T / 128) * (taps * D + 1) * D floats; dWb points at W_conv's gradient (b_conv's follows it)
 hipError_t fade_conv_grad(const ConvGradArgs &a, float *dWb, bool bf16, ReduceBatch &rb, hipStream_t s) {
@@ -1008,9 +1133,16 @@ hipError_t fade_conv_grad(const ConvGradArgs &a, float *dWb, bool bf16, ReduceBa
 hipError_t fade_bwd_embed(const BwdTokenArgs &a, int nblocks, float *sums, float *contrib, float *dE, float *dparams, bool bf16, ReduceBatch &rb,
                           hipStream_t s) {
   if (256 % a.D || a.D > 32 || a.D % 8) return hipErrorInvalidValue;
-  const long long tokens = (long long)a.B * a.T, per = (tokens + nblocks - 1) / nblocks;
-  if (bf16) hipLaunchKernelGGL(symbol_sums_partial_kernel<bf16_t>, dim3(nblocks, 2), dim3(256), 0, s, a, per);
-  else hipLaunchKernelGGL(symbol_sums_partial_kernel<float>, dim3(nblocks, 2), dim3(256), 0, s, a, per);
+  if (a.D != 16 && a.D != 32) return hipErrorInvalidValue;
+  const long long tokens = (long long)a.B * a.T;
+  const int per = (int)(((tokens + nblocks - 1) / nblocks + 127) / 128 * 128);  // whole 128-token chunks per workgroup
+  if (bf16) {
+    if (a.D == 32) hipLaunchKernelGGL((symbol_sums_mfma_kernel<bf16_t, 32>), dim3(nblocks), dim3(256), 0, s, a, per);
+    else hipLaunchKernelGGL((symbol_sums_mfma_kernel<bf16_t, 16>), dim3(nblocks), dim3(256), 0, s, a, per);
+  } else {
+    if (a.D == 32) hipLaunchKernelGGL((symbol_sums_mfma_kernel<float, 32>), dim3(nblocks), dim3(256), 0, s, a, per);
+    else hipLaunchKernelGGL((symbol_sums_mfma_kernel<float, 16>), dim3(nblocks), dim3(256), 0, s, a, per);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if ((e = fade_reduce_rows(nblocks, 2 * 256 * a.D, a.part, sums, s)) != hipSuccess) return e;

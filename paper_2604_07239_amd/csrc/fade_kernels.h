@@ -183,6 +183,8 @@ struct BwdCciArgs {
   float lr, beta1, beta2, eps;
 };
 struct BwdSlotArgs {
+  WinSrc ws;
+  int B, T;
   int Dh, Dc, c, D, round_bf16;
   const void *dhm;        // [B][Dh]
   const float *Wm;        // fp32 master W_m [Dc][Dh]
@@ -190,6 +192,8 @@ struct BwdSlotArgs {
   const float *Wg, *Wv;   // [D][c] compute values
   float *dgg, *dgv;       // [B][c]
   float *dxt;             // [B][D]
+  const float *tabXe32;   // [256][D] normalised embedding rows (x_t of the newest symbol)
+  float *part;            // [ceil(B / 4)][2][D][c] first stage of dW_g, dW_v
 };
 struct ConvGradArgs {
   int B, T, D, taps;
@@ -206,9 +210,6 @@ struct BwdTokenArgs {
   float *part;                    // [blocks][2][256][D] per-symbol partial sums
 };
 
-hipError_t fade_update_prep(const WinSrc &ws, int B, UpdateState *u, float beta1, float beta2, hipStream_t s);
-hipError_t fade_dlogits(const WinSrc &ws, const uint8_t *targets, long long tstride, int B, const float *probs, const UpdateState *u,
-                        void *dl, bool bf16, hipStream_t s);
 hipError_t fade_transpose(const TransposeArgs &a, int N, bool bf16, hipStream_t s);
 hipError_t fade_transpose_batch(const TransposeBatch &tb, bool bf16, hipStream_t s);
 hipError_t fade_embed_t(const WinSrc &ws, int B, int Bp, int T, int D, const void *tab, void *XT, bool bf16, hipStream_t s);
@@ -246,6 +247,8 @@ struct ReduceBatch {
   }
 };
 hipError_t fade_reduce_batch(const ReduceBatch &rb, hipStream_t s);
+hipError_t fade_loss_grad(const WinSrc &ws, const uint8_t *targets, long long tstride, int B, const float *probs, UpdateState *u, float beta1,
+                          float beta2, void *dl, float *col_part, float *dbo, bool bf16, ReduceBatch &rb, hipStream_t s);
 // Adam on a [K][N] matrix of the blob in 64 x 64 blocks, writing the refreshed bf16 operand copies in the same pass: the
 // forward fragments (optionally with a LayerNorm gain folded in, plus the partial column sums of its fix-up vectors) and the
 // fragments of the transpose. A matrix may be one half of the interleaved GeGLU pair (virtual column mapping).
@@ -267,9 +270,7 @@ struct AdamRefreshBatch {
 hipError_t fade_adam_refresh(const AdamRefreshBatch &ab, hipStream_t s);
 hipError_t fade_colsum(int B, int N, const void *src, float *part, float *out, bool bf16, ReduceBatch &rb, hipStream_t s);
 hipError_t fade_bwd_cci(const BwdCciArgs &a, bool bf16, hipStream_t s);
-hipError_t fade_bwd_slot(const BwdSlotArgs &a, int B, bool bf16, hipStream_t s);
-hipError_t fade_slot_weight_grad(const WinSrc &ws, int B, int T, int D, int c, const float *tabXe32, const float *dgg, const float *dgv,
-                                 float *part, float *dWgv, ReduceBatch &rb, hipStream_t s);
+hipError_t fade_bwd_slot(const BwdSlotArgs &a, float *dWgv, bool bf16, ReduceBatch &rb, hipStream_t s);
 hipError_t fade_conv_grad(const ConvGradArgs &a, float *dWb, bool bf16, ReduceBatch &rb, hipStream_t s);
 hipError_t fade_bwd_embed(const BwdTokenArgs &a, int nblocks, float *sums, float *contrib, float *dE, float *dparams, bool bf16, ReduceBatch &rb,
                           hipStream_t s);
