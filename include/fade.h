@@ -105,7 +105,8 @@ int fade_step_probs(fade_ctx *ctx, const uint8_t *windows_dev, const uint8_t *ac
 
 /* Online mode only: mean NLL (Eq. 12) of targets_dev[B] over the active streams under the probabilities of
  * the preceding fade_step_probs, backward through the step, one Adam update of every parameter (shared
- * weights and each active stream's W_U slice). Asynchronous like fade_step_probs. */
+ * weights and each active stream's W_U slice). The library keeps its own copy of that call's windows, so the caller's
+ * window buffer need not outlive fade_step_probs. Asynchronous like fade_step_probs. */
 int fade_step_update(fade_ctx *ctx, const uint8_t *targets_dev, const uint8_t *active_dev);
 
 /* Upper bound of the container size for n input bytes. */

@@ -135,6 +135,7 @@ struct fade_ctx {
   size_t Bp = 0;  // batch rounded up to 64: leading dimension of the feature-major copies and row count of GEMM_W operands
   float *grad = nullptr, *adam_m = nullptr, *adam_v = nullptr;
   UpdateState *ustate = nullptr;
+  uint8_t *win_copy = nullptr;  // online mode: the windows of the last fade_step_probs, for fade_step_update
   float *tabXhat = nullptr, *tabRstd = nullptr, *convt_f32 = nullptr;
   void *WT_o = nullptr, *WT_f = nullptr, *WT_fgv = nullptr, *WT_c = nullptr, *WT_up = nullptr, *WT_down = nullptr, *WT_r = nullptr,
        *WT_conv = nullptr;
@@ -1022,6 +1023,7 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
     TRY_ALLOC(dev_alloc(c, &c->dgv, d.B * d.c));
     TRY_ALLOC(dev_alloc(c, &c->dxt, d.B * d.D));
     TRY_ALLOC(dev_alloc(c, &c->row_dlam, 3 * d.B));
+    TRY_ALLOC(dev_alloc(c, &c->win_copy, d.B * d.T));
     const size_t tokens = d.B * d.T, rb = (d.B + fade_rows_per_block() - 1) / fade_rows_per_block();
     c->emb_blocks = (int)std::min<size_t>(128, (tokens + 127) / 128);
     TRY_ALLOC(dev_alloc(c, &c->conv_part, (tokens + 127) / 128 * (d.k * d.D + 1) * d.D));
@@ -1074,7 +1076,11 @@ int fade_step_probs(fade_ctx *c, const uint8_t *windows_dev, const uint8_t *acti
   if (!c->have_weights) return fail(c, FADE_E_NO_WEIGHTS, "no weights loaded");
   WinSrc ws{};
   ws.base = windows_dev; ws.stride = (long long)c->d.T; ws.n = 0; ws.active = active_dev ? active_dev : c->ones; ws.i = (long long)c->d.T;
-  c->last_ws = ws;  // fade_step_update re-reads these windows (embedding gradient): they must stay valid until then
+  if (c->online) {  // fade_step_update re-reads the windows (embedding and slot gradients): keep a copy, the caller's may be gone by then
+    HIP_TRY(c, hipMemcpyAsync(c->win_copy, windows_dev, c->d.B * c->d.T, hipMemcpyDeviceToDevice, c->stream));
+    ws.base = c->win_copy;
+  }
+  c->last_ws = ws;
   return forward(c, ws, CODE_NONE, nullptr, freq_dev, probs_dev);
 }
 

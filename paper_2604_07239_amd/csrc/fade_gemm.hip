@@ -827,6 +827,8 @@ hipError_t launch_tn(const GemmArgs &g, hipStream_t s) {
 template <int EPI>
 hipError_t launch_pipe_auto(const GemmArgs &g, hipStream_t s) {
   const int tiles128 = ((g.M + 127) / 128) * (g.N / 128);
+  const int tiles256 = ((g.M + 255) / 256) * (g.N / 128);
+  if (fade_gemm_tune() == 10 || (fade_gemm_tune() == 0 && tiles256 >= 256)) return launch_pipe<256, 128, 3, EPI>(g, s);
   if (fade_gemm_tune() == 1 || (fade_gemm_tune() == 0 && tiles128 >= 256)) return launch_pipe<128, 128, 4, EPI>(g, s);
   if (fade_gemm_tune() == 4) return launch_pipe<64, 128, 3, EPI>(g, s);
   if (fade_gemm_tune() == 5) return launch_pipe<64, 128, 2, EPI>(g, s);

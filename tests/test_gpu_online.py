@@ -31,6 +31,8 @@ def _grad_check(dtype, B, T, D, H, seed, tol):
         ad = None if act is None else torch.from_numpy(act).cuda()
         _log(f"online step {i} {dtype} B={B}")
         g.step_probs(wd, ad, None, probs_d)
+        torch.cuda.synchronize()
+        wd.zero_()  # the library works from its own copy of the windows: the caller's buffer may change before the update
         _, po = o.step_probs(win, act)
         live = np.ones(B, bool) if act is None else act.astype(bool)
         assert np.abs(probs_d.cpu().numpy()[live] - po[live]).max() <= 1e-3
@@ -112,3 +114,50 @@ def test_online_is_deterministic():
     a = g.encode(src)
     b = g.encode(src)
     assert a.tobytes() == b.tobytes()
+
+
+def test_online_update_config2_full_batch():
+    """Configuration 2 at its full B = 1024 (the launch shapes bench.py times): one online step from identical states.
+    The shared-weight gradient couples all streams, so the oracle runs the whole batch once (about half a minute on one
+    core); the step after the update is checked on a sample of streams."""
+    torch = need_gpu()
+    import paper_2604_07239_amd as fa
+    spec = fi.CONFIGS[2]
+    B, T, D, H = spec["B"], spec["T"], spec["D"], spec["H"]
+    blob = fi.config_blob(2)
+    g = fa.Fade(fa.make_config(B, T, D, H, dtype=fa.BF16, update_mode=fa.ONLINE_ADAM))
+    g.load_weights(blob.data)
+    o = orc.Oracle(orc.make_config(B, T, D, H, dtype=orc.BF16, update_mode=orc.ONLINE_ADAM))
+    o.load_weights(blob.data)
+    data = fi.config_bytes(2, B * 256).reshape(B, -1)[:, :T + 2]
+    win = np.ascontiguousarray(data[:, :T]); tgt = np.ascontiguousarray(data[:, T])
+    probs_d = torch.zeros((B, 256), dtype=torch.float32, device="cuda")
+    _log("cfg2 online: forward")
+    wd = torch.from_numpy(win).cuda()  # the update re-reads the windows: they must stay alive until then
+    g.step_probs(wd, None, None, probs_d)
+    _, po = o.step_probs(win, None)
+    assert np.abs(probs_d.cpu().numpy() - po).max() <= 1e-3
+    _log("cfg2 online: oracle backward")
+    go = o.backward(tgt, None)
+    _log("cfg2 online: GPU update")
+    g.step_update(torch.from_numpy(tgt).cuda(), None)
+    gg = g.debug_grad()
+    bad = {}
+    for name, shape, _ in blob.specs:
+        if name == "W_U":
+            continue
+        a = blob.view(gg, name).astype(np.float64).ravel()
+        r = blob.view(go, name).ravel()
+        err = np.abs(a - r).max() / max(np.abs(r).max(), 1e-12)
+        if err > (0.6 if a.size == 1 else 3e-2):
+            bad[name] = float(err)
+    assert not bad, f"gradient mismatch (max |dg| / max |g|): {bad}"
+    o.step_update(tgt, None)
+    act = np.zeros(B, np.uint8); act[:8] = 1; act[-8:] = 1
+    win2 = np.ascontiguousarray(data[:, 1:T + 1])
+    _log("cfg2 online: step after the update")
+    wd2 = torch.from_numpy(win2).cuda()
+    g.step_probs(wd2, None, None, probs_d)
+    _, po2 = o.step_probs(win2, act)
+    live = act.astype(bool)
+    assert np.abs(probs_d.cpu().numpy()[live] - po2[live]).max() <= 1e-3

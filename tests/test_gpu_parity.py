@@ -181,6 +181,50 @@ def test_step_parity_bf16_config2_shape_sampled():
         assert np.all(np.abs(pg.astype(np.float64).sum(1) - 1) < 1e-5)
 
 
+def _sampled_streams_parity(cfg, streams, steps=2):
+    """Full batch of a benchmark configuration on the GPU (the launch shapes bench.py times: tile sizes and grids depend on
+    B); the oracle follows a sample of streams, each with its own W_U slice. Streams are independent in the frozen step."""
+    torch = need_gpu()
+    import paper_2604_07239_amd as fa
+    spec = fi.CONFIGS[cfg]
+    B, T, D, H = spec["B"], spec["T"], spec["D"], spec["H"]
+    blob = fi.config_blob(cfg)
+    idx = np.asarray(streams)
+    sub = fi.Blob(len(idx), T, D, H)
+    for name, _, _ in sub.specs:
+        sub[name] = blob[name][idx] if name == "W_U" else blob[name]
+    g = fa.Fade(fa.make_config(B, T, D, H, dtype=fa.BF16))
+    g.load_weights(blob.data)
+    o = orc.Oracle(orc.make_config(len(idx), T, D, H, dtype=orc.BF16))
+    o.load_weights(sub.data)
+    data = fi.config_bytes(cfg, B * 256).reshape(B, -1)[:, :T + steps]
+    probs_d = torch.zeros((B, 256), dtype=torch.float32, device="cuda")
+    freq_d = torch.zeros((B, 256), dtype=torch.int16, device="cuda")
+    for i in range(steps):
+        win = np.ascontiguousarray(data[:, i:i + T])
+        _log(f"cfg{cfg} full batch B={B} step {i}")
+        g.step_probs(torch.from_numpy(win).cuda(), None, freq_d, probs_d)
+        _, po = o.step_probs(np.ascontiguousarray(win[idx]))
+        pg = probs_d.cpu().numpy()
+        assert np.abs(pg[idx] - po).max() <= 1e-3
+        np.testing.assert_allclose(pg[idx], po, rtol=5e-2, atol=2e-5)
+        # properties that hold for every stream of the batch
+        assert np.all(np.isfinite(pg)) and np.all(np.abs(pg.astype(np.float64).sum(1) - 1) < 1e-5)
+        fg = freq_d.cpu().numpy().view(np.uint16)
+        assert fg.min() >= 1 and np.all(fg.astype(np.int64).sum(1) == 65536)
+        np.testing.assert_array_equal(fg[idx], orc.quantize(pg[idx]))
+
+
+def test_step_parity_config3_full_batch_sampled():
+    """B = 4096 (configurations 3 and 4 share the model shape): 256-row tiles in the router / gate products."""
+    _sampled_streams_parity(3, list(range(6)) + [1023, 2048, 4000] + list(range(4090, 4096)))
+
+
+def test_step_parity_config5_full_batch_sampled():
+    """B = 16384, H = 512: the largest configuration."""
+    _sampled_streams_parity(5, list(range(4)) + [5000, 9999] + list(range(16380, 16384)), steps=2)
+
+
 # ---------------------------------------------------------------------------------------------------
 # compress / decompress
 # ---------------------------------------------------------------------------------------------------
