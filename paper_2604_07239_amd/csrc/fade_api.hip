@@ -1,6 +1,5 @@
 // fade_api.hip — libfade's C ABI: context, device state, the step sequence and the compress / decompress loops.
 #include <algorithm>
-#include <chrono>
 #include <initializer_list>
 #include <utility>
 #include <cmath>
@@ -123,7 +122,7 @@ struct fade_ctx {
   float *y = nullptr, *logits = nullptr, *stats_c = nullptr, *stats_f = nullptr, *stats_o = nullptr;
   // bf16 path: split-K partials, folded-LayerNorm vectors, the materialised H of Eq. 10
   float *part_down = nullptr, *part_fnr = nullptr, *part_head = nullptr;
-  float *s_down = nullptr, *t_down = nullptr, *s_fnr = nullptr, *t_fnr = nullptr, *fold_part = nullptr;
+  float *s_down = nullptr, *t_down = nullptr, *s_fnr = nullptr, *t_fnr = nullptr;
   float *fold_down = nullptr, *fold_fnr = nullptr;  // per 64-row block partials of those vectors, written by the Adam + refresh kernel
   void *Hout = nullptr;
   int sp_down = 1, sp_fnr = 1, sp_head = 1;
@@ -831,7 +830,6 @@ int run_loop(fade_ctx *c, uint8_t *bytes_dev, size_t n, size_t first, size_t cou
   const size_t last = (count == 0 || first + count > L) ? L : first + count;
   WinSrc ws{};
   ws.base = bytes_dev; ws.stride = (long long)L; ws.n = (long long)n; ws.active = nullptr;
-  const auto t_host0 = std::chrono::steady_clock::now();
   for (size_t i = first; i < last; ++i) {
     ws.i = (long long)i;
     if (i < d.T) {
@@ -847,10 +845,6 @@ int run_loop(fade_ctx *c, uint8_t *bytes_dev, size_t n, size_t first, size_t cou
     }
   }
   c->loop_next = last;
-  if (getenv("FADE_TRACE_HOST")) {
-    const double ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_host0).count();
-    fprintf(stderr, "[fade] host enqueue: %.3f ms for %zu steps (%.1f us/step) before the final wait\n", ms, last - first, 1e3 * ms / (double)(last - first));
-  }
   if (mode == CODE_ENCODE && last == L && !c->enc_complete) {
     HIP_TRY(c, fade_coder_finish(c->cb, (int)d.B, (long long)L, (long long)n, s));
     c->enc_complete = true;
@@ -943,7 +937,6 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
     c->t_down = c->s_down + d.dl;
     TRY_ALLOC(dev_alloc(c, &c->s_fnr, 4 * d.De));
     c->t_fnr = c->s_fnr + 2 * d.De;
-    TRY_ALLOC(dev_alloc(c, &c->fold_part, 16 * 2 * std::max<size_t>(d.dl, 2 * d.De)));
     TRY_ALLOC(dev_alloc(c, &c->fold_down, d.Dh / 64 * 2 * d.dl));
     TRY_ALLOC(dev_alloc(c, &c->fold_fnr, d.Dh / 64 * 2 * 2 * d.De));
   } else {  // fp32: most operands are used straight from the master blob
@@ -1025,12 +1018,12 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
     TRY_ALLOC(dev_alloc(c, &c->row_dlam, 3 * d.B));
     TRY_ALLOC(dev_alloc(c, &c->win_copy, d.B * d.T));
     const size_t tokens = d.B * d.T, rb = (d.B + fade_rows_per_block() - 1) / fade_rows_per_block();
-    c->emb_blocks = (int)std::min<size_t>(128, (tokens + 127) / 128);
+    c->emb_blocks = (int)std::min<size_t>(256, (tokens + 127) / 128);
     TRY_ALLOC(dev_alloc(c, &c->conv_part, (tokens + 127) / 128 * (d.k * d.D + 1) * d.D));
     TRY_ALLOC(dev_alloc(c, &c->tok_part, 256 * 4 * d.D));
     TRY_ALLOC(dev_alloc(c, &c->sym_sums, 2 * 256 * d.D));
     TRY_ALLOC(dev_alloc(c, &c->ln_part, 3 * rb * 2 * d.Dh));
-    TRY_ALLOC(dev_alloc(c, &c->col_part, (d.B + 31) / 32 * 256));
+    TRY_ALLOC(dev_alloc(c, &c->col_part, (d.B + 7) / 8 * 256));
     TRY_ALLOC(dev_alloc(c, &c->slot_part, (d.B + 3) / 4 * 2 * d.D * d.c));
     TRY_ALLOC(dev_alloc(c, &c->emb_part, (size_t)c->emb_blocks * 2 * 256 * d.D));
     if (hipMemsetAsync(c->grad, 0, np * sizeof(float), c->stream) != hipSuccess) { fade_destroy(c); return FADE_E_HIP; }

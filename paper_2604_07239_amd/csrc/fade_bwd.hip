@@ -95,7 +95,7 @@ __device__ __forceinline__ float block_sum(float v, float *red /*[4]*/) {
 // Start of the update, one launch: the number of active streams (every workgroup counts for itself), Adam's step count
 // and bias corrections (workgroup 0 records them for the kernels that follow), the loss gradient
 //   dlogits = (p - onehot(target)) / n_active for active streams, 0 otherwise   (gradient of the mean NLL, Eq. 12)
-// and the first stage of db_o (column sums over this workgroup's 32 streams). Thread = one of the 256 symbols.
+// and the first stage of db_o (column sums over this workgroup's 8 streams). Thread = one of the 256 symbols.
 // ---------------------------------------------------------------------------------------------------
 template <typename AT>
 __global__ __launch_bounds__(256) void loss_grad_kernel(WinSrc ws, const uint8_t *targets, long long tstride, int B, const float *probs,
@@ -119,20 +119,20 @@ __global__ __launch_bounds__(256) void loss_grad_kernel(WinSrc ws, const uint8_t
       u->inv_na = sc;
     }
   }
-  const int b0 = blockIdx.x * 32;
+  const int b0 = blockIdx.x * 8;
   float colsum = 0.0f;
-  // targets and flags of the 32 streams first, then the probabilities (all loads in flight together)
-  float p[32];
-  int x[32];
+  // targets and flags of the 8 streams first, then the probabilities (all loads in flight together)
+  float p[8];
+  int x[8];
 #pragma unroll
-  for (int r = 0; r < 32; ++r) {
+  for (int r = 0; r < 8; ++r) {
     const int b = b0 + r;
     const bool act = b < B && stream_active(ws, b);
     x[r] = act ? (int)targets[(long long)b * tstride] : -1;
     p[r] = b < B ? probs[(size_t)b * 256 + tid] : 0.0f;
   }
 #pragma unroll
-  for (int r = 0; r < 32; ++r) {
+  for (int r = 0; r < 8; ++r) {
     const int b = b0 + r;
     if (b >= B) break;
     const float g = x[r] >= 0 ? sc * (p[r] - (tid == x[r] ? 1.0f : 0.0f)) : 0.0f;
@@ -557,16 +557,6 @@ __global__ __launch_bounds__(256) void reduce_batch_kernel(ReduceBatch rb) {
     if (rb.adam[k]) adam_element(rb.opt, (size_t)(rb.out[k] - rb.opt.grad_base) + n, t);
   }
 }
-// stage 1 for a plain matrix: part[rb][n] = sum over the 32 rows of row block rb of src[b][n]
-template <typename AT>
-__global__ __launch_bounds__(256) void colsum_partial_kernel(int B, int N, const AT *src, float *part) {
-  const int n = blockIdx.y * 256 + threadIdx.x, b0 = blockIdx.x * 32;
-  if (n >= N) return;
-  float s = 0.0f;
-  for (int r = 0; r < 32 && b0 + r < B; ++r) s += (float)src[(size_t)(b0 + r) * N + n];
-  part[(size_t)blockIdx.x * N + n] = s;
-}
-
 // ---------------------------------------------------------------------------------------------------
 // Eq. 7's per-stream memory, backward + its own Adam step (one wavefront per stream, d_low = 64):
 //   dz = sum of split partials; dy[k] = sum_n W_U[b][k][n] dz[n]; grad W_U[b][k][n] = y[k] dz[n].
@@ -767,8 +757,8 @@ __global__ __launch_bounds__(256) void conv_grad_partial_kernel(ConvGradArgs a) 
 //   d gamma_e = sum_s xhat_s * SX[s], d beta_e = sum_s SX[s]  (same with SL for the pair of Eq. 4's LayerNorm).
 // ---------------------------------------------------------------------------------------------------
 // Stage 1 of the per-symbol sums, on the matrix cores: S[s][n] = sum over tokens t of onehot[t][s] * V[t][n], with V = [dX paths | dX_l]
-// (2 D columns). The one-hot operand is exact in bf16; V is split into three bf16 terms (hi + mid + lo carries 24 mantissa
-// bits), so the result is an fp32-accurate sum in a fixed order. One workgroup owns a contiguous token range and leaves a
+// (2 D columns). The one-hot operand is exact in bf16; V is split into bf16 terms (hi + mid + lo carries 24 mantissa bits; two
+// terms are enough for bf16 inputs), so the result is an fp32-accurate sum in a fixed order. One workgroup owns a contiguous token range and leaves a
 // partial table [2][256][D]; wavefront w owns symbols 64 w .. 64 w + 63. V is staged row-major (16-byte pieces, permuted as
 // in the weight-gradient kernel) and read with the transposing LDS load.
 template <typename AT, int D>
@@ -777,7 +767,9 @@ __global__ __launch_bounds__(256) void symbol_sums_mfma_kernel(BwdTokenArgs a, i
   typedef __attribute__((ext_vector_type(8))) short i16x8;
   typedef __attribute__((ext_vector_type(8))) unsigned short u16x8;
   constexpr int W2 = 2 * D, PITCH = W2 * 2, NT = W2 / 32, PPR = W2 / 8, CH = 128;
-  __shared__ __attribute__((aligned(16))) unsigned char vs[3][CH * PITCH];
+  // bf16 inputs: a sum of two bf16 values (plus, for one token in T, an fp32 term) is carried by two terms to 2^-17
+  constexpr int NS = sizeof(AT) == 2 ? 2 : 3;
+  __shared__ __attribute__((aligned(16))) unsigned char vs[NS][CH * PITCH];
   __shared__ __attribute__((aligned(16))) unsigned short sym[CH];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lgT = 31 - __builtin_clz(a.T), Tm1 = a.T - 1;
@@ -851,7 +843,7 @@ __global__ __launch_bounds__(256) void symbol_sums_mfma_kernel(BwdTokenArgs a, i
       const int pos = tl * PITCH + ((pc ^ swz(tl)) << 4);
       *reinterpret_cast<bf16x8 *>(&vs[0][pos]) = hi;
       *reinterpret_cast<bf16x8 *>(&vs[1][pos]) = mid;
-      *reinterpret_cast<bf16x8 *>(&vs[2][pos]) = lo;
+      if (NS == 3) *reinterpret_cast<bf16x8 *>(&vs[NS - 1][pos]) = lo;
     }
     if (tid < CH) sym[tid] = psym;
     __syncthreads();
@@ -869,7 +861,7 @@ __global__ __launch_bounds__(256) void symbol_sums_mfma_kernel(BwdTokenArgs a, i
 #pragma unroll
       for (int j = 0; j < NT; ++j)
 #pragma unroll
-        for (int sp = 0; sp < 3; ++sp) {
+        for (int sp = 0; sp < NS; ++sp) {
           const unsigned char *p = &vs[sp][0] + b_off[j] + ks * 16 * PITCH;
           const i16x4 l4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)p);
           const i16x4 h4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)(p + 4 * PITCH));
@@ -911,23 +903,6 @@ __global__ __launch_bounds__(64) void embed_finish_kernel(int D, const float *su
     float *c = contrib + (size_t)s * 4 * D;
     c[i] = xh * sx; c[D + i] = sx; c[2 * D + i] = xh * sl; c[3 * D + i] = sl;
   }
-}
-
-// ---------------------------------------------------------------------------------------------------
-// Adam (bias-corrected, no weight decay) on a range of the blob
-// ---------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void adam_kernel(size_t n, const float *grad, float *master, float *m, float *v, const UpdateState *u,
-                                                   float lr, float beta1, float beta2, float eps) {
-  const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (t >= n) return;
-  const UpdateState us = *u;
-  if (us.na == 0) return;
-  const float g = grad[t];
-  const float mk = beta1 * m[t] + (1.0f - beta1) * g;
-  const float vk = beta2 * v[t] + (1.0f - beta2) * g * g;
-  m[t] = mk;
-  v[t] = vk;
-  master[t] = master[t] - lr * (mk / us.c1) / (sqrtf(vk / us.c2) + eps);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -1036,10 +1011,10 @@ inline unsigned nblk(size_t n, unsigned per) { return (unsigned)((n + per - 1) /
     return hipGetLastError();                                                                     \
   } while (0)
 
-// col_part must hold ceil(B / 32) * 256 floats; db_o's second stage is queued in rb
+// col_part must hold ceil(B / 8) * 256 floats; db_o's second stage is queued in rb
 hipError_t fade_loss_grad(const WinSrc &ws, const uint8_t *targets, long long tstride, int B, const float *probs, UpdateState *u, float beta1,
                           float beta2, void *dl, float *col_part, float *dbo, bool bf16, ReduceBatch &rb, hipStream_t s) {
-  const int P = (B + 31) / 32;
+  const int P = (B + 7) / 8;
   if (bf16) hipLaunchKernelGGL(loss_grad_kernel<bf16_t>, dim3(P), dim3(256), 0, s, ws, targets, tstride, B, probs, u, beta1, beta2, static_cast<bf16_t *>(dl), col_part);
   else hipLaunchKernelGGL(loss_grad_kernel<float>, dim3(P), dim3(256), 0, s, ws, targets, tstride, B, probs, u, beta1, beta2, static_cast<float *>(dl), col_part);
   hipError_t e = hipGetLastError();
@@ -1097,16 +1072,6 @@ hipError_t fade_reduce_batch(const ReduceBatch &rb, hipStream_t s) {
   hipLaunchKernelGGL(reduce_batch_kernel, dim3(nblk((size_t)maxN, 32), rb.count), dim3(256), 0, s, rb);
   return hipGetLastError();
 }
-// out[n] = sum_b src[b][n]; part must hold ceil(B / 32) * N floats
-hipError_t fade_colsum(int B, int N, const void *src, float *part, float *out, bool bf16, ReduceBatch &rb, hipStream_t s) {
-  const int P = (B + 31) / 32;
-  const dim3 grid(P, (N + 255) / 256);
-  if (bf16) hipLaunchKernelGGL(colsum_partial_kernel<bf16_t>, grid, dim3(256), 0, s, B, N, static_cast<const bf16_t *>(src), part);
-  else hipLaunchKernelGGL(colsum_partial_kernel<float>, grid, dim3(256), 0, s, B, N, static_cast<const float *>(src), part);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  return rb.push(P, N, part, out) ? hipSuccess : hipErrorInvalidValue;
-}
 hipError_t fade_bwd_cci(const BwdCciArgs &a, bool bf16, hipStream_t s) { DISPATCH_AT(bf16, bwd_cci_kernel, dim3(a.B), dim3(256), s, a); }
 // a.part must hold ceil(B / 4) * 2 * D * c floats; dWgv points at W_g's gradient (W_v's follows it in the blob)
 hipError_t fade_bwd_slot(const BwdSlotArgs &a, float *dWgv, bool bf16, ReduceBatch &rb, hipStream_t s) {
@@ -1155,11 +1120,5 @@ hipError_t fade_adam_refresh(const AdamRefreshBatch &ab, hipStream_t s) {
   for (int i = 0; i < ab.count; ++i)
     if (ab.m[i].K % 64 || ab.m[i].N % 64 || ab.m[i].off % 4 || ab.m[i].vstride % 64 || ab.m[i].vcol0 % 64) return hipErrorInvalidValue;
   hipLaunchKernelGGL(adam_refresh_kernel, dim3(ab.total_blocks), dim3(256), 0, s, ab);
-  return hipGetLastError();
-}
-hipError_t fade_adam(size_t n, const float *grad, float *master, float *m, float *v, const UpdateState *u, float lr, float beta1, float beta2,
-                     float eps, hipStream_t s) {
-  if (n == 0) return hipSuccess;
-  hipLaunchKernelGGL(adam_kernel, dim3(nblk(n, 256)), dim3(256), 0, s, n, grad, master, m, v, u, lr, beta1, beta2, eps);
   return hipGetLastError();
 }

@@ -100,8 +100,6 @@ struct PrepBatch {
 };
 hipError_t fade_prep_batch(const PrepBatch &pb, hipStream_t s);
 hipError_t fade_convt_build(const float *Wconv, int taps, int D, int Kc, float *V, hipStream_t s);
-hipError_t fade_fold_vectors(const float *W0, const float *W1, int K, int N, int interleave, const float *gamma, const float *beta,
-                             float *part, float *st_out, hipStream_t s);
 hipError_t fade_cci(const CciArgs &a, hipStream_t s);
 hipError_t fade_geglu(const GegluArgs &a, hipStream_t s);
 hipError_t fade_hout(const HoutArgs &a, bool bf16, hipStream_t s);
@@ -268,11 +266,8 @@ struct AdamRefreshBatch {
   AdamArrays opt;
 };
 hipError_t fade_adam_refresh(const AdamRefreshBatch &ab, hipStream_t s);
-hipError_t fade_colsum(int B, int N, const void *src, float *part, float *out, bool bf16, ReduceBatch &rb, hipStream_t s);
 hipError_t fade_bwd_cci(const BwdCciArgs &a, bool bf16, hipStream_t s);
 hipError_t fade_bwd_slot(const BwdSlotArgs &a, float *dWgv, bool bf16, ReduceBatch &rb, hipStream_t s);
 hipError_t fade_conv_grad(const ConvGradArgs &a, float *dWb, bool bf16, ReduceBatch &rb, hipStream_t s);
 hipError_t fade_bwd_embed(const BwdTokenArgs &a, int nblocks, float *sums, float *contrib, float *dE, float *dparams, bool bf16, ReduceBatch &rb,
                           hipStream_t s);
-hipError_t fade_adam(size_t n, const float *grad, float *master, float *m, float *v, const UpdateState *u, float lr, float beta1, float beta2,
-                     float eps, hipStream_t s);

@@ -178,43 +178,6 @@ __global__ __launch_bounds__(256) void bmm_kernel(const float *y, const AT *WU, 
 // so the product runs on the raw activations h and the normalisation becomes a per-row / per-column fix-up in
 // the kernel that reduces the split-K partials. s is summed from the bf16 values the matrix cores multiply.
 // ---------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void fold_vectors_kernel(const float *W0, const float *W1, int K, int N, int interleave,
-                                                           const float *gamma, const float *beta, float *part /*[gridDim.y][2][N]*/) {
-  // workgroup (x, y): 64 columns, K range y; four row phases per range, each in increasing k, combined in phase order
-  __shared__ float ps[4][64], pt[4][64];
-  const int v = blockIdx.x * 64 + (threadIdx.x & 63), kq = threadIdx.x >> 6;
-  const int kper = K / (int)gridDim.y, k0 = (int)blockIdx.y * kper;
-  const float *src = W0;
-  int col = v, ld = N;
-  if (interleave) {
-    ld = N / 2;
-    col = (v / 128) * 64 + (v & 63);
-    if ((v & 127) >= 64) src = W1;
-  }
-  float sa = 0.0f, ta = 0.0f;
-  for (int k = k0 + kq; k < k0 + kper; k += 4) {
-    const float w = (float)(bf16_t)src[(size_t)k * ld + col];
-    sa += (float)(bf16_t)(gamma[k] * w);
-    ta = fmaf(beta[k], w, ta);
-  }
-  ps[kq][threadIdx.x & 63] = sa;
-  pt[kq][threadIdx.x & 63] = ta;
-  __syncthreads();
-  if (kq == 0) {
-    const int c = threadIdx.x;
-    float *p = part + (size_t)blockIdx.y * 2 * N;
-    p[v] = (ps[0][c] + ps[1][c]) + (ps[2][c] + ps[3][c]);
-    p[N + v] = (pt[0][c] + pt[1][c]) + (pt[2][c] + pt[3][c]);
-  }
-}
-__global__ __launch_bounds__(256) void fold_reduce_kernel(int P, int N2, const float *part, float *out) {
-  const int n = blockIdx.x * 256 + threadIdx.x;
-  if (n >= N2) return;
-  float s = 0.0f;
-  for (int p = 0; p < P; ++p) s += part[(size_t)p * N2 + n];
-  out[n] = s;
-}
-
 __device__ __forceinline__ void moments_from_partials(const float *stats, int stats_n, int width, float &mean, float &rstd) {
   fade_row_moments(stats, stats_n, width, mean, rstd);
 }
@@ -738,16 +701,6 @@ hipError_t fade_bmm(const float *y, const void *WU, void *z, int B, bool bf16, h
   return hipGetLastError();
 }
 // st_out: [2][N] (s then t); part: scratch of 16 * 2 * N floats
-hipError_t fade_fold_vectors(const float *W0, const float *W1, int K, int N, int interleave, const float *gamma, const float *beta,
-                             float *part, float *st_out, hipStream_t s) {
-  if (N % 64 || K % 64) return hipErrorInvalidValue;
-  const int ksp = 16;
-  hipLaunchKernelGGL(fold_vectors_kernel, dim3(N / 64, ksp), dim3(256), 0, s, W0, W1, K, N, interleave, gamma, beta, part);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(fold_reduce_kernel, dim3(blocks_for((size_t)2 * N, 256)), dim3(256), 0, s, ksp, 2 * N, part, st_out);
-  return hipGetLastError();
-}
 hipError_t fade_cci(const CciArgs &a, hipStream_t s) {
   hipLaunchKernelGGL(cci_kernel, dim3((a.B + 3) / 4), dim3(256), 0, s, a);
   return hipGetLastError();
