@@ -7,6 +7,8 @@ and, in online mode, the weight update. The workload is benchmark configuration 
 source, B = 1024 streams, T = 64, D = 32, H = 256, bf16 operands): the timed region codes steps
 [T + W, T + W + K) of every stream with the input already resident in HBM, first compressing, then
 decompressing the same bytes (checked byte-exact). `--full` runs the whole job end to end instead.
+The headline (`value`) is the method as Algorithm 1 defines it, weights updated after every coded symbol; the default run also
+measures the same steps with frozen weights (inference only) and reports them under `frozen_weights`.
 
 Prints ONE JSON line (see the keys below); `roofline` describes the dominant kernel (the D_h x D_h router /
 gate product), timed with HIP events on the library's stream in a second pass over the same steps;
@@ -40,7 +42,7 @@ def parse():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 256 MiB device copy (torch) so that a counter run can be scaled against known traffic")
     ap.add_argument("--oracle-streams", type=int, default=64)
-    ap.add_argument("--oracle-steps", type=int, default=None, help="model steps of the oracle sample (default 24 frozen, 8 online)")
+    ap.add_argument("--oracle-steps", type=int, default=None, help="model steps of the oracle sample (default 24)")
     return ap.parse_args()
 
 
@@ -83,72 +85,90 @@ def main():
     n = src.size
     blob = fi.config_blob(a.config)
 
-    g = fa.Fade(fa.make_config(B, T, D, H, dtype=dtype, update_mode=fa.ONLINE_ADAM if mode == "online" else fa.FROZEN))
-    g.load_weights(blob.data)
-    src_dev = torch.from_numpy(src).cuda()
-    dst_dev = torch.zeros(n, dtype=torch.uint8, device="cuda")
-    torch.cuda.synchronize()
+    def measure(mode):
+        """compress + decompress of the timed steps in one update mode, then the event-profiled pass"""
+        g = fa.Fade(fa.make_config(B, T, D, H, dtype=dtype, update_mode=fa.ONLINE_ADAM if mode == "online" else fa.FROZEN))
+        g.load_weights(blob.data)
+        src_dev = torch.from_numpy(src).cuda()
+        dst_dev = torch.zeros(n, dtype=torch.uint8, device="cuda")
+        torch.cuda.synchronize()
 
-    def timed_encode():
-        if a.full:
+        def timed_encode():
+            if a.full:
+                torch.cuda.synchronize(); t0 = time.perf_counter()
+                g.encode_device(src_dev, n, 0, 0)
+                torch.cuda.synchronize(); return time.perf_counter() - t0
+            g.encode_device(src_dev, n, 0, first)          # uniform warm-up symbols + W untimed model steps
             torch.cuda.synchronize(); t0 = time.perf_counter()
-            g.encode_device(src_dev, n, 0, 0)
+            g.encode_device(src_dev, n, first, count)      # exactly K timed steps (and the termination of each stream)
             torch.cuda.synchronize(); return time.perf_counter() - t0
-        g.encode_device(src_dev, n, 0, first)          # uniform warm-up symbols + W untimed model steps
-        torch.cuda.synchronize(); t0 = time.perf_counter()
-        g.encode_device(src_dev, n, first, count)      # exactly K timed steps (and the termination of each stream)
-        torch.cuda.synchronize(); return time.perf_counter() - t0
 
-    def timed_decode(lens, data):
-        if a.full:
+        def timed_decode(lens, data):
+            if a.full:
+                torch.cuda.synchronize(); t0 = time.perf_counter()
+                g.decode_device(lens, data, dst_dev, n, 0, 0)
+                torch.cuda.synchronize(); return time.perf_counter() - t0
+            g.decode_device(lens, data, dst_dev, n, 0, first)
             torch.cuda.synchronize(); t0 = time.perf_counter()
-            g.decode_device(lens, data, dst_dev, n, 0, 0)
+            g.decode_device(None, None, dst_dev, n, first, count)
             torch.cuda.synchronize(); return time.perf_counter() - t0
-        g.decode_device(lens, data, dst_dev, n, 0, first)
-        torch.cuda.synchronize(); t0 = time.perf_counter()
-        g.decode_device(None, None, dst_dev, n, first, count)
-        torch.cuda.synchronize(); return time.perf_counter() - t0
 
-    t_enc = timed_encode()
-    lens, data = g.payloads()
-    t_dec = timed_decode(lens, data)
-    ok = bool(torch.equal(dst_dev, src_dev))
-    steps_timed = L if a.full else K
-    bytes_timed = n if a.full else B * K
-    container = 64 + 4 * B + int(data.size)
-    enc_MBps = bytes_timed / t_enc / 1e6
-    dec_MBps = bytes_timed / t_dec / 1e6
+        t_enc = timed_encode()
+        lens, data = g.payloads()
+        t_dec = timed_decode(lens, data)
+        ok = bool(torch.equal(dst_dev, src_dev))
+        steps_timed = L if a.full else K
+        bytes_timed = n if a.full else B * K
+        container = 64 + 4 * B + int(data.size)
+        enc_MBps = bytes_timed / t_enc / 1e6
+        dec_MBps = bytes_timed / t_dec / 1e6
 
-    # second pass over the same steps with a HIP event pair around every launch (on the library's stream)
-    prof = {}
-    if not a.full:
-        g.encode_device(src_dev, n, 0, first)
-        g.profile(True)
-        g.encode_device(src_dev, n, first, count)
-        prof = g.profile_read()
-        g.profile(False)
-    kern = {k: {"avg_us": 1e3 * ms / max(cnt, 1), "launches": int(cnt)} for k, (ms, cnt) in prof.items()}
+        # second pass over the same steps with a HIP event pair around every launch (on the library's stream)
+        prof = {}
+        if not a.full:
+            g.encode_device(src_dev, n, 0, first)
+            g.profile(True)
+            g.encode_device(src_dev, n, first, count)
+            prof = g.profile_read()
+            g.profile(False)
+        kern = {k: {"avg_us": 1e3 * ms / max(cnt, 1), "launches": int(cnt)} for k, (ms, cnt) in prof.items()}
+        fwd_flop = 2 * (2 * D * (H // T) + T * 3 * D * D + 2 * Dh * Dh + 2 * Dh * dl + dl * dl + 4 * H * Dh + 256 * Dh)
+        roofline = None
+        if "gemm_router" in kern and spec["dtype"] == "bf16":
+            # dominant kernel: alpha = sigma(X W_r) with the mix epilogue, and its twin the gate product (Eq. 5-6, 8)
+            us = 0.5 * (kern["gemm_router"]["avg_us"] + kern["gemm_gate"]["avg_us"])
+            flop = 2.0 * B * Dh * Dh
+            ach = flop / (us * 1e-6) / 1e12
+            # HBM bytes per launch: FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 from profiles/cfg2_frozen_pmc_counters.md and
+            # profiles/cfg2_online_kernel_trace_and_hbm.md (counter runs of this same program, scaled against a 256 MiB copy);
+            # only known for the configuration and modes profiled.
+            traffic = ROUTER_GATE_TRAFFIC_BYTES.get((a.config, mode))
+            roofline = {"bound": "mfma", "kernel": "gemm_pipe_kernel (router / gate product, M=B, N=K=D_h)", "achieved": round(ach, 2),
+                        "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s", "frac": round(ach * 1e12 / MFMA_BF16_PEAK, 4),
+                        "traffic": traffic, "avg_us": round(us, 2), "flop_per_launch": flop,
+                        "algorithmic_bytes_per_launch": 2 * ((6 if mode == "online" else 5) * B * Dh + Dh * Dh)}
+        step_us_events = sum(v["avg_us"] for k, v in kern.items() if k != "code_uniform")
+        return dict(t_enc=t_enc, t_dec=t_dec, ok=ok, steps_timed=steps_timed, bytes_timed=bytes_timed, container=container, enc_MBps=enc_MBps,
+                    dec_MBps=dec_MBps, kern=kern, roofline=roofline, step_us_events=step_us_events)
+
+    r = measure(mode)
+    t_enc, t_dec, ok, steps_timed, bytes_timed, container = r["t_enc"], r["t_dec"], r["ok"], r["steps_timed"], r["bytes_timed"], r["container"]
+    enc_MBps, dec_MBps, kern, roofline, step_us_events = r["enc_MBps"], r["dec_MBps"], r["kern"], r["roofline"], r["step_us_events"]
     fwd_flop = 2 * (2 * D * (H // T) + T * 3 * D * D + 2 * Dh * Dh + 2 * Dh * dl + dl * dl + 4 * H * Dh + 256 * Dh)
-    roofline = None
-    if "gemm_router" in kern and spec["dtype"] == "bf16":
-        # dominant kernel: alpha = sigma(X W_r) with the mix epilogue, and its twin the gate product (Eq. 5-6, 8)
-        us = 0.5 * (kern["gemm_router"]["avg_us"] + kern["gemm_gate"]["avg_us"])
-        flop = 2.0 * B * Dh * Dh
-        ach = flop / (us * 1e-6) / 1e12
-        # HBM bytes per launch: FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 from profiles/cfg2_frozen_pmc_counters.md and
-        # profiles/cfg2_online_kernel_trace_and_hbm.md (counter runs of this same program, scaled against a 256 MiB copy);
-        # only known for the configuration and modes profiled.
-        traffic = ROUTER_GATE_TRAFFIC_BYTES.get((a.config, mode))
-        roofline = {"bound": "mfma", "kernel": "gemm_pipe_kernel (router / gate product, M=B, N=K=D_h)", "achieved": round(ach, 2),
-                    "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s", "frac": round(ach * 1e12 / MFMA_BF16_PEAK, 4),
-                    "traffic": traffic, "avg_us": round(us, 2), "flop_per_launch": flop,
-                    "algorithmic_bytes_per_launch": 2 * ((6 if mode == "online" else 5) * B * Dh + Dh * Dh)}
-    step_us_events = sum(v["avg_us"] for k, v in kern.items() if k != "code_uniform")
+    other = None
+    if a.mode is None and not a.full:  # default run: the inference-only variant (frozen weights) of the same steps beside the headline
+        f = measure("frozen")
+        other = {"update_mode": "frozen", "compress_MBps": round(f["enc_MBps"], 3), "decompress_MBps": round(f["dec_MBps"], 3),
+                 "ms_per_step": round(1e3 * f["t_enc"] / f["steps_timed"], 5), "round_trip_exact": f["ok"],
+                 "bits_per_byte": round(8.0 * f["container"] / n, 4),
+                 "step_fraction_of_mfma_peak": round(fwd_flop * f["bytes_timed"] / f["t_enc"] / MFMA_BF16_PEAK, 4), "roofline": f["roofline"],
+                 "sum_kernels_us": round(f["step_us_events"], 2)}
+        ok = ok and f["ok"]
 
     cpu = None
     if not a.no_cpu_baseline:
         import oracle as orc
-        Bo, So = min(a.oracle_streams, B), (a.oracle_steps or (8 if mode == "online" else 24))
+        Bo, So = min(a.oracle_streams, B), (a.oracle_steps or 24)
         sub = fi.slice_blob(blob, spec, Bo) if Bo != B else blob
         o = orc.Oracle(orc.make_config(Bo, T, D, H, dtype=orc.BF16 if spec["dtype"] == "bf16" else orc.F32,
                                        update_mode=orc.ONLINE_ADAM if mode == "online" else orc.FROZEN))
@@ -176,7 +196,7 @@ def main():
         "round_trip_exact": ok, "bits_per_byte": round(8.0 * container / n, 4),
         "fwd_flop_per_byte": fwd_flop,
         "step_fraction_of_mfma_peak": round(fwd_flop * bytes_timed / t_enc / MFMA_BF16_PEAK, 4) if mode == "frozen" else None,
-        "roofline": roofline, "cpu_baseline": cpu,
+        "roofline": roofline, "cpu_baseline": cpu, "frozen_weights": other,
         "kernels_us": {k: round(v["avg_us"], 2) for k, v in kern.items()}, "sum_kernels_us": round(step_us_events, 2),
     }
     print(json.dumps(out))
