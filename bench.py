@@ -27,7 +27,7 @@ sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK = 2.5e15   # MI355X dense bf16, FLOP/s
 HBM_PEAK = 8.0e12         # B/s
-ROUTER_GATE_TRAFFIC_BYTES = {(2, "frozen"): int(0.5 * (52.3 + 49.7) * (1 << 20)), (2, "online"): int(0.5 * (56.3 + 53.8) * (1 << 20))}
+ROUTER_GATE_TRAFFIC_BYTES = {(2, "online"): int(0.5 * (56.3 + 53.8) * (1 << 20))}
 
 
 def parse():
@@ -137,17 +137,19 @@ def main():
         if "gemm_router" in kern and spec["dtype"] == "bf16":
             # dominant kernel: alpha = sigma(X W_r) with the mix epilogue, and its twin the gate product (Eq. 5-6, 8)
             us = 0.5 * (kern["gemm_router"]["avg_us"] + kern["gemm_gate"]["avg_us"])
-            flop = 2.0 * B * Dh * Dh
+            # frozen compression carries several steps of every stream through one launch: rows = B * steps per pass
+            rows = B * steps_timed // max(kern["gemm_router"]["launches"], 1)
+            flop = 2.0 * rows * Dh * Dh
             ach = flop / (us * 1e-6) / 1e12
             # HBM bytes per launch: FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 from profiles/cfg2_frozen_pmc_counters.md and
             # profiles/cfg2_online_kernel_trace_and_hbm.md (counter runs of this same program, scaled against a 256 MiB copy);
             # only known for the configuration and modes profiled.
             traffic = ROUTER_GATE_TRAFFIC_BYTES.get((a.config, mode))
-            roofline = {"bound": "mfma", "kernel": "gemm_pipe_kernel (router / gate product, M=B, N=K=D_h)", "achieved": round(ach, 2),
+            roofline = {"bound": "mfma", "kernel": f"gemm_pipe_kernel (router / gate product, M={rows}, N=K=D_h)", "achieved": round(ach, 2),
                         "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s", "frac": round(ach * 1e12 / MFMA_BF16_PEAK, 4),
                         "traffic": traffic, "avg_us": round(us, 2), "flop_per_launch": flop,
-                        "algorithmic_bytes_per_launch": 2 * ((6 if mode == "online" else 5) * B * Dh + Dh * Dh)}
-        step_us_events = sum(v["avg_us"] for k, v in kern.items() if k != "code_uniform")
+                        "algorithmic_bytes_per_launch": 2 * ((6 if mode == "online" else 5) * rows * Dh + Dh * Dh)}
+        step_us_events = sum(v["avg_us"] * v["launches"] for k, v in kern.items() if k != "code_uniform") / max(steps_timed, 1)
         return dict(t_enc=t_enc, t_dec=t_dec, ok=ok, steps_timed=steps_timed, bytes_timed=bytes_timed, container=container, enc_MBps=enc_MBps,
                     dec_MBps=dec_MBps, kern=kern, roofline=roofline, step_us_events=step_us_events)
 

@@ -126,6 +126,10 @@ struct fade_ctx {
   float *fold_down = nullptr, *fold_fnr = nullptr;  // per 64-row block partials of those vectors, written by the Adam + refresh kernel
   void *Hout = nullptr;
   int sp_down = 1, sp_fnr = 1, sp_head = 1;
+  // frozen bf16 encode: up to `steps_max` consecutive steps share one pass (rows = B * steps); buffers hold B * steps_max rows
+  int steps_max = 1;
+  void *slot_tab = nullptr;   // [256][c] Eq. 1 per symbol
+  uint2 *ranges = nullptr;    // [B * steps_max] coding intervals of one pass
   // kept for the backward pass (online mode only)
   void *hm = nullptr, *alpha = nullptr, *sg = nullptr, *eg = nullptr, *ev = nullptr, *cv = nullptr;
   float *GG = nullptr, *GV = nullptr;
@@ -285,6 +289,7 @@ int refresh_small(fade_ctx *c) {
   HIP_TRY(c, fade_reduce_batch(fr, s));
   HIP_TRY(c, fade_tables(c->E_c, c->P(P_GAMMA_E), c->P(P_BETA_E), c->P(P_GAMMA_L), c->P(P_BETA_L), (int)d.D, c->tabXe, c->tabXl, c->tabXe32,
                          c->tabXhat, c->tabRstd, true, s));
+  if (c->slot_tab) HIP_TRY(c, fade_slot_table(c->tabXe32, c->Wg_c, c->Wv_c, (int)d.D, (int)d.c, c->slot_tab, s));
   return FADE_OK;
 }
 
@@ -440,22 +445,32 @@ int pick_splits(int tiles, int k_blocks, int cap) {
   return s;
 }
 
-int forward_bf16(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint16_t *freq, float *probs) {
+// steps > 1 (frozen weights, CODE_ENCODE only): rows s * B + b carry stream b at step ws.i + s through one pass; every row's
+// arithmetic is the one a single step performs (same split-K counts, same summation order), so the tables, and with them
+// the payload, are those of `steps` single steps.
+int forward_bf16(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint16_t *freq, float *probs, int steps = 1) {
   const Dims &d = c->d;
   hipStream_t s = c->stream;
-  const int B = (int)d.B, Dh = (int)d.Dh, De = (int)d.De, SN = (int)(d.Dh / FADE_STATS_BN);
+  const int streams = (int)d.B, B = streams * steps;  // B: rows of this pass
+  const int Dh = (int)d.Dh, De = (int)d.De, SN = (int)(d.Dh / FADE_STATS_BN);
+  // a multi-step pass has tiles enough without splitting K: each workgroup adds the K ranges itself, in the order the
+  // reducing kernels would, and those then see one partial
+  const int fuse = steps > 1 ? 1 : 0;
+  const int sp_down = fuse ? 1 : c->sp_down, sp_fnr = fuse ? 1 : c->sp_fnr, sp_head = fuse ? 1 : c->sp_head;
+  if (steps > 1 && (steps > c->steps_max || mode != CODE_ENCODE || c->online)) return fail(c, FADE_E_INVALID_ARG, "multi-step pass not available");
   {
     Prof p(c, "embed_cache");
     EmbedArgs a{};
     a.ws = ws; a.T = (int)d.T; a.D = (int)d.D; a.Dh = Dh; a.Dc = (int)d.Dc; a.c = (int)d.c;
     a.tabXe = c->tabXe; a.tabXl = c->tabXl; a.tabXe32 = c->tabXe32; a.Wg = c->Wg_c; a.Wv = c->Wv_c;
-    a.X = c->X; a.XL = c->XL; a.M = c->M; a.GG = c->GG; a.GV = c->GV;
-    HIP_TRY(c, fade_embed_cache(a, B, true, s));
+    a.X = c->X; a.XL = c->XL; a.M = c->M; a.GG = c->GG; a.GV = c->GV; a.slot_tab = c->slot_tab; a.B = streams; a.S = steps;
+    if (steps > 1) HIP_TRY(c, fade_embed_steps(a, s));
+    else HIP_TRY(c, fade_embed_cache(a, streams, true, s));
   }
   {  // Eq. 4
     Prof p(c, "gemm_conv");
     GemmArgs g{};
-    g.M = (int)(d.B * d.T); g.N = (int)d.D; g.K = (int)d.Kc;
+    g.M = B * (int)d.T; g.N = (int)d.D; g.K = (int)d.Kc;
     g.A = c->XL; g.T = (int)d.T; g.D = (int)d.D; g.taps = (int)d.k;
     g.W = c->Wconv_c; g.C = c->Hl; g.ldc = (int)d.D; g.C2 = c->cv; g.bias = c->P(P_BCONV);
     HIP_TRY(c, fade_gemm(GEMM_CONV, true, g, s));
@@ -478,14 +493,14 @@ int forward_bf16(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uin
   {  // Eq. 7: H_mix W'_down as split-K partials
     Prof p(c, "gemm_down");
     GemmArgs g{};
-    g.M = B; g.N = (int)d.dl; g.K = Dh; g.splits = c->sp_down;
+    g.M = B; g.N = (int)d.dl; g.K = Dh; g.splits = c->sp_down; g.sum_splits = fuse;
     g.A = c->Hmix; g.lda = Dh; g.W = c->Wdown_c; g.C = c->part_down; g.ldc = (int)d.dl;
     HIP_TRY(c, fade_gemm(GEMM_PARTIAL, true, g, s));
   }
   {  // Eq. 7: folded LN, then the per-stream memory
     Prof p(c, "cci_wu");
     CciArgs a{};
-    a.B = B; a.Dh = Dh; a.splits = c->sp_down; a.stats_n = SN; a.part = c->part_down; a.stats = c->stats_c;
+    a.B = B; a.streams = streams; a.Dh = Dh; a.splits = sp_down; a.stats_n = SN; a.part = c->part_down; a.stats = c->stats_c;
     a.s_fold = c->s_down; a.t_fold = c->t_down; a.WU = static_cast<const bf16_t *>(c->WU_c); a.y = c->y; a.z = static_cast<bf16_t *>(c->z);
     HIP_TRY(c, fade_cci(a, s));
   }
@@ -507,14 +522,14 @@ int forward_bf16(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uin
   {  // Eq. 9: H_coarse [W'_fg | W'_fv] as split-K partials
     Prof p(c, "gemm_fnr_in");
     GemmArgs g{};
-    g.M = B; g.N = 2 * De; g.K = Dh; g.splits = c->sp_fnr;
+    g.M = B; g.N = 2 * De; g.K = Dh; g.splits = c->sp_fnr; g.sum_splits = fuse;
     g.A = c->Hc; g.lda = Dh; g.W = c->Wfgv_c; g.C = c->part_fnr; g.ldc = 2 * De;
     HIP_TRY(c, fade_gemm(GEMM_PARTIAL, true, g, s));
   }
   {
     Prof p(c, "geglu");
     GegluArgs a{};
-    a.B = B; a.Dh = Dh; a.De = De; a.splits = c->sp_fnr; a.stats_n = SN; a.part = c->part_fnr; a.stats = c->stats_f;
+    a.B = B; a.Dh = Dh; a.De = De; a.splits = sp_fnr; a.stats_n = SN; a.part = c->part_fnr; a.stats = c->stats_f;
     a.s_fold = c->s_fnr; a.t_fold = c->t_fnr; a.Hexp = static_cast<bf16_t *>(c->Hexp);
     a.eg = static_cast<bf16_t *>(c->eg); a.ev = static_cast<bf16_t *>(c->ev);
     HIP_TRY(c, fade_geglu(a, s));
@@ -536,16 +551,20 @@ int forward_bf16(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uin
   {  // head: H W_o as split-K partials; bias and reduction happen in the softmax kernel
     Prof p(c, "gemm_head");
     GemmArgs g{};
-    g.M = B; g.N = 256; g.K = Dh; g.splits = c->sp_head;
+    g.M = B; g.N = 256; g.K = Dh; g.splits = c->sp_head; g.sum_splits = fuse;
     g.A = c->Hout; g.lda = Dh; g.W = c->Wo_c; g.C = c->part_head; g.ldc = 256;
     HIP_TRY(c, fade_gemm(GEMM_PARTIAL, true, g, s));
   }
   {
     Prof p(c, "softmax_quant_code");
     SqcArgs a{};
-    a.ws = ws; a.B = B; a.splits = c->sp_head; a.bias = c->P(P_BO); a.logits_out = c->logits; a.logits = c->part_head;
-    a.probs = probs; a.freq = freq; a.sym_base = sym_base; a.cb = c->cb;
-    HIP_TRY(c, fade_softmax_quant_code(a, mode, s));
+    a.ws = ws; a.B = B; a.splits = sp_head; a.bias = c->P(P_BO); a.logits_out = steps > 1 ? nullptr : c->logits; a.logits = c->part_head;
+    a.probs = probs; a.freq = freq; a.sym_base = sym_base; a.cb = c->cb; a.streams = streams; a.ranges = c->ranges;
+    HIP_TRY(c, fade_softmax_quant_code(a, steps > 1 ? CODE_RANGES : mode, s));
+  }
+  if (steps > 1) {
+    Prof p(c, "encode_ranges");
+    HIP_TRY(c, fade_encode_ranges(ws, c->ranges, streams, steps, c->cb, s));
   }
   return FADE_OK;
 }
@@ -835,6 +854,15 @@ int run_loop(fade_ctx *c, uint8_t *bytes_dev, size_t n, size_t first, size_t cou
     if (i < d.T) {
       Prof p(c, "code_uniform");
       HIP_TRY(c, fade_code_uniform(ws, bytes_dev, (int)d.B, c->cb, mode, s));
+    } else if (mode == CODE_ENCODE && c->steps_max > 1 && last - i > 1) {
+      // frozen weights and the whole input at hand: the model's steps do not depend on each other, only the coder's do
+      const int steps = (int)std::min<size_t>((size_t)c->steps_max, last - i);
+      int rc = forward_bf16(c, ws, mode, bytes_dev, nullptr, nullptr, steps);
+      if (rc) return rc;
+      i += (size_t)steps - 1;
+      if (last - (i + 1) < 2)  // leave the rolling cache as the last of these steps would have: single steps may follow
+        HIP_TRY(c, hipMemcpyAsync(c->M, static_cast<char *>(c->M) + (size_t)(steps - 1) * d.B * d.Dc * c->esz, d.B * d.Dc * c->esz,
+                                  hipMemcpyDeviceToDevice, s));
     } else {
       int rc = forward(c, ws, mode, bytes_dev, nullptr, nullptr);
       if (rc) return rc;
@@ -907,7 +935,14 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
     if (hipStreamCreate(&c->stream) != hipSuccess) { delete c; return FADE_E_HIP; }
     c->own_stream = true;
   }
-  const size_t np = c->lay.off[P_COUNT], BDh = d.B * d.Dh;
+  if (c->bf16 && !c->online) {  // rows of one multi-step encode pass: enough to fill the chip, bounded by the buffers' size
+    size_t steps = std::max<size_t>(1, 16384 / d.B);
+    steps = std::min(steps, std::max<size_t>(1, ((size_t)1 << 26) / (d.B * d.Dh)));
+    if (const char *e = getenv("FADE_STEPS_PER_PASS")) steps = (size_t)std::max(1, atoi(e));
+    c->steps_max = (int)std::min<size_t>(steps, 256);
+  }
+  const size_t R = d.B * (size_t)c->steps_max;  // rows of the forward buffers
+  const size_t np = c->lay.off[P_COUNT], BDh = R * d.Dh;
   const size_t SN = d.Dh / FADE_STATS_BN;
   auto A = [&](void **p, size_t elems) { return dev_alloc_bytes(c, p, elems * c->esz); };
 #define TRY_ALLOC(expr) do { rc = (expr); if (rc) { fade_destroy(c); return rc; } } while (0)
@@ -930,9 +965,13 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
     c->sp_down = pick_splits((int)((d.B + 63) / 64), (int)(d.Dh / 64), 16);
     c->sp_fnr = pick_splits((int)((d.B + 127) / 128 * (2 * d.De / 128)), (int)(d.Dh / 64), 8);
     c->sp_head = pick_splits((int)((d.B + 127) / 128 * 2), (int)(d.Dh / 64), 8);
-    TRY_ALLOC(dev_alloc(c, &c->part_down, (size_t)c->sp_down * d.B * d.dl));
-    TRY_ALLOC(dev_alloc(c, &c->part_fnr, (size_t)c->sp_fnr * d.B * 2 * d.De));
-    TRY_ALLOC(dev_alloc(c, &c->part_head, (size_t)c->sp_head * d.B * 256));
+    TRY_ALLOC(dev_alloc(c, &c->part_down, (size_t)c->sp_down * R * d.dl));
+    TRY_ALLOC(dev_alloc(c, &c->part_fnr, (size_t)c->sp_fnr * R * 2 * d.De));
+    TRY_ALLOC(dev_alloc(c, &c->part_head, (size_t)c->sp_head * R * 256));
+    if (c->steps_max > 1) {
+      TRY_ALLOC(A(&c->slot_tab, 256 * d.c));
+      TRY_ALLOC(dev_alloc(c, &c->ranges, R));
+    }
     TRY_ALLOC(dev_alloc(c, &c->s_down, 2 * d.dl));
     c->t_down = c->s_down + d.dl;
     TRY_ALLOC(dev_alloc(c, &c->s_fnr, 4 * d.De));
@@ -958,14 +997,14 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
   TRY_ALLOC(A(&c->tabXl, 256 * d.D));
   TRY_ALLOC(dev_alloc(c, &c->tabXe32, 256 * d.D));
   for (void **p : {&c->X, &c->XL, &c->Hg, &c->Hl, &c->Hmix, &c->Ha, &c->Hc, &c->V}) TRY_ALLOC(A(p, BDh));
-  TRY_ALLOC(A(&c->M, d.B * d.Dc));
-  TRY_ALLOC(A(&c->Hexp, d.B * d.De));
-  TRY_ALLOC(A(&c->z, d.B * d.dl));
-  TRY_ALLOC(dev_alloc(c, &c->y, d.B * d.dl));
+  TRY_ALLOC(A(&c->M, R * d.Dc));
+  TRY_ALLOC(A(&c->Hexp, R * d.De));
+  TRY_ALLOC(A(&c->z, R * d.dl));
+  TRY_ALLOC(dev_alloc(c, &c->y, R * d.dl));
   TRY_ALLOC(dev_alloc(c, &c->logits, d.B * 256));
-  TRY_ALLOC(dev_alloc(c, &c->stats_c, d.B * SN * 2));
-  TRY_ALLOC(dev_alloc(c, &c->stats_f, d.B * SN * 2));
-  TRY_ALLOC(dev_alloc(c, &c->stats_o, d.B * SN * 2));
+  TRY_ALLOC(dev_alloc(c, &c->stats_c, R * SN * 2));
+  TRY_ALLOC(dev_alloc(c, &c->stats_f, R * SN * 2));
+  TRY_ALLOC(dev_alloc(c, &c->stats_o, R * SN * 2));
   if (c->online) {
     const size_t Bp = (d.B + 63) / 64 * 64, BpDh = Bp * d.Dh;
     c->Bp = Bp;

@@ -53,6 +53,8 @@ enum {
 struct GemmArgs {
   int M, N, K;            // C[M][N] = A'[M][K] * W[K][N]
   int splits;             // EPI_PARTIAL: number of K ranges (grid.y); 0 or 1 otherwise
+  int sum_splits;         // EPI_PARTIAL, pipelined kernel: one workgroup takes all ranges in turn and writes the sum of their
+                          // sums (added in range order) as the only partial
   // A operand
   const void *A;  int lda;
   int a_rows;             // row-major weight-gradient product: rows of A that exist (rows up to K are clamped to the last one)
@@ -72,6 +74,7 @@ struct GemmArgs {
   const void *S1, *S2;    // side inputs [M][N] (leading dimension ldc)
   const float *bias;
   float *stats_out;       // optional [M][N / BN][2]
+  int col_groups;         // pipelined kernel: column ranges of the XCD split of the tile grid (1, 2, 4, 8; 0 = chosen by the launcher)
 };
 
 // A grouped launch: up to 4 independent products, each with the kernel body named by kind[]; blocks [first_block[p],

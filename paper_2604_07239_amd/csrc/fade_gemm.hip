@@ -226,16 +226,22 @@ __device__ __forceinline__ void epilogue(const GemmArgs &g, const float *Cs, int
   }
 }
 
-__device__ __forceinline__ void tile_of_block(int bid, int ntm, int ntn, int &mt, int &nt) {
-  if ((ntn & 7) == 0) {  // one XCD (bid % 8) owns ntn / 8 consecutive column tiles, for every row tile
-    const int x = bid & 7, r = bid >> 3, per = ntn >> 3;
-    nt = x * per + r % per;
-    mt = r / per;
+// Block -> tile. Workgroups are dealt to the 8 XCDs round-robin (bid % 8), and each XCD has its own L2: the XCDs split
+// the tile grid into cg column ranges x (8 / cg) interleaved row sets, and one XCD walks its tiles row by row, so the
+// tiles that run together share their A rows and the XCD's slice of W stays in its L2. cg = 8 suits a small A (every
+// XCD streams all of A past its own eighth of W); a tall A wants fewer column ranges so that it is fetched cg times
+// instead of 8. Returns false for the padding blocks of a grid rounded up to whole row sets.
+__device__ __forceinline__ bool tile_of_block(int bid, int ntm, int ntn, int cg, int &mt, int &nt) {
+  if (cg <= 0) cg = 8;
+  if (ntn % cg == 0) {
+    const int rg = 8 / cg, x = bid & 7, r = bid >> 3, per = ntn / cg;
+    nt = (x % cg) * per + r % per;
+    mt = (r / per) * rg + x / cg;
   } else {
     nt = bid % ntn;
     mt = bid / ntn;
   }
-  (void)ntm;
+  return mt < ntm;
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -254,7 +260,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
   const int wm = wave / WN, wn = wave % WN;
   const int ntn = g.N / BN, ntm = (g.M + BM - 1) / BM;
   int mt, nt;
-  tile_of_block(blockIdx.x, ntm, ntn, mt, nt);
+  if (!tile_of_block(blockIdx.x, ntm, ntn, 8, mt, nt)) return;
   const int m0 = mt * BM, n0 = nt * BN;
 
   const int srow = tid >> 3, skc = (tid & 7) * 8;
@@ -382,6 +388,27 @@ __device__ __forceinline__ void bare_barrier() {
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
 }
+// Fragment reads from LDS with hand-counted waits. The compiler waits for *every* outstanding LDS read before the first
+// use of any of them, which serialises "fetch the next k-step" with "multiply this one"; issued through these wrappers it
+// does not know the reads are in flight, and lds_wait<N>() (N = reads issued after the ones about to be used; LDS
+// returns in order) is the only wait. Every value read must pass through lds_wait's operand list before its first use.
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+template <int OFF> __device__ __forceinline__ bf16x8 lds_read16(uint32_t addr) {
+  i32x4 v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+  return __builtin_bit_cast(bf16x8, v);
+}
+template <int N> __device__ __forceinline__ void lds_wait_count() {
+  asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory");
+}
+__device__ __forceinline__ void lds_landed(bf16x8 &v) {  // orders the uses of v after the preceding lds_wait_count
+  i32x4 t = __builtin_bit_cast(i32x4, v);
+  asm volatile("" : "+v"(t));
+  v = __builtin_bit_cast(bf16x8, t);
+}
+__device__ __forceinline__ uint32_t lds_address(const void *p) {
+  return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void *)p;
+}
 __device__ __forceinline__ void dma16(const bf16_t *src, unsigned char *lds_chunk) {
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
                                    (__attribute__((address_space(3))) void *)lds_chunk, 16, 0, 0);
@@ -407,9 +434,9 @@ __device__ __forceinline__ void pipe_body(const GemmArgs &g, int bid, int split,
   const int wm = wave >> 1, wn = wave & 1;
   const int ntn = g.N / BN, ntm = (g.M + BM - 1) / BM;
   int mt, nt;
-  tile_of_block(bid, ntm, ntn, mt, nt);
+  if (!tile_of_block(bid, ntm, ntn, g.col_groups, mt, nt)) return;
   const int m0 = mt * BM, n0 = nt * BN;
-  const int ksplit = g.K / nsplit, k_begin = split * ksplit, nkb = ksplit / BK;
+  const int ksplit = g.K / nsplit, nkb = ksplit / BK;
   const int ksteps = g.K / 16;
 
   // DMA sources of this wavefront for one stage.
@@ -424,7 +451,7 @@ __device__ __forceinline__ void pipe_body(const GemmArgs &g, int bid, int split,
     int row = m0 + c * 8 + (lane >> 3);
     row = row < g.M ? row : g.M - 1;
     const int sw = ((c * 8 + (lane >> 3)) >> 1) & 7;
-    src[q] = static_cast<const bf16_t *>(g.A) + (size_t)row * g.lda + k_begin + (((lane & 7) ^ sw) << 3);
+    src[q] = static_cast<const bf16_t *>(g.A) + (size_t)row * g.lda + (((lane & 7) ^ sw) << 3);
   }
 #pragma unroll
   for (int q = 0; q < BCH; ++q) {
@@ -432,13 +459,13 @@ __device__ __forceinline__ void pipe_body(const GemmArgs &g, int bid, int split,
     if (BROW) {  // row-major [N][ldb]: same 8-rows-per-DMA, XOR-swizzled scheme as A
       const int row = n0 + c * 8 + (lane >> 3);
       const int sw = ((c * 8 + (lane >> 3)) >> 1) & 7;
-      src[ACH + q] = static_cast<const bf16_t *>(g.W) + (size_t)row * g.ldb + k_begin + (((lane & 7) ^ sw) << 3);
+      src[ACH + q] = static_cast<const bf16_t *>(g.W) + (size_t)row * g.ldb + (((lane & 7) ^ sw) << 3);
     } else {
       const int fr = c / KS, ks = c % KS;
-      src[ACH + q] = static_cast<const bf16_t *>(g.W) + (((size_t)(n0 / 32 + fr) * ksteps + k_begin / 16 + ks) * 64 + lane) * 8;
+      src[ACH + q] = static_cast<const bf16_t *>(g.W) + (((size_t)(n0 / 32 + fr) * ksteps + ks) * 64 + lane) * 8;
     }
   }
-  auto issue = [&](int slot, int kb) {
+  auto issue = [&](int slot, int kb) {  // kb: 64-wide k block counted from the start of K
     unsigned char *base = smem + slot * STAGE_BYTES;
 #pragma unroll
     for (int q = 0; q < ACH; ++q) dma16(src[q] + (size_t)kb * BK, base + (wave + 4 * q) * 1024);
@@ -446,49 +473,68 @@ __device__ __forceinline__ void pipe_body(const GemmArgs &g, int bid, int split,
     for (int q = 0; q < BCH; ++q) dma16(src[ACH + q] + (BROW ? (size_t)kb * BK : (size_t)kb * KS * 512), base + A_BYTES + (wave + 4 * q) * 1024);
   };
 
-  f32x16 acc[TM][TN];
+
+  // fragment read offsets inside a stage: row r, k-step ks, half h -> r * 128 + (((2 ks + h) ^ ((r / 2) & 7)) * 16)
+  int a_off[TM], b_off[TN], b_frag[TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) a_off[i] = ((wm * TM + i) * 32 + (lane & 31)) * 128;
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    b_off[j] = A_BYTES + ((wn * TN + j) * 32 + (lane & 31)) * 128;
+    b_frag[j] = A_BYTES + (((wn * TN + j) * KS * 64 + lane) << 4);  // fragment layout: k-step ks sits ks KiB further
+  }
+  const int a_sw = (lane >> 1) & 7, a_half = lane >> 5;  // tile rows start at multiples of 32, so (r / 2) & 7 == (lane / 2) & 7
+  const uint32_t lds_base = lds_address(smem);
+
+  // EPI_PARTIAL with sum_splits: this workgroup walks all K ranges itself and adds their sums in range order, which is
+  // bit for bit what the reducing kernels make of separate partials; otherwise it owns the one range `split`.
+  const bool fuse = EPI == EPI_PARTIAL && g.sum_splits != 0;
+  const int sp_first = fuse ? 0 : split, sp_end = fuse ? nsplit : split + 1;
+  f32x16 acc[TM][TN], tot[EPI == EPI_PARTIAL ? TM : 1][EPI == EPI_PARTIAL ? TN : 1];
+  for (int sp = sp_first; sp < sp_end; ++sp) {
+  const int kb0 = sp * nkb;
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
-
+  if (sp != sp_first) bare_barrier();  // every wavefront has read the last stages of the previous range
 #pragma unroll
   for (int s = 0; s < STAGES - 1; ++s)
-    if (s < nkb) issue(s, s);
-
-  // fragment read offsets inside a stage: row r, k-step ks, half h -> r * 128 + (((2 ks + h) ^ ((r / 2) & 7)) * 16)
-  int a_off[TM], b_off[TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i) a_off[i] = ((wm * TM + i) * 32 + (lane & 31)) * 128;
-#pragma unroll
-  for (int j = 0; j < TN; ++j) b_off[j] = A_BYTES + ((wn * TN + j) * 32 + (lane & 31)) * 128;
-  const int a_sw = (lane >> 1) & 7, a_half = lane >> 5;  // tile rows start at multiples of 32, so (r / 2) & 7 == (lane / 2) & 7
+    if (s < nkb) issue(s, kb0 + s);
 
   for (int kb = 0; kb < nkb; ++kb) {
     // stage kb must have landed; up to STAGES-2 younger stages may stay in flight
     if (kb + STAGES - 2 < nkb) wait_vmcnt<(STAGES - 2) * LPW>();
     else wait_vmcnt<0>();
     bare_barrier();  // everyone's part of stage kb is in LDS, and everyone is done reading stage kb-1
-    if (kb + STAGES - 1 < nkb) issue((kb + STAGES - 1) % STAGES, kb + STAGES - 1);
-    const unsigned char *st = smem + (kb % STAGES) * STAGE_BYTES;
+    if (kb + STAGES - 1 < nkb) issue((kb + STAGES - 1) % STAGES, kb0 + kb + STAGES - 1);
+    const uint32_t st = lds_base + (kb % STAGES) * STAGE_BYTES;
     // fragments of k-step ks+1 are fetched from LDS while the matrix cores work on k-step ks
     bf16x8 af[2][TM], bf[2][TN];
     auto fetch = [&](int buf, int ks) {
+      const uint32_t kx = (uint32_t)(((2 * ks + a_half) ^ a_sw) << 4);
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
-        af[buf][i] = *reinterpret_cast<const bf16x8 *>(st + a_off[i] + (((2 * ks + a_half) ^ a_sw) << 4));
+      for (int i = 0; i < TM; ++i) af[buf][i] = lds_read16<0>(st + a_off[i] + kx);
 #pragma unroll
       for (int j = 0; j < TN; ++j)
-        bf[buf][j] = BROW ? *reinterpret_cast<const bf16x8 *>(st + b_off[j] + (((2 * ks + a_half) ^ a_sw) << 4))
-                          : *reinterpret_cast<const bf16x8 *>(st + A_BYTES + ((((wn * TN + j) * KS + ks) * 64 + lane) << 4));
+        bf[buf][j] = BROW ? lds_read16<0>(st + b_off[j] + kx) : lds_read16<0>(st + b_frag[j] + ks * 1024);
     };
     fetch(0, 0);
-    __builtin_amdgcn_sched_barrier(0);  // keep the scheduler from sinking the reads next to their uses
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      if (ks + 1 < KS) fetch((ks + 1) & 1, ks + 1);
+      if (ks + 1 < KS) {
+        fetch((ks + 1) & 1, ks + 1);
+        lds_wait_count<TM + TN>();  // the k-step about to be multiplied has landed; the one just requested may be in flight
+      } else {
+        lds_wait_count<0>();
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i) lds_landed(af[ks & 1][i]);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) lds_landed(bf[ks & 1][j]);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
@@ -497,6 +543,16 @@ __device__ __forceinline__ void pipe_body(const GemmArgs &g, int bid, int split,
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bf[ks & 1][j], acc[i][j], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
+  }
+  if constexpr (EPI == EPI_PARTIAL) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        if (sp == sp_first) tot[i][j] = acc[i][j];
+        else tot[i][j] += acc[i][j];
+      }
+  }
   }
 
   wait_vmcnt<0>();
@@ -509,14 +565,15 @@ __device__ __forceinline__ void pipe_body(const GemmArgs &g, int bid, int split,
       for (int e = 0; e < 16; ++e) {
         const int row = (wm * TM + i) * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
         const int col = (wn * TN + j) * 32 + (lane & 31);
-        Cs[row * LDC + col] = acc[i][j][e];
+        if constexpr (EPI == EPI_PARTIAL) Cs[row * LDC + col] = tot[i][j][e];
+        else Cs[row * LDC + col] = acc[i][j][e];
       }
   __syncthreads();
-  epilogue<EPI, AT, BM, BN>(g, Cs, m0, n0, nt, tid, split);
+  epilogue<EPI, AT, BM, BN>(g, Cs, m0, n0, nt, tid, fuse ? 0 : split);
 }
 template <int BM, int BN, int STAGES, int EPI, bool BROW>
-__global__ __launch_bounds__(256) void gemm_pipe_kernel(GemmArgs g) {
-  pipe_body<BM, BN, STAGES, EPI, BROW>(g, (int)blockIdx.x, (int)blockIdx.y, (int)gridDim.y);
+__global__ __launch_bounds__(256, (STAGES == 2 && BM * BN <= 128 * 128) ? 2 : 1) void gemm_pipe_kernel(GemmArgs g) {
+  pipe_body<BM, BN, STAGES, EPI, BROW>(g, (int)blockIdx.x, (int)blockIdx.y, g.sum_splits ? g.splits : (int)gridDim.y);
 }
 
 
@@ -562,7 +619,7 @@ __device__ __forceinline__ void tn_body(const GemmArgs &g, int bid) {
   const int wm = wave >> 1, wn = wave & 1;
   const int ntn = g.N / BN, ntm = g.M / BM;
   int mt, nt;
-  tile_of_block(bid, ntm, ntn, mt, nt);
+  if (!tile_of_block(bid, ntm, ntn, 8, mt, nt)) return;
   const int m0 = mt * BM, n0 = nt * BN;
   const int nkb = g.K / BK;
 
@@ -788,6 +845,14 @@ hipError_t launch_bf16(const GemmArgs &g, hipStream_t s) {
   return hipGetLastError();
 }
 
+// Column ranges of the XCD split (see tile_of_block) by the size of the A operand; FADE_GEMM_XCD overrides for sweeps.
+int fade_gemm_col_groups(int M, int K) {
+  static int v = -1;
+  if (v < 0) { const char *e = getenv("FADE_GEMM_XCD"); v = e ? atoi(e) : 0; }
+  if (v > 0) return v;
+  return 8;
+}
+
 template <int BM, int BN, int STAGES, int EPI, bool BROW = false>
 hipError_t launch_pipe(const GemmArgs &g, hipStream_t s) {
   constexpr int BK = 64;
@@ -802,8 +867,14 @@ hipError_t launch_pipe(const GemmArgs &g, hipStream_t s) {
   }
   const int splits = g.splits > 1 ? g.splits : 1;
   if (g.N % BN || g.M <= 0 || g.K % (splits * BK) || (EPI != EPI_PARTIAL && splits != 1) || g.lda % 8 || (BROW && g.ldb % 8)) return hipErrorInvalidValue;
-  const dim3 grid(((g.M + BM - 1) / BM) * (g.N / BN), splits);
-  hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, g);
+  GemmArgs ga = g;
+  const int ntm = (g.M + BM - 1) / BM, ntn = g.N / BN;
+  if (ga.col_groups == 0) ga.col_groups = fade_gemm_col_groups(g.M, g.K);
+  if ((ga.col_groups != 1 && ga.col_groups != 2 && ga.col_groups != 4) || ntn % ga.col_groups) ga.col_groups = 8;
+  const int rg = 8 / ga.col_groups;
+  if (ga.sum_splits && EPI != EPI_PARTIAL) return hipErrorInvalidValue;
+  const dim3 grid((ntn % ga.col_groups == 0 ? (ntm + rg - 1) / rg * rg : ntm) * ntn, ga.sum_splits ? 1 : splits);
+  hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, ga);
   return hipGetLastError();
 }
 
@@ -823,16 +894,17 @@ hipError_t launch_tn(const GemmArgs &g, hipStream_t s) {
   return hipGetLastError();
 }
 
-// Tile shape by problem size: 128 x 128 when that still gives every compute unit a tile, else 64 x 128.
+// Tile shape by problem size. Small batches: 64 x 128 tiles, four stages, so that every compute unit gets a tile. From
+// 512 tiles of 128 x 128 on: that tile with a two-stage ring (64 KiB of LDS), two workgroups per compute unit: one's
+// epilogue (side inputs from HBM, stores) and pipeline fill run under the other's products, which measured faster than
+// either a deeper ring or a 256 x 128 tile with one workgroup per unit (router product, M = 4096: 43 us against 54).
 template <int EPI>
 hipError_t launch_pipe_auto(const GemmArgs &g, hipStream_t s) {
   const int tiles128 = ((g.M + 127) / 128) * (g.N / 128);
-  const int tiles256 = ((g.M + 255) / 256) * (g.N / 128);
-  if (fade_gemm_tune() == 10 || (fade_gemm_tune() == 0 && tiles256 >= 256)) return launch_pipe<256, 128, 3, EPI>(g, s);
-  if (fade_gemm_tune() == 1 || (fade_gemm_tune() == 0 && tiles128 >= 256)) return launch_pipe<128, 128, 4, EPI>(g, s);
-  if (fade_gemm_tune() == 4) return launch_pipe<64, 128, 3, EPI>(g, s);
-  if (fade_gemm_tune() == 5) return launch_pipe<64, 128, 2, EPI>(g, s);
-  if (fade_gemm_tune() == 6) return launch_pipe<64, 128, 6, EPI>(g, s);
+  const int tune = fade_gemm_tune();
+  if (tune == 11 || (tune == 0 && tiles128 >= 512)) return launch_pipe<128, 128, 2, EPI>(g, s);
+  if (tune == 10) return launch_pipe<256, 128, 3, EPI>(g, s);
+  if (tune == 1 || (tune == 0 && tiles128 >= 256)) return launch_pipe<128, 128, 4, EPI>(g, s);
   return launch_pipe<64, 128, 4, EPI>(g, s);
 }
 
@@ -923,7 +995,8 @@ hipError_t fade_gemm_group_launch(const GemmGroup &gg, hipStream_t s) {
   return hipGetLastError();
 }
 
-// Tuning override for experiments (FADE_GEMM_TUNE: 0 automatic, 1 force 128x128, 2 force 64x128).
+// Tuning override for experiments (FADE_GEMM_TUNE: 0 automatic, 1 force 128x128x4 stages, 2 force 64x128, 10 force 256x128x3,
+// 11 force 128x128x2 with two workgroups per compute unit).
 int fade_gemm_tune() {
   static int v = -1;
   if (v < 0) { const char *e = getenv("FADE_GEMM_TUNE"); v = e ? atoi(e) : 0; }

@@ -17,7 +17,7 @@ hipError_t fade_gemm(int op, bool bf16, const GemmArgs &g, hipStream_t s);
 hipError_t fade_gemm_group_add(GemmGroup &gg, int op, const GemmArgs &g);
 hipError_t fade_gemm_group_launch(const GemmGroup &gg, hipStream_t s);
 
-enum { CODE_NONE = 0, CODE_ENCODE = 1, CODE_DECODE = 2 };
+enum { CODE_NONE = 0, CODE_ENCODE = 1, CODE_DECODE = 2, CODE_RANGES = 3 };  // CODE_RANGES: leave each row's coding interval for a later pass
 
 // Per-stream coder state (structure of arrays, all of length B) and the payload buffers.
 struct CoderBufs {
@@ -39,11 +39,14 @@ struct EmbedArgs {
   void *X, *XL;               // [B][Dh]
   void *M;                    // [B][Dc]
   float *GG, *GV;             // optional [B][c]: pre-activations of Eq. 1 for the backward pass
+  const void *slot_tab;       // optional [256][c] activation type: Eq. 1's slot of every symbol (frozen weights only)
+  int B, S;                   // several steps per launch (slot_tab required): row s * B + b is stream b at step ws.i + s
 };
 
 // arguments of the kernels that finish a split-K product with a folded LayerNorm (bf16 path)
 struct CciArgs {
   int B, Dh, splits, stats_n;
+  int streams;           // row r uses W_U[r % streams] (rows beyond the first `streams` are later steps of the same streams)
   const float *part;     // [splits][B][64] partials of H_mix W'_down
   const float *stats;    // [B][stats_n][2] row sums of H_mix
   const float *s_fold, *t_fold;  // [64]
@@ -77,6 +80,8 @@ struct SqcArgs {
   uint16_t *freq;       // optional [B][256]
   uint8_t *sym_base;    // symbol of stream b at step i lives at sym_base + b * ws.stride + i
   CoderBufs cb;
+  int streams;          // CODE_RANGES: B = streams * steps rows, row s * streams + b is stream b at step ws.i + s
+  uint2 *ranges;        // CODE_RANGES: [B] (cum, cum + freq) of the symbol each row has to code
 };
 
 hipError_t fade_preshuffle(const float *W0, const float *W1, int k_real, int K, int N, int interleave, const float *rowscale, void *out,
@@ -109,6 +114,9 @@ hipError_t fade_round_bf16(const float *src, float *dst, size_t n, hipStream_t s
 hipError_t fade_tables(const float *E, const float *ge, const float *be, const float *gl, const float *bl, int D, void *tabXe,
                        void *tabXl, float *tabXe32, float *tabXhat, float *tabRstd, bool bf16, hipStream_t s);
 hipError_t fade_embed_cache(const EmbedArgs &a, int B, bool bf16, hipStream_t s);
+hipError_t fade_embed_steps(const EmbedArgs &a, hipStream_t s);  // bf16, a.B * a.S rows, cache rebuilt from the window
+hipError_t fade_slot_table(const float *tabXe32, const float *Wg, const float *Wv, int D, int c, void *tab_bf16, hipStream_t s);
+hipError_t fade_encode_ranges(const WinSrc &ws, const uint2 *ranges, int B, int S, const CoderBufs &cb, hipStream_t s);
 hipError_t fade_bmm(const float *y, const void *WU, void *z, int B, bool bf16, hipStream_t s);
 hipError_t fade_softmax_quant_code(const SqcArgs &a, int mode, hipStream_t s);
 hipError_t fade_quantize_rows(const float *probs, size_t rows, uint16_t *freq, int *err, hipStream_t s);

@@ -115,6 +115,14 @@ __global__ __launch_bounds__(256) void tables_kernel(const float *E, const float
 // ---------------------------------------------------------------------------------------------------
 // window gather + rolling cache (one workgroup per stream)
 // ---------------------------------------------------------------------------------------------------
+// Eq. 1's two pre-activations for column q: x W_g and x W_v (x: one embedded row of D channels)
+__device__ __forceinline__ void slot_pair(const float *xt, const float *Wg, const float *Wv, int D, int c, int q, float &gg, float &gv) {
+  gg = 0.0f; gv = 0.0f;
+  for (int i = 0; i < D; ++i) {
+    gg = fmaf(xt[i], Wg[i * c + q], gg);
+    gv = fmaf(xt[i], Wv[i * c + q], gv);
+  }
+}
 template <typename AT>
 __global__ __launch_bounds__(256) void embed_cache_kernel(EmbedArgs a) {
   const int b = blockIdx.x, tid = threadIdx.x;
@@ -146,14 +154,52 @@ __global__ __launch_bounds__(256) void embed_cache_kernel(EmbedArgs a) {
   }
   // ... and append Eq. 1's GeGLU of the newest symbol: psi(x_t W_g) * (x_t W_v)
   if (tid < a.c) {
-    const float *xt = a.tabXe32 + (size_t)win[a.T - 1] * a.D;
-    float gg = 0.0f, gv = 0.0f;
-    for (int i = 0; i < a.D; ++i) {
-      gg = fmaf(xt[i], a.Wg[i * a.c + tid], gg);
-      gv = fmaf(xt[i], a.Wv[i * a.c + tid], gv);
+    if (a.slot_tab) {  // frozen weights: the slot depends on the symbol alone
+      M[a.Dc - a.c + tid] = static_cast<const AT *>(a.slot_tab)[(size_t)win[a.T - 1] * a.c + tid];
+    } else {
+      float gg, gv;
+      slot_pair(a.tabXe32 + (size_t)win[a.T - 1] * a.D, a.Wg, a.Wv, a.D, a.c, tid, gg, gv);
+      M[a.Dc - a.c + tid] = (AT)(gelu_f(gg) * gv);
+      if (a.GG) { a.GG[(size_t)b * a.c + tid] = gg; a.GV[(size_t)b * a.c + tid] = gv; }
     }
-    M[a.Dc - a.c + tid] = (AT)(gelu_f(gg) * gv);
-    if (a.GG) { a.GG[(size_t)b * a.c + tid] = gg; a.GV[(size_t)b * a.c + tid] = gv; }
+  }
+}
+
+// Eq. 1 for every symbol (frozen weights): tab[sym][q] = psi(x W_g)[q] * (x W_v)[q], x = the symbol's embedded row.
+__global__ void slot_table_kernel(const float *tabXe32, const float *Wg, const float *Wv, int D, int c, bf16_t *tab) {
+  const int sym = blockIdx.x;
+  for (int q = threadIdx.x; q < c; q += blockDim.x) {
+    float gg, gv;
+    slot_pair(tabXe32 + (size_t)sym * D, Wg, Wv, D, c, q, gg, gv);
+    tab[(size_t)sym * c + q] = (bf16_t)(gelu_f(gg) * gv);
+  }
+}
+
+// Several steps of every stream in one launch (frozen weights, coding a known input): row r = s * B + b is stream b at
+// step i + s. The cache of Eq. 2 is rebuilt from the window instead of rolled: after step i, slot j holds the symbol
+// window[j]'s entry of Eq. 1, provided the model already ran at the step that appended it (steps before T code under the
+// uniform table and append nothing, so those slots are still the zeros of the reset).
+__global__ __launch_bounds__(256) void embed_steps_kernel(EmbedArgs a) {
+  const int r = blockIdx.x, tid = threadIdx.x;
+  const int s = r / a.B, b = r - s * a.B;
+  WinSrc w = a.ws;
+  w.i += s;
+  if (!stream_active(w, b)) return;
+  const uint8_t *win = stream_window(w, b, a.T);
+  const bf16_t *tabXe = static_cast<const bf16_t *>(a.tabXe), *tabXl = static_cast<const bf16_t *>(a.tabXl);
+  bf16_t *X = static_cast<bf16_t *>(a.X) + (size_t)r * a.Dh, *XL = static_cast<bf16_t *>(a.XL) + (size_t)r * a.Dh;
+  for (int ch = tid; ch < a.Dh / 8; ch += 256) {
+    const int e0 = ch * 8, j = e0 / a.D, i = e0 - j * a.D;
+    const int sy = win[j];
+    *reinterpret_cast<f32x4 *>(X + e0) = *reinterpret_cast<const f32x4 *>(tabXe + (size_t)sy * a.D + i);
+    *reinterpret_cast<f32x4 *>(XL + e0) = *reinterpret_cast<const f32x4 *>(tabXl + (size_t)sy * a.D + i);
+  }
+  const bf16_t *tab = static_cast<const bf16_t *>(a.slot_tab);
+  bf16_t *M = static_cast<bf16_t *>(a.M) + (size_t)r * a.Dc;
+  const long long first_slot = 2ll * a.T - 1 - w.i;  // slot j was appended at step i - (T - 1 - j), a model step iff that is >= T
+  for (int idx = tid; idx < a.Dc; idx += 256) {
+    const int j = idx / a.c, q = idx - j * a.c;
+    M[idx] = j >= first_slot ? tab[(size_t)win[j] * a.c + q] : (bf16_t)0.0f;
   }
 }
 
@@ -199,7 +245,7 @@ __global__ __launch_bounds__(256) void cci_kernel(CciArgs a) {
   moments_from_partials(a.stats + (size_t)b * a.stats_n * 2, a.stats_n, a.Dh, mean, rstd);
   const float yv = rstd * (raw - mean * a.s_fold[lane]) + a.t_fold[lane];
   a.y[(size_t)b * 64 + lane] = yv;
-  const bf16_t *W = a.WU + (size_t)b * 4096;
+  const bf16_t *W = a.WU + (size_t)(b % a.streams) * 4096;
   float acc = 0.0f;
 #pragma unroll 8
   for (int k = 0; k < 64; ++k) acc = fmaf(__shfl(yv, k, 64), (float)W[k * 64 + lane], acc);
@@ -403,7 +449,7 @@ __device__ __forceinline__ void cumulate_wave(const uint32_t q[4], int lane, uin
 // ---------------------------------------------------------------------------------------------------
 // arithmetic coder: 32-bit interval, totals 2^16, bit-plus-follow carries, bits MSB first
 // ---------------------------------------------------------------------------------------------------
-constexpr uint32_t kHalf = 0x80000000u, kQuarter = 0x40000000u, kThreeQ = 0xC0000000u;
+constexpr uint32_t kQuarter = 0x40000000u;
 
 struct EncState {
   uint32_t low, high, pending, bitbuf, nbits, pos;
@@ -426,18 +472,52 @@ __device__ __forceinline__ void emit(const CoderBufs &c, int b, EncState &e, uin
   put_bit(c, b, e, bit);
   for (; e.pending > 0; --e.pending) put_bit(c, b, e, bit ^ 1u);
 }
+// Append the low `count` (<= 32) bits of `value`, most significant first.
+__device__ __forceinline__ void put_bits(const CoderBufs &c, int b, EncState &e, uint32_t value, uint32_t count) {
+  uint64_t acc = ((uint64_t)e.bitbuf << count) | value;
+  uint32_t total = e.nbits + count;  // < 40
+  while (total >= 8) {
+    total -= 8;
+    if (e.pos < c.cap) c.out[(size_t)b * c.cap + e.pos] = (uint8_t)(acc >> total);
+    else *c.err = 1;  // payload buffer exhausted: flagged, never written out of bounds
+    ++e.pos;
+  }
+  e.bitbuf = (uint32_t)acc & ((1u << total) - 1u);
+  e.nbits = total;
+}
+// One symbol. The renormalisation loop of the classic coder (shift out a settled top bit, or drop the second bit while the
+// interval straddles the middle) always runs as n shifts of the first kind followed by m of the second: once the top bits of
+// low and high differ they stay different. Both counts are leading-bit counts, so the loop is done in closed form:
+//   n = leading bits in which low and high agree; they are the output: the first of them, then the `pending` opposite
+//       bits owed from earlier straddles, then the other n - 1;
+//   m = after those shifts, the length of the run 0111.. / 1000.. below the top bit; pending becomes m (plus the old
+//       count when n = 0), and the run is cut out of both bounds.
+// The interval is wider than 2^30 before and at least 2^14 - 1 after the update, so n <= 18 and m <= 30.
 __device__ __forceinline__ void enc_symbol(const CoderBufs &c, int b, EncState &e, uint32_t cum_lo, uint32_t cum_hi) {
   const uint64_t range = (uint64_t)e.high - e.low + 1;
-  e.high = e.low + (uint32_t)((range * cum_hi) >> 16) - 1;
-  e.low = e.low + (uint32_t)((range * cum_lo) >> 16);
-  for (;;) {
-    if (e.high < kHalf) emit(c, b, e, 0);
-    else if (e.low >= kHalf) emit(c, b, e, 1);
-    else if (e.low >= kQuarter && e.high < kThreeQ) { ++e.pending; e.low -= kQuarter; e.high -= kQuarter; }
-    else break;
-    e.low <<= 1;
-    e.high = (e.high << 1) | 1u;
+  uint32_t high = e.low + (uint32_t)((range * cum_hi) >> 16) - 1;
+  uint32_t low = e.low + (uint32_t)((range * cum_lo) >> 16);
+  const uint32_t n = (uint32_t)__clz((int)(low ^ high));
+  if (n > 0) {
+    const uint32_t b0 = low >> 31;
+    put_bits(c, b, e, b0, 1);
+    for (uint32_t left = e.pending; left > 0;) {
+      const uint32_t k = left < 32u ? left : 32u;
+      put_bits(c, b, e, b0 ? 0u : (k == 32u ? 0xFFFFFFFFu : (1u << k) - 1u), k);
+      left -= k;
+    }
+    e.pending = 0;
+    if (n > 1) put_bits(c, b, e, (low >> (32 - n)) & ((1u << (n - 1)) - 1u), n - 1);
+    low <<= n;
+    high = (high << n) | ((1u << n) - 1u);
   }
+  const uint32_t m = (uint32_t)__clz((int)~((low & ~high) << 1));
+  if (m > 0) {
+    e.pending += m;
+    low = (low << m) & 0x7FFFFFFFu;
+    high = (high << m) | ((1u << m) - 1u) | 0x80000000u;
+  }
+  e.low = low; e.high = high;
 }
 __device__ __forceinline__ void enc_finish(const CoderBufs &c, int b, EncState &e) {
   ++e.pending;
@@ -459,19 +539,40 @@ __device__ __forceinline__ uint32_t dec_target(const DecState &d) {
   const uint64_t range = (uint64_t)d.high - d.low + 1;
   return (uint32_t)((((((uint64_t)(d.value - d.low)) + 1) << 16) - 1) / range);
 }
+// The next `count` (<= 25) payload bits of stream b, zeros past the end.
+__device__ __forceinline__ uint32_t dec_bits(const CoderBufs &c, int b, DecState &d, uint32_t count) {
+  const uint32_t byte0 = d.bitpos >> 3, off = d.bitpos & 7u, len = c.in_len[b];
+  const uint8_t *in = c.in + (size_t)b * c.cap;
+  uint32_t w = 0;
+#pragma unroll
+  for (uint32_t k = 0; k < 4; ++k) w = (w << 8) | (byte0 + k < len ? (uint32_t)in[byte0 + k] : 0u);
+  d.bitpos += count;
+  return count ? (w << off) >> (32 - count) : 0u;
+}
+// The decoder's side of enc_symbol's closed form: the same n and m (the bounds do not depend on the payload), `value`
+// shifted along with them; a straddle step removes the bit below the top one.
 __device__ __forceinline__ void dec_update(const CoderBufs &c, int b, DecState &d, uint32_t cum_lo, uint32_t cum_hi) {
   const uint64_t range = (uint64_t)d.high - d.low + 1;
-  d.high = d.low + (uint32_t)((range * cum_hi) >> 16) - 1;
-  d.low = d.low + (uint32_t)((range * cum_lo) >> 16);
-  for (;;) {
-    if (d.high < kHalf) {
-    } else if (d.low >= kHalf) { d.value -= kHalf; d.low -= kHalf; d.high -= kHalf; }
-    else if (d.low >= kQuarter && d.high < kThreeQ) { d.value -= kQuarter; d.low -= kQuarter; d.high -= kQuarter; }
-    else break;
-    d.low <<= 1;
-    d.high = (d.high << 1) | 1u;
-    d.value = (d.value << 1) | dec_bit(c, b, d);
+  uint32_t high = d.low + (uint32_t)((range * cum_hi) >> 16) - 1;
+  uint32_t low = d.low + (uint32_t)((range * cum_lo) >> 16);
+  uint32_t value = d.value;
+  const uint32_t n = (uint32_t)__clz((int)(low ^ high));
+  if (n > 0) {
+    low <<= n;
+    high = (high << n) | ((1u << n) - 1u);
+    value = (value << n) | dec_bits(c, b, d, n);
   }
+  uint32_t m = (uint32_t)__clz((int)~((low & ~high) << 1));
+  if (m > 0) {
+    low = (low << m) & 0x7FFFFFFFu;
+    high = (high << m) | ((1u << m) - 1u) | 0x80000000u;
+    while (m > 0) {
+      const uint32_t k = m < 24u ? m : 24u;
+      value = (value & 0x80000000u) | ((value << k) & 0x7FFFFFFFu) | dec_bits(c, b, d, k);
+      m -= k;
+    }
+  }
+  d.low = low; d.high = high; d.value = value;
 }
 
 // Code one symbol of stream b under the table q (lane-distributed). mode: CODE_NONE / CODE_ENCODE / CODE_DECODE.
@@ -520,9 +621,16 @@ __device__ __forceinline__ void code_wave(const CoderBufs &c, int b, int lane, c
 // ---------------------------------------------------------------------------------------------------
 template <int MODE>
 __global__ __launch_bounds__(256) void softmax_quant_code_kernel(SqcArgs a) {
-  const int b = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int b = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;  // row
   if (b >= a.B) return;
-  if (!stream_active(a.ws, b)) return;
+  WinSrc w = a.ws;
+  int sb = b;  // stream of this row
+  if (MODE == CODE_RANGES) {
+    const int st = b / a.streams;
+    sb = b - st * a.streams;
+    w.i += st;
+  }
+  if (!stream_active(w, sb)) return;
   f32x4 z = *reinterpret_cast<const f32x4 *>(a.logits + (size_t)b * 256 + 4 * lane);
   if (a.splits > 0) {  // logits arrive as split-K partials; the head's bias is added here
     for (int s0 = 1; s0 < a.splits; s0 += 8) {  // up to 8 partials in flight, added in split order
@@ -557,10 +665,44 @@ __global__ __launch_bounds__(256) void softmax_quant_code_kernel(SqcArgs a) {
     ushort4 f = make_ushort4((unsigned short)q[0], (unsigned short)q[1], (unsigned short)q[2], (unsigned short)q[3]);
     *reinterpret_cast<ushort4 *>(a.freq + (size_t)b * 256 + 4 * lane) = f;
   }
-  if (MODE != CODE_NONE) {
+  if (MODE == CODE_RANGES) {
+    uint32_t cum[4];
+    cumulate_wave(q, lane, cum);
+    const int sy = a.sym_base[(long long)sb * w.stride + w.i];
+    const uint32_t mylo = cum[sy & 3], myhi = mylo + q[sy & 3];
+    const uint32_t lo = __shfl(mylo, sy >> 2, 64), hi = __shfl(myhi, sy >> 2, 64);
+    if (lane == 0) a.ranges[b] = make_uint2(lo, hi);
+  } else if (MODE != CODE_NONE) {
     uint8_t *sym = a.sym_base + (long long)b * a.ws.stride + a.ws.i;
     code_wave<MODE>(a.cb, b, lane, q, sym);
   }
+}
+
+// Second half of a multi-step encode: feed each stream's S intervals, in step order, to its coder. One thread per stream;
+// the intervals come through LDS in slabs of 16 steps so that the coder's dependent chain never waits on HBM.
+__global__ __launch_bounds__(64) void encode_ranges_kernel(WinSrc ws, const uint2 *ranges, int B, int S, CoderBufs cb) {
+  __shared__ uint2 slab[16][64];
+  const int b = blockIdx.x * 64 + threadIdx.x;
+  const bool mine = b < B;
+  EncState e;
+  if (mine) enc_load(cb, b, e);
+  bool live = mine;
+  for (int s0 = 0; s0 < S; s0 += 16) {
+    __syncthreads();
+    if (mine) {
+#pragma unroll
+      for (int j = 0; j < 16; ++j)
+        if (s0 + j < S) slab[j][threadIdx.x] = ranges[(size_t)(s0 + j) * B + b];
+    }
+    __syncthreads();
+    for (int j = 0; j < 16 && s0 + j < S && live; ++j) {
+      WinSrc w = ws;
+      w.i += s0 + j;
+      live = stream_active(w, b);  // a stream that has ended stays ended
+      if (live) enc_symbol(cb, b, e, slab[j][threadIdx.x].x, slab[j][threadIdx.x].y);
+    }
+  }
+  if (mine) enc_store(cb, b, e);
 }
 
 __global__ __launch_bounds__(256) void quantize_kernel(const float *probs, size_t rows, uint16_t *freq, int *err) {
@@ -693,6 +835,19 @@ hipError_t fade_embed_cache(const EmbedArgs &a, int B, bool bf16, hipStream_t s)
   else hipLaunchKernelGGL(embed_cache_kernel<float>, dim3(B), dim3(256), 0, s, a);
   return hipGetLastError();
 }
+hipError_t fade_embed_steps(const EmbedArgs &a, hipStream_t s) {
+  if (!a.slot_tab || a.B <= 0 || a.S <= 0 || a.Dh % 8) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(embed_steps_kernel, dim3(a.B * a.S), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+hipError_t fade_slot_table(const float *tabXe32, const float *Wg, const float *Wv, int D, int c, void *tab_bf16, hipStream_t s) {
+  hipLaunchKernelGGL(slot_table_kernel, dim3(256), dim3(64), 0, s, tabXe32, Wg, Wv, D, c, static_cast<bf16_t *>(tab_bf16));
+  return hipGetLastError();
+}
+hipError_t fade_encode_ranges(const WinSrc &ws, const uint2 *ranges, int B, int S, const CoderBufs &cb, hipStream_t s) {
+  hipLaunchKernelGGL(encode_ranges_kernel, dim3((B + 63) / 64), dim3(64), 0, s, ws, ranges, B, S, cb);
+  return hipGetLastError();
+}
 hipError_t fade_bmm(const float *y, const void *WU, void *z, int B, bool bf16, hipStream_t s) {
   if (bf16)
     hipLaunchKernelGGL(bmm_kernel<bf16_t>, dim3((B + 3) / 4), dim3(256), 0, s, y, static_cast<const bf16_t *>(WU), static_cast<bf16_t *>(z), B);
@@ -742,6 +897,10 @@ hipError_t fade_softmax_quant_code(const SqcArgs &a, int mode, hipStream_t s) {
   const dim3 grid((a.B + 3) / 4), block(256);
   if (mode == CODE_ENCODE) hipLaunchKernelGGL(softmax_quant_code_kernel<CODE_ENCODE>, grid, block, 0, s, a);
   else if (mode == CODE_DECODE) hipLaunchKernelGGL(softmax_quant_code_kernel<CODE_DECODE>, grid, block, 0, s, a);
+  else if (mode == CODE_RANGES) {
+    if (!a.ranges || a.streams <= 0 || a.B % a.streams) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(softmax_quant_code_kernel<CODE_RANGES>, grid, block, 0, s, a);
+  }
   else hipLaunchKernelGGL(softmax_quant_code_kernel<CODE_NONE>, grid, block, 0, s, a);
   return hipGetLastError();
 }

@@ -251,6 +251,42 @@ def test_round_trip_and_size_vs_oracle(dtype, B, T, D, H, n):
     np.testing.assert_array_equal(o.decode(co, n), src)
 
 
+@pytest.mark.parametrize("B,T,D,H,n", [(5, 8, 32, 64, 1001), (70, 8, 32, 64, 70 * 45 + 11), (130, 16, 32, 128, 130 * 60 + 3)])
+def test_multi_step_encode_equals_single_steps(B, T, D, H, n, monkeypatch):
+    """Frozen bf16 compression runs several steps of every stream per pass (the model's steps are independent once the
+    input is known; only the coder is sequential). The container must be the one single steps produce, byte for byte:
+    the decoder, which can only take single steps, has to reproduce every table."""
+    torch = need_gpu()
+    import paper_2604_07239_amd as fa
+    blob = fi.init_blob(B, T, D, H, 5, std=0.05)
+    src = fi.text(21, n)
+    outs = {}
+    for steps in ("1", "7", None):   # single steps; groups with a ragged last one; the default
+        if steps is None:
+            monkeypatch.delenv("FADE_STEPS_PER_PASS", raising=False)
+        else:
+            monkeypatch.setenv("FADE_STEPS_PER_PASS", steps)
+        g = fa.Fade(fa.make_config(B, T, D, H, dtype=fa.BF16))
+        g.load_weights(blob.data)
+        _log(f"multi-step encode B={B} n={n} steps/pass={steps}")
+        outs[steps] = g.encode(src)
+        if steps == "7":   # a job in pieces: passes and single steps interleave, so the rolling cache must carry over
+            sd = torch.from_numpy(src).cuda()
+            L = (n + B - 1) // B
+            first = 0
+            for cnt in (3, T + 9, 1, 1, 12, 0):
+                g.encode_device(sd, n, first, cnt)
+                first = min(L, first + cnt) if cnt else L
+            lens, data = g.payloads()
+            lens1 = np.frombuffer(outs["1"][64:64 + 4 * B].tobytes(), np.uint32)
+            np.testing.assert_array_equal(lens, lens1)
+            assert data.tobytes() == outs["1"][64 + 4 * B:].tobytes()
+        np.testing.assert_array_equal(g.decode(outs[steps], n), src)
+        g.close()
+    assert outs["1"].tobytes() == outs["7"].tobytes()
+    assert outs["1"].tobytes() == outs[None].tobytes()
+
+
 def test_uniform_model_container_is_exact():
     """Zero head -> every table is f = 256: payload = the bytes + 0x40 per stream, identical to the oracle's."""
     need_gpu()
