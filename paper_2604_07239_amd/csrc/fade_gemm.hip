@@ -388,27 +388,6 @@ __device__ __forceinline__ void bare_barrier() {
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
 }
-// Fragment reads from LDS with hand-counted waits. The compiler waits for *every* outstanding LDS read before the first
-// use of any of them, which serialises "fetch the next k-step" with "multiply this one"; issued through these wrappers it
-// does not know the reads are in flight, and lds_wait<N>() (N = reads issued after the ones about to be used; LDS
-// returns in order) is the only wait. Every value read must pass through lds_wait's operand list before its first use.
-typedef __attribute__((ext_vector_type(4))) int i32x4;
-template <int OFF> __device__ __forceinline__ bf16x8 lds_read16(uint32_t addr) {
-  i32x4 v;
-  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
-  return __builtin_bit_cast(bf16x8, v);
-}
-template <int N> __device__ __forceinline__ void lds_wait_count() {
-  asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory");
-}
-__device__ __forceinline__ void lds_landed(bf16x8 &v) {  // orders the uses of v after the preceding lds_wait_count
-  i32x4 t = __builtin_bit_cast(i32x4, v);
-  asm volatile("" : "+v"(t));
-  v = __builtin_bit_cast(bf16x8, t);
-}
-__device__ __forceinline__ uint32_t lds_address(const void *p) {
-  return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void *)p;
-}
 __device__ __forceinline__ void dma16(const bf16_t *src, unsigned char *lds_chunk) {
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
                                    (__attribute__((address_space(3))) void *)lds_chunk, 16, 0, 0);
@@ -475,16 +454,12 @@ __device__ __forceinline__ void pipe_body(const GemmArgs &g, int bid, int split,
 
 
   // fragment read offsets inside a stage: row r, k-step ks, half h -> r * 128 + (((2 ks + h) ^ ((r / 2) & 7)) * 16)
-  int a_off[TM], b_off[TN], b_frag[TN];
+  int a_off[TM], b_off[TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i) a_off[i] = ((wm * TM + i) * 32 + (lane & 31)) * 128;
 #pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    b_off[j] = A_BYTES + ((wn * TN + j) * 32 + (lane & 31)) * 128;
-    b_frag[j] = A_BYTES + (((wn * TN + j) * KS * 64 + lane) << 4);  // fragment layout: k-step ks sits ks KiB further
-  }
+  for (int j = 0; j < TN; ++j) b_off[j] = A_BYTES + ((wn * TN + j) * 32 + (lane & 31)) * 128;
   const int a_sw = (lane >> 1) & 7, a_half = lane >> 5;  // tile rows start at multiples of 32, so (r / 2) & 7 == (lane / 2) & 7
-  const uint32_t lds_base = lds_address(smem);
 
   // EPI_PARTIAL with sum_splits: this workgroup walks all K ranges itself and adds their sums in range order, which is
   // bit for bit what the reducing kernels make of separate partials; otherwise it owns the one range `split`.
@@ -510,31 +485,23 @@ __device__ __forceinline__ void pipe_body(const GemmArgs &g, int bid, int split,
     else wait_vmcnt<0>();
     bare_barrier();  // everyone's part of stage kb is in LDS, and everyone is done reading stage kb-1
     if (kb + STAGES - 1 < nkb) issue((kb + STAGES - 1) % STAGES, kb0 + kb + STAGES - 1);
-    const uint32_t st = lds_base + (kb % STAGES) * STAGE_BYTES;
+    const unsigned char *st = smem + (kb % STAGES) * STAGE_BYTES;
     // fragments of k-step ks+1 are fetched from LDS while the matrix cores work on k-step ks
     bf16x8 af[2][TM], bf[2][TN];
     auto fetch = [&](int buf, int ks) {
-      const uint32_t kx = (uint32_t)(((2 * ks + a_half) ^ a_sw) << 4);
 #pragma unroll
-      for (int i = 0; i < TM; ++i) af[buf][i] = lds_read16<0>(st + a_off[i] + kx);
+      for (int i = 0; i < TM; ++i)
+        af[buf][i] = *reinterpret_cast<const bf16x8 *>(st + a_off[i] + (((2 * ks + a_half) ^ a_sw) << 4));
 #pragma unroll
       for (int j = 0; j < TN; ++j)
-        bf[buf][j] = BROW ? lds_read16<0>(st + b_off[j] + kx) : lds_read16<0>(st + b_frag[j] + ks * 1024);
+        bf[buf][j] = BROW ? *reinterpret_cast<const bf16x8 *>(st + b_off[j] + (((2 * ks + a_half) ^ a_sw) << 4))
+                          : *reinterpret_cast<const bf16x8 *>(st + A_BYTES + ((((wn * TN + j) * KS + ks) * 64 + lane) << 4));
     };
     fetch(0, 0);
-    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_sched_barrier(0);  // keep the scheduler from sinking the reads next to their uses
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      if (ks + 1 < KS) {
-        fetch((ks + 1) & 1, ks + 1);
-        lds_wait_count<TM + TN>();  // the k-step about to be multiplied has landed; the one just requested may be in flight
-      } else {
-        lds_wait_count<0>();
-      }
-#pragma unroll
-      for (int i = 0; i < TM; ++i) lds_landed(af[ks & 1][i]);
-#pragma unroll
-      for (int j = 0; j < TN; ++j) lds_landed(bf[ks & 1][j]);
+      if (ks + 1 < KS) fetch((ks + 1) & 1, ks + 1);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
@@ -850,7 +817,9 @@ int fade_gemm_col_groups(int M, int K) {
   static int v = -1;
   if (v < 0) { const char *e = getenv("FADE_GEMM_XCD"); v = e ? atoi(e) : 0; }
   if (v > 0) return v;
-  return 8;
+  // Router product, M = 16384, N = K = 2048 (A 64 MiB, 200 MiB algorithmic reads): 8 ranges fetch 678 MiB from memory,
+  // 4 fetch 467, 2 fetch 433, 1 (rows only; W then streams through every L2) 453, at equal run time within 3 %.
+  return (size_t)M * K >= ((size_t)4 << 20) ? 4 : 8;
 }
 
 template <int BM, int BN, int STAGES, int EPI, bool BROW = false>

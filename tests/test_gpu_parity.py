@@ -287,6 +287,36 @@ def test_multi_step_encode_equals_single_steps(B, T, D, H, n, monkeypatch):
     assert outs["1"].tobytes() == outs[None].tobytes()
 
 
+def test_multi_step_encode_config2_full_batch():
+    """The same identity at benchmark configuration 2's full batch, where a pass carries 16 x 1024 rows through the
+    tall-product tiles and in-workgroup split sums that bench.py's frozen compression times."""
+    need_gpu()
+    import paper_2604_07239_amd as fa
+    spec = fi.CONFIGS[2]
+    B, T, D, H = spec["B"], spec["T"], spec["D"], spec["H"]
+    blob = fi.config_blob(2)
+    L = T + 41
+    src = np.ascontiguousarray(fi.config_bytes(2, B * 256).reshape(B, -1)[:, :L]).reshape(-1)[:B * L - 700]   # ragged tail
+    outs = []
+    for steps in ("1", None):
+        import os
+        if steps is None:
+            os.environ.pop("FADE_STEPS_PER_PASS", None)
+        else:
+            os.environ["FADE_STEPS_PER_PASS"] = steps
+        try:
+            g = fa.Fade(fa.make_config(B, T, D, H, dtype=fa.BF16))
+        finally:
+            os.environ.pop("FADE_STEPS_PER_PASS", None)
+        g.load_weights(blob.data)
+        _log(f"cfg2 multi-step encode, steps/pass={steps}")
+        outs.append(g.encode(src))
+        if steps is None:
+            np.testing.assert_array_equal(g.decode(outs[-1], src.size), src)
+        g.close()
+    assert outs[0].tobytes() == outs[1].tobytes()
+
+
 def test_uniform_model_container_is_exact():
     """Zero head -> every table is f = 256: payload = the bytes + 0x40 per stream, identical to the oracle's."""
     need_gpu()
