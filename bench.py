@@ -27,7 +27,7 @@ sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK = 2.5e15   # MI355X dense bf16, FLOP/s
 HBM_PEAK = 8.0e12         # B/s
-ROUTER_GATE_TRAFFIC_BYTES = {(2, "online"): int(0.5 * (56.3 + 53.8) * (1 << 20))}
+ROUTER_GATE_TRAFFIC_BYTES = {(2, "frozen"): int(0.5 * (466.7 + 66.1 + 457.1 + 66.1) * (1 << 20)), (2, "online"): int(0.5 * (56.3 + 53.8) * (1 << 20))}
 
 
 def parse():
@@ -141,8 +141,8 @@ def main():
             rows = B * steps_timed // max(kern["gemm_router"]["launches"], 1)
             flop = 2.0 * rows * Dh * Dh
             ach = flop / (us * 1e-6) / 1e12
-            # HBM bytes per launch: FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 from profiles/cfg2_frozen_pmc_counters.md and
-            # profiles/cfg2_online_kernel_trace_and_hbm.md (counter runs of this same program, scaled against a 256 MiB copy);
+            # HBM bytes per launch: FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 from profiles/cfg2_frozen_multistep_kernel_trace_and_hbm.md
+            # and profiles/cfg2_online_kernel_trace_and_hbm.md (counter runs of this same program, scaled against a 256 MiB copy);
             # only known for the configuration and modes profiled.
             traffic = ROUTER_GATE_TRAFFIC_BYTES.get((a.config, mode))
             roofline = {"bound": "mfma", "kernel": f"gemm_pipe_kernel (router / gate product, M={rows}, N=K=D_h)", "achieved": round(ach, 2),

@@ -813,13 +813,17 @@ hipError_t launch_bf16(const GemmArgs &g, hipStream_t s) {
 }
 
 // Column ranges of the XCD split (see tile_of_block) by the size of the A operand; FADE_GEMM_XCD overrides for sweeps.
-int fade_gemm_col_groups(int M, int K) {
+int fade_gemm_col_groups(int M, int K, int N) {
   static int v = -1;
   if (v < 0) { const char *e = getenv("FADE_GEMM_XCD"); v = e ? atoi(e) : 0; }
   if (v > 0) return v;
   // Router product, M = 16384, N = K = 2048 (A 64 MiB, 200 MiB algorithmic reads): 8 ranges fetch 678 MiB from memory,
   // 4 fetch 467, 2 fetch 433, 1 (rows only; W then streams through every L2) 453, at equal run time within 3 %.
-  return (size_t)M * K >= ((size_t)4 << 20) ? 4 : 8;
+  // Tall A: as few ranges as keep an XCD's slice of W (K x N / ranges, bf16) within 2 MiB, half of its L2.
+  if ((size_t)M * K < ((size_t)4 << 20)) return 8;
+  int cg = 1;
+  while (cg < 8 && (size_t)K * N * 2 / cg > ((size_t)2 << 20)) cg *= 2;
+  return cg;
 }
 
 template <int BM, int BN, int STAGES, int EPI, bool BROW = false>
@@ -838,7 +842,7 @@ hipError_t launch_pipe(const GemmArgs &g, hipStream_t s) {
   if (g.N % BN || g.M <= 0 || g.K % (splits * BK) || (EPI != EPI_PARTIAL && splits != 1) || g.lda % 8 || (BROW && g.ldb % 8)) return hipErrorInvalidValue;
   GemmArgs ga = g;
   const int ntm = (g.M + BM - 1) / BM, ntn = g.N / BN;
-  if (ga.col_groups == 0) ga.col_groups = fade_gemm_col_groups(g.M, g.K);
+  if (ga.col_groups == 0) ga.col_groups = fade_gemm_col_groups(g.M, g.K, g.N);
   if ((ga.col_groups != 1 && ga.col_groups != 2 && ga.col_groups != 4) || ntn % ga.col_groups) ga.col_groups = 8;
   const int rg = 8 / ga.col_groups;
   if (ga.sum_splits && EPI != EPI_PARTIAL) return hipErrorInvalidValue;
