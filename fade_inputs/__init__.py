@@ -97,10 +97,10 @@ def config_bytes(cfg_id, nbytes=None):
     return _SOURCES[spec["source"]](SEED_BASE + cfg_id, n)
 
 
-def tensor_specs(B, T, D, H, d_low=64, c=None, k=3):
+def tensor_specs(B, T, D, H, d_low=64, c=None, k=3, d_cache=None, d_e=None):
     """[(name, shape, init)] in blob order; init is 'normal' (N(0, 0.02)), 'one' or 'zero'."""
-    Dh, Dc, De = T * D, H, H
-    c = H // T if c is None else c
+    Dh, Dc, De = T * D, d_cache or H, d_e or H
+    c = Dc // T if c is None else c
     return [
         ("E", (256, D), "normal"),
         ("gamma_e", (D,), "one"), ("beta_e", (D,), "zero"),
@@ -125,8 +125,8 @@ def tensor_specs(B, T, D, H, d_low=64, c=None, k=3):
 class Blob:
     """A flat fp32 weight blob with named views."""
 
-    def __init__(self, B, T, D, H, d_low=64, c=None, k=3):
-        self.specs = tensor_specs(B, T, D, H, d_low, c, k)
+    def __init__(self, B, T, D, H, d_low=64, c=None, k=3, d_cache=None, d_e=None):
+        self.specs = tensor_specs(B, T, D, H, d_low, c, k, d_cache, d_e)
         self.offsets = OrderedDict()
         o = 0
         for name, shape, _ in self.specs:
@@ -148,10 +148,10 @@ class Blob:
         return flat[o:o + n].reshape(shape)
 
 
-def init_blob(B, T, D, H, seed, d_low=64, c=None, k=3, std=0.02):
+def init_blob(B, T, D, H, seed, d_low=64, c=None, k=3, std=0.02, d_cache=None, d_e=None):
     """Random init: matrices, conv taps, embedding and every W_U slice ~ N(0, std) (one independent
     draw per element), residual scales and LayerNorm gains 1, biases and LayerNorm shifts 0."""
-    blob = Blob(B, T, D, H, d_low, c, k)
+    blob = Blob(B, T, D, H, d_low, c, k, d_cache, d_e)
     for i, (name, shape, init) in enumerate(blob.specs):
         v = blob[name]
         if init == "normal":

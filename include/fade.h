@@ -30,7 +30,7 @@
 extern "C" {
 #endif
 
-#define FADE_ABI_VERSION 1u
+#define FADE_ABI_VERSION 2u
 
 typedef struct fade_ctx fade_ctx; /* opaque; owns all device state */
 
@@ -43,10 +43,12 @@ typedef struct {
   uint32_t B;            /* streams coded in lock-step (batch axis; stream k owns slice k of W_U) */
   uint32_t T;            /* context window in bytes ("time steps") */
   uint32_t D;            /* embedding dimension; D_h = T * D */
-  uint32_t H;            /* hidden width: rolling-cache width D_cache and refiner width D_e */
+  uint32_t H;            /* hidden width: rolling-cache width D_cache and refiner width D_e unless given below */
   uint32_t d_low;        /* d_h of Eq. 7 (low-rank width of the per-stream memory); 0 => 64 */
-  uint32_t cache_chunk;  /* c: width of one rolling-cache slot (GeGLU output of Eq. 1); 0 => H / T */
+  uint32_t cache_chunk;  /* c: width of one rolling-cache slot (GeGLU output of Eq. 1); 0 => D_cache / T */
   uint32_t conv_k;       /* taps of the causal Conv1d of Eq. 4; 0 => 3 */
+  uint32_t d_cache;      /* D_cache, width of the rolling cache M (T slots of c); 0 => H */
+  uint32_t d_e;          /* D_e, expansion width of the fine refiner (Eq. 9-10); 0 => H */
   uint32_t dtype;        /* FADE_F32 | FADE_BF16 */
   uint32_t update_mode;  /* FADE_FROZEN | FADE_ONLINE_ADAM */
   float lr, beta1, beta2, eps; /* Adam; 0 => 1e-3, 0.9, 0.999, 1e-8 */
@@ -69,10 +71,10 @@ enum {
 
 /* Bytes of the canonical weight blob for a configuration (0 if the configuration is invalid). The blob is
  * fp32, tensors back to back in this order, every matrix row-major [in][out] so that y = x W:
- *   E[256][D]; gamma_e[D]; beta_e[D]; gamma_l[D]; beta_l[D]; W_g[D][c]; W_v[D][c]; W_m[H][D_h]; lambda_m[1];
+ *   E[256][D]; gamma_e[D]; beta_e[D]; gamma_l[D]; beta_l[D]; W_g[D][c]; W_v[D][c]; W_m[D_cache][D_h]; lambda_m[1];
  *   W_conv[k][D][D]; b_conv[D]; W_r[D_h][D_h]; gamma_c[D_h]; beta_c[D_h]; W_down[D_h][d_low];
  *   W_U[B][d_low][d_low]; W_up[d_low][D_h]; W_c[D_h][D_h]; lambda_c[1]; gamma_f[D_h]; beta_f[D_h];
- *   W_fg[D_h][H]; W_fv[D_h][H]; W_f[H][D_h]; gamma_o[D_h]; beta_o[D_h]; lambda_o[1]; W_o[D_h][256]; b_o[256].
+ *   W_fg[D_h][D_e]; W_fv[D_h][D_e]; W_f[D_e][D_h]; gamma_o[D_h]; beta_o[D_h]; lambda_o[1]; W_o[D_h][256]; b_o[256].
  * (E, W_g/W_v: Eq. 1; W_m, lambda_m: Eq. 3; W_conv: Eq. 4; W_r: Eq. 5; W_down/W_U/W_up: Eq. 7; W_c, lambda_c:
  * Eq. 8; W_fg/W_fv: Eq. 9; W_f, lambda_o: Eq. 10; W_o/b_o: the 256-way output head the problem statement
  * implies. gamma_e/beta_e normalise X per token; gamma_l/beta_l are Eq. 4's LN; gamma_c, gamma_f, gamma_o are
@@ -80,10 +82,11 @@ enum {
 size_t fade_weights_nbytes(const fade_config *cfg);
 
 /* Create a context: validates the configuration and allocates all device state (compute weights, rolling
- * caches M [B][H], per-stream memories W_U, activations, coder state; optimiser state in online mode).
- * Supported shapes: D % 32 == 0 (FADE_BF16) or D % 16 == 0 (FADE_F32), (T*D) % 128 == 0, H % 64 == 0 and
- * H <= 1024, d_low == 64, conv_k <= 4, H % cache_chunk == 0, cache_chunk <= 64; with FADE_ONLINE_ADAM also
- * T*D <= 2048, D <= 32, T a divisor of 128 and D a divisor of 256; anything else is FADE_E_BAD_CONFIG. No device, or a device ordinal out of range: FADE_E_HIP. *out is NULL on failure. */
+ * caches M [B][D_cache], per-stream memories W_U, activations, coder state; optimiser state in online mode).
+ * Supported shapes: D % 32 == 0 (FADE_BF16) or D % 16 == 0 (FADE_F32), (T*D) % 128 == 0, D_cache % 64 == 0 and
+ * D_cache <= 4096, D_e % 64 == 0 and D_e <= 8192, d_low == 64, conv_k <= 4, D_cache % cache_chunk == 0,
+ * cache_chunk <= 256; with FADE_ONLINE_ADAM also T*D <= 2048, D <= 32, T a divisor of 128, D a divisor of 256 and
+ * cache_chunk <= 64; anything else is FADE_E_BAD_CONFIG. No device, or a device ordinal out of range: FADE_E_HIP. *out is NULL on failure. */
 int fade_create(const fade_config *cfg, fade_ctx **out);
 
 /* Load the canonical fp32 blob from host memory (copied; rounded to bf16 for FADE_BF16 matrix operands) and

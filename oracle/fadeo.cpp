@@ -378,12 +378,12 @@ int fail(fadeo_ctx *c, int code, const char *msg) {
 
 bool resolve_dims(const fadeo_config &cfg, Dims &d) {
   d.B = cfg.B; d.T = cfg.T; d.D = cfg.D; d.H = cfg.H;
-  d.Dh = d.T * d.D; d.Dc = d.H; d.De = d.H;
+  d.Dh = d.T * d.D; d.Dc = cfg.d_cache ? cfg.d_cache : d.H; d.De = cfg.d_e ? cfg.d_e : d.H;
   d.dl = cfg.d_low ? cfg.d_low : 64;
   d.k = cfg.conv_k ? cfg.conv_k : 3;
   if (d.B == 0 || d.T == 0 || d.D == 0 || d.H == 0) return false;
   if (cfg.cache_chunk) d.c = cfg.cache_chunk;
-  else { if (d.H % d.T) return false; d.c = d.H / d.T; }
+  else { if (d.Dc % d.T) return false; d.c = d.Dc / d.T; }
   if (d.c == 0 || d.Dc % d.c) return false;
   if (cfg.dtype > FADEO_BF16 || cfg.update_mode > FADEO_ONLINE_ADAM) return false;
   return true;
@@ -679,7 +679,8 @@ void write_header(const fadeo_ctx *C, uint64_t n, uint8_t *h) {
   h[0] = 'F'; h[1] = 'A'; h[2] = 'D'; h[3] = 'E';
   put_u16(h + 4, 1);
   h[6] = (uint8_t)C->cfg.dtype; h[7] = (uint8_t)C->cfg.update_mode;
-  put_u16(h + 8, (uint32_t)C->d.T); put_u16(h + 10, (uint32_t)C->d.D); put_u32(h + 12, (uint32_t)C->d.H);
+  put_u16(h + 8, (uint32_t)C->d.T); put_u16(h + 10, (uint32_t)C->d.D); put_u32(h + 12, (uint32_t)C->d.De);
+  if (C->d.Dc != C->d.De) put_u32(h + 44, (uint32_t)C->d.Dc);  // 0: the cache is as wide as the refiner
   put_u16(h + 16, (uint32_t)C->d.dl); put_u16(h + 18, (uint32_t)C->d.c); put_u16(h + 20, (uint32_t)C->d.k);
   put_u32(h + 24, (uint32_t)C->d.B);
   put_u32(h + 28, f32_bits(C->cfg.lr)); put_u32(h + 32, f32_bits(C->cfg.beta1));
@@ -691,7 +692,8 @@ int check_header(fadeo_ctx *C, const uint8_t *h, uint64_t *n) {
   if (!(h[0] == 'F' && h[1] == 'A' && h[2] == 'D' && h[3] == 'E') || get_u16(h + 4) != 1)
     return fail(C, FADEO_E_CORRUPT_STREAM, "bad magic or version");
   const bool same = h[6] == C->cfg.dtype && h[7] == C->cfg.update_mode && get_u16(h + 8) == C->d.T &&
-                    get_u16(h + 10) == C->d.D && get_u32(h + 12) == C->d.H && get_u16(h + 16) == C->d.dl &&
+                    get_u16(h + 10) == C->d.D && get_u32(h + 12) == C->d.De && get_u32(h + 44) == (C->d.Dc != C->d.De ? C->d.Dc : 0) &&
+                    get_u16(h + 16) == C->d.dl &&
                     get_u16(h + 18) == C->d.c && get_u16(h + 20) == C->d.k && get_u32(h + 24) == C->d.B &&
                     get_u32(h + 28) == f32_bits(C->cfg.lr) && get_u32(h + 32) == f32_bits(C->cfg.beta1) &&
                     get_u32(h + 36) == f32_bits(C->cfg.beta2) && get_u32(h + 40) == f32_bits(C->cfg.eps);

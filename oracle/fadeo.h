@@ -30,10 +30,12 @@ enum { FADEO_FROZEN = 0, FADEO_ONLINE_ADAM = 1 };
 /* Same field order as the product library's config: the harness fills one and hands it to both. */
 typedef struct {
   uint32_t struct_size, abi_version;
-  uint32_t B, T, D, H;     /* streams, context window, embedding dim, hidden width (= D_cache = D_e) */
+  uint32_t B, T, D, H;     /* streams, context window, embedding dim, hidden width (D_cache = D_e = H unless given below) */
   uint32_t d_low;          /* d_h of Eq. 7; 0 => 64 */
-  uint32_t cache_chunk;    /* c: width of one rolling-cache slot; 0 => H / T */
+  uint32_t cache_chunk;    /* c: width of one rolling-cache slot; 0 => D_cache / T */
   uint32_t conv_k;         /* taps of the causal Conv1d of Eq. 4; 0 => 3 */
+  uint32_t d_cache;        /* D_cache (rolling cache width, Eq. 2-3); 0 => H */
+  uint32_t d_e;            /* D_e (expansion width of Eq. 9-10); 0 => H */
   uint32_t dtype;          /* FADEO_F32 | FADEO_BF16 */
   uint32_t update_mode;    /* FADEO_FROZEN | FADEO_ONLINE_ADAM */
   float lr, beta1, beta2, eps; /* 0 => 1e-3, 0.9, 0.999, 1e-8 */

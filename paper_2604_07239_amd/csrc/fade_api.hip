@@ -48,13 +48,13 @@ Layout make_layout(const Dims &d, bool canonical) {
 int resolve_dims(const fade_config &cfg, Dims &d, std::string *why) {
   auto bad = [&](const char *m) { if (why) *why = m; return FADE_E_BAD_CONFIG; };
   d.B = cfg.B; d.T = cfg.T; d.D = cfg.D; d.H = cfg.H;
-  d.Dh = d.T * d.D; d.Dc = d.H; d.De = d.H;
+  d.Dh = d.T * d.D; d.Dc = cfg.d_cache ? cfg.d_cache : d.H; d.De = cfg.d_e ? cfg.d_e : d.H;
   d.dl = cfg.d_low ? cfg.d_low : 64;
   d.k = cfg.conv_k ? cfg.conv_k : 3;
   if (!d.B || !d.T || !d.D || !d.H) return bad("B, T, D, H must be positive");
   if (cfg.cache_chunk) d.c = cfg.cache_chunk;
-  else { if (d.H % d.T) return bad("H is not a multiple of T and cache_chunk is 0"); d.c = d.H / d.T; }
-  if (!d.c || d.Dc % d.c) return bad("H is not a multiple of cache_chunk");
+  else { if (d.Dc % d.T) return bad("D_cache is not a multiple of T and cache_chunk is 0"); d.c = d.Dc / d.T; }
+  if (!d.c || d.Dc % d.c) return bad("D_cache is not a multiple of cache_chunk");
   if (cfg.dtype > FADE_BF16 || cfg.update_mode > FADE_ONLINE_ADAM) return bad("unknown dtype or update_mode");
   d.Kc = (d.k * d.D + 63) / 64 * 64;
   return FADE_OK;
@@ -65,13 +65,15 @@ int check_kernel_limits(const fade_config &cfg, const Dims &d, std::string *why)
   auto bad = [&](const char *m) { if (why) *why = m; return FADE_E_BAD_CONFIG; };
   if (d.dl != 64) return bad("kernels need d_low == 64");
   if (d.Dh % 128) return bad("kernels need T*D to be a multiple of 128");
-  if (d.H % 64 || d.H > 1024) return bad("kernels need H to be a multiple of 64, at most 1024");
-  if (d.c > 64) return bad("kernels need cache_chunk <= 64");
+  if (d.Dc % 64 || d.Dc > 4096) return bad("kernels need D_cache to be a multiple of 64, at most 4096");
+  if (d.De % 64 || d.De > 8192) return bad("kernels need D_e to be a multiple of 64, at most 8192");
+  if (d.c > 256) return bad("kernels need cache_chunk <= 256");
   if (d.k > 4) return bad("kernels need conv_k <= 4");
   if (cfg.dtype == FADE_BF16 ? (d.D % 32 != 0) : (d.D % 16 != 0)) return bad("kernels need D % 32 == 0 (bf16) or D % 16 == 0 (fp32)");
   if (d.B * d.T > 0x7fffffffull / 4 || d.B > (1u << 20)) return bad("B too large");
   if (cfg.update_mode == FADE_ONLINE_ADAM && (d.Dh > 2048 || d.D > 32 || 128 % d.T || 256 % d.D))
     return bad("the update kernels need T*D <= 2048, D in {16, 32} and T a power of two up to 128");
+  if (cfg.update_mode == FADE_ONLINE_ADAM && d.c > 64) return bad("the update kernels need cache_chunk <= 64");
   return FADE_OK;
 }
 
@@ -1212,7 +1214,8 @@ int fade_encode(fade_ctx *c, const uint8_t *src_host, size_t n, uint8_t *dst_hos
     std::memcpy(h, "FADE", 4);
     wr16(h + 4, 1);
     h[6] = (uint8_t)c->cfg.dtype; h[7] = (uint8_t)c->cfg.update_mode;
-    wr16(h + 8, (uint32_t)c->d.T); wr16(h + 10, (uint32_t)c->d.D); wr32(h + 12, (uint32_t)c->d.H);
+    wr16(h + 8, (uint32_t)c->d.T); wr16(h + 10, (uint32_t)c->d.D); wr32(h + 12, (uint32_t)c->d.De);
+    if (c->d.Dc != c->d.De) wr32(h + 44, (uint32_t)c->d.Dc);  // 0: the cache is as wide as the refiner
     wr16(h + 16, (uint32_t)c->d.dl); wr16(h + 18, (uint32_t)c->d.c); wr16(h + 20, (uint32_t)c->d.k);
     wr32(h + 24, (uint32_t)B);
     wr32(h + 28, fbits(c->cfg.lr)); wr32(h + 32, fbits(c->cfg.beta1)); wr32(h + 36, fbits(c->cfg.beta2)); wr32(h + 40, fbits(c->cfg.eps));
@@ -1233,7 +1236,7 @@ int fade_decode(fade_ctx *c, const uint8_t *src_host, size_t src_len, uint8_t *d
   const uint8_t *h = src_host;
   if (std::memcmp(h, "FADE", 4) != 0 || rd16(h + 4) != 1) return fail(c, FADE_E_CORRUPT_STREAM, "bad magic or version");
   const bool same = h[6] == c->cfg.dtype && h[7] == c->cfg.update_mode && rd16(h + 8) == c->d.T && rd16(h + 10) == c->d.D &&
-                    rd32(h + 12) == c->d.H && rd16(h + 16) == c->d.dl && rd16(h + 18) == c->d.c && rd16(h + 20) == c->d.k &&
+                    rd32(h + 12) == c->d.De && rd32(h + 44) == (c->d.Dc != c->d.De ? c->d.Dc : 0) && rd16(h + 16) == c->d.dl && rd16(h + 18) == c->d.c && rd16(h + 20) == c->d.k &&
                     rd32(h + 24) == B && rd32(h + 28) == fbits(c->cfg.lr) && rd32(h + 32) == fbits(c->cfg.beta1) &&
                     rd32(h + 36) == fbits(c->cfg.beta2) && rd32(h + 40) == fbits(c->cfg.eps);
   if (!same) return fail(c, FADE_E_BAD_CONFIG, "container was written with a different configuration");

@@ -140,15 +140,15 @@ __global__ __launch_bounds__(256) void embed_cache_kernel(EmbedArgs a) {
   }
   // Eq. 2: shift the cache left by one slot (through registers, so the move is safe in place) ...
   AT *M = static_cast<AT *>(a.M) + (size_t)b * a.Dc;
-  AT keep[4];
+  AT keep[16];  // D_cache <= 4096
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
+  for (int q = 0; q < 16; ++q) {
     const int idx = q * 256 + tid;
     if (idx < a.Dc) keep[q] = M[idx];
   }
   __syncthreads();
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
+  for (int q = 0; q < 16; ++q) {
     const int idx = q * 256 + tid;
     if (idx < a.Dc && idx >= a.c) M[idx - a.c] = keep[q];
   }
@@ -831,6 +831,7 @@ hipError_t fade_tables(const float *E, const float *ge, const float *be, const f
   return hipGetLastError();
 }
 hipError_t fade_embed_cache(const EmbedArgs &a, int B, bool bf16, hipStream_t s) {
+  if (a.Dc > 4096 || a.c > 256 || a.c <= 0) return hipErrorInvalidValue;  // the kernel's register file holds one cache row
   if (bf16) hipLaunchKernelGGL(embed_cache_kernel<bf16_t>, dim3(B), dim3(256), 0, s, a);
   else hipLaunchKernelGGL(embed_cache_kernel<float>, dim3(B), dim3(256), 0, s, a);
   return hipGetLastError();

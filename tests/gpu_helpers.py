@@ -16,7 +16,7 @@ def need_gpu():
 def make_pair(B, T, D, H, dtype, seed=1, update_mode=0, std=0.02, randomize=False, **kw):
     """(libfade context, oracle context, blob) with identical configuration and weights."""
     import paper_2604_07239_amd as fa
-    blob = fi.init_blob(B, T, D, H, seed, std=std)
+    blob = fi.init_blob(B, T, D, H, seed, std=std, d_cache=kw.get("d_cache"), d_e=kw.get("d_e"))
     if randomize:
         rng = np.random.default_rng(seed)
         for name, shape, init in blob.specs:

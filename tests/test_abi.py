@@ -31,7 +31,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_config_struct_matches_header_size():
     import paper_2604_07239_amd as fa
-    assert C.sizeof(fa.Config) == 15 * 4 + 4 + 8   # 11 u32 + 4 float + i32 + pointer (8-aligned)
+    assert C.sizeof(fa.Config) == 17 * 4 + 4 + 8   # 13 u32 + 4 float + i32 + pointer (8-aligned)
 
 
 def test_host_side_validation_needs_no_gpu():
@@ -39,6 +39,10 @@ def test_host_side_validation_needs_no_gpu():
     L = fa.lib()
     assert fa.weights_nbytes(fa.make_config(1024, 64, 32, 256)) == 15_490_723 * 4
     assert fa.weights_nbytes(fa.make_config(4, 3, 32, 64)) == 0          # H % T != 0 and no cache_chunk
+    # separate cache and refiner widths: only W_m, W_g/W_v (through c) and the three refiner matrices change size
+    base, wide = fa.make_config(8, 16, 32, 256), fa.make_config(8, 16, 32, 256, d_cache=512, d_e=1024)
+    Dh = 16 * 32
+    assert (fa.weights_nbytes(wide) - fa.weights_nbytes(base)) // 4 == (512 - 256) * Dh + 2 * 32 * (32 - 16) + 3 * Dh * (1024 - 256)
     h = C.c_void_p()
     bad = fa.make_config(4, 8, 32, 64)
     bad.abi_version = 99

@@ -15,9 +15,9 @@ def _log(m):
     print(m, flush=True)
 
 
-def _grad_check(dtype, B, T, D, H, seed, tol):
+def _grad_check(dtype, B, T, D, H, seed, tol, **widths):
     torch = need_gpu()
-    g, o, blob = make_pair(B, T, D, H, dtype, seed=seed, update_mode=1, randomize=True, std=0.05)
+    g, o, blob = make_pair(B, T, D, H, dtype, seed=seed, update_mode=1, randomize=True, std=0.05, **widths)
     rng = np.random.default_rng(seed)
     data = rng.integers(0, 256, (B, T + 3), dtype=np.uint8)
     probs_d = torch.zeros((B, 256), dtype=torch.float32, device="cuda")
@@ -86,6 +86,11 @@ def test_online_gradients_fp32_config1_shape():
 
 def test_online_gradients_bf16_small():
     _grad_check("bf16", 37, 8, 32, 64, seed=5, tol=3e-2)
+
+
+def test_online_gradients_separate_cache_and_refiner_widths():
+    _grad_check("bf16", 37, 8, 32, 64, seed=7, tol=3e-2, d_cache=512, d_e=128)
+    _grad_check("f32", 7, 8, 16, 64, seed=8, tol=2e-4, d_cache=128, d_e=192)
 
 
 def test_online_gradients_bf16_two_tiles():

@@ -95,9 +95,9 @@ TAP_TOL = {  # absolute tolerance per tap for the bf16 path at unit-scale activa
 }
 
 
-def _step_parity(B, T, D, H, dtype, steps, randomize, seed, std=0.02):
+def _step_parity(B, T, D, H, dtype, steps, randomize, seed, std=0.02, **widths):
     torch = need_gpu()
-    g, o, _ = make_pair(B, T, D, H, dtype, seed=seed, randomize=randomize, std=std)
+    g, o, _ = make_pair(B, T, D, H, dtype, seed=seed, randomize=randomize, std=std, **widths)
     rng = np.random.default_rng(seed)
     data = rng.integers(0, 256, (B, T + steps), dtype=np.uint8)
     freq_d = torch.zeros((B, 256), dtype=torch.int16, device="cuda")
@@ -145,6 +145,17 @@ def test_step_parity_bf16_small(B):
 
 def test_step_parity_bf16_wide_cache():
     _step_parity(33, 16, 32, 128, "bf16", steps=4, randomize=True, seed=3)
+
+
+@pytest.mark.parametrize("dtype,B,T,D,H,d_cache,d_e", [
+    ("bf16", 37, 8, 32, 64, 256, 128),     # cache slots of 32, refiner narrower than the cache
+    ("bf16", 70, 16, 32, 128, 1024, 512),  # the paper-default proportions at 1/4 scale: slots of 64, D_e = D_h
+    ("bf16", 9, 16, 32, 64, 4096, 1024),   # the widest cache the kernels take: slots of 256
+    ("f32", 11, 8, 16, 64, 128, 192),
+])
+def test_step_parity_separate_cache_and_refiner_widths(dtype, B, T, D, H, d_cache, d_e):
+    """D_cache and D_e given apart from H (the paper's default model has D_cache = 4096, D_e = 8192)."""
+    _step_parity(B, T, D, H, dtype, steps=T + 3 if T <= 8 else 4, randomize=True, seed=B, d_cache=d_cache, d_e=d_e)
 
 
 def test_step_parity_fp32_config1_shape():
@@ -251,14 +262,15 @@ def test_round_trip_and_size_vs_oracle(dtype, B, T, D, H, n):
     np.testing.assert_array_equal(o.decode(co, n), src)
 
 
-@pytest.mark.parametrize("B,T,D,H,n", [(5, 8, 32, 64, 1001), (70, 8, 32, 64, 70 * 45 + 11), (130, 16, 32, 128, 130 * 60 + 3)])
-def test_multi_step_encode_equals_single_steps(B, T, D, H, n, monkeypatch):
+@pytest.mark.parametrize("B,T,D,H,n,widths", [(5, 8, 32, 64, 1001, {}), (70, 8, 32, 64, 70 * 45 + 11, {}), (130, 16, 32, 128, 130 * 60 + 3, {}),
+                                              (21, 16, 32, 64, 21 * 50 + 5, dict(d_cache=2048, d_e=256))])
+def test_multi_step_encode_equals_single_steps(B, T, D, H, n, widths, monkeypatch):
     """Frozen bf16 compression runs several steps of every stream per pass (the model's steps are independent once the
     input is known; only the coder is sequential). The container must be the one single steps produce, byte for byte:
     the decoder, which can only take single steps, has to reproduce every table."""
     torch = need_gpu()
     import paper_2604_07239_amd as fa
-    blob = fi.init_blob(B, T, D, H, 5, std=0.05)
+    blob = fi.init_blob(B, T, D, H, 5, std=0.05, **widths)
     src = fi.text(21, n)
     outs = {}
     for steps in ("1", "7", None):   # single steps; groups with a ragged last one; the default
@@ -266,7 +278,7 @@ def test_multi_step_encode_equals_single_steps(B, T, D, H, n, monkeypatch):
             monkeypatch.delenv("FADE_STEPS_PER_PASS", raising=False)
         else:
             monkeypatch.setenv("FADE_STEPS_PER_PASS", steps)
-        g = fa.Fade(fa.make_config(B, T, D, H, dtype=fa.BF16))
+        g = fa.Fade(fa.make_config(B, T, D, H, dtype=fa.BF16, **widths))
         g.load_weights(blob.data)
         _log(f"multi-step encode B={B} n={n} steps/pass={steps}")
         outs[steps] = g.encode(src)
@@ -315,6 +327,21 @@ def test_multi_step_encode_config2_full_batch():
             np.testing.assert_array_equal(g.decode(outs[-1], src.size), src)
         g.close()
     assert outs[0].tobytes() == outs[1].tobytes()
+
+
+def test_round_trip_separate_cache_and_refiner_widths():
+    need_gpu()
+    B, n = 21, 21 * 70 + 9
+    g, o, _ = make_pair(B, 16, 32, 64, "bf16", seed=5, std=0.05, d_cache=1024, d_e=512)
+    src = fi.text(78, n)
+    c = g.encode(src)
+    np.testing.assert_array_equal(g.decode(c, n), src)
+    co = o.encode(src)
+    assert c[:64].tobytes() == co[:64].tobytes()          # both record D_e and D_cache in the header
+    assert abs(c.size - co.size) <= 0.005 * co.size + B
+    g2, _, _ = make_pair(B, 16, 32, 64, "bf16", seed=5, std=0.05, d_cache=1024, d_e=256)
+    with pytest.raises(Exception):
+        g2.decode(c, n)                                    # another refiner width: refused
 
 
 def test_uniform_model_container_is_exact():

@@ -10,7 +10,7 @@ import pytest
 
 import fade_inputs as fi
 import oracle as orc
-from helpers import TINY, randomize_small, tiny_oracle
+from helpers import SPLIT_WIDTHS, TINY, randomize_small, tiny_oracle
 
 
 def gelu(x):
@@ -170,13 +170,14 @@ def test_embedding_layernorm_flatten_closed_form():
 def _selector_blob(rng, kw):
     """Every matrix a scaled selector, every small parameter random and non-default."""
     B, T, D, H, dl, c, k = kw["B"], kw["T"], kw["D"], kw["H"], kw["d_low"], kw["cache_chunk"], kw["conv_k"]
+    Dc, De = kw.get("d_cache") or H, kw.get("d_e") or H
     Dh = T * D
-    blob = fi.Blob(B, T, D, H, dl, c, k)
+    blob = fi.Blob(B, T, D, H, dl, c, k, kw.get("d_cache"), kw.get("d_e"))
     blob["E"] = rng.standard_normal((256, D))
     randomize_small(blob, rng)
     sel = {}
-    for name, (ni, no) in dict(W_g=(D, c), W_v=(D, c), W_m=(H, Dh), W_r=(Dh, Dh), W_down=(Dh, dl),
-                               W_up=(dl, Dh), W_c=(Dh, Dh), W_fg=(Dh, H), W_fv=(Dh, H), W_f=(H, Dh),
+    for name, (ni, no) in dict(W_g=(D, c), W_v=(D, c), W_m=(Dc, Dh), W_r=(Dh, Dh), W_down=(Dh, dl),
+                               W_up=(dl, Dh), W_c=(Dh, Dh), W_fg=(Dh, De), W_fv=(Dh, De), W_f=(De, Dh),
                                W_o=(Dh, 256)).items():
         W, src, sc = selector(rng, ni, no)
         blob[name] = W
@@ -233,10 +234,11 @@ def _gather_forward(blob, sel, kw, win, M_prev):
     return dict(X=X, CACHE=M, H_GLOBAL=Hg, H_LOCAL=Hl, ALPHA=alpha, H_MIX=Hmix, Y_DOWN=y), slot
 
 
-def test_selector_network_closed_form():
+@pytest.mark.parametrize("widths", [{}, SPLIT_WIDTHS])
+def test_selector_network_closed_form(widths):
     rng = np.random.default_rng(5)
-    o, _, kw = tiny_oracle()
-    B, T, D, H, dl = kw["B"], kw["T"], kw["D"], kw["H"], kw["d_low"]
+    o, _, kw = tiny_oracle(**widths)
+    B, T, D, H, dl = kw["B"], kw["T"], kw["D"], kw.get("d_cache") or kw["H"], kw["d_low"]
     blob, sel = _selector_blob(rng, kw)
     o.load_weights(blob.data)
     f8 = lambda n: blob[n].astype(np.float64)

@@ -5,7 +5,7 @@ import pytest
 
 import fade_inputs as fi
 import oracle as orc
-from helpers import randomize_small, tiny_oracle
+from helpers import SPLIT_WIDTHS, randomize_small, tiny_oracle
 
 
 def _loss_at(o, data, win, tgt, active, warm):
@@ -16,10 +16,10 @@ def _loss_at(o, data, win, tgt, active, warm):
     return o.loss(tgt, active)
 
 
-@pytest.mark.parametrize("active", [None, np.array([1, 0, 1], np.uint8)])
-def test_gradient_matches_finite_differences(active):
+@pytest.mark.parametrize("active,widths", [(None, {}), (np.array([1, 0, 1], np.uint8), {}), (None, SPLIT_WIDTHS)])
+def test_gradient_matches_finite_differences(active, widths):
     rng = np.random.default_rng(21)
-    o, blob, kw = tiny_oracle(std=0.4)
+    o, blob, kw = tiny_oracle(std=0.4, **widths)
     randomize_small(blob, rng)
     B, T = kw["B"], kw["T"]
     warm = [rng.integers(0, 256, (B, T), dtype=np.uint8) for _ in range(2)]  # non-zero older cache slots
@@ -72,7 +72,7 @@ def _fd_loss(o, data, blob, name, win, tgt, active, warm):
 
 def _final_step_with(o, data, win, tgt, active):
     kw = dict(B=o.cfg.B, T=o.cfg.T, D=o.cfg.D, H=o.cfg.H, d_low=o.cfg.d_low, cache_chunk=o.cfg.cache_chunk,
-              conv_k=o.cfg.conv_k)
+              conv_k=o.cfg.conv_k, d_cache=o.cfg.d_cache, d_e=o.cfg.d_e)
     B = kw["B"]
     caches = [o.tap("CACHE", b) for b in range(B)]
     c = kw["cache_chunk"]
