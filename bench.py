@@ -35,7 +35,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2048)
     ap.add_argument("--warmup", type=int, default=64)
-    ap.add_argument("--config", type=int, default=2, help="benchmark configuration (1-5)")
+    ap.add_argument("--config", type=int, default=2, help="benchmark configuration (1-5; 6 = the paper-default model shape)")
     ap.add_argument("--mode", choices=["frozen", "online"], default=None)
     ap.add_argument("--full", action="store_true", help="run the whole job (all L steps) instead of K timed steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -67,6 +67,8 @@ def main():
         return
     spec = fi.CONFIGS[a.config]
     B, T, D, H = spec["B"], spec["T"], spec["D"], spec["H"]
+    widths = dict(d_cache=spec.get("d_cache", 0), d_e=spec.get("d_e", 0))
+    Dc, De = widths["d_cache"] or H, widths["d_e"] or H
     Dh, dl = T * D, 64
     dtype = fa.BF16 if spec["dtype"] == "bf16" else fa.F32
     mode = a.mode or "online"   # the method adapts its weights while coding (Algorithm 1); frozen is the inference-only variant
@@ -87,7 +89,7 @@ def main():
 
     def measure(mode):
         """compress + decompress of the timed steps in one update mode, then the event-profiled pass"""
-        g = fa.Fade(fa.make_config(B, T, D, H, dtype=dtype, update_mode=fa.ONLINE_ADAM if mode == "online" else fa.FROZEN))
+        g = fa.Fade(fa.make_config(B, T, D, H, dtype=dtype, update_mode=fa.ONLINE_ADAM if mode == "online" else fa.FROZEN, **widths))
         g.load_weights(blob.data)
         src_dev = torch.from_numpy(src).cuda()
         dst_dev = torch.zeros(n, dtype=torch.uint8, device="cuda")
@@ -132,7 +134,7 @@ def main():
             prof = g.profile_read()
             g.profile(False)
         kern = {k: {"avg_us": 1e3 * ms / max(cnt, 1), "launches": int(cnt)} for k, (ms, cnt) in prof.items()}
-        fwd_flop = 2 * (2 * D * (H // T) + T * 3 * D * D + 2 * Dh * Dh + 2 * Dh * dl + dl * dl + 4 * H * Dh + 256 * Dh)
+        fwd_flop = 2 * (2 * D * (Dc // T) + T * 3 * D * D + 2 * Dh * Dh + 2 * Dh * dl + dl * dl + (Dc + 3 * De) * Dh + 256 * Dh)
         roofline = None
         if "gemm_router" in kern and spec["dtype"] == "bf16":
             # dominant kernel: alpha = sigma(X W_r) with the mix epilogue, and its twin the gate product (Eq. 5-6, 8)
@@ -149,6 +151,17 @@ def main():
                         "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s", "frac": round(ach * 1e12 / MFMA_BF16_PEAK, 4),
                         "traffic": traffic, "avg_us": round(us, 2), "flop_per_launch": flop,
                         "algorithmic_bytes_per_launch": 2 * ((6 if mode == "online" else 5) * rows * Dh + Dh * Dh)}
+        if roofline and 2 * De > Dh and "gemm_fnr_in" in kern:
+            # refiner-dominated shapes (D_e >> D_h, the paper's default model): the dominant product is Eq. 9's pair
+            # H_coarse [W_fg | W_fv], M rows x K = D_h x N = 2 D_e, fp32 output for the folded LayerNorm + GeGLU that follows
+            us = kern["gemm_fnr_in"]["avg_us"]
+            rows = B * steps_timed // max(kern["gemm_fnr_in"]["launches"], 1)
+            flop = 2.0 * rows * Dh * 2 * De
+            ach = flop / (us * 1e-6) / 1e12
+            roofline = {"bound": "mfma", "kernel": f"gemm_pipe_kernel (refiner input product, M={rows}, K=D_h, N=2 D_e)", "achieved": round(ach, 2),
+                        "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s", "frac": round(ach * 1e12 / MFMA_BF16_PEAK, 4),
+                        "traffic": None, "avg_us": round(us, 2), "flop_per_launch": flop,
+                        "algorithmic_bytes_per_launch": 2 * rows * Dh + 2 * Dh * 2 * De + 4 * rows * 2 * De}
         step_us_events = sum(v["avg_us"] * v["launches"] for k, v in kern.items() if k != "code_uniform") / max(steps_timed, 1)
         return dict(t_enc=t_enc, t_dec=t_dec, ok=ok, steps_timed=steps_timed, bytes_timed=bytes_timed, container=container, enc_MBps=enc_MBps,
                     dec_MBps=dec_MBps, kern=kern, roofline=roofline, step_us_events=step_us_events)
@@ -156,7 +169,7 @@ def main():
     r = measure(mode)
     t_enc, t_dec, ok, steps_timed, bytes_timed, container = r["t_enc"], r["t_dec"], r["ok"], r["steps_timed"], r["bytes_timed"], r["container"]
     enc_MBps, dec_MBps, kern, roofline, step_us_events = r["enc_MBps"], r["dec_MBps"], r["kern"], r["roofline"], r["step_us_events"]
-    fwd_flop = 2 * (2 * D * (H // T) + T * 3 * D * D + 2 * Dh * Dh + 2 * Dh * dl + dl * dl + 4 * H * Dh + 256 * Dh)
+    fwd_flop = 2 * (2 * D * (Dc // T) + T * 3 * D * D + 2 * Dh * Dh + 2 * Dh * dl + dl * dl + (Dc + 3 * De) * Dh + 256 * Dh)
     other = None
     if a.mode is None and not a.full:  # default run: the inference-only variant (frozen weights) of the same steps beside the headline
         f = measure("frozen")
@@ -172,7 +185,7 @@ def main():
         import oracle as orc
         Bo, So = min(a.oracle_streams, B), (a.oracle_steps or 24)
         sub = fi.slice_blob(blob, spec, Bo) if Bo != B else blob
-        o = orc.Oracle(orc.make_config(Bo, T, D, H, dtype=orc.BF16 if spec["dtype"] == "bf16" else orc.F32,
+        o = orc.Oracle(orc.make_config(Bo, T, D, H, **widths, dtype=orc.BF16 if spec["dtype"] == "bf16" else orc.F32,
                                        update_mode=orc.ONLINE_ADAM if mode == "online" else orc.FROZEN))
         o.load_weights(sub.data)
         osrc = np.ascontiguousarray(full.reshape(B, L)[:Bo, :T + So]).reshape(-1)
@@ -190,7 +203,7 @@ def main():
         "ms_per_step": round(1e3 * t_enc / steps_timed, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": spec["dtype"], "data": "synthetic",
         "config": {"workload": f"cfg{a.config}: {spec['nbytes'] >> 20} MiB {spec['source']} source, B={B} streams, T={T}, D={D}, "
-                               f"H={H}, d_low=64, {spec['dtype']} operands / fp32 accumulate, random-init N(0,0.02); "
+                               f"D_cache={Dc}, D_e={De}, d_low=64, {spec['dtype']} operands / fp32 accumulate, random-init N(0,0.02); "
                                + ("whole job" if a.full else f"timed on steps [{first},{first + K}) of every stream"),
                    "update_mode": mode, "B": B, "bytes_timed": int(bytes_timed)},
         "decompress_MBps": round(dec_MBps, 3), "decompress_ms_per_step": round(1e3 * t_dec / steps_timed, 5),

@@ -16,13 +16,15 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB = os.path.join(HERE, "libfadegen.so")
 SEED_BASE = 0xFADE0000
 
-# name -> (B, T, D, H, dtype, bytes, generator) of the five benchmark configurations
+# name -> (B, T, D, H, dtype, bytes, generator) of the five benchmark configurations, and 6: the model shape the paper
+# adopts as its default (Cache_dim = 4096, FNR_dim = 8192 at a 16-byte window) on a 256 MiB text-like input
 CONFIGS = OrderedDict([
     (1, dict(B=16, T=32, D=16, H=128, dtype="f32", nbytes=1 << 20, source="markov2")),
     (2, dict(B=1024, T=64, D=32, H=256, dtype="bf16", nbytes=64 << 20, source="text")),
     (3, dict(B=4096, T=64, D=32, H=256, dtype="bf16", nbytes=256 << 20, source="genome")),
     (4, dict(B=4096, T=64, D=32, H=256, dtype="bf16", nbytes=256 << 20, source="float")),
     (5, dict(B=16384, T=64, D=32, H=512, dtype="bf16", nbytes=1 << 30, source="mixed")),
+    (6, dict(B=4096, T=16, D=32, H=8192, d_cache=4096, d_e=8192, dtype="bf16", nbytes=256 << 20, source="text")),
 ])
 
 
@@ -169,14 +171,14 @@ def config_blob(cfg_id, B=None):
     """Random-init blob of benchmark configuration `cfg_id`; `B` overrides the stream count (the first
     B slices of W_U are then identical to those of the full blob, every other tensor is unchanged)."""
     spec = CONFIGS[cfg_id]
-    full = init_blob(spec["B"], spec["T"], spec["D"], spec["H"], SEED_BASE + cfg_id)
+    full = init_blob(spec["B"], spec["T"], spec["D"], spec["H"], SEED_BASE + cfg_id, d_cache=spec.get("d_cache"), d_e=spec.get("d_e"))
     if B is None or B == spec["B"]:
         return full
     return slice_blob(full, spec, B)
 
 
 def slice_blob(full, spec, B):
-    sub = Blob(B, spec["T"], spec["D"], spec["H"])
+    sub = Blob(B, spec["T"], spec["D"], spec["H"], d_cache=spec.get("d_cache"), d_e=spec.get("d_e"))
     for name, _, _ in sub.specs:
         if name == "W_U":
             sub[name] = full[name][:B]

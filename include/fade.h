@@ -85,8 +85,8 @@ size_t fade_weights_nbytes(const fade_config *cfg);
  * caches M [B][D_cache], per-stream memories W_U, activations, coder state; optimiser state in online mode).
  * Supported shapes: D % 32 == 0 (FADE_BF16) or D % 16 == 0 (FADE_F32), (T*D) % 128 == 0, D_cache % 64 == 0 and
  * D_cache <= 4096, D_e % 64 == 0 and D_e <= 8192, d_low == 64, conv_k <= 4, D_cache % cache_chunk == 0,
- * cache_chunk <= 256; with FADE_ONLINE_ADAM also T*D <= 2048, D <= 32, T a divisor of 128, D a divisor of 256 and
- * cache_chunk <= 64; anything else is FADE_E_BAD_CONFIG. No device, or a device ordinal out of range: FADE_E_HIP. *out is NULL on failure. */
+ * cache_chunk <= 256; with FADE_ONLINE_ADAM also T*D <= 2048, D <= 32, T a divisor of 128 and D a divisor of 256;
+ * anything else is FADE_E_BAD_CONFIG. No device, or a device ordinal out of range: FADE_E_HIP. *out is NULL on failure. */
 int fade_create(const fade_config *cfg, fade_ctx **out);
 
 /* Load the canonical fp32 blob from host memory (copied; rounded to bf16 for FADE_BF16 matrix operands) and

@@ -73,7 +73,6 @@ int check_kernel_limits(const fade_config &cfg, const Dims &d, std::string *why)
   if (d.B * d.T > 0x7fffffffull / 4 || d.B > (1u << 20)) return bad("B too large");
   if (cfg.update_mode == FADE_ONLINE_ADAM && (d.Dh > 2048 || d.D > 32 || 128 % d.T || 256 % d.D))
     return bad("the update kernels need T*D <= 2048, D in {16, 32} and T a power of two up to 128");
-  if (cfg.update_mode == FADE_ONLINE_ADAM && d.c > 64) return bad("the update kernels need cache_chunk <= 64");
   return FADE_OK;
 }
 
@@ -144,6 +143,7 @@ struct fade_ctx {
   float *tabXhat = nullptr, *tabRstd = nullptr, *convt_f32 = nullptr;
   void *WT_o = nullptr, *WT_f = nullptr, *WT_fgv = nullptr, *WT_c = nullptr, *WT_up = nullptr, *WT_down = nullptr, *WT_r = nullptr,
        *WT_conv = nullptr;
+  void *WT_mslot = nullptr, *dg_slot = nullptr;  // wide cache slots (c % 64 == 0): W_m's last slot transposed (fragments [Dh][c]), dg [B][c]
   void *dl = nullptr, *dHout = nullptr, *dnv = nullptr, *dV = nullptr, *dHc = nullptr, *dHexp = nullptr, *dE = nullptr, *du = nullptr,
        *dHa = nullptr, *dac = nullptr, *dHmix1 = nullptr, *dHmix2 = nullptr, *dy_at = nullptr, *dnc = nullptr, *dar = nullptr,
        *dhm = nullptr, *dcv = nullptr, *dX1 = nullptr, *dX2 = nullptr, *dxl = nullptr;
@@ -284,6 +284,7 @@ int refresh_small(fade_ctx *c) {
   padd(PREP_ROUND, c->P(P_WV), 0, 0, d.D * d.c, c->Wv_c);
   padd(PREP_FRAG, c->P(P_WCONV), d.k * d.D, d.Kc, d.D, c->Wconv_c);
   if (c->online) padd(PREP_FRAG_CONVT, c->P(P_WCONV), d.k * d.D, d.Kc, d.D, c->WT_conv);
+  if (c->WT_mslot) padd(PREP_FRAG_T, c->P(P_WM) + (d.Dc - d.c) * d.Dh, d.c, d.c, d.Dh, c->WT_mslot);
   HIP_TRY(c, fade_prep_batch(pb, s));
   ReduceBatch fr{};  // s then t, adjacent
   fr.push_plain((int)(d.Dh / 64), (int)(2 * d.dl), c->fold_down, c->s_down);
@@ -521,6 +522,14 @@ int forward_bf16(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uin
     g.lam = c->P(P_LAMBDA_C); g.stats_out = c->stats_f;
     HIP_TRY(c, fade_gemm(GEMM_GATE, true, g, s));
   }
+  if (c->sp_fnr == 1) {  // Eq. 9, enough tiles without splitting K: folded LN and GeGLU in the product's epilogue
+    Prof p(c, "gemm_fnr_in");
+    GemmArgs g{};
+    g.M = B; g.N = 2 * De; g.K = Dh;
+    g.A = c->Hc; g.lda = Dh; g.W = c->Wfgv_c; g.C = c->Hexp; g.ldc = De; g.C2 = c->eg; g.C3 = c->ev;
+    g.stats = c->stats_f; g.stats_n = SN; g.fold_s = c->s_fnr; g.fold_t = c->t_fnr;
+    HIP_TRY(c, fade_gemm(GEMM_FNR_IN, true, g, s));
+  } else {
   {  // Eq. 9: H_coarse [W'_fg | W'_fv] as split-K partials
     Prof p(c, "gemm_fnr_in");
     GemmArgs g{};
@@ -535,6 +544,7 @@ int forward_bf16(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uin
     a.s_fold = c->s_fnr; a.t_fold = c->t_fnr; a.Hexp = static_cast<bf16_t *>(c->Hexp);
     a.eg = static_cast<bf16_t *>(c->eg); a.ev = static_cast<bf16_t *>(c->ev);
     HIP_TRY(c, fade_geglu(a, s));
+  }
   }
   {  // Eq. 10: H_expand W_f (+ statistics for its LayerNorm)
     Prof p(c, "gemm_fnr_out");
@@ -754,7 +764,12 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
   }
   {
     Prof p(c, "bwd_slot");
+    if (c->dg_slot) {  // wide slots: dg = d(hm) W_m[Dc-c..Dc)^T as a product
+      GemmArgs g = args_x(c, c->dhm, Dh, (int)d.c, c->WT_mslot, c->P(P_WM) + (d.Dc - d.c) * d.Dh, Dh, c->dg_slot);
+      HIP_TRY(c, fade_gemm(GEMM_X_STORE, bf, g, s));
+    }
     BwdSlotArgs a{};
+    a.dg = c->dg_slot;
     a.Dh = Dh; a.Dc = (int)d.Dc; a.c = (int)d.c; a.D = (int)d.D; a.round_bf16 = bf ? 1 : 0; a.dhm = c->dhm; a.Wm = c->P(P_WM);
     a.GG = c->GG; a.GV = c->GV; a.Wg = c->Wg_c; a.Wv = c->Wv_c; a.dgg = c->dgg; a.dgv = c->dgv; a.dxt = c->dxt;
     a.ws = ws; a.B = B; a.T = (int)d.T; a.tabXe32 = c->tabXe32; a.part = c->slot_part;
@@ -967,9 +982,11 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
     c->sp_down = pick_splits((int)((d.B + 63) / 64), (int)(d.Dh / 64), 16);
     c->sp_fnr = pick_splits((int)((d.B + 127) / 128 * (2 * d.De / 128)), (int)(d.Dh / 64), 8);
     c->sp_head = pick_splits((int)((d.B + 127) / 128 * 2), (int)(d.Dh / 64), 8);
-    TRY_ALLOC(dev_alloc(c, &c->part_down, (size_t)c->sp_down * R * d.dl));
-    TRY_ALLOC(dev_alloc(c, &c->part_fnr, (size_t)c->sp_fnr * R * 2 * d.De));
-    TRY_ALLOC(dev_alloc(c, &c->part_head, (size_t)c->sp_head * R * 256));
+    // single steps leave one slice per K range, multi-step passes one slice of all their rows
+    const auto part_rows = [&](int splits) { return std::max((size_t)splits * d.B, R); };
+    TRY_ALLOC(dev_alloc(c, &c->part_down, part_rows(c->sp_down) * d.dl));
+    if (c->sp_fnr > 1) TRY_ALLOC(dev_alloc(c, &c->part_fnr, part_rows(c->sp_fnr) * 2 * d.De));  // one K range: no partials (folded epilogue)
+    TRY_ALLOC(dev_alloc(c, &c->part_head, part_rows(c->sp_head) * 256));
     if (c->steps_max > 1) {
       TRY_ALLOC(A(&c->slot_tab, 256 * d.c));
       TRY_ALLOC(dev_alloc(c, &c->ranges, R));
@@ -1033,7 +1050,9 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
       TRY_ALLOC(A(&c->WT_down, d.Dh * d.dl));
       TRY_ALLOC(A(&c->WT_r, d.Dh * d.Dh));
       TRY_ALLOC(A(&c->WT_conv, d.Kc * d.D));
+      if (d.c % 64 == 0) TRY_ALLOC(A(&c->WT_mslot, d.Dh * d.c));
     }
+    if (d.c % 64 == 0) TRY_ALLOC(A(&c->dg_slot, Bp * d.c));
     // gradients that serve as the right operand of a weight-gradient product have Bp rows (padding rows stay zero)
     struct { void **p; size_t n; } bufs[] = {
         {&c->dl, Bp * 256}, {&c->dHout, BDh}, {&c->dnv, BDh}, {&c->dV, BpDh}, {&c->dHc, BDh}, {&c->dHexp, d.B * d.De},

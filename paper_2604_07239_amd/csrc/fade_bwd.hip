@@ -611,71 +611,111 @@ __global__ __launch_bounds__(256) void bwd_cci_kernel(BwdCciArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Eq. 1-3 backward through the newest cache slot, one wavefront per stream (4 streams per workgroup):
+// Eq. 1-3 backward through the newest cache slot. A wavefront owns SPW streams (4 * SPW per workgroup):
 //   dg[q] = sum_n d(hm)[n] W_m[Dc-c+q][n];  d gg = dg gv psi'(gg);  d gv = dg psi(gg);  dxt = W_g d gg + W_v d gv
-// and the first stage of dW_g[i][q] = sum_b xt[b][i] d gg[b][q] (same for W_v): the workgroup's 4 streams, in order,
+// and the first stage of dW_g[i][q] = sum_b xt[b][i] d gg[b][q] (same for W_v): the workgroup's streams, in order,
 // as part[workgroup][2][D][c] (blob order); the second stage adds the workgroups in index order.
+// Without a.dg every wavefront walks all c rows of W_m's last slot itself, which is fine for the narrow slots of the
+// benchmark shapes (c = 4..8) and far too much L2 traffic for wide ones: there dg comes from a product (a.dg) and this
+// kernel only does the element-wise part. Narrow rows (D_h <= 512: one 8-wide chunk per lane, KCH = 1) put 4 streams on a
+// wavefront.
 // ---------------------------------------------------------------------------------------------------
-template <typename AT>
+template <typename AT, int SPW, int KCH>
 __global__ __launch_bounds__(256) void bwd_slot_kernel(BwdSlotArgs a) {
-  __shared__ float dg_s[4][2][64];
-  __shared__ int sym_s[4];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, b = blockIdx.x * 4 + wave;
-  const bool live = b < a.B;
-  const int nch = a.Dh / 8;  // 8-wide chunks of a row: lane owns chunks lane, lane + 64, ... (D_h <= 2048: at most 4)
-  float dh[4][8];
+  constexpr int NS = 4 * SPW;  // streams per workgroup
+  __shared__ float dg_s[NS][2][256];  // cache_chunk <= 256
+  __shared__ float xt_s[NS][64];      // D <= 64
+  __shared__ int sym_s[NS];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int b0 = blockIdx.x * NS + wave * SPW;  // this wavefront's first stream
+  const int nch = a.Dh / 8;  // 8-wide chunks of a row: lane owns chunks lane, lane + 64, ... (KCH of them)
+  float dh[SPW][KCH][8];
 #pragma unroll
-  for (int k = 0; k < 4; ++k) {
+  for (int u = 0; u < SPW; ++u)
 #pragma unroll
-    for (int i = 0; i < 8; ++i) dh[k][i] = 0.0f;
-    const int ch = lane + 64 * k;
-    if (live && ch < nch) ld8<AT>(static_cast<const AT *>(a.dhm) + (size_t)b * a.Dh + ch * 8, dh[k]);
-  }
-  float mine = 0.0f;  // lane q ends up with dg[q]
-  for (int q = 0; q < a.c; ++q) {
-    const float *wrow = a.Wm + (size_t)(a.Dc - a.c + q) * a.Dh;
-    float s = 0.0f;
+    for (int k = 0; k < KCH; ++k) {
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
+      for (int i = 0; i < 8; ++i) dh[u][k][i] = 0.0f;
       const int ch = lane + 64 * k;
-      if (ch < nch) {
-        float w[8];
-        ld8<float>(wrow + ch * 8, w);
+      if (b0 + u < a.B && ch < nch) ld8<AT>(static_cast<const AT *>(a.dhm) + (size_t)(b0 + u) * a.Dh + ch * 8, dh[u][k]);
+    }
+  for (int q0 = 0; q0 < a.c; q0 += 64) {  // 64 slot columns at a time: lane ql ends up with dg[q0 + ql] of each stream
+    const int qn = a.c - q0 < 64 ? a.c - q0 : 64;
+    float mine[SPW];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) s = fmaf(dh[k][i], a.round_bf16 ? (float)(bf16_t)w[i] : w[i], s);
+    for (int u = 0; u < SPW; ++u) {
+      mine[u] = 0.0f;
+      if (a.dg && lane < qn && b0 + u < a.B) mine[u] = (float)static_cast<const AT *>(a.dg)[(size_t)(b0 + u) * a.c + q0 + lane];
+    }
+    for (int ql = 0; ql < (a.dg ? 0 : qn); ++ql) {
+      const float *wrow = a.Wm + (size_t)(a.Dc - a.c + q0 + ql) * a.Dh;
+      float sacc[SPW];
+#pragma unroll
+      for (int u = 0; u < SPW; ++u) sacc[u] = 0.0f;
+#pragma unroll
+      for (int k = 0; k < KCH; ++k) {
+        const int ch = lane + 64 * k;
+        if (ch < nch) {
+          float w[8];
+          ld8<float>(wrow + ch * 8, w);
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            const float wi = a.round_bf16 ? (float)(bf16_t)w[i] : w[i];
+#pragma unroll
+            for (int u = 0; u < SPW; ++u) sacc[u] = fmaf(dh[u][k][i], wi, sacc[u]);
+          }
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < SPW; ++u) {
+        float sv = sacc[u];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) sv += __shfl_xor(sv, off, 64);
+        if (lane == ql) mine[u] = sv;
       }
     }
+    if (lane < qn) {
+      const int q = q0 + lane;
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
-    if (lane == q) mine = s;
-  }
-  if (lane < a.c) {
-    float dgg = 0.0f, dgv = 0.0f;
-    if (live) {
-      const float gg = a.GG[(size_t)b * a.c + lane], gv = a.GV[(size_t)b * a.c + lane];
-      dgg = mine * gv * gelu_grad_f(gg);
-      dgv = mine * gelu_f(gg);
-      a.dgg[(size_t)b * a.c + lane] = dgg;
-      a.dgv[(size_t)b * a.c + lane] = dgv;
+      for (int u = 0; u < SPW; ++u) {
+        const int b = b0 + u;
+        float dgg = 0.0f, dgv = 0.0f;
+        if (b < a.B) {
+          const float gg = a.GG[(size_t)b * a.c + q], gv = a.GV[(size_t)b * a.c + q];
+          dgg = mine[u] * gv * gelu_grad_f(gg);
+          dgv = mine[u] * gelu_f(gg);
+          a.dgg[(size_t)b * a.c + q] = dgg;
+          a.dgv[(size_t)b * a.c + q] = dgv;
+        }
+        dg_s[wave * SPW + u][0][q] = dgg;
+        dg_s[wave * SPW + u][1][q] = dgv;
+      }
     }
-    dg_s[wave][0][lane] = dgg;
-    dg_s[wave][1][lane] = dgv;
   }
-  if (lane == 0) sym_s[wave] = (live && stream_active(a.ws, b)) ? (int)stream_window(a.ws, b, a.T)[a.T - 1] : -1;
+  if (lane < SPW) {
+    const int b = b0 + lane;
+    sym_s[wave * SPW + lane] = (b < a.B && stream_active(a.ws, b)) ? (int)stream_window(a.ws, b, a.T)[a.T - 1] : -1;
+  }
   __syncthreads();
-  if (live && lane < a.D) {
-    float s = 0.0f;
-    for (int q = 0; q < a.c; ++q) s += a.Wg[lane * a.c + q] * dg_s[wave][0][q] + a.Wv[lane * a.c + q] * dg_s[wave][1][q];
-    a.dxt[(size_t)b * a.D + lane] = s;
+  // one thread per (stream, channel): the stream's x_t row goes to LDS (zero for an inactive stream: it then adds
+  // nothing below), and dxt[channel] = sum_q W_g[channel][q] d gg[q] + W_v[channel][q] d gv[q]
+  for (int t = tid; t < NS * a.D; t += 256) {
+    const int k = t / a.D, i = t - k * a.D, b = blockIdx.x * NS + k;
+    xt_s[k][i] = sym_s[k] >= 0 ? a.tabXe32[(size_t)sym_s[k] * a.D + i] : 0.0f;
+    if (b < a.B) {
+      float sv = 0.0f;
+      for (int q = 0; q < a.c; ++q) sv += a.Wg[i * a.c + q] * dg_s[k][0][q] + a.Wv[i * a.c + q] * dg_s[k][1][q];
+      a.dxt[(size_t)b * a.D + i] = sv;
+    }
   }
+  __syncthreads();
   const int nout = 2 * a.D * a.c;
   for (int t = tid; t < nout; t += 256) {
     const int which = t / (a.D * a.c), r = t - which * a.D * a.c, i = r / a.c, q = r - i * a.c;
-    float s = 0.0f;
+    float sv = 0.0f;
 #pragma unroll
-    for (int k = 0; k < 4; ++k)
-      if (sym_s[k] >= 0) s = fmaf(a.tabXe32[(size_t)sym_s[k] * a.D + i], dg_s[k][which][q], s);  // inactive streams contribute nothing
-    a.part[(size_t)blockIdx.x * nout + t] = s;
+    for (int k = 0; k < NS; ++k) sv = fmaf(xt_s[k][i], dg_s[k][which][q], sv);
+    a.part[(size_t)blockIdx.x * nout + t] = sv;
   }
 }
 
@@ -1075,10 +1115,16 @@ hipError_t fade_reduce_batch(const ReduceBatch &rb, hipStream_t s) {
 hipError_t fade_bwd_cci(const BwdCciArgs &a, bool bf16, hipStream_t s) { DISPATCH_AT(bf16, bwd_cci_kernel, dim3(a.B), dim3(256), s, a); }
 // a.part must hold ceil(B / 4) * 2 * D * c floats; dWgv points at W_g's gradient (W_v's follows it in the blob)
 hipError_t fade_bwd_slot(const BwdSlotArgs &a, float *dWgv, bool bf16, ReduceBatch &rb, hipStream_t s) {
-  if (a.Dh > 2048 || a.Dh % 8 || a.c > 64 || a.D > 64) return hipErrorInvalidValue;
-  const int P = (a.B + 3) / 4;
-  if (bf16) hipLaunchKernelGGL(bwd_slot_kernel<bf16_t>, dim3(P), dim3(256), 0, s, a);
-  else hipLaunchKernelGGL(bwd_slot_kernel<float>, dim3(P), dim3(256), 0, s, a);
+  if (a.Dh > 2048 || a.Dh % 8 || a.c > 256 || a.D > 64) return hipErrorInvalidValue;
+  const bool narrow = a.Dh <= 512;  // one chunk per lane: room for 4 streams per wavefront
+  const int P = narrow ? (a.B + 15) / 16 : (a.B + 3) / 4;
+  if (narrow) {
+    if (bf16) hipLaunchKernelGGL((bwd_slot_kernel<bf16_t, 4, 1>), dim3(P), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((bwd_slot_kernel<float, 4, 1>), dim3(P), dim3(256), 0, s, a);
+  } else {
+    if (bf16) hipLaunchKernelGGL((bwd_slot_kernel<bf16_t, 1, 4>), dim3(P), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((bwd_slot_kernel<float, 1, 4>), dim3(P), dim3(256), 0, s, a);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   return rb.push(P, 2 * a.D * a.c, a.part, dWgv) ? hipSuccess : hipErrorInvalidValue;

@@ -48,7 +48,15 @@ enum {
   EPI_CONV,        // C = psi(acc + bias[n])                    (Eq. 4)
   EPI_PARTIAL,     // C (fp32)[split][M][N] = acc of this block's K range (summed later in split order)
   EPI_GRAD,        // C (fp32) = acc: a weight gradient; with C3 set, columns interleaved per 128 go to the pair (C, C3)
+  EPI_GEGLU_FOLD,  // EPI_GEGLU on a product of raw activations: the LayerNorm folded into W is finished here, per row
+                   // (statistics of A) and per column (fold_s, fold_t), then C = psi(gate) * value; C2 / C3 = gate / value
 };
+
+// LN(h) W = rstd * (h W' - mean * s) + t for one output element (raw = h W'); one spelling for every kernel that finishes
+// a folded LayerNorm, so that they agree to the bit.
+__device__ __forceinline__ float fade_fold_ln(float raw, float mean, float rstd, float s, float t) {
+  return fmaf(rstd, fmaf(-mean, s, raw), t);
+}
 
 struct GemmArgs {
   int M, N, K;            // C[M][N] = A'[M][K] * W[K][N]
@@ -74,6 +82,7 @@ struct GemmArgs {
   const void *S1, *S2;    // side inputs [M][N] (leading dimension ldc)
   const float *bias;
   float *stats_out;       // optional [M][N / BN][2]
+  const float *fold_s, *fold_t;  // EPI_GEGLU_FOLD: the folded LayerNorm's column vectors [N] (stats / stats_n: rows of A)
   int col_groups;         // pipelined kernel: column ranges of the XCD split of the tile grid (1, 2, 4, 8; 0 = chosen by the launcher)
 };
 

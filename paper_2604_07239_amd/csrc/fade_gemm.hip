@@ -134,11 +134,12 @@ __device__ __forceinline__ void row_moments(const GemmArgs &g, int m, float &mea
 template <int EPI, typename AT, int BM, int BN>
 __device__ __forceinline__ void epilogue(const GemmArgs &g, const float *Cs, int m0, int n0, int nt, int tid, int split = 0) {
   constexpr int LDC = BN + 4;
-  constexpr int BNO = (EPI == EPI_GEGLU) ? BN / 2 : BN;  // output columns of this tile
+  constexpr bool kGeglu = EPI == EPI_GEGLU || EPI == EPI_GEGLU_FOLD;
+  constexpr int BNO = kGeglu ? BN / 2 : BN;  // output columns of this tile
   constexpr int CH = BNO / 8;                            // chunks (threads) per row
   constexpr int RP = 256 / CH;                           // rows per pass
   const int c8 = (tid % CH) * 8, r0 = tid / CH;
-  const int nout0 = (EPI == EPI_GEGLU) ? nt * BNO : n0;  // first output column of the tile
+  const int nout0 = kGeglu ? nt * BNO : n0;  // first output column of the tile
   float lam = 0.0f;
   if (EPI == EPI_GLOBAL || EPI == EPI_GATE) lam = g.lam[0];
 #pragma unroll 1
@@ -190,6 +191,21 @@ __device__ __forceinline__ void epilogue(const GemmArgs &g, const float *Cs, int
         store8(static_cast<AT *>(g.C) + o, out);
         if (g.C2) store8(static_cast<AT *>(g.C2) + o, x);
         if (g.C3) store8(static_cast<AT *>(g.C3) + o, xv);
+      } else if (EPI == EPI_GEGLU_FOLD) {
+        float xv[8], sg[8], tg[8], sv[8], tv[8], eg[8], ev[8], mean, rstd;
+        load8(Cs + r * LDC + BNO + c8, xv);
+        load8(g.fold_s + n0 + c8, sg); load8(g.fold_t + n0 + c8, tg);
+        load8(g.fold_s + n0 + BNO + c8, sv); load8(g.fold_t + n0 + BNO + c8, tv);
+        row_moments(g, m, mean, rstd);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          eg[i] = fade_fold_ln(x[i], mean, rstd, sg[i], tg[i]);
+          ev[i] = fade_fold_ln(xv[i], mean, rstd, sv[i], tv[i]);
+          out[i] = gelu_f(eg[i]) * ev[i];
+        }
+        store8(static_cast<AT *>(g.C) + o, out);
+        if (g.C2) store8(static_cast<AT *>(g.C2) + o, eg);
+        if (g.C3) store8(static_cast<AT *>(g.C3) + o, ev);
       } else if (EPI == EPI_GRAD) {
         if (g.C3) {
           const int v = n0 + c8;
@@ -986,6 +1002,9 @@ hipError_t fade_gemm(int op, bool bf16, const GemmArgs &g, hipStream_t s) {
       case GEMM_UP:       return launch_pipe_auto<EPI_STORE>(g, s);
       case GEMM_GATE:     return launch_pipe_auto<EPI_GATE>(g, s);
       case GEMM_FNR_OUT:  return launch_pipe_auto<EPI_STORE>(g, s);
+      case GEMM_FNR_IN:   // Eq. 9 in one piece (no split-K): folded LayerNorm and GeGLU in the epilogue
+        if (!g.stats || !g.fold_s || !g.fold_t) return hipErrorInvalidValue;
+        return launch_pipe_auto<EPI_GEGLU_FOLD>(g, s);
       case GEMM_PARTIAL:  // split-K products whose LayerNorm / bias / non-linearity follow in the reducing kernel
         if (g.N % 128 == 0) return launch_pipe<128, 128, 4, EPI_PARTIAL>(g, s);
         return launch_pipe<64, 64, 4, EPI_PARTIAL>(g, s);

@@ -193,6 +193,8 @@ struct BwdSlotArgs {
   int B, T;
   int Dh, Dc, c, D, round_bf16;
   const void *dhm;        // [B][Dh]
+  const void *dg;         // optional [B][c] (activation type): d(hm) W_m[Dc-c..Dc)^T already formed by a product; else
+                          // the kernel forms it from Wm itself
   const float *Wm;        // fp32 master W_m [Dc][Dh]
   const float *GG, *GV;   // [B][c]
   const float *Wg, *Wv;   // [D][c] compute values

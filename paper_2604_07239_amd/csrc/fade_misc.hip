@@ -284,8 +284,8 @@ __global__ __launch_bounds__(256) void geglu_kernel(GegluArgs a) {
   bf16x8 out, eg, ev;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    const float gi = rstd * (g[i] - mean * a.s_fold[vg + i]) + a.t_fold[vg + i];
-    const float vi = rstd * (v[i] - mean * a.s_fold[vv + i]) + a.t_fold[vv + i];
+    const float gi = fade_fold_ln(g[i], mean, rstd, a.s_fold[vg + i], a.t_fold[vg + i]);
+    const float vi = fade_fold_ln(v[i], mean, rstd, a.s_fold[vv + i], a.t_fold[vv + i]);
     out[i] = (bf16_t)(gelu_f(gi) * vi);
     eg[i] = (bf16_t)gi;
     ev[i] = (bf16_t)vi;

@@ -93,6 +93,18 @@ def test_online_gradients_separate_cache_and_refiner_widths():
     _grad_check("f32", 7, 8, 16, 64, seed=8, tol=2e-4, d_cache=128, d_e=192)
 
 
+def test_online_gradients_refiner_product_without_split_k():
+    """D_e = 8192: Eq. 9's product finishes its folded LayerNorm and GeGLU in the epilogue and leaves the gate / value
+    pre-activations the backward pass needs."""
+    _grad_check("bf16", 130, 16, 32, 64, seed=11, tol=3e-2, d_cache=1024, d_e=8192)
+
+
+def test_online_gradients_widest_cache_slots():
+    """Cache slots of 256 (D_cache = 4096 at T = 16, the paper-default cache): the slot backward walks them 64 at a time."""
+    _grad_check("bf16", 9, 16, 32, 64, seed=9, tol=3e-2, d_cache=4096, d_e=256)
+    _grad_check("f32", 5, 16, 16, 64, seed=10, tol=2e-4, d_cache=2048, d_e=64)
+
+
 def test_online_gradients_bf16_two_tiles():
     _grad_check("bf16", 130, 16, 32, 128, seed=6, tol=3e-2)
 

@@ -152,6 +152,7 @@ def test_step_parity_bf16_wide_cache():
     ("bf16", 70, 16, 32, 128, 1024, 512),  # the paper-default proportions at 1/4 scale: slots of 64, D_e = D_h
     ("bf16", 9, 16, 32, 64, 4096, 1024),   # the widest cache the kernels take: slots of 256
     ("f32", 11, 8, 16, 64, 128, 192),
+    ("bf16", 130, 16, 32, 64, 1024, 8192),  # enough column tiles for the refiner's input product to skip split-K
 ])
 def test_step_parity_separate_cache_and_refiner_widths(dtype, B, T, D, H, d_cache, d_e):
     """D_cache and D_e given apart from H (the paper's default model has D_cache = 4096, D_e = 8192)."""
@@ -201,12 +202,13 @@ def _sampled_streams_parity(cfg, streams, steps=2):
     B, T, D, H = spec["B"], spec["T"], spec["D"], spec["H"]
     blob = fi.config_blob(cfg)
     idx = np.asarray(streams)
-    sub = fi.Blob(len(idx), T, D, H)
+    widths = dict(d_cache=spec.get("d_cache", 0), d_e=spec.get("d_e", 0))
+    sub = fi.Blob(len(idx), T, D, H, **widths)
     for name, _, _ in sub.specs:
         sub[name] = blob[name][idx] if name == "W_U" else blob[name]
-    g = fa.Fade(fa.make_config(B, T, D, H, dtype=fa.BF16))
+    g = fa.Fade(fa.make_config(B, T, D, H, dtype=fa.BF16, **widths))
     g.load_weights(blob.data)
-    o = orc.Oracle(orc.make_config(len(idx), T, D, H, dtype=orc.BF16))
+    o = orc.Oracle(orc.make_config(len(idx), T, D, H, dtype=orc.BF16, **widths))
     o.load_weights(sub.data)
     data = fi.config_bytes(cfg, B * 256).reshape(B, -1)[:, :T + steps]
     probs_d = torch.zeros((B, 256), dtype=torch.float32, device="cuda")
@@ -229,6 +231,12 @@ def _sampled_streams_parity(cfg, streams, steps=2):
 def test_step_parity_config3_full_batch_sampled():
     """B = 4096 (configurations 3 and 4 share the model shape): 256-row tiles in the router / gate products."""
     _sampled_streams_parity(3, list(range(6)) + [1023, 2048, 4000] + list(range(4090, 4096)))
+
+
+def test_step_parity_paper_default_shape_full_batch_sampled():
+    """Configuration 6: T = 16, D = 32, D_cache = 4096, D_e = 8192 at B = 4096, the model the paper adopts as its default.
+    The refiner's input product runs without split-K here: folded LayerNorm and GeGLU in its epilogue."""
+    _sampled_streams_parity(6, list(range(4)) + [1023, 2048] + list(range(4092, 4096)), steps=2)
 
 
 def test_step_parity_config5_full_batch_sampled():
