@@ -119,8 +119,8 @@ size_t fade_encode_bound(const fade_ctx *ctx, size_t n);
  * bytes [kL, min(n, (k+1)L))); the first T symbols of each stream are coded with the uniform table, every
  * later symbol with the model's table, followed in online mode by the update. Resets the context first.
  * Container (little-endian): 64-byte header {magic "FADE", version u16, dtype u8, update_mode u8, T u16, D u16,
- * H u32, d_low u16, c u16, k u16, pad u16, B u32, lr, beta1, beta2, eps (f32 bits), pad u32, n u64, FNV-1a-64 of
- * the weight blob}, then B x u32 payload lengths, then the B payloads. Weights are not stored.
+ * D_e u32, d_low u16, c u16, k u16, pad u16, B u32, lr, beta1, beta2, eps (f32 bits), D_cache u32 (0 when it equals
+ * D_e), n u64, FNV-1a-64 of the weight blob}, then B x u32 payload lengths, then the B payloads. Weights are not stored.
  * Frozen bf16 contexts take several consecutive steps of every stream per pass here and in fade_encode_device (the
  * model's steps are independent once the input is known); the container is byte for byte the one single steps write.
  * The steps per pass are fixed at fade_create (about 16384 / B, at most 256; environment variable
