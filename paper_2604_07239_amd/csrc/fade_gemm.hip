@@ -131,13 +131,12 @@ __device__ __forceinline__ void row_moments(const GemmArgs &g, int m, float &mea
 // ---------------------------------------------------------------------------------------------------
 // epilogue: the accumulator tile sits in LDS as fp32 [BM][BN + 4]; threads walk it in 8-wide row chunks
 // ---------------------------------------------------------------------------------------------------
-template <int EPI, typename AT, int BM, int BN>
+template <int EPI, typename AT, int BM, int BN, int LDC = BN + 4, int NT = 256>
 __device__ __forceinline__ void epilogue(const GemmArgs &g, const float *Cs, int m0, int n0, int nt, int tid, int split = 0) {
-  constexpr int LDC = BN + 4;
   constexpr bool kGeglu = EPI == EPI_GEGLU || EPI == EPI_GEGLU_FOLD;
   constexpr int BNO = kGeglu ? BN / 2 : BN;  // output columns of this tile
   constexpr int CH = BNO / 8;                            // chunks (threads) per row
-  constexpr int RP = 256 / CH;                           // rows per pass
+  constexpr int RP = NT / CH;                            // rows per pass
   const int c8 = (tid % CH) * 8, r0 = tid / CH;
   const int nout0 = kGeglu ? nt * BNO : n0;  // first output column of the tile
   float lam = 0.0f;
@@ -409,24 +408,25 @@ __device__ __forceinline__ void dma16(const bf16_t *src, unsigned char *lds_chun
                                    (__attribute__((address_space(3))) void *)lds_chunk, 16, 0, 0);
 }
 
-template <int BM, int BN, int STAGES, int EPI, bool BROW>
+template <int BM, int BN, int STAGES, int EPI, bool BROW, int NW = 4>
 __device__ __forceinline__ void pipe_body(const GemmArgs &g, int bid, int split, int nsplit) {
   typedef bf16_t AT;
   constexpr int BK = 64, KS = 4;
-  constexpr int TM = BM / 64, TN = BN / 64;          // 32x32 tiles per wavefront (wavefronts 2 x 2)
+  constexpr int WN = NW / 2;                         // wavefronts 2 (rows) x WN (columns)
+  constexpr int TM = BM / 64, TN = BN / (32 * WN);   // 32x32 tiles per wavefront
   constexpr int BFR = BN / 32;
   constexpr int A_BYTES = BM * 128;                  // A stage: BM rows of 64 k (128 bytes), 16-byte pieces XOR-swizzled
-  constexpr int ACH = BM / 8 / 4;                    // A DMAs per wavefront and stage (one DMA = 8 rows x 128 bytes)
-  constexpr int BCH = BROW ? BN / 8 / 4 : BFR * KS / 4;  // W DMAs per wavefront and stage (one fragment, or 8 rows x 128 bytes)
+  constexpr int ACH = BM / 8 / NW;                   // A DMAs per wavefront and stage (one DMA = 8 rows x 128 bytes)
+  constexpr int BCH = BROW ? BN / 8 / NW : BFR * KS / NW;  // W DMAs per wavefront and stage (one fragment, or 8 rows x 128 bytes)
   constexpr int LPW = ACH + BCH;
   constexpr int STAGE_BYTES = A_BYTES + BFR * KS * 1024, LDC = BN + 4;
-  static_assert((BM / 8) % 4 == 0 && (BFR * KS) % 4 == 0 && (BN / 8) % 4 == 0, "chunk split");
+  static_assert((BM / 8) % NW == 0 && (BFR * KS) % NW == 0 && (BN / 8) % NW == 0, "chunk split");
   static_assert((STAGES - 2) * LPW <= 63, "vmcnt range");
   extern __shared__ __align__(16) unsigned char smem[];
   float *Cs = reinterpret_cast<float *>(smem);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WN, wn = wave % WN;
   const int ntn = g.N / BN, ntm = (g.M + BM - 1) / BM;
   int mt, nt;
   if (!tile_of_block(bid, ntm, ntn, g.col_groups, mt, nt)) return;
@@ -442,7 +442,7 @@ __device__ __forceinline__ void pipe_body(const GemmArgs &g, int bid, int split,
   const bf16_t *src[LPW];
 #pragma unroll
   for (int q = 0; q < ACH; ++q) {
-    const int c = wave + 4 * q;
+    const int c = wave + NW * q;
     int row = m0 + c * 8 + (lane >> 3);
     row = row < g.M ? row : g.M - 1;
     const int sw = ((c * 8 + (lane >> 3)) >> 1) & 7;
@@ -450,7 +450,7 @@ __device__ __forceinline__ void pipe_body(const GemmArgs &g, int bid, int split,
   }
 #pragma unroll
   for (int q = 0; q < BCH; ++q) {
-    const int c = wave + 4 * q;
+    const int c = wave + NW * q;
     if (BROW) {  // row-major [N][ldb]: same 8-rows-per-DMA, XOR-swizzled scheme as A
       const int row = n0 + c * 8 + (lane >> 3);
       const int sw = ((c * 8 + (lane >> 3)) >> 1) & 7;
@@ -463,9 +463,9 @@ __device__ __forceinline__ void pipe_body(const GemmArgs &g, int bid, int split,
   auto issue = [&](int slot, int kb) {  // kb: 64-wide k block counted from the start of K
     unsigned char *base = smem + slot * STAGE_BYTES;
 #pragma unroll
-    for (int q = 0; q < ACH; ++q) dma16(src[q] + (size_t)kb * BK, base + (wave + 4 * q) * 1024);
+    for (int q = 0; q < ACH; ++q) dma16(src[q] + (size_t)kb * BK, base + (wave + NW * q) * 1024);
 #pragma unroll
-    for (int q = 0; q < BCH; ++q) dma16(src[ACH + q] + (BROW ? (size_t)kb * BK : (size_t)kb * KS * 512), base + A_BYTES + (wave + 4 * q) * 1024);
+    for (int q = 0; q < BCH; ++q) dma16(src[ACH + q] + (BROW ? (size_t)kb * BK : (size_t)kb * KS * 512), base + A_BYTES + (wave + NW * q) * 1024);
   };
 
 
@@ -539,6 +539,33 @@ __device__ __forceinline__ void pipe_body(const GemmArgs &g, int bid, int split,
   }
 
   wait_vmcnt<0>();
+  if constexpr (NW == 8) {
+    // 256 x 256 tile: the fp32 tile does not fit LDS at once. It leaves in slabs of 64 rows, each handed to the epilogue as
+    // 128-column halves (the width the row statistics are kept at), so every output is formed exactly as by the smaller tiles.
+    static_assert(EPI != EPI_PARTIAL && EPI != EPI_GEGLU && EPI != EPI_GEGLU_FOLD && TM % 2 == 0 && BN % 128 == 0, "slab epilogue");
+#pragma unroll
+    for (int p = 0; p < BM / 64; ++p) {
+      constexpr int ROWS_PER_WAVE = 32 * TM;
+      const int owner = (p * 64) / ROWS_PER_WAVE, i0 = ((p * 64) % ROWS_PER_WAVE) / 32;
+      __syncthreads();  // the ring, or the previous slab, is no longer being read
+      if (wm == owner) {
+#pragma unroll
+        for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+              const int row = ii * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+              const int col = (wn * TN + j) * 32 + (lane & 31);
+              Cs[row * LDC + col] = acc[i0 + ii][j][e];
+            }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int h = 0; h < BN / 128; ++h)
+        epilogue<EPI, AT, 64, 128, LDC, NW * 64>(g, Cs + h * 128, m0 + p * 64, n0 + h * 128, nt * (BN / 128) + h, tid, 0);
+    }
+  } else {
   __syncthreads();
 #pragma unroll
   for (int i = 0; i < TM; ++i)
@@ -553,6 +580,11 @@ __device__ __forceinline__ void pipe_body(const GemmArgs &g, int bid, int split,
       }
   __syncthreads();
   epilogue<EPI, AT, BM, BN>(g, Cs, m0, n0, nt, tid, fuse ? 0 : split);
+  }
+}
+template <int EPI>
+__global__ __launch_bounds__(512, 1) void gemm_pipe8_kernel(GemmArgs g) {  // 256 x 256 tile, two stages, eight wavefronts
+  pipe_body<256, 256, 2, EPI, false, 8>(g, (int)blockIdx.x, 0, 1);
 }
 template <int BM, int BN, int STAGES, int EPI, bool BROW>
 __global__ __launch_bounds__(256, (STAGES == 2 && BM * BN <= 128 * 128) ? 2 : 1) void gemm_pipe_kernel(GemmArgs g) {
@@ -883,6 +915,27 @@ hipError_t launch_tn(const GemmArgs &g, hipStream_t s) {
   return hipGetLastError();
 }
 
+template <int EPI>
+hipError_t launch_pipe8(const GemmArgs &g, hipStream_t s) {
+  constexpr size_t lds = 2 * (256 * 128 + 8 * 4 * 1024);  // two stages of 64 KiB; the 64-row epilogue slabs (65 KiB) alias them
+  static bool attr_done = false;
+  auto kern = gemm_pipe8_kernel<EPI>;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  if (g.N % 256 || g.M <= 0 || g.K % 64 || g.splits > 1 || g.lda % 8) return hipErrorInvalidValue;
+  GemmArgs ga = g;
+  const int ntm = (g.M + 255) / 256, ntn = g.N / 256;
+  if (ga.col_groups == 0) ga.col_groups = fade_gemm_col_groups(g.M, g.K, g.N);
+  if ((ga.col_groups != 1 && ga.col_groups != 2 && ga.col_groups != 4) || ntn % ga.col_groups) ga.col_groups = 8;
+  const int rg = 8 / ga.col_groups;
+  const dim3 grid((ntn % ga.col_groups == 0 ? (ntm + rg - 1) / rg * rg : ntm) * ntn);
+  hipLaunchKernelGGL(kern, grid, dim3(512), lds, s, ga);
+  return hipGetLastError();
+}
+
 // Tile shape by problem size. Small batches: 64 x 128 tiles, four stages, so that every compute unit gets a tile. From
 // 512 tiles of 128 x 128 on: that tile with a two-stage ring (64 KiB of LDS), two workgroups per compute unit: one's
 // epilogue (side inputs from HBM, stores) and pipeline fill run under the other's products, which measured faster than
@@ -891,6 +944,13 @@ template <int EPI>
 hipError_t launch_pipe_auto(const GemmArgs &g, hipStream_t s) {
   const int tiles128 = ((g.M + 127) / 128) * (g.N / 128);
   const int tune = fade_gemm_tune();
+  if constexpr (EPI != EPI_PARTIAL && EPI != EPI_GEGLU && EPI != EPI_GEGLU_FOLD) {
+    // 256 x 256 tiles on eight wavefronts once every compute unit gets one: half the operand bytes per flop of 128 x 128, and
+    // two wavefronts per SIMD to run matrix instructions under each other's LDS / DMA traffic (router product: 74 us against
+    // 82 at M = 8192, 166 against 183 at M = 16384; with only 128 tiles at M = 4096 it loses, 68 against 43)
+    const int tiles256 = ((g.M + 255) / 256) * (g.N / 256);
+    if (g.N % 256 == 0 && (tune == 12 || (tune == 0 && tiles256 >= 256 && g.K >= 1024))) return launch_pipe8<EPI>(g, s);  // short K: the epilogue dominates, two small workgroups per unit hide it better
+  }
   if (tune == 11 || (tune == 0 && tiles128 >= 512)) return launch_pipe<128, 128, 2, EPI>(g, s);
   if (tune == 10) return launch_pipe<256, 128, 3, EPI>(g, s);
   if (tune == 1 || (tune == 0 && tiles128 >= 256)) return launch_pipe<128, 128, 4, EPI>(g, s);
@@ -985,7 +1045,7 @@ hipError_t fade_gemm_group_launch(const GemmGroup &gg, hipStream_t s) {
 }
 
 // Tuning override for experiments (FADE_GEMM_TUNE: 0 automatic, 1 force 128x128x4 stages, 2 force 64x128, 10 force 256x128x3,
-// 11 force 128x128x2 with two workgroups per compute unit).
+// 11 force 128x128x2 with two workgroups per compute unit, 12 force 256x256x2 on eight wavefronts).
 int fade_gemm_tune() {
   static int v = -1;
   if (v < 0) { const char *e = getenv("FADE_GEMM_TUNE"); v = e ? atoi(e) : 0; }
