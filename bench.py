@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=64)
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration (1-5; 6 = the paper-default model shape)")
     ap.add_argument("--mode", choices=["frozen", "online"], default=None)
+    ap.add_argument("--ablation", type=int, default=0, choices=[0, 1, 2, 3, 4, 5],
+                    help="head on a prefix of the model (the paper's progressive ablation; 1-4: frozen weights only)")
     ap.add_argument("--full", action="store_true", help="run the whole job (all L steps) instead of K timed steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -72,6 +74,9 @@ def main():
     Dh, dl = T * D, 64
     dtype = fa.BF16 if spec["dtype"] == "bf16" else fa.F32
     mode = a.mode or "online"   # the method adapts its weights while coding (Algorithm 1); frozen is the inference-only variant
+    if 1 <= a.ablation <= 4:
+        mode = "frozen"
+        widths["ablation"] = a.ablation
     K, W = a.steps, a.warmup
 
     full = fi.config_bytes(a.config)
@@ -134,11 +139,11 @@ def main():
             prof = g.profile_read()
             g.profile(False)
         kern = {k: {"avg_us": 1e3 * ms / max(cnt, 1), "launches": int(cnt)} for k, (ms, cnt) in prof.items()}
-        fwd_flop = 2 * (2 * D * (Dc // T) + T * 3 * D * D + 2 * Dh * Dh + 2 * Dh * dl + dl * dl + (Dc + 3 * De) * Dh + 256 * Dh)
         roofline = None
         if "gemm_router" in kern and spec["dtype"] == "bf16":
             # dominant kernel: alpha = sigma(X W_r) with the mix epilogue, and its twin the gate product (Eq. 5-6, 8)
-            us = 0.5 * (kern["gemm_router"]["avg_us"] + kern["gemm_gate"]["avg_us"])
+            twins = [kern[k]["avg_us"] for k in ("gemm_router", "gemm_gate") if k in kern]
+            us = sum(twins) / len(twins)
             # frozen compression carries several steps of every stream through one launch: rows = B * steps per pass
             rows = B * steps_timed // max(kern["gemm_router"]["launches"], 1)
             flop = 2.0 * rows * Dh * Dh
@@ -151,6 +156,15 @@ def main():
                         "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s", "frac": round(ach * 1e12 / MFMA_BF16_PEAK, 4),
                         "traffic": traffic, "avg_us": round(us, 2), "flop_per_launch": flop,
                         "algorithmic_bytes_per_launch": 2 * ((6 if mode == "online" else 5) * rows * Dh + Dh * Dh)}
+        if roofline is None and "gemm_global" in kern and spec["dtype"] == "bf16":   # ablation level 1: the global projection is all there is
+            us = kern["gemm_global"]["avg_us"]
+            rows = B * steps_timed // max(kern["gemm_global"]["launches"], 1)
+            flop = 2.0 * rows * Dc * Dh
+            ach = flop / (us * 1e-6) / 1e12
+            roofline = {"bound": "mfma", "kernel": f"gemm_pipe_kernel (global projection, M={rows}, K=D_cache, N=D_h)", "achieved": round(ach, 2),
+                        "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s", "frac": round(ach * 1e12 / MFMA_BF16_PEAK, 4),
+                        "traffic": None, "avg_us": round(us, 2), "flop_per_launch": flop,
+                        "algorithmic_bytes_per_launch": 2 * (rows * Dc + Dc * Dh + 2 * rows * Dh)}
         if roofline and 2 * De > Dh and "gemm_fnr_in" in kern:
             # refiner-dominated shapes (D_e >> D_h, the paper's default model): the dominant product is Eq. 9's pair
             # H_coarse [W_fg | W_fv], M rows x K = D_h x N = 2 D_e, fp32 output for the folded LayerNorm + GeGLU that follows
@@ -169,9 +183,11 @@ def main():
     r = measure(mode)
     t_enc, t_dec, ok, steps_timed, bytes_timed, container = r["t_enc"], r["t_dec"], r["ok"], r["steps_timed"], r["bytes_timed"], r["container"]
     enc_MBps, dec_MBps, kern, roofline, step_us_events = r["enc_MBps"], r["dec_MBps"], r["kern"], r["roofline"], r["step_us_events"]
-    fwd_flop = 2 * (2 * D * (Dc // T) + T * 3 * D * D + 2 * Dh * Dh + 2 * Dh * dl + dl * dl + (Dc + 3 * De) * Dh + 256 * Dh)
+    lvl = a.ablation or 5
+    fwd_flop = 2 * (2 * D * (Dc // T) + Dc * Dh + 256 * Dh + (T * 3 * D * D + Dh * Dh if lvl >= 2 else 0)
+                    + (2 * Dh * dl + dl * dl if lvl >= 3 else 0) + (Dh * Dh if lvl >= 4 else 0) + (3 * De * Dh if lvl >= 5 else 0))
     other = None
-    if a.mode is None and not a.full:  # default run: the inference-only variant (frozen weights) of the same steps beside the headline
+    if a.mode is None and not a.full and not 1 <= a.ablation <= 4:  # default run: the inference-only variant (frozen weights) of the same steps beside the headline
         f = measure("frozen")
         other = {"update_mode": "frozen", "compress_MBps": round(f["enc_MBps"], 3), "decompress_MBps": round(f["dec_MBps"], 3),
                  "ms_per_step": round(1e3 * f["t_enc"] / f["steps_timed"], 5), "round_trip_exact": f["ok"],
@@ -205,7 +221,7 @@ def main():
         "config": {"workload": f"cfg{a.config}: {spec['nbytes'] >> 20} MiB {spec['source']} source, B={B} streams, T={T}, D={D}, "
                                f"D_cache={Dc}, D_e={De}, d_low=64, {spec['dtype']} operands / fp32 accumulate, random-init N(0,0.02); "
                                + ("whole job" if a.full else f"timed on steps [{first},{first + K}) of every stream"),
-                   "update_mode": mode, "B": B, "bytes_timed": int(bytes_timed)},
+                   "update_mode": mode, "B": B, "bytes_timed": int(bytes_timed), "ablation_level": a.ablation or 5},
         "decompress_MBps": round(dec_MBps, 3), "decompress_ms_per_step": round(1e3 * t_dec / steps_timed, 5),
         "total_MBps": round(2 * bytes_timed / (t_enc + t_dec) / 1e6, 3),
         "round_trip_exact": ok, "bits_per_byte": round(8.0 * container / n, 4),

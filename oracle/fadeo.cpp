@@ -386,6 +386,7 @@ bool resolve_dims(const fadeo_config &cfg, Dims &d) {
   else { if (d.Dc % d.T) return false; d.c = d.Dc / d.T; }
   if (d.c == 0 || d.Dc % d.c) return false;
   if (cfg.dtype > FADEO_BF16 || cfg.update_mode > FADEO_ONLINE_ADAM) return false;
+  if (cfg.ablation > 5 || (cfg.ablation >= 1 && cfg.ablation <= 4 && cfg.update_mode != FADEO_FROZEN)) return false;
   return true;
 }
 
@@ -427,6 +428,12 @@ void forward_stream(fadeo_ctx *C, size_t b, const uint8_t *win) {
   const double lam_m = (double)C->P(P_LAMBDA_M)[0];
   for (size_t i = 0; i < Dh; ++i) a.Hg[i] = gelu(a.hm[i]) + lam_m * X[i];
 
+  // Progressive ablation (the paper's component table): the output head reads the feature vector of the last stage
+  // that is switched on. 1: the global stream alone; 2: + local stream and router; 3: + channel interaction without
+  // its gate; 4: with the gate; 0 / 5: the full model.
+  const unsigned level = C->cfg.ablation == 0 ? 5u : C->cfg.ablation;
+  const double *feat = a.Hg.data();
+  if (level >= 2) {
   // Eq. 4: causal Conv1d over time (k taps, channels D -> D, left zero padding, bias), psi, flatten.
   const float *Wc = C->P(P_WCONV);
   for (size_t j = 0; j < T; ++j) {
@@ -449,6 +456,9 @@ void forward_stream(fadeo_ctx *C, size_t b, const uint8_t *win) {
     a.alpha[i] = sigmoid(a.ar[i]);
     a.Hmix[i] = a.alpha[i] * a.Hg[i] + (1.0 - a.alpha[i]) * a.Hl[i];
   }
+  feat = a.Hmix.data();
+  }
+  if (level >= 3) {
 
   // Eq. 7: H_a = Up(BMM(Down(LN(H_mix)), W_U)); slice b of W_U belongs to stream b; purely linear chain.
   layer_norm(a.Hmix.data(), Dh, C->P(P_GAMMA_C), C->P(P_BETA_C), a.nc.data(), a.nc_hat.data(), &a.rstd_c);
@@ -456,13 +466,20 @@ void forward_stream(fadeo_ctx *C, size_t b, const uint8_t *win) {
   vec_mat(a.y.data(), C->P(P_WU) + b * d.dl * d.dl, d.dl, d.dl, a.z.data());
   vec_mat(a.z.data(), C->P(P_WUP), d.dl, Dh, a.Ha.data());
 
-  // Eq. 8: H_coarse = H_a (.) sigma(H_mix W_c) + lambda_c H_mix
-  vec_mat(a.Hmix.data(), C->P(P_WC), Dh, Dh, a.ac.data());
+  // Eq. 8: H_coarse = H_a (.) sigma(H_mix W_c) + lambda_c H_mix; without the gate (level 3) the sigmoid factor is dropped
   const double lam_c = (double)C->P(P_LAMBDA_C)[0];
-  for (size_t i = 0; i < Dh; ++i) {
-    a.sg[i] = sigmoid(a.ac[i]);
-    a.Hc[i] = a.Ha[i] * a.sg[i] + lam_c * a.Hmix[i];
+  if (level >= 4) {
+    vec_mat(a.Hmix.data(), C->P(P_WC), Dh, Dh, a.ac.data());
+    for (size_t i = 0; i < Dh; ++i) {
+      a.sg[i] = sigmoid(a.ac[i]);
+      a.Hc[i] = a.Ha[i] * a.sg[i] + lam_c * a.Hmix[i];
+    }
+  } else {
+    for (size_t i = 0; i < Dh; ++i) a.Hc[i] = a.Ha[i] + lam_c * a.Hmix[i];
   }
+  feat = a.Hc.data();
+  }
+  if (level >= 5) {
 
   // Eq. 9: H_expand = psi(u W_fg) (.) (u W_fv), u = LN(H_coarse)
   layer_norm(a.Hc.data(), Dh, C->P(P_GAMMA_F), C->P(P_BETA_F), a.u.data(), a.u_hat.data(), &a.rstd_f);
@@ -475,10 +492,12 @@ void forward_stream(fadeo_ctx *C, size_t b, const uint8_t *win) {
   layer_norm(a.v.data(), Dh, C->P(P_GAMMA_O), C->P(P_BETA_O), a.nv.data(), a.nv_hat.data(), &a.rstd_o);
   const double lam_o = (double)C->P(P_LAMBDA_O)[0];
   for (size_t i = 0; i < Dh; ++i) a.Hout[i] = gelu(a.nv[i]) + lam_o * a.Hc[i];
+  feat = a.Hout.data();
+  }
 
   // head (implied by the problem statement: a distribution over the 256 byte values): one linear
   // layer with bias, then a max-subtracted softmax.
-  vec_mat(a.Hout.data(), C->P(P_WO), Dh, 256, a.logits.data());
+  vec_mat(feat, C->P(P_WO), Dh, 256, a.logits.data());
   double mx = -INFINITY;
   for (int i = 0; i < 256; ++i) {
     a.logits[i] += (double)C->P(P_BO)[i];

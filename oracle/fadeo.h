@@ -36,6 +36,8 @@ typedef struct {
   uint32_t conv_k;         /* taps of the causal Conv1d of Eq. 4; 0 => 3 */
   uint32_t d_cache;        /* D_cache (rolling cache width, Eq. 2-3); 0 => H */
   uint32_t d_e;            /* D_e (expansion width of Eq. 9-10); 0 => H */
+  uint32_t ablation;       /* 0 or 5: full model; 1: head on H_global; 2: on H_mix; 3: on H_a + lambda_c H_mix; 4: on H_coarse
+                            * (frozen weights only) */
   uint32_t dtype;          /* FADEO_F32 | FADEO_BF16 */
   uint32_t update_mode;    /* FADEO_FROZEN | FADEO_ONLINE_ADAM */
   float lr, beta1, beta2, eps; /* 0 => 1e-3, 0.9, 0.999, 1e-8 */

@@ -18,20 +18,20 @@ class Config(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("abi_version", C.c_uint32),
                 ("B", C.c_uint32), ("T", C.c_uint32), ("D", C.c_uint32), ("H", C.c_uint32),
                 ("d_low", C.c_uint32), ("cache_chunk", C.c_uint32), ("conv_k", C.c_uint32),
-                ("d_cache", C.c_uint32), ("d_e", C.c_uint32),
+                ("d_cache", C.c_uint32), ("d_e", C.c_uint32), ("ablation", C.c_uint32),
                 ("dtype", C.c_uint32), ("update_mode", C.c_uint32),
                 ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
                 ("device", C.c_int32), ("hip_stream", C.c_void_p)]
 
 
 def make_config(B, T, D, H, d_low=0, cache_chunk=0, conv_k=0, dtype=BF16, update_mode=FROZEN, lr=0.0, beta1=0.0,
-                beta2=0.0, eps=0.0, device=0, hip_stream=None, d_cache=0, d_e=0):
+                beta2=0.0, eps=0.0, device=0, hip_stream=None, d_cache=0, d_e=0, ablation=0):
     c = Config()
     c.struct_size = C.sizeof(Config)
     c.abi_version = ABI_VERSION
     c.B, c.T, c.D, c.H = B, T, D, H
     c.d_low, c.cache_chunk, c.conv_k = d_low, cache_chunk, conv_k
-    c.d_cache, c.d_e = d_cache, d_e
+    c.d_cache, c.d_e, c.ablation = d_cache, d_e, ablation
     c.dtype, c.update_mode = dtype, update_mode
     c.lr, c.beta1, c.beta2, c.eps = lr, beta1, beta2, eps
     c.device, c.hip_stream = device, hip_stream

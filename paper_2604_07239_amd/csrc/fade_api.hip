@@ -56,6 +56,7 @@ int resolve_dims(const fade_config &cfg, Dims &d, std::string *why) {
   else { if (d.Dc % d.T) return bad("D_cache is not a multiple of T and cache_chunk is 0"); d.c = d.Dc / d.T; }
   if (!d.c || d.Dc % d.c) return bad("D_cache is not a multiple of cache_chunk");
   if (cfg.dtype > FADE_BF16 || cfg.update_mode > FADE_ONLINE_ADAM) return bad("unknown dtype or update_mode");
+  if (cfg.ablation > 5) return bad("ablation level must be 0..5");
   d.Kc = (d.k * d.D + 63) / 64 * 64;
   return FADE_OK;
 }
@@ -64,6 +65,8 @@ int resolve_dims(const fade_config &cfg, Dims &d, std::string *why) {
 int check_kernel_limits(const fade_config &cfg, const Dims &d, std::string *why) {
   auto bad = [&](const char *m) { if (why) *why = m; return FADE_E_BAD_CONFIG; };
   if (d.dl != 64) return bad("kernels need d_low == 64");
+  if (cfg.ablation >= 1 && cfg.ablation <= 4 && (cfg.dtype != FADE_BF16 || cfg.update_mode != FADE_FROZEN))
+    return bad("ablation levels 1-4 are built for the bf16 path with frozen weights only");
   if (d.Dh % 128) return bad("kernels need T*D to be a multiple of 128");
   if (d.Dc % 64 || d.Dc > 4096) return bad("kernels need D_cache to be a multiple of 64, at most 4096");
   if (d.De % 64 || d.De > 8192) return bad("kernels need D_e to be a multiple of 64, at most 8192");
@@ -461,6 +464,9 @@ int forward_bf16(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uin
   const int fuse = steps > 1 ? 1 : 0;
   const int sp_down = fuse ? 1 : c->sp_down, sp_fnr = fuse ? 1 : c->sp_fnr, sp_head = fuse ? 1 : c->sp_head;
   if (steps > 1 && (steps > c->steps_max || mode != CODE_ENCODE || c->online)) return fail(c, FADE_E_INVALID_ARG, "multi-step pass not available");
+  // progressive ablation (the paper's component table): the head reads the last stage that is switched on
+  const int level = c->cfg.ablation == 0 ? 5 : (int)c->cfg.ablation;
+  const void *feat = c->Hg;
   {
     Prof p(c, "embed_cache");
     EmbedArgs a{};
@@ -470,7 +476,7 @@ int forward_bf16(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uin
     if (steps > 1) HIP_TRY(c, fade_embed_steps(a, s));
     else HIP_TRY(c, fade_embed_cache(a, streams, true, s));
   }
-  {  // Eq. 4
+  if (level >= 2) {  // Eq. 4
     Prof p(c, "gemm_conv");
     GemmArgs g{};
     g.M = B * (int)d.T; g.N = (int)d.D; g.K = (int)d.Kc;
@@ -485,7 +491,8 @@ int forward_bf16(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uin
     g.A = c->M; g.lda = (int)d.Dc; g.W = c->Wm_c; g.C = c->Hg; g.ldc = Dh; g.C2 = c->hm; g.S1 = c->X; g.lam = c->P(P_LAMBDA_M);
     HIP_TRY(c, fade_gemm(GEMM_GLOBAL, true, g, s));
   }
-  {  // Eq. 5-6
+  if (level >= 2) {  // Eq. 5-6
+    feat = c->Hmix;
     Prof p(c, "gemm_router");
     GemmArgs g{};
     g.M = B; g.N = Dh; g.K = Dh;
@@ -493,28 +500,33 @@ int forward_bf16(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uin
     g.stats_out = c->stats_c;
     HIP_TRY(c, fade_gemm(GEMM_ROUTER, true, g, s));
   }
-  {  // Eq. 7: H_mix W'_down as split-K partials
+  if (level >= 3) {  // Eq. 7: H_mix W'_down as split-K partials
     Prof p(c, "gemm_down");
     GemmArgs g{};
     g.M = B; g.N = (int)d.dl; g.K = Dh; g.splits = c->sp_down; g.sum_splits = fuse;
     g.A = c->Hmix; g.lda = Dh; g.W = c->Wdown_c; g.C = c->part_down; g.ldc = (int)d.dl;
     HIP_TRY(c, fade_gemm(GEMM_PARTIAL, true, g, s));
   }
-  {  // Eq. 7: folded LN, then the per-stream memory
+  if (level >= 3) {  // Eq. 7: folded LN, then the per-stream memory
     Prof p(c, "cci_wu");
     CciArgs a{};
     a.B = B; a.streams = streams; a.Dh = Dh; a.splits = sp_down; a.stats_n = SN; a.part = c->part_down; a.stats = c->stats_c;
     a.s_fold = c->s_down; a.t_fold = c->t_down; a.WU = static_cast<const bf16_t *>(c->WU_c); a.y = c->y; a.z = static_cast<bf16_t *>(c->z);
     HIP_TRY(c, fade_cci(a, s));
   }
-  {  // Eq. 7: Up
+  if (level >= 3) {  // Eq. 7: Up
+    feat = c->Hc;
     Prof p(c, "gemm_up");
     GemmArgs g{};
     g.M = B; g.N = Dh; g.K = (int)d.dl;
     g.A = c->z; g.lda = (int)d.dl; g.W = c->Wup_c; g.C = c->Ha; g.ldc = Dh;
     HIP_TRY(c, fade_gemm(GEMM_UP, true, g, s));
   }
-  {  // Eq. 8
+  if (level == 3) {  // Eq. 8 without its gate
+    Prof p(c, "residual_add");
+    HIP_TRY(c, fade_residual_add(c->Ha, c->Hmix, c->P(P_LAMBDA_C), c->Hc, (size_t)B * Dh, s));
+  }
+  if (level >= 4) {  // Eq. 8
     Prof p(c, "gemm_gate");
     GemmArgs g{};
     g.M = B; g.N = Dh; g.K = Dh;
@@ -522,7 +534,8 @@ int forward_bf16(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uin
     g.lam = c->P(P_LAMBDA_C); g.stats_out = c->stats_f;
     HIP_TRY(c, fade_gemm(GEMM_GATE, true, g, s));
   }
-  if (c->sp_fnr == 1) {  // Eq. 9, enough tiles without splitting K: folded LN and GeGLU in the product's epilogue
+  if (level < 5) {
+  } else if (c->sp_fnr == 1) {  // Eq. 9, enough tiles without splitting K: folded LN and GeGLU in the product's epilogue
     Prof p(c, "gemm_fnr_in");
     GemmArgs g{};
     g.M = B; g.N = 2 * De; g.K = Dh;
@@ -546,14 +559,15 @@ int forward_bf16(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uin
     HIP_TRY(c, fade_geglu(a, s));
   }
   }
-  {  // Eq. 10: H_expand W_f (+ statistics for its LayerNorm)
+  if (level >= 5) {  // Eq. 10: H_expand W_f (+ statistics for its LayerNorm)
     Prof p(c, "gemm_fnr_out");
     GemmArgs g{};
     g.M = B; g.N = Dh; g.K = De;
     g.A = c->Hexp; g.lda = De; g.W = c->Wf_c; g.C = c->V; g.ldc = Dh; g.stats_out = c->stats_o;
     HIP_TRY(c, fade_gemm(GEMM_FNR_OUT, true, g, s));
   }
-  {  // Eq. 10's tail
+  if (level >= 5) {  // Eq. 10's tail
+    feat = c->Hout;
     Prof p(c, "hout");
     HoutArgs a{};
     a.B = B; a.Dh = Dh; a.stats_n = SN; a.V = c->V; a.Hc = c->Hc;
@@ -564,7 +578,7 @@ int forward_bf16(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uin
     Prof p(c, "gemm_head");
     GemmArgs g{};
     g.M = B; g.N = 256; g.K = Dh; g.splits = c->sp_head; g.sum_splits = fuse;
-    g.A = c->Hout; g.lda = Dh; g.W = c->Wo_c; g.C = c->part_head; g.ldc = 256;
+    g.A = feat; g.lda = Dh; g.W = c->Wo_c; g.C = c->part_head; g.ldc = 256;
     HIP_TRY(c, fade_gemm(GEMM_PARTIAL, true, g, s));
   }
   {

@@ -106,6 +106,7 @@ struct PrepBatch {
 hipError_t fade_prep_batch(const PrepBatch &pb, hipStream_t s);
 hipError_t fade_convt_build(const float *Wconv, int taps, int D, int Kc, float *V, hipStream_t s);
 hipError_t fade_cci(const CciArgs &a, hipStream_t s);
+hipError_t fade_residual_add(const void *x, const void *y, const float *lam, void *out, size_t n, hipStream_t s);  // bf16: out = x + lam[0] * y
 hipError_t fade_geglu(const GegluArgs &a, hipStream_t s);
 hipError_t fade_hout(const HoutArgs &a, bool bf16, hipStream_t s);
 hipError_t fade_virtual_copy(const float *W0, const float *W1, int k_real, int K, int N, int interleave, float *out, hipStream_t s);

@@ -327,6 +327,18 @@ __global__ __launch_bounds__(256) void hout_kernel(HoutArgs a) {
   for (int i = 0; i < 8; ++i) out[i] = (AT)(gelu_f((v[i] - mean) * rstd * ga[i] + be[i]) + lam * hc[i]);
 }
 
+// Eq. 8 with its gate switched off (ablation level 3): out = x + lam * y, 8 bf16 per thread.
+__global__ __launch_bounds__(256) void residual_add_kernel(const bf16_t *x, const bf16_t *y, const float *lam, bf16_t *out, size_t n8) {
+  const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (t >= n8) return;
+  const bf16x8 xv = reinterpret_cast<const bf16x8 *>(x)[t], yv = reinterpret_cast<const bf16x8 *>(y)[t];
+  const float l = lam[0];
+  bf16x8 o;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) o[i] = (bf16_t)fmaf(l, (float)yv[i], (float)xv[i]);
+  reinterpret_cast<bf16x8 *>(out)[t] = o;
+}
+
 // All element-wise weight preparation of one refresh in a single launch: blockIdx.y picks the descriptor.
 __global__ __launch_bounds__(256) void prep_batch_kernel(PrepBatch pb) {
   const PrepDesc &d = pb.d[blockIdx.y];
@@ -863,6 +875,12 @@ hipError_t fade_cci(const CciArgs &a, hipStream_t s) {
 }
 hipError_t fade_geglu(const GegluArgs &a, hipStream_t s) {
   hipLaunchKernelGGL(geglu_kernel, dim3(blocks_for((size_t)a.B * (a.De / 8), 256)), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+hipError_t fade_residual_add(const void *x, const void *y, const float *lam, void *out, size_t n, hipStream_t s) {
+  if (n % 8) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(residual_add_kernel, dim3(blocks_for(n / 8, 256)), dim3(256), 0, s, static_cast<const bf16_t *>(x), static_cast<const bf16_t *>(y),
+                     lam, static_cast<bf16_t *>(out), n / 8);
   return hipGetLastError();
 }
 hipError_t fade_hout(const HoutArgs &a, bool bf16, hipStream_t s) {

@@ -31,7 +31,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_config_struct_matches_header_size():
     import paper_2604_07239_amd as fa
-    assert C.sizeof(fa.Config) == 17 * 4 + 4 + 8   # 13 u32 + 4 float + i32 + pointer (8-aligned)
+    assert C.sizeof(fa.Config) == 19 * 4 + 4 + 8   # 14 u32 + 4 float + i32 (+ 4 padding) + pointer (8-aligned)
 
 
 def test_host_side_validation_needs_no_gpu():

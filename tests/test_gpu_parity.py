@@ -95,6 +95,10 @@ TAP_TOL = {  # absolute tolerance per tap for the bf16 path at unit-scale activa
 }
 
 
+ABLATION_TAPS = {1: ("X", "CACHE", "H_GLOBAL", "LOGITS"), 2: ("X", "CACHE", "H_GLOBAL", "H_LOCAL", "H_MIX", "LOGITS"),
+                 3: ("H_MIX", "Y_DOWN", "Z_BMM", "H_A", "H_COARSE", "LOGITS"), 4: ("H_MIX", "H_A", "H_COARSE", "LOGITS")}
+
+
 def _step_parity(B, T, D, H, dtype, steps, randomize, seed, std=0.02, **widths):
     torch = need_gpu()
     g, o, _ = make_pair(B, T, D, H, dtype, seed=seed, randomize=randomize, std=std, **widths)
@@ -127,6 +131,8 @@ def _step_parity(B, T, D, H, dtype, steps, randomize, seed, std=0.02, **widths):
         # the table is the exact quantiser image of the GPU's own probabilities
         np.testing.assert_array_equal(fg[live], orc.quantize(pg[live]))
         for name, tol in TAP_TOL.items():
+            if widths.get("ablation") and name not in ABLATION_TAPS[widths["ablation"]]:
+                continue   # stages past the cut are not computed
             t = g.tap(name)
             assert t is not None, name
             for b in np.flatnonzero(live)[:8]:
@@ -157,6 +163,44 @@ def test_step_parity_bf16_wide_cache():
 def test_step_parity_separate_cache_and_refiner_widths(dtype, B, T, D, H, d_cache, d_e):
     """D_cache and D_e given apart from H (the paper's default model has D_cache = 4096, D_e = 8192)."""
     _step_parity(B, T, D, H, dtype, steps=T + 3 if T <= 8 else 4, randomize=True, seed=B, d_cache=d_cache, d_e=d_e)
+
+
+@pytest.mark.parametrize("level", [1, 2, 3, 4])
+def test_step_parity_ablation_levels(level):
+    """The paper's progressive ablation as a configuration switch: the head reads H_global / H_mix / H_a + lambda_c H_mix /
+    H_coarse instead of the refiner's output."""
+    _step_parity(70, 8, 32, 64, "bf16", steps=10, randomize=True, seed=20 + level, ablation=level)
+
+
+def test_ablation_round_trip_and_multi_step_identity(monkeypatch):
+    need_gpu()
+    import paper_2604_07239_amd as fa
+    B, T, D, H, n = 33, 8, 32, 64, 33 * 40 + 7
+    blob = fi.init_blob(B, T, D, H, 5, std=0.05)
+    src = fi.text(31, n)
+    sizes = {}
+    for level in (1, 2, 3, 4, 5):
+        outs = []
+        for steps in ("1", None):
+            if steps is None:
+                monkeypatch.delenv("FADE_STEPS_PER_PASS", raising=False)
+            else:
+                monkeypatch.setenv("FADE_STEPS_PER_PASS", steps)
+            g = fa.Fade(fa.make_config(B, T, D, H, dtype=fa.BF16, ablation=level))
+            g.load_weights(blob.data)
+            outs.append(g.encode(src))
+            np.testing.assert_array_equal(g.decode(outs[-1], n), src)
+            g.close()
+        assert outs[0].tobytes() == outs[1].tobytes()
+        o = orc.Oracle(orc.make_config(B, T, D, H, dtype=orc.BF16, ablation=level))
+        o.load_weights(blob.data)
+        co = o.encode(src)
+        assert abs(outs[0].size - co.size) <= 0.005 * co.size + B
+        sizes[level] = outs[0].size
+    import ctypes as C
+    h = C.c_void_p()
+    assert fa.lib().fade_create(C.byref(fa.make_config(B, T, D, H, dtype=fa.BF16, ablation=2, update_mode=fa.ONLINE_ADAM)), C.byref(h)) == -2
+    assert fa.lib().fade_create(C.byref(fa.make_config(B, T, 16, H, dtype=fa.F32, ablation=2)), C.byref(h)) == -2
 
 
 def test_step_parity_fp32_config1_shape():

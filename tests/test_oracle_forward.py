@@ -369,3 +369,49 @@ def test_bf16_mode_rounds_matrices_only():
     o32.load_weights(rounded.data)
     win = windows_for(rng, kw["B"], kw["T"])
     np.testing.assert_array_equal(o16.step_probs(win)[1], o32.step_probs(win)[1])
+
+
+# ---------------------------------------------------------------------------------------------------
+# progressive ablation levels (the paper's component table): which feature vector feeds the head
+# ---------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("level", [1, 2, 3, 4, 5])
+def test_ablation_level_feeds_the_head_from_the_right_stage(level):
+    """The stages up to the cut are those of the full model (whose taps the closed-form tests pin), and the head is a
+    linear layer + softmax, so the truncated model's probabilities can be recomputed by hand from the full model's taps."""
+    rng = np.random.default_rng(31)
+    full, blob, kw = tiny_oracle(std=0.4)
+    randomize_small(blob, rng)
+    full.load_weights(blob.data)
+    cut = orc.Oracle(orc.make_config(ablation=level, **kw))
+    cut.load_weights(blob.data)
+    B, T = kw["B"], kw["T"]
+    f8 = lambda n: blob[n].astype(np.float64)
+    for step in range(T + 1):
+        win = windows_for(rng, B, T)
+        full.step_probs(win)
+        _, p = cut.step_probs(win)
+        for b in range(B):
+            feat = {1: full.tap("H_GLOBAL", b), 2: full.tap("H_MIX", b),
+                    3: full.tap("H_A", b) + f8("lambda_c")[0] * full.tap("H_MIX", b),
+                    4: full.tap("H_COARSE", b), 5: full.tap("H_OUT", b)}[level]
+            logits = feat @ f8("W_o") + f8("b_o")
+            pe = np.exp(logits - logits.max())
+            pe /= pe.sum()
+            np.testing.assert_allclose(p[b], pe.astype(np.float32), rtol=0, atol=1e-7)
+    if level == 1:   # the global stream alone does not see the conv, router or refiner weights
+        other = fi.Blob(B, T, kw["D"], kw["H"], kw["d_low"], kw["cache_chunk"], kw["conv_k"])
+        other.data[...] = blob.data
+        for name in ("W_conv", "W_r", "W_c", "W_fg", "W_f", "W_up"):
+            other[name] = other[name] + 0.5
+        a, b2 = orc.Oracle(orc.make_config(ablation=1, **kw)), orc.Oracle(orc.make_config(ablation=1, **kw))
+        a.load_weights(blob.data); b2.load_weights(other.data)
+        win = windows_for(rng, B, T)
+        np.testing.assert_array_equal(a.step_probs(win)[1], b2.step_probs(win)[1])
+
+
+def test_ablation_levels_are_frozen_only():
+    import ctypes as C
+    L = orc.lib()
+    h = C.c_void_p()
+    assert L.fadeo_create(C.byref(orc.make_config(B=2, T=4, D=4, H=8, ablation=2, update_mode=orc.ONLINE_ADAM)), C.byref(h)) == -2
+    assert L.fadeo_create(C.byref(orc.make_config(B=2, T=4, D=4, H=8, ablation=6)), C.byref(h)) == -2
