@@ -754,22 +754,27 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmArgs g) {
 // Several independent products in ONE launch (a block-uniform switch picks the problem and its kernel body): the products
 // of one backward phase (dX = dY W^T, dW = L^T dY, ...) consume the same gradient and do not depend on each other, and at
 // B = 1024 none of them fills the chip alone.
-__global__ __launch_bounds__(256) void gemm_group_kernel(GemmGroup gg) {
+template <int STAGES>
+__device__ __forceinline__ void group_body(const GemmGroup &gg) {
   int p = 0;
   while (p + 1 < gg.count && (int)blockIdx.x >= gg.first_block[p + 1]) ++p;
   const int local = (int)blockIdx.x - gg.first_block[p], tiles = gg.tiles[p];
   const GemmArgs &g = gg.g[p];
   switch (gg.kind[p]) {
-    case GK_STORE_64x128:   pipe_body<64, 128, 4, EPI_STORE, false>(g, local, 0, 1); break;
-    case GK_STORE_128x128:  pipe_body<128, 128, 4, EPI_STORE, false>(g, local, 0, 1); break;
-    case GK_STORE_64x64:    pipe_body<64, 64, 4, EPI_STORE, false>(g, local, 0, 1); break;
-    case GK_PARTIAL_64x64:  pipe_body<64, 64, 4, EPI_PARTIAL, false>(g, local % tiles, local / tiles, gg.splits[p]); break;
-    case GK_TN_64x128:      tn_body<64, 128, 4>(g, local); break;
-    case GK_TN_128x128:     tn_body<128, 128, 4>(g, local); break;
-    case GK_TN_64x64:       tn_body<64, 64, 4>(g, local); break;
+    case GK_STORE_64x128:   pipe_body<64, 128, STAGES, EPI_STORE, false>(g, local, 0, 1); break;
+    case GK_STORE_128x128:  pipe_body<128, 128, STAGES, EPI_STORE, false>(g, local, 0, 1); break;
+    case GK_STORE_64x64:    pipe_body<64, 64, STAGES, EPI_STORE, false>(g, local, 0, 1); break;
+    case GK_PARTIAL_64x64:  pipe_body<64, 64, STAGES, EPI_PARTIAL, false>(g, local % tiles, local / tiles, gg.splits[p]); break;
+    case GK_TN_64x128:      tn_body<64, 128, STAGES>(g, local); break;
+    case GK_TN_128x128:     tn_body<128, 128, STAGES>(g, local); break;
+    case GK_TN_64x64:       tn_body<64, 64, STAGES>(g, local); break;
     default: break;
   }
 }
+__global__ __launch_bounds__(256) void gemm_group_kernel(GemmGroup gg) { group_body<4>(gg); }
+// The same with two-stage rings and at most 256 registers: two workgroups share a compute unit, so one's pipeline fill and
+// epilogue run under the other's products. For groups with workgroups enough to use that (large batches).
+__global__ __launch_bounds__(256, 2) void gemm_group2_kernel(GemmGroup gg) { group_body<2>(gg); }
 
 
 // ---------------------------------------------------------------------------------------------------
@@ -985,12 +990,15 @@ hipError_t launch_f32(const GemmArgs &g, hipStream_t s) {
 // grouped launches (bf16 path)
 // ---------------------------------------------------------------------------------------------------
 namespace {
-size_t group_kind_lds(int kind) {
+size_t group_kind_lds(int kind, int stages) {  // the larger of the operand ring and the fp32 tile parked for the epilogue
+  size_t ring, tile;
   switch (kind) {
-    case GK_STORE_64x128: case GK_TN_64x128: return 4 * (8192 + 16384);
-    case GK_TN_128x128: case GK_STORE_128x128: return 4 * (16384 + 16384);
-    default: return 4 * (8192 + 8192);  // the 64 x 64 kinds
+    case GK_STORE_64x128: case GK_TN_64x128: ring = 8192 + 16384; tile = 64 * 132 * 4; break;
+    case GK_TN_128x128: case GK_STORE_128x128: ring = 16384 + 16384; tile = 128 * 132 * 4; break;
+    default: ring = 8192 + 8192; tile = 64 * 68 * 4; break;  // the 64 x 64 kinds
   }
+  ring *= (size_t)stages;
+  return ring > tile ? ring : tile;
 }
 }  // namespace
 
@@ -1035,17 +1043,25 @@ hipError_t fade_gemm_group_launch(const GemmGroup &gg, hipStream_t s) {
   static bool attr_done = false;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_group_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * (16384 + 16384));
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_group2_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 132 * 4);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
+  // two workgroups per compute unit pay off once the group has about two workgroups for every unit (400 of them; B = 1024: the gate / router
+  // groups 52 -> 44 us, the small refiner group 18 -> 24 us if forced; B = 4096: 177 -> 139 us)
+  const int tune = fade_gemm_tune();
+  const int stages = (tune == 14 || (tune != 13 && gg.first_block[gg.count] >= 400)) ? 2 : 4;
   size_t lds = 0;
-  for (int p = 0; p < gg.count; ++p) lds = group_kind_lds(gg.kind[p]) > lds ? group_kind_lds(gg.kind[p]) : lds;
-  hipLaunchKernelGGL(gemm_group_kernel, dim3(gg.first_block[gg.count]), dim3(256), lds, s, gg);
+  for (int p = 0; p < gg.count; ++p) lds = group_kind_lds(gg.kind[p], stages) > lds ? group_kind_lds(gg.kind[p], stages) : lds;
+  if (stages == 2) hipLaunchKernelGGL(gemm_group2_kernel, dim3(gg.first_block[gg.count]), dim3(256), lds, s, gg);
+  else hipLaunchKernelGGL(gemm_group_kernel, dim3(gg.first_block[gg.count]), dim3(256), lds, s, gg);
   return hipGetLastError();
 }
 
 // Tuning override for experiments (FADE_GEMM_TUNE: 0 automatic, 1 force 128x128x4 stages, 2 force 64x128, 10 force 256x128x3,
-// 11 force 128x128x2 with two workgroups per compute unit, 12 force 256x256x2 on eight wavefronts).
+// 11 force 128x128x2 with two workgroups per compute unit, 12 force 256x256x2 on eight wavefronts; grouped launches:
+// 13 force the four-stage kernel, 14 force the two-stage one).
 int fade_gemm_tune() {
   static int v = -1;
   if (v < 0) { const char *e = getenv("FADE_GEMM_TUNE"); v = e ? atoi(e) : 0; }
