@@ -27,7 +27,7 @@ sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK = 2.5e15   # MI355X dense bf16, FLOP/s
 HBM_PEAK = 8.0e12         # B/s
-ROUTER_GATE_TRAFFIC_BYTES = {(2, "frozen"): int(0.5 * (466.7 + 66.1 + 457.1 + 66.1) * (1 << 20)), (2, "online"): int(0.5 * (56.3 + 53.8) * (1 << 20))}
+ROUTER_GATE_TRAFFIC_BYTES = {(2, "frozen"): int(0.5 * (346.9 + 55.3 + 345.4 + 55.5) * (1 << 20)), (2, "online"): int(0.5 * (56.3 + 53.8) * (1 << 20))}
 
 
 def parse():
