@@ -386,7 +386,7 @@ bool resolve_dims(const fadeo_config &cfg, Dims &d) {
   else { if (d.Dc % d.T) return false; d.c = d.Dc / d.T; }
   if (d.c == 0 || d.Dc % d.c) return false;
   if (cfg.dtype > FADEO_BF16 || cfg.update_mode > FADEO_ONLINE_ADAM) return false;
-  if (cfg.ablation > 5 || (cfg.ablation >= 1 && cfg.ablation <= 4 && cfg.update_mode != FADEO_FROZEN)) return false;
+  if (cfg.ablation > 5) return false;
   return true;
 }
 
@@ -523,14 +523,23 @@ void backward_stream(fadeo_ctx *C, size_t b, uint8_t target, double scale, doubl
   dvec dlog(256);
   for (int i = 0; i < 256; ++i) dlog[i] = scale * (a.p[i] - (i == (int)target ? 1.0 : 0.0));
 
-  // head
-  outer_acc(a.Hout.data(), dlog.data(), Dh, 256, G(P_WO));
+  // head: its input is the feature vector of the ablation level (forward_stream), and the gradient enters the chain there;
+  // parameters of the stages that are switched off get no gradient
+  const unsigned level = C->cfg.ablation == 0 ? 5u : C->cfg.ablation;
+  const dvec &feat = level >= 5 ? a.Hout : level >= 3 ? a.Hc : level == 2 ? a.Hmix : a.Hg;
+  outer_acc(feat.data(), dlog.data(), Dh, 256, G(P_WO));
   for (int i = 0; i < 256; ++i) G(P_BO)[i] += dlog[i];
   dvec dHout(Dh);
   mat_vec_t(C->P(P_WO), dlog.data(), Dh, 256, dHout.data());
 
+  dvec dHc(Dh, 0.0), dHmix(Dh, 0.0), dHg(Dh, 0.0), dHl(Dh, 0.0), dX(Dh, 0.0), tmp(Dh);
+  if (level == 4 || level == 3) dHc = dHout;
+  if (level == 2) dHmix = dHout;
+  if (level == 1) dHg = dHout;
+
+  if (level >= 5) {
   // Eq. 10
-  dvec dHc(Dh, 0.0), dnv(Dh), dv(Dh, 0.0);
+  dvec dnv(Dh), dv(Dh, 0.0);
   const double lam_o = (double)C->P(P_LAMBDA_O)[0];
   for (size_t i = 0; i < Dh; ++i) {
     dnv[i] = dHout[i] * gelu_grad(a.nv[i]);
@@ -543,7 +552,7 @@ void backward_stream(fadeo_ctx *C, size_t b, uint8_t target, double scale, doubl
   mat_vec_t(C->P(P_WF), dv.data(), d.De, Dh, dHexp.data());
 
   // Eq. 9
-  dvec deg(d.De), dev(d.De), du(Dh), tmp(Dh);
+  dvec deg(d.De), dev(d.De), du(Dh);
   for (size_t i = 0; i < d.De; ++i) {
     deg[i] = dHexp[i] * a.ev[i] * gelu_grad(a.eg[i]);
     dev[i] = dHexp[i] * gelu(a.eg[i]);
@@ -554,19 +563,23 @@ void backward_stream(fadeo_ctx *C, size_t b, uint8_t target, double scale, doubl
   mat_vec_t(C->P(P_WFV), dev.data(), Dh, d.De, tmp.data());
   for (size_t i = 0; i < Dh; ++i) du[i] += tmp[i];
   layer_norm_bwd(du.data(), a.u_hat.data(), a.rstd_f, Dh, C->P(P_GAMMA_F), G(P_GAMMA_F), G(P_BETA_F), dHc.data());
+  }
 
-  // Eq. 8
-  dvec dHa(Dh), dac(Dh), dHmix(Dh, 0.0);
+  if (level >= 3) {
+  // Eq. 8 (level 3: without the gate, H_coarse = H_a + lambda_c H_mix)
+  dvec dHa(Dh), dac(Dh);
   const double lam_c = (double)C->P(P_LAMBDA_C)[0];
   for (size_t i = 0; i < Dh; ++i) {
-    dHa[i] = dHc[i] * a.sg[i];
-    dac[i] = dHc[i] * a.Ha[i] * a.sg[i] * (1.0 - a.sg[i]);
+    dHa[i] = level >= 4 ? dHc[i] * a.sg[i] : dHc[i];
+    dac[i] = level >= 4 ? dHc[i] * a.Ha[i] * a.sg[i] * (1.0 - a.sg[i]) : 0.0;
     G(P_LAMBDA_C)[0] += dHc[i] * a.Hmix[i];
     dHmix[i] += lam_c * dHc[i];
   }
-  outer_acc(a.Hmix.data(), dac.data(), Dh, Dh, G(P_WC));
-  mat_vec_t(C->P(P_WC), dac.data(), Dh, Dh, tmp.data());
-  for (size_t i = 0; i < Dh; ++i) dHmix[i] += tmp[i];
+  if (level >= 4) {
+    outer_acc(a.Hmix.data(), dac.data(), Dh, Dh, G(P_WC));
+    mat_vec_t(C->P(P_WC), dac.data(), Dh, Dh, tmp.data());
+    for (size_t i = 0; i < Dh; ++i) dHmix[i] += tmp[i];
+  }
 
   // Eq. 7
   dvec dz(d.dl), dy(d.dl), dnc(Dh);
@@ -577,9 +590,12 @@ void backward_stream(fadeo_ctx *C, size_t b, uint8_t target, double scale, doubl
   outer_acc(a.nc.data(), dy.data(), Dh, d.dl, G(P_WDOWN));
   mat_vec_t(C->P(P_WDOWN), dy.data(), Dh, d.dl, dnc.data());
   layer_norm_bwd(dnc.data(), a.nc_hat.data(), a.rstd_c, Dh, C->P(P_GAMMA_C), G(P_GAMMA_C), G(P_BETA_C), dHmix.data());
+  }
 
+  dvec dxl(Dh, 0.0);
+  if (level >= 2) {
   // Eq. 5-6
-  dvec dHg(Dh), dHl(Dh), dar(Dh), dX(Dh);
+  dvec dar(Dh);
   for (size_t i = 0; i < Dh; ++i) {
     dHg[i] = dHmix[i] * a.alpha[i];
     dHl[i] = dHmix[i] * (1.0 - a.alpha[i]);
@@ -589,7 +605,7 @@ void backward_stream(fadeo_ctx *C, size_t b, uint8_t target, double scale, doubl
   mat_vec_t(C->P(P_WR), dar.data(), Dh, Dh, dX.data());
 
   // Eq. 4
-  dvec dxl(Dh, 0.0), dcv(D);
+  dvec dcv(D);
   for (size_t j = 0; j < T; ++j) {
     for (size_t o = 0; o < D; ++o) {
       dcv[o] = dHl[j * D + o] * gelu_grad(a.cv[j * D + o]);
@@ -610,6 +626,7 @@ void backward_stream(fadeo_ctx *C, size_t b, uint8_t target, double scale, doubl
         dxl[(size_t)src * D + i] += acc;
       }
     }
+  }
   }
 
   // Eq. 3

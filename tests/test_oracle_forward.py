@@ -409,9 +409,8 @@ def test_ablation_level_feeds_the_head_from_the_right_stage(level):
         np.testing.assert_array_equal(a.step_probs(win)[1], b2.step_probs(win)[1])
 
 
-def test_ablation_levels_are_frozen_only():
+def test_ablation_level_out_of_range_is_refused():
     import ctypes as C
     L = orc.lib()
     h = C.c_void_p()
-    assert L.fadeo_create(C.byref(orc.make_config(B=2, T=4, D=4, H=8, ablation=2, update_mode=orc.ONLINE_ADAM)), C.byref(h)) == -2
     assert L.fadeo_create(C.byref(orc.make_config(B=2, T=4, D=4, H=8, ablation=6)), C.byref(h)) == -2

@@ -16,7 +16,9 @@ def _loss_at(o, data, win, tgt, active, warm):
     return o.loss(tgt, active)
 
 
-@pytest.mark.parametrize("active,widths", [(None, {}), (np.array([1, 0, 1], np.uint8), {}), (None, SPLIT_WIDTHS)])
+@pytest.mark.parametrize("active,widths", [(None, {}), (np.array([1, 0, 1], np.uint8), {}), (None, SPLIT_WIDTHS),
+                                           (None, dict(ablation=1)), (None, dict(ablation=2)), (None, dict(ablation=3)),
+                                           (np.array([1, 0, 1], np.uint8), dict(ablation=4))])
 def test_gradient_matches_finite_differences(active, widths):
     rng = np.random.default_rng(21)
     o, blob, kw = tiny_oracle(std=0.4, **widths)
@@ -72,7 +74,7 @@ def _fd_loss(o, data, blob, name, win, tgt, active, warm):
 
 def _final_step_with(o, data, win, tgt, active):
     kw = dict(B=o.cfg.B, T=o.cfg.T, D=o.cfg.D, H=o.cfg.H, d_low=o.cfg.d_low, cache_chunk=o.cfg.cache_chunk,
-              conv_k=o.cfg.conv_k, d_cache=o.cfg.d_cache, d_e=o.cfg.d_e)
+              conv_k=o.cfg.conv_k, d_cache=o.cfg.d_cache, d_e=o.cfg.d_e, ablation=o.cfg.ablation)
     B = kw["B"]
     caches = [o.tap("CACHE", b) for b in range(B)]
     c = kw["cache_chunk"]
