@@ -38,7 +38,7 @@ def parse():
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration (1-5; 6 = the paper-default model shape)")
     ap.add_argument("--mode", choices=["frozen", "online"], default=None)
     ap.add_argument("--ablation", type=int, default=0, choices=[0, 1, 2, 3, 4, 5],
-                    help="head on a prefix of the model (the paper's progressive ablation; 1-4: frozen weights only)")
+                    help="head on a prefix of the model (the paper's progressive ablation)")
     ap.add_argument("--full", action="store_true", help="run the whole job (all L steps) instead of K timed steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -75,7 +75,6 @@ def main():
     dtype = fa.BF16 if spec["dtype"] == "bf16" else fa.F32
     mode = a.mode or "online"   # the method adapts its weights while coding (Algorithm 1); frozen is the inference-only variant
     if 1 <= a.ablation <= 4:
-        mode = "frozen"
         widths["ablation"] = a.ablation
     K, W = a.steps, a.warmup
 
@@ -187,7 +186,7 @@ def main():
     fwd_flop = 2 * (2 * D * (Dc // T) + Dc * Dh + 256 * Dh + (T * 3 * D * D + Dh * Dh if lvl >= 2 else 0)
                     + (2 * Dh * dl + dl * dl if lvl >= 3 else 0) + (Dh * Dh if lvl >= 4 else 0) + (3 * De * Dh if lvl >= 5 else 0))
     other = None
-    if a.mode is None and not a.full and not 1 <= a.ablation <= 4:  # default run: the inference-only variant (frozen weights) of the same steps beside the headline
+    if a.mode is None and not a.full:  # default run: the inference-only variant (frozen weights) of the same steps beside the headline
         f = measure("frozen")
         other = {"update_mode": "frozen", "compress_MBps": round(f["enc_MBps"], 3), "decompress_MBps": round(f["dec_MBps"], 3),
                  "ms_per_step": round(1e3 * f["t_enc"] / f["steps_timed"], 5), "round_trip_exact": f["ok"],

@@ -65,8 +65,7 @@ int resolve_dims(const fade_config &cfg, Dims &d, std::string *why) {
 int check_kernel_limits(const fade_config &cfg, const Dims &d, std::string *why) {
   auto bad = [&](const char *m) { if (why) *why = m; return FADE_E_BAD_CONFIG; };
   if (d.dl != 64) return bad("kernels need d_low == 64");
-  if (cfg.ablation >= 1 && cfg.ablation <= 4 && (cfg.dtype != FADE_BF16 || cfg.update_mode != FADE_FROZEN))
-    return bad("ablation levels 1-4 are built for the bf16 path with frozen weights only");
+  if (cfg.ablation >= 1 && cfg.ablation <= 4 && cfg.dtype != FADE_BF16) return bad("ablation levels 1-4 are built for the bf16 path only");
   if (d.Dh % 128) return bad("kernels need T*D to be a multiple of 128");
   if (d.Dc % 64 || d.Dc > 4096) return bad("kernels need D_cache to be a multiple of 64, at most 4096");
   if (d.De % 64 || d.De > 8192) return bad("kernels need D_e to be a multiple of 64, at most 8192");
@@ -662,6 +661,11 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
   const int RB = (B + fade_rows_per_block() - 1) / fade_rows_per_block();
   ReduceBatch rq{};  // second-stage reductions nothing in here waits for: one launch before Adam
   int rc;
+  // ablation level: the head's gradient enters the chain at the level's feature vector; the stages behind it do not run
+  // and their parameters keep a zero gradient (their Adam step is then exactly zero)
+  const int level = c->cfg.ablation == 0 ? 5 : (int)c->cfg.ablation;
+  const void *feat = level >= 5 ? c->Hout : level >= 3 ? c->Hc : level == 2 ? c->Hmix : c->Hg;
+  void *dfeat = level >= 5 ? c->dHout : level >= 3 ? c->dHc : c->dHmix1;
   {
     Prof p(c, "bwd_prep_dlogits");
     HIP_TRY(c, fade_loss_grad(ws, targets, tstride, B, c->probs_buf, c->ustate, c->cfg.beta1, c->cfg.beta2, c->dl, c->col_part, Gp(P_BO), bf, rq, s));
@@ -669,10 +673,10 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
   if (bf) {  // the two left operands the forward pass never stores: LN(H_coarse), LN(H_mix), row-major
     Prof p(c, "ln_apply", w);
     LnApplyBatch lb{};
-    lb.count = 2; lb.B = B; lb.Dh = Dh; lb.stats_n = SN;
-    lb.a[0] = {c->Hc, c->LT[2], c->stats_f, c->P(P_GAMMA_F), c->P(P_BETA_F)};
-    lb.a[1] = {c->Hmix, c->LT[5], c->stats_c, c->P(P_GAMMA_C), c->P(P_BETA_C)};
-    HIP_TRY(c, fade_ln_apply(lb, true, w));
+    lb.B = B; lb.Dh = Dh; lb.stats_n = SN;
+    if (level >= 5) lb.a[lb.count++] = {c->Hc, c->LT[2], c->stats_f, c->P(P_GAMMA_F), c->P(P_BETA_F)};
+    if (level >= 3) lb.a[lb.count++] = {c->Hmix, c->LT[5], c->stats_c, c->P(P_GAMMA_C), c->P(P_BETA_C)};
+    if (lb.count) HIP_TRY(c, fade_ln_apply(lb, true, w));
   } else {  // fp32 path: feature-major copies of every forward activation that is the left operand of a weight gradient
     Prof p(c, "transpose", w);
     TransposeBatch tb{};
@@ -693,10 +697,11 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
   // head
   {
     PhaseGemms ph;
-    ph.add(GEMM_W_TN, args_w(c, c->Hout, Dh, c->LT[0], Dh, c->dl, 256, Gp(P_WO), nullptr));
-    ph.add(GEMM_X_STORE, args_x(c, c->dl, 256, Dh, c->WT_o, c->P(P_WO), 256, c->dHout));
+    ph.add(GEMM_W_TN, args_w(c, feat, Dh, c->LT[0], Dh, c->dl, 256, Gp(P_WO), nullptr));
+    ph.add(GEMM_X_STORE, args_x(c, c->dl, 256, Dh, c->WT_o, c->P(P_WO), 256, dfeat));
     if ((rc = run_phase(c, "gemms_head", ph))) return rc;
   }
+  if (level >= 5) {
   {  // Eq. 10
     Prof p(c, "bwd_out");
     BwdOutArgs a{};
@@ -721,19 +726,24 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     ph.add(GEMM_X_STORE, args_x(c, c->dE, 2 * De, Dh, c->WT_fgv, static_cast<const float *>(c->Wfgv_c), 2 * De, c->du));
     if ((rc = run_phase(c, "gemms_fnr_in", ph))) return rc;
   }
+  }
+  if (level >= 3) {
   {  // LN of Eq. 9 + Eq. 8
     Prof p(c, "bwd_gate");
     BwdGateArgs a{};
-    a.B = B; a.Dh = Dh; a.stats_n = SN; a.ln_part = c->ln_part + (size_t)RB * 2 * Dh; a.du = c->du; a.Hc = c->Hc; a.dHc = c->dHc; a.sg = c->sg; a.Ha = c->Ha; a.Hmix = c->Hmix;
+    a.B = B; a.Dh = Dh; a.stats_n = SN; a.ln_part = c->ln_part + (size_t)RB * 2 * Dh; a.du = level >= 5 ? c->du : nullptr; a.Hc = c->Hc; a.dHc = c->dHc;
+    a.sg = level >= 4 ? c->sg : nullptr; a.Ha = c->Ha; a.Hmix = c->Hmix;
     a.stats = c->stats_f; a.gamma = c->P(P_GAMMA_F); a.lam = c->P(P_LAMBDA_C); a.dHa = c->dHa; a.dac = c->dac; a.dHmix = c->dHmix1;
     a.row_dlam = c->row_dlam + B;
     HIP_TRY(c, fade_bwd_gate(a, bf, s));
-    rq.push(RB, 2 * Dh, c->ln_part + (size_t)RB * 2 * Dh, Gp(P_GAMMA_F));
+    if (level >= 5) rq.push(RB, 2 * Dh, c->ln_part + (size_t)RB * 2 * Dh, Gp(P_GAMMA_F));
   }
   {  // Eq. 8's gate product and Eq. 7's Up
     PhaseGemms ph;
-    ph.add(GEMM_W_TN, args_w(c, c->Hmix, Dh, c->LT[3], Dh, c->dac, Dh, Gp(P_WC), nullptr));
-    ph.add(GEMM_X_STORE, args_x(c, c->dac, Dh, Dh, c->WT_c, c->P(P_WC), Dh, c->dHmix2));
+    if (level >= 4) {
+      ph.add(GEMM_W_TN, args_w(c, c->Hmix, Dh, c->LT[3], Dh, c->dac, Dh, Gp(P_WC), nullptr));
+      ph.add(GEMM_X_STORE, args_x(c, c->dac, Dh, Dh, c->WT_c, c->P(P_WC), Dh, c->dHmix2));
+    }
     ph.add(GEMM_W_TN, args_w(c, c->z, dl, c->LT[4], dl, c->dHa, Dh, Gp(P_WUP), nullptr));
     GemmArgs g{};
     g.M = B; g.N = dl; g.K = Dh; g.splits = c->sp_dz; g.A = c->dHa; g.lda = Dh; g.C = c->dz_part; g.ldc = dl;
@@ -757,22 +767,26 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     ph.add(GEMM_X_STORE, args_x(c, c->dy_at, dl, Dh, c->WT_down, c->P(P_WDOWN), dl, c->dnc));
     if ((rc = run_phase(c, "gemms_down", ph))) return rc;
   }
+  }
   {  // LN of Eq. 7 + Eq. 5-6 + branch activations
     Prof p(c, "bwd_mix");
     BwdMixArgs a{};
-    a.B = B; a.Dh = Dh; a.stats_n = SN; a.ln_part = c->ln_part + (size_t)RB * 4 * Dh; a.dnc = c->dnc; a.Hmix = c->Hmix; a.dHmix1 = c->dHmix1; a.dHmix2 = c->dHmix2; a.alpha = c->alpha;
+    a.B = B; a.Dh = Dh; a.stats_n = SN; a.ln_part = c->ln_part + (size_t)RB * 4 * Dh; a.dnc = level >= 3 ? c->dnc : nullptr; a.Hmix = c->Hmix; a.dHmix1 = c->dHmix1;
+    a.dHmix2 = level >= 4 ? c->dHmix2 : nullptr; a.alpha = level >= 2 ? c->alpha : nullptr;
     a.Hg = c->Hg; a.Hl = c->Hl; a.hm = c->hm; a.cv = c->cv; a.X = c->X; a.stats = c->stats_c; a.gamma = c->P(P_GAMMA_C);
     a.lam = c->P(P_LAMBDA_M); a.dar = c->dar; a.dhm = c->dhm; a.dcv = c->dcv; a.dX = c->dX1; a.row_dlam = c->row_dlam + 2 * B;
     HIP_TRY(c, fade_bwd_mix(a, bf, s));
-    rq.push(RB, 2 * Dh, c->ln_part + (size_t)RB * 4 * Dh, Gp(P_GAMMA_C));
-    rq.push(B, 1, c->row_dlam, Gp(P_LAMBDA_O));  // the three residual scales: per-stream terms, one column each
-    rq.push(B, 1, c->row_dlam + B, Gp(P_LAMBDA_C));
+    if (level >= 3) rq.push(RB, 2 * Dh, c->ln_part + (size_t)RB * 4 * Dh, Gp(P_GAMMA_C));
+    if (level >= 5) rq.push(B, 1, c->row_dlam, Gp(P_LAMBDA_O));  // the three residual scales: per-stream terms, one column each
+    if (level >= 3) rq.push(B, 1, c->row_dlam + B, Gp(P_LAMBDA_C));
     rq.push(B, 1, c->row_dlam + 2 * B, Gp(P_LAMBDA_M));
   }
   {  // router and global stream
     PhaseGemms ph;
-    ph.add(GEMM_W_TN, args_w(c, c->X, Dh, c->LT[7], Dh, c->dar, Dh, Gp(P_WR), nullptr));
-    ph.add(GEMM_X_STORE, args_x(c, c->dar, Dh, Dh, c->WT_r, c->P(P_WR), Dh, c->dX2));
+    if (level >= 2) {
+      ph.add(GEMM_W_TN, args_w(c, c->X, Dh, c->LT[7], Dh, c->dar, Dh, Gp(P_WR), nullptr));
+      ph.add(GEMM_X_STORE, args_x(c, c->dar, Dh, Dh, c->WT_r, c->P(P_WR), Dh, c->dX2));
+    }
     ph.add(GEMM_W_TN, args_w(c, c->M, (int)d.Dc, c->LT[6], (int)d.Dc, c->dhm, Dh, Gp(P_WM), nullptr));
     if ((rc = run_phase(c, "gemms_router_global", ph))) return rc;
   }
@@ -789,7 +803,7 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     a.ws = ws; a.B = B; a.T = (int)d.T; a.tabXe32 = c->tabXe32; a.part = c->slot_part;
     HIP_TRY(c, fade_bwd_slot(a, Gp(P_WG), bf, rq, s));
   }
-  {  // local stream
+  if (level >= 2) {  // local stream
     Prof p(c, "bwd_conv");
     ConvGradArgs a{};
     a.B = B; a.T = (int)d.T; a.D = (int)d.D; a.taps = (int)d.k; a.XL = c->XL; a.dcv = c->dcv; a.part = c->conv_part;

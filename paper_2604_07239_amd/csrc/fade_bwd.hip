@@ -353,6 +353,7 @@ __global__ __launch_bounds__(256) void bwd_geglu_kernel(int B, int De, const AT 
 
 // LN (Eq. 9) backward into dH_coarse, then Eq. 8 backward element-wise:
 // dH_a = dHc * s, d(gate logits) = dHc * H_a * s (1 - s), dH_mix = lambda_c dHc, row part of d lambda_c.
+// Ablation levels: a.du == NULL: no refiner behind H_coarse, dHc arrives complete; a.sg == NULL: Eq. 8 without its gate.
 template <typename AT>
 __global__ __launch_bounds__(256) void bwd_gate_kernel(BwdGateArgs a) {
   constexpr int R = kRowsPerBlock;
@@ -376,7 +377,9 @@ __global__ __launch_bounds__(256) void bwd_gate_kernel(BwdGateArgs a) {
       moments(a.stats + (size_t)b * a.stats_n * 2, a.stats_n, a.Dh, mean, rstd[r]);
       const size_t base = (size_t)b * a.Dh + tid * 8;
       float du[8], hc[8];
-      ld8<AT>(static_cast<const AT *>(a.du) + base, du);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) du[i] = 0.0f;
+      if (a.du) ld8<AT>(static_cast<const AT *>(a.du) + base, du);
       ld8<AT>(static_cast<const AT *>(a.Hc) + base, hc);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
@@ -400,7 +403,9 @@ __global__ __launch_bounds__(256) void bwd_gate_kernel(BwdGateArgs a) {
       const float m1 = sums[r] / (float)a.Dh, m2 = sums[R + r] / (float)a.Dh;
       float dhc[8], sg[8], ha[8], hm[8], dHa[8], dac[8], dmix[8];
       ld8<AT>(static_cast<const AT *>(a.dHc) + base, dhc);
-      ld8<AT>(static_cast<const AT *>(a.sg) + base, sg);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) sg[i] = 1.0f;
+      if (a.sg) ld8<AT>(static_cast<const AT *>(a.sg) + base, sg);
       ld8<AT>(static_cast<const AT *>(a.Ha) + base, ha);
       ld8<AT>(static_cast<const AT *>(a.Hmix) + base, hm);
 #pragma unroll
@@ -412,7 +417,7 @@ __global__ __launch_bounds__(256) void bwd_gate_kernel(BwdGateArgs a) {
         sl[r] += d * hm[i];
       }
       st8<AT>(static_cast<AT *>(a.dHa) + base, dHa);
-      st8<AT>(static_cast<AT *>(a.dac) + base, dac);
+      if (a.sg) st8<AT>(static_cast<AT *>(a.dac) + base, dac);
       st8<AT>(static_cast<AT *>(a.dHmix) + base, dmix);
     }
   }
@@ -432,6 +437,8 @@ __global__ __launch_bounds__(256) void bwd_gate_kernel(BwdGateArgs a) {
 // LN (Eq. 7) backward into dH_mix (+ the gate path's contribution), then Eq. 5-6 and the branch activations:
 // dHg = dmix a, dHl = dmix (1-a), d(router logits) = dmix (Hg - Hl) a (1-a), d(global pre-act) = dHg psi'(hm),
 // d(conv pre-act) = dHl psi'(cv), dX = lambda_m dHg, row part of d lambda_m.
+// Ablation levels: a.dnc == NULL: nothing behind H_mix but what dHmix1 (+ dHmix2) carry; a.dHmix2 == NULL: no gate product;
+// a.alpha == NULL: the global stream alone (alpha = 1: no local stream, no router), dar / dcv are not written.
 template <typename AT>
 __global__ __launch_bounds__(256) void bwd_mix_kernel(BwdMixArgs a) {
   constexpr int R = kRowsPerBlock;
@@ -455,8 +462,12 @@ __global__ __launch_bounds__(256) void bwd_mix_kernel(BwdMixArgs a) {
       moments(a.stats + (size_t)b * a.stats_n * 2, a.stats_n, a.Dh, mean, rstd[r]);
       const size_t base = (size_t)b * a.Dh + tid * 8;
       float dn[8], hm[8];
-      ld8<AT>(static_cast<const AT *>(a.dnc) + base, dn);
-      ld8<AT>(static_cast<const AT *>(a.Hmix) + base, hm);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { dn[i] = 0.0f; hm[i] = 0.0f; }
+      if (a.dnc) {
+        ld8<AT>(static_cast<const AT *>(a.dnc) + base, dn);
+        ld8<AT>(static_cast<const AT *>(a.Hmix) + base, hm);
+      }
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         xh[r][i] = (hm[i] - mean) * rstd[r];
@@ -479,12 +490,16 @@ __global__ __launch_bounds__(256) void bwd_mix_kernel(BwdMixArgs a) {
       const float m1 = sums[r] / (float)a.Dh, m2 = sums[R + r] / (float)a.Dh;
       float d1[8], d2[8], al[8], hg[8], hl[8], pre_g[8], pre_c[8], x[8], dar[8], dhm[8], dcv[8], dX[8];
       ld8<AT>(static_cast<const AT *>(a.dHmix1) + base, d1);
-      ld8<AT>(static_cast<const AT *>(a.dHmix2) + base, d2);
-      ld8<AT>(static_cast<const AT *>(a.alpha) + base, al);
-      ld8<AT>(static_cast<const AT *>(a.Hg) + base, hg);
-      ld8<AT>(static_cast<const AT *>(a.Hl) + base, hl);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { d2[i] = 0.0f; al[i] = 1.0f; hg[i] = 0.0f; hl[i] = 0.0f; pre_c[i] = 0.0f; }
+      if (a.dHmix2) ld8<AT>(static_cast<const AT *>(a.dHmix2) + base, d2);
+      if (a.alpha) {
+        ld8<AT>(static_cast<const AT *>(a.alpha) + base, al);
+        ld8<AT>(static_cast<const AT *>(a.Hg) + base, hg);
+        ld8<AT>(static_cast<const AT *>(a.Hl) + base, hl);
+        ld8<AT>(static_cast<const AT *>(a.cv) + base, pre_c);
+      }
       ld8<AT>(static_cast<const AT *>(a.hm) + base, pre_g);
-      ld8<AT>(static_cast<const AT *>(a.cv) + base, pre_c);
       ld8<AT>(static_cast<const AT *>(a.X) + base, x);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
@@ -496,9 +511,11 @@ __global__ __launch_bounds__(256) void bwd_mix_kernel(BwdMixArgs a) {
         dX[i] = lam * dHg;
         sl[r] += dHg * x[i];
       }
-      st8<AT>(static_cast<AT *>(a.dar) + base, dar);
+      if (a.alpha) {
+        st8<AT>(static_cast<AT *>(a.dar) + base, dar);
+        st8<AT>(static_cast<AT *>(a.dcv) + base, dcv);
+      }
       st8<AT>(static_cast<AT *>(a.dhm) + base, dhm);
-      st8<AT>(static_cast<AT *>(a.dcv) + base, dcv);
       st8<AT>(static_cast<AT *>(a.dX) + base, dX);
     }
   }

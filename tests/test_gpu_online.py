@@ -99,6 +99,26 @@ def test_online_gradients_refiner_product_without_split_k():
     _grad_check("bf16", 130, 16, 32, 64, seed=11, tol=3e-2, d_cache=1024, d_e=8192)
 
 
+@pytest.mark.parametrize("level", [1, 2, 3, 4])
+def test_online_gradients_ablation_levels(level):
+    """The update with the head on a prefix of the model: the gradient enters at that stage, later stages get none."""
+    # 5e-2: the second step starts from states that already differ by Adam's sign-like first step on W_U, which the small
+    # W_down gradient of the truncated models feels most (4 % on one seed; first-step gradients agree within 1 %)
+    _grad_check("bf16", 37, 8, 32, 64, seed=30 + level, tol=5e-2, ablation=level)
+
+
+@pytest.mark.parametrize("level", [1, 3])
+def test_online_round_trip_ablation_levels(level):
+    need_gpu()
+    B, n = 33, 33 * 50 + 4
+    g, o, _ = make_pair(B, 8, 32, 64, "bf16", seed=8, update_mode=1, std=0.05, lr=2e-3, ablation=level)
+    src = fi.genome(6, n)
+    c = g.encode(src)
+    np.testing.assert_array_equal(g.decode(c, n), src)
+    co = o.encode(src)
+    assert abs(c.size - co.size) <= 0.005 * co.size + B
+
+
 def test_online_gradients_widest_cache_slots():
     """Cache slots of 256 (D_cache = 4096 at T = 16, the paper-default cache): the slot backward walks them 64 at a time."""
     _grad_check("bf16", 9, 16, 32, 64, seed=9, tol=3e-2, d_cache=4096, d_e=256)

@@ -199,7 +199,6 @@ def test_ablation_round_trip_and_multi_step_identity(monkeypatch):
         sizes[level] = outs[0].size
     import ctypes as C
     h = C.c_void_p()
-    assert fa.lib().fade_create(C.byref(fa.make_config(B, T, D, H, dtype=fa.BF16, ablation=2, update_mode=fa.ONLINE_ADAM)), C.byref(h)) == -2
     assert fa.lib().fade_create(C.byref(fa.make_config(B, T, 16, H, dtype=fa.F32, ablation=2)), C.byref(h)) == -2
 
 
