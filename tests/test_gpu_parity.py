@@ -378,6 +378,18 @@ def test_multi_step_encode_config2_full_batch():
             np.testing.assert_array_equal(g.decode(outs[-1], src.size), src)
         g.close()
     assert outs[0].tobytes() == outs[1].tobytes()
+    # sampled (full-length) streams against the oracle, which codes them alone (frozen streams are independent):
+    # the payload lengths agree
+    idx = np.array([0, 1, 511, 1000])
+    sub = fi.Blob(len(idx), T, D, H)
+    for name, _, _ in sub.specs:
+        sub[name] = blob[name][idx] if name == "W_U" else blob[name]
+    o = orc.Oracle(orc.make_config(len(idx), T, D, H, dtype=orc.BF16))
+    o.load_weights(sub.data)
+    co = o.encode(np.concatenate([src[i * L:(i + 1) * L] for i in idx]))
+    lens_g = np.frombuffer(outs[1][64:64 + 4 * B].tobytes(), np.uint32)[idx].astype(np.int64)
+    lens_o = np.frombuffer(co[64:64 + 4 * len(idx)].tobytes(), np.uint32).astype(np.int64)
+    assert np.all(np.abs(lens_g - lens_o) <= 1 + 0.005 * lens_o), (lens_g, lens_o)
 
 
 def test_round_trip_separate_cache_and_refiner_widths():
