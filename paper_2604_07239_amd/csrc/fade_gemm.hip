@@ -131,18 +131,60 @@ __device__ __forceinline__ void row_moments(const GemmArgs &g, int m, float &mea
 // ---------------------------------------------------------------------------------------------------
 // epilogue: the accumulator tile sits in LDS as fp32 [BM][BN + 4]; threads walk it in 8-wide row chunks
 // ---------------------------------------------------------------------------------------------------
-template <int EPI, typename AT, int BM, int BN, int LDC = BN + 4, int NT = 256>
-__device__ __forceinline__ void epilogue(const GemmArgs &g, const float *Cs, int m0, int n0, int nt, int tid, int split = 0) {
+// Side inputs an epilogue reads beside the accumulator: 2 for the mix and gate forms, 1 for the global projection.
+template <int EPI> struct EpiSides { static constexpr int n = (EPI == EPI_MIX || EPI == EPI_GATE) ? 2 : (EPI == EPI_GLOBAL ? 1 : 0); };
+
+// Issue the global loads of one 8-wide chunk of the side inputs (element offset o); the values stay raw until used.
+template <int EPI, typename AT>
+__device__ __forceinline__ void epi_side_load(const GemmArgs &g, size_t o, bool live, Raw8<AT> *sd) {
+  if (!live) return;
+  if (EpiSides<EPI>::n >= 1) raw_load(sd[0], static_cast<const AT *>(g.S1) + o);
+  if (EpiSides<EPI>::n >= 2) raw_load(sd[1], static_cast<const AT *>(g.S2) + o);
+}
+
+// A thread walks rows r0, r0 + RP, ... of its 8-wide column chunk. The side inputs (and the row moments of the folded
+// form) of U consecutive passes are requested together before the first of them is used, so that one memory latency
+// covers U rows; with PRE the caller has requested them even earlier (`pre`: [pass][input], all BM / RP passes).
+template <int EPI, typename AT, int BM, int BN, int LDC = BN + 4, int NT = 256, bool PRE = false>
+__device__ __forceinline__ void epilogue(const GemmArgs &g, const float *Cs, int m0, int n0, int nt, int tid, int split = 0,
+                                         const Raw8<AT> (*pre)[2] = nullptr) {
   constexpr bool kGeglu = EPI == EPI_GEGLU || EPI == EPI_GEGLU_FOLD;
   constexpr int BNO = kGeglu ? BN / 2 : BN;  // output columns of this tile
   constexpr int CH = BNO / 8;                            // chunks (threads) per row
   constexpr int RP = NT / CH;                            // rows per pass
+  constexpr int PASSES = (BM + RP - 1) / RP;
+  constexpr int NS = EpiSides<EPI>::n;
+  constexpr bool kAhead = NS > 0 || EPI == EPI_GEGLU_FOLD;
+  constexpr int U = PRE ? PASSES : (kAhead ? (PASSES < 4 ? PASSES : 4) : 1);
+  constexpr bool kRagged = BM % (RP * U) != 0;  // a tile shorter than one round of passes: some threads own no row
+  static_assert(PASSES % U == 0 && !(PRE && kRagged), "row passes");
   const int c8 = (tid % CH) * 8, r0 = tid / CH;
   const int nout0 = kGeglu ? nt * BNO : n0;  // first output column of the tile
   float lam = 0.0f;
   if (EPI == EPI_GLOBAL || EPI == EPI_GATE) lam = g.lam[0];
+  float sg[8], tg[8], sv[8], tv[8];
+  if (EPI == EPI_GEGLU_FOLD) {
+    load8(g.fold_s + n0 + c8, sg); load8(g.fold_t + n0 + c8, tg);
+    load8(g.fold_s + n0 + BNO + c8, sv); load8(g.fold_t + n0 + BNO + c8, tv);
+  }
 #pragma unroll 1
-  for (int r = r0; r < BM; r += RP) {
+  for (int rb = r0; rb < BM; rb += RP * U) {
+    Raw8<AT> own[PRE ? 1 : U][2];
+    float mean[U], rstd[U];
+    if (!PRE) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int m = m0 + rb + u * RP;
+        if (kRagged && rb + u * RP >= BM) continue;
+        epi_side_load<EPI, AT>(g, (size_t)m * g.ldc + nout0 + c8, m < g.M, own[u]);
+        if (EPI == EPI_GEGLU_FOLD) row_moments(g, m, mean[u], rstd[u]);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+    const Raw8<AT> *sd = PRE ? pre[u] : own[u];
+    const int r = rb + u * RP;
+    if (kRagged && r >= BM) continue;
     const int m = m0 + r;
     const bool live = m < g.M;
     float x[8], out[8];
@@ -161,27 +203,27 @@ __device__ __forceinline__ void epilogue(const GemmArgs &g, const float *Cs, int
         store8(static_cast<float *>(g.C) + o, out);
       } else if (EPI == EPI_GLOBAL) {
         float s1[8];
-        load8(static_cast<const AT *>(g.S1) + o, s1);
+        raw_to_float(sd[0], s1);
 #pragma unroll
         for (int i = 0; i < 8; ++i) out[i] = gelu_f(x[i]) + lam * s1[i];
         store8(static_cast<AT *>(g.C) + o, out);
         if (g.C2) store8(static_cast<AT *>(g.C2) + o, x);
       } else if (EPI == EPI_MIX) {
         float s1[8], s2[8], al[8];
-        load8(static_cast<const AT *>(g.S1) + o, s1);
-        load8(static_cast<const AT *>(g.S2) + o, s2);
+        raw_to_float(sd[0], s1);
+        raw_to_float(sd[1], s2);
 #pragma unroll
         for (int i = 0; i < 8; ++i) { al[i] = sigmoid_f(x[i]); out[i] = al[i] * s1[i] + (1.0f - al[i]) * s2[i]; }
         store8(static_cast<AT *>(g.C) + o, out);
         if (g.C2) store8(static_cast<AT *>(g.C2) + o, al);
       } else if (EPI == EPI_GATE) {
-        float s1[8], s2[8], sg[8];
-        load8(static_cast<const AT *>(g.S1) + o, s1);
-        load8(static_cast<const AT *>(g.S2) + o, s2);
+        float s1[8], s2[8], sgm[8];
+        raw_to_float(sd[0], s1);
+        raw_to_float(sd[1], s2);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) { sg[i] = sigmoid_f(x[i]); out[i] = s1[i] * sg[i] + lam * s2[i]; }
+        for (int i = 0; i < 8; ++i) { sgm[i] = sigmoid_f(x[i]); out[i] = s1[i] * sgm[i] + lam * s2[i]; }
         store8(static_cast<AT *>(g.C) + o, out);
-        if (g.C2) store8(static_cast<AT *>(g.C2) + o, sg);
+        if (g.C2) store8(static_cast<AT *>(g.C2) + o, sgm);
       } else if (EPI == EPI_GEGLU) {
         float xv[8];
         load8(Cs + r * LDC + BNO + c8, xv);
@@ -191,15 +233,12 @@ __device__ __forceinline__ void epilogue(const GemmArgs &g, const float *Cs, int
         if (g.C2) store8(static_cast<AT *>(g.C2) + o, x);
         if (g.C3) store8(static_cast<AT *>(g.C3) + o, xv);
       } else if (EPI == EPI_GEGLU_FOLD) {
-        float xv[8], sg[8], tg[8], sv[8], tv[8], eg[8], ev[8], mean, rstd;
+        float xv[8], eg[8], ev[8];
         load8(Cs + r * LDC + BNO + c8, xv);
-        load8(g.fold_s + n0 + c8, sg); load8(g.fold_t + n0 + c8, tg);
-        load8(g.fold_s + n0 + BNO + c8, sv); load8(g.fold_t + n0 + BNO + c8, tv);
-        row_moments(g, m, mean, rstd);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-          eg[i] = fade_fold_ln(x[i], mean, rstd, sg[i], tg[i]);
-          ev[i] = fade_fold_ln(xv[i], mean, rstd, sv[i], tv[i]);
+          eg[i] = fade_fold_ln(x[i], mean[u], rstd[u], sg[i], tg[i]);
+          ev[i] = fade_fold_ln(xv[i], mean[u], rstd[u], sv[i], tv[i]);
           out[i] = gelu_f(eg[i]) * ev[i];
         }
         store8(static_cast<AT *>(g.C) + o, out);
@@ -216,12 +255,12 @@ __device__ __forceinline__ void epilogue(const GemmArgs &g, const float *Cs, int
       } else if (EPI == EPI_PARTIAL) {
         store8(static_cast<float *>(g.C) + ((size_t)split * g.M + m) * g.ldc + n0 + c8, x);
       } else if (EPI == EPI_CONV) {
-        float bi[8], pre[8];
+        float bi[8], pre_act[8];
         load8(g.bias + n0 + c8, bi);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) { pre[i] = x[i] + bi[i]; out[i] = gelu_f(pre[i]); }
+        for (int i = 0; i < 8; ++i) { pre_act[i] = x[i] + bi[i]; out[i] = gelu_f(pre_act[i]); }
         store8(static_cast<AT *>(g.C) + o, out);
-        if (g.C2) store8(static_cast<AT *>(g.C2) + o, pre);
+        if (g.C2) store8(static_cast<AT *>(g.C2) + o, pre_act);
       }
     } else {
 #pragma unroll
@@ -237,6 +276,7 @@ __device__ __forceinline__ void epilogue(const GemmArgs &g, const float *Cs, int
         float *p = g.stats_out + ((size_t)m * (g.N / BN) + nt) * 2;
         p[0] = s; p[1] = q;
       }
+    }
     }
   }
 }
@@ -543,10 +583,27 @@ __device__ __forceinline__ void pipe_body(const GemmArgs &g, int bid, int split,
     // 256 x 256 tile: the fp32 tile does not fit LDS at once. It leaves in slabs of 64 rows, each handed to the epilogue as
     // 128-column halves (the width the row statistics are kept at), so every output is formed exactly as by the smaller tiles.
     static_assert(EPI != EPI_PARTIAL && EPI != EPI_GEGLU && EPI != EPI_GEGLU_FOLD && TM % 2 == 0 && BN % 128 == 0, "slab epilogue");
+    // The side inputs of slab p + 1 are requested before slab p is worked on: with one workgroup on the CU nothing else
+    // would cover their latency. sd: [buffer][column half][pass][input].
+    constexpr int NT8 = NW * 64, SP = 64 / (NT8 / 16);   // passes of a thread over a 64-row, 128-column slab half
+    Raw8<AT> sd[2][BN / 128][SP][2];
+    auto side = [&](int buf, int p) {
+      if constexpr (EpiSides<EPI>::n > 0) {
+#pragma unroll
+        for (int h = 0; h < BN / 128; ++h)
+#pragma unroll
+          for (int u = 0; u < SP; ++u) {
+            const int m = m0 + p * 64 + u * (NT8 / 16) + tid / 16;
+            epi_side_load<EPI, AT>(g, (size_t)m * g.ldc + n0 + h * 128 + (tid % 16) * 8, m < g.M, sd[buf][h][u]);
+          }
+      }
+    };
+    side(0, 0);
 #pragma unroll
     for (int p = 0; p < BM / 64; ++p) {
       constexpr int ROWS_PER_WAVE = 32 * TM;
       const int owner = (p * 64) / ROWS_PER_WAVE, i0 = ((p * 64) % ROWS_PER_WAVE) / 32;
+      if (p + 1 < BM / 64) side((p + 1) & 1, p + 1);
       __syncthreads();  // the ring, or the previous slab, is no longer being read
       if (wm == owner) {
 #pragma unroll
@@ -563,7 +620,8 @@ __device__ __forceinline__ void pipe_body(const GemmArgs &g, int bid, int split,
       __syncthreads();
 #pragma unroll
       for (int h = 0; h < BN / 128; ++h)
-        epilogue<EPI, AT, 64, 128, LDC, NW * 64>(g, Cs + h * 128, m0 + p * 64, n0 + h * 128, nt * (BN / 128) + h, tid, 0);
+        epilogue<EPI, AT, 64, 128, LDC, NT8, EpiSides<EPI>::n != 0>(g, Cs + h * 128, m0 + p * 64, n0 + h * 128, nt * (BN / 128) + h, tid, 0,
+                                                                     sd[p & 1][h]);
     }
   } else {
   __syncthreads();
