@@ -12,7 +12,8 @@ measures the same steps with frozen weights (inference only) and reports them un
 
 Prints ONE JSON line (see the keys below); `roofline` describes the dominant kernel (the D_h x D_h router /
 gate product), timed with HIP events on the library's stream in a second pass over the same steps;
-`cpu_baseline` times the CPU oracle on a bounded sample of the same workload.
+`update_roofline` (online mode) does the same for the longest single launch of the update, the HBM-bound Adam pass over
+the nine big matrices; `cpu_baseline` times the CPU oracle on a bounded sample of the same workload.
 """
 import argparse
 import json
@@ -28,6 +29,8 @@ sys.path.insert(0, ROOT)
 MFMA_BF16_PEAK = 2.5e15   # MI355X dense bf16, FLOP/s
 HBM_PEAK = 8.0e12         # B/s
 ROUTER_GATE_TRAFFIC_BYTES = {(2, "frozen"): int(0.5 * (346.9 + 55.3 + 345.4 + 55.5) * (1 << 20)), (2, "online"): int(0.5 * (56.3 + 53.8) * (1 << 20))}
+# adam_refresh_kernel, same counter runs (profiles/cfg2_online_kernel_trace_and_hbm.md)
+ADAM_TRAFFIC_BYTES = {(2, "online"): int(426.7 * (1 << 20))}
 
 
 def parse():
@@ -175,9 +178,21 @@ def main():
                         "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s", "frac": round(ach * 1e12 / MFMA_BF16_PEAK, 4),
                         "traffic": None, "avg_us": round(us, 2), "flop_per_launch": flop,
                         "algorithmic_bytes_per_launch": 2 * rows * Dh + 2 * Dh * 2 * De + 4 * rows * 2 * De}
+        update_roofline = None
+        if "adam_matrices" in kern and spec["dtype"] == "bf16":
+            # the longest single launch of an online step: Adam on the nine big matrices fused with the refresh of their bf16
+            # operand copies. Per parameter: gradient, both moments and the master weight read (16 B), moments and weight
+            # written (12 B), one bf16 copy per orientation the products use (2 B each; W_m has one orientation only).
+            P = 2 * Dh * Dh + 3 * Dh * De + Dc * Dh + 256 * Dh + 2 * dl * Dh
+            nbytes = 32 * P - 2 * Dc * Dh
+            us = kern["adam_matrices"]["avg_us"]
+            ach = nbytes / (us * 1e-6) / 1e9
+            update_roofline = {"bound": "hbm", "kernel": "adam_refresh_kernel (Adam + operand refresh of the nine big matrices)",
+                               "achieved": round(ach, 1), "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": round(ach * 1e9 / HBM_PEAK, 4),
+                               "traffic": ADAM_TRAFFIC_BYTES.get((a.config, mode)), "avg_us": round(us, 2), "algorithmic_bytes_per_launch": nbytes}
         step_us_events = sum(v["avg_us"] * v["launches"] for k, v in kern.items() if k != "code_uniform") / max(steps_timed, 1)
         return dict(t_enc=t_enc, t_dec=t_dec, ok=ok, steps_timed=steps_timed, bytes_timed=bytes_timed, container=container, enc_MBps=enc_MBps,
-                    dec_MBps=dec_MBps, kern=kern, roofline=roofline, step_us_events=step_us_events)
+                    dec_MBps=dec_MBps, kern=kern, roofline=roofline, update_roofline=update_roofline, step_us_events=step_us_events)
 
     r = measure(mode)
     t_enc, t_dec, ok, steps_timed, bytes_timed, container = r["t_enc"], r["t_dec"], r["ok"], r["steps_timed"], r["bytes_timed"], r["container"]
@@ -226,7 +241,7 @@ def main():
         "round_trip_exact": ok, "bits_per_byte": round(8.0 * container / n, 4),
         "fwd_flop_per_byte": fwd_flop,
         "step_fraction_of_mfma_peak": round(fwd_flop * bytes_timed / t_enc / MFMA_BF16_PEAK, 4) if mode == "frozen" else None,
-        "roofline": roofline, "cpu_baseline": cpu, "frozen_weights": other,
+        "roofline": roofline, "update_roofline": r["update_roofline"], "cpu_baseline": cpu, "frozen_weights": other,
         "kernels_us": {k: round(v["avg_us"], 2) for k, v in kern.items()}, "sum_kernels_us": round(step_us_events, 2),
     }
     print(json.dumps(out))

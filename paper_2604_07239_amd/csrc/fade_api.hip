@@ -822,14 +822,21 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     // gamma_e, beta_e, gamma_l, beta_l are adjacent in the blob
     HIP_TRY(c, fade_bwd_embed(a, c->emb_blocks, c->sym_sums, c->tok_part, Gp(P_E), Gp(P_GAMMA_E), bf, rq, s));
   }
-  {  // Adam on everything except W_U (done in place above) and the refresh of every compute copy
-    Prof p(c, "adam_refresh");
+  // Adam on everything except W_U (done in place above) and the refresh of every compute copy
+  {
+    Prof p(c, "adam_small");
     const AdamArrays opt{c->grad, c->master, c->adam_m, c->adam_v, c->ustate, c->cfg.lr, c->cfg.beta1, c->cfg.beta2, c->cfg.eps};
     // vectors, scalars, biases and the small tensors: Adam right where their gradient sums are finished
     rq.opt = opt;
     rq.push(1, (int)(256 * d.D), Gp(P_E), Gp(P_E));  // dE is complete already: a one-row "sum" that only adds the Adam step
     HIP_TRY(c, fade_reduce_batch(rq, s));
+  }
+  {
+    Prof p(c, "adam_matrices");
     if ((rc = refresh_matrices(c, true))) return rc;
+  }
+  {
+    Prof p(c, "refresh_small");
     rc = bf ? refresh_small(c) : prepare_compute(c, false);
     if (rc) return rc;
   }
