@@ -154,6 +154,10 @@ struct fade_ctx {
         *conv_part = nullptr, *tok_part = nullptr;
   float *ln_part = nullptr, *col_part = nullptr, *slot_part = nullptr, *emb_part = nullptr;
   int sp_dz = 1, emb_blocks = 128;
+  // weight gradients with few output tiles are left as partial sums over ranges of the batch (bf16 path): per parameter
+  // tensor the number of ranges (1: none) and the slices [ranges][K][N]; the Adam pass adds them up
+  int gsp[P_COUNT] = {};
+  float *gpart[P_COUNT] = {};
 
   // coder and step bookkeeping
   CoderBufs cb{};
@@ -256,17 +260,19 @@ int refresh_matrices(fade_ctx *c, bool adam) {
     m.off = c->lay.off[id]; m.K = (int)K; m.N = (int)N; m.vcol0 = vcol0; m.vstride = vstride; m.VN = (int)VN;
     m.frag = bf ? frag : nullptr; m.fragT = (bf && c->online) ? fragT : nullptr; m.gamma = bf ? ga : nullptr; m.beta = bf ? be : nullptr; m.fold_part = fp;
     m.first_block = ab.total_blocks;
+    m.gpart = (adam && c->gsp[id] > 1) ? c->gpart[id] : nullptr; m.gsplits = c->gsp[id];
     ab.total_blocks += (int)((K / 64) * (N / 64));
   };
-  add(P_WR, d.Dh, d.Dh, 0, 64, d.Dh, c->Wr_c, c->WT_r, nullptr, nullptr, nullptr);
-  add(P_WC, d.Dh, d.Dh, 0, 64, d.Dh, c->Wc_c, c->WT_c, nullptr, nullptr, nullptr);
+  // matrices whose gradient may arrive as partial sums go first: their blocks have the longer chain of loads
+  add(P_WDOWN, d.Dh, d.dl, 0, 64, d.dl, c->Wdown_c, c->WT_down, c->P(P_GAMMA_C), c->P(P_BETA_C), c->fold_down);
+  add(P_WO, d.Dh, 256, 0, 64, 256, c->Wo_c, c->WT_o, nullptr, nullptr, nullptr);
+  add(P_WF, d.De, d.Dh, 0, 64, d.Dh, c->Wf_c, c->WT_f, nullptr, nullptr, nullptr);
   add(P_WFG, d.Dh, d.De, 0, 128, 2 * d.De, c->Wfgv_c, c->WT_fgv, c->P(P_GAMMA_F), c->P(P_BETA_F), c->fold_fnr);
   add(P_WFV, d.Dh, d.De, 64, 128, 2 * d.De, c->Wfgv_c, c->WT_fgv, c->P(P_GAMMA_F), c->P(P_BETA_F), c->fold_fnr);
+  add(P_WR, d.Dh, d.Dh, 0, 64, d.Dh, c->Wr_c, c->WT_r, nullptr, nullptr, nullptr);
+  add(P_WC, d.Dh, d.Dh, 0, 64, d.Dh, c->Wc_c, c->WT_c, nullptr, nullptr, nullptr);
   add(P_WM, d.Dc, d.Dh, 0, 64, d.Dh, c->Wm_c, nullptr, nullptr, nullptr, nullptr);
-  add(P_WF, d.De, d.Dh, 0, 64, d.Dh, c->Wf_c, c->WT_f, nullptr, nullptr, nullptr);
-  add(P_WO, d.Dh, 256, 0, 64, 256, c->Wo_c, c->WT_o, nullptr, nullptr, nullptr);
   add(P_WUP, d.dl, d.Dh, 0, 64, d.Dh, c->Wup_c, c->WT_up, nullptr, nullptr, nullptr);
-  add(P_WDOWN, d.Dh, d.dl, 0, 64, d.dl, c->Wdown_c, c->WT_down, c->P(P_GAMMA_C), c->P(P_BETA_C), c->fold_down);
   HIP_TRY(c, fade_adam_refresh(ab, c->stream));
   return FADE_OK;
 }
@@ -617,11 +623,19 @@ GemmArgs args_x(fade_ctx *c, const void *dY, int Kred, int Nout, const void *wt_
 // dW[Kw][N] = L^T R over the batch. bf16 path: both operands row-major as the forward / backward kernels left them
 // (L [B][ldL], R [Bp][N] with zero rows past the batch), turned on the way out of LDS. fp32 path: LT is a feature-major
 // copy [Kw][Bp] of L, R is read row-major.
-GemmArgs args_w(fade_ctx *c, const void *L, int ldL, const void *LT, int Kw, const void *R, int N, float *dW, float *dW_pair) {
+GemmArgs args_w(fade_ctx *c, const void *L, int ldL, const void *LT, int Kw, const void *R, int N, int id, int id_pair = -1) {
   GemmArgs g{};
-  g.M = Kw; g.N = N; g.K = (int)c->Bp; g.C = dW; g.C3 = dW_pair; g.ldc = N; g.W = R;
-  if (c->bf16) { g.A = L; g.lda = ldL; g.a_rows = (int)c->d.B; g.ldb = N; }
-  else { g.A = LT; g.lda = (int)c->Bp; }
+  float *G = c->grad;
+  g.M = Kw; g.N = N; g.K = (int)c->Bp; g.ldc = N; g.W = R;
+  g.C = G + c->lay.off[id];
+  if (id_pair >= 0) g.C3 = G + c->lay.off[id_pair];
+  if (c->bf16) {
+    g.A = L; g.lda = ldL; g.a_rows = (int)c->d.B; g.ldb = N;
+    if (c->gsp[id] > 1) {  // partial sums over ranges of the batch; a pair splits alike
+      g.splits = c->gsp[id]; g.C = c->gpart[id];
+      if (id_pair >= 0) g.C3 = c->gpart[id_pair];
+    }
+  } else { g.A = LT; g.lda = (int)c->Bp; }
   return g;
 }
 // The products of one backward phase consume the same gradient and are independent: one grouped launch (bf16 path), or
@@ -697,7 +711,7 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
   // head
   {
     PhaseGemms ph;
-    ph.add(GEMM_W_TN, args_w(c, feat, Dh, c->LT[0], Dh, c->dl, 256, Gp(P_WO), nullptr));
+    ph.add(GEMM_W_TN, args_w(c, feat, Dh, c->LT[0], Dh, c->dl, 256, P_WO));
     ph.add(GEMM_X_STORE, args_x(c, c->dl, 256, Dh, c->WT_o, c->P(P_WO), 256, dfeat));
     if ((rc = run_phase(c, "gemms_head", ph))) return rc;
   }
@@ -712,7 +726,7 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
   }
   {
     PhaseGemms ph;
-    ph.add(GEMM_W_TN, args_w(c, c->Hexp, De, c->LT[1], De, c->dV, Dh, Gp(P_WF), nullptr));
+    ph.add(GEMM_W_TN, args_w(c, c->Hexp, De, c->LT[1], De, c->dV, Dh, P_WF));
     ph.add(GEMM_X_STORE, args_x(c, c->dV, Dh, De, c->WT_f, c->P(P_WF), Dh, c->dHexp));
     if ((rc = run_phase(c, "gemms_fnr_out", ph))) return rc;
   }
@@ -722,7 +736,7 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
   }
   {
     PhaseGemms ph;
-    ph.add(GEMM_W_TN, args_w(c, c->LT[2], Dh, c->LT[2], Dh, c->dE, 2 * De, Gp(P_WFG), Gp(P_WFV)));
+    ph.add(GEMM_W_TN, args_w(c, c->LT[2], Dh, c->LT[2], Dh, c->dE, 2 * De, P_WFG, P_WFV));
     ph.add(GEMM_X_STORE, args_x(c, c->dE, 2 * De, Dh, c->WT_fgv, static_cast<const float *>(c->Wfgv_c), 2 * De, c->du));
     if ((rc = run_phase(c, "gemms_fnr_in", ph))) return rc;
   }
@@ -741,10 +755,10 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
   {  // Eq. 8's gate product and Eq. 7's Up
     PhaseGemms ph;
     if (level >= 4) {
-      ph.add(GEMM_W_TN, args_w(c, c->Hmix, Dh, c->LT[3], Dh, c->dac, Dh, Gp(P_WC), nullptr));
+      ph.add(GEMM_W_TN, args_w(c, c->Hmix, Dh, c->LT[3], Dh, c->dac, Dh, P_WC));
       ph.add(GEMM_X_STORE, args_x(c, c->dac, Dh, Dh, c->WT_c, c->P(P_WC), Dh, c->dHmix2));
     }
-    ph.add(GEMM_W_TN, args_w(c, c->z, dl, c->LT[4], dl, c->dHa, Dh, Gp(P_WUP), nullptr));
+    ph.add(GEMM_W_TN, args_w(c, c->z, dl, c->LT[4], dl, c->dHa, Dh, P_WUP));
     GemmArgs g{};
     g.M = B; g.N = dl; g.K = Dh; g.splits = c->sp_dz; g.A = c->dHa; g.lda = Dh; g.C = c->dz_part; g.ldc = dl;
     if (bf) g.W = c->WT_up;
@@ -763,7 +777,7 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
   }
   {
     PhaseGemms ph;
-    ph.add(GEMM_W_TN, args_w(c, c->LT[5], Dh, c->LT[5], Dh, c->dy_at, dl, Gp(P_WDOWN), nullptr));
+    ph.add(GEMM_W_TN, args_w(c, c->LT[5], Dh, c->LT[5], Dh, c->dy_at, dl, P_WDOWN));
     ph.add(GEMM_X_STORE, args_x(c, c->dy_at, dl, Dh, c->WT_down, c->P(P_WDOWN), dl, c->dnc));
     if ((rc = run_phase(c, "gemms_down", ph))) return rc;
   }
@@ -784,10 +798,10 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
   {  // router and global stream
     PhaseGemms ph;
     if (level >= 2) {
-      ph.add(GEMM_W_TN, args_w(c, c->X, Dh, c->LT[7], Dh, c->dar, Dh, Gp(P_WR), nullptr));
+      ph.add(GEMM_W_TN, args_w(c, c->X, Dh, c->LT[7], Dh, c->dar, Dh, P_WR));
       ph.add(GEMM_X_STORE, args_x(c, c->dar, Dh, Dh, c->WT_r, c->P(P_WR), Dh, c->dX2));
     }
-    ph.add(GEMM_W_TN, args_w(c, c->M, (int)d.Dc, c->LT[6], (int)d.Dc, c->dhm, Dh, Gp(P_WM), nullptr));
+    ph.add(GEMM_W_TN, args_w(c, c->M, (int)d.Dc, c->LT[6], (int)d.Dc, c->dhm, Dh, P_WM));
     if ((rc = run_phase(c, "gemms_router_global", ph))) return rc;
   }
   {
@@ -1103,6 +1117,28 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
       struct { void **p; size_t n; } lts[] = {{&c->LT[0], d.Dh * Bp}, {&c->LT[1], d.De * Bp}, {&c->LT[3], d.Dh * Bp}, {&c->LT[4], d.dl * Bp},
                                                {&c->LT[6], d.Dc * Bp}, {&c->LT[7], d.Dh * Bp}};
       for (auto &b : lts) TRY_ALLOC(A(b.p, b.n));
+    }
+    if (c->bf16) {
+      // weight gradients whose tiles are few: the contraction (the batch) is cut into ranges until the product has ~256
+      // workgroups; products with tiles enough keep their single pass. The Adam pass reads every range's slice, so a
+      // big matrix is cut only when its chain of 64-row blocks is long (B >= 2048) and into ranges of at least 8 blocks;
+      // W_down (128 K elements) is cut down to ranges of 2 blocks. B = 1024: Down phase 16 -> 13 us, the others unchanged
+      // (cutting them too cost 11 us more in the Adam pass than it saved); B = 4096: head / FNR-out / FNR-in / Down
+      // phases 52 / 55 / 55 / 62 -> 24 / 37 / 39 / 16 us for 12 us more in the Adam pass.
+      const struct { int id, pair, M, N; } gw[] = {{P_WO, -1, (int)d.Dh, 256}, {P_WF, -1, (int)d.De, (int)d.Dh}, {P_WFG, P_WFV, (int)d.Dh, (int)(2 * d.De)},
+                                                    {P_WDOWN, -1, (int)d.Dh, (int)d.dl}};
+      for (const auto &w : gw) {
+        const int tiles = fade_gemm_tn_tiles(w.M, w.N);
+        if (tiles <= 0 || tiles >= 192) continue;
+        const bool small = c->lay.len[w.id] <= (256u << 10);
+        const int nkb = (int)(Bp / 64);
+        if (!small && nkb < 32) continue;
+        const int sp = pick_splits(tiles, small ? nkb : nkb / 4, 16);  // nkb / 4: ranges of at least 8 blocks
+        if (sp <= 1 || nkb % sp) continue;
+        c->gsp[w.id] = sp;
+        TRY_ALLOC(dev_alloc(c, &c->gpart[w.id], (size_t)sp * c->lay.len[w.id]));
+        if (w.pair >= 0) { c->gsp[w.pair] = sp; TRY_ALLOC(dev_alloc(c, &c->gpart[w.pair], (size_t)sp * c->lay.len[w.pair])); }
+      }
     }
     c->sp_dz = c->bf16 ? pick_splits((int)((d.B + 63) / 64), (int)(d.Dh / 64), 16) : 1;
     TRY_ALLOC(dev_alloc(c, &c->dz_part, (size_t)c->sp_dz * d.B * d.dl));

@@ -985,11 +985,26 @@ __global__ __launch_bounds__(256) void adam_refresh_kernel(AdamRefreshBatch ab) 
     f32x4 g[4], mm[4], vv[4], w[4];
     size_t idx[4];
 #pragma unroll
+    for (int q = 0; q < 4; ++q) idx[q] = M.off + (size_t)(k0 + (tid >> 4) + 16 * q) * M.N + n0 + c4;
+    // a gradient that arrives as partial sums over ranges of the batch: add them in range order and keep the sum (done
+    // before the other operands are fetched, so that it needs no registers of its own)
+    const bool parts = !ab.refresh_only && M.gpart != nullptr;
+    if (parts) {
+      const size_t mat = (size_t)M.K * M.N;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) g[q] = *reinterpret_cast<const f32x4 *>(M.gpart + (idx[q] - M.off));
+#pragma unroll 2
+      for (int sp = 1; sp < M.gsplits; ++sp)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) g[q] += *reinterpret_cast<const f32x4 *>(M.gpart + sp * mat + (idx[q] - M.off));
+#pragma unroll
+      for (int q = 0; q < 4; ++q) *reinterpret_cast<f32x4 *>(const_cast<float *>(ab.opt.grad_base) + idx[q]) = g[q];
+    }
+#pragma unroll
     for (int q = 0; q < 4; ++q) {
-      idx[q] = M.off + (size_t)(k0 + (tid >> 4) + 16 * q) * M.N + n0 + c4;
       w[q] = *reinterpret_cast<const f32x4 *>(ab.opt.master + idx[q]);
       if (!ab.refresh_only) {
-        g[q] = *reinterpret_cast<const f32x4 *>(ab.opt.grad_base + idx[q]);
+        if (!parts) g[q] = *reinterpret_cast<const f32x4 *>(ab.opt.grad_base + idx[q]);
         mm[q] = *reinterpret_cast<const f32x4 *>(ab.opt.m + idx[q]);
         vv[q] = *reinterpret_cast<const f32x4 *>(ab.opt.v + idx[q]);
       }

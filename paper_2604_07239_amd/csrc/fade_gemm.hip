@@ -244,13 +244,13 @@ __device__ __forceinline__ void epilogue(const GemmArgs &g, const float *Cs, int
         store8(static_cast<AT *>(g.C) + o, out);
         if (g.C2) store8(static_cast<AT *>(g.C2) + o, eg);
         if (g.C3) store8(static_cast<AT *>(g.C3) + o, ev);
-      } else if (EPI == EPI_GRAD) {
+      } else if (EPI == EPI_GRAD) {  // split: partial sum over one range of the batch, slices [split][M][width] behind each other
         if (g.C3) {
           const int v = n0 + c8;
           float *dstp = ((v & 127) < 64) ? static_cast<float *>(g.C) : static_cast<float *>(g.C3);
-          store8(dstp + (size_t)m * (g.N / 2) + (v / 128) * 64 + (v & 63), x);
+          store8(dstp + ((size_t)split * g.M + m) * (g.N / 2) + (v / 128) * 64 + (v & 63), x);
         } else {
-          store8(static_cast<float *>(g.C) + o, x);
+          store8(static_cast<float *>(g.C) + (size_t)split * g.M * g.ldc + o, x);
         }
       } else if (EPI == EPI_PARTIAL) {
         store8(static_cast<float *>(g.C) + ((size_t)split * g.M + m) * g.ldc + n0 + c8, x);
@@ -674,7 +674,7 @@ template <int PITCH> __device__ __forceinline__ int tn_swizzle(int r) {
 }
 
 template <int BM, int BN, int STAGES>
-__device__ __forceinline__ void tn_body(const GemmArgs &g, int bid) {
+__device__ __forceinline__ void tn_body(const GemmArgs &g, int bid, int split = 0, int nsplit = 1) {
   typedef bf16_t AT;
   constexpr int BK = 64, KS = 4;
   constexpr int TM = BM / 64, TN = BN / 64;
@@ -694,7 +694,7 @@ __device__ __forceinline__ void tn_body(const GemmArgs &g, int bid) {
   int mt, nt;
   if (!tile_of_block(bid, ntm, ntn, 8, mt, nt)) return;
   const int m0 = mt * BM, n0 = nt * BN;
-  const int nkb = g.K / BK;
+  const int nkb = g.K / BK / nsplit, kb0 = split * nkb;  // this workgroup's range of the contraction (the batch)
 
   // DMA c of an operand covers rows c * R .. c * R + R - 1 of the stage; lane i lands at byte 16 i of that KiB, i.e. at
   // (row, piece) = (c * R + i / P, i % P), and fetches the piece whose index is XORed as described above.
@@ -735,7 +735,7 @@ __device__ __forceinline__ void tn_body(const GemmArgs &g, int bid) {
 
 #pragma unroll
   for (int s = 0; s < STAGES - 1; ++s)
-    if (s < nkb) issue(s, s);
+    if (s < nkb) issue(s, kb0 + s);
 
   // address this lane supplies to the transposing loads of k-step 0 (first of the two loads; the second is 4 rows on):
   // row 8 * (lane / 32) + (lane % 16) / 4, columns tile * 32 + 16 * ((lane / 16) % 2) + 4 * (lane % 4) .. + 3
@@ -753,7 +753,7 @@ __device__ __forceinline__ void tn_body(const GemmArgs &g, int bid) {
     if (kb + STAGES - 2 < nkb) wait_vmcnt<(STAGES - 2) * LPW>();
     else wait_vmcnt<0>();
     bare_barrier();
-    if (kb + STAGES - 1 < nkb) issue((kb + STAGES - 1) % STAGES, kb + STAGES - 1);
+    if (kb + STAGES - 1 < nkb) issue((kb + STAGES - 1) % STAGES, kb0 + kb + STAGES - 1);
     const unsigned char *st = smem + (kb % STAGES) * STAGE_BYTES;
     i16x8 af[2][TM], bf[2][TN];
     auto tr_load = [&](const unsigned char *p) {
@@ -802,7 +802,7 @@ __device__ __forceinline__ void tn_body(const GemmArgs &g, int bid) {
         Cs[row * LDC + col] = acc[i][j][e];
       }
   __syncthreads();
-  epilogue<EPI_GRAD, AT, BM, BN>(g, Cs, m0, n0, nt, tid);
+  epilogue<EPI_GRAD, AT, BM, BN>(g, Cs, m0, n0, nt, tid, split);
 }
 template <int BM, int BN, int STAGES>
 __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmArgs g) {
@@ -823,9 +823,9 @@ __device__ __forceinline__ void group_body(const GemmGroup &gg) {
     case GK_STORE_128x128:  pipe_body<128, 128, STAGES, EPI_STORE, false>(g, local, 0, 1); break;
     case GK_STORE_64x64:    pipe_body<64, 64, STAGES, EPI_STORE, false>(g, local, 0, 1); break;
     case GK_PARTIAL_64x64:  pipe_body<64, 64, STAGES, EPI_PARTIAL, false>(g, local % tiles, local / tiles, gg.splits[p]); break;
-    case GK_TN_64x128:      tn_body<64, 128, STAGES>(g, local); break;
-    case GK_TN_128x128:     tn_body<128, 128, STAGES>(g, local); break;
-    case GK_TN_64x64:       tn_body<64, 64, STAGES>(g, local); break;
+    case GK_TN_64x128:      tn_body<64, 128, STAGES>(g, local % tiles, local / tiles, gg.splits[p]); break;
+    case GK_TN_128x128:     tn_body<128, 128, STAGES>(g, local % tiles, local / tiles, gg.splits[p]); break;
+    case GK_TN_64x64:       tn_body<64, 64, STAGES>(g, local % tiles, local / tiles, gg.splits[p]); break;
     default: break;
   }
 }
@@ -1060,6 +1060,22 @@ size_t group_kind_lds(int kind, int stages) {  // the larger of the operand ring
 }
 }  // namespace
 
+// Tile shape of a weight-gradient product dW[M][N] in a grouped launch.
+static bool tn_shape(int M, int N, int &kind, int &bm, int &bn) {
+  if (N % 128 == 0) {
+    const bool big = M % 128 == 0 && (M / 128) * (N / 128) >= 256 && fade_gemm_tune() != 8;
+    kind = big ? GK_TN_128x128 : GK_TN_64x128; bm = big ? 128 : 64; bn = 128;
+    return true;
+  }
+  if (N % 64 == 0) { kind = GK_TN_64x64; bm = 64; bn = 64; return true; }
+  return false;
+}
+int fade_gemm_tn_tiles(int M, int N) {
+  int kind, bm, bn;
+  if (M <= 0 || M % 64 || !tn_shape(M, N, kind, bm, bn)) return 0;
+  return (M / bm) * (N / bn);
+}
+
 // Append one product to a group; the kernel body is chosen from the operation and the shape. op is one of GEMM_X_STORE
 // (C = A W, W as fragments), GEMM_PARTIAL (split-K partials, N = 64) and GEMM_W_TN (dW from row-major operands).
 hipError_t fade_gemm_group_add(GemmGroup &gg, int op, const GemmArgs &g) {
@@ -1078,11 +1094,9 @@ hipError_t fade_gemm_group_add(GemmGroup &gg, int op, const GemmArgs &g) {
     if (g.K % (splits * 64)) return hipErrorInvalidValue;
   } else if (op == GEMM_W_TN) {
     if (g.a_rows <= 0 || g.a_rows > g.K || g.ldb % 8 || g.M % 64) return hipErrorInvalidValue;
-    if (g.N % 128 == 0) {
-      const bool big = g.M % 128 == 0 && (g.M / 128) * (g.N / 128) >= 256 && fade_gemm_tune() != 8;
-      kind = big ? GK_TN_128x128 : GK_TN_64x128; bm = big ? 128 : 64; bn = 128;
-    } else if (g.N % 64 == 0) { kind = GK_TN_64x64; bm = 64; bn = 64; }
-    else return hipErrorInvalidValue;
+    splits = g.splits > 1 ? g.splits : 1;  // ranges of the batch, each leaving its own slice of C (and C3)
+    if (g.K % (splits * 64)) return hipErrorInvalidValue;
+    if (!tn_shape(g.M, g.N, kind, bm, bn)) return hipErrorInvalidValue;
   } else {
     return hipErrorInvalidValue;
   }

@@ -14,6 +14,7 @@ enum {
 // Launch one of the model step's products (see fade_gemm.hip). bf16 selects the MFMA path (activations
 // bf16, W in fragment order) or the fp32 path (activations fp32, W plain [K][N]).
 hipError_t fade_gemm(int op, bool bf16, const GemmArgs &g, hipStream_t s);
+int fade_gemm_tn_tiles(int M, int N);  // workgroups per batch range of a grouped weight-gradient product dW[M][N]; 0: shape not supported
 hipError_t fade_gemm_group_add(GemmGroup &gg, int op, const GemmArgs &g);
 hipError_t fade_gemm_group_launch(const GemmGroup &gg, hipStream_t s);
 
@@ -232,7 +233,7 @@ hipError_t fade_reduce_rows(int P, int N, const float *part, float *out, hipStre
 // waits for are queued here and run as ONE launch just before Adam. The stage-1 launchers below take the queue.
 // Adam's hyper-parameters and state arrays (device layout; gradient, master weights and both moments share the offsets)
 struct AdamArrays {
-  const float *grad_base;
+  const float *grad_base;  // gradients in blob order (the Adam pass over the matrices stores sums of partial gradients here: see AdamMat)
   float *master, *m, *v;
   const UpdateState *u;
   float lr, beta1, beta2, eps;
@@ -269,6 +270,10 @@ struct AdamMat {
   const float *gamma, *beta;
   float *fold_part;        // [K / 64][2][VN] when gamma is set
   int first_block;
+  // gradient left as gsplits partial sums [gsplits][K][N] over ranges of the batch (NULL: complete in the gradient array);
+  // the Adam pass adds them in range order and stores the sum in the gradient array
+  const float *gpart;
+  int gsplits;
 };
 struct AdamRefreshBatch {
   int count, total_blocks;
