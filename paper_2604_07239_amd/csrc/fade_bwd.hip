@@ -552,24 +552,32 @@ __global__ __launch_bounds__(256) void reduce_rows_kernel(int P, int N, const fl
     out[n] = t;
   }
 }
-__global__ __launch_bounds__(256) void reduce_batch_kernel(ReduceBatch rb) {
-  // same arithmetic as reduce_rows_kernel, blockIdx.y picks the queued reduction
-  __shared__ float ps[8][32];
-  const int k = blockIdx.y, P = rb.P[k], N = rb.N[k];
-  if ((int)blockIdx.x * 32 >= N) return;  // uniform over the workgroup
+// Several queued column sums in one launch (blockIdx.y picks the item). 1024 threads = cw columns x (1024 / cw) row
+// phases, cw = 32 or, for an item narrower than that, the next power of two >= N (a [B][1] column of per-stream terms
+// then has all 1024 threads on its rows). Phase h adds rows h, h + phases, ... in increasing order; the phase sums are
+// folded pairwise in a fixed tree: the result does not depend on timing.
+__global__ __launch_bounds__(1024) void reduce_batch_kernel(ReduceBatch rb) {
+  __shared__ float ps[1024];
+  const int k = blockIdx.y, P = rb.P[k], N = rb.N[k], tid = threadIdx.x;
+  int lg = 5;
+  while (lg > 0 && (1 << (lg - 1)) >= N) --lg;
+  const int cw = 1 << lg, phases = 1024 >> lg;
+  if ((int)blockIdx.x * cw >= N) return;  // uniform over the workgroup
   const float *part = rb.part[k];
-  const int c = threadIdx.x & 31, h = threadIdx.x >> 5, n = blockIdx.x * 32 + c;
+  const int c = tid & (cw - 1), h = tid >> lg, n = blockIdx.x * cw + c;
   float s = 0.0f;
   if (n < N) {
-#pragma unroll 4
-    for (int p = h; p < P; p += 8) s += part[(size_t)p * N + n];
+#pragma unroll 8
+    for (int p = h; p < P; p += phases) s += part[(size_t)p * N + n];
   }
-  ps[h][c] = s;
+  ps[tid] = s;  // [phase][column]
   __syncthreads();
+  for (int st = phases >> 1; st > 0; st >>= 1) {
+    if (h < st) ps[tid] += ps[tid + (st << lg)];
+    __syncthreads();
+  }
   if (h == 0 && n < N) {
-    float t = 0.0f;
-#pragma unroll
-    for (int q = 0; q < 8; ++q) t += ps[q][c];
+    const float t = ps[tid];
     rb.out[k][n] = t;
     if (rb.adam[k]) adam_element(rb.opt, (size_t)(rb.out[k] - rb.opt.grad_base) + n, t);
   }
@@ -751,11 +759,21 @@ __global__ __launch_bounds__(256) void conv_grad_partial_kernel(ConvGradArgs a) 
   __shared__ __attribute__((aligned(16))) float ds[128 * 32];
   const int tid = threadIdx.x, D = a.D, pad = a.taps - 1;
   const int lgD = 31 - __builtin_clz(D), lgT = 31 - __builtin_clz(a.T), Tm = a.T - 1, Tp = a.T + pad;  // D, T: powers of two
-  const long long tokens = (long long)a.B * a.T, t0 = (long long)blockIdx.x * 128;
-  const AT *XL = static_cast<const AT *>(a.XL) + (size_t)t0 * D, *dcv = static_cast<const AT *>(a.dcv) + (size_t)t0 * D;
+  const long long tokens = (long long)a.B * a.T, nchunks = (tokens + 127) / 128;
   const int used = (((128 >> lgT) * Tp) << lgD) + 32;
-  for (int e = tid; e < used; e += 256) xs[e] = 0.0f;
-  __syncthreads();
+  for (int e = tid; e < used; e += 256) xs[e] = 0.0f;  // the zero rows stay zero: the tiles below never touch them
+  const int rows = a.taps * D;                    // (tap, i) pairs
+  const int o = tid & (D - 1), grp = tid >> lgD, ngrp = 256 >> lgD;
+  const int per = (rows + ngrp - 1) / ngrp;       // (tap, i) rows owned by this thread's group (<= 16)
+  const float *xp = xs + grp * per;
+  float acc[16], bsum = 0.0f;
+#pragma unroll
+  for (int q = 0; q < 16; ++q) acc[q] = 0.0f;
+  // a workgroup takes chunks blockIdx.x, blockIdx.x + gridDim.x, ... and keeps adding into the same registers
+  for (long long chunk = blockIdx.x; chunk < nchunks; chunk += gridDim.x) {
+  const long long t0 = chunk * 128;
+  const AT *XL = static_cast<const AT *>(a.XL) + (size_t)t0 * D, *dcv = static_cast<const AT *>(a.dcv) + (size_t)t0 * D;
+  __syncthreads();  // the zero fill, or the previous chunk's reads, are done
   const int left = (int)((tokens - t0 < 128 ? tokens - t0 : 128)) << lgD;  // elements of this tile that exist
   for (int e = tid * 8; e < (128 << lgD); e += 2048) {
     float x[8], d[8];
@@ -767,13 +785,6 @@ __global__ __launch_bounds__(256) void conv_grad_partial_kernel(ConvGradArgs a) 
     for (int q = 0; q < 8; ++q) { xs[at + q] = x[q]; ds[e + q] = d[q]; }
   }
   __syncthreads();
-  const int rows = a.taps * D;                    // (tap, i) pairs
-  const int o = tid & (D - 1), grp = tid >> lgD, ngrp = 256 >> lgD;
-  const int per = (rows + ngrp - 1) / ngrp;       // (tap, i) rows owned by this thread's group (<= 16)
-  const float *xp = xs + grp * per;
-  float acc[16], bsum = 0.0f;
-#pragma unroll
-  for (int q = 0; q < 16; ++q) acc[q] = 0.0f;
   // rows past `per` (or past `rows`) are read and accumulated too (in bounds thanks to the slack) and dropped at the end
   if ((per & 3) == 0) {
     for (int tl = 0; tl < 128; ++tl) {
@@ -795,6 +806,7 @@ __global__ __launch_bounds__(256) void conv_grad_partial_kernel(ConvGradArgs a) 
 #pragma unroll
       for (int q = 0; q < 16; ++q) acc[q] = fmaf(x[q], d, acc[q]);
     }
+  }
   }
   float *part = a.part + (size_t)blockIdx.x * (rows + 1) * D;
 #pragma unroll
@@ -1141,7 +1153,7 @@ hipError_t fade_reduce_batch(const ReduceBatch &rb, hipStream_t s) {
   if (rb.count <= 0) return hipSuccess;
   int maxN = 0;
   for (int i = 0; i < rb.count; ++i) maxN = rb.N[i] > maxN ? rb.N[i] : maxN;
-  hipLaunchKernelGGL(reduce_batch_kernel, dim3(nblk((size_t)maxN, 32), rb.count), dim3(256), 0, s, rb);
+  hipLaunchKernelGGL(reduce_batch_kernel, dim3(nblk((size_t)maxN, 32), rb.count), dim3(1024), 0, s, rb);
   return hipGetLastError();
 }
 hipError_t fade_bwd_cci(const BwdCciArgs &a, bool bf16, hipStream_t s) { DISPATCH_AT(bf16, bwd_cci_kernel, dim3(a.B), dim3(256), s, a); }
@@ -1164,7 +1176,8 @@ hipError_t fade_bwd_slot(const BwdSlotArgs &a, float *dWgv, bool bf16, ReduceBat
 // a.part must hold ceil(B * T / 128) * (taps * D + 1) * D floats; dWb points at W_conv's gradient (b_conv's follows it)
 hipError_t fade_conv_grad(const ConvGradArgs &a, float *dWb, bool bf16, ReduceBatch &rb, hipStream_t s) {
   if (256 % a.D || a.D > 32 || a.D < 16 || 128 % a.T || a.T < 4 || a.taps > 4 || (a.taps * a.D + 256 / a.D - 1) / (256 / a.D) > 16) return hipErrorInvalidValue;
-  const int P = (int)(((long long)a.B * a.T + 127) / 128);
+  const long long nchunks = ((long long)a.B * a.T + 127) / 128;
+  const int P = (int)(nchunks < 512 ? nchunks : 512);  // 128-token chunks are dealt round-robin to at most 512 workgroups
   if (bf16) hipLaunchKernelGGL(conv_grad_partial_kernel<bf16_t>, dim3(P), dim3(256), 0, s, a);
   else hipLaunchKernelGGL(conv_grad_partial_kernel<float>, dim3(P), dim3(256), 0, s, a);
   hipError_t e = hipGetLastError();
