@@ -208,19 +208,29 @@ __global__ __launch_bounds__(256) void transpose_batch_kernel(TransposeBatch tb)
   transpose_tile<AT>(a, b0, n0, tile, mr);
 }
 
-template <typename AT>
+template <typename AT, int RPT>
 __global__ __launch_bounds__(256) void ln_apply_kernel(LnApplyBatch lb) {
+  __shared__ float mom[FADE_GROUP_ROWS_MAX][2];
   const LnApplyArgs &a = lb.a[blockIdx.y];
   const int chunks = lb.Dh / 8;
+  const int r0 = fade_group_moments<RPT>(a.stats, lb.stats_n, lb.Dh, chunks, lb.B, mom);
   const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (t >= (size_t)lb.B * chunks) return;
-  const int b = (int)(t / chunks), c8 = (int)(t % chunks) * 8;
-  float mean, rstd, v[8];
-  moments(a.stats + (size_t)b * lb.stats_n * 2, lb.stats_n, lb.Dh, mean, rstd);
-  ld8<AT>(static_cast<const AT *>(a.src) + (size_t)b * lb.Dh + c8, v);
+  if (t >= (size_t)((lb.B + RPT - 1) / RPT) * chunks) return;
+  const int b0 = (int)(t / chunks) * RPT, c8 = (int)(t % chunks) * 8;
+  float v[RPT][8], ga[8], be[8];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) v[i] = (v[i] - mean) * rstd * a.gamma[c8 + i] + a.beta[c8 + i];
-  st8<AT>(static_cast<AT *>(a.dst) + (size_t)b * lb.Dh + c8, v);
+  for (int i = 0; i < RPT; ++i)
+    if (b0 + i < lb.B) ld8<AT>(static_cast<const AT *>(a.src) + (size_t)(b0 + i) * lb.Dh + c8, v[i]);
+  ld8<float>(a.gamma + c8, ga);
+  ld8<float>(a.beta + c8, be);
+#pragma unroll
+  for (int i = 0; i < RPT; ++i) {
+    if (b0 + i >= lb.B) continue;
+    const float mean = mom[b0 + i - r0][0], rstd = mom[b0 + i - r0][1];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[i][j] = (v[i][j] - mean) * rstd * ga[j] + be[j];
+    st8<AT>(static_cast<AT *>(a.dst) + (size_t)(b0 + i) * lb.Dh + c8, v[i]);
+  }
 }
 
 // X_T[j*D+i][b] = LN_e(E[w_{b,j}])[i] straight from the per-symbol table (X is a gather, so is its transpose)
@@ -1110,10 +1120,16 @@ hipError_t fade_transpose(const TransposeArgs &a, int N, bool bf16, hipStream_t 
   DISPATCH_AT(bf16, transpose_kernel, dim3((a.B + 63) / 64, N / 64), dim3(256), s, a);
 }
 hipError_t fade_ln_apply(const LnApplyBatch &lb, bool bf16, hipStream_t s) {
-  if (lb.count <= 0 || lb.count > 2 || lb.Dh % 8) return hipErrorInvalidValue;
-  const dim3 grid(nblk((size_t)lb.B * (lb.Dh / 8), 256), lb.count);
-  if (bf16) hipLaunchKernelGGL(ln_apply_kernel<bf16_t>, grid, dim3(256), 0, s, lb);
-  else hipLaunchKernelGGL(ln_apply_kernel<float>, grid, dim3(256), 0, s, lb);
+  if (lb.count <= 0 || lb.count > 2 || lb.Dh % 8 || lb.Dh < 64) return hipErrorInvalidValue;
+  const int rpt = fade_rows_per_thread((long long)lb.B * lb.count, lb.Dh / 8);
+  const dim3 grid(nblk((size_t)((lb.B + rpt - 1) / rpt) * (lb.Dh / 8), 256), lb.count);
+  if (rpt == 4) {
+    if (bf16) hipLaunchKernelGGL((ln_apply_kernel<bf16_t, 4>), grid, dim3(256), 0, s, lb);
+    else hipLaunchKernelGGL((ln_apply_kernel<float, 4>), grid, dim3(256), 0, s, lb);
+  } else {
+    if (bf16) hipLaunchKernelGGL((ln_apply_kernel<bf16_t, 1>), grid, dim3(256), 0, s, lb);
+    else hipLaunchKernelGGL((ln_apply_kernel<float, 1>), grid, dim3(256), 0, s, lb);
+  }
   return hipGetLastError();
 }
 hipError_t fade_transpose_batch(const TransposeBatch &tb, bool bf16, hipStream_t s) {

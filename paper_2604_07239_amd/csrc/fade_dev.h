@@ -123,6 +123,25 @@ __device__ __forceinline__ void fade_row_moments(const float *stats, int stats_n
   rstd = 1.0f / sqrtf(fmaxf(q * inv - mean * mean, 0.0f) + 1e-5f);
 }
 
+// Row-wise element kernels: thread t = blockIdx.x * 256 + tid owns the 8-wide chunk t % chunks of the RPT rows of row
+// group t / chunks (RPT = 4 for tall inputs: one fetch of the per-column vectors serves 4 rows, whose loads are in flight
+// together; RPT = 1 when there are too few rows to fill the chip that way). The moments of the rows a workgroup covers
+// are formed once per row and shared through LDS instead of once per thread. mom must hold RPT * (256 / chunks + 2)
+// rows (chunks >= 8: at most FADE_GROUP_ROWS_MAX). Returns the workgroup's first row; ends with a barrier.
+#define FADE_GROUP_ROWS_MAX 136
+template <int RPT>
+__device__ __forceinline__ int fade_group_moments(const float *stats, int stats_n, int width, int chunks, int rows, float (*mom)[2]) {
+  const long long t0 = (long long)blockIdx.x * 256;
+  const int g0 = (int)(t0 / chunks), g1 = (int)((t0 + 255) / chunks);
+  const int r0 = g0 * RPT, nr = (g1 - g0 + 1) * RPT;
+  for (int r = threadIdx.x; r < nr; r += 256)
+    if (r0 + r < rows) fade_row_moments(stats + (size_t)(r0 + r) * stats_n * 2, stats_n, width, mom[r][0], mom[r][1]);
+  __syncthreads();
+  return r0;
+}
+// rows per thread for `rows` rows of `chunks` chunks: 4 once that still leaves four workgroups for every compute unit
+inline int fade_rows_per_thread(long long rows, int chunks) { return (rows / 4) * chunks / 256 >= 1024 ? 4 : 1; }
+
 // ---------------------------------------------------------------------------------------------------
 // activation arithmetic shared by every kernel (encoder and decoder run the same code, so they agree bit for bit)
 // ---------------------------------------------------------------------------------------------------

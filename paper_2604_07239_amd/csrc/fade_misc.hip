@@ -307,24 +307,48 @@ template <> __device__ __forceinline__ void ldv8<float>(const float *p, float v[
 #pragma unroll
   for (int i = 0; i < 4; ++i) { v[i] = a[i]; v[4 + i] = b[i]; }
 }
-template <typename AT>
+template <typename AT> __device__ __forceinline__ void stv8(AT *p, const float v[8]);
+template <> __device__ __forceinline__ void stv8<bf16_t>(bf16_t *p, const float v[8]) {
+  bf16x8 r;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) r[i] = (bf16_t)v[i];
+  *reinterpret_cast<bf16x8 *>(p) = r;
+}
+template <> __device__ __forceinline__ void stv8<float>(float *p, const float v[8]) {
+  f32x4 a, b;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { a[i] = v[i]; b[i] = v[4 + i]; }
+  *reinterpret_cast<f32x4 *>(p) = a;
+  *reinterpret_cast<f32x4 *>(p + 4) = b;
+}
+template <typename AT, int RPT>
 __global__ __launch_bounds__(256) void hout_kernel(HoutArgs a) {
+  __shared__ float mom[FADE_GROUP_ROWS_MAX][2];
   const int chunks = a.Dh / 8;
+  const int r0 = fade_group_moments<RPT>(a.stats, a.stats_n, a.Dh, chunks, a.B, mom);
   const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (t >= (size_t)a.B * chunks) return;
-  const int b = (int)(t / chunks), c8 = (int)(t % chunks) * 8;
-  float mean, rstd;
-  moments_from_partials(a.stats + (size_t)b * a.stats_n * 2, a.stats_n, a.Dh, mean, rstd);
-  const size_t o = (size_t)b * a.Dh + c8;
-  float v[8], hc[8], ga[8], be[8];
-  ldv8<AT>(static_cast<const AT *>(a.V) + o, v);
-  ldv8<AT>(static_cast<const AT *>(a.Hc) + o, hc);
+  if (t >= (size_t)((a.B + RPT - 1) / RPT) * chunks) return;
+  const int b0 = (int)(t / chunks) * RPT, c8 = (int)(t % chunks) * 8;
+  float v[RPT][8], hc[RPT][8], ga[8], be[8];
+#pragma unroll
+  for (int i = 0; i < RPT; ++i) {
+    if (b0 + i >= a.B) continue;
+    const size_t o = (size_t)(b0 + i) * a.Dh + c8;
+    ldv8<AT>(static_cast<const AT *>(a.V) + o, v[i]);
+    ldv8<AT>(static_cast<const AT *>(a.Hc) + o, hc[i]);
+  }
   ldv8<float>(a.gamma + c8, ga);
   ldv8<float>(a.beta + c8, be);
   const float lam = a.lam[0];
-  AT *out = static_cast<AT *>(a.Hout) + o;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) out[i] = (AT)(gelu_f((v[i] - mean) * rstd * ga[i] + be[i]) + lam * hc[i]);
+  for (int i = 0; i < RPT; ++i) {
+    if (b0 + i >= a.B) continue;
+    const float mean = mom[b0 + i - r0][0], rstd = mom[b0 + i - r0][1];
+    float out[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) out[j] = gelu_f((v[i][j] - mean) * rstd * ga[j] + be[j]) + lam * hc[i][j];
+    stv8<AT>(static_cast<AT *>(a.Hout) + (size_t)(b0 + i) * a.Dh + c8, out);
+  }
 }
 
 // Eq. 8 with its gate switched off (ablation level 3): out = x + lam * y, 8 bf16 per thread.
@@ -884,9 +908,16 @@ hipError_t fade_residual_add(const void *x, const void *y, const float *lam, voi
   return hipGetLastError();
 }
 hipError_t fade_hout(const HoutArgs &a, bool bf16, hipStream_t s) {
-  const dim3 grid(blocks_for((size_t)a.B * (a.Dh / 8), 256));
-  if (bf16) hipLaunchKernelGGL(hout_kernel<bf16_t>, grid, dim3(256), 0, s, a);
-  else hipLaunchKernelGGL(hout_kernel<float>, grid, dim3(256), 0, s, a);
+  if (a.Dh % 8 || a.Dh < 64 || a.B <= 0) return hipErrorInvalidValue;
+  const int rpt = fade_rows_per_thread(a.B, a.Dh / 8);
+  const dim3 grid(blocks_for((size_t)((a.B + rpt - 1) / rpt) * (a.Dh / 8), 256));
+  if (rpt == 4) {
+    if (bf16) hipLaunchKernelGGL((hout_kernel<bf16_t, 4>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((hout_kernel<float, 4>), grid, dim3(256), 0, s, a);
+  } else {
+    if (bf16) hipLaunchKernelGGL((hout_kernel<bf16_t, 1>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((hout_kernel<float, 1>), grid, dim3(256), 0, s, a);
+  }
   return hipGetLastError();
 }
 hipError_t fade_preshuffle_t(const float *W0, const float *W1, int K, int N, int interleave, void *out, hipStream_t s) {
