@@ -672,7 +672,7 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
   const int B = (int)d.B, Dh = (int)d.Dh, De = (int)d.De, dl = (int)d.dl, SN = (int)(d.Dh / FADE_STATS_BN);
   float *G = c->grad;
   auto Gp = [&](int id) { return G + c->lay.off[id]; };
-  const int RB = (B + fade_rows_per_block() - 1) / fade_rows_per_block();
+  const int RB = (B + fade_rows_per_block(B) - 1) / fade_rows_per_block(B);
   ReduceBatch rq{};  // second-stage reductions nothing in here waits for: one launch before Adam
   int rc;
   // ablation level: the head's gradient enters the chain at the level's feature vector; the stages behind it do not run
@@ -1148,7 +1148,7 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
     TRY_ALLOC(dev_alloc(c, &c->dxt, d.B * d.D));
     TRY_ALLOC(dev_alloc(c, &c->row_dlam, 3 * d.B));
     TRY_ALLOC(dev_alloc(c, &c->win_copy, d.B * d.T));
-    const size_t tokens = d.B * d.T, rb = (d.B + fade_rows_per_block() - 1) / fade_rows_per_block();
+    const size_t tokens = d.B * d.T, rb = (d.B + fade_rows_per_block((int)d.B) - 1) / fade_rows_per_block((int)d.B);
     c->emb_blocks = (int)std::min<size_t>(256, (tokens + 127) / 128);
     TRY_ALLOC(dev_alloc(c, &c->conv_part, (tokens + 127) / 128 * (d.k * d.D + 1) * d.D));
     TRY_ALLOC(dev_alloc(c, &c->tok_part, 256 * 4 * d.D));

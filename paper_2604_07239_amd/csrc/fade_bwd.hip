@@ -254,7 +254,11 @@ __global__ __launch_bounds__(256) void embed_t_kernel(WinSrc ws, int B, int Bp, 
 // row-wise backward passes (one workgroup per stream; a thread owns 8-wide chunks tid, tid+256, ...)
 // ---------------------------------------------------------------------------------------------------
 // a thread of the row kernels owns one 8-wide chunk: D_h <= 2048
-constexpr int kRowsPerBlock = 4; // rows handled by one workgroup; its LayerNorm gain / shift partial sums cover those rows
+// Rows handled by one workgroup of the row kernels; its LayerNorm gain / shift partial sums cover those rows. Few rows per
+// workgroup while the batch is small (more workgroups to hide the two dependent rounds of loads), four for large batches
+// (fewer partial sums to write and add up). B = 1024: the three kernels 15.5 / 20.0 / 26.7 us with four rows, 13.7 / 14.8 /
+// 21.3 with two (one row: 13.3 / 14.4 / 20.1, but 8 us more in the reduction of twice as many partial sums).
+inline int rows_per_block(int B) { return B <= 2048 ? 2 : 4; }
 
 // Several row sums at once over a 256-thread workgroup (same fixed order as block_sum); red holds 4 * N floats.
 template <int N>
@@ -274,13 +278,12 @@ __device__ __forceinline__ void block_sum_n(float (&v)[N], float *red) {
   for (int k = 0; k < N; ++k) v[k] = (red[k] + red[N + k]) + (red[2 * N + k] + red[3 * N + k]);
 }
 
-// The row kernels below take their kRowsPerBlock rows through each phase together (all loads of a phase in flight at once,
+// The row kernels below take their R rows through each phase together (all loads of a phase in flight at once,
 // one workgroup reduction per phase for all rows), not row after row: they are bound by memory latency, not by arithmetic.
 
 // Eq. 10 backward: dnv = dH * psi'(nv), LN backward -> dV; dH_coarse = lambda_o dH; row part of d lambda_o.
-template <typename AT>
+template <typename AT, int R>
 __global__ __launch_bounds__(256) void bwd_out_kernel(BwdOutArgs a) {
-  constexpr int R = kRowsPerBlock;
   __shared__ float red[4 * 3 * R];
   const int tid = threadIdx.x, nch = a.Dh / 8;
   const bool mine = tid < nch;
@@ -364,9 +367,8 @@ __global__ __launch_bounds__(256) void bwd_geglu_kernel(int B, int De, const AT 
 // LN (Eq. 9) backward into dH_coarse, then Eq. 8 backward element-wise:
 // dH_a = dHc * s, d(gate logits) = dHc * H_a * s (1 - s), dH_mix = lambda_c dHc, row part of d lambda_c.
 // Ablation levels: a.du == NULL: no refiner behind H_coarse, dHc arrives complete; a.sg == NULL: Eq. 8 without its gate.
-template <typename AT>
+template <typename AT, int R>
 __global__ __launch_bounds__(256) void bwd_gate_kernel(BwdGateArgs a) {
-  constexpr int R = kRowsPerBlock;
   __shared__ float red[4 * 2 * R];
   const int tid = threadIdx.x, nch = a.Dh / 8;
   const bool mine = tid < nch;
@@ -449,9 +451,8 @@ __global__ __launch_bounds__(256) void bwd_gate_kernel(BwdGateArgs a) {
 // d(conv pre-act) = dHl psi'(cv), dX = lambda_m dHg, row part of d lambda_m.
 // Ablation levels: a.dnc == NULL: nothing behind H_mix but what dHmix1 (+ dHmix2) carry; a.dHmix2 == NULL: no gate product;
 // a.alpha == NULL: the global stream alone (alpha = 1: no local stream, no router), dar / dcv are not written.
-template <typename AT>
+template <typename AT, int R>
 __global__ __launch_bounds__(256) void bwd_mix_kernel(BwdMixArgs a) {
-  constexpr int R = kRowsPerBlock;
   __shared__ float red[4 * 2 * R];
   const int tid = threadIdx.x, nch = a.Dh / 8;
   const bool mine = tid < nch;
@@ -1151,16 +1152,31 @@ hipError_t fade_embed_t(const WinSrc &ws, int B, int Bp, int T, int D, const voi
   else hipLaunchKernelGGL(embed_t_kernel<float>, dim3(nblk(n, 256)), dim3(256), 0, s, ws, B, Bp, T, D, static_cast<const float *>(tab), static_cast<float *>(XT));
   return hipGetLastError();
 }
-hipError_t fade_bwd_out(const BwdOutArgs &a, bool bf16, hipStream_t s) { DISPATCH_AT(bf16, bwd_out_kernel, dim3((a.B + kRowsPerBlock - 1) / kRowsPerBlock), dim3(256), s, a); }
+#define DISPATCH_ROWS(bf16, KERNEL, B, stream, args)                                                                             \
+  do {                                                                                                                            \
+    const int R_ = rows_per_block(B);                                                                                             \
+    const dim3 grid_((B + R_ - 1) / R_);                                                                                          \
+    if (bf16) {                                                                                                                   \
+      if (R_ == 1) hipLaunchKernelGGL((KERNEL<bf16_t, 1>), grid_, dim3(256), 0, stream, args);                                    \
+      else if (R_ == 2) hipLaunchKernelGGL((KERNEL<bf16_t, 2>), grid_, dim3(256), 0, stream, args);                               \
+      else hipLaunchKernelGGL((KERNEL<bf16_t, 4>), grid_, dim3(256), 0, stream, args);                                            \
+    } else {                                                                                                                      \
+      if (R_ == 1) hipLaunchKernelGGL((KERNEL<float, 1>), grid_, dim3(256), 0, stream, args);                                     \
+      else if (R_ == 2) hipLaunchKernelGGL((KERNEL<float, 2>), grid_, dim3(256), 0, stream, args);                                \
+      else hipLaunchKernelGGL((KERNEL<float, 4>), grid_, dim3(256), 0, stream, args);                                             \
+    }                                                                                                                             \
+    return hipGetLastError();                                                                                                     \
+  } while (0)
+hipError_t fade_bwd_out(const BwdOutArgs &a, bool bf16, hipStream_t s) { DISPATCH_ROWS(bf16, bwd_out_kernel, a.B, s, a); }
 hipError_t fade_bwd_geglu(int B, int De, const void *dHexp, const void *eg, const void *ev, void *dE, bool bf16, hipStream_t s) {
   const size_t n = (size_t)B * (De / 8);
   if (bf16) hipLaunchKernelGGL(bwd_geglu_kernel<bf16_t>, dim3(nblk(n, 256)), dim3(256), 0, s, B, De, static_cast<const bf16_t *>(dHexp), static_cast<const bf16_t *>(eg), static_cast<const bf16_t *>(ev), static_cast<bf16_t *>(dE));
   else hipLaunchKernelGGL(bwd_geglu_kernel<float>, dim3(nblk(n, 256)), dim3(256), 0, s, B, De, static_cast<const float *>(dHexp), static_cast<const float *>(eg), static_cast<const float *>(ev), static_cast<float *>(dE));
   return hipGetLastError();
 }
-hipError_t fade_bwd_gate(const BwdGateArgs &a, bool bf16, hipStream_t s) { DISPATCH_AT(bf16, bwd_gate_kernel, dim3((a.B + kRowsPerBlock - 1) / kRowsPerBlock), dim3(256), s, a); }
-hipError_t fade_bwd_mix(const BwdMixArgs &a, bool bf16, hipStream_t s) { DISPATCH_AT(bf16, bwd_mix_kernel, dim3((a.B + kRowsPerBlock - 1) / kRowsPerBlock), dim3(256), s, a); }
-int fade_rows_per_block() { return kRowsPerBlock; }
+hipError_t fade_bwd_gate(const BwdGateArgs &a, bool bf16, hipStream_t s) { DISPATCH_ROWS(bf16, bwd_gate_kernel, a.B, s, a); }
+hipError_t fade_bwd_mix(const BwdMixArgs &a, bool bf16, hipStream_t s) { DISPATCH_ROWS(bf16, bwd_mix_kernel, a.B, s, a); }
+int fade_rows_per_block(int B) { return rows_per_block(B); }
 hipError_t fade_reduce_rows(int P, int N, const float *part, float *out, hipStream_t s) {
   hipLaunchKernelGGL(reduce_rows_kernel, dim3(nblk((size_t)N, 32)), dim3(256), 0, s, P, N, part, out);
   return hipGetLastError();

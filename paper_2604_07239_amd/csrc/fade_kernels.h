@@ -227,7 +227,7 @@ hipError_t fade_bwd_out(const BwdOutArgs &a, bool bf16, hipStream_t s);
 hipError_t fade_bwd_geglu(int B, int De, const void *dHexp, const void *eg, const void *ev, void *dE, bool bf16, hipStream_t s);
 hipError_t fade_bwd_gate(const BwdGateArgs &a, bool bf16, hipStream_t s);
 hipError_t fade_bwd_mix(const BwdMixArgs &a, bool bf16, hipStream_t s);
-int fade_rows_per_block();
+int fade_rows_per_block(int B);  // rows per workgroup of the backward row kernels at batch size B
 hipError_t fade_reduce_rows(int P, int N, const float *part, float *out, hipStream_t s);
 // Second stages (out[n] = sum over p < P of part[p][n], rows added in a fixed order) that nothing inside the backward pass
 // waits for are queued here and run as ONE launch just before Adam. The stage-1 launchers below take the queue.
