@@ -602,6 +602,17 @@ template <typename AT>
 __global__ __launch_bounds__(256) void bwd_cci_kernel(BwdCciArgs a) {
   __shared__ float dz_s[64], y_s[64];
   const int b = blockIdx.x, tid = threadIdx.x;
+  // the Adam operands of this stream (4 x 4 consecutive elements per thread and array) are requested first: nothing
+  // below depends on them until the update, so their latency runs under the dz / dy part
+  float *master = a.master + (size_t)b * 4096, *m = a.m + (size_t)b * 4096, *v = a.v + (size_t)b * 4096;
+  f32x4 w4[4], m4[4], v4[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int idx = (e * 256 + tid) * 4;
+    w4[e] = *reinterpret_cast<const f32x4 *>(master + idx);
+    m4[e] = *reinterpret_cast<const f32x4 *>(m + idx);
+    v4[e] = *reinterpret_cast<const f32x4 *>(v + idx);
+  }
   if (tid < 64) {
     float dz = 0.0f;
     for (int s0 = 0; s0 < a.splits; s0 += 8) {  // 8 partials in flight, added in split order
@@ -619,8 +630,11 @@ __global__ __launch_bounds__(256) void bwd_cci_kernel(BwdCciArgs a) {
   {  // dy[k] = row k of W_U[b] dot dz: four threads per row, 16 columns each, combined in a fixed butterfly
     const int k = tid >> 2, q = tid & 3;
     float s = 0.0f;
+    float wr[16];
+    ld8<AT>(Wc + k * 64 + q * 16, wr);
+    ld8<AT>(Wc + k * 64 + q * 16 + 8, wr + 8);
 #pragma unroll
-    for (int n = 0; n < 16; ++n) s = fmaf((float)Wc[k * 64 + q * 16 + n], dz_s[q * 16 + n], s);
+    for (int n = 0; n < 16; ++n) s = fmaf(wr[n], dz_s[q * 16 + n], s);
     s += __shfl_xor(s, 1, 64);
     s += __shfl_xor(s, 2, 64);
     if (q == 0) {
@@ -631,18 +645,25 @@ __global__ __launch_bounds__(256) void bwd_cci_kernel(BwdCciArgs a) {
   const UpdateState u = *a.u;
   if (u.na == 0) return;
   __syncthreads();  // every read of the old W_U[b] is done before it is rewritten
-  float *master = a.master + (size_t)b * 4096, *m = a.m + (size_t)b * 4096, *v = a.v + (size_t)b * 4096;
-#pragma unroll 4
-  for (int e = 0; e < 16; ++e) {
-    const int idx = e * 256 + tid, k = idx >> 6, n = idx & 63;
-    const float g = y_s[k] * dz_s[n];
-    const float mk = a.beta1 * m[idx] + (1.0f - a.beta1) * g;
-    const float vk = a.beta2 * v[idx] + (1.0f - a.beta2) * g * g;
-    m[idx] = mk;
-    v[idx] = vk;
-    const float w = master[idx] - a.lr * (mk / u.c1) / (sqrtf(vk / u.c2) + a.eps);
-    master[idx] = w;
-    Wc[idx] = (AT)w;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int idx = (e * 256 + tid) * 4, k = idx >> 6, n = idx & 63;
+    float wn[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float g = y_s[k] * dz_s[n + i];
+      const float mk = a.beta1 * m4[e][i] + (1.0f - a.beta1) * g;
+      const float vk = a.beta2 * v4[e][i] + (1.0f - a.beta2) * g * g;
+      m4[e][i] = mk;
+      v4[e][i] = vk;
+      wn[i] = w4[e][i] - a.lr * (mk / u.c1) / (sqrtf(vk / u.c2) + a.eps);
+      w4[e][i] = wn[i];
+    }
+    *reinterpret_cast<f32x4 *>(m + idx) = m4[e];
+    *reinterpret_cast<f32x4 *>(v + idx) = v4[e];
+    *reinterpret_cast<f32x4 *>(master + idx) = w4[e];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) Wc[idx + i] = (AT)wn[i];
   }
 }
 
