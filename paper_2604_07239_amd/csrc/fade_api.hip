@@ -32,7 +32,10 @@ struct Layout {
 };
 
 // canonical: the blob of the C ABI, tensors back to back. Device arrays (master, gradient, Adam moments) start every tensor on
-// a 16-byte boundary instead (only the three scalar residual scales get padding), so that kernels can use 16-byte accesses.
+// a 16-byte boundary instead (only the three scalar residual scales get padding), so that kernels can use 16-byte accesses,
+// and the big matrices on a 128-byte boundary: the Adam pass walks them in 64 x 64 blocks whose 256-byte row pieces then
+// cover two whole cache lines instead of parts of three. Padding comes in front of a matrix only, so the neighbours that
+// some kernels write as one run (a LayerNorm's gain and shift, W_g and W_v, W_conv and b_conv) stay adjacent.
 Layout make_layout(const Dims &d, bool canonical) {
   const size_t n[P_COUNT] = {
       256 * d.D, d.D, d.D, d.D, d.D, d.D * d.c, d.D * d.c, d.Dc * d.Dh, 1, d.k * d.D * d.D, d.D, d.Dh * d.Dh, d.Dh, d.Dh,
@@ -40,7 +43,11 @@ Layout make_layout(const Dims &d, bool canonical) {
       d.Dh, d.Dh, 1, d.Dh * 256, 256};
   Layout L;
   size_t o = 0;
-  for (int i = 0; i < P_COUNT; ++i) { L.off[i] = o; o += canonical ? n[i] : (n[i] + 3) / 4 * 4; L.len[i] = n[i]; }
+  for (int i = 0; i < P_COUNT; ++i) {
+    const bool big = i == P_WM || i == P_WR || i == P_WDOWN || i == P_WU || i == P_WUP || i == P_WC || i == P_WFG || i == P_WFV || i == P_WF || i == P_WO;
+    if (!canonical && big) o = (o + 31) / 32 * 32;
+    L.off[i] = o; o += canonical ? n[i] : (n[i] + 3) / 4 * 4; L.len[i] = n[i];
+  }
   L.off[P_COUNT] = o;
   return L;
 }
