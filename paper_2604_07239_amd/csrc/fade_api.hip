@@ -761,9 +761,9 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
   }
   {  // Eq. 8's gate product and Eq. 7's Up
     PhaseGemms ph;
-    if (level >= 4) {
-      ph.add(GEMM_W_TN, args_w(c, c->Hmix, Dh, c->LT[3], Dh, c->dac, Dh, P_WC));
+    if (level >= 4) {  // the activation gradient first: its workgroups have the longest chain (K = D_h against K = batch)
       ph.add(GEMM_X_STORE, args_x(c, c->dac, Dh, Dh, c->WT_c, c->P(P_WC), Dh, c->dHmix2));
+      ph.add(GEMM_W_TN, args_w(c, c->Hmix, Dh, c->LT[3], Dh, c->dac, Dh, P_WC));
     }
     ph.add(GEMM_W_TN, args_w(c, c->z, dl, c->LT[4], dl, c->dHa, Dh, P_WUP));
     GemmArgs g{};
@@ -805,8 +805,8 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
   {  // router and global stream
     PhaseGemms ph;
     if (level >= 2) {
-      ph.add(GEMM_W_TN, args_w(c, c->X, Dh, c->LT[7], Dh, c->dar, Dh, P_WR));
       ph.add(GEMM_X_STORE, args_x(c, c->dar, Dh, Dh, c->WT_r, c->P(P_WR), Dh, c->dX2));
+      ph.add(GEMM_W_TN, args_w(c, c->X, Dh, c->LT[7], Dh, c->dar, Dh, P_WR));
     }
     ph.add(GEMM_W_TN, args_w(c, c->M, (int)d.Dc, c->LT[6], (int)d.Dc, c->dhm, Dh, P_WM));
     if ((rc = run_phase(c, "gemms_router_global", ph))) return rc;

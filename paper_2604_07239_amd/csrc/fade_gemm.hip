@@ -1083,7 +1083,10 @@ hipError_t fade_gemm_group_add(GemmGroup &gg, int op, const GemmArgs &g) {
   int kind, bm, bn, splits = 1;
   if (op == GEMM_X_STORE) {
     bm = 64;
-    if (g.N % 128 == 0 && ((g.M + 127) / 128) * (g.N / 128) >= 128 && fade_gemm_tune() != 9) { kind = GK_STORE_128x128; bm = 128; bn = 128; }
+    const int t128 = g.N % 128 == 0 ? ((g.M + 127) / 128) * (g.N / 128) : 0;
+    // 128 x 128 tiles from 256 of them on, or from 128 when the contraction is long (then the bytes per flop matter more than
+    // the number of workgroups: B = 1024, K = D_h = 2048: 43 us against 48 with 64 x 128; K = 64: 12.6 against 9.0)
+    if ((t128 >= 256 || (t128 >= 128 && g.K >= 1024)) && fade_gemm_tune() != 9) { kind = GK_STORE_128x128; bm = 128; bn = 128; }
     else if (g.N % 128 == 0 && ((g.M + 63) / 64) * (g.N / 128) >= 128) { kind = GK_STORE_64x128; bn = 128; }
     else if (g.N % 64 == 0) { kind = GK_STORE_64x64; bn = 64; }
     else return hipErrorInvalidValue;
