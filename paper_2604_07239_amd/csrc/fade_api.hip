@@ -718,6 +718,7 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
   // head
   {
     PhaseGemms ph;
+    // within a phase the product with the longest chain of K blocks goes first (its workgroups start first)
     ph.add(GEMM_W_TN, args_w(c, feat, Dh, c->LT[0], Dh, c->dl, 256, P_WO));
     ph.add(GEMM_X_STORE, args_x(c, c->dl, 256, Dh, c->WT_o, c->P(P_WO), 256, dfeat));
     if ((rc = run_phase(c, "gemms_head", ph))) return rc;
@@ -733,8 +734,8 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
   }
   {
     PhaseGemms ph;
-    ph.add(GEMM_W_TN, args_w(c, c->Hexp, De, c->LT[1], De, c->dV, Dh, P_WF));
     ph.add(GEMM_X_STORE, args_x(c, c->dV, Dh, De, c->WT_f, c->P(P_WF), Dh, c->dHexp));
+    ph.add(GEMM_W_TN, args_w(c, c->Hexp, De, c->LT[1], De, c->dV, Dh, P_WF));
     if ((rc = run_phase(c, "gemms_fnr_out", ph))) return rc;
   }
   {  // Eq. 9
