@@ -165,6 +165,8 @@ struct fade_ctx {
   // tensor the number of ranges (1: none) and the slices [ranges][K][N]; the Adam pass adds them up
   int gsp[P_COUNT] = {};
   float *gpart[P_COUNT] = {};
+  int sp_du = 1;            // ranges of K = 2 D_e in du = dE [W_fg W_fv]^T (bf16 path, wide refiners)
+  float *du_part = nullptr;
 
   // coder and step bookkeeping
   CoderBufs cb{};
@@ -749,8 +751,15 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
   }
   {
     PhaseGemms ph;
-    ph.add(GEMM_W_TN, args_w(c, c->LT[2], Dh, c->LT[2], Dh, c->dE, 2 * De, P_WFG, P_WFV));
-    ph.add(GEMM_X_STORE, args_x(c, c->dE, 2 * De, Dh, c->WT_fgv, static_cast<const float *>(c->Wfgv_c), 2 * De, c->du));
+    GemmArgs gx = args_x(c, c->dE, 2 * De, Dh, c->WT_fgv, static_cast<const float *>(c->Wfgv_c), 2 * De, c->du);
+    if (c->sp_du > 1) {  // a long contraction (K = 2 D_e) over few output tiles: ranges of K as fp32 partials, summed by the next kernel
+      gx.splits = c->sp_du; gx.C = c->du_part;
+      ph.add(GEMM_PARTIAL, gx);
+      ph.add(GEMM_W_TN, args_w(c, c->LT[2], Dh, c->LT[2], Dh, c->dE, 2 * De, P_WFG, P_WFV));
+    } else {
+      ph.add(GEMM_W_TN, args_w(c, c->LT[2], Dh, c->LT[2], Dh, c->dE, 2 * De, P_WFG, P_WFV));
+      ph.add(GEMM_X_STORE, gx);
+    }
     if ((rc = run_phase(c, "gemms_fnr_in", ph))) return rc;
   }
   }
@@ -758,7 +767,8 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
   {  // LN of Eq. 9 + Eq. 8
     Prof p(c, "bwd_gate");
     BwdGateArgs a{};
-    a.B = B; a.Dh = Dh; a.stats_n = SN; a.ln_part = c->ln_part + (size_t)RB * 2 * Dh; a.du = level >= 5 ? c->du : nullptr; a.Hc = c->Hc; a.dHc = c->dHc;
+    a.B = B; a.Dh = Dh; a.stats_n = SN; a.ln_part = c->ln_part + (size_t)RB * 2 * Dh; a.du = level >= 5 ? c->du : nullptr;
+    if (level >= 5 && c->sp_du > 1) { a.du_part = c->du_part; a.du_splits = c->sp_du; } a.Hc = c->Hc; a.dHc = c->dHc;
     a.sg = level >= 4 ? c->sg : nullptr; a.Ha = c->Ha; a.Hmix = c->Hmix;
     a.stats = c->stats_f; a.gamma = c->P(P_GAMMA_F); a.lam = c->P(P_LAMBDA_C); a.dHa = c->dHa; a.dac = c->dac; a.dHmix = c->dHmix1;
     a.row_dlam = c->row_dlam + B;
@@ -1146,6 +1156,10 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
         TRY_ALLOC(dev_alloc(c, &c->gpart[w.id], (size_t)sp * c->lay.len[w.id]));
         if (w.pair >= 0) { c->gsp[w.pair] = sp; TRY_ALLOC(dev_alloc(c, &c->gpart[w.pair], (size_t)sp * c->lay.len[w.pair])); }
       }
+    }
+    if (c->bf16 && 2 * d.De >= 4096 && d.Dh % 128 == 0) {
+      c->sp_du = pick_splits((int)((d.B + 127) / 128 * (d.Dh / 128)) / 2, (int)(2 * d.De / 64 / 4), 16);  // ~384+ workgroups, ranges of 8+ blocks
+      if (c->sp_du > 1) TRY_ALLOC(dev_alloc(c, &c->du_part, (size_t)c->sp_du * d.B * d.Dh));
     }
     c->sp_dz = c->bf16 ? pick_splits((int)((d.B + 63) / 64), (int)(d.Dh / 64), 16) : 1;
     TRY_ALLOC(dev_alloc(c, &c->dz_part, (size_t)c->sp_dz * d.B * d.dl));

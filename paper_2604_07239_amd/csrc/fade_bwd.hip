@@ -391,7 +391,18 @@ __global__ __launch_bounds__(256) void bwd_gate_kernel(BwdGateArgs a) {
       float du[8], hc[8];
 #pragma unroll
       for (int i = 0; i < 8; ++i) du[i] = 0.0f;
-      if (a.du) ld8<AT>(static_cast<const AT *>(a.du) + base, du);
+      if (a.du_part) {
+        for (int sp = 0; sp < a.du_splits; ++sp) {
+          float pv[8];
+          ld8<float>(a.du_part + (size_t)sp * a.B * a.Dh + base, pv);
+#pragma unroll
+          for (int i = 0; i < 8; ++i) du[i] += pv[i];
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) du[i] = (float)(AT)du[i];  // the value the unsplit product would have stored
+      } else if (a.du) {
+        ld8<AT>(static_cast<const AT *>(a.du) + base, du);
+      }
       ld8<AT>(static_cast<const AT *>(a.Hc) + base, hc);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {

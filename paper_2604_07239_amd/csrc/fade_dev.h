@@ -88,7 +88,7 @@ struct GemmArgs {
 
 // A grouped launch: up to 4 independent products, each with the kernel body named by kind[]; blocks [first_block[p],
 // first_block[p + 1]) work on problem p (tiles[p] output tiles x splits[p] ranges of K).
-enum { GK_STORE_64x128 = 0, GK_STORE_64x64, GK_STORE_128x128, GK_PARTIAL_64x64, GK_TN_64x128, GK_TN_128x128, GK_TN_64x64 };
+enum { GK_STORE_64x128 = 0, GK_STORE_64x64, GK_STORE_128x128, GK_PARTIAL_64x64, GK_PARTIAL_128x128, GK_TN_64x128, GK_TN_128x128, GK_TN_64x64 };
 struct GemmGroup {
   int count;
   int kind[4], tiles[4], splits[4], first_block[5];

@@ -823,6 +823,7 @@ __device__ __forceinline__ void group_body(const GemmGroup &gg) {
     case GK_STORE_128x128:  pipe_body<128, 128, STAGES, EPI_STORE, false>(g, local, 0, 1); break;
     case GK_STORE_64x64:    pipe_body<64, 64, STAGES, EPI_STORE, false>(g, local, 0, 1); break;
     case GK_PARTIAL_64x64:  pipe_body<64, 64, STAGES, EPI_PARTIAL, false>(g, local % tiles, local / tiles, gg.splits[p]); break;
+    case GK_PARTIAL_128x128: pipe_body<128, 128, STAGES, EPI_PARTIAL, false>(g, local % tiles, local / tiles, gg.splits[p]); break;
     case GK_TN_64x128:      tn_body<64, 128, STAGES>(g, local % tiles, local / tiles, gg.splits[p]); break;
     case GK_TN_128x128:     tn_body<128, 128, STAGES>(g, local % tiles, local / tiles, gg.splits[p]); break;
     case GK_TN_64x64:       tn_body<64, 64, STAGES>(g, local % tiles, local / tiles, gg.splits[p]); break;
@@ -1052,7 +1053,7 @@ size_t group_kind_lds(int kind, int stages) {  // the larger of the operand ring
   size_t ring, tile;
   switch (kind) {
     case GK_STORE_64x128: case GK_TN_64x128: ring = 8192 + 16384; tile = 64 * 132 * 4; break;
-    case GK_TN_128x128: case GK_STORE_128x128: ring = 16384 + 16384; tile = 128 * 132 * 4; break;
+    case GK_TN_128x128: case GK_STORE_128x128: case GK_PARTIAL_128x128: ring = 16384 + 16384; tile = 128 * 132 * 4; break;
     default: ring = 8192 + 8192; tile = 64 * 68 * 4; break;  // the 64 x 64 kinds
   }
   ring *= (size_t)stages;
@@ -1077,7 +1078,7 @@ int fade_gemm_tn_tiles(int M, int N) {
 }
 
 // Append one product to a group; the kernel body is chosen from the operation and the shape. op is one of GEMM_X_STORE
-// (C = A W, W as fragments), GEMM_PARTIAL (split-K partials, N = 64) and GEMM_W_TN (dW from row-major operands).
+// (C = A W, W as fragments), GEMM_PARTIAL (split-K partials [splits][M][N], fp32) and GEMM_W_TN (dW from row-major operands).
 hipError_t fade_gemm_group_add(GemmGroup &gg, int op, const GemmArgs &g) {
   if (gg.count >= 4 || g.M <= 0 || g.K <= 0 || g.K % 64 || g.lda % 8) return hipErrorInvalidValue;
   int kind, bm, bn, splits = 1;
@@ -1086,13 +1087,17 @@ hipError_t fade_gemm_group_add(GemmGroup &gg, int op, const GemmArgs &g) {
     const int t128 = g.N % 128 == 0 ? ((g.M + 127) / 128) * (g.N / 128) : 0;
     // 128 x 128 tiles from 256 of them on, or from 128 when the contraction is long (then the bytes per flop matter more than
     // the number of workgroups: B = 1024, K = D_h = 2048: 43 us against 48 with 64 x 128; K = 64: 12.6 against 9.0)
-    if ((t128 >= 256 || (t128 >= 128 && g.K >= 1024)) && fade_gemm_tune() != 9) { kind = GK_STORE_128x128; bm = 128; bn = 128; }
+    // a very long contraction with few output tiles (du = dE [W_fg W_fv]^T at D_e = 8192: K = 16384, 4096 x 512 outputs) is a
+    // chain of hundreds of K blocks per workgroup: small tiles, many workgroups (D_e = 8192, B = 4096: that phase 327 -> 2xx us)
+    if (g.K >= 4096 && g.N % 64 == 0 && t128 < 256) { kind = GK_STORE_64x64; bn = 64; }
+    else if ((t128 >= 256 || (t128 >= 128 && g.K >= 1024)) && fade_gemm_tune() != 9) { kind = GK_STORE_128x128; bm = 128; bn = 128; }
     else if (g.N % 128 == 0 && ((g.M + 63) / 64) * (g.N / 128) >= 128) { kind = GK_STORE_64x128; bn = 128; }
     else if (g.N % 64 == 0) { kind = GK_STORE_64x64; bn = 64; }
     else return hipErrorInvalidValue;
   } else if (op == GEMM_PARTIAL) {
-    if (g.N % 64) return hipErrorInvalidValue;
-    kind = GK_PARTIAL_64x64; bm = 64; bn = 64;
+    if (g.N % 64 || g.sum_splits) return hipErrorInvalidValue;
+    if (g.N % 128 == 0) { kind = GK_PARTIAL_128x128; bm = 128; bn = 128; }
+    else { kind = GK_PARTIAL_64x64; bm = 64; bn = 64; }
     splits = g.splits > 1 ? g.splits : 1;
     if (g.K % (splits * 64)) return hipErrorInvalidValue;
   } else if (op == GEMM_W_TN) {

@@ -171,6 +171,8 @@ struct BwdGateArgs {
   const float *stats, *gamma, *lam;
   void *dHa, *dac, *dHmix;
   float *row_dlam;
+  const float *du_part;  // instead of du: split-K partials [du_splits][B][Dh] of the product that forms it, added here in range order
+  int du_splits;
 };
 struct BwdMixArgs {
   int B, Dh, stats_n;
