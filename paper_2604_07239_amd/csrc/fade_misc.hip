@@ -140,17 +140,33 @@ __global__ __launch_bounds__(256) void embed_cache_kernel(EmbedArgs a) {
   }
   // Eq. 2: shift the cache left by one slot (through registers, so the move is safe in place) ...
   AT *M = static_cast<AT *>(a.M) + (size_t)b * a.Dc;
-  AT keep[16];  // D_cache <= 4096
+  if (a.c % V == 0) {  // wide slots: the shift is a whole number of 16-byte pieces
+    const int np = a.Dc / V, sh = a.c / V;
+    piece_t kp[4];  // D_cache <= 4096: at most 1024 pieces
 #pragma unroll
-  for (int q = 0; q < 16; ++q) {
-    const int idx = q * 256 + tid;
-    if (idx < a.Dc) keep[q] = M[idx];
-  }
-  __syncthreads();
+    for (int q = 0; q < 4; ++q) {
+      const int idx = q * 256 + tid;
+      if (idx < np) kp[q] = reinterpret_cast<const piece_t *>(M)[idx];
+    }
+    __syncthreads();
 #pragma unroll
-  for (int q = 0; q < 16; ++q) {
-    const int idx = q * 256 + tid;
-    if (idx < a.Dc && idx >= a.c) M[idx - a.c] = keep[q];
+    for (int q = 0; q < 4; ++q) {
+      const int idx = q * 256 + tid;
+      if (idx < np && idx >= sh) reinterpret_cast<piece_t *>(M)[idx - sh] = kp[q];
+    }
+  } else {
+    AT keep[16];  // D_cache <= 4096
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      const int idx = q * 256 + tid;
+      if (idx < a.Dc) keep[q] = M[idx];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      const int idx = q * 256 + tid;
+      if (idx < a.Dc && idx >= a.c) M[idx - a.c] = keep[q];
+    }
   }
   // ... and append Eq. 1's GeGLU of the newest symbol: psi(x_t W_g) * (x_t W_v)
   if (tid < a.c) {
