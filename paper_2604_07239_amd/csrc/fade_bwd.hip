@@ -860,6 +860,75 @@ __global__ __launch_bounds__(256) void conv_grad_partial_kernel(ConvGradArgs a) 
   if (grp == 0) part[(size_t)rows * D + o] = bsum;
 }
 
+// The same on the matrix cores (bf16 activations, D = 32): per 128-token chunk, dW_conv[r] (32 x 32) = X_r^T dcv with X_r the
+// input tile shifted by tap r, a contraction over the tokens. Both operands sit in LDS row-major as they are in memory
+// (bf16, 64 bytes per token, the input tile with its zero rows in front of every stream) and are read with the transposing
+// LDS load (see the weight-gradient kernel in fade_gemm.hip: a lane supplies the address of 4 consecutive values of ITS
+// row, so the rows of one fragment need not be equidistant, which is what the per-stream zero rows require). Wavefront r
+// owns tap r; wavefront 0 also forms the bias gradient as a product with a fragment of ones. bf16 x bf16 products are exact in
+// fp32, so this differs from the scalar kernel in summation order only.
+__global__ __launch_bounds__(256) void conv_grad_mfma_kernel(ConvGradArgs a) {
+  typedef __attribute__((ext_vector_type(4))) short i16x4;
+  typedef __attribute__((ext_vector_type(8))) short i16x8;
+  constexpr int D = 32, PITCH = 64, XROWS = 128 + 3 * 32;  // taps <= 4, T >= 4: at most 32 streams x 3 zero rows
+  __shared__ __attribute__((aligned(16))) unsigned char xs[XROWS * PITCH];
+  __shared__ __attribute__((aligned(16))) unsigned char ds[128 * PITCH];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, pad = a.taps - 1;
+  const int lgT = 31 - __builtin_clz(a.T), Tm = a.T - 1, Tp = a.T + pad;
+  const long long tokens = (long long)a.B * a.T, nchunks = (tokens + 127) / 128;
+  for (int e = tid; e < XROWS * PITCH / 16; e += 256) reinterpret_cast<f32x4 *>(xs)[e] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+  f32x16 acc, accb;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) { acc[e] = 0.0f; accb[e] = 0.0f; }
+  bf16x8 ones;
+#pragma unroll
+  for (int q = 0; q < 8; ++q) ones[q] = (bf16_t)1.0f;
+  // this lane's part of a fragment: rows (tokens) 8 (lane / 32) + (lane % 16) / 4 and 4 further, 4 columns from byte colb on
+  const int s16 = lane & 15, tk = (lane >> 5) * 8 + (s16 >> 2), mh = (lane >> 4) & 1;
+  const int colb = ((2 * mh + ((s16 & 3) >> 1)) << 4) + (s16 & 1) * 8;
+  auto prow = [&](int tl) { return (tl >> lgT) * Tp + (tl & Tm); };  // row of token tl's tap 0 in the padded tile
+  auto tr_load = [](const unsigned char *p) { return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)p); };
+  const bf16_t *XL = static_cast<const bf16_t *>(a.XL), *dcv = static_cast<const bf16_t *>(a.dcv);
+  for (long long chunk = blockIdx.x; chunk < nchunks; chunk += gridDim.x) {
+    const long long t0 = chunk * 128;
+    __syncthreads();  // the zero fill, or the previous chunk's reads, are done
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {  // 128 tokens x 4 pieces of 16 bytes, for each operand
+      const int e = tid + 256 * it, tl = e >> 2, pc = e & 3;
+      f32x4 xv = {0.0f, 0.0f, 0.0f, 0.0f}, dv = xv;
+      if (t0 + tl < tokens) {
+        xv = *reinterpret_cast<const f32x4 *>(XL + (size_t)(t0 + tl) * D + pc * 8);
+        dv = *reinterpret_cast<const f32x4 *>(dcv + (size_t)(t0 + tl) * D + pc * 8);
+      }
+      *reinterpret_cast<f32x4 *>(xs + (prow(tl) + pad) * PITCH + pc * 16) = xv;
+      *reinterpret_cast<f32x4 *>(ds + tl * PITCH + pc * 16) = dv;
+    }
+    __syncthreads();
+    if (wave < a.taps) {
+#pragma unroll 2
+      for (int ks = 0; ks < 8; ++ks) {
+        const int tl = ks * 16 + tk;
+        const i16x4 al = tr_load(xs + (prow(tl) + wave) * PITCH + colb), ah = tr_load(xs + (prow(tl + 4) + wave) * PITCH + colb);
+        const i16x4 bl = tr_load(ds + tl * PITCH + colb), bh = tr_load(ds + (tl + 4) * PITCH + colb);
+        const bf16x8 af = __builtin_bit_cast(bf16x8, (i16x8)__builtin_shufflevector(al, ah, 0, 1, 2, 3, 4, 5, 6, 7));
+        const bf16x8 bf = __builtin_bit_cast(bf16x8, (i16x8)__builtin_shufflevector(bl, bh, 0, 1, 2, 3, 4, 5, 6, 7));
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bf, acc, 0, 0, 0);
+        if (wave == 0) accb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, bf, accb, 0, 0, 0);
+      }
+    }
+  }
+  const int rows = a.taps * D;
+  float *part = a.part + (size_t)blockIdx.x * (rows + 1) * D;
+  if (wave < a.taps) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int i = (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+      part[(size_t)(wave * D + i) * D + (lane & 31)] = acc[e];
+    }
+  }
+  if (wave == 0 && lane < 32) part[(size_t)rows * D + lane] = accb[0];
+}
+
 // ---------------------------------------------------------------------------------------------------
 // the two per-token LayerNorms and the embedding, backward. For a fixed symbol s the LayerNorm backward is a LINEAR map of
 // the incoming gradient (mean, 1/sigma and x-hat depend on E[s] only), so tokens are first summed per symbol:
@@ -1242,7 +1311,8 @@ hipError_t fade_conv_grad(const ConvGradArgs &a, float *dWb, bool bf16, ReduceBa
   if (256 % a.D || a.D > 32 || a.D < 16 || 128 % a.T || a.T < 4 || a.taps > 4 || (a.taps * a.D + 256 / a.D - 1) / (256 / a.D) > 16) return hipErrorInvalidValue;
   const long long nchunks = ((long long)a.B * a.T + 127) / 128;
   const int P = (int)(nchunks < 512 ? nchunks : 512);  // 128-token chunks are dealt round-robin to at most 512 workgroups
-  if (bf16) hipLaunchKernelGGL(conv_grad_partial_kernel<bf16_t>, dim3(P), dim3(256), 0, s, a);
+  if (bf16 && a.D == 32) hipLaunchKernelGGL(conv_grad_mfma_kernel, dim3(P), dim3(256), 0, s, a);
+  else if (bf16) hipLaunchKernelGGL(conv_grad_partial_kernel<bf16_t>, dim3(P), dim3(256), 0, s, a);
   else hipLaunchKernelGGL(conv_grad_partial_kernel<float>, dim3(P), dim3(256), 0, s, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
