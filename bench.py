@@ -28,7 +28,7 @@ sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK = 2.5e15   # MI355X dense bf16, FLOP/s
 HBM_PEAK = 8.0e12         # B/s
-ROUTER_GATE_TRAFFIC_BYTES = {(2, "frozen"): int(0.5 * (346.9 + 55.3 + 345.4 + 55.5) * (1 << 20)), (2, "online"): int(0.5 * (56.4 + 53.5) * (1 << 20))}
+ROUTER_GATE_TRAFFIC_BYTES = {(2, "frozen"): int(0.5 * (320.5 + 66.0 + 314.1 + 66.1) * (1 << 20)), (2, "online"): int(0.5 * (56.4 + 53.5) * (1 << 20))}
 # adam_refresh_kernel, same counter runs (profiles/cfg2_online_kernel_trace_and_hbm.md)
 ADAM_TRAFFIC_BYTES = {(2, "online"): int((171.59 + 167.46) * (1 << 20))}
 

@@ -925,7 +925,7 @@ hipError_t launch_bf16(const GemmArgs &g, hipStream_t s) {
 }
 
 // Column ranges of the XCD split (see tile_of_block) by the size of the A operand; FADE_GEMM_XCD overrides for sweeps.
-int fade_gemm_col_groups(int M, int K, int N) {
+int fade_gemm_col_groups(int M, int K, int N, size_t w_slice = (size_t)2 << 20) {
   static int v = -1;
   if (v < 0) { const char *e = getenv("FADE_GEMM_XCD"); v = e ? atoi(e) : 0; }
   if (v > 0) return v;
@@ -934,7 +934,7 @@ int fade_gemm_col_groups(int M, int K, int N) {
   // Tall A: as few ranges as keep an XCD's slice of W (K x N / ranges, bf16) within 2 MiB, half of its L2.
   if ((size_t)M * K < ((size_t)4 << 20)) return 8;
   int cg = 1;
-  while (cg < 8 && (size_t)K * N * 2 / cg > ((size_t)2 << 20)) cg *= 2;
+  while (cg < 8 && (size_t)K * N * 2 / cg > w_slice) cg *= 2;
   return cg;
 }
 
@@ -992,7 +992,9 @@ hipError_t launch_pipe8(const GemmArgs &g, hipStream_t s) {
   if (g.N % 256 || g.M <= 0 || g.K % 64 || g.splits > 1 || g.lda % 8) return hipErrorInvalidValue;
   GemmArgs ga = g;
   const int ntm = (g.M + 255) / 256, ntn = g.N / 256;
-  if (ga.col_groups == 0) ga.col_groups = fade_gemm_col_groups(g.M, g.K, g.N);
+  // 256-wide column tiles: a 4 MiB slice of W per XCD does as well as 2 MiB in time and fetches less (router product,
+  // M = 16384: 8 / 4 / 2 / 1 column ranges fetch 656 / 416 / 320 / 320 MiB, 171 / 167 / 166 / 167 us)
+  if (ga.col_groups == 0) ga.col_groups = fade_gemm_col_groups(g.M, g.K, g.N, (size_t)4 << 20);
   if ((ga.col_groups != 1 && ga.col_groups != 2 && ga.col_groups != 4) || ntn % ga.col_groups) ga.col_groups = 8;
   const int rg = 8 / ga.col_groups;
   const dim3 grid((ntn % ga.col_groups == 0 ? (ntm + rg - 1) / rg * rg : ntm) * ntn);
