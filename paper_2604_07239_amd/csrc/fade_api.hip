@@ -481,16 +481,21 @@ int forward_bf16(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uin
   // progressive ablation (the paper's component table): the head reads the last stage that is switched on
   const int level = c->cfg.ablation == 0 ? 5 : (int)c->cfg.ablation;
   const void *feat = c->Hg;
+  const bool conv_fused = level >= 2 && d.D == 32 && d.T <= 128 && d.k * 32 <= d.Kc && d.Kc <= 128;
   {
     Prof p(c, "embed_cache");
     EmbedArgs a{};
     a.ws = ws; a.T = (int)d.T; a.D = (int)d.D; a.Dh = Dh; a.Dc = (int)d.Dc; a.c = (int)d.c;
     a.tabXe = c->tabXe; a.tabXl = c->tabXl; a.tabXe32 = c->tabXe32; a.Wg = c->Wg_c; a.Wv = c->Wv_c;
     a.X = c->X; a.XL = c->XL; a.M = c->M; a.GG = c->GG; a.GV = c->GV; a.slot_tab = c->slot_tab; a.B = streams; a.S = steps;
+    if (conv_fused) {  // Eq. 4 rides along: one launch less, and the per-token rows XL only exist for the backward pass
+      a.conv_W = c->Wconv_c; a.conv_b = c->P(P_BCONV); a.Hl = c->Hl; a.cv = c->cv; a.taps = (int)d.k; a.Kc = (int)d.Kc;
+      if (!c->online) a.XL = nullptr;
+    }
     if (steps > 1) HIP_TRY(c, fade_embed_steps(a, s));
     else HIP_TRY(c, fade_embed_cache(a, streams, true, s));
   }
-  if (level >= 2) {  // Eq. 4
+  if (level >= 2 && !conv_fused) {  // Eq. 4
     Prof p(c, "gemm_conv");
     GemmArgs g{};
     g.M = B * (int)d.T; g.N = (int)d.D; g.K = (int)d.Kc;

@@ -42,6 +42,13 @@ struct EmbedArgs {
   float *GG, *GV;             // optional [B][c]: pre-activations of Eq. 1 for the backward pass
   const void *slot_tab;       // optional [256][c] activation type: Eq. 1's slot of every symbol (frozen weights only)
   int B, S;                   // several steps per launch (slot_tab required): row s * B + b is stream b at step ws.i + s
+  // Eq. 4 in the same launch (bf16, D = 32; conv_W == NULL: a separate product does it): W_conv as MFMA fragments
+  // [K_c / 16][64][8], bias [D], outputs H_local [rows][T][D] and, optionally, the pre-activations for the backward pass.
+  // XL may then be NULL when nothing else reads it.
+  const void *conv_W;
+  const float *conv_b;
+  void *Hl, *cv;
+  int taps, Kc;
 };
 
 // arguments of the kernels that finish a split-K product with a folded LayerNorm (bf16 path)

@@ -123,20 +123,70 @@ __device__ __forceinline__ void slot_pair(const float *xt, const float *Wg, cons
     gv = fmaf(xt[i], Wv[i * c + q], gv);
   }
 }
+// Eq. 4 for one window on the matrix cores (bf16, D = 32): H_local[j][o] = psi(b[o] + sum_{r,i} xl[j - (taps-1) + r][i] W[r][i][o]).
+// Wavefront w owns tokens 32 w .. 32 w + 31 (T <= 128). A lane's operand piece, 8 consecutive channels of one tap of one
+// token, is one 16-byte read of the per-symbol table; the W fragments are read as they lie. One accumulator takes the K
+// steps in order and the tail is the product kernel's conv epilogue, so the result is bit for bit that kernel's.
+__device__ __forceinline__ void conv_window_mfma(const EmbedArgs &a, const uint8_t *win, const bf16_t *tabXl, size_t row) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (wave * 32 >= a.T) return;
+  const int j = wave * 32 + (lane & 31), ksteps = a.Kc / 16;  // K_c <= 128: at most 8 K steps, 2 per tap
+  const bf16x8 *Wf = static_cast<const bf16x8 *>(a.conv_W) + lane;
+  // all operand reads are requested before the first matrix instruction: the symbols of the taps, then the table pieces
+  int sym[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int tok = j - (a.taps - 1) + r;
+    sym[r] = (r < a.taps && tok >= 0 && j < a.T) ? (int)win[tok] : -1;
+  }
+  bf16x8 af[8], bf[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    const int i = (ks & 1) * 16 + (lane >> 5) * 8, sy = sym[ks >> 1];  // k = 16 ks + 8 (lane / 32) = 32 tap + i
+#pragma unroll
+    for (int q = 0; q < 8; ++q) { af[ks][q] = (bf16_t)0.0f; bf[ks][q] = (bf16_t)0.0f; }
+    if (ks < ksteps) {
+      if (sy >= 0) af[ks] = *reinterpret_cast<const bf16x8 *>(tabXl + (size_t)sy * 32 + i);
+      bf[ks] = Wf[(size_t)ks * 64];
+    }
+  }
+  f32x16 acc;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[e] = 0.0f;
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks)
+    if (ks < ksteps) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks], bf[ks], acc, 0, 0, 0);
+  const int o = lane & 31;
+  const float bias = a.conv_b[o];
+  bf16_t *Hl = static_cast<bf16_t *>(a.Hl) + row * a.Dh, *cv = a.cv ? static_cast<bf16_t *>(a.cv) + row * a.Dh : nullptr;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) {
+    const int t = wave * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+    if (t < a.T) {
+      const float pre = acc[e] + bias;
+      Hl[t * 32 + o] = (bf16_t)gelu_f(pre);
+      if (cv) cv[t * 32 + o] = (bf16_t)pre;
+    }
+  }
+}
+
 template <typename AT>
 __global__ __launch_bounds__(256) void embed_cache_kernel(EmbedArgs a) {
   const int b = blockIdx.x, tid = threadIdx.x;
   if (!stream_active(a.ws, b)) return;
   const uint8_t *win = stream_window(a.ws, b, a.T);
   const AT *tabXe = static_cast<const AT *>(a.tabXe), *tabXl = static_cast<const AT *>(a.tabXl);
-  AT *X = static_cast<AT *>(a.X) + (size_t)b * a.Dh, *XL = static_cast<AT *>(a.XL) + (size_t)b * a.Dh;
+  AT *X = static_cast<AT *>(a.X) + (size_t)b * a.Dh, *XL = a.XL ? static_cast<AT *>(a.XL) + (size_t)b * a.Dh : nullptr;
   constexpr int V = 16 / sizeof(AT);  // elements per 16-byte piece
   typedef f32x4 piece_t;              // 16 bytes, whatever the element type
   for (int ch = tid; ch < a.Dh / V; ch += 256) {
     const int e0 = ch * V, j = e0 / a.D, i = e0 - j * a.D;
     const int s = win[j];
     *reinterpret_cast<piece_t *>(X + e0) = *reinterpret_cast<const piece_t *>(tabXe + (size_t)s * a.D + i);
-    *reinterpret_cast<piece_t *>(XL + e0) = *reinterpret_cast<const piece_t *>(tabXl + (size_t)s * a.D + i);
+    if (a.XL) *reinterpret_cast<piece_t *>(XL + e0) = *reinterpret_cast<const piece_t *>(tabXl + (size_t)s * a.D + i);
+  }
+  if constexpr (sizeof(AT) == 2) {
+    if (a.conv_W) conv_window_mfma(a, win, reinterpret_cast<const bf16_t *>(tabXl), (size_t)b);
   }
   // Eq. 2: shift the cache left by one slot (through registers, so the move is safe in place) ...
   AT *M = static_cast<AT *>(a.M) + (size_t)b * a.Dc;
@@ -203,13 +253,14 @@ __global__ __launch_bounds__(256) void embed_steps_kernel(EmbedArgs a) {
   if (!stream_active(w, b)) return;
   const uint8_t *win = stream_window(w, b, a.T);
   const bf16_t *tabXe = static_cast<const bf16_t *>(a.tabXe), *tabXl = static_cast<const bf16_t *>(a.tabXl);
-  bf16_t *X = static_cast<bf16_t *>(a.X) + (size_t)r * a.Dh, *XL = static_cast<bf16_t *>(a.XL) + (size_t)r * a.Dh;
+  bf16_t *X = static_cast<bf16_t *>(a.X) + (size_t)r * a.Dh, *XL = a.XL ? static_cast<bf16_t *>(a.XL) + (size_t)r * a.Dh : nullptr;
   for (int ch = tid; ch < a.Dh / 8; ch += 256) {
     const int e0 = ch * 8, j = e0 / a.D, i = e0 - j * a.D;
     const int sy = win[j];
     *reinterpret_cast<f32x4 *>(X + e0) = *reinterpret_cast<const f32x4 *>(tabXe + (size_t)sy * a.D + i);
-    *reinterpret_cast<f32x4 *>(XL + e0) = *reinterpret_cast<const f32x4 *>(tabXl + (size_t)sy * a.D + i);
+    if (a.XL) *reinterpret_cast<f32x4 *>(XL + e0) = *reinterpret_cast<const f32x4 *>(tabXl + (size_t)sy * a.D + i);
   }
+  if (a.conv_W) conv_window_mfma(a, win, tabXl, (size_t)r);
   const bf16_t *tab = static_cast<const bf16_t *>(a.slot_tab);
   bf16_t *M = static_cast<bf16_t *>(a.M) + (size_t)r * a.Dc;
   const long long first_slot = 2ll * a.T - 1 - w.i;  // slot j was appended at step i - (T - 1 - j), a model step iff that is >= T
@@ -884,12 +935,14 @@ hipError_t fade_tables(const float *E, const float *ge, const float *be, const f
 }
 hipError_t fade_embed_cache(const EmbedArgs &a, int B, bool bf16, hipStream_t s) {
   if (a.Dc > 4096 || a.c > 256 || a.c <= 0) return hipErrorInvalidValue;  // the kernel's register file holds one cache row
+  if (a.conv_W && (!bf16 || a.D != 32 || a.T > 128 || a.Kc % 16 || a.Kc > 128 || a.taps * 32 > a.Kc || !a.Hl || !a.conv_b)) return hipErrorInvalidValue;
   if (bf16) hipLaunchKernelGGL(embed_cache_kernel<bf16_t>, dim3(B), dim3(256), 0, s, a);
   else hipLaunchKernelGGL(embed_cache_kernel<float>, dim3(B), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 hipError_t fade_embed_steps(const EmbedArgs &a, hipStream_t s) {
   if (!a.slot_tab || a.B <= 0 || a.S <= 0 || a.Dh % 8) return hipErrorInvalidValue;
+  if (a.conv_W && (a.D != 32 || a.T > 128 || a.Kc % 16 || a.Kc > 128 || a.taps * 32 > a.Kc || !a.Hl || !a.conv_b)) return hipErrorInvalidValue;
   hipLaunchKernelGGL(embed_steps_kernel, dim3(a.B * a.S), dim3(256), 0, s, a);
   return hipGetLastError();
 }
