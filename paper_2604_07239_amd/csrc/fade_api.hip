@@ -287,9 +287,16 @@ int refresh_matrices(fade_ctx *c, bool adam) {
 }
 // bf16 path, after the matrices: the small operands (embedding, slot pair, conv taps in both orientations), the folded-LayerNorm
 // vectors from their per-block partials, the per-symbol tables
-int refresh_small(fade_ctx *c) {
+// `pending`: second-stage reductions of the update still to be launched; the two folded-LayerNorm sums join that launch.
+int refresh_small(fade_ctx *c, ReduceBatch *pending = nullptr) {
   const Dims &d = c->d;
   hipStream_t s = c->stream;
+  ReduceBatch local{};
+  ReduceBatch &fr = pending ? *pending : local;  // s then t, adjacent
+  if (!fr.push_plain((int)(d.Dh / 64), (int)(2 * d.dl), c->fold_down, c->s_down) ||
+      !fr.push_plain((int)(d.Dh / 64), (int)(4 * d.De), c->fold_fnr, c->s_fnr))
+    return fail(c, FADE_E_INVALID_ARG, "reduction queue full");
+  HIP_TRY(c, fade_reduce_batch(fr, s));
   PrepBatch pb{};
   auto padd = [&](int kind, const float *W0, size_t k_real, size_t K, size_t N, void *out) {
     PrepDesc &q = pb.d[pb.count++];
@@ -302,13 +309,10 @@ int refresh_small(fade_ctx *c) {
   padd(PREP_FRAG, c->P(P_WCONV), d.k * d.D, d.Kc, d.D, c->Wconv_c);
   if (c->online) padd(PREP_FRAG_CONVT, c->P(P_WCONV), d.k * d.D, d.Kc, d.D, c->WT_conv);
   if (c->WT_mslot) padd(PREP_FRAG_T, c->P(P_WM) + (d.Dc - d.c) * d.Dh, d.c, d.c, d.Dh, c->WT_mslot);
+  pb.has_tables = 1;  // same launch: the tables read the master embedding and round it as the copy above does
+  pb.tab = TablesArgs{c->P(P_E), c->P(P_GAMMA_E), c->P(P_BETA_E), c->P(P_GAMMA_L), c->P(P_BETA_L), (int)d.D, 1, c->tabXe, c->tabXl, c->tabXe32,
+                      c->tabXhat, c->tabRstd};
   HIP_TRY(c, fade_prep_batch(pb, s));
-  ReduceBatch fr{};  // s then t, adjacent
-  fr.push_plain((int)(d.Dh / 64), (int)(2 * d.dl), c->fold_down, c->s_down);
-  fr.push_plain((int)(d.Dh / 64), (int)(4 * d.De), c->fold_fnr, c->s_fnr);
-  HIP_TRY(c, fade_reduce_batch(fr, s));
-  HIP_TRY(c, fade_tables(c->E_c, c->P(P_GAMMA_E), c->P(P_BETA_E), c->P(P_GAMMA_L), c->P(P_BETA_L), (int)d.D, c->tabXe, c->tabXl, c->tabXe32,
-                         c->tabXhat, c->tabRstd, true, s));
   if (c->slot_tab) HIP_TRY(c, fade_slot_table(c->tabXe32, c->Wg_c, c->Wv_c, (int)d.D, (int)d.c, c->slot_tab, s));
   return FADE_OK;
 }
@@ -858,22 +862,25 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     // gamma_e, beta_e, gamma_l, beta_l are adjacent in the blob
     HIP_TRY(c, fade_bwd_embed(a, c->emb_blocks, c->sym_sums, c->tok_part, Gp(P_E), Gp(P_GAMMA_E), bf, rq, s));
   }
-  // Adam on everything except W_U (done in place above) and the refresh of every compute copy
-  {
-    Prof p(c, "adam_small");
-    const AdamArrays opt{c->grad, c->master, c->adam_m, c->adam_v, c->ustate, c->cfg.lr, c->cfg.beta1, c->cfg.beta2, c->cfg.eps};
-    // vectors, scalars, biases and the small tensors: Adam right where their gradient sums are finished
-    rq.opt = opt;
-    rq.push(1, (int)(256 * d.D), Gp(P_E), Gp(P_E));  // dE is complete already: a one-row "sum" that only adds the Adam step
-    HIP_TRY(c, fade_reduce_batch(rq, s));
-  }
+  // Adam on everything except W_U (done in place above) and the refresh of every compute copy: the matrices first (their
+  // pass leaves the partial sums of the folded-LayerNorm vectors), then one launch for every pending column sum (vectors,
+  // scalars, biases and the small tensors get their Adam step right where their gradient sums are finished), then the small
+  // operand copies and the per-symbol tables
   {
     Prof p(c, "adam_matrices");
     if ((rc = refresh_matrices(c, true))) return rc;
   }
   {
     Prof p(c, "refresh_small");
-    rc = bf ? refresh_small(c) : prepare_compute(c, false);
+    const AdamArrays opt{c->grad, c->master, c->adam_m, c->adam_v, c->ustate, c->cfg.lr, c->cfg.beta1, c->cfg.beta2, c->cfg.eps};
+    rq.opt = opt;
+    rq.push(1, (int)(256 * d.D), Gp(P_E), Gp(P_E));  // dE is complete already: a one-row "sum" that only adds the Adam step
+    if (bf) {
+      rc = refresh_small(c, &rq);
+    } else {
+      HIP_TRY(c, fade_reduce_batch(rq, s));
+      rc = prepare_compute(c, false);
+    }
     if (rc) return rc;
   }
   return FADE_OK;

@@ -107,9 +107,18 @@ struct PrepDesc {
   void *out;
   int taps, D;            // PREP_FRAG_CONVT: W0 = W_conv [taps][D][D]; virtual [K][D] with row (r*D+o), column i = W_conv[r][i][o]
 };
+// the per-symbol tables in the same launch (has_tables): they read the master embedding and round it themselves
+struct TablesArgs {
+  const float *E, *ge, *be, *gl, *bl;
+  int D, round_bf16;       // round_bf16: E counts as its bf16 rounding (what the bf16 path's embedding copy holds)
+  void *tabXe, *tabXl;     // bf16
+  float *tabXe32, *tabXhat, *tabRstd;
+};
 struct PrepBatch {
   PrepDesc d[20];
   int count;
+  int has_tables;
+  TablesArgs tab;
 };
 hipError_t fade_prep_batch(const PrepBatch &pb, hipStream_t s);
 hipError_t fade_convt_build(const float *Wconv, int taps, int D, int Kc, float *V, hipStream_t s);

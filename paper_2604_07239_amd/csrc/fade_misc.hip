@@ -84,11 +84,12 @@ __global__ void round_bf16_kernel(const float *src, float *dst, size_t n) {
 // Per-symbol tables: LN_D(E[s]) with the two affine pairs (X of the Design paragraph; LN of Eq. 4), and, for the
 // update, the normalised row x-hat and 1/sigma. One workgroup per symbol, lane = channel (D <= 256).
 template <typename AT>
-__global__ __launch_bounds__(256) void tables_kernel(const float *E, const float *ge, const float *be, const float *gl, const float *bl, int D,
-                                                     AT *tabXe, AT *tabXl, float *tabXe32, float *tabXhat, float *tabRstd) {
+__device__ __forceinline__ void tables_body(int s, const float *E, bool round_bf16, const float *ge, const float *be, const float *gl, const float *bl, int D,
+                                            AT *tabXe, AT *tabXl, float *tabXe32, float *tabXhat, float *tabRstd) {
   __shared__ float red[256];
-  const int s = blockIdx.x, i = threadIdx.x;
-  const float e = i < D ? E[(size_t)s * D + i] : 0.0f;
+  const int i = threadIdx.x;
+  float e = i < D ? E[(size_t)s * D + i] : 0.0f;
+  if (round_bf16) e = (float)(bf16_t)e;
   red[i] = e;
   __syncthreads();
   float mean = 0.0f;
@@ -110,6 +111,11 @@ __global__ __launch_bounds__(256) void tables_kernel(const float *E, const float
     if (tabXhat) tabXhat[(size_t)s * D + i] = h;
   }
   if (i == 0 && tabRstd) tabRstd[s] = rstd;
+}
+template <typename AT>
+__global__ __launch_bounds__(256) void tables_kernel(const float *E, const float *ge, const float *be, const float *gl, const float *bl, int D,
+                                                     AT *tabXe, AT *tabXl, float *tabXe32, float *tabXhat, float *tabRstd) {
+  tables_body<AT>(blockIdx.x, E, false, ge, be, gl, bl, D, tabXe, tabXl, tabXe32, tabXhat, tabRstd);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -432,6 +438,13 @@ __global__ __launch_bounds__(256) void residual_add_kernel(const bf16_t *x, cons
 
 // All element-wise weight preparation of one refresh in a single launch: blockIdx.y picks the descriptor.
 __global__ __launch_bounds__(256) void prep_batch_kernel(PrepBatch pb) {
+  if ((int)blockIdx.y == pb.count) {  // the per-symbol tables: workgroup x = symbol x
+    const TablesArgs &t = pb.tab;
+    if (blockIdx.x < 256)
+      tables_body<bf16_t>(blockIdx.x, t.E, t.round_bf16 != 0, t.ge, t.be, t.gl, t.bl, t.D, static_cast<bf16_t *>(t.tabXe), static_cast<bf16_t *>(t.tabXl),
+                          t.tabXe32, t.tabXhat, t.tabRstd);
+    return;
+  }
   const PrepDesc &d = pb.d[blockIdx.y];
   const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (d.kind == PREP_ROUND) {
@@ -1005,7 +1018,11 @@ hipError_t fade_prep_batch(const PrepBatch &pb, hipStream_t s) {
     else n = (size_t)(d.N / 32) * (d.K / 16) * 64;
     if (n > most) most = n;
   }
-  hipLaunchKernelGGL(prep_batch_kernel, dim3(blocks_for(most, 256), pb.count), dim3(256), 0, s, pb);
+  if (pb.has_tables) {
+    if (pb.tab.D > 256) return hipErrorInvalidValue;
+    if (most < 256 * 256) most = 256 * 256;  // 256 workgroups for the tables
+  }
+  hipLaunchKernelGGL(prep_batch_kernel, dim3(blocks_for(most, 256), pb.count + (pb.has_tables ? 1 : 0)), dim3(256), 0, s, pb);
   return hipGetLastError();
 }
 hipError_t fade_convt_build(const float *Wconv, int taps, int D, int Kc, float *V, hipStream_t s) {
