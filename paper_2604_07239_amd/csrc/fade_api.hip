@@ -847,11 +847,15 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     Prof p(c, "bwd_conv");
     ConvGradArgs a{};
     a.B = B; a.T = (int)d.T; a.D = (int)d.D; a.taps = (int)d.k; a.XL = c->XL; a.dcv = c->dcv; a.part = c->conv_part;
+    const bool both = bf && d.D == 32 && d.Kc <= 128 && d.k * 32 <= d.Kc;  // the matrix-core kernel also forms d(input)
+    if (both) { a.WT = c->WT_conv; a.dxl = c->dxl; a.Kc = (int)d.Kc; }
     HIP_TRY(c, fade_conv_grad(a, Gp(P_WCONV), bf, rq, s));  // W_conv then b_conv, adjacent in the blob
-    GemmArgs g{};
-    g.M = (int)(d.B * d.T); g.N = (int)d.D; g.K = (int)d.Kc; g.A = c->dcv; g.T = (int)d.T; g.D = (int)d.D; g.taps = (int)d.k;
-    g.W = bf ? c->WT_conv : static_cast<const void *>(c->convt_f32); g.C = c->dxl; g.ldc = (int)d.D;
-    HIP_TRY(c, fade_gemm(GEMM_CONVT, bf, g, s));
+    if (!both) {
+      GemmArgs g{};
+      g.M = (int)(d.B * d.T); g.N = (int)d.D; g.K = (int)d.Kc; g.A = c->dcv; g.T = (int)d.T; g.D = (int)d.D; g.taps = (int)d.k;
+      g.W = bf ? c->WT_conv : static_cast<const void *>(c->convt_f32); g.C = c->dxl; g.ldc = (int)d.D;
+      HIP_TRY(c, fade_gemm(GEMM_CONVT, bf, g, s));
+    }
   }
   {  // the two per-token LayerNorms and the embedding
     Prof p(c, "bwd_embed");

@@ -889,6 +889,17 @@ __global__ __launch_bounds__(256) void conv_grad_mfma_kernel(ConvGradArgs a) {
   auto prow = [&](int tl) { return (tl >> lgT) * Tp + (tl & Tm); };  // row of token tl's tap 0 in the padded tile
   auto tr_load = [](const unsigned char *p) { return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)p); };
   const bf16_t *XL = static_cast<const bf16_t *>(a.XL), *dcv = static_cast<const bf16_t *>(a.dcv);
+  // d(input) = the anti-causal convolution of dcv with the taps turned round: token j gets sum_r dcv[j + (taps-1) - r] W[r]^T,
+  // as far as that token is still in the window. Wavefront w owns tokens 32 w .. 32 w + 31 of the chunk; its operand piece
+  // (8 consecutive channels of one token) is one 16-byte read of the dcv tile as it lies.
+  const int xsteps = a.WT ? a.Kc / 16 : 0;  // <= 8
+  bf16x8 wt[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) wt[ks][q] = (bf16_t)0.0f;
+    if (ks < xsteps) wt[ks] = static_cast<const bf16x8 *>(a.WT)[(size_t)ks * 64 + lane];
+  }
   for (long long chunk = blockIdx.x; chunk < nchunks; chunk += gridDim.x) {
     const long long t0 = chunk * 128;
     __syncthreads();  // the zero fill, or the previous chunk's reads, are done
@@ -914,6 +925,29 @@ __global__ __launch_bounds__(256) void conv_grad_mfma_kernel(ConvGradArgs a) {
         const bf16x8 bf = __builtin_bit_cast(bf16x8, (i16x8)__builtin_shufflevector(bl, bh, 0, 1, 2, 3, 4, 5, 6, 7));
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bf, acc, 0, 0, 0);
         if (wave == 0) accb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, bf, accb, 0, 0, 0);
+      }
+    }
+    if (a.WT) {
+      const int tl = wave * 32 + (lane & 31), jj = tl & Tm;
+      f32x16 accx;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) accx[e] = 0.0f;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        if (ks < xsteps) {
+          const int k = ks * 16 + (lane >> 5) * 8, tap = k >> 5, o = k & 31, ahead = pad - tap;  // D = 32
+          bf16x8 af;
+#pragma unroll
+          for (int q = 0; q < 8; ++q) af[q] = (bf16_t)0.0f;
+          if (tap < a.taps && jj + ahead <= Tm) af = *reinterpret_cast<const bf16x8 *>(ds + (tl + ahead) * PITCH + o * 2);
+          accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, wt[ks], accx, 0, 0, 0);
+        }
+      }
+      bf16_t *dxl = static_cast<bf16_t *>(a.dxl);
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const long long t = t0 + wave * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+        if (t < tokens) dxl[(size_t)t * D + (lane & 31)] = (bf16_t)accx[e];
       }
     }
   }
@@ -1311,6 +1345,7 @@ hipError_t fade_conv_grad(const ConvGradArgs &a, float *dWb, bool bf16, ReduceBa
   if (256 % a.D || a.D > 32 || a.D < 16 || 128 % a.T || a.T < 4 || a.taps > 4 || (a.taps * a.D + 256 / a.D - 1) / (256 / a.D) > 16) return hipErrorInvalidValue;
   const long long nchunks = ((long long)a.B * a.T + 127) / 128;
   const int P = (int)(nchunks < 512 ? nchunks : 512);  // 128-token chunks are dealt round-robin to at most 512 workgroups
+  if (a.WT && (!bf16 || a.D != 32 || !a.dxl || a.Kc % 16 || a.Kc > 128 || a.taps * 32 > a.Kc)) return hipErrorInvalidValue;
   if (bf16 && a.D == 32) hipLaunchKernelGGL(conv_grad_mfma_kernel, dim3(P), dim3(256), 0, s, a);
   else if (bf16) hipLaunchKernelGGL(conv_grad_partial_kernel<bf16_t>, dim3(P), dim3(256), 0, s, a);
   else hipLaunchKernelGGL(conv_grad_partial_kernel<float>, dim3(P), dim3(256), 0, s, a);

@@ -227,6 +227,11 @@ struct ConvGradArgs {
   int B, T, D, taps;
   const void *XL, *dcv;   // [B*T][D]
   float *part;            // [ceil(B*T/128)][taps*D + 1][D]
+  // bf16, D = 32 only: Eq. 4 backward w.r.t. its input in the same launch (WT == NULL: a separate product does it).
+  // WT: fragments of the virtual [Kc][D] matrix with row (r * D + o), column i = W_conv[r][i][o]; dxl [B*T][D].
+  const void *WT;
+  void *dxl;
+  int Kc;
 };
 struct BwdTokenArgs {
   WinSrc ws;
