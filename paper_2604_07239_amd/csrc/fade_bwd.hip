@@ -1098,25 +1098,43 @@ __global__ __launch_bounds__(256) void symbol_sums_mfma_kernel(BwdTokenArgs a, i
       }
 }
 
-// Finish on the tables: one workgroup per symbol, lane = channel. sums: [2][256][D] (SX then SL).
-// Writes dE[s] and this symbol's contribution to (d gamma_e, d beta_e, d gamma_l, d beta_l) as contrib[s][4][D].
-__global__ __launch_bounds__(64) void embed_finish_kernel(int D, const float *sums, const float *tabXhat, const float *tabRstd,
-                                                          const float *gamma_e, const float *gamma_l, float *dE, float *contrib) {
+// Finish on the tables: one workgroup per symbol. First the symbol's two rows of the per-symbol sums (SX then SL) from the
+// P partial tables part[P][2][256][D] (64 columns x 4 phases; phase h adds partials h, h + 4, ... in increasing order, the
+// phase sums are added in phase order), then, lane = channel, dE[s] and this symbol's contribution to (d gamma_e, d beta_e,
+// d gamma_l, d beta_l) as contrib[s][4][D]. D <= 32.
+__global__ __launch_bounds__(256) void embed_finish_kernel(int D, int P, const float *part, const float *tabXhat, const float *tabRstd,
+                                                           const float *gamma_e, const float *gamma_l, float *dE, float *contrib) {
+  __shared__ float ps[4][64];
   __shared__ float red[4][64];
-  const int s = blockIdx.x, i = threadIdx.x;
+  const int s = blockIdx.x, tid = threadIdx.x, c = tid & 63, h = tid >> 6;
+  float acc = 0.0f;
+  if (c < 2 * D) {
+    const int tab = c / D, ch = c - tab * D;
+    const float *src = part + ((size_t)tab * 256 + s) * D + ch;
+    const size_t stride = (size_t)2 * 256 * D;
+#pragma unroll 8
+    for (int p = h; p < P; p += 4) acc += src[(size_t)p * stride];
+  }
+  ps[h][c] = acc;
+  __syncthreads();
+  const int i = tid;
   const bool on = i < D;
-  const float sx = on ? sums[(size_t)s * D + i] : 0.0f, sl = on ? sums[(size_t)(256 + s) * D + i] : 0.0f;
+  float sx = 0.0f, sl = 0.0f;
+  if (on) {
+    sx = ((ps[0][i] + ps[1][i]) + ps[2][i]) + ps[3][i];
+    sl = ((ps[0][D + i] + ps[1][D + i]) + ps[2][D + i]) + ps[3][D + i];
+  }
   const float xh = on ? tabXhat[(size_t)s * D + i] : 0.0f;
   const float he = on ? sx * gamma_e[i] : 0.0f, hl = on ? sl * gamma_l[i] : 0.0f;
-  red[0][i] = he; red[1][i] = he * xh; red[2][i] = hl; red[3][i] = hl * xh;
+  if (i < 64) { red[0][i] = he; red[1][i] = he * xh; red[2][i] = hl; red[3][i] = hl * xh; }
   __syncthreads();
-  float m[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-  for (int k = 0; k < D; ++k) { m[0] += red[0][k]; m[1] += red[1][k]; m[2] += red[2][k]; m[3] += red[3][k]; }
   if (on) {
+    float m[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int k = 0; k < D; ++k) { m[0] += red[0][k]; m[1] += red[1][k]; m[2] += red[2][k]; m[3] += red[3][k]; }
     const float inv = 1.0f / (float)D;
     dE[(size_t)s * D + i] = tabRstd[s] * ((he - m[0] * inv - xh * m[1] * inv) + (hl - m[2] * inv - xh * m[3] * inv));
-    float *c = contrib + (size_t)s * 4 * D;
-    c[i] = xh * sx; c[D + i] = sx; c[2 * D + i] = xh * sl; c[3 * D + i] = sl;
+    float *cb = contrib + (size_t)s * 4 * D;
+    cb[i] = xh * sx; cb[D + i] = sx; cb[2 * D + i] = xh * sl; cb[3 * D + i] = sl;
   }
 }
 
@@ -1370,8 +1388,8 @@ hipError_t fade_bwd_embed(const BwdTokenArgs &a, int nblocks, float *sums, float
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if ((e = fade_reduce_rows(nblocks, 2 * 256 * a.D, a.part, sums, s)) != hipSuccess) return e;
-  hipLaunchKernelGGL(embed_finish_kernel, dim3(256), dim3(64), 0, s, a.D, sums, a.tabXhat, a.tabRstd, a.gamma_e, a.gamma_l, dE, contrib);
+  (void)sums;  // the second stage of the per-symbol sums happens inside the finishing kernel
+  hipLaunchKernelGGL(embed_finish_kernel, dim3(256), dim3(256), 0, s, a.D, nblocks, a.part, a.tabXhat, a.tabRstd, a.gamma_e, a.gamma_l, dE, contrib);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   return rb.push(256, 4 * a.D, contrib, dparams) ? hipSuccess : hipErrorInvalidValue;
 }
