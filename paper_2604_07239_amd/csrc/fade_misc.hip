@@ -133,8 +133,8 @@ __device__ __forceinline__ void slot_pair(const float *xt, const float *Wg, cons
 // Wavefront w owns tokens 32 w .. 32 w + 31 (T <= 128). A lane's operand piece, 8 consecutive channels of one tap of one
 // token, is one 16-byte read of the per-symbol table; the W fragments are read as they lie. One accumulator takes the K
 // steps in order and the tail is the product kernel's conv epilogue, so the result is bit for bit that kernel's.
-__device__ __forceinline__ void conv_window_mfma(const EmbedArgs &a, const uint8_t *win, const bf16_t *tabXl, size_t row) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+__device__ __forceinline__ void conv_window_mfma(const EmbedArgs &a, const uint8_t *win, const bf16_t *tabXl, size_t row, int wave) {
+  const int lane = threadIdx.x & 63;  // `wave`: which 32 tokens of the window the calling wavefront takes
   if (wave * 32 >= a.T) return;
   const int j = wave * 32 + (lane & 31), ksteps = a.Kc / 16;  // K_c <= 128: at most 8 K steps, 2 per tap
   const bf16x8 *Wf = static_cast<const bf16x8 *>(a.conv_W) + lane;
@@ -192,7 +192,7 @@ __global__ __launch_bounds__(256) void embed_cache_kernel(EmbedArgs a) {
     if (a.XL) *reinterpret_cast<piece_t *>(XL + e0) = *reinterpret_cast<const piece_t *>(tabXl + (size_t)s * a.D + i);
   }
   if constexpr (sizeof(AT) == 2) {
-    if (a.conv_W) conv_window_mfma(a, win, reinterpret_cast<const bf16_t *>(tabXl), (size_t)b);
+    if (a.conv_W) conv_window_mfma(a, win, reinterpret_cast<const bf16_t *>(tabXl), (size_t)b, tid >> 6);
   }
   // Eq. 2: shift the cache left by one slot (through registers, so the move is safe in place) ...
   AT *M = static_cast<AT *>(a.M) + (size_t)b * a.Dc;
@@ -251,28 +251,41 @@ __global__ void slot_table_kernel(const float *tabXe32, const float *Wg, const f
 // step i + s. The cache of Eq. 2 is rebuilt from the window instead of rolled: after step i, slot j holds the symbol
 // window[j]'s entry of Eq. 1, provided the model already ran at the step that appended it (steps before T code under the
 // uniform table and append nothing, so those slots are still the zeros of the reset).
-__global__ __launch_bounds__(256) void embed_steps_kernel(EmbedArgs a) {
-  const int r = blockIdx.x, tid = threadIdx.x;
-  const int s = r / a.B, b = r - s * a.B;
-  WinSrc w = a.ws;
-  w.i += s;
-  if (!stream_active(w, b)) return;
-  const uint8_t *win = stream_window(w, b, a.T);
+__global__ __launch_bounds__(256) void embed_steps_kernel(EmbedArgs a, int rpb) {
+  // rpb rows per workgroup (4, 2 or 1: as many as give every wavefront one 32-token tile of Eq. 4)
+  const int tid = threadIdx.x, rows = a.B * a.S;
   const bf16_t *tabXe = static_cast<const bf16_t *>(a.tabXe), *tabXl = static_cast<const bf16_t *>(a.tabXl);
-  bf16_t *X = static_cast<bf16_t *>(a.X) + (size_t)r * a.Dh, *XL = a.XL ? static_cast<bf16_t *>(a.XL) + (size_t)r * a.Dh : nullptr;
-  for (int ch = tid; ch < a.Dh / 8; ch += 256) {
-    const int e0 = ch * 8, j = e0 / a.D, i = e0 - j * a.D;
-    const int sy = win[j];
-    *reinterpret_cast<f32x4 *>(X + e0) = *reinterpret_cast<const f32x4 *>(tabXe + (size_t)sy * a.D + i);
-    if (a.XL) *reinterpret_cast<f32x4 *>(XL + e0) = *reinterpret_cast<const f32x4 *>(tabXl + (size_t)sy * a.D + i);
-  }
-  if (a.conv_W) conv_window_mfma(a, win, tabXl, (size_t)r);
   const bf16_t *tab = static_cast<const bf16_t *>(a.slot_tab);
-  bf16_t *M = static_cast<bf16_t *>(a.M) + (size_t)r * a.Dc;
-  const long long first_slot = 2ll * a.T - 1 - w.i;  // slot j was appended at step i - (T - 1 - j), a model step iff that is >= T
-  for (int idx = tid; idx < a.Dc; idx += 256) {
-    const int j = idx / a.c, q = idx - j * a.c;
-    M[idx] = j >= first_slot ? tab[(size_t)win[j] * a.c + q] : (bf16_t)0.0f;
+  for (int q = 0; q < rpb; ++q) {
+    const int r = blockIdx.x * rpb + q;
+    if (r >= rows) break;
+    const int s = r / a.B, b = r - s * a.B;
+    WinSrc w = a.ws;
+    w.i += s;
+    if (!stream_active(w, b)) continue;
+    const uint8_t *win = stream_window(w, b, a.T);
+    bf16_t *X = static_cast<bf16_t *>(a.X) + (size_t)r * a.Dh, *XL = a.XL ? static_cast<bf16_t *>(a.XL) + (size_t)r * a.Dh : nullptr;
+    for (int ch = tid; ch < a.Dh / 8; ch += 256) {
+      const int e0 = ch * 8, j = e0 / a.D, i = e0 - j * a.D;
+      const int sy = win[j];
+      *reinterpret_cast<f32x4 *>(X + e0) = *reinterpret_cast<const f32x4 *>(tabXe + (size_t)sy * a.D + i);
+      if (XL) *reinterpret_cast<f32x4 *>(XL + e0) = *reinterpret_cast<const f32x4 *>(tabXl + (size_t)sy * a.D + i);
+    }
+    bf16_t *M = static_cast<bf16_t *>(a.M) + (size_t)r * a.Dc;
+    const long long first_slot = 2ll * a.T - 1 - w.i;  // slot j was appended at step i - (T - 1 - j), a model step iff that is >= T
+    for (int idx = tid; idx < a.Dc; idx += 256) {
+      const int j = idx / a.c, qq = idx - j * a.c;
+      M[idx] = j >= first_slot ? tab[(size_t)win[j] * a.c + qq] : (bf16_t)0.0f;
+    }
+  }
+  if (a.conv_W) {  // wavefront w: row w / tiles-per-row of this workgroup, tokens 32 (w % tiles-per-row) ..
+    const int wave = tid >> 6, tpr = 4 / rpb, q = wave / tpr, r = blockIdx.x * rpb + q;
+    if (r < rows) {
+      const int s = r / a.B, b = r - s * a.B;
+      WinSrc w = a.ws;
+      w.i += s;
+      if (stream_active(w, b)) conv_window_mfma(a, stream_window(w, b, a.T), tabXl, (size_t)r, wave % tpr);
+    }
   }
 }
 
@@ -956,7 +969,8 @@ hipError_t fade_embed_cache(const EmbedArgs &a, int B, bool bf16, hipStream_t s)
 hipError_t fade_embed_steps(const EmbedArgs &a, hipStream_t s) {
   if (!a.slot_tab || a.B <= 0 || a.S <= 0 || a.Dh % 8) return hipErrorInvalidValue;
   if (a.conv_W && (a.D != 32 || a.T > 128 || a.Kc % 16 || a.Kc > 128 || a.taps * 32 > a.Kc || !a.Hl || !a.conv_b)) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(embed_steps_kernel, dim3(a.B * a.S), dim3(256), 0, s, a);
+  const int tiles = (a.T + 31) / 32, rpb = (a.conv_W && tiles <= 2) ? 4 / tiles : 1;  // tiles = 3 or 4: one row, idle wavefronts
+  hipLaunchKernelGGL(embed_steps_kernel, dim3((a.B * a.S + rpb - 1) / rpb), dim3(256), 0, s, a, rpb);
   return hipGetLastError();
 }
 hipError_t fade_slot_table(const float *tabXe32, const float *Wg, const float *Wv, int D, int c, void *tab_bf16, hipStream_t s) {
