@@ -162,16 +162,31 @@ __device__ __forceinline__ void conv_window_mfma(const EmbedArgs &a, const uint8
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks)
     if (ks < ksteps) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks], bf[ks], acc, 0, 0, 0);
+  // The tile leaves through LDS (this wavefront's own 32 x 32 patch: no workgroup barrier) so that a lane stores 16
+  // consecutive channels of one token, 2 x 16 bytes per output, instead of 16 scattered 2-byte values.
+  __shared__ float patch[4][32][33];
+  float (*pt)[33] = patch[(threadIdx.x >> 6) & 3];
   const int o = lane & 31;
   const float bias = a.conv_b[o];
-  bf16_t *Hl = static_cast<bf16_t *>(a.Hl) + row * a.Dh, *cv = a.cv ? static_cast<bf16_t *>(a.cv) + row * a.Dh : nullptr;
 #pragma unroll
-  for (int e = 0; e < 16; ++e) {
-    const int t = wave * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-    if (t < a.T) {
-      const float pre = acc[e] + bias;
-      Hl[t * 32 + o] = (bf16_t)gelu_f(pre);
-      if (cv) cv[t * 32 + o] = (bf16_t)pre;
+  for (int e = 0; e < 16; ++e) pt[(e >> 2) * 8 + (lane >> 5) * 4 + (e & 3)][o] = acc[e] + bias;
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the wavefront's LDS writes have landed before its lanes read each other's
+  const int tr = lane >> 1, c0 = (lane & 1) * 16, t = wave * 32 + tr;
+  if (t < a.T) {
+    bf16x8 h[2], p[2];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      const float pre = pt[tr][c0 + q];
+      h[q >> 3][q & 7] = (bf16_t)gelu_f(pre);
+      p[q >> 3][q & 7] = (bf16_t)pre;
+    }
+    bf16_t *Hl = static_cast<bf16_t *>(a.Hl) + row * a.Dh + t * 32 + c0;
+    *reinterpret_cast<bf16x8 *>(Hl) = h[0];
+    *reinterpret_cast<bf16x8 *>(Hl + 8) = h[1];
+    if (a.cv) {
+      bf16_t *cv = static_cast<bf16_t *>(a.cv) + row * a.Dh + t * 32 + c0;
+      *reinterpret_cast<bf16x8 *>(cv) = p[0];
+      *reinterpret_cast<bf16x8 *>(cv + 8) = p[1];
     }
   }
 }
