@@ -157,7 +157,7 @@ struct fade_ctx {
        *dHa = nullptr, *dac = nullptr, *dHmix1 = nullptr, *dHmix2 = nullptr, *dy_at = nullptr, *dnc = nullptr, *dar = nullptr,
        *dhm = nullptr, *dcv = nullptr, *dX1 = nullptr, *dX2 = nullptr, *dxl = nullptr;
   void *LT[8] = {};  // left operands of the weight gradients that need a copy: LN(H_coarse), LN(H_mix) row-major (bf16 path); feature-major copies [width][Bp] of all eight (fp32 path)
-  float *dz_part = nullptr, *dy = nullptr, *dgg = nullptr, *dgv = nullptr, *dxt = nullptr, *sym_sums = nullptr, *row_dlam = nullptr,
+  float *dz_part = nullptr, *dy = nullptr, *dgg = nullptr, *dgv = nullptr, *dxt = nullptr, *row_dlam = nullptr,
         *conv_part = nullptr, *tok_part = nullptr;
   float *ln_part = nullptr, *col_part = nullptr, *slot_part = nullptr, *emb_part = nullptr;
   int sp_dz = 1, emb_blocks = 128;
@@ -864,7 +864,7 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     a.tabXhat = c->tabXhat; a.tabRstd = c->tabRstd; a.gamma_e = c->P(P_GAMMA_E); a.gamma_l = c->P(P_GAMMA_L);
     a.part = c->emb_part;
     // gamma_e, beta_e, gamma_l, beta_l are adjacent in the blob
-    HIP_TRY(c, fade_bwd_embed(a, c->emb_blocks, c->sym_sums, c->tok_part, Gp(P_E), Gp(P_GAMMA_E), bf, rq, s));
+    HIP_TRY(c, fade_bwd_embed(a, c->emb_blocks, c->tok_part, Gp(P_E), Gp(P_GAMMA_E), bf, rq, s));
   }
   // Adam on everything except W_U (done in place above) and the refresh of every compute copy: the matrices first (their
   // pass leaves the partial sums of the folded-LayerNorm vectors), then one launch for every pending column sum (vectors,
@@ -1189,7 +1189,6 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
     c->emb_blocks = (int)std::min<size_t>(256, (tokens + 127) / 128);
     TRY_ALLOC(dev_alloc(c, &c->conv_part, (tokens + 127) / 128 * (d.k * d.D + 1) * d.D));
     TRY_ALLOC(dev_alloc(c, &c->tok_part, 256 * 4 * d.D));
-    TRY_ALLOC(dev_alloc(c, &c->sym_sums, 2 * 256 * d.D));
     TRY_ALLOC(dev_alloc(c, &c->ln_part, 3 * rb * 2 * d.Dh));
     TRY_ALLOC(dev_alloc(c, &c->col_part, (d.B + 7) / 8 * 256));
     TRY_ALLOC(dev_alloc(c, &c->slot_part, (d.B + 3) / 4 * 2 * d.D * d.c));

@@ -554,26 +554,8 @@ __global__ __launch_bounds__(256) void bwd_mix_kernel(BwdMixArgs a) {
   }
 }
 
-// Column sums in two deterministic stages. Stage 1 (here, or inside a producer kernel) leaves partial sums per row block
-// as part[P][N]; stage 2 adds the P partials of each column in index order.
-__global__ __launch_bounds__(256) void reduce_rows_kernel(int P, int N, const float *part, float *out) {
-  // 32 columns x 8 phases: phase h adds rows h, h+8, ... in increasing order; the 8 phase sums are added in phase order
-  __shared__ float ps[8][32];
-  const int c = threadIdx.x & 31, h = threadIdx.x >> 5, n = blockIdx.x * 32 + c;
-  float s = 0.0f;
-  if (n < N) {
-#pragma unroll 4
-    for (int p = h; p < P; p += 8) s += part[(size_t)p * N + n];
-  }
-  ps[h][c] = s;
-  __syncthreads();
-  if (h == 0 && n < N) {
-    float t = 0.0f;
-#pragma unroll
-    for (int k = 0; k < 8; ++k) t += ps[k][c];
-    out[n] = t;
-  }
-}
+// Column sums in two deterministic stages. Stage 1 (inside a producer kernel) leaves partial sums per row block as
+// part[P][N]; stage 2 adds the P partials of each column in a fixed order.
 // Several queued column sums in one launch (blockIdx.y picks the item). 1024 threads = cw columns x (1024 / cw) row
 // phases, cw = 32 or, for an item narrower than that, the next power of two >= N (a [B][1] column of per-stream terms
 // then has all 1024 threads on its rows). Phase h adds rows h, h + phases, ... in increasing order; the phase sums are
@@ -1330,10 +1312,6 @@ hipError_t fade_bwd_geglu(int B, int De, const void *dHexp, const void *eg, cons
 hipError_t fade_bwd_gate(const BwdGateArgs &a, bool bf16, hipStream_t s) { DISPATCH_ROWS(bf16, bwd_gate_kernel, a.B, s, a); }
 hipError_t fade_bwd_mix(const BwdMixArgs &a, bool bf16, hipStream_t s) { DISPATCH_ROWS(bf16, bwd_mix_kernel, a.B, s, a); }
 int fade_rows_per_block(int B) { return rows_per_block(B); }
-hipError_t fade_reduce_rows(int P, int N, const float *part, float *out, hipStream_t s) {
-  hipLaunchKernelGGL(reduce_rows_kernel, dim3(nblk((size_t)N, 32)), dim3(256), 0, s, P, N, part, out);
-  return hipGetLastError();
-}
 hipError_t fade_reduce_batch(const ReduceBatch &rb, hipStream_t s) {
   if (rb.count <= 0) return hipSuccess;
   int maxN = 0;
@@ -1371,9 +1349,9 @@ hipError_t fade_conv_grad(const ConvGradArgs &a, float *dWb, bool bf16, ReduceBa
   if (e != hipSuccess) return e;
   return rb.push(P, (a.taps * a.D + 1) * a.D, a.part, dWb) ? hipSuccess : hipErrorInvalidValue;
 }
-// a.part: nblocks * 2 * 256 * D floats; sums: 2 * 256 * D; contrib: 256 * 4 * D.
+// a.part: nblocks * 2 * 256 * D floats; contrib: 256 * 4 * D.
 // dE: gradient of the embedding; dparams: gradient of gamma_e (beta_e, gamma_l, beta_l follow it in the blob).
-hipError_t fade_bwd_embed(const BwdTokenArgs &a, int nblocks, float *sums, float *contrib, float *dE, float *dparams, bool bf16, ReduceBatch &rb,
+hipError_t fade_bwd_embed(const BwdTokenArgs &a, int nblocks, float *contrib, float *dE, float *dparams, bool bf16, ReduceBatch &rb,
                           hipStream_t s) {
   if (256 % a.D || a.D > 32 || a.D % 8) return hipErrorInvalidValue;
   if (a.D != 16 && a.D != 32) return hipErrorInvalidValue;
@@ -1388,7 +1366,7 @@ hipError_t fade_bwd_embed(const BwdTokenArgs &a, int nblocks, float *sums, float
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  (void)sums;  // the second stage of the per-symbol sums happens inside the finishing kernel
+  // the second stage of the per-symbol sums happens inside the finishing kernel
   hipLaunchKernelGGL(embed_finish_kernel, dim3(256), dim3(256), 0, s, a.D, nblocks, a.part, a.tabXhat, a.tabRstd, a.gamma_e, a.gamma_l, dE, contrib);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   return rb.push(256, 4 * a.D, contrib, dparams) ? hipSuccess : hipErrorInvalidValue;

@@ -251,7 +251,6 @@ hipError_t fade_bwd_geglu(int B, int De, const void *dHexp, const void *eg, cons
 hipError_t fade_bwd_gate(const BwdGateArgs &a, bool bf16, hipStream_t s);
 hipError_t fade_bwd_mix(const BwdMixArgs &a, bool bf16, hipStream_t s);
 int fade_rows_per_block(int B);  // rows per workgroup of the backward row kernels at batch size B
-hipError_t fade_reduce_rows(int P, int N, const float *part, float *out, hipStream_t s);
 // Second stages (out[n] = sum over p < P of part[p][n], rows added in a fixed order) that nothing inside the backward pass
 // waits for are queued here and run as ONE launch just before Adam. The stage-1 launchers below take the queue.
 // Adam's hyper-parameters and state arrays (device layout; gradient, master weights and both moments share the offsets)
@@ -308,5 +307,5 @@ hipError_t fade_adam_refresh(const AdamRefreshBatch &ab, hipStream_t s);
 hipError_t fade_bwd_cci(const BwdCciArgs &a, bool bf16, hipStream_t s);
 hipError_t fade_bwd_slot(const BwdSlotArgs &a, float *dWgv, bool bf16, ReduceBatch &rb, hipStream_t s);
 hipError_t fade_conv_grad(const ConvGradArgs &a, float *dWb, bool bf16, ReduceBatch &rb, hipStream_t s);
-hipError_t fade_bwd_embed(const BwdTokenArgs &a, int nblocks, float *sums, float *contrib, float *dE, float *dparams, bool bf16, ReduceBatch &rb,
+hipError_t fade_bwd_embed(const BwdTokenArgs &a, int nblocks, float *contrib, float *dE, float *dparams, bool bf16, ReduceBatch &rb,
                           hipStream_t s);
