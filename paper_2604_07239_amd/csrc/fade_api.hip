@@ -1158,15 +1158,29 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
       // W_down (128 K elements) is cut down to ranges of 2 blocks. B = 1024: Down phase 16 -> 13 us, the others unchanged
       // (cutting them too cost 11 us more in the Adam pass than it saved); B = 4096: head / FNR-out / FNR-in / Down
       // phases 52 / 55 / 55 / 62 -> 24 / 37 / 39 / 16 us for 12 us more in the Adam pass.
+      // The two D_h x D_h gradients (256 tiles: a full product by the rule above) share their phase with an activation
+      // gradient whose workgroups walk D_h / 64 blocks while theirs walk the batch; after the first round of the 512
+      // workgroup slots they run on half the chip, and two ranges make that second round a full one. The Adam pass pays
+      // 15 us for the two extra 16 MiB slices, which B = 4096 only just gets back (phases 114 / 123 -> 106 / 115 us) and
+      // B = 16384 does (445 / 460 -> 375 / 470, step 3.74 -> 3.64 ms): from 8192 rows on, with W_up and W_m of the same phases.
       const struct { int id, pair, M, N; } gw[] = {{P_WO, -1, (int)d.Dh, 256}, {P_WF, -1, (int)d.De, (int)d.Dh}, {P_WFG, P_WFV, (int)d.Dh, (int)(2 * d.De)},
-                                                    {P_WDOWN, -1, (int)d.Dh, (int)d.dl}};
+                                                    {P_WDOWN, -1, (int)d.Dh, (int)d.dl}, {P_WUP, -1, (int)d.dl, (int)d.Dh}, {P_WM, -1, (int)d.Dc, (int)d.Dh},
+                                                    {P_WC, -1, (int)d.Dh, (int)d.Dh}, {P_WR, -1, (int)d.Dh, (int)d.Dh}};
       for (const auto &w : gw) {
         const int tiles = fade_gemm_tn_tiles(w.M, w.N);
-        if (tiles <= 0 || tiles >= 192) continue;
+        if (tiles <= 0) continue;
         const bool small = c->lay.len[w.id] <= (256u << 10);
         const int nkb = (int)(Bp / 64);
-        if (!small && nkb < 32) continue;
-        const int sp = pick_splits(tiles, small ? nkb : nkb / 4, 16);  // nkb / 4: ranges of at least 8 blocks
+        if ((w.id == P_WUP || w.id == P_WM || w.id == P_WC || w.id == P_WR) && nkb < 128) continue;
+        int sp;
+        if (tiles < 192) {
+          if (!small && nkb < 32) continue;
+          sp = pick_splits(tiles, small ? nkb : nkb / 4, 16);  // nkb / 4: ranges of at least 8 blocks
+        } else if (tiles < 512 && nkb >= 32 && nkb % 2 == 0) {
+          sp = 2;
+        } else {
+          continue;
+        }
         if (sp <= 1 || nkb % sp) continue;
         c->gsp[w.id] = sp;
         TRY_ALLOC(dev_alloc(c, &c->gpart[w.id], (size_t)sp * c->lay.len[w.id]));
