@@ -123,8 +123,10 @@ def main():
             torch.cuda.synchronize(); return time.perf_counter() - t0
 
         t_enc = timed_encode()
+        print(f"[bench] {mode}: compressed {'the whole input' if a.full else f'{K} steps'} in {t_enc:.2f} s", file=sys.stderr, flush=True)
         lens, data = g.payloads()
         t_dec = timed_decode(lens, data)
+        print(f"[bench] {mode}: decompressed in {t_dec:.2f} s", file=sys.stderr, flush=True)
         ok = bool(torch.equal(dst_dev, src_dev))
         steps_timed = L if a.full else K
         bytes_timed = n if a.full else B * K
