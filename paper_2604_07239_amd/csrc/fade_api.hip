@@ -705,18 +705,21 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
   const int level = c->cfg.ablation == 0 ? 5 : (int)c->cfg.ablation;
   const void *feat = level >= 5 ? c->Hout : level >= 3 ? c->Hc : level == 2 ? c->Hmix : c->Hg;
   void *dfeat = level >= 5 ? c->dHout : level >= 3 ? c->dHc : c->dHmix1;
-  {
+  if (bf) {  // the loss gradient, and in the same launch the two left operands the forward pass never stores: LN(H_coarse), LN(H_mix), row-major
     Prof p(c, "bwd_prep_dlogits");
-    HIP_TRY(c, fade_loss_grad(ws, targets, tstride, B, c->probs_buf, c->ustate, c->cfg.beta1, c->cfg.beta2, c->dl, c->col_part, Gp(P_BO), bf, rq, s));
-  }
-  if (bf) {  // the two left operands the forward pass never stores: LN(H_coarse), LN(H_mix), row-major
-    Prof p(c, "ln_apply", w);
     LnApplyBatch lb{};
     lb.B = B; lb.Dh = Dh; lb.stats_n = SN;
     if (level >= 5) lb.a[lb.count++] = {c->Hc, c->LT[2], c->stats_f, c->P(P_GAMMA_F), c->P(P_BETA_F)};
     if (level >= 3) lb.a[lb.count++] = {c->Hmix, c->LT[5], c->stats_c, c->P(P_GAMMA_C), c->P(P_BETA_C)};
-    if (lb.count) HIP_TRY(c, fade_ln_apply(lb, true, w));
+    lb.with_loss = 1;
+    lb.loss = LossGradArgs{ws, targets, tstride, c->probs_buf, c->ustate, c->cfg.beta1, c->cfg.beta2, c->dl, c->col_part};
+    HIP_TRY(c, fade_ln_apply(lb, true, s));
+    if (!rq.push((B + 7) / 8, 256, c->col_part, Gp(P_BO))) return fail(c, FADE_E_INVALID_ARG, "reduction queue full");
   } else {  // fp32 path: feature-major copies of every forward activation that is the left operand of a weight gradient
+    {
+      Prof p(c, "bwd_prep_dlogits");
+      HIP_TRY(c, fade_loss_grad(ws, targets, tstride, B, c->probs_buf, c->ustate, c->cfg.beta1, c->cfg.beta2, c->dl, c->col_part, Gp(P_BO), bf, rq, s));
+    }
     Prof p(c, "transpose", w);
     TransposeBatch tb{};
     auto add = [&](const void *src, int width, void *dst, const float *st, const float *ga, const float *be) {

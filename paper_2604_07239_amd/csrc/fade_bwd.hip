@@ -98,8 +98,8 @@ __device__ __forceinline__ float block_sum(float v, float *red /*[4]*/) {
 // and the first stage of db_o (column sums over this workgroup's 8 streams). Thread = one of the 256 symbols.
 // ---------------------------------------------------------------------------------------------------
 template <typename AT>
-__global__ __launch_bounds__(256) void loss_grad_kernel(WinSrc ws, const uint8_t *targets, long long tstride, int B, const float *probs,
-                                                        UpdateState *u, float beta1, float beta2, AT *dl, float *col_part) {
+__device__ __forceinline__ void loss_grad_body(int block, const WinSrc &ws, const uint8_t *targets, long long tstride, int B, const float *probs,
+                                               UpdateState *u, float beta1, float beta2, AT *dl, float *col_part) {
   __shared__ int cnt[4];
   const int tid = threadIdx.x;
   int mine = 0;
@@ -110,7 +110,7 @@ __global__ __launch_bounds__(256) void loss_grad_kernel(WinSrc ws, const uint8_t
   __syncthreads();
   const int na = cnt[0] + cnt[1] + cnt[2] + cnt[3];
   const float sc = na > 0 ? 1.0f / (float)na : 0.0f;
-  if (blockIdx.x == 0 && tid == 0) {
+  if (block == 0 && tid == 0) {
     u->na = na;
     if (na > 0) {
       u->t += 1;
@@ -119,7 +119,7 @@ __global__ __launch_bounds__(256) void loss_grad_kernel(WinSrc ws, const uint8_t
       u->inv_na = sc;
     }
   }
-  const int b0 = blockIdx.x * 8;
+  const int b0 = block * 8;
   float colsum = 0.0f;
   // targets and flags of the 8 streams first, then the probabilities (all loads in flight together)
   float p[8];
@@ -140,7 +140,13 @@ __global__ __launch_bounds__(256) void loss_grad_kernel(WinSrc ws, const uint8_t
     dl[(size_t)b * 256 + tid] = gq;
     colsum += (float)gq;  // db_o is the column sum of the gradient the products see
   }
-  col_part[(size_t)blockIdx.x * 256 + tid] = colsum;
+  col_part[(size_t)block * 256 + tid] = colsum;
+}
+
+template <typename AT>
+__global__ __launch_bounds__(256) void loss_grad_kernel(WinSrc ws, const uint8_t *targets, long long tstride, int B, const float *probs,
+                                                        UpdateState *u, float beta1, float beta2, AT *dl, float *col_part) {
+  loss_grad_body<AT>(blockIdx.x, ws, targets, tstride, B, probs, u, beta1, beta2, dl, col_part);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -210,6 +216,12 @@ __global__ __launch_bounds__(256) void transpose_batch_kernel(TransposeBatch tb)
 
 template <typename AT, int RPT>
 __global__ __launch_bounds__(256) void ln_apply_kernel(LnApplyBatch lb) {
+  if ((int)blockIdx.y == lb.count) {  // the loss gradient's workgroups (with_loss)
+    const LossGradArgs &l = lb.loss;
+    if ((int)blockIdx.x < (lb.B + 7) / 8)
+      loss_grad_body<AT>(blockIdx.x, l.ws, l.targets, l.tstride, lb.B, l.probs, l.u, l.beta1, l.beta2, static_cast<AT *>(l.dl), l.col_part);
+    return;
+  }
   __shared__ float mom[FADE_GROUP_ROWS_MAX][2];
   const LnApplyArgs &a = lb.a[blockIdx.y];
   const int chunks = lb.Dh / 8;
@@ -1256,9 +1268,11 @@ hipError_t fade_transpose(const TransposeArgs &a, int N, bool bf16, hipStream_t 
   DISPATCH_AT(bf16, transpose_kernel, dim3((a.B + 63) / 64, N / 64), dim3(256), s, a);
 }
 hipError_t fade_ln_apply(const LnApplyBatch &lb, bool bf16, hipStream_t s) {
-  if (lb.count <= 0 || lb.count > 2 || lb.Dh % 8 || lb.Dh < 64) return hipErrorInvalidValue;
-  const int rpt = fade_rows_per_thread((long long)lb.B * lb.count, lb.Dh / 8);
-  const dim3 grid(nblk((size_t)((lb.B + rpt - 1) / rpt) * (lb.Dh / 8), 256), lb.count);
+  if (lb.count < 0 || lb.count > 2 || (lb.count == 0 && !lb.with_loss) || lb.Dh % 8 || lb.Dh < 64) return hipErrorInvalidValue;
+  const int rpt = fade_rows_per_thread((long long)lb.B * (lb.count ? lb.count : 1), lb.Dh / 8);
+  unsigned gx = lb.count ? nblk((size_t)((lb.B + rpt - 1) / rpt) * (lb.Dh / 8), 256) : 1;
+  if (lb.with_loss && gx < (unsigned)((lb.B + 7) / 8)) gx = (unsigned)((lb.B + 7) / 8);
+  const dim3 grid(gx, lb.count + (lb.with_loss ? 1 : 0));
   if (rpt == 4) {
     if (bf16) hipLaunchKernelGGL((ln_apply_kernel<bf16_t, 4>), grid, dim3(256), 0, s, lb);
     else hipLaunchKernelGGL((ln_apply_kernel<float, 4>), grid, dim3(256), 0, s, lb);

@@ -164,7 +164,17 @@ struct TransposeArgs {
 // u = LN(h) written out row-major (the forward pass folds these LayerNorms into the following product and never stores u;
 // the weight gradients of Eq. 7's Down and Eq. 9's pair need it as their left operand)
 struct LnApplyArgs { const void *src; void *dst; const float *stats, *gamma, *beta; };
-struct LnApplyBatch { LnApplyArgs a[2]; int count, B, Dh, stats_n; };
+// The loss gradient (fade_loss_grad's work) can ride in the same launch: it needs nothing the copies produce.
+struct LossGradArgs {
+  WinSrc ws;
+  const uint8_t *targets; long long tstride;
+  const float *probs;
+  UpdateState *u;
+  float beta1, beta2;
+  void *dl;
+  float *col_part;
+};
+struct LnApplyBatch { LnApplyArgs a[2]; int count, B, Dh, stats_n; int with_loss; LossGradArgs loss; };
 hipError_t fade_ln_apply(const LnApplyBatch &lb, bool bf16, hipStream_t s);
 // several transposes in one launch (blockIdx.z picks one)
 struct TransposeBatch {
