@@ -834,26 +834,30 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     if ((rc = run_phase(c, "gemms_router_global", ph))) return rc;
   }
   {
-    Prof p(c, "bwd_slot");
-    if (c->dg_slot) {  // wide slots: dg = d(hm) W_m[Dc-c..Dc)^T as a product
-      GemmArgs g = args_x(c, c->dhm, Dh, (int)d.c, c->WT_mslot, c->P(P_WM) + (d.Dc - d.c) * d.Dh, Dh, c->dg_slot);
-      HIP_TRY(c, fade_gemm(GEMM_X_STORE, bf, g, s));
-    }
+    const bool both = bf && level >= 2 && d.D == 32 && d.Kc <= 128 && d.k * 32 <= d.Kc;  // the matrix-core conv kernel also forms d(input)
     BwdSlotArgs a{};
     a.dg = c->dg_slot;
     a.Dh = Dh; a.Dc = (int)d.Dc; a.c = (int)d.c; a.D = (int)d.D; a.round_bf16 = bf ? 1 : 0; a.dhm = c->dhm; a.Wm = c->P(P_WM);
     a.GG = c->GG; a.GV = c->GV; a.Wg = c->Wg_c; a.Wv = c->Wv_c; a.dgg = c->dgg; a.dgv = c->dgv; a.dxt = c->dxt;
     a.ws = ws; a.B = B; a.T = (int)d.T; a.tabXe32 = c->tabXe32; a.part = c->slot_part;
-    HIP_TRY(c, fade_bwd_slot(a, Gp(P_WG), bf, rq, s));
-  }
-  if (level >= 2) {  // local stream
-    Prof p(c, "bwd_conv");
-    ConvGradArgs a{};
-    a.B = B; a.T = (int)d.T; a.D = (int)d.D; a.taps = (int)d.k; a.XL = c->XL; a.dcv = c->dcv; a.part = c->conv_part;
-    const bool both = bf && d.D == 32 && d.Kc <= 128 && d.k * 32 <= d.Kc;  // the matrix-core kernel also forms d(input)
-    if (both) { a.WT = c->WT_conv; a.dxl = c->dxl; a.Kc = (int)d.Kc; }
-    HIP_TRY(c, fade_conv_grad(a, Gp(P_WCONV), bf, rq, s));  // W_conv then b_conv, adjacent in the blob
-    if (!both) {
+    ConvGradArgs cg{};  // local stream
+    cg.B = B; cg.T = (int)d.T; cg.D = (int)d.D; cg.taps = (int)d.k; cg.XL = c->XL; cg.dcv = c->dcv; cg.part = c->conv_part;
+    {
+      Prof p(c, "bwd_slot");
+      if (c->dg_slot) {  // wide slots: dg = d(hm) W_m[Dc-c..Dc)^T as a product
+        GemmArgs g = args_x(c, c->dhm, Dh, (int)d.c, c->WT_mslot, c->P(P_WM) + (d.Dc - d.c) * d.Dh, Dh, c->dg_slot);
+        HIP_TRY(c, fade_gemm(GEMM_X_STORE, bf, g, s));
+      }
+      if (both) {  // newest-slot backward and conv backward are independent: one launch (W_g then W_v, W_conv then b_conv: adjacent in the blob)
+        cg.WT = c->WT_conv; cg.dxl = c->dxl; cg.Kc = (int)d.Kc;
+        HIP_TRY(c, fade_bwd_slot_conv(a, Gp(P_WG), cg, Gp(P_WCONV), rq, s));
+      } else {
+        HIP_TRY(c, fade_bwd_slot(a, Gp(P_WG), bf, rq, s));
+      }
+    }
+    if (level >= 2 && !both) {
+      Prof p(c, "bwd_conv");
+      HIP_TRY(c, fade_conv_grad(cg, Gp(P_WCONV), bf, rq, s));  // W_conv then b_conv, adjacent in the blob
       GemmArgs g{};
       g.M = (int)(d.B * d.T); g.N = (int)d.D; g.K = (int)d.Kc; g.A = c->dcv; g.T = (int)d.T; g.D = (int)d.D; g.taps = (int)d.k;
       g.W = bf ? c->WT_conv : static_cast<const void *>(c->convt_f32); g.C = c->dxl; g.ldc = (int)d.D;

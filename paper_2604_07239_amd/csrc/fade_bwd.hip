@@ -683,13 +683,13 @@ __global__ __launch_bounds__(256) void bwd_cci_kernel(BwdCciArgs a) {
 // wavefront.
 // ---------------------------------------------------------------------------------------------------
 template <typename AT, int SPW, int KCH>
-__global__ __launch_bounds__(256) void bwd_slot_kernel(BwdSlotArgs a) {
+__device__ __forceinline__ void bwd_slot_body(const BwdSlotArgs &a, int block) {
   constexpr int NS = 4 * SPW;  // streams per workgroup
   __shared__ float dg_s[NS][2][256];  // cache_chunk <= 256
   __shared__ float xt_s[NS][64];      // D <= 64
   __shared__ int sym_s[NS];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int b0 = blockIdx.x * NS + wave * SPW;  // this wavefront's first stream
+  const int b0 = block * NS + wave * SPW;  // this wavefront's first stream
   const int nch = a.Dh / 8;  // 8-wide chunks of a row: lane owns chunks lane, lane + 64, ... (KCH of them)
   float dh[SPW][KCH][8];
 #pragma unroll
@@ -762,7 +762,7 @@ __global__ __launch_bounds__(256) void bwd_slot_kernel(BwdSlotArgs a) {
   // one thread per (stream, channel): the stream's x_t row goes to LDS (zero for an inactive stream: it then adds
   // nothing below), and dxt[channel] = sum_q W_g[channel][q] d gg[q] + W_v[channel][q] d gv[q]
   for (int t = tid; t < NS * a.D; t += 256) {
-    const int k = t / a.D, i = t - k * a.D, b = blockIdx.x * NS + k;
+    const int k = t / a.D, i = t - k * a.D, b = block * NS + k;
     xt_s[k][i] = sym_s[k] >= 0 ? a.tabXe32[(size_t)sym_s[k] * a.D + i] : 0.0f;
     if (b < a.B) {
       float sv = 0.0f;
@@ -777,8 +777,12 @@ __global__ __launch_bounds__(256) void bwd_slot_kernel(BwdSlotArgs a) {
     float sv = 0.0f;
 #pragma unroll
     for (int k = 0; k < NS; ++k) sv = fmaf(xt_s[k][i], dg_s[k][which][q], sv);
-    a.part[(size_t)blockIdx.x * nout + t] = sv;
+    a.part[(size_t)block * nout + t] = sv;
   }
+}
+template <typename AT, int SPW, int KCH>
+__global__ __launch_bounds__(256) void bwd_slot_kernel(BwdSlotArgs a) {
+  bwd_slot_body<AT, SPW, KCH>(a, (int)blockIdx.x);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -861,7 +865,7 @@ __global__ __launch_bounds__(256) void conv_grad_partial_kernel(ConvGradArgs a) 
 // row, so the rows of one fragment need not be equidistant, which is what the per-stream zero rows require). Wavefront r
 // owns tap r; wavefront 0 also forms the bias gradient as a product with a fragment of ones. bf16 x bf16 products are exact in
 // fp32, so this differs from the scalar kernel in summation order only.
-__global__ __launch_bounds__(256) void conv_grad_mfma_kernel(ConvGradArgs a) {
+__device__ __forceinline__ void conv_grad_mfma_body(const ConvGradArgs &a, int block, int nblocks) {
   typedef __attribute__((ext_vector_type(4))) short i16x4;
   typedef __attribute__((ext_vector_type(8))) short i16x8;
   constexpr int D = 32, PITCH = 64, XROWS = 128 + 3 * 32;  // taps <= 4, T >= 4: at most 32 streams x 3 zero rows
@@ -894,7 +898,7 @@ __global__ __launch_bounds__(256) void conv_grad_mfma_kernel(ConvGradArgs a) {
     for (int q = 0; q < 8; ++q) wt[ks][q] = (bf16_t)0.0f;
     if (ks < xsteps) wt[ks] = static_cast<const bf16x8 *>(a.WT)[(size_t)ks * 64 + lane];
   }
-  for (long long chunk = blockIdx.x; chunk < nchunks; chunk += gridDim.x) {
+  for (long long chunk = block; chunk < nchunks; chunk += nblocks) {
     const long long t0 = chunk * 128;
     __syncthreads();  // the zero fill, or the previous chunk's reads, are done
 #pragma unroll
@@ -946,7 +950,7 @@ __global__ __launch_bounds__(256) void conv_grad_mfma_kernel(ConvGradArgs a) {
     }
   }
   const int rows = a.taps * D;
-  float *part = a.part + (size_t)blockIdx.x * (rows + 1) * D;
+  float *part = a.part + (size_t)block * (rows + 1) * D;
   if (wave < a.taps) {
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
@@ -955,6 +959,16 @@ __global__ __launch_bounds__(256) void conv_grad_mfma_kernel(ConvGradArgs a) {
     }
   }
   if (wave == 0 && lane < 32) part[(size_t)rows * D + lane] = accb[0];
+}
+__global__ __launch_bounds__(256) void conv_grad_mfma_kernel(ConvGradArgs a) {
+  conv_grad_mfma_body(a, (int)blockIdx.x, (int)gridDim.x);
+}
+// The newest-slot backward and the conv backward both start from what the mix backward left and feed the embedding
+// backward: independent, so one launch carries both (the first pslot workgroups take the slot part).
+template <int SPW, int KCH>
+__global__ __launch_bounds__(256) void slot_conv_kernel(BwdSlotArgs sa, ConvGradArgs ca, int pslot) {
+  if ((int)blockIdx.x < pslot) bwd_slot_body<bf16_t, SPW, KCH>(sa, (int)blockIdx.x);
+  else conv_grad_mfma_body(ca, (int)blockIdx.x - pslot, (int)gridDim.x - pslot);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -1349,6 +1363,21 @@ hipError_t fade_bwd_slot(const BwdSlotArgs &a, float *dWgv, bool bf16, ReduceBat
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   return rb.push(P, 2 * a.D * a.c, a.part, dWgv) ? hipSuccess : hipErrorInvalidValue;
+}
+// Both of the above in one launch (bf16, D = 32, the matrix-core conv kernel with its input gradient).
+hipError_t fade_bwd_slot_conv(const BwdSlotArgs &sa, float *dWgv, const ConvGradArgs &ca, float *dWb, ReduceBatch &rb, hipStream_t s) {
+  if (sa.Dh > 2048 || sa.Dh % 8 || sa.c > 256 || sa.D > 64) return hipErrorInvalidValue;
+  if (ca.D != 32 || 128 % ca.T || ca.T < 4 || ca.taps > 4 || !ca.WT || !ca.dxl || ca.Kc % 16 || ca.Kc > 128 || ca.taps * 32 > ca.Kc) return hipErrorInvalidValue;
+  const bool narrow = sa.Dh <= 512;
+  const int Ps = narrow ? (sa.B + 15) / 16 : (sa.B + 3) / 4;
+  const long long nchunks = ((long long)ca.B * ca.T + 127) / 128;
+  const int Pc = (int)(nchunks < 512 ? nchunks : 512);
+  if (narrow) hipLaunchKernelGGL((slot_conv_kernel<4, 1>), dim3(Ps + Pc), dim3(256), 0, s, sa, ca, Ps);
+  else hipLaunchKernelGGL((slot_conv_kernel<1, 4>), dim3(Ps + Pc), dim3(256), 0, s, sa, ca, Ps);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (!rb.push(Ps, 2 * sa.D * sa.c, sa.part, dWgv) || !rb.push(Pc, (ca.taps * ca.D + 1) * ca.D, ca.part, dWb)) return hipErrorInvalidValue;
+  return hipSuccess;
 }
 // a.part must hold ceil(B * T / 128) * (taps * D + 1) * D floats; dWb points at W_conv's gradient (b_conv's follows it)
 hipError_t fade_conv_grad(const ConvGradArgs &a, float *dWb, bool bf16, ReduceBatch &rb, hipStream_t s) {

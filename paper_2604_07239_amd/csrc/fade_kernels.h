@@ -316,6 +316,7 @@ struct AdamRefreshBatch {
 hipError_t fade_adam_refresh(const AdamRefreshBatch &ab, hipStream_t s);
 hipError_t fade_bwd_cci(const BwdCciArgs &a, bool bf16, hipStream_t s);
 hipError_t fade_bwd_slot(const BwdSlotArgs &a, float *dWgv, bool bf16, ReduceBatch &rb, hipStream_t s);
+hipError_t fade_bwd_slot_conv(const BwdSlotArgs &sa, float *dWgv, const ConvGradArgs &ca, float *dWb, ReduceBatch &rb, hipStream_t s);
 hipError_t fade_conv_grad(const ConvGradArgs &a, float *dWb, bool bf16, ReduceBatch &rb, hipStream_t s);
 hipError_t fade_bwd_embed(const BwdTokenArgs &a, int nblocks, float *contrib, float *dE, float *dparams, bool bf16, ReduceBatch &rb,
                           hipStream_t s);
