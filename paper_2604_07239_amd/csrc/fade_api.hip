@@ -706,7 +706,7 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
   const void *feat = level >= 5 ? c->Hout : level >= 3 ? c->Hc : level == 2 ? c->Hmix : c->Hg;
   void *dfeat = level >= 5 ? c->dHout : level >= 3 ? c->dHc : c->dHmix1;
   if (bf) {  // the loss gradient, and in the same launch the two left operands the forward pass never stores: LN(H_coarse), LN(H_mix), row-major
-    Prof p(c, "bwd_prep_dlogits");
+    Prof p(c, "bwd_loss_ln_copies");
     LnApplyBatch lb{};
     lb.B = B; lb.Dh = Dh; lb.stats_n = SN;
     if (level >= 5) lb.a[lb.count++] = {c->Hc, c->LT[2], c->stats_f, c->P(P_GAMMA_F), c->P(P_BETA_F)};
@@ -843,7 +843,7 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     ConvGradArgs cg{};  // local stream
     cg.B = B; cg.T = (int)d.T; cg.D = (int)d.D; cg.taps = (int)d.k; cg.XL = c->XL; cg.dcv = c->dcv; cg.part = c->conv_part;
     {
-      Prof p(c, "bwd_slot");
+      Prof p(c, "bwd_slot_conv");
       if (c->dg_slot) {  // wide slots: dg = d(hm) W_m[Dc-c..Dc)^T as a product
         GemmArgs g = args_x(c, c->dhm, Dh, (int)d.c, c->WT_mslot, c->P(P_WM) + (d.Dc - d.c) * d.Dh, Dh, c->dg_slot);
         HIP_TRY(c, fade_gemm(GEMM_X_STORE, bf, g, s));
