@@ -78,13 +78,19 @@ def float_ar1(seed, n):
 def mixed(seed, n, block=64 << 20):
     """Alternating blocks of the text, genome and float sources, block j seeded with seed + j."""
     gens = (text, genome, float_ar1)
-    parts, j, left = [], 0, n
+    jobs, j, left = [], 0, n
     while left > 0:
         m = min(block, left)
-        parts.append(gens[j % 3](seed + j, m))
+        jobs.append((gens[j % 3], seed + j, m))
         left -= m
         j += 1
-    return np.concatenate(parts) if parts else np.empty(0, np.uint8)
+    if not jobs:
+        return np.empty(0, np.uint8)
+    # the blocks are independent (own seed each) and the generators run outside the interpreter lock
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=min(8, len(jobs), os.cpu_count() or 1)) as ex:
+        parts = list(ex.map(lambda q: q[0](q[1], q[2]), jobs))
+    return np.concatenate(parts)
 
 
 _SOURCES = dict(markov2=markov2, text=text, genome=genome, float=float_ar1, mixed=mixed)

@@ -718,6 +718,7 @@ void write_header(const fadeo_ctx *C, uint64_t n, uint8_t *h) {
   put_u16(h + 8, (uint32_t)C->d.T); put_u16(h + 10, (uint32_t)C->d.D); put_u32(h + 12, (uint32_t)C->d.De);
   if (C->d.Dc != C->d.De) put_u32(h + 44, (uint32_t)C->d.Dc);  // 0: the cache is as wide as the refiner
   put_u16(h + 16, (uint32_t)C->d.dl); put_u16(h + 18, (uint32_t)C->d.c); put_u16(h + 20, (uint32_t)C->d.k);
+  h[22] = (uint8_t)(C->cfg.ablation == 0 ? 5u : C->cfg.ablation);  // which stage feeds the head: part of the model's definition
   put_u32(h + 24, (uint32_t)C->d.B);
   put_u32(h + 28, f32_bits(C->cfg.lr)); put_u32(h + 32, f32_bits(C->cfg.beta1));
   put_u32(h + 36, f32_bits(C->cfg.beta2)); put_u32(h + 40, f32_bits(C->cfg.eps));
@@ -731,6 +732,7 @@ int check_header(fadeo_ctx *C, const uint8_t *h, uint64_t *n) {
                     get_u16(h + 10) == C->d.D && get_u32(h + 12) == C->d.De && get_u32(h + 44) == (C->d.Dc != C->d.De ? C->d.Dc : 0) &&
                     get_u16(h + 16) == C->d.dl &&
                     get_u16(h + 18) == C->d.c && get_u16(h + 20) == C->d.k && get_u32(h + 24) == C->d.B &&
+                    h[22] == (C->cfg.ablation == 0 ? 5u : C->cfg.ablation) &&
                     get_u32(h + 28) == f32_bits(C->cfg.lr) && get_u32(h + 32) == f32_bits(C->cfg.beta1) &&
                     get_u32(h + 36) == f32_bits(C->cfg.beta2) && get_u32(h + 40) == f32_bits(C->cfg.eps);
   if (!same) return fail(C, FADEO_E_BAD_CONFIG, "container was written with a different configuration");

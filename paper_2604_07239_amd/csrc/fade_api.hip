@@ -1367,6 +1367,7 @@ int fade_encode(fade_ctx *c, const uint8_t *src_host, size_t n, uint8_t *dst_hos
     wr16(h + 8, (uint32_t)c->d.T); wr16(h + 10, (uint32_t)c->d.D); wr32(h + 12, (uint32_t)c->d.De);
     if (c->d.Dc != c->d.De) wr32(h + 44, (uint32_t)c->d.Dc);  // 0: the cache is as wide as the refiner
     wr16(h + 16, (uint32_t)c->d.dl); wr16(h + 18, (uint32_t)c->d.c); wr16(h + 20, (uint32_t)c->d.k);
+    h[22] = (uint8_t)(c->cfg.ablation == 0 ? 5 : c->cfg.ablation);  // the stage that feeds the head (same blob, same hash, another model)
     wr32(h + 24, (uint32_t)B);
     wr32(h + 28, fbits(c->cfg.lr)); wr32(h + 32, fbits(c->cfg.beta1)); wr32(h + 36, fbits(c->cfg.beta2)); wr32(h + 40, fbits(c->cfg.eps));
     wr64(h + 48, n); wr64(h + 56, c->weights_hash);
@@ -1387,6 +1388,7 @@ int fade_decode(fade_ctx *c, const uint8_t *src_host, size_t src_len, uint8_t *d
   if (std::memcmp(h, "FADE", 4) != 0 || rd16(h + 4) != 1) return fail(c, FADE_E_CORRUPT_STREAM, "bad magic or version");
   const bool same = h[6] == c->cfg.dtype && h[7] == c->cfg.update_mode && rd16(h + 8) == c->d.T && rd16(h + 10) == c->d.D &&
                     rd32(h + 12) == c->d.De && rd32(h + 44) == (c->d.Dc != c->d.De ? c->d.Dc : 0) && rd16(h + 16) == c->d.dl && rd16(h + 18) == c->d.c && rd16(h + 20) == c->d.k &&
+                    h[22] == (c->cfg.ablation == 0 ? 5u : c->cfg.ablation) &&
                     rd32(h + 24) == B && rd32(h + 28) == fbits(c->cfg.lr) && rd32(h + 32) == fbits(c->cfg.beta1) &&
                     rd32(h + 36) == fbits(c->cfg.beta2) && rd32(h + 40) == fbits(c->cfg.eps);
   if (!same) return fail(c, FADE_E_BAD_CONFIG, "container was written with a different configuration");

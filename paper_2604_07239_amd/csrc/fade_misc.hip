@@ -287,10 +287,16 @@ __global__ __launch_bounds__(256) void embed_steps_kernel(EmbedArgs a, int rpb) 
       if (XL) *reinterpret_cast<f32x4 *>(XL + e0) = *reinterpret_cast<const f32x4 *>(tabXl + (size_t)sy * a.D + i);
     }
     bf16_t *M = static_cast<bf16_t *>(a.M) + (size_t)r * a.Dc;
-    const long long first_slot = 2ll * a.T - 1 - w.i;  // slot j was appended at step i - (T - 1 - j), a model step iff that is >= T
+    // The cache holds Dc / c slots, oldest first. Slot j was appended at step i - (slots - 1 - j), a model step iff that is
+    // >= T, and holds Eq. 1's entry of the symbol that was newest then, x[i - slots + j] = win[T - slots + j]: inside the
+    // window when there are at most T slots, otherwise further back in the stream's own bytes (never before its start:
+    // a model step's newest symbol has index >= T - 1).
+    const int slots = a.Dc / a.c;
+    const long long first_slot = (long long)slots - 1 + a.T - w.i;
+    const uint8_t *newest = win + (a.T - slots);
     for (int idx = tid; idx < a.Dc; idx += 256) {
       const int j = idx / a.c, qq = idx - j * a.c;
-      M[idx] = j >= first_slot ? tab[(size_t)win[j] * a.c + qq] : (bf16_t)0.0f;
+      M[idx] = j >= first_slot ? tab[(size_t)newest[j] * a.c + qq] : (bf16_t)0.0f;
     }
   }
   if (a.conv_W) {  // wavefront w: row w / tiles-per-row of this workgroup, tokens 32 (w % tiles-per-row) ..

@@ -350,6 +350,37 @@ def test_multi_step_encode_equals_single_steps(B, T, D, H, n, widths, monkeypatc
     assert outs["1"].tobytes() == outs[None].tobytes()
 
 
+@pytest.mark.parametrize("chunk", [16, 4])
+def test_multi_step_encode_with_explicit_cache_chunk(chunk, monkeypatch):
+    """A cache whose slot count differs from the window length (T = 8; 64 / 16 = 4 slots, 64 / 4 = 16 slots): the pass
+    that rebuilds the cache from the stream's bytes must pick the symbols the rolling cache appended, also the ones that
+    have already left the window. Multi-step containers equal the single-step one byte for byte, both round-trip, and the
+    size matches the oracle's."""
+    need_gpu()
+    import paper_2604_07239_amd as fa
+    B, T, D, H, n = 9, 8, 32, 64, 9 * 61 + 4
+    blob = fi.init_blob(B, T, D, H, 5, std=0.05, c=chunk)
+    src = fi.text(23, n)
+    outs = {}
+    for steps in ("1", "5", None):
+        if steps is None:
+            monkeypatch.delenv("FADE_STEPS_PER_PASS", raising=False)
+        else:
+            monkeypatch.setenv("FADE_STEPS_PER_PASS", steps)
+        g = fa.Fade(fa.make_config(B, T, D, H, dtype=fa.BF16, cache_chunk=chunk))
+        g.load_weights(blob.data)
+        _log(f"multi-step encode cache_chunk={chunk} steps/pass={steps}")
+        outs[steps] = g.encode(src)
+        np.testing.assert_array_equal(g.decode(outs[steps], n), src)
+        g.close()
+    assert outs["1"].tobytes() == outs["5"].tobytes()
+    assert outs["1"].tobytes() == outs[None].tobytes()
+    o = orc.Oracle(orc.make_config(B, T, D, H, dtype=orc.BF16, cache_chunk=chunk))
+    o.load_weights(blob.data)
+    co = o.encode(src)
+    assert abs(outs["1"].size - co.size) <= 0.005 * co.size + 2 * B
+
+
 def test_multi_step_encode_config2_full_batch():
     """The same identity at benchmark configuration 2's full batch, where a pass carries 16 x 1024 rows through the
     tall-product tiles and in-workgroup split sums that bench.py's frozen compression times."""
@@ -448,6 +479,27 @@ def test_error_paths_from_host():
     assert e.value.code == -4
     g.load_weights(blob.data)
     np.testing.assert_array_equal(g.decode(c, 300), src)   # the context survives every error above
+    # another ablation level reads the same blob (same hash) as another model: the header's level byte refuses it
+    g3 = fa.Fade(fa.make_config(5, 8, 32, 64, ablation=3))
+    g3.load_weights(blob.data)
+    with pytest.raises(fa.FadeError) as e:
+        g3.decode(c, 300)
+    assert e.value.code == -2
+    g3.close()
+    # corrupted payload bytes: the decoder reads only inside each stream's own payload (lengths are checked on the host,
+    # reads past a payload's end return zeros), so the call ends with CORRUPT_STREAM or with wrong bytes, never a fault
+    rng = np.random.default_rng(3)
+    body = 64 + 4 * 5
+    for trial in range(6):
+        m = c.copy()
+        pos = rng.integers(body, c.size, 4)
+        m[pos] ^= rng.integers(1, 256, 4).astype(np.uint8)
+        try:
+            out = g.decode(m, 300)
+            assert out.size == 300
+        except fa.FadeError as e2:
+            assert e2.code == -6
+    np.testing.assert_array_equal(g.decode(c, 300), src)
     with pytest.raises(fa.FadeError) as e:
         fa.Fade(fa.make_config(5, 8, 24, 64))               # unsupported D
     assert e.value.code == -2

@@ -98,6 +98,15 @@ def test_container_error_paths():
     with pytest.raises(orc.OracleError) as e:
         o2.decode(c, 90)               # different configuration
     assert e.value.code == -2
+    # another ablation level is another model on the same blob (same hash): the header records the level
+    o3, b3, _ = tiny_oracle(B=3, ablation=3)
+    o3.load_weights(blob.data)
+    with pytest.raises(orc.OracleError) as e:
+        o3.decode(c, 90)
+    assert e.value.code == -2
+    c3 = o3.encode(src)
+    assert c3[22] == 3 and c[22] == 5
+    np.testing.assert_array_equal(o3.decode(c3, 90), src)
 
 
 def test_bad_configs_rejected():
