@@ -3,12 +3,16 @@
 
 A "step" is one pass of the whole hot path over one batch: for each of the B streams the model step
 (embedding -> DMD -> HGR -> head -> softmax -> frequency table), the arithmetic coding of the next byte
-and, in online mode, the weight update. The workload is benchmark configuration 2 (64 MiB text-like
-source, B = 1024 streams, T = 64, D = 32, H = 256, bf16 operands): the timed region codes steps
-[T + W, T + W + K) of every stream with the input already resident in HBM, first compressing, then
-decompressing the same bytes (checked byte-exact). `--full` runs the whole job end to end instead.
-The headline (`value`) is the method as Algorithm 1 defines it, weights updated after every coded symbol; the default run also
-measures the same steps with frozen weights (inference only) and reports them under `frozen_weights`.
+and, in online mode, the weight update. The workload is benchmark configuration 5, the largest of the five
+(1 GiB mixed source in 64 MiB blocks, B = 16384 streams, T = 64, D = 32, H = 512, bf16 operands): the timed
+region codes steps [T + W, T + W + K) of every stream with the input already resident in HBM, first
+compressing, then decompressing the same bytes (checked byte-exact). Only the first T + W + K bytes of every
+stream travel to the GPU (the generators still produce the whole 1 GiB: a stream's first bytes depend on
+everything before them in its block). `--full` runs the whole job end to end instead; `--config` picks
+another configuration (1-5, or 6: the paper's default model shape).
+The headline (`value`) is the method as Algorithm 1 defines it, weights updated after every coded symbol; the
+default run also measures the same steps with frozen weights (inference only) and reports them under
+`frozen_weights`.
 
 Prints ONE JSON line (see the keys below); `roofline` describes the dominant kernel (the D_h x D_h router /
 gate product), timed with HIP events on the library's stream in a second pass over the same steps;
@@ -28,9 +32,17 @@ sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK = 2.5e15   # MI355X dense bf16, FLOP/s
 HBM_PEAK = 8.0e12         # B/s
-ROUTER_GATE_TRAFFIC_BYTES = {(2, "frozen"): int(0.5 * (320.5 + 66.0 + 314.1 + 66.1) * (1 << 20)), (2, "online"): int(0.5 * (56.4 + 53.5) * (1 << 20))}
-# adam_refresh_kernel, same counter runs (profiles/cfg2_online_kernel_trace_and_hbm.md)
-ADAM_TRAFFIC_BYTES = {(2, "online"): int((171.59 + 167.46) * (1 << 20))}
+MiB = 1 << 20
+# HBM bytes per launch of the router / gate product by launch shape (rows M of the launch, update mode): scaled
+# FETCH_SIZE + WRITE_SIZE of counter runs of this same program, one row of the named file under profiles/ each
+# (FETCH x 2.0, WRITE x 1.0 against a plain 256 MiB copy, see profiles/cfg2_frozen_pmc_counters.md). A shape that
+# was not profiled reports null.
+ROUTER_GATE_TRAFFIC_BYTES = {
+    (16384, 2048, "frozen"): int(0.5 * (320.5 + 66.0 + 314.1 + 66.1) * MiB),   # profiles/cfg2_frozen_multistep_kernel_trace_and_hbm.md
+    (1024, 2048, "online"): int(0.5 * (56.4 + 53.5) * MiB),                    # profiles/cfg2_online_kernel_trace_and_hbm.md
+}
+# adam_refresh_kernel by (parameters of the nine big matrices, mode), same counter runs
+ADAM_TRAFFIC_BYTES = {(11272192, "online"): int((171.59 + 167.46) * MiB)}      # profiles/cfg2_online_kernel_trace_and_hbm.md
 
 
 def parse():
@@ -38,7 +50,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2048)
     ap.add_argument("--warmup", type=int, default=64)
-    ap.add_argument("--config", type=int, default=2, help="benchmark configuration (1-5; 6 = the paper-default model shape)")
+    ap.add_argument("--config", type=int, default=5, help="benchmark configuration (1-5; 6 = the paper-default model shape)")
     ap.add_argument("--mode", choices=["frozen", "online"], default=None)
     ap.add_argument("--ablation", type=int, default=0, choices=[0, 1, 2, 3, 4, 5],
                     help="head on a prefix of the model (the paper's progressive ablation)")
@@ -46,8 +58,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 256 MiB device copy (torch) so that a counter run can be scaled against known traffic")
-    ap.add_argument("--oracle-streams", type=int, default=64)
-    ap.add_argument("--oracle-steps", type=int, default=None, help="model steps of the oracle sample (default 24)")
+    ap.add_argument("--oracle-streams", type=int, default=None, help="streams of the oracle sample (default 64, 48 at B >= 16384)")
+    ap.add_argument("--oracle-steps", type=int, default=32, help="model steps of the oracle sample")
     return ap.parse_args()
 
 
@@ -81,8 +93,12 @@ def main():
         widths["ablation"] = a.ablation
     K, W = a.steps, a.warmup
 
+    t_gen = time.perf_counter()
     full = fi.config_bytes(a.config)
     L = full.size // B
+    Bo = min(a.oracle_streams or (48 if B >= 16384 else 64), B)
+    So = a.oracle_steps
+    osrc = np.ascontiguousarray(full.reshape(B, L)[:Bo, :T + So]).reshape(-1)   # the oracle's sample of the same workload
     if a.full:
         src = full
         first, count = 0, 0
@@ -91,8 +107,16 @@ def main():
         K = steps_total - T - W
         src = np.ascontiguousarray(full.reshape(B, L)[:, :steps_total]).reshape(-1)
         first, count = T + W, K
+    del full
     n = src.size
     blob = fi.config_blob(a.config)
+    print(f"[bench] cfg{a.config}: input and weights generated in {time.perf_counter() - t_gen:.1f} s", file=sys.stderr, flush=True)
+    # frozen bf16 compression carries several steps of every stream through one pass (fade_create's rule, restated)
+    spp = 1
+    if spec["dtype"] == "bf16":
+        spp = max(1, min(256, 16384 // B, (1 << 26) // (B * Dh)))
+        if os.environ.get("FADE_STEPS_PER_PASS"):
+            spp = max(1, min(256, int(os.environ["FADE_STEPS_PER_PASS"])))
 
     def measure(mode):
         """compress + decompress of the timed steps in one update mode, then the event-profiled pass"""
@@ -135,11 +159,15 @@ def main():
         dec_MBps = bytes_timed / t_dec / 1e6
 
         # second pass over the same steps with a HIP event pair around every launch (on the library's stream)
+        # (whole passes only, so that every launch of a kernel has one shape and the per-launch figures below are exact)
         prof = {}
+        steps_prof = count
         if not a.full:
+            if mode == "frozen" and count >= spp:
+                steps_prof = count // spp * spp
             g.encode_device(src_dev, n, 0, first)
             g.profile(True)
-            g.encode_device(src_dev, n, first, count)
+            g.encode_device(src_dev, n, first, steps_prof)
             prof = g.profile_read()
             g.profile(False)
         kern = {k: {"avg_us": 1e3 * ms / max(cnt, 1), "launches": int(cnt)} for k, (ms, cnt) in prof.items()}
@@ -149,20 +177,18 @@ def main():
             twins = [kern[k]["avg_us"] for k in ("gemm_router", "gemm_gate") if k in kern]
             us = sum(twins) / len(twins)
             # frozen compression carries several steps of every stream through one launch: rows = B * steps per pass
-            rows = B * steps_timed // max(kern["gemm_router"]["launches"], 1)
+            rows = B * steps_prof // max(kern["gemm_router"]["launches"], 1)
             flop = 2.0 * rows * Dh * Dh
             ach = flop / (us * 1e-6) / 1e12
-            # HBM bytes per launch: FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 from profiles/cfg2_frozen_multistep_kernel_trace_and_hbm.md
-            # and profiles/cfg2_online_kernel_trace_and_hbm.md (counter runs of this same program, scaled against a 256 MiB copy);
-            # only known for the configuration and modes profiled.
-            traffic = ROUTER_GATE_TRAFFIC_BYTES.get((a.config, mode))
+            # HBM bytes per launch of this shape from the counter runs under profiles/ (null for a shape that was not profiled)
+            traffic = ROUTER_GATE_TRAFFIC_BYTES.get((rows, Dh, mode))
             roofline = {"bound": "mfma", "kernel": f"gemm_pipe_kernel (router / gate product, M={rows}, N=K=D_h)", "achieved": round(ach, 2),
                         "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s", "frac": round(ach * 1e12 / MFMA_BF16_PEAK, 4),
                         "traffic": traffic, "avg_us": round(us, 2), "flop_per_launch": flop,
                         "algorithmic_bytes_per_launch": 2 * ((6 if mode == "online" else 5) * rows * Dh + Dh * Dh)}
         if roofline is None and "gemm_global" in kern and spec["dtype"] == "bf16":   # ablation level 1: the global projection is all there is
             us = kern["gemm_global"]["avg_us"]
-            rows = B * steps_timed // max(kern["gemm_global"]["launches"], 1)
+            rows = B * steps_prof // max(kern["gemm_global"]["launches"], 1)
             flop = 2.0 * rows * Dc * Dh
             ach = flop / (us * 1e-6) / 1e12
             roofline = {"bound": "mfma", "kernel": f"gemm_pipe_kernel (global projection, M={rows}, K=D_cache, N=D_h)", "achieved": round(ach, 2),
@@ -173,7 +199,7 @@ def main():
             # refiner-dominated shapes (D_e >> D_h, the paper's default model): the dominant product is Eq. 9's pair
             # H_coarse [W_fg | W_fv], M rows x K = D_h x N = 2 D_e, fp32 output for the folded LayerNorm + GeGLU that follows
             us = kern["gemm_fnr_in"]["avg_us"]
-            rows = B * steps_timed // max(kern["gemm_fnr_in"]["launches"], 1)
+            rows = B * steps_prof // max(kern["gemm_fnr_in"]["launches"], 1)
             flop = 2.0 * rows * Dh * 2 * De
             ach = flop / (us * 1e-6) / 1e12
             roofline = {"bound": "mfma", "kernel": f"gemm_pipe_kernel (refiner input product, M={rows}, K=D_h, N=2 D_e)", "achieved": round(ach, 2),
@@ -191,8 +217,8 @@ def main():
             ach = nbytes / (us * 1e-6) / 1e9
             update_roofline = {"bound": "hbm", "kernel": "adam_refresh_kernel (Adam + operand refresh of the nine big matrices)",
                                "achieved": round(ach, 1), "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": round(ach * 1e9 / HBM_PEAK, 4),
-                               "traffic": ADAM_TRAFFIC_BYTES.get((a.config, mode)), "avg_us": round(us, 2), "algorithmic_bytes_per_launch": nbytes}
-        step_us_events = sum(v["avg_us"] * v["launches"] for k, v in kern.items() if k != "code_uniform") / max(steps_timed, 1)
+                               "traffic": ADAM_TRAFFIC_BYTES.get((P, mode)), "avg_us": round(us, 2), "algorithmic_bytes_per_launch": nbytes}
+        step_us_events = sum(v["avg_us"] * v["launches"] for k, v in kern.items() if k != "code_uniform") / max(steps_prof if not a.full else steps_timed, 1)
         return dict(t_enc=t_enc, t_dec=t_dec, ok=ok, steps_timed=steps_timed, bytes_timed=bytes_timed, container=container, enc_MBps=enc_MBps,
                     dec_MBps=dec_MBps, kern=kern, roofline=roofline, update_roofline=update_roofline, step_us_events=step_us_events)
 
@@ -215,12 +241,10 @@ def main():
     cpu = None
     if not a.no_cpu_baseline:
         import oracle as orc
-        Bo, So = min(a.oracle_streams, B), (a.oracle_steps or 24)
         sub = fi.slice_blob(blob, spec, Bo) if Bo != B else blob
         o = orc.Oracle(orc.make_config(Bo, T, D, H, **widths, dtype=orc.BF16 if spec["dtype"] == "bf16" else orc.F32,
                                        update_mode=orc.ONLINE_ADAM if mode == "online" else orc.FROZEN))
         o.load_weights(sub.data)
-        osrc = np.ascontiguousarray(full.reshape(B, L)[:Bo, :T + So]).reshape(-1)
         t0 = time.perf_counter()
         oc = o.encode(osrc)
         t_o = time.perf_counter() - t0
