@@ -167,6 +167,17 @@ int fade_coder_encode_tables(fade_ctx *ctx, const uint16_t *freq_dev, const uint
 int fade_coder_decode_tables(fade_ctx *ctx, const uint16_t *freq_dev, size_t n_steps, size_t n_streams,
                              const uint8_t *in_dev, size_t cap, const uint32_t *len_dev, uint8_t *sym_dev);
 
+/* fade_coder_encode_tables for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): same arguments, same output bit for bit, but the per-stream coder state lives
+ * in a fixed array inside the library's device image (8 x uint32 per stream, FADE_NOALLOC_MAX_STREAMS streams, 2 MiB per
+ * GPU, held until the process ends) instead of a temporary allocation. The call allocates and frees nothing.
+ * n_streams > FADE_NOALLOC_MAX_STREAMS => FADE_E_INVALID_ARG. Every call on a GPU shares that GPU's array (also across
+ * contexts): calls that overlap in time on one GPU race; one after the other they are independent, each call
+ * re-initialises the state it uses. Synchronises before returning. */
+#define FADE_NOALLOC_MAX_STREAMS 65536
+int fade_coder_encode_tables_noalloc(fade_ctx *ctx, const uint16_t *freq_dev, const uint8_t *sym_dev, size_t n_steps,
+                                     size_t n_streams, uint8_t *out_dev, size_t cap, uint32_t *len_dev);
+
 /* Debug/test taps: copy an intermediate activation of the most recent step to host as fp32, [B][width].
  * `which` uses FADE_TAP_*; returns the width (0 if unknown); out_host may be NULL to query the width. */
 enum {

@@ -66,6 +66,7 @@ def lib():
         L.fade_quantize.argtypes = [vp, vp, sz, vp]
         L.fade_coder_encode_tables.argtypes = [vp, vp, vp, sz, sz, vp, sz, vp]
         L.fade_coder_decode_tables.argtypes = [vp, vp, sz, sz, vp, sz, vp, vp]
+        L.fade_coder_encode_tables_noalloc.argtypes = [vp, vp, vp, sz, sz, vp, sz, vp]
         L.fade_tap.restype = sz
         L.fade_tap.argtypes = [vp, C.c_int, vp, sz]
         L.fade_get_weights.argtypes = [vp, vp, sz]
@@ -210,6 +211,9 @@ class Fade:
 
     def coder_encode_tables(self, freq_dev, sym_dev, n_steps, n_streams, out_dev, cap, len_dev):
         self._chk(self.L.fade_coder_encode_tables(self.h, _dp(freq_dev), _dp(sym_dev), n_steps, n_streams, _dp(out_dev), cap, _dp(len_dev)))
+
+    def coder_encode_tables_noalloc(self, freq_dev, sym_dev, n_steps, n_streams, out_dev, cap, len_dev):
+        self._chk(self.L.fade_coder_encode_tables_noalloc(self.h, _dp(freq_dev), _dp(sym_dev), n_steps, n_streams, _dp(out_dev), cap, _dp(len_dev)))
 
     def coder_decode_tables(self, freq_dev, n_steps, n_streams, in_dev, cap, len_dev, sym_dev):
         self._chk(self.L.fade_coder_decode_tables(self.h, _dp(freq_dev), n_steps, n_streams, _dp(in_dev), cap, _dp(len_dev), _dp(sym_dev)))

@@ -103,6 +103,34 @@ uint32_t fbits(float f) { uint32_t u; std::memcpy(&u, &f, 4); return u; }
 
 }  // namespace
 
+// Coder state of fade_coder_encode_tables_noalloc: device memory that lives in the library's image instead of coming from
+// hipMalloc (eight uint32 per stream: low, high, pending, bit buffer, bit count, position, value, bit position). Every GPU
+// the library runs on holds its own copy until the process ends. The name below is a host-side stand-in, not a device
+// address: host code only ever uses the pointer hipGetSymbolAddress returns for the current device (scratch_for_device).
+static __device__ __align__(256) uint32_t scratch[8 * FADE_NOALLOC_MAX_STREAMS];
+
+namespace {
+constexpr int kMaxDevices = 64;
+uint32_t *g_scratch_ptr[kMaxDevices] = {};
+// Address of `scratch` on `device`, looked up once per device with that device current.
+hipError_t scratch_for_device(int device, uint32_t **out) {
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  if (!g_scratch_ptr[device]) {
+    int cur = -1;
+    hipError_t e = hipGetDevice(&cur);
+    if (e != hipSuccess) return e;
+    if (cur != device && (e = hipSetDevice(device)) != hipSuccess) return e;
+    void *p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (cur != device) (void)hipSetDevice(cur);
+    if (e != hipSuccess) return e;
+    g_scratch_ptr[device] = static_cast<uint32_t *>(p);
+  }
+  *out = g_scratch_ptr[device];
+  return hipSuccess;
+}
+}  // namespace
+
 struct fade_ctx {
   fade_config cfg;
   Dims d;
@@ -176,6 +204,7 @@ struct fade_ctx {
   uint8_t *ones = nullptr;
   WinSrc last_ws{};
   int *dev_err = nullptr;
+  uint32_t *scratch_dev = nullptr;   // this device's copy of the file-scope scratch array (see scratch_for_device)
   size_t loop_n = 0, loop_next = 0;  // job size and next step of the device-resident loop in progress
   int loop_mode = 0;
   bool enc_complete = false;
@@ -1025,6 +1054,7 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
   if (hipSetDevice(cfg->device) != hipSuccess) return FADE_E_HIP;
   fade_ctx *c = new (std::nothrow) fade_ctx();
   if (!c) return FADE_E_OOM;
+  if (scratch_for_device(cfg->device, &c->scratch_dev) != hipSuccess) { delete c; return FADE_E_HIP; }
   c->cfg = *cfg;
   if (c->cfg.lr == 0.0f) c->cfg.lr = 1e-3f;
   if (c->cfg.beta1 == 0.0f) c->cfg.beta1 = 0.9f;
@@ -1423,21 +1453,27 @@ int fade_quantize(fade_ctx *c, const float *probs_dev, size_t rows, uint16_t *fr
   return check_dev_err(c);
 }
 
+// `state`: 8 * n_streams uint32 of device memory for the coder state, or NULL: allocated here and freed on return. With a
+// caller-provided state nothing in here allocates (flags are cleared by a kernel, not by a memset node).
 static int coder_tables(fade_ctx *c, const uint16_t *freq_dev, uint8_t *sym_dev, size_t n_steps, size_t n_streams, uint8_t *buf_dev,
-                        size_t cap, uint32_t *len_dev, int mode) {
+                        size_t cap, uint32_t *len_dev, int mode, uint32_t *state = nullptr) {
   if (!c || (!freq_dev && n_steps) || (!sym_dev && n_steps) || !buf_dev || !len_dev || n_streams == 0) return FADE_E_INVALID_ARG;
   hipStream_t s = c->stream;
-  // private coder state for n_streams streams
-  uint32_t *state = nullptr;
-  hipError_t e = hipMalloc(reinterpret_cast<void **>(&state), 8 * n_streams * sizeof(uint32_t));
-  if (e != hipSuccess) return hip_fail(c, e, "hipMalloc(coder state)");
+  const bool own_state = state == nullptr;
+  hipError_t e = hipSuccess;
+  if (own_state) {  // private coder state for n_streams streams
+    e = hipMalloc(reinterpret_cast<void **>(&state), 8 * n_streams * sizeof(uint32_t));
+    if (e != hipSuccess) return hip_fail(c, e, "hipMalloc(coder state)");
+  }
   CoderBufs cb{};
   cb.low = state; cb.high = state + n_streams; cb.pending = state + 2 * n_streams; cb.bitbuf = state + 3 * n_streams;
   cb.nbits = state + 4 * n_streams; cb.pos = state + 5 * n_streams; cb.value = state + 6 * n_streams; cb.bitpos = state + 7 * n_streams;
   cb.out = buf_dev; cb.in = buf_dev; cb.in_len = len_dev; cb.cap = cap; cb.err = c->dev_err;
   int rc = FADE_OK;
   do {
-    if ((e = hipMemsetAsync(c->dev_err, 0, sizeof(int), s)) != hipSuccess) { rc = hip_fail(c, e, "memset"); break; }
+    if (own_state) e = hipMemsetAsync(c->dev_err, 0, sizeof(int), s);
+    else e = fade_fill_u32(reinterpret_cast<uint32_t *>(c->dev_err), 0u, 1, s);
+    if (e != hipSuccess) { rc = hip_fail(c, e, "clear error flag"); break; }
     if ((e = fade_coder_init(cb, (int)n_streams, mode == CODE_DECODE, s)) != hipSuccess) { rc = hip_fail(c, e, "coder_init"); break; }
     for (size_t i = 0; i < n_steps && rc == FADE_OK; ++i) {
       e = fade_code_tables(freq_dev + i * n_streams * 256, sym_dev + i * n_streams, (int)n_streams, cb, mode, s);
@@ -1452,8 +1488,19 @@ static int coder_tables(fade_ctx *c, const uint16_t *freq_dev, uint8_t *sym_dev,
     if ((e = hipStreamSynchronize(s)) != hipSuccess) { rc = hip_fail(c, e, "sync"); break; }
     rc = check_dev_err(c);
   } while (0);
-  (void)hipFree(state);
+  if (own_state) (void)hipFree(state);
   return rc;
+}
+
+int fade_coder_encode_tables_noalloc(fade_ctx *c, const uint16_t *freq_dev, const uint8_t *sym_dev, size_t n_steps, size_t n_streams,
+                                     uint8_t *out_dev, size_t cap, uint32_t *len_dev) {
+  if (!c) return FADE_E_INVALID_ARG;
+  if (n_streams > FADE_NOALLOC_MAX_STREAMS)
+    return fail(c, FADE_E_INVALID_ARG, "fade_coder_encode_tables_noalloc: n_streams exceeds FADE_NOALLOC_MAX_STREAMS (65536)");
+  if (!c->scratch_dev) return fail(c, FADE_E_HIP, "scratch array has no device address");
+  // coder_init rewrites all eight state words of every stream it will use, so what the previous call left behind in the
+  // shared array is never read
+  return coder_tables(c, freq_dev, const_cast<uint8_t *>(sym_dev), n_steps, n_streams, out_dev, cap, len_dev, CODE_ENCODE, c->scratch_dev);
 }
 
 int fade_coder_encode_tables(fade_ctx *c, const uint16_t *freq_dev, const uint8_t *sym_dev, size_t n_steps, size_t n_streams,

@@ -141,6 +141,7 @@ hipError_t fade_quantize_rows(const float *probs, size_t rows, uint16_t *freq, i
 hipError_t fade_code_tables(const uint16_t *freq, uint8_t *sym, int n_streams, const CoderBufs &cb, int mode, hipStream_t s);
 hipError_t fade_code_uniform(const WinSrc &ws, uint8_t *sym_base, int B, const CoderBufs &cb, int mode, hipStream_t s);
 hipError_t fade_coder_init(const CoderBufs &cb, int B, int decode, hipStream_t s);
+hipError_t fade_fill_u32(uint32_t *dst, uint32_t value, size_t n, hipStream_t s);  // a fill as a kernel (safe to capture in a graph, unlike a memset node)
 hipError_t fade_coder_finish(const CoderBufs &cb, int B, long long stride, long long n, hipStream_t s);
 hipError_t fade_payload_move(uint8_t *strided, size_t cap, uint8_t *flat, const unsigned long long *offsets, const uint32_t *lens, int B,
                              int gather, hipStream_t s);

@@ -994,6 +994,15 @@ hipError_t fade_embed_steps(const EmbedArgs &a, hipStream_t s) {
   hipLaunchKernelGGL(embed_steps_kernel, dim3((a.B * a.S + rpb - 1) / rpb), dim3(256), 0, s, a, rpb);
   return hipGetLastError();
 }
+__global__ void fill_u32_kernel(uint32_t *dst, uint32_t value, size_t n) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = value;
+}
+hipError_t fade_fill_u32(uint32_t *dst, uint32_t value, size_t n, hipStream_t s) {
+  if (!n) return hipSuccess;
+  hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, dst, value, n);
+  return hipGetLastError();
+}
 hipError_t fade_slot_table(const float *tabXe32, const float *Wg, const float *Wv, int D, int c, void *tab_bf16, hipStream_t s) {
   hipLaunchKernelGGL(slot_table_kernel, dim3(256), dim3(64), 0, s, tabXe32, Wg, Wv, D, c, static_cast<bf16_t *>(tab_bf16));
   return hipGetLastError();
