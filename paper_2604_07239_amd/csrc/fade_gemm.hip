@@ -16,6 +16,7 @@
 //     row tiles: each XCD then pulls only its 1/8 of W through its L2.
 // fp32 path (small-batch configuration): same prologues/epilogues around a plain FMA core.
 #include <cstdlib>
+#include <type_traits>
 
 #include "fade_dev.h"
 #include "fade_kernels.h"
@@ -448,6 +449,24 @@ __device__ __forceinline__ void dma16(const bf16_t *src, unsigned char *lds_chun
                                    (__attribute__((address_space(3))) void *)lds_chunk, 16, 0, 0);
 }
 
+// LDS fragment reads whose completion is waited for by hand: the compiler would wait for every outstanding read before the
+// first matrix instruction of a group (s_waitcnt lgkmcnt(0)), also for the reads just issued for the next group. Reads issued
+// through lds_read16 are invisible to it; lds_wait<N> lets the N youngest stay in flight (LDS returns in order) and
+// lds_landed ties the value to the wait, so that no use can move above it.
+template <int OFF> __device__ __forceinline__ bf16x8 lds_read16(uint32_t addr) {
+  typedef __attribute__((ext_vector_type(4))) int i32x4;
+  i32x4 v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+  return __builtin_bit_cast(bf16x8, v);
+}
+template <int N> __device__ __forceinline__ void lds_wait() { asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory"); }
+__device__ __forceinline__ void lds_landed(bf16x8 &v) {
+  typedef __attribute__((ext_vector_type(4))) int i32x4;
+  i32x4 t = __builtin_bit_cast(i32x4, v);
+  asm volatile("" : "+v"(t));
+  v = __builtin_bit_cast(bf16x8, t);
+}
+
 template <int BM, int BN, int STAGES, int EPI, bool BROW, int NW = 4>
 __device__ __forceinline__ void pipe_body(const GemmArgs &g, int bid, int split, int nsplit) {
   typedef bf16_t AT;
@@ -579,21 +598,198 @@ __device__ __forceinline__ void pipe_body(const GemmArgs &g, int bid, int split,
   }
 
   wait_vmcnt<0>();
-  if constexpr (NW == 8) {
-    // 256 x 256 tile: the fp32 tile does not fit LDS at once. It leaves in slabs of 64 rows, each handed to the epilogue as
-    // 128-column halves (the width the row statistics are kept at), so every output is formed exactly as by the smaller tiles.
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int row = (wm * TM + i) * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+        const int col = (wn * TN + j) * 32 + (lane & 31);
+        if constexpr (EPI == EPI_PARTIAL) Cs[row * LDC + col] = tot[i][j][e];
+        else Cs[row * LDC + col] = acc[i][j][e];
+      }
+  __syncthreads();
+  epilogue<EPI, AT, BM, BN>(g, Cs, m0, n0, nt, tid, fuse ? 0 : split);
+}
+template <int BM, int BN, int STAGES, int EPI, bool BROW>
+__global__ __launch_bounds__(256, (STAGES == 2 && BM * BN <= 128 * 128) ? 2 : 1) void gemm_pipe_kernel(GemmArgs g) {
+  pipe_body<BM, BN, STAGES, EPI, BROW>(g, (int)blockIdx.x, (int)blockIdx.y, g.sum_splits ? g.splits : (int)gridDim.y);
+}
+
+
+// ---------------------------------------------------------------------------------------------------
+// The same product with stages of 32 along K (two k-steps) in a ring of STAGES: half the bytes per stage, so that the ring
+// is deep enough (three stages ahead) for the LDS-DMA of all compute units together, which the L2 fabric serves at about
+// 50 bytes per clock and unit, and so that the fragments of a stage's first k-step can be fetched from LDS while the matrix
+// cores still work on the last k-step of the stage before: the wait for a stage's DMA and the workgroup barrier sit in
+// the middle of a stage, between its two k-steps, and no fragment read is ever waited for with idle matrix cores.
+//   iteration h:  fetch (h, k-step 1) | MFMA (h, 0) | wait DMA of h+1, barrier, issue DMA of h+STAGES-1 | fetch (h+1, 0) | MFMA (h, 1)
+// A stage: A as BM rows of 64 bytes (one DMA = 16 rows; the four 16-byte pieces of row r XOR-permuted by (r / 4) % 4, so
+// that the 16 rows a quarter-wavefront reads one piece of cover all 64 banks), then W as ready-made 1 KiB fragments.
+// The slot that iteration h refills is the one stage h-1 lived in: its last fragment read was waited for before
+// MFMA (h-1, 1) was issued, which every wavefront has done when it arrives at iteration h's barrier.
+// Every output element sees the same sequence of k-steps as in pipe_body, so both give the same bits.
+// ---------------------------------------------------------------------------------------------------
+template <int BM, int BN, int STAGES, int EPI, int NW = 4>
+__device__ __forceinline__ void pipe2_body(const GemmArgs &g, int bid, int split, int nsplit) {
+  typedef bf16_t AT;
+  constexpr int BK = 32, KS = 2;
+  constexpr int WN = NW / 2;                         // wavefronts 2 (rows) x WN (columns)
+  constexpr int TM = BM / 64, TN = BN / (32 * WN);   // 32x32 tiles per wavefront
+  constexpr int BFR = BN / 32;
+  constexpr int A_BYTES = BM * 64;                   // A stage: BM rows of 32 k (64 bytes)
+  constexpr int ACH = BM / 16 / NW;                  // A DMAs per wavefront and stage (one DMA = 16 rows x 64 bytes)
+  constexpr int BCH = BFR * KS / NW;                 // W DMAs per wavefront and stage (one fragment each)
+  constexpr int LPW = ACH + BCH;
+  constexpr int STAGE_BYTES = A_BYTES + BFR * KS * 1024, LDC = BN + 4;
+  constexpr bool SLAB = BM > 128;                    // the fp32 tile leaves through LDS in slabs of 64 rows
+  static_assert((BM / 16) % NW == 0 && (BFR * KS) % NW == 0 && STAGES >= 3, "chunk split");
+  static_assert((STAGES - 3) * LPW <= 63, "vmcnt range");
+  extern __shared__ __align__(16) unsigned char smem[];
+  float *Cs = reinterpret_cast<float *>(smem);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+  const int ntn = g.N / BN, ntm = (g.M + BM - 1) / BM;
+  int mt, nt;
+  if (!tile_of_block(bid, ntm, ntn, g.col_groups, mt, nt)) return;
+  const int m0 = mt * BM, n0 = nt * BN;
+  const int ksplit = g.K / nsplit, nkh = ksplit / BK;
+  const int ksteps = g.K / 16;
+
+  const bf16_t *src[LPW];
+#pragma unroll
+  for (int q = 0; q < ACH; ++q) {
+    const int c = wave + NW * q, r = c * 16 + (lane >> 2);
+    int row = m0 + r;
+    row = row < g.M ? row : g.M - 1;
+    src[q] = static_cast<const bf16_t *>(g.A) + (size_t)row * g.lda + (((lane & 3) ^ ((r >> 2) & 3)) << 3);
+  }
+#pragma unroll
+  for (int q = 0; q < BCH; ++q) {
+    const int c = wave + NW * q, fr = c / KS, ks = c % KS;
+    src[ACH + q] = static_cast<const bf16_t *>(g.W) + (((size_t)(n0 / 32 + fr) * ksteps + ks) * 64 + lane) * 8;
+  }
+  auto issue = [&](int slot, int kh) {  // kh: 32-wide stage counted from the start of K
+    unsigned char *base = smem + slot * STAGE_BYTES;
+#pragma unroll
+    for (int q = 0; q < ACH; ++q) dma16(src[q] + (size_t)kh * BK, base + (wave + NW * q) * 1024);
+#pragma unroll
+    for (int q = 0; q < BCH; ++q) dma16(src[ACH + q] + (size_t)kh * KS * 512, base + A_BYTES + (wave + NW * q) * 1024);
+  };
+
+  // fragment read addresses inside a stage (bytes from the stage's start): A tile i of this wavefront at a_base[k-step] +
+  // i * 2048 (32 rows of 64 bytes), W tile j at b_base + k-step * 1024 + j * 2048
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
+  const int a_sw = (lane >> 2) & 3, a_half = lane >> 5;  // tile rows start at multiples of 32: (r / 4) % 4 == (lane / 4) % 4
+  uint32_t a_base[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) a_base[ks] = lds0 + (wm * TM * 32 + (lane & 31)) * 64 + (((2 * ks + a_half) ^ a_sw) << 4);
+  const uint32_t b_base = lds0 + A_BYTES + (((wn * TN * KS) * 64 + lane) << 4);
+
+  const bool fuse = EPI == EPI_PARTIAL && g.sum_splits != 0;
+  const int sp_first = fuse ? 0 : split, sp_end = fuse ? nsplit : split + 1;
+  f32x16 acc[TM][TN], tot[EPI == EPI_PARTIAL ? TM : 1][EPI == EPI_PARTIAL ? TN : 1];
+  for (int sp = sp_first; sp < sp_end; ++sp) {
+    const int kh0 = sp * nkh;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+    if (sp != sp_first) bare_barrier();  // every wavefront has read the last stages of the previous range
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; ++s)
+      if (s < nkh) issue(s, kh0 + s);
+
+    bf16x8 af[2][TM], bf[2][TN];
+    auto fetch = [&](auto buf_c, int slot, auto ks_c) {  // TM + TN reads, left in flight
+      constexpr int buf = decltype(buf_c)::value, ks = decltype(ks_c)::value;
+      const uint32_t sa = a_base[ks] + slot * STAGE_BYTES, sb = b_base + slot * STAGE_BYTES;
+      static_assert(TM <= 4 && TN <= 4, "tiles per wavefront");
+      af[buf][0] = lds_read16<0>(sa);
+      if constexpr (TM > 1) af[buf][1] = lds_read16<2048>(sa);
+      if constexpr (TM > 2) af[buf][2] = lds_read16<4096>(sa);
+      if constexpr (TM > 3) af[buf][3] = lds_read16<6144>(sa);
+      bf[buf][0] = lds_read16<ks * 1024>(sb);
+      if constexpr (TN > 1) bf[buf][1] = lds_read16<ks * 1024 + 2048>(sb);
+      if constexpr (TN > 2) bf[buf][2] = lds_read16<ks * 1024 + 4096>(sb);
+      if constexpr (TN > 3) bf[buf][3] = lds_read16<ks * 1024 + 6144>(sb);
+    };
+    auto mfma = [&](auto buf_c, auto newer_c) {  // newer: reads issued after this buffer's, allowed to stay in flight
+      constexpr int buf = decltype(buf_c)::value;
+      lds_wait<decltype(newer_c)::value>();
+#pragma unroll
+      for (int i = 0; i < TM; ++i) lds_landed(af[buf][i]);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) lds_landed(bf[buf][j]);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bf[buf][j], acc[i][j], 0, 0, 0);
+    };
+    typedef std::integral_constant<int, 0> I0;
+    typedef std::integral_constant<int, 1> I1;
+    typedef std::integral_constant<int, TM + TN> INext;
+    // stage 0 has landed once at most the younger stages of the preamble are in flight
+    if (nkh >= STAGES - 1) wait_vmcnt<(STAGES - 2) * LPW>();
+    else wait_vmcnt<0>();
+    bare_barrier();
+    fetch(I0{}, 0, I0{});
+    int slot = 0, fill = STAGES - 1;  // slot of stage h; slot the next DMA goes to
+    // One iteration: the two k-steps of stage h around the hand-over to stage h + 1. STEADY: a further stage is requested;
+    // else the ring only drains.
+    auto step = [&](int h, auto steady) {
+      fetch(I1{}, slot, I1{});
+      mfma(I0{}, INext{});
+      if constexpr (decltype(steady)::value) wait_vmcnt<(STAGES - 3) * LPW>();
+      else wait_vmcnt<0>();
+      bare_barrier();  // stage h+1 is in LDS for everyone, and everyone is done reading stage h-1
+      if constexpr (decltype(steady)::value) {
+        issue(fill, kh0 + h + STAGES - 1);
+        fill = fill + 1 == STAGES ? 0 : fill + 1;
+      }
+      slot = slot + 1 == STAGES ? 0 : slot + 1;
+      fetch(I0{}, slot, I0{});
+      mfma(I1{}, INext{});
+    };
+    int h = 0;
+    for (; h + STAGES - 1 < nkh; ++h) step(h, std::true_type{});
+    for (; h + 1 < nkh; ++h) step(h, std::false_type{});
+    fetch(I1{}, slot, I1{});  // last stage: nothing follows
+    mfma(I0{}, INext{});
+    mfma(I1{}, I0{});
+    if constexpr (EPI == EPI_PARTIAL) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          if (sp == sp_first) tot[i][j] = acc[i][j];
+          else tot[i][j] += acc[i][j];
+        }
+    }
+  }
+
+  wait_vmcnt<0>();
+  if constexpr (SLAB) {
+    // The fp32 tile does not fit LDS at once: it leaves in slabs of 64 rows, each handed to the epilogue as 128-column
+    // pieces (the width the row statistics are kept at), so every output is formed exactly as by the smaller tiles.
     static_assert(EPI != EPI_PARTIAL && EPI != EPI_GEGLU && EPI != EPI_GEGLU_FOLD && TM % 2 == 0 && BN % 128 == 0, "slab epilogue");
-    // The side inputs of slab p + 1 are requested before slab p is worked on: with one workgroup on the CU nothing else
-    // would cover their latency. sd: [buffer][column half][pass][input].
-    constexpr int NT8 = NW * 64, SP = 64 / (NT8 / 16);   // passes of a thread over a 64-row, 128-column slab half
-    Raw8<AT> sd[2][BN / 128][SP][2];
+    constexpr int NT = NW * 64, SP = 64 / (NT / 16);     // passes of a thread over a 64-row, 128-column slab piece
+    // With one workgroup on the unit (eight wavefronts) the side inputs of slab p + 1 are requested before slab p is worked
+    // on; with two workgroups per unit the other one's matrix work covers that latency and the registers are not spent.
+    constexpr bool PRE = NW == 8 && EpiSides<EPI>::n != 0;
+    Raw8<AT> sd[PRE ? 2 : 1][BN / 128][SP][2];
     auto side = [&](int buf, int p) {
-      if constexpr (EpiSides<EPI>::n > 0) {
+      if constexpr (PRE) {
 #pragma unroll
         for (int h = 0; h < BN / 128; ++h)
 #pragma unroll
           for (int u = 0; u < SP; ++u) {
-            const int m = m0 + p * 64 + u * (NT8 / 16) + tid / 16;
+            const int m = m0 + p * 64 + u * (NT / 16) + tid / 16;
             epi_side_load<EPI, AT>(g, (size_t)m * g.ldc + n0 + h * 128 + (tid % 16) * 8, m < g.M, sd[buf][h][u]);
           }
       }
@@ -620,35 +816,30 @@ __device__ __forceinline__ void pipe_body(const GemmArgs &g, int bid, int split,
       __syncthreads();
 #pragma unroll
       for (int h = 0; h < BN / 128; ++h)
-        epilogue<EPI, AT, 64, 128, LDC, NT8, EpiSides<EPI>::n != 0>(g, Cs + h * 128, m0 + p * 64, n0 + h * 128, nt * (BN / 128) + h, tid, 0,
-                                                                     sd[p & 1][h]);
+        epilogue<EPI, AT, 64, 128, LDC, NT, PRE>(g, Cs + h * 128, m0 + p * 64, n0 + h * 128, nt * (BN / 128) + h, tid, 0, sd[PRE ? (p & 1) : 0][h]);
     }
   } else {
-  __syncthreads();
+    __syncthreads();
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < TN; ++j)
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int row = (wm * TM + i) * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-        const int col = (wn * TN + j) * 32 + (lane & 31);
-        if constexpr (EPI == EPI_PARTIAL) Cs[row * LDC + col] = tot[i][j][e];
-        else Cs[row * LDC + col] = acc[i][j][e];
-      }
-  __syncthreads();
-  epilogue<EPI, AT, BM, BN>(g, Cs, m0, n0, nt, tid, fuse ? 0 : split);
+        for (int e = 0; e < 16; ++e) {
+          const int row = (wm * TM + i) * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+          const int col = (wn * TN + j) * 32 + (lane & 31);
+          if constexpr (EPI == EPI_PARTIAL) Cs[row * LDC + col] = tot[i][j][e];
+          else Cs[row * LDC + col] = acc[i][j][e];
+        }
+    __syncthreads();
+    epilogue<EPI, AT, BM, BN>(g, Cs, m0, n0, nt, tid, fuse ? 0 : split);
   }
 }
-template <int EPI>
-__global__ __launch_bounds__(512, 1) void gemm_pipe8_kernel(GemmArgs g) {  // 256 x 256 tile, two stages, eight wavefronts
-  pipe_body<256, 256, 2, EPI, false, 8>(g, (int)blockIdx.x, 0, 1);
+// WPU: workgroups the launch bounds leave room for on one compute unit
+template <int BM, int BN, int STAGES, int EPI, int NW, int WPU>
+__global__ __launch_bounds__(NW * 64, WPU) void gemm_pipe2_kernel(GemmArgs g) {
+  pipe2_body<BM, BN, STAGES, EPI, NW>(g, (int)blockIdx.x, (int)blockIdx.y, g.sum_splits ? g.splits : (int)gridDim.y);
 }
-template <int BM, int BN, int STAGES, int EPI, bool BROW>
-__global__ __launch_bounds__(256, (STAGES == 2 && BM * BN <= 128 * 128) ? 2 : 1) void gemm_pipe_kernel(GemmArgs g) {
-  pipe_body<BM, BN, STAGES, EPI, BROW>(g, (int)blockIdx.x, (int)blockIdx.y, g.sum_splits ? g.splits : (int)gridDim.y);
-}
-
 
 // ---------------------------------------------------------------------------------------------------
 // Weight gradients from ROW-MAJOR operands: C[M][N] = sum over rows b < K of A[b][m] * W[b][n]  (dW = L^T R over the batch;
@@ -979,26 +1170,29 @@ hipError_t launch_tn(const GemmArgs &g, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <int EPI>
-hipError_t launch_pipe8(const GemmArgs &g, hipStream_t s) {
-  constexpr size_t lds = 2 * (256 * 128 + 8 * 4 * 1024);  // two stages of 64 KiB; the 64-row epilogue slabs (65 KiB) alias them
+template <int BM, int BN, int STAGES, int EPI, int NW, int WPU>
+hipError_t launch_pipe2(const GemmArgs &g, hipStream_t s) {
+  constexpr size_t lds_ring = (size_t)STAGES * (BM * 64 + (BN / 32) * 2 * 1024);
+  constexpr size_t lds_c = BM > 128 ? (size_t)64 * (BN + 4) * sizeof(float) : (size_t)BM * (BN + 4) * sizeof(float);
+  constexpr size_t lds = lds_ring > lds_c ? lds_ring : lds_c;
+  static_assert(lds * WPU <= 160 * 1024, "LDS per compute unit");
   static bool attr_done = false;
-  auto kern = gemm_pipe8_kernel<EPI>;
+  auto kern = gemm_pipe2_kernel<BM, BN, STAGES, EPI, NW, WPU>;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  if (g.N % 256 || g.M <= 0 || g.K % 64 || g.splits > 1 || g.lda % 8) return hipErrorInvalidValue;
+  const int splits = g.splits > 1 ? g.splits : 1;
+  if (g.N % BN || g.M <= 0 || g.K % (splits * 32) || (EPI != EPI_PARTIAL && splits != 1) || g.lda % 8) return hipErrorInvalidValue;
+  if (g.sum_splits && EPI != EPI_PARTIAL) return hipErrorInvalidValue;
   GemmArgs ga = g;
-  const int ntm = (g.M + 255) / 256, ntn = g.N / 256;
-  // 256-wide column tiles: a 4 MiB slice of W per XCD does as well as 2 MiB in time and fetches less (router product,
-  // M = 16384: 8 / 4 / 2 / 1 column ranges fetch 656 / 416 / 320 / 320 MiB, 171 / 167 / 166 / 167 us)
-  if (ga.col_groups == 0) ga.col_groups = fade_gemm_col_groups(g.M, g.K, g.N, (size_t)4 << 20);
+  const int ntm = (g.M + BM - 1) / BM, ntn = g.N / BN;
+  if (ga.col_groups == 0) ga.col_groups = fade_gemm_col_groups(g.M, g.K, g.N, BN >= 256 ? (size_t)4 << 20 : (size_t)2 << 20);
   if ((ga.col_groups != 1 && ga.col_groups != 2 && ga.col_groups != 4) || ntn % ga.col_groups) ga.col_groups = 8;
   const int rg = 8 / ga.col_groups;
-  const dim3 grid((ntn % ga.col_groups == 0 ? (ntm + rg - 1) / rg * rg : ntm) * ntn);
-  hipLaunchKernelGGL(kern, grid, dim3(512), lds, s, ga);
+  const dim3 grid((ntn % ga.col_groups == 0 ? (ntm + rg - 1) / rg * rg : ntm) * ntn, ga.sum_splits ? 1 : splits);
+  hipLaunchKernelGGL(kern, grid, dim3(NW * 64), lds, s, ga);
   return hipGetLastError();
 }
 
@@ -1006,17 +1200,20 @@ hipError_t launch_pipe8(const GemmArgs &g, hipStream_t s) {
 // 512 tiles of 128 x 128 on: that tile with a two-stage ring (64 KiB of LDS), two workgroups per compute unit: one's
 // epilogue (side inputs from HBM, stores) and pipeline fill run under the other's products, which measured faster than
 // either a deeper ring or a 256 x 128 tile with one workgroup per unit (router product, M = 4096: 43 us against 54).
+// Once every compute unit gets a 256 x 256 tile (M >= 8192 at N = 2048): that tile on eight wavefronts with the ring of
+// four 32-wide stages (pipe2_body): half the operand bytes per flop of 128 x 128 and two wavefronts per SIMD. On random
+// operands at M = 16384, N = 2048: K = 2048 188 us against 207 for the same tile on a two-stage ring of 64-wide stages,
+// 230 for 128 x 128; K = 512 88 against 104; mix epilogue in both. With a contraction of 64 the two shapes tie.
 template <int EPI>
 hipError_t launch_pipe_auto(const GemmArgs &g, hipStream_t s) {
   const int tiles128 = ((g.M + 127) / 128) * (g.N / 128);
   const int tune = fade_gemm_tune();
   if constexpr (EPI != EPI_PARTIAL && EPI != EPI_GEGLU && EPI != EPI_GEGLU_FOLD) {
-    // 256 x 256 tiles on eight wavefronts once every compute unit gets one: half the operand bytes per flop of 128 x 128, and
-    // two wavefronts per SIMD to run matrix instructions under each other's LDS / DMA traffic (router product: 74 us against
-    // 82 at M = 8192, 166 against 183 at M = 16384; with only 128 tiles at M = 4096 it loses, 68 against 43)
     const int tiles256 = ((g.M + 255) / 256) * (g.N / 256);
-    if (g.N % 256 == 0 && (tune == 12 || (tune == 0 && tiles256 >= 256 && g.K >= 1024))) return launch_pipe8<EPI>(g, s);  // short K: the epilogue dominates, two small workgroups per unit hide it better
+    if (g.N % 256 == 0 && (tune == 20 || (tune == 0 && tiles256 >= 256 && g.K >= 256))) return launch_pipe2<256, 256, 4, EPI, 8, 1>(g, s);
+    if (tune == 21) return launch_pipe2<256, 128, 3, EPI, 4, 2>(g, s);
   }
+  if (tune == 23) return launch_pipe2<128, 128, 4, EPI, 4, 2>(g, s);
   if (tune == 11 || (tune == 0 && tiles128 >= 512)) return launch_pipe<128, 128, 2, EPI>(g, s);
   if (tune == 10) return launch_pipe<256, 128, 3, EPI>(g, s);
   if (tune == 1 || (tune == 0 && tiles128 >= 256)) return launch_pipe<128, 128, 4, EPI>(g, s);
@@ -1142,8 +1339,9 @@ hipError_t fade_gemm_group_launch(const GemmGroup &gg, hipStream_t s) {
 }
 
 // Tuning override for experiments (FADE_GEMM_TUNE: 0 automatic, 1 force 128x128x4 stages, 2 force 64x128, 10 force 256x128x3,
-// 11 force 128x128x2 with two workgroups per compute unit, 12 force 256x256x2 on eight wavefronts; grouped launches:
-// 13 force the four-stage kernel, 14 force the two-stage one).
+// 11 force 128x128x2 with two workgroups per compute unit; rings of 32-wide stages: 20 force 256x256 on eight wavefronts,
+// 21 256x128 with two workgroups per unit, 23 128x128 with two workgroups per unit; grouped launches: 13 force the
+// four-stage kernel, 14 force the two-stage one).
 int fade_gemm_tune() {
   static int v = -1;
   if (v < 0) { const char *e = getenv("FADE_GEMM_TUNE"); v = e ? atoi(e) : 0; }
