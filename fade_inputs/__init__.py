@@ -13,7 +13,8 @@ from collections import OrderedDict
 import numpy as np
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB = os.path.join(HERE, "libfadegen.so")
+SANITIZE = os.environ.get("FADE_HOST_SANITIZE") == "1"   # separate ASan + UBSan build of the generators (see oracle/buildlib.py)
+LIB = os.path.join(HERE, "libfadegen_san.so" if SANITIZE else "libfadegen.so")
 SEED_BASE = 0xFADE0000
 
 # name -> (B, T, D, H, dtype, bytes, generator) of the five benchmark configurations, and 6: the model shape the paper
@@ -32,7 +33,8 @@ def build(force: bool = True) -> str:
     src = os.path.join(HERE, "gen.c")
     if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(src):
         return LIB
-    subprocess.run(["gcc", "-O2", "-fPIC", "-shared", "-Wall", "-o", LIB, src, "-lm"], check=True)
+    san = ["-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined"] if SANITIZE else []
+    subprocess.run(["gcc", "-O2", *san, "-fPIC", "-shared", "-Wall", "-o", LIB, src, "-lm"], check=True)
     return LIB
 
 

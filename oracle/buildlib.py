@@ -3,7 +3,10 @@ import os
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB = os.path.join(HERE, "libfadeo.so")
+# FADE_HOST_SANITIZE=1: a separate build with AddressSanitizer + UndefinedBehaviorSanitizer (host code only), for running
+# the CPU tests once under the sanitizers: LD_PRELOAD=$(gcc -print-file-name=libasan.so) FADE_HOST_SANITIZE=1 pytest -m "not gpu"
+SANITIZE = os.environ.get("FADE_HOST_SANITIZE") == "1"
+LIB = os.path.join(HERE, "libfadeo_san.so" if SANITIZE else "libfadeo.so")
 
 
 def build(force: bool = True) -> str:
@@ -13,6 +16,8 @@ def build(force: bool = True) -> str:
         return LIB
     cmd = ["g++", "-std=c++17", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared",
            "-Wall", "-Wextra", "-o", LIB, src]
+    if SANITIZE:
+        cmd[3:3] = ["-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined"]
     subprocess.run(cmd, check=True, cwd=HERE)
     return LIB
 
