@@ -204,6 +204,7 @@ struct fade_ctx {
   uint8_t *ones = nullptr;
   WinSrc last_ws{};
   int *dev_err = nullptr;
+  bool debug_wu_grad = false;        // FADE_DEBUG_WU_GRAD=1 at fade_create: the per-stream gradient is also written to the gradient array
   uint32_t *scratch_dev = nullptr;   // this device's copy of the file-scope scratch array (see scratch_for_device)
   size_t loop_n = 0, loop_next = 0;  // job size and next step of the device-resident loop in progress
   int loop_mode = 0;
@@ -834,6 +835,7 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     a.master = c->master + c->lay.off[P_WU]; a.m = c->adam_m + c->lay.off[P_WU]; a.v = c->adam_v + c->lay.off[P_WU];
     a.dy = c->dy; a.dy_at = c->dy_at; a.u = c->ustate;
     a.lr = c->cfg.lr; a.beta1 = c->cfg.beta1; a.beta2 = c->cfg.beta2; a.eps = c->cfg.eps;
+    a.g_dbg = c->debug_wu_grad ? c->grad + c->lay.off[P_WU] : nullptr;
     HIP_TRY(c, fade_bwd_cci(a, bf, s));
   }
   {
@@ -1066,6 +1068,7 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
   c->bf16 = cfg->dtype == FADE_BF16;
   c->online = cfg->update_mode == FADE_ONLINE_ADAM;
   c->esz = c->bf16 ? 2 : 4;
+  if (const char *e = getenv("FADE_DEBUG_WU_GRAD")) c->debug_wu_grad = e[0] == '1';
   if (cfg->hip_stream) c->stream = static_cast<hipStream_t>(cfg->hip_stream);
   else {
     if (hipStreamCreate(&c->stream) != hipSuccess) { delete c; return FADE_E_HIP; }

@@ -573,7 +573,9 @@ __global__ __launch_bounds__(256) void bwd_mix_kernel(BwdMixArgs a) {
 // then has all 1024 threads on its rows). Phase h adds rows h, h + phases, ... in increasing order; the phase sums are
 // folded pairwise in a fixed tree: the result does not depend on timing.
 __global__ __launch_bounds__(1024) void reduce_batch_kernel(ReduceBatch rb) {
-  __shared__ float ps[1024];
+  // The sums run in fp64 (rounded to fp32 once at the end): some of them, the residual-scale gradients above all, are small
+  // differences of many large terms, and fp64 adds cost nothing here.
+  __shared__ double ps[1024];
   const int k = blockIdx.y, P = rb.P[k], N = rb.N[k], tid = threadIdx.x;
   int lg = 5;
   while (lg > 0 && (1 << (lg - 1)) >= N) --lg;
@@ -581,10 +583,10 @@ __global__ __launch_bounds__(1024) void reduce_batch_kernel(ReduceBatch rb) {
   if ((int)blockIdx.x * cw >= N) return;  // uniform over the workgroup
   const float *part = rb.part[k];
   const int c = tid & (cw - 1), h = tid >> lg, n = blockIdx.x * cw + c;
-  float s = 0.0f;
+  double s = 0.0;
   if (n < N) {
 #pragma unroll 8
-    for (int p = h; p < P; p += phases) s += part[(size_t)p * N + n];
+    for (int p = h; p < P; p += phases) s += (double)part[(size_t)p * N + n];
   }
   ps[tid] = s;  // [phase][column]
   __syncthreads();
@@ -593,7 +595,7 @@ __global__ __launch_bounds__(1024) void reduce_batch_kernel(ReduceBatch rb) {
     __syncthreads();
   }
   if (h == 0 && n < N) {
-    const float t = ps[tid];
+    const float t = (float)ps[tid];
     rb.out[k][n] = t;
     if (rb.adam[k]) adam_element(rb.opt, (size_t)(rb.out[k] - rb.opt.grad_base) + n, t);
   }
@@ -654,6 +656,12 @@ __global__ __launch_bounds__(256) void bwd_cci_kernel(BwdCciArgs a) {
   for (int e = 0; e < 4; ++e) {
     const int idx = (e * 256 + tid) * 4, k = idx >> 6, n = idx & 63;
     float wn[4];
+    if (a.g_dbg) {  // debug: the gradient itself, which otherwise only exists in registers
+      f32x4 g4;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) g4[i] = y_s[k] * dz_s[n + i];
+      *reinterpret_cast<f32x4 *>(a.g_dbg + (size_t)b * 4096 + idx) = g4;
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const float g = y_s[k] * dz_s[n + i];

@@ -218,6 +218,7 @@ struct BwdCciArgs {
   float *dy; void *dy_at; // [B][64]
   const UpdateState *u;
   float lr, beta1, beta2, eps;
+  float *g_dbg;           // optional [B][64][64]: the gradient y dz^T written out (debug: it is otherwise consumed in registers)
 };
 struct BwdSlotArgs {
   WinSrc ws;

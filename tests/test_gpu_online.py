@@ -15,9 +15,47 @@ def _log(m):
     print(m, flush=True)
 
 
+# The three residual-scale gradients (d lambda = sum over streams and channels of dH * H) are single numbers formed from
+# 10^4 .. 10^7 terms of both signs (the LayerNorm output that lambda_m scales sums to almost nothing per token): what the
+# path's rounding leaves is proportional to the terms' size, not to the much smaller sum. The second-stage sums run in
+# fp64; the bars below are the tensor bar times 2 (bf16 path, worst seen 1.5) and times 6 (fp32 path, worst seen 5:
+# fp32 activations, fp32 per-row sums and a 1.5e-7 erf against the oracle's fp64), down from 20.
+def _lambda_bar(tol):
+    return 2.0 if tol >= 1e-2 else 6.0
+
+
+def _make_pair_with_wu_grad(*args, **kw):
+    """make_pair for a context that also writes the per-stream gradient to the gradient array (debug switch read at creation)."""
+    import os
+    os.environ["FADE_DEBUG_WU_GRAD"] = "1"
+    try:
+        return make_pair(*args, **kw)
+    finally:
+        os.environ.pop("FADE_DEBUG_WU_GRAD", None)
+
+
+def _compare_gradients(blob, gg, go, tol, where, wu_rows=None):
+    """every tensor's gradient against the oracle's, relative to the tensor's largest gradient; W_U per element too"""
+    bad, lam = {}, {}
+    for name, shape, _ in blob.specs:
+        a = blob.view(gg, name).astype(np.float64)
+        r = blob.view(go, name).astype(np.float64)
+        if name == "W_U" and wu_rows is not None:
+            a = a[wu_rows]
+        a, r = a.ravel(), r.ravel()
+        scale = max(np.abs(r).max(), 1e-12)
+        err = np.abs(a - r).max() / scale
+        if a.size == 1:
+            lam[name] = round(float(err), 4)
+        if err > (tol * _lambda_bar(tol) if a.size == 1 else tol):
+            bad[name] = float(err)
+    _log(f"{where}: residual-scale gradient errors {lam}")
+    assert not bad, f"{where}: gradient mismatch (max |dg| / max |g|): {bad}"
+
+
 def _grad_check(dtype, B, T, D, H, seed, tol, **widths):
     torch = need_gpu()
-    g, o, blob = make_pair(B, T, D, H, dtype, seed=seed, update_mode=1, randomize=True, std=0.05, **widths)
+    g, o, blob = _make_pair_with_wu_grad(B, T, D, H, dtype, seed=seed, update_mode=1, randomize=True, std=0.05, **widths)
     rng = np.random.default_rng(seed)
     data = rng.integers(0, 256, (B, T + 3), dtype=np.uint8)
     probs_d = torch.zeros((B, 256), dtype=torch.float32, device="cuda")
@@ -39,18 +77,9 @@ def _grad_check(dtype, B, T, D, H, seed, tol, **widths):
         go = o.backward(tgt, act)
         g.step_update(torch.from_numpy(tgt).cuda(), ad)
         gg = g.debug_grad()
-        bad = {}
-        for name, shape, _ in blob.specs:
-            if name == "W_U":
-                continue
-            a = blob.view(gg, name).astype(np.float64).ravel()
-            r = blob.view(go, name).ravel()
-            scale = max(np.abs(r).max(), 1e-12)
-            err = np.abs(a - r).max() / scale
-            # the three residual scales are single sums with heavy cancellation: fp32 summation order shows there
-            if err > (tol * 20 if a.size == 1 else tol):
-                bad[name] = float(err)
-        assert not bad, f"step {i}: gradient mismatch (max |dg| / max |g|): {bad}"
+        _compare_gradients(blob, gg, go, tol, f"step {i}")
+        if act is not None:   # a masked stream's slice of the per-stream memory gets no gradient at all
+            assert not blob.view(gg, "W_U")[act == 0].any()
         o.step_update(tgt, act)
         # weights after the update: Adam's early steps are sign-like, so compare where the gradient is not tiny
         # (first update only: later, a sign flip of an earlier, smaller gradient legitimately persists in the moments)
@@ -168,7 +197,12 @@ def test_online_update_config2_full_batch():
     spec = fi.CONFIGS[2]
     B, T, D, H = spec["B"], spec["T"], spec["D"], spec["H"]
     blob = fi.config_blob(2)
-    g = fa.Fade(fa.make_config(B, T, D, H, dtype=fa.BF16, update_mode=fa.ONLINE_ADAM))
+    import os
+    os.environ["FADE_DEBUG_WU_GRAD"] = "1"
+    try:
+        g = fa.Fade(fa.make_config(B, T, D, H, dtype=fa.BF16, update_mode=fa.ONLINE_ADAM))
+    finally:
+        os.environ.pop("FADE_DEBUG_WU_GRAD", None)
     g.load_weights(blob.data)
     o = orc.Oracle(orc.make_config(B, T, D, H, dtype=orc.BF16, update_mode=orc.ONLINE_ADAM))
     o.load_weights(blob.data)
@@ -185,16 +219,7 @@ def test_online_update_config2_full_batch():
     _log("cfg2 online: GPU update")
     g.step_update(torch.from_numpy(tgt).cuda(), None)
     gg = g.debug_grad()
-    bad = {}
-    for name, shape, _ in blob.specs:
-        if name == "W_U":
-            continue
-        a = blob.view(gg, name).astype(np.float64).ravel()
-        r = blob.view(go, name).ravel()
-        err = np.abs(a - r).max() / max(np.abs(r).max(), 1e-12)
-        if err > (0.6 if a.size == 1 else 3e-2):
-            bad[name] = float(err)
-    assert not bad, f"gradient mismatch (max |dg| / max |g|): {bad}"
+    _compare_gradients(blob, gg, go, 3e-2, "cfg2 full batch")
     o.step_update(tgt, None)
     act = np.zeros(B, np.uint8); act[:8] = 1; act[-8:] = 1
     win2 = np.ascontiguousarray(data[:, 1:T + 1])
@@ -204,3 +229,83 @@ def test_online_update_config2_full_batch():
     _, po2 = o.step_probs(win2, act)
     live = act.astype(bool)
     assert np.abs(probs_d.cpu().numpy()[live] - po2[live]).max() <= 1e-3
+
+
+@pytest.mark.parametrize("cfg", [3, 4, 5])
+def test_online_update_large_batch_launch_shapes(cfg):
+    """One online step at the full batch of configurations 3, 4 and 5 (B = 4096 / 4096 / 16384: four rows per workgroup in
+    the backward row kernels, weight gradients in ranges of the batch, 1024-thread second-stage reductions, the tall-product
+    tiles), on each configuration's own source bytes (4: the float32 series). About 256 streams spread over the batch are
+    active; the oracle runs exactly those streams on their own W_U slices (the loss is the mean over the active streams on
+    both sides, and masked streams contribute nothing), so every shared gradient, the active W_U gradients, the weights'
+    effect on the next step's probabilities and the masked streams' untouched state can be compared."""
+    torch = need_gpu()
+    import os
+    import paper_2604_07239_amd as fa
+    spec = fi.CONFIGS[cfg]
+    B, T, D, H = spec["B"], spec["T"], spec["D"], spec["H"]
+    blob = fi.config_blob(cfg)
+    idx = np.unique(np.linspace(0, B - 1, 256).astype(np.int64))
+    act = np.zeros(B, np.uint8); act[idx] = 1
+    os.environ["FADE_DEBUG_WU_GRAD"] = "1"
+    try:
+        g = fa.Fade(fa.make_config(B, T, D, H, dtype=fa.BF16, update_mode=fa.ONLINE_ADAM))
+    finally:
+        os.environ.pop("FADE_DEBUG_WU_GRAD", None)
+    g.load_weights(blob.data)
+    sub = fi.Blob(len(idx), T, D, H)
+    for name, _, _ in sub.specs:
+        sub[name] = blob[name][idx] if name == "W_U" else blob[name]
+    o = orc.Oracle(orc.make_config(len(idx), T, D, H, dtype=orc.BF16, update_mode=orc.ONLINE_ADAM))
+    o.load_weights(sub.data)
+    # the configuration's own kind of bytes (a 16 MiB prefix of its generator; for the mixed source that is text), one row per stream
+    data = fi.config_bytes(cfg, 16 << 20)[:B * 1024].reshape(B, 1024)[:, 512:512 + T + 2]
+    win = np.ascontiguousarray(data[:, :T]); tgt = np.ascontiguousarray(data[:, T])
+    probs_d = torch.zeros((B, 256), dtype=torch.float32, device="cuda")
+    ad = torch.from_numpy(act).cuda()
+    _log(f"cfg{cfg} online, B={B}, {len(idx)} active streams: forward")
+    g.step_probs(torch.from_numpy(win).cuda(), ad, None, probs_d)
+    _, po = o.step_probs(np.ascontiguousarray(win[idx]), None)
+    assert np.abs(probs_d.cpu().numpy()[idx] - po).max() <= 1e-3
+    _log(f"cfg{cfg} online: oracle backward")
+    go = o.backward(np.ascontiguousarray(tgt[idx]), None)
+    _log(f"cfg{cfg} online: GPU update")
+    g.step_update(torch.from_numpy(tgt).cuda(), ad)
+    gg = g.debug_grad()
+    _compare_gradients(sub, _sub_view(blob, sub, gg, idx), go, 3e-2, f"cfg{cfg} full batch")
+    wu = blob.view(gg, "W_U")
+    mask = np.ones(B, bool); mask[idx] = False
+    assert not wu[mask].any()                                    # masked streams: no gradient
+    w1 = g.get_weights()
+    assert np.array_equal(blob.view(w1, "W_U")[mask], blob["W_U"][mask])   # ... and an untouched memory
+    o.step_update(np.ascontiguousarray(tgt[idx]), None)
+    # weights after the update (Adam's first step is sign-like, lr * g / (|g| + eps): only entries whose gradient is well
+    # above the path's gradient error are sure to move the same way on both sides)
+    wo = o.get_weights()
+    w1s = _sub_view(blob, sub, w1, idx)
+    for name, _, _ in sub.specs:
+        a, r, gr = sub.view(w1s, name).ravel(), sub.view(wo, name).ravel(), sub.view(go, name).ravel()
+        big = np.abs(gr) > 0.12 * max(np.abs(gr).max(), 1e-30)
+        if big.any():
+            assert np.abs(a[big] - r[big]).max() <= 0.3e-3 + 1e-6, name
+    win2 = np.ascontiguousarray(data[:, 1:T + 1])
+    _log(f"cfg{cfg} online: step after the update")
+    g.step_probs(torch.from_numpy(win2).cuda(), ad, None, probs_d)
+    _, po2 = o.step_probs(np.ascontiguousarray(win2[idx]), None)
+    # After that step the two states differ wherever a gradient's sign lies within the path's error (2 lr apart), and on
+    # these sources (a handful of distinct symbols per batch) every stream pushes the same few logits, so one step moves
+    # probabilities by factors: the next step's probabilities agree within 1e-3 plus 5 % of the probability (the relative
+    # bar the forward parity tests use), not within 1e-3 alone as from identical states (checked above).
+    dp = np.abs(probs_d.cpu().numpy()[idx] - po2)
+    _log(f"cfg{cfg} online: after the update max |dp| {dp.max():.2e}, max p {po2.max():.3f}, max |dp| / (1e-3 + 0.05 p) {(dp / (1e-3 + 0.05 * po2)).max():.2f}")
+    assert np.all(dp <= 1e-3 + 0.05 * po2)
+    g.close()
+
+
+def _sub_view(blob, sub, flat, idx):
+    """a flat array in the full batch's blob layout -> the sub-batch layout (W_U rows idx, everything else as it is)"""
+    out = np.zeros(sub.data.size, flat.dtype)
+    for name, _, _ in sub.specs:
+        v = blob.view(flat, name)
+        sub.view(out, name)[...] = v[idx] if name == "W_U" else v
+    return out
