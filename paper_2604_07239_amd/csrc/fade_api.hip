@@ -204,6 +204,8 @@ struct fade_ctx {
   uint8_t *ones = nullptr;
   WinSrc last_ws{};
   int *dev_err = nullptr;
+  bool rows16 = false;               // fp32 path at very small batches: 16 x 16 product tiles, row statistics per 16 columns
+  size_t stats_n = 0;                // partial (sum, sum of squares) pairs per row the statistics buffers hold
   bool debug_wu_grad = false;        // FADE_DEBUG_WU_GRAD=1 at fade_create: the per-stream gradient is also written to the gradient array
   uint32_t *scratch_dev = nullptr;   // this device's copy of the file-scope scratch array (see scratch_for_device)
   size_t loop_n = 0, loop_next = 0;  // job size and next step of the device-resident loop in progress
@@ -393,7 +395,8 @@ int forward_f32(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint
   const Dims &d = c->d;
   hipStream_t s = c->stream;
   const bool bf = false;
-  const int B = (int)d.B, Dh = (int)d.Dh, SN = (int)(d.Dh / FADE_STATS_BN);
+  const int B = (int)d.B, Dh = (int)d.Dh, SN = (int)c->stats_n;
+  const int r16 = c->rows16 ? 1 : 0;
   {
     Prof p(c, "embed_cache");
     EmbedArgs a{};
@@ -408,6 +411,7 @@ int forward_f32(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint
     g.M = (int)(d.B * d.T); g.N = (int)d.D; g.K = (int)d.Kc;
     g.A = c->XL; g.T = (int)d.T; g.D = (int)d.D; g.taps = (int)d.k;
     g.W = c->Wconv_c; g.C = c->Hl; g.ldc = (int)d.D; g.C2 = c->cv; g.bias = c->P(P_BCONV);
+    g.rows16 = r16;
     HIP_TRY(c, fade_gemm(GEMM_CONV, bf, g, s));
   }
   {  // Eq. 3
@@ -415,6 +419,7 @@ int forward_f32(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint
     GemmArgs g{};
     g.M = B; g.N = Dh; g.K = (int)d.Dc;
     g.A = c->M; g.lda = (int)d.Dc; g.W = c->Wm_c; g.C = c->Hg; g.ldc = Dh; g.C2 = c->hm; g.S1 = c->X; g.lam = c->P(P_LAMBDA_M);
+    g.rows16 = r16;
     HIP_TRY(c, fade_gemm(GEMM_GLOBAL, bf, g, s));
   }
   {  // Eq. 5-6
@@ -423,6 +428,7 @@ int forward_f32(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint
     g.M = B; g.N = Dh; g.K = Dh;
     g.A = c->X; g.lda = Dh; g.W = c->Wr_c; g.C = c->Hmix; g.ldc = Dh; g.C2 = c->alpha; g.S1 = c->Hg; g.S2 = c->Hl;
     g.stats_out = c->stats_c;
+    g.rows16 = r16;
     HIP_TRY(c, fade_gemm(GEMM_ROUTER, bf, g, s));
   }
   {  // Eq. 7: Down(LN(H_mix))
@@ -431,6 +437,7 @@ int forward_f32(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint
     g.M = B; g.N = (int)d.dl; g.K = Dh;
     g.A = c->Hmix; g.lda = Dh; g.stats = c->stats_c; g.stats_n = SN; g.gamma = c->P(P_GAMMA_C); g.beta = c->P(P_BETA_C);
     g.W = c->Wdown_c; g.C = c->y; g.ldc = (int)d.dl;
+    g.rows16 = r16;
     HIP_TRY(c, fade_gemm(GEMM_DOWN, bf, g, s));
   }
   {  // Eq. 7: the per-stream memory
@@ -442,6 +449,7 @@ int forward_f32(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint
     GemmArgs g{};
     g.M = B; g.N = Dh; g.K = (int)d.dl;
     g.A = c->z; g.lda = (int)d.dl; g.W = c->Wup_c; g.C = c->Ha; g.ldc = Dh;
+    g.rows16 = r16;
     HIP_TRY(c, fade_gemm(GEMM_UP, bf, g, s));
   }
   {  // Eq. 8
@@ -450,6 +458,7 @@ int forward_f32(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint
     g.M = B; g.N = Dh; g.K = Dh;
     g.A = c->Hmix; g.lda = Dh; g.W = c->Wc_c; g.C = c->Hc; g.ldc = Dh; g.C2 = c->sg; g.S1 = c->Ha; g.S2 = c->Hmix;
     g.lam = c->P(P_LAMBDA_C); g.stats_out = c->stats_f;
+    g.rows16 = r16;
     HIP_TRY(c, fade_gemm(GEMM_GATE, bf, g, s));
   }
   {  // Eq. 9
@@ -458,6 +467,7 @@ int forward_f32(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint
     g.M = B; g.N = (int)(2 * d.De); g.K = Dh;
     g.A = c->Hc; g.lda = Dh; g.stats = c->stats_f; g.stats_n = SN; g.gamma = c->P(P_GAMMA_F); g.beta = c->P(P_BETA_F);
     g.W = c->Wfgv_c; g.C = c->Hexp; g.ldc = (int)d.De; g.C2 = c->eg; g.C3 = c->ev;
+    g.rows16 = r16;
     HIP_TRY(c, fade_gemm(GEMM_FNR_IN, bf, g, s));
   }
   {  // Eq. 10: H_expand W_f (+ statistics for its LayerNorm)
@@ -465,6 +475,7 @@ int forward_f32(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint
     GemmArgs g{};
     g.M = B; g.N = Dh; g.K = (int)d.De;
     g.A = c->Hexp; g.lda = (int)d.De; g.W = c->Wf_c; g.C = c->V; g.ldc = Dh; g.stats_out = c->stats_o;
+    g.rows16 = r16;
     HIP_TRY(c, fade_gemm(GEMM_FNR_OUT, bf, g, s));
   }
   if (c->online) {  // the update needs H itself (for dW_o); frozen mode forms it only inside the head's operand load
@@ -480,6 +491,7 @@ int forward_f32(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint
     g.M = B; g.N = 256; g.K = Dh;
     g.A = c->V; g.A2 = c->Hc; g.lda = Dh; g.stats = c->stats_o; g.stats_n = SN; g.gamma = c->P(P_GAMMA_O); g.beta = c->P(P_BETA_O);
     g.lam = c->P(P_LAMBDA_O); g.W = c->Wo_c; g.C = c->logits; g.ldc = 256; g.bias = c->P(P_BO);
+    g.rows16 = r16;
     HIP_TRY(c, fade_gemm(GEMM_HEAD, bf, g, s));
   }
   {
@@ -506,7 +518,7 @@ int forward_bf16(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uin
   const Dims &d = c->d;
   hipStream_t s = c->stream;
   const int streams = (int)d.B, B = streams * steps;  // B: rows of this pass
-  const int Dh = (int)d.Dh, De = (int)d.De, SN = (int)(d.Dh / FADE_STATS_BN);
+  const int Dh = (int)d.Dh, De = (int)d.De, SN = (int)c->stats_n;
   // a multi-step pass has tiles enough without splitting K: each workgroup adds the K ranges itself, in the order the
   // reducing kernels would, and those then see one partial
   const int fuse = steps > 1 ? 1 : 0;
@@ -715,7 +727,7 @@ int run_phase(fade_ctx *c, const char *name, const PhaseGemms &ph) {
 TransposeArgs tr_desc(fade_ctx *c, const void *src, int ld, void *dst, const float *stats, const float *gamma, const float *beta) {
   TransposeArgs t{};
   t.src = src; t.ld = ld; t.dst = dst; t.Bp = (int)c->Bp; t.B = (int)c->d.B;
-  t.stats = stats; t.stats_n = (int)(c->d.Dh / FADE_STATS_BN); t.width = ld; t.gamma = gamma; t.beta = beta;
+  t.stats = stats; t.stats_n = (int)c->stats_n; t.width = ld; t.gamma = gamma; t.beta = beta;
   return t;
 }
 int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long tstride) {
@@ -724,7 +736,7 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
   // second stream; that variant produced rare wrong results on this machine whose cause was not found, so both are one stream.
   hipStream_t s = c->stream, w = c->stream;
   const bool bf = c->bf16;
-  const int B = (int)d.B, Dh = (int)d.Dh, De = (int)d.De, dl = (int)d.dl, SN = (int)(d.Dh / FADE_STATS_BN);
+  const int B = (int)d.B, Dh = (int)d.Dh, De = (int)d.De, dl = (int)d.dl, SN = (int)c->stats_n;
   float *G = c->grad;
   auto Gp = [&](int id) { return G + c->lay.off[id]; };
   const int RB = (B + fade_rows_per_block(B) - 1) / fade_rows_per_block(B);
@@ -1082,7 +1094,12 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
   }
   const size_t R = d.B * (size_t)c->steps_max;  // rows of the forward buffers
   const size_t np = c->lay.off[P_COUNT], BDh = R * d.Dh;
-  const size_t SN = d.Dh / FADE_STATS_BN;
+  // fp32 contexts of up to 256 streams use the small-batch products (statistics per 16 columns); FADE_F32_ROWS16=0 keeps the general kernel
+  c->rows16 = !c->bf16 && d.B <= 256 && d.Dh <= 2048 && d.Dc <= 2048 && d.De <= 2048 && d.Dh % 16 == 0 && d.Dc % 16 == 0 && d.De % 64 == 0 &&
+              d.Kc % 16 == 0 && d.D % 16 == 0;
+  if (const char *e = getenv("FADE_F32_ROWS16")) c->rows16 = c->rows16 && e[0] != '0';
+  const size_t SN = c->rows16 ? d.Dh / 16 : d.Dh / FADE_STATS_BN;
+  c->stats_n = SN;
   auto A = [&](void **p, size_t elems) { return dev_alloc_bytes(c, p, elems * c->esz); };
 #define TRY_ALLOC(expr) do { rc = (expr); if (rc) { fade_destroy(c); return rc; } } while (0)
   TRY_ALLOC(dev_alloc(c, &c->master, np));

@@ -83,6 +83,7 @@ struct GemmArgs {
   const float *bias;
   float *stats_out;       // optional [M][N / BN][2]
   const float *fold_s, *fold_t;  // EPI_GEGLU_FOLD: the folded LayerNorm's column vectors [N] (stats / stats_n: rows of A)
+  int rows16;             // fp32 path: the small-batch kernel (16 x 16 tiles; row statistics per 16 columns instead of per 128)
   int col_groups;         // pipelined kernel: column ranges of the XCD split of the tile grid (1, 2, 4, 8; 0 = chosen by the launcher)
 };
 

@@ -1097,6 +1097,108 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g) {
   epilogue<EPI, AT, BM, BN>(g, Cs, m0, n0, nt, tid);
 }
 
+// ---------------------------------------------------------------------------------------------------
+// fp32 products of very small batches (the 16-stream configuration): 16 rows x 16 columns per workgroup, the whole
+// contraction inside it. With 16 rows a 128-column tile leaves four workgroups on a 256-unit chip walking K in lock step
+// (50 us for a 16 x 512 x 512 product); here N / 16 workgroups each keep the 16 operand rows in LDS (prologue applied
+// once) and split K sixteen ways across lanes: thread (r, q) adds row r's terms k = q, q + 16, ... for the tile's 16
+// columns, reading W's 64-byte row pieces straight from L2, and a fixed butterfly over q finishes the sums. The weights
+// (4 MB for that configuration) stay L2-resident across steps, so a step streams them once from L2.
+// GeGLU tiles take 8 gate and the matching 8 value columns of a 128-column group (columns c and c + 64).
+// Row statistics are left per 16-column tile: consumers must be told stats_n = N / 16.
+// ---------------------------------------------------------------------------------------------------
+template <int PRO, int EPI>
+__global__ __launch_bounds__(256) void gemm_f32_rows_kernel(GemmArgs g) {
+  typedef float AT;
+  constexpr int BM = 16, BN = 16, LDC = BN + 4;
+  constexpr bool kGeglu = EPI == EPI_GEGLU;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int LDA = g.K + 16;  // rows 16 banks apart: the four rows a wavefront reads at one k do not collide
+  float *As = reinterpret_cast<float *>(smem);   // [16][LDA]
+  float *Cs = As + BM * LDA;                     // [16][LDC]
+  float *mom = Cs + BM * LDC;                    // [16][2]
+  const int tid = threadIdx.x, nt = blockIdx.x, m0 = blockIdx.y * BM;
+  const int n0 = kGeglu ? (nt / 8) * 128 + (nt % 8) * 8 : nt * BN;   // first (gate) column of the tile in W
+  float lam = 0.0f;
+  if (PRO == PRO_FINAL) lam = g.lam[0];
+  if (PRO == PRO_LN || PRO == PRO_FINAL) {
+    if (tid < BM) {
+      float mean, rstd;
+      row_moments(g, m0 + tid, mean, rstd);
+      mom[tid * 2] = mean; mom[tid * 2 + 1] = rstd;
+    }
+    __syncthreads();
+  }
+  const int kch = g.K / 8;
+  for (int c = tid; c < BM * kch; c += 256) {
+    const int row = c / kch, kc = (c - row * kch) * 8;
+    Raw8<AT> a, a2;
+    stage_load<PRO, AT>(g, m0 + row, kc, a, a2);
+    float v[8];
+    stage_transform<PRO, AT>(g, kc, a, a2, (PRO == PRO_LN || PRO == PRO_FINAL) ? mom[row * 2] : 0.0f,
+                             (PRO == PRO_LN || PRO == PRO_FINAL) ? mom[row * 2 + 1] : 1.0f, lam, v);
+    store8(As + row * LDA + kc, v);
+  }
+  __syncthreads();
+  const int r = tid >> 4, q = tid & 15;
+  const float *W = static_cast<const float *>(g.W) + n0;
+  const float *Ar = As + r * LDA;
+  float acc[16];
+#pragma unroll
+  for (int j = 0; j < 16; ++j) acc[j] = 0.0f;
+  // eight of a lane's k values at a time: their 32 row pieces of W are requested together (one L2 latency per batch,
+  // not per k); rows past K are clamped and their terms dropped
+  for (int k0 = q; k0 < g.K; k0 += 128) {
+    f32x4 w[8][4];
+    float av[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int k = k0 + 16 * u, kk = k < g.K ? k : q;
+      const float *wr = W + (size_t)kk * g.N;
+      w[u][0] = *reinterpret_cast<const f32x4 *>(wr); w[u][1] = *reinterpret_cast<const f32x4 *>(wr + 4);
+      w[u][2] = *reinterpret_cast<const f32x4 *>(wr + (kGeglu ? 64 : 8)); w[u][3] = *reinterpret_cast<const f32x4 *>(wr + (kGeglu ? 68 : 12));
+      av[u] = k < g.K ? Ar[kk] : 0.0f;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (k0 + 16 * u < g.K) {  // in k order, so that the sum does not depend on the batching
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          acc[i] = fmaf(av[u], w[u][0][i], acc[i]); acc[4 + i] = fmaf(av[u], w[u][1][i], acc[4 + i]);
+          acc[8 + i] = fmaf(av[u], w[u][2][i], acc[8 + i]); acc[12 + i] = fmaf(av[u], w[u][3][i], acc[12 + i]);
+        }
+      }
+    }
+  }
+  // the sixteen K slices of a row sit in sixteen neighbouring lanes: fixed butterfly, then lane q keeps column q
+  float mine = 0.0f;
+#pragma unroll
+  for (int j = 0; j < 16; ++j) {
+    float t = acc[j];
+    t += __shfl_xor(t, 1, 64); t += __shfl_xor(t, 2, 64); t += __shfl_xor(t, 4, 64); t += __shfl_xor(t, 8, 64);
+    if (q == j) mine = t;
+  }
+  Cs[r * LDC + q] = mine;
+  __syncthreads();
+  epilogue<EPI, AT, BM, BN>(g, Cs, m0, kGeglu ? 0 : n0, nt, tid);
+}
+
+template <int PRO, int EPI>
+hipError_t launch_f32_rows(const GemmArgs &g, hipStream_t s) {
+  constexpr bool kGeglu = EPI == EPI_GEGLU;
+  if (g.M <= 0 || g.K % 16 || g.K > 2048 || g.N % (kGeglu ? 128 : 16) || g.wt) return hipErrorInvalidValue;
+  const size_t lds = ((size_t)16 * (g.K + 16) + 16 * 20 + 32) * sizeof(float);
+  static size_t attr = 0;
+  auto kern = gemm_f32_rows_kernel<PRO, EPI>;
+  if (lds > attr) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    attr = lds;
+  }
+  hipLaunchKernelGGL(kern, dim3(g.N / 16, (g.M + 15) / 16), dim3(256), lds, s, g);
+  return hipGetLastError();
+}
+
 template <int WM, int WN, int TM, int TN, int PRO, int EPI>
 hipError_t launch_bf16(const GemmArgs &g, hipStream_t s) {
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
@@ -1377,6 +1479,20 @@ hipError_t fade_gemm(int op, bool bf16, const GemmArgs &g, hipStream_t s) {
         }
         return launch_tn<64, 64, 4>(g, s);
       case GEMM_CONVT:    return launch_bf16<4, 1, 1, 1, PRO_CONVT, EPI_STORE>(g, s);
+      default: return hipErrorInvalidValue;
+    }
+  }
+  if (g.rows16) {  // very small batches: 16 x 16 tiles, statistics per 16 columns (see gemm_f32_rows_kernel)
+    switch (op) {
+      case GEMM_CONV:     return launch_f32_rows<PRO_CONV, EPI_CONV>(g, s);
+      case GEMM_GLOBAL:   return launch_f32_rows<PRO_PLAIN, EPI_GLOBAL>(g, s);
+      case GEMM_ROUTER:   return launch_f32_rows<PRO_PLAIN, EPI_MIX>(g, s);
+      case GEMM_DOWN:     return launch_f32_rows<PRO_LN, EPI_STORE_F32>(g, s);
+      case GEMM_UP:       return launch_f32_rows<PRO_PLAIN, EPI_STORE>(g, s);
+      case GEMM_GATE:     return launch_f32_rows<PRO_PLAIN, EPI_GATE>(g, s);
+      case GEMM_FNR_IN:   return launch_f32_rows<PRO_LN, EPI_GEGLU>(g, s);
+      case GEMM_FNR_OUT:  return launch_f32_rows<PRO_PLAIN, EPI_STORE>(g, s);
+      case GEMM_HEAD:     return launch_f32_rows<PRO_FINAL, EPI_STORE_F32>(g, s);
       default: return hipErrorInvalidValue;
     }
   }
