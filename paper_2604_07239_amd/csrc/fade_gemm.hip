@@ -777,7 +777,8 @@ __device__ __forceinline__ void pipe2_body(const GemmArgs &g, int bid, int split
   if constexpr (SLAB) {
     // The fp32 tile does not fit LDS at once: it leaves in slabs of 64 rows, each handed to the epilogue as 128-column
     // pieces (the width the row statistics are kept at), so every output is formed exactly as by the smaller tiles.
-    static_assert(EPI != EPI_PARTIAL && EPI != EPI_GEGLU && EPI != EPI_GEGLU_FOLD && TM % 2 == 0 && BN % 128 == 0, "slab epilogue");
+    // (a GeGLU tile is gate | value per 128 columns, so each 128-column piece is a complete pair)
+    static_assert(EPI != EPI_PARTIAL && TM % 2 == 0 && BN % 128 == 0, "slab epilogue");
     constexpr int NT = NW * 64, SP = 64 / (NT / 16);     // passes of a thread over a 64-row, 128-column slab piece
     // With one workgroup on the unit (eight wavefronts) the side inputs of slab p + 1 are requested before slab p is worked
     // on; with two workgroups per unit the other one's matrix work covers that latency and the registers are not spent.
@@ -1310,7 +1311,7 @@ template <int EPI>
 hipError_t launch_pipe_auto(const GemmArgs &g, hipStream_t s) {
   const int tiles128 = ((g.M + 127) / 128) * (g.N / 128);
   const int tune = fade_gemm_tune();
-  if constexpr (EPI != EPI_PARTIAL && EPI != EPI_GEGLU && EPI != EPI_GEGLU_FOLD) {
+  if constexpr (EPI != EPI_PARTIAL) {
     const int tiles256 = ((g.M + 255) / 256) * (g.N / 256);
     if (g.N % 256 == 0 && (tune == 20 || (tune == 0 && tiles256 >= 256 && g.K >= 256))) return launch_pipe2<256, 256, 4, EPI, 8, 1>(g, s);
     if (tune == 21) return launch_pipe2<256, 128, 3, EPI, 4, 2>(g, s);
