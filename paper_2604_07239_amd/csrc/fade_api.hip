@@ -631,7 +631,11 @@ int forward_bf16(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uin
     g.A = c->Hexp; g.lda = De; g.W = c->Wf_c; g.C = c->V; g.ldc = Dh; g.stats_out = c->stats_o;
     HIP_TRY(c, fade_gemm(GEMM_FNR_OUT, true, g, s));
   }
-  if (level >= 5) {  // Eq. 10's tail
+  // Frozen weights: nothing but the head reads H, so Eq. 10's tail is formed in the head product's operand load
+  // (FADE_FUSE_HEAD=0 keeps the separate kernel; the update needs H itself for the head's weight gradient).
+  static const bool fuse_head_env = !(getenv("FADE_FUSE_HEAD") && getenv("FADE_FUSE_HEAD")[0] == '0');
+  const bool fuse_head = level >= 5 && !c->online && fuse_head_env;
+  if (level >= 5 && !fuse_head) {  // Eq. 10's tail
     feat = c->Hout;
     Prof p(c, "hout");
     HoutArgs a{};
@@ -644,7 +648,12 @@ int forward_bf16(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uin
     GemmArgs g{};
     g.M = B; g.N = 256; g.K = Dh; g.splits = c->sp_head; g.sum_splits = fuse;
     g.A = feat; g.lda = Dh; g.W = c->Wo_c; g.C = c->part_head; g.ldc = 256;
-    HIP_TRY(c, fade_gemm(GEMM_PARTIAL, true, g, s));
+    if (fuse_head) {
+      g.A = c->V; g.A2 = c->Hc; g.stats = c->stats_o; g.stats_n = SN; g.gamma = c->P(P_GAMMA_O); g.beta = c->P(P_BETA_O); g.lam = c->P(P_LAMBDA_O);
+      HIP_TRY(c, fade_gemm(GEMM_HEAD, true, g, s));
+    } else {
+      HIP_TRY(c, fade_gemm(GEMM_PARTIAL, true, g, s));
+    }
   }
   {
     Prof p(c, "softmax_quant_code");

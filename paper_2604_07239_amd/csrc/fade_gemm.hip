@@ -328,11 +328,18 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     if (PRO == PRO_FINAL) lam = g.lam[0];
   }
 
-  const int nkb = g.K / BK, ksteps = g.K / 16;
+  // EPI_PARTIAL: the contraction in ranges (grid.y), each leaving its own partial, or, with sum_splits, every range in
+  // turn inside this workgroup with their sums added in range order: the same bits as separate partials added later
+  const bool fuse = EPI == EPI_PARTIAL && g.sum_splits != 0;
+  const int nsplit = EPI == EPI_PARTIAL ? (fuse ? g.splits : (int)gridDim.y) : 1;
+  const int sp_first = fuse ? 0 : (int)blockIdx.y, sp_end = fuse ? nsplit : (int)blockIdx.y + 1;
+  const int nkb = g.K / BK / nsplit, ksteps = g.K / 16;
   // fragment stream of this wavefront's first column tile
   const bf16x8 *Wf = static_cast<const bf16x8 *>(g.W) + ((size_t)((n0 + wn * TN * 32) / 32) * ksteps) * 64 + lane;
 
-  f32x16 acc[TM][TN];
+  f32x16 acc[TM][TN], tot[EPI == EPI_PARTIAL ? TM : 1][EPI == EPI_PARTIAL ? TN : 1];
+  for (int sp = sp_first; sp < sp_end; ++sp) {
+  const int kb0 = sp * nkb;
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -343,13 +350,14 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
   Raw8<AT> ra[PASSES], ra2[PASSES];
   bf16x8 bcur[4][TN], bnext[4][TN];
 
-  // preamble: K block 0
+  // preamble: the range's first K block
 #pragma unroll
-  for (int p = 0; p < PASSES; ++p) stage_load<PRO, AT>(g, m0 + p * 32 + srow, skc, ra[p], ra2[p]);
+  for (int p = 0; p < PASSES; ++p) stage_load<PRO, AT>(g, m0 + p * 32 + srow, kb0 * BK + skc, ra[p], ra2[p]);
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-    for (int j = 0; j < TN; ++j) bcur[ks][j] = Wf[((size_t)j * ksteps + ks) * 64];
+    for (int j = 0; j < TN; ++j) bcur[ks][j] = Wf[((size_t)j * ksteps + kb0 * 4 + ks) * 64];
+  if (sp != sp_first) __syncthreads();  // the previous range's last block has been read
 #pragma unroll
   for (int p = 0; p < PASSES; ++p) {
     bf16_t *dst = As + (p * 32 + srow) * LDA + skc;
@@ -357,7 +365,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
       *reinterpret_cast<bf16x8 *>(dst) = ra[p].v;
     } else {
       float v[8];
-      stage_transform<PRO, AT>(g, skc, ra[p], ra2[p], mean[p], rstd[p], lam, v);
+      stage_transform<PRO, AT>(g, kb0 * BK + skc, ra[p], ra2[p], mean[p], rstd[p], lam, v);
       store8(dst, v);
     }
   }
@@ -365,13 +373,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
   for (int kb = 0; kb < nkb; ++kb) {
     const bool more = kb + 1 < nkb;
     if (more) {
-      const int k1 = (kb + 1) * BK;
+      const int k1 = (kb0 + kb + 1) * BK;
 #pragma unroll
       for (int p = 0; p < PASSES; ++p) stage_load<PRO, AT>(g, m0 + p * 32 + srow, k1 + skc, ra[p], ra2[p]);
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) bnext[ks][j] = Wf[((size_t)j * ksteps + (kb + 1) * 4 + ks) * 64];
+        for (int j = 0; j < TN; ++j) bnext[ks][j] = Wf[((size_t)j * ksteps + (kb0 + kb + 1) * 4 + ks) * 64];
     }
     __syncthreads();
     const bf16_t *Ab = As + (kb & 1) * BM * LDA;
@@ -389,7 +397,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     }
     if (more) {
       bf16_t *An = As + ((kb + 1) & 1) * BM * LDA;
-      const int k1 = (kb + 1) * BK;
+      const int k1 = (kb0 + kb + 1) * BK;
 #pragma unroll
       for (int p = 0; p < PASSES; ++p) {
         bf16_t *dst = An + (p * 32 + srow) * LDA + skc;
@@ -407,6 +415,16 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
         for (int j = 0; j < TN; ++j) bcur[ks][j] = bnext[ks][j];
     }
   }
+  if constexpr (EPI == EPI_PARTIAL) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        if (sp == sp_first) tot[i][j] = acc[i][j];
+        else tot[i][j] += acc[i][j];
+      }
+  }
+  }
 
   // park the accumulators: lane l of a 32x32 tile holds column l % 32, rows (e / 4) * 8 + (l / 32) * 4 + e % 4
   __syncthreads();
@@ -418,10 +436,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
       for (int e = 0; e < 16; ++e) {
         const int row = (wm * TM + i) * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
         const int col = (wn * TN + j) * 32 + (lane & 31);
-        Cs[row * LDC + col] = acc[i][j][e];
+        if constexpr (EPI == EPI_PARTIAL) Cs[row * LDC + col] = tot[i][j][e];
+        else Cs[row * LDC + col] = acc[i][j][e];
       }
   __syncthreads();
-  epilogue<EPI, AT, BM, BN>(g, Cs, m0, n0, nt, tid);
+  epilogue<EPI, AT, BM, BN>(g, Cs, m0, n0, nt, tid, fuse ? 0 : (int)blockIdx.y);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -1212,9 +1231,10 @@ hipError_t launch_bf16(const GemmArgs &g, hipStream_t s) {
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  if (g.N % BN || g.K % 64 || g.M <= 0) return hipErrorInvalidValue;
+  const int splits = (EPI == EPI_PARTIAL && g.splits > 1) ? g.splits : 1;
+  if (g.N % BN || g.K % (64 * splits) || g.M <= 0 || (EPI != EPI_PARTIAL && (g.splits > 1 || g.sum_splits))) return hipErrorInvalidValue;
   const int grid = ((g.M + BM - 1) / BM) * (g.N / BN);
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, s, g);
+  hipLaunchKernelGGL(kern, dim3(grid, g.sum_splits ? 1 : splits), dim3(256), lds, s, g);
   return hipGetLastError();
 }
 
@@ -1480,6 +1500,10 @@ hipError_t fade_gemm(int op, bool bf16, const GemmArgs &g, hipStream_t s) {
         }
         return launch_tn<64, 64, 4>(g, s);
       case GEMM_CONVT:    return launch_bf16<4, 1, 1, 1, PRO_CONVT, EPI_STORE>(g, s);
+      case GEMM_HEAD:     // head on H = psi(LN(V)) + lam * H_coarse formed in the operand load (Eq. 10's tail never goes to memory):
+        // 32 rows x all 256 columns per workgroup (two workgroups per unit), so every row is transformed once; split-K partials as GEMM_PARTIAL leaves them
+        if (!g.stats || !g.A2 || !g.gamma || !g.beta || !g.lam || g.N != 256) return hipErrorInvalidValue;
+        return launch_bf16<1, 4, 1, 2, PRO_FINAL, EPI_PARTIAL>(g, s);
       default: return hipErrorInvalidValue;
     }
   }
