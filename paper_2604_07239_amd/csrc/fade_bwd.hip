@@ -271,6 +271,9 @@ __global__ __launch_bounds__(256) void embed_t_kernel(WinSrc ws, int B, int Bp, 
 // (fewer partial sums to write and add up). B = 1024: the three kernels 15.5 / 20.0 / 26.7 us with four rows, 13.7 / 14.8 /
 // 21.3 with two (one row: 13.3 / 14.4 / 20.1, but 8 us more in the reduction of twice as many partial sums).
 inline int rows_per_block(int B) { return B <= 2048 ? 2 : 4; }
+// Row groups one workgroup of a row kernel walks through, adding the LayerNorm-gain partials of all of them in registers:
+// at large batches this keeps the first-stage partial buffers (one row of 2 D_h floats per workgroup) small.
+__host__ __device__ inline int row_groups(int B) { return B >= 8192 ? 4 : 1; }
 
 // Several row sums at once over a 256-thread workgroup (same fixed order as block_sum); red holds 4 * N floats.
 template <int N>
@@ -305,9 +308,11 @@ __global__ __launch_bounds__(256) void bwd_out_kernel(BwdOutArgs a) {
   for (int i = 0; i < 8; ++i) { ga[i] = be[i] = pg[i] = pb[i] = 0.0f; }
   if (mine) { ld8<float>(a.gamma + tid * 8, ga); ld8<float>(a.beta + tid * 8, be); }
   float dh[R][8], xh[R][8], rstd[R], sums[3 * R];
+  const int G = row_groups(a.B);
+  for (int rb = blockIdx.x * G; rb < (int)blockIdx.x * G + G; ++rb) {
 #pragma unroll
   for (int r = 0; r < R; ++r) {
-    const int b = blockIdx.x * R + r;
+    const int b = rb * R + r;
     float s1 = 0.0f, s2 = 0.0f, sl = 0.0f, mean = 0.0f;
     rstd[r] = 0.0f;
 #pragma unroll
@@ -339,7 +344,7 @@ __global__ __launch_bounds__(256) void bwd_out_kernel(BwdOutArgs a) {
   block_sum_n<3 * R>(sums, red);
 #pragma unroll
   for (int r = 0; r < R; ++r) {
-    const int b = blockIdx.x * R + r;
+    const int b = rb * R + r;
     if (b >= a.B) break;
     if (tid == 0) a.row_dlam[b] = sums[2 * R + r];
     if (mine) {
@@ -349,6 +354,7 @@ __global__ __launch_bounds__(256) void bwd_out_kernel(BwdOutArgs a) {
       for (int i = 0; i < 8; ++i) dv[i] = rstd[r] * (dh[r][i] - m1 - xh[r][i] * m2);
       st8<AT>(static_cast<AT *>(a.dV) + (size_t)b * a.Dh + tid * 8, dv);
     }
+  }
   }
   if (mine) {
     float *p = a.ln_part + (size_t)blockIdx.x * 2 * a.Dh;
@@ -390,9 +396,11 @@ __global__ __launch_bounds__(256) void bwd_gate_kernel(BwdGateArgs a) {
   for (int i = 0; i < 8; ++i) { ga[i] = pg[i] = pb[i] = 0.0f; }
   if (mine) ld8<float>(a.gamma + tid * 8, ga);
   float dh[R][8], xh[R][8], rstd[R], sums[2 * R], sl[R];
+  const int G = row_groups(a.B);
+  for (int rb = blockIdx.x * G; rb < (int)blockIdx.x * G + G; ++rb) {
 #pragma unroll
   for (int r = 0; r < R; ++r) {
-    const int b = blockIdx.x * R + r;
+    const int b = rb * R + r;
     float s1 = 0.0f, s2 = 0.0f, mean = 0.0f;
     rstd[r] = 0.0f;
 #pragma unroll
@@ -431,7 +439,7 @@ __global__ __launch_bounds__(256) void bwd_gate_kernel(BwdGateArgs a) {
   block_sum_n<2 * R>(sums, red);
 #pragma unroll
   for (int r = 0; r < R; ++r) {
-    const int b = blockIdx.x * R + r;
+    const int b = rb * R + r;
     sl[r] = 0.0f;
     if (b < a.B && mine) {
       const size_t base = (size_t)b * a.Dh + tid * 8;
@@ -460,7 +468,8 @@ __global__ __launch_bounds__(256) void bwd_gate_kernel(BwdGateArgs a) {
   if (tid == 0) {
 #pragma unroll
     for (int r = 0; r < R; ++r)
-      if (blockIdx.x * R + r < a.B) a.row_dlam[blockIdx.x * R + r] = sl[r];
+      if (rb * R + r < a.B) a.row_dlam[rb * R + r] = sl[r];
+  }
   }
   if (mine) {
     float *p = a.ln_part + (size_t)blockIdx.x * 2 * a.Dh;
@@ -485,9 +494,11 @@ __global__ __launch_bounds__(256) void bwd_mix_kernel(BwdMixArgs a) {
   for (int i = 0; i < 8; ++i) { ga[i] = pg[i] = pb[i] = 0.0f; }
   if (mine) ld8<float>(a.gamma + tid * 8, ga);
   float dh[R][8], xh[R][8], rstd[R], sums[2 * R], sl[R];
+  const int G = row_groups(a.B);
+  for (int rb = blockIdx.x * G; rb < (int)blockIdx.x * G + G; ++rb) {
 #pragma unroll
   for (int r = 0; r < R; ++r) {
-    const int b = blockIdx.x * R + r;
+    const int b = rb * R + r;
     float s1 = 0.0f, s2 = 0.0f, mean = 0.0f;
     rstd[r] = 0.0f;
 #pragma unroll
@@ -517,7 +528,7 @@ __global__ __launch_bounds__(256) void bwd_mix_kernel(BwdMixArgs a) {
   block_sum_n<2 * R>(sums, red);
 #pragma unroll
   for (int r = 0; r < R; ++r) {
-    const int b = blockIdx.x * R + r;
+    const int b = rb * R + r;
     sl[r] = 0.0f;
     if (b < a.B && mine) {
       const size_t base = (size_t)b * a.Dh + tid * 8;
@@ -557,7 +568,8 @@ __global__ __launch_bounds__(256) void bwd_mix_kernel(BwdMixArgs a) {
   if (tid == 0) {
 #pragma unroll
     for (int r = 0; r < R; ++r)
-      if (blockIdx.x * R + r < a.B) a.row_dlam[blockIdx.x * R + r] = sl[r];
+      if (rb * R + r < a.B) a.row_dlam[rb * R + r] = sl[r];
+  }
   }
   if (mine) {
     float *p = a.ln_part + (size_t)blockIdx.x * 2 * a.Dh;
@@ -1325,8 +1337,8 @@ hipError_t fade_embed_t(const WinSrc &ws, int B, int Bp, int T, int D, const voi
 }
 #define DISPATCH_ROWS(bf16, KERNEL, B, stream, args)                                                                             \
   do {                                                                                                                            \
-    const int R_ = rows_per_block(B);                                                                                             \
-    const dim3 grid_((B + R_ - 1) / R_);                                                                                          \
+    const int R_ = rows_per_block(B), RG_ = R_ * row_groups(B);                                                                   \
+    const dim3 grid_((B + RG_ - 1) / RG_);                                                                                        \
     if (bf16) {                                                                                                                   \
       if (R_ == 1) hipLaunchKernelGGL((KERNEL<bf16_t, 1>), grid_, dim3(256), 0, stream, args);                                    \
       else if (R_ == 2) hipLaunchKernelGGL((KERNEL<bf16_t, 2>), grid_, dim3(256), 0, stream, args);                               \
@@ -1347,7 +1359,7 @@ hipError_t fade_bwd_geglu(int B, int De, const void *dHexp, const void *eg, cons
 }
 hipError_t fade_bwd_gate(const BwdGateArgs &a, bool bf16, hipStream_t s) { DISPATCH_ROWS(bf16, bwd_gate_kernel, a.B, s, a); }
 hipError_t fade_bwd_mix(const BwdMixArgs &a, bool bf16, hipStream_t s) { DISPATCH_ROWS(bf16, bwd_mix_kernel, a.B, s, a); }
-int fade_rows_per_block(int B) { return rows_per_block(B); }
+int fade_rows_per_block(int B) { return rows_per_block(B) * row_groups(B); }
 hipError_t fade_reduce_batch(const ReduceBatch &rb, hipStream_t s) {
   if (rb.count <= 0) return hipSuccess;
   int maxN = 0;
