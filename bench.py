@@ -182,10 +182,11 @@ def main():
             ach = flop / (us * 1e-6) / 1e12
             # HBM bytes per launch of this shape from the counter runs under profiles/ (null for a shape that was not profiled)
             traffic = ROUTER_GATE_TRAFFIC_BYTES.get((rows, Dh, mode))
-            roofline = {"bound": "mfma", "kernel": f"gemm_pipe_kernel (router / gate product, M={rows}, N=K=D_h)", "achieved": round(ach, 2),
+            roofline = {"bound": "mfma", "kernel": f"{'gemm_pipe2_kernel' if rows >= 8192 else 'gemm_pipe_kernel'} (router / gate product, M={rows}, N=K=D_h)", "achieved": round(ach, 2),
                         "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s", "frac": round(ach * 1e12 / MFMA_BF16_PEAK, 4),
                         "traffic": traffic, "avg_us": round(us, 2), "flop_per_launch": flop,
-                        "algorithmic_bytes_per_launch": 2 * ((6 if mode == "online" else 5) * rows * Dh + Dh * Dh)}
+                        # operand rows, the two side inputs and the output (+ alpha / the gate, kept for the update only), W once
+                        "algorithmic_bytes_per_launch": 2 * ((5 if mode == "online" else 4) * rows * Dh + Dh * Dh)}
         if roofline is None and "gemm_global" in kern and spec["dtype"] == "bf16":   # ablation level 1: the global projection is all there is
             us = kern["gemm_global"]["avg_us"]
             rows = B * steps_prof // max(kern["gemm_global"]["launches"], 1)

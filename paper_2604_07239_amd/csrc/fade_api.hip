@@ -410,7 +410,7 @@ int forward_f32(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint
     GemmArgs g{};
     g.M = (int)(d.B * d.T); g.N = (int)d.D; g.K = (int)d.Kc;
     g.A = c->XL; g.T = (int)d.T; g.D = (int)d.D; g.taps = (int)d.k;
-    g.W = c->Wconv_c; g.C = c->Hl; g.ldc = (int)d.D; g.C2 = c->cv; g.bias = c->P(P_BCONV);
+    g.W = c->Wconv_c; g.C = c->Hl; g.ldc = (int)d.D; g.C2 = c->online ? c->cv : nullptr; g.bias = c->P(P_BCONV);
     g.rows16 = r16;
     HIP_TRY(c, fade_gemm(GEMM_CONV, bf, g, s));
   }
@@ -418,7 +418,7 @@ int forward_f32(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint
     Prof p(c, "gemm_global");
     GemmArgs g{};
     g.M = B; g.N = Dh; g.K = (int)d.Dc;
-    g.A = c->M; g.lda = (int)d.Dc; g.W = c->Wm_c; g.C = c->Hg; g.ldc = Dh; g.C2 = c->hm; g.S1 = c->X; g.lam = c->P(P_LAMBDA_M);
+    g.A = c->M; g.lda = (int)d.Dc; g.W = c->Wm_c; g.C = c->Hg; g.ldc = Dh; g.C2 = c->online ? c->hm : nullptr; g.S1 = c->X; g.lam = c->P(P_LAMBDA_M);
     g.rows16 = r16;
     HIP_TRY(c, fade_gemm(GEMM_GLOBAL, bf, g, s));
   }
@@ -426,7 +426,7 @@ int forward_f32(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint
     Prof p(c, "gemm_router");
     GemmArgs g{};
     g.M = B; g.N = Dh; g.K = Dh;
-    g.A = c->X; g.lda = Dh; g.W = c->Wr_c; g.C = c->Hmix; g.ldc = Dh; g.C2 = c->alpha; g.S1 = c->Hg; g.S2 = c->Hl;
+    g.A = c->X; g.lda = Dh; g.W = c->Wr_c; g.C = c->Hmix; g.ldc = Dh; g.C2 = c->online ? c->alpha : nullptr; g.S1 = c->Hg; g.S2 = c->Hl;
     g.stats_out = c->stats_c;
     g.rows16 = r16;
     HIP_TRY(c, fade_gemm(GEMM_ROUTER, bf, g, s));
@@ -456,7 +456,7 @@ int forward_f32(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint
     Prof p(c, "gemm_gate");
     GemmArgs g{};
     g.M = B; g.N = Dh; g.K = Dh;
-    g.A = c->Hmix; g.lda = Dh; g.W = c->Wc_c; g.C = c->Hc; g.ldc = Dh; g.C2 = c->sg; g.S1 = c->Ha; g.S2 = c->Hmix;
+    g.A = c->Hmix; g.lda = Dh; g.W = c->Wc_c; g.C = c->Hc; g.ldc = Dh; g.C2 = c->online ? c->sg : nullptr; g.S1 = c->Ha; g.S2 = c->Hmix;
     g.lam = c->P(P_LAMBDA_C); g.stats_out = c->stats_f;
     g.rows16 = r16;
     HIP_TRY(c, fade_gemm(GEMM_GATE, bf, g, s));
@@ -466,7 +466,7 @@ int forward_f32(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint
     GemmArgs g{};
     g.M = B; g.N = (int)(2 * d.De); g.K = Dh;
     g.A = c->Hc; g.lda = Dh; g.stats = c->stats_f; g.stats_n = SN; g.gamma = c->P(P_GAMMA_F); g.beta = c->P(P_BETA_F);
-    g.W = c->Wfgv_c; g.C = c->Hexp; g.ldc = (int)d.De; g.C2 = c->eg; g.C3 = c->ev;
+    g.W = c->Wfgv_c; g.C = c->Hexp; g.ldc = (int)d.De; if (c->online) { g.C2 = c->eg; g.C3 = c->ev; }
     g.rows16 = r16;
     HIP_TRY(c, fade_gemm(GEMM_FNR_IN, bf, g, s));
   }
@@ -535,7 +535,7 @@ int forward_bf16(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uin
     a.tabXe = c->tabXe; a.tabXl = c->tabXl; a.tabXe32 = c->tabXe32; a.Wg = c->Wg_c; a.Wv = c->Wv_c;
     a.X = c->X; a.XL = c->XL; a.M = c->M; a.GG = c->GG; a.GV = c->GV; a.slot_tab = c->slot_tab; a.B = streams; a.S = steps;
     if (conv_fused) {  // Eq. 4 rides along: one launch less, and the per-token rows XL only exist for the backward pass
-      a.conv_W = c->Wconv_c; a.conv_b = c->P(P_BCONV); a.Hl = c->Hl; a.cv = c->cv; a.taps = (int)d.k; a.Kc = (int)d.Kc;
+      a.conv_W = c->Wconv_c; a.conv_b = c->P(P_BCONV); a.Hl = c->Hl; a.cv = c->online ? c->cv : nullptr; a.taps = (int)d.k; a.Kc = (int)d.Kc;
       if (!c->online) a.XL = nullptr;
     }
     if (steps > 1) HIP_TRY(c, fade_embed_steps(a, s));
@@ -546,14 +546,14 @@ int forward_bf16(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uin
     GemmArgs g{};
     g.M = B * (int)d.T; g.N = (int)d.D; g.K = (int)d.Kc;
     g.A = c->XL; g.T = (int)d.T; g.D = (int)d.D; g.taps = (int)d.k;
-    g.W = c->Wconv_c; g.C = c->Hl; g.ldc = (int)d.D; g.C2 = c->cv; g.bias = c->P(P_BCONV);
+    g.W = c->Wconv_c; g.C = c->Hl; g.ldc = (int)d.D; g.C2 = c->online ? c->cv : nullptr; g.bias = c->P(P_BCONV);
     HIP_TRY(c, fade_gemm(GEMM_CONV, true, g, s));
   }
   {  // Eq. 3
     Prof p(c, "gemm_global");
     GemmArgs g{};
     g.M = B; g.N = Dh; g.K = (int)d.Dc;
-    g.A = c->M; g.lda = (int)d.Dc; g.W = c->Wm_c; g.C = c->Hg; g.ldc = Dh; g.C2 = c->hm; g.S1 = c->X; g.lam = c->P(P_LAMBDA_M);
+    g.A = c->M; g.lda = (int)d.Dc; g.W = c->Wm_c; g.C = c->Hg; g.ldc = Dh; g.C2 = c->online ? c->hm : nullptr; g.S1 = c->X; g.lam = c->P(P_LAMBDA_M);
     HIP_TRY(c, fade_gemm(GEMM_GLOBAL, true, g, s));
   }
   if (level >= 2) {  // Eq. 5-6
@@ -561,7 +561,7 @@ int forward_bf16(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uin
     Prof p(c, "gemm_router");
     GemmArgs g{};
     g.M = B; g.N = Dh; g.K = Dh;
-    g.A = c->X; g.lda = Dh; g.W = c->Wr_c; g.C = c->Hmix; g.ldc = Dh; g.C2 = c->alpha; g.S1 = c->Hg; g.S2 = c->Hl;
+    g.A = c->X; g.lda = Dh; g.W = c->Wr_c; g.C = c->Hmix; g.ldc = Dh; g.C2 = c->online ? c->alpha : nullptr; g.S1 = c->Hg; g.S2 = c->Hl;
     g.stats_out = c->stats_c;
     HIP_TRY(c, fade_gemm(GEMM_ROUTER, true, g, s));
   }
@@ -595,7 +595,7 @@ int forward_bf16(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uin
     Prof p(c, "gemm_gate");
     GemmArgs g{};
     g.M = B; g.N = Dh; g.K = Dh;
-    g.A = c->Hmix; g.lda = Dh; g.W = c->Wc_c; g.C = c->Hc; g.ldc = Dh; g.C2 = c->sg; g.S1 = c->Ha; g.S2 = c->Hmix;
+    g.A = c->Hmix; g.lda = Dh; g.W = c->Wc_c; g.C = c->Hc; g.ldc = Dh; g.C2 = c->online ? c->sg : nullptr; g.S1 = c->Ha; g.S2 = c->Hmix;
     g.lam = c->P(P_LAMBDA_C); g.stats_out = c->stats_f;
     HIP_TRY(c, fade_gemm(GEMM_GATE, true, g, s));
   }
@@ -604,7 +604,7 @@ int forward_bf16(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uin
     Prof p(c, "gemm_fnr_in");
     GemmArgs g{};
     g.M = B; g.N = 2 * De; g.K = Dh;
-    g.A = c->Hc; g.lda = Dh; g.W = c->Wfgv_c; g.C = c->Hexp; g.ldc = De; g.C2 = c->eg; g.C3 = c->ev;
+    g.A = c->Hc; g.lda = Dh; g.W = c->Wfgv_c; g.C = c->Hexp; g.ldc = De; if (c->online) { g.C2 = c->eg; g.C3 = c->ev; }
     g.stats = c->stats_f; g.stats_n = SN; g.fold_s = c->s_fnr; g.fold_t = c->t_fnr;
     HIP_TRY(c, fade_gemm(GEMM_FNR_IN, true, g, s));
   } else {
@@ -620,7 +620,7 @@ int forward_bf16(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uin
     GegluArgs a{};
     a.B = B; a.Dh = Dh; a.De = De; a.splits = sp_fnr; a.stats_n = SN; a.part = c->part_fnr; a.stats = c->stats_f;
     a.s_fold = c->s_fnr; a.t_fold = c->t_fnr; a.Hexp = static_cast<bf16_t *>(c->Hexp);
-    a.eg = static_cast<bf16_t *>(c->eg); a.ev = static_cast<bf16_t *>(c->ev);
+    if (c->online) { a.eg = static_cast<bf16_t *>(c->eg); a.ev = static_cast<bf16_t *>(c->ev); }  // only the update reads them
     HIP_TRY(c, fade_geglu(a, s));
   }
   }
