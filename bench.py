@@ -38,11 +38,15 @@ MiB = 1 << 20
 # (FETCH x 2.0, WRITE x 1.0 against a plain 256 MiB copy, see profiles/cfg2_frozen_pmc_counters.md). A shape that
 # was not profiled reports null.
 ROUTER_GATE_TRAFFIC_BYTES = {
-    (16384, 2048, "frozen"): int(0.5 * (320.5 + 66.0 + 314.1 + 66.1) * MiB),   # profiles/cfg2_frozen_multistep_kernel_trace_and_hbm.md
+    (16384, 2048, "frozen"): int(0.5 * (320.5 + 66.0 + 314.0 + 66.1) * MiB),   # profiles/cfg5_frozen_kernel_trace_and_hbm.md (cfg 2's 16-step passes have the same shape)
+    (16384, 2048, "online"): int(0.5 * (320.4 + 130.2 + 314.2 + 130.3) * MiB), # profiles/cfg5_online_kernel_trace_and_hbm.md
     (1024, 2048, "online"): int(0.5 * (56.4 + 53.5) * MiB),                    # profiles/cfg2_online_kernel_trace_and_hbm.md
 }
+# the same for the fp32 small-batch product (gemm_f32_rows_kernel) by (B, D_h, mode): profiles/cfg1_kernel_trace_and_hbm.md
+F32_ROUTER_GATE_TRAFFIC_BYTES = {}
 # adam_refresh_kernel by (parameters of the nine big matrices, mode), same counter runs
-ADAM_TRAFFIC_BYTES = {(11272192, "online"): int((171.59 + 167.46) * MiB)}      # profiles/cfg2_online_kernel_trace_and_hbm.md
+ADAM_TRAFFIC_BYTES = {(11272192, "online"): int((171.59 + 167.46) * MiB),      # profiles/cfg2_online_kernel_trace_and_hbm.md
+                      (13369344, "online"): int((269.41 + 253.27) * MiB)}      # profiles/cfg5_online_kernel_trace_and_hbm.md
 
 
 def parse():
@@ -207,6 +211,16 @@ def main():
                         "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s", "frac": round(ach * 1e12 / MFMA_BF16_PEAK, 4),
                         "traffic": None, "avg_us": round(us, 2), "flop_per_launch": flop,
                         "algorithmic_bytes_per_launch": 2 * rows * Dh + 2 * Dh * 2 * De + 4 * rows * 2 * De}
+        if roofline is None and "gemm_router" in kern and spec["dtype"] == "f32":
+            # fp32 at a small batch (cfg 1): every product streams its fp32 weight matrix once past a handful of rows, so the
+            # step is bound by weight bytes (and by launch latency); the widest weight stream is the D_h x D_h router / gate product
+            twins = [kern[k]["avg_us"] for k in ("gemm_router", "gemm_gate") if k in kern]
+            us = sum(twins) / len(twins)
+            nbytes = 4 * (Dh * Dh + (5 if mode == "online" else 4) * B * Dh)
+            ach = nbytes / (us * 1e-6) / 1e9
+            roofline = {"bound": "hbm", "kernel": f"gemm_f32_rows_kernel (router / gate product, M={B}, N=K=D_h, fp32 weights)", "achieved": round(ach, 2),
+                        "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": round(ach * 1e9 / HBM_PEAK, 5),
+                        "traffic": F32_ROUTER_GATE_TRAFFIC_BYTES.get((B, Dh, mode)), "avg_us": round(us, 2), "algorithmic_bytes_per_launch": nbytes}
         update_roofline = None
         if "adam_matrices" in kern and spec["dtype"] == "bf16":
             # the longest single launch of an online step: Adam on the nine big matrices fused with the refresh of their bf16

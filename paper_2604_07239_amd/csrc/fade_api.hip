@@ -725,8 +725,17 @@ struct PhaseGemms {
 int run_phase(fade_ctx *c, const char *name, const PhaseGemms &ph) {
   Prof p(c, name);
   if (c->bf16) {
+    // An activation gradient that fills the chip with 256 x 256 tiles by itself (large batches) runs as a launch of its
+    // own on the eight-wavefront kernel: half the operand bytes per flop of the 128 x 128 tiles a group is made of
+    // (B = 16384: gate phase 357 -> 337 us, router phase 454 -> 434). With a short contraction (the head's K = 256) the
+    // overlap with the weight gradient inside a group is worth more (87 us grouped against 105).
     GemmGroup gg{};
-    for (int i = 0; i < ph.n; ++i) HIP_TRY(c, fade_gemm_group_add(gg, ph.op[i], ph.g[i]));
+    for (int i = 0; i < ph.n; ++i) {
+      const GemmArgs &g = ph.g[i];
+      const bool alone = ph.op[i] == GEMM_X_STORE && g.N % 256 == 0 && g.K >= 1024 && ((g.M + 255) / 256) * (g.N / 256) >= 256;
+      if (alone) HIP_TRY(c, fade_gemm(GEMM_X_STORE, true, g, c->stream));
+      else HIP_TRY(c, fade_gemm_group_add(gg, ph.op[i], g));
+    }
     HIP_TRY(c, fade_gemm_group_launch(gg, c->stream));
   } else {
     for (int i = 0; i < ph.n; ++i) HIP_TRY(c, fade_gemm(ph.op[i] == GEMM_W_TN ? GEMM_W : ph.op[i], false, ph.g[i], c->stream));
