@@ -732,8 +732,9 @@ int run_phase(fade_ctx *c, const char *name, const PhaseGemms &ph) {
     GemmGroup gg{};
     for (int i = 0; i < ph.n; ++i) {
       const GemmArgs &g = ph.g[i];
-      const bool alone = ph.op[i] == GEMM_X_STORE && g.N % 256 == 0 && g.K >= 1024 && ((g.M + 255) / 256) * (g.N / 256) >= 256;
-      if (alone) HIP_TRY(c, fade_gemm(GEMM_X_STORE, true, g, c->stream));
+      const bool alone = (ph.op[i] == GEMM_X_STORE && g.N % 256 == 0 && g.K >= 1024 && ((g.M + 255) / 256) * (g.N / 256) >= 256) ||
+                         (ph.op[i] == GEMM_W_TN && fade_gemm_tn2_ok(g.M, g.N, g.K));
+      if (alone) HIP_TRY(c, fade_gemm(ph.op[i], true, g, c->stream));
       else HIP_TRY(c, fade_gemm_group_add(gg, ph.op[i], g));
     }
     HIP_TRY(c, fade_gemm_group_launch(gg, c->stream));
@@ -1242,6 +1243,17 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
                                                     {P_WDOWN, -1, (int)d.Dh, (int)d.dl}, {P_WUP, -1, (int)d.dl, (int)d.Dh}, {P_WM, -1, (int)d.Dc, (int)d.Dh},
                                                     {P_WC, -1, (int)d.Dh, (int)d.Dh}, {P_WR, -1, (int)d.Dh, (int)d.Dh}};
       for (const auto &w : gw) {
+        if (fade_gemm_tn2_ok(w.M, w.N, (int)Bp)) {  // 256 x 256 tiles, one workgroup per compute unit: ranges until every unit has one
+          const int tiles256 = (w.M / 256) * (w.N / 256), nkb = (int)(Bp / 64);
+          int sp = 1;
+          while (sp < 16 && tiles256 * sp * 2 <= 256 && nkb % (sp * 2) == 0 && nkb / (sp * 2) >= 8) sp *= 2;
+          if (sp > 1) {
+            c->gsp[w.id] = sp;
+            TRY_ALLOC(dev_alloc(c, &c->gpart[w.id], (size_t)sp * c->lay.len[w.id]));
+            if (w.pair >= 0) { c->gsp[w.pair] = sp; TRY_ALLOC(dev_alloc(c, &c->gpart[w.pair], (size_t)sp * c->lay.len[w.pair])); }
+          }
+          continue;
+        }
         const int tiles = fade_gemm_tn_tiles(w.M, w.N);
         if (tiles <= 0) continue;
         const bool small = c->lay.len[w.id] <= (256u << 10);

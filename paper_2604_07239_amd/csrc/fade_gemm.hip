@@ -485,6 +485,18 @@ __device__ __forceinline__ void lds_landed(bf16x8 &v) {
   asm volatile("" : "+v"(t));
   v = __builtin_bit_cast(bf16x8, t);
 }
+// The same for gfx950's transposing read of four 16-bit values per lane (ds_read_b64_tr_b16); two of them make one operand.
+typedef __attribute__((ext_vector_type(2))) int i32x2;
+template <int OFF> __device__ __forceinline__ i32x2 tr_read8(uint32_t addr) {
+  i32x2 v;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+  return v;
+}
+__device__ __forceinline__ void tr_landed(i32x2 &v) { asm volatile("" : "+v"(v)); }
+__device__ __forceinline__ bf16x8 tr_pair(i32x2 lo, i32x2 hi) {
+  typedef __attribute__((ext_vector_type(4))) int i32x4;
+  return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3));
+}
 
 template <int BM, int BN, int STAGES, int EPI, bool BROW, int NW = 4>
 __device__ __forceinline__ void pipe_body(const GemmArgs &g, int bid, int split, int nsplit) {
@@ -880,30 +892,33 @@ typedef __attribute__((ext_vector_type(4))) short i16x4;
 typedef __attribute__((ext_vector_type(8))) short i16x8;
 // piece permutation of row r in a stage whose rows are PITCH bytes long
 template <int PITCH> __device__ __forceinline__ int tn_swizzle(int r) {
-  static_assert(PITCH == 128 || PITCH == 256, "row pitch");
-  return PITCH == 256 ? ((r & 3) << 2) : (((r >> 1) & 1) << 2);
+  static_assert(PITCH == 128 || PITCH == 256 || PITCH == 512, "row pitch");
+  return PITCH >= 256 ? ((r & 3) << 2) : (((r >> 1) & 1) << 2);  // 512: the permutation stays inside a row's 256-byte half
 }
 
-template <int BM, int BN, int STAGES>
-__device__ __forceinline__ void tn_body(const GemmArgs &g, int bid, int split = 0, int nsplit = 1) {
+// NW wavefronts as 2 (rows) x NW / 2 (columns); a 256 x 256 tile on eight of them hands its fp32 result to the epilogue in
+// slabs of 64 rows (as pipe2_body does), half the operand bytes and three quarters of the LDS reads per flop of 128 x 128.
+template <int BM, int BN, int STAGES, int NW = 4>
+__device__ __forceinline__ void tn_body(const GemmArgs &g, int bid, int split = 0, int nsplit = 1, int mt_in = -1, int nt_in = -1) {
   typedef bf16_t AT;
   constexpr int BK = 64, KS = 4;
-  constexpr int TM = BM / 64, TN = BN / 64;
+  constexpr int WN = NW / 2;
+  constexpr int TM = BM / 64, TN = BN / (32 * WN);
   constexpr int PA = BM / 8, PB = BN / 8;          // 16-byte pieces per row
   constexpr int RA = 64 / PA, RB = 64 / PB;        // rows per DMA
   constexpr int A_BYTES = BK * BM * 2, B_BYTES = BK * BN * 2;
-  constexpr int ACH = BK / RA / 4, BCH = BK / RB / 4;  // DMAs per wavefront and stage
+  constexpr int ACH = BK / RA / NW, BCH = BK / RB / NW;  // DMAs per wavefront and stage
   constexpr int LPW = ACH + BCH, STAGE_BYTES = A_BYTES + B_BYTES, LDC = BN + 4;
-  static_assert(PA >= 8 && PB >= 8 && (BK / RA) % 4 == 0 && (BK / RB) % 4 == 0, "tile shape");
+  static_assert(PA >= 8 && PB >= 8 && (BK / RA) % NW == 0 && (BK / RB) % NW == 0 && BN % (32 * WN) == 0, "tile shape");
   static_assert((STAGES - 2) * LPW <= 63, "vmcnt range");
   extern __shared__ __align__(16) unsigned char smem[];
   float *Cs = reinterpret_cast<float *>(smem);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WN, wn = wave % WN;
   const int ntn = g.N / BN, ntm = g.M / BM;
-  int mt, nt;
-  if (!tile_of_block(bid, ntm, ntn, 8, mt, nt)) return;
+  int mt = mt_in, nt = nt_in;
+  if (mt_in < 0 && !tile_of_block(bid, ntm, ntn, 8, mt, nt)) return;
   const int m0 = mt * BM, n0 = nt * BN;
   const int nkb = g.K / BK / nsplit, kb0 = split * nkb;  // this workgroup's range of the contraction (the batch)
 
@@ -913,13 +928,13 @@ __device__ __forceinline__ void tn_body(const GemmArgs &g, int bid, int split = 
   const bf16_t *a_col[ACH], *b_src[BCH];
 #pragma unroll
   for (int q = 0; q < ACH; ++q) {
-    const int row = (wave + 4 * q) * RA + lane / PA, piece = (lane % PA) ^ tn_swizzle<BM * 2>(row);
+    const int row = (wave + NW * q) * RA + lane / PA, piece = (lane % PA) ^ tn_swizzle<BM * 2>(row);
     a_row[q] = row;
     a_col[q] = static_cast<const bf16_t *>(g.A) + m0 + piece * 8;
   }
 #pragma unroll
   for (int q = 0; q < BCH; ++q) {
-    const int row = (wave + 4 * q) * RB + lane / PB, piece = (lane % PB) ^ tn_swizzle<BN * 2>(row);
+    const int row = (wave + NW * q) * RB + lane / PB, piece = (lane % PB) ^ tn_swizzle<BN * 2>(row);
     b_row[q] = row;
     b_src[q] = static_cast<const bf16_t *>(g.W) + (size_t)row * g.ldb + n0 + piece * 8;
   }
@@ -930,10 +945,10 @@ __device__ __forceinline__ void tn_body(const GemmArgs &g, int bid, int split = 
     for (int q = 0; q < ACH; ++q) {
       int r = kb * BK + a_row[q];
       r = r < last_a ? r : last_a;  // past the batch: any finite row, its partner row of W is zero
-      dma16(a_col[q] + (size_t)r * g.lda, base + (wave + 4 * q) * 1024);
+      dma16(a_col[q] + (size_t)r * g.lda, base + (wave + NW * q) * 1024);
     }
 #pragma unroll
-    for (int q = 0; q < BCH; ++q) dma16(b_src[q] + (size_t)kb * BK * g.ldb, base + A_BYTES + (wave + 4 * q) * 1024);
+    for (int q = 0; q < BCH; ++q) dma16(b_src[q] + (size_t)kb * BK * g.ldb, base + A_BYTES + (wave + NW * q) * 1024);
   };
 
   f32x16 acc[TM][TN];
@@ -960,47 +975,85 @@ __device__ __forceinline__ void tn_body(const GemmArgs &g, int bid, int split = 
     b_off[j] = A_BYTES + r0 * (BN * 2) + ((((wn * TN + j) * 4 + 2 * mh + ((s16 & 3) >> 1)) ^ tn_swizzle<BN * 2>(r0)) << 4) + (s16 & 1) * 8;
   // rows 4 and 16 further on have the same (r & 3) and the same ((r >> 1) & 1): the permutation term does not change
 
+  // The transposing reads go through inline assembly with hand-placed waits (tr_read8 / lds_wait / tr_landed): issued through
+  // the builtin, the compiler orders every one of them behind the LDS-DMA just requested for the next stage
+  // (s_waitcnt vmcnt(0) in front of the first read), which exposes a full memory latency per stage.
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
   for (int kb = 0; kb < nkb; ++kb) {
     if (kb + STAGES - 2 < nkb) wait_vmcnt<(STAGES - 2) * LPW>();
     else wait_vmcnt<0>();
     bare_barrier();
     if (kb + STAGES - 1 < nkb) issue((kb + STAGES - 1) % STAGES, kb0 + kb + STAGES - 1);
-    const unsigned char *st = smem + (kb % STAGES) * STAGE_BYTES;
-    i16x8 af[2][TM], bf[2][TN];
-    auto tr_load = [&](const unsigned char *p) {
-      return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)p);
-    };
-    auto fetch = [&](int buf, int ks) {
+    const uint32_t st = lds0 + (kb % STAGES) * STAGE_BYTES;
+    i32x2 alo[2][TM], ahi[2][TM], blo[2][TN], bhi[2][TN];
+    auto fetch = [&](auto buf_c, auto ks_c) {
+      constexpr int buf = decltype(buf_c)::value, ks = decltype(ks_c)::value;
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
-        const unsigned char *p = st + a_off[i] + ks * 16 * (BM * 2);
-        const i16x4 lo = tr_load(p), hi = tr_load(p + 4 * (BM * 2));
-        af[buf][i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        alo[buf][i] = tr_read8<ks * 16 * (BM * 2)>(st + a_off[i]);
+        ahi[buf][i] = tr_read8<ks * 16 * (BM * 2) + 4 * (BM * 2)>(st + a_off[i]);
       }
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
-        const unsigned char *p = st + b_off[j] + ks * 16 * (BN * 2);
-        const i16x4 lo = tr_load(p), hi = tr_load(p + 4 * (BN * 2));
-        bf[buf][j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        blo[buf][j] = tr_read8<ks * 16 * (BN * 2)>(st + b_off[j]);
+        bhi[buf][j] = tr_read8<ks * 16 * (BN * 2) + 4 * (BN * 2)>(st + b_off[j]);
       }
     };
-    fetch(0, 0);
-    __builtin_amdgcn_sched_barrier(0);
+    auto mfma = [&](auto buf_c, auto newer_c) {  // newer: reads issued after this buffer's, allowed to stay in flight
+      constexpr int buf = decltype(buf_c)::value;
+      lds_wait<decltype(newer_c)::value>();
+      bf16x8 af[TM], bf[TN];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      if (ks + 1 < KS) fetch((ks + 1) & 1, ks + 1);
-      __builtin_amdgcn_sched_barrier(0);
+      for (int i = 0; i < TM; ++i) { tr_landed(alo[buf][i]); tr_landed(ahi[buf][i]); af[i] = tr_pair(alo[buf][i], ahi[buf][i]); }
+#pragma unroll
+      for (int j = 0; j < TN; ++j) { tr_landed(blo[buf][j]); tr_landed(bhi[buf][j]); bf[j] = tr_pair(blo[buf][j], bhi[buf][j]); }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[ks & 1][i]), __builtin_bit_cast(bf16x8, bf[ks & 1][j]),
-                                                              acc[i][j], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-    }
+        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+    };
+    typedef std::integral_constant<int, 0> I0;
+    typedef std::integral_constant<int, 1> I1;
+    typedef std::integral_constant<int, 2> I2;
+    typedef std::integral_constant<int, 3> I3;
+    typedef std::integral_constant<int, 2 * (TM + TN)> INext;
+    static_assert(KS == 4 && 2 * (TM + TN) <= 15, "k-steps per stage; lgkmcnt range");
+    fetch(I0{}, I0{});
+    fetch(I1{}, I1{});
+    mfma(I0{}, INext{});
+    fetch(I0{}, I2{});
+    mfma(I1{}, INext{});
+    fetch(I1{}, I3{});
+    mfma(I0{}, INext{});
+    mfma(I1{}, I0{});
   }
 
   wait_vmcnt<0>();
+  if constexpr (BM > 128) {
+    static_assert(TM % 2 == 0 && BN % 128 == 0, "slab epilogue");
+#pragma unroll
+    for (int p = 0; p < BM / 64; ++p) {
+      constexpr int ROWS_PER_WAVE = 32 * TM;
+      const int owner = (p * 64) / ROWS_PER_WAVE, i0 = ((p * 64) % ROWS_PER_WAVE) / 32;
+      __syncthreads();  // the ring, or the previous slab, is no longer being read
+      if (wm == owner) {
+#pragma unroll
+        for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+              const int row = ii * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+              const int col = (wn * TN + j) * 32 + (lane & 31);
+              Cs[row * LDC + col] = acc[i0 + ii][j][e];
+            }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int h = 0; h < BN / 128; ++h)
+        epilogue<EPI_GRAD, AT, 64, 128, LDC, NW * 64>(g, Cs + h * 128, m0 + p * 64, n0 + h * 128, nt * (BN / 128) + h, tid, split);
+    }
+  } else {
   __syncthreads();
 #pragma unroll
   for (int i = 0; i < TM; ++i)
@@ -1014,10 +1067,24 @@ __device__ __forceinline__ void tn_body(const GemmArgs &g, int bid, int split = 
       }
   __syncthreads();
   epilogue<EPI_GRAD, AT, BM, BN>(g, Cs, m0, n0, nt, tid, split);
+  }
 }
 template <int BM, int BN, int STAGES>
 __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmArgs g) {
   tn_body<BM, BN, STAGES>(g, (int)blockIdx.x);
+}
+// 256 x 256 tiles on eight wavefronts, one workgroup per compute unit; blockIdx.y is the range of the batch.
+// Workgroups go to the eight XCDs round-robin and each XCD has its own L2: an XCD takes whole units of eight workgroups,
+// a unit being a block of 2 x 4 tiles of one range of the batch (2 + 4 operand panels for 8 tiles; one row or column of
+// tiles would need 1 + 8).
+__global__ __launch_bounds__(512, 1) void gemm_tn2_kernel(GemmArgs g, int nsplit) {
+  const int ntm = g.M / 256, ntn = g.N / 256, tiles = ntm * ntn, bid = (int)blockIdx.x;
+  if (ntm % 2 == 0 && ntn % 4 == 0 && (tiles / 8 * nsplit) % 8 == 0) {
+    const int x = bid & 7, r = bid >> 3, u = x + 8 * (r >> 3), w = r & 7, U = tiles / 8, b = u % U, split = u / U;
+    tn_body<256, 256, 2, 8>(g, 0, split, nsplit, (b / (ntn / 4)) * 2 + (w >> 2), (b % (ntn / 4)) * 4 + (w & 3));
+  } else {
+    tn_body<256, 256, 2, 8>(g, bid % tiles, bid / tiles, nsplit);
+  }
 }
 
 // Several independent products in ONE launch (a block-uniform switch picks the problem and its kernel body): the products
@@ -1293,6 +1360,21 @@ hipError_t launch_tn(const GemmArgs &g, hipStream_t s) {
   return hipGetLastError();
 }
 
+hipError_t launch_tn2(const GemmArgs &g, hipStream_t s) {
+  constexpr size_t lds = (size_t)2 * 64 * (256 + 256) * 2;
+  static_assert(lds >= (size_t)64 * 260 * sizeof(float) && lds <= 160 * 1024, "LDS per compute unit");
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_tn2_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const int splits = g.splits > 1 ? g.splits : 1;
+  if (g.M % 256 || g.N % 256 || g.K <= 0 || g.K % (splits * 64) || g.a_rows <= 0 || g.a_rows > g.K || g.lda % 8 || g.ldb % 8) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(gemm_tn2_kernel, dim3((g.M / 256) * (g.N / 256) * splits), dim3(512), lds, s, g, splits);
+  return hipGetLastError();
+}
+
 template <int BM, int BN, int STAGES, int EPI, int NW, int WPU>
 hipError_t launch_pipe2(const GemmArgs &g, hipStream_t s) {
   constexpr size_t lds_ring = (size_t)STAGES * (BM * 64 + (BN / 32) * 2 * 1024);
@@ -1392,6 +1474,11 @@ static bool tn_shape(int M, int N, int &kind, int &bm, int &bn) {
   }
   if (N % 64 == 0) { kind = GK_TN_64x64; bm = 64; bn = 64; return true; }
   return false;
+}
+// A weight gradient that gets the 256 x 256 tiles of gemm_tn2_kernel, as a launch of its own: large batches, 16 tiles or
+// more (fewer would need ranges of the batch shorter than the pipeline is worth).
+bool fade_gemm_tn2_ok(int M, int N, int K) {
+  return M > 0 && M % 256 == 0 && N % 256 == 0 && K >= 8192 && (M / 256) * (N / 256) >= 16 && fade_gemm_tune() != 26;
 }
 int fade_gemm_tn_tiles(int M, int N) {
   int kind, bm, bn;
@@ -1494,6 +1581,7 @@ hipError_t fade_gemm(int op, bool bf16, const GemmArgs &g, hipStream_t s) {
         if (g.N % 128 == 0) return launch_pipe<64, 128, 4, EPI_GRAD, true>(g, s);
         return launch_pipe<64, 64, 4, EPI_GRAD, true>(g, s);
       case GEMM_W_TN:     // the same from row-major operands (no copies): A = L [a_rows][lda], W = R [K][ldb]
+        if (fade_gemm_tn2_ok(g.M, g.N, g.K)) return launch_tn2(g, s);
         if (g.N % 128 == 0) {
           if (fade_gemm_tune() == 7 && g.M % 128 == 0) return launch_tn<128, 128, 4>(g, s);
           return launch_tn<64, 128, 4>(g, s);

@@ -14,6 +14,7 @@ enum {
 // Launch one of the model step's products (see fade_gemm.hip). bf16 selects the MFMA path (activations
 // bf16, W in fragment order) or the fp32 path (activations fp32, W plain [K][N]).
 hipError_t fade_gemm(int op, bool bf16, const GemmArgs &g, hipStream_t s);
+bool fade_gemm_tn2_ok(int M, int N, int K);  // dW[M][N] over a batch of K rows runs on 256 x 256 tiles as a launch of its own
 int fade_gemm_tn_tiles(int M, int N);  // workgroups per batch range of a grouped weight-gradient product dW[M][N]; 0: shape not supported
 hipError_t fade_gemm_group_add(GemmGroup &gg, int op, const GemmArgs &g);
 hipError_t fade_gemm_group_launch(const GemmGroup &gg, hipStream_t s);
