@@ -560,12 +560,17 @@ __device__ __forceinline__ void pipe_body(const GemmArgs &g, int bid, int split,
 
 
   // fragment read offsets inside a stage: row r, k-step ks, half h -> r * 128 + (((2 ks + h) ^ ((r / 2) & 7)) * 16)
-  int a_off[TM], b_off[TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i) a_off[i] = ((wm * TM + i) * 32 + (lane & 31)) * 128;
-#pragma unroll
-  for (int j = 0; j < TN; ++j) b_off[j] = A_BYTES + ((wn * TN + j) * 32 + (lane & 31)) * 128;
+  // as LDS addresses of this lane per k-step (A tile i of the wavefront 4096 bytes = 32 rows further on; W fragment j
+  // KS KiB further on, or 32 rows for a row-major W)
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
   const int a_sw = (lane >> 1) & 7, a_half = lane >> 5;  // tile rows start at multiples of 32, so (r / 2) & 7 == (lane / 2) & 7
+  uint32_t a_ks[KS], b_ks[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    a_ks[ks] = lds0 + (wm * TM * 32 + (lane & 31)) * 128 + (((2 * ks + a_half) ^ a_sw) << 4);
+    b_ks[ks] = BROW ? lds0 + A_BYTES + (wn * TN * 32 + (lane & 31)) * 128 + (((2 * ks + a_half) ^ a_sw) << 4)
+                    : lds0 + A_BYTES + (((wn * TN * KS) * 64 + lane) << 4);
+  }
 
   // EPI_PARTIAL with sum_splits: this workgroup walks all K ranges itself and adds their sums in range order, which is
   // bit for bit what the reducing kernels make of separate partials; otherwise it owns the one range `split`.
@@ -591,31 +596,51 @@ __device__ __forceinline__ void pipe_body(const GemmArgs &g, int bid, int split,
     else wait_vmcnt<0>();
     bare_barrier();  // everyone's part of stage kb is in LDS, and everyone is done reading stage kb-1
     if (kb + STAGES - 1 < nkb) issue((kb + STAGES - 1) % STAGES, kb0 + kb + STAGES - 1);
-    const unsigned char *st = smem + (kb % STAGES) * STAGE_BYTES;
-    // fragments of k-step ks+1 are fetched from LDS while the matrix cores work on k-step ks
+    // fragments of k-step ks+1 are fetched from LDS while the matrix cores work on k-step ks: reads through lds_read16 with
+    // hand-placed waits (the compiler's own wait in front of a group of matrix instructions also covers the reads just issued
+    // for the next group)
+    const uint32_t st = (kb % STAGES) * STAGE_BYTES;
     bf16x8 af[2][TM], bf[2][TN];
-    auto fetch = [&](int buf, int ks) {
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-        af[buf][i] = *reinterpret_cast<const bf16x8 *>(st + a_off[i] + (((2 * ks + a_half) ^ a_sw) << 4));
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-        bf[buf][j] = BROW ? *reinterpret_cast<const bf16x8 *>(st + b_off[j] + (((2 * ks + a_half) ^ a_sw) << 4))
-                          : *reinterpret_cast<const bf16x8 *>(st + A_BYTES + ((((wn * TN + j) * KS + ks) * 64 + lane) << 4));
+    auto fetch = [&](auto buf_c, auto ks_c) {
+      constexpr int buf = decltype(buf_c)::value, ks = decltype(ks_c)::value;
+      static_assert(TM <= 4 && TN <= 4, "tiles per wavefront");
+      const uint32_t sa = a_ks[ks] + st, sb = BROW ? b_ks[ks] + st : b_ks[0] + st;
+      constexpr int BO = BROW ? 0 : ks * 1024, BS = BROW ? 4096 : KS * 1024;
+      af[buf][0] = lds_read16<0>(sa);
+      if constexpr (TM > 1) af[buf][1] = lds_read16<4096>(sa);
+      if constexpr (TM > 2) af[buf][2] = lds_read16<8192>(sa);
+      if constexpr (TM > 3) af[buf][3] = lds_read16<12288>(sa);
+      bf[buf][0] = lds_read16<BO>(sb);
+      if constexpr (TN > 1) bf[buf][1] = lds_read16<BO + BS>(sb);
+      if constexpr (TN > 2) bf[buf][2] = lds_read16<BO + 2 * BS>(sb);
+      if constexpr (TN > 3) bf[buf][3] = lds_read16<BO + 3 * BS>(sb);
     };
-    fetch(0, 0);
-    __builtin_amdgcn_sched_barrier(0);  // keep the scheduler from sinking the reads next to their uses
+    auto mfma = [&](auto buf_c, auto newer_c) {  // newer: reads issued after this buffer's, allowed to stay in flight
+      constexpr int buf = decltype(buf_c)::value;
+      lds_wait<decltype(newer_c)::value>();
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      if (ks + 1 < KS) fetch((ks + 1) & 1, ks + 1);
-      __builtin_amdgcn_sched_barrier(0);
+      for (int i = 0; i < TM; ++i) lds_landed(af[buf][i]);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) lds_landed(bf[buf][j]);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bf[ks & 1][j], acc[i][j], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-    }
+        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bf[buf][j], acc[i][j], 0, 0, 0);
+    };
+    typedef std::integral_constant<int, 0> I0;
+    typedef std::integral_constant<int, 1> I1;
+    typedef std::integral_constant<int, 2> I2;
+    typedef std::integral_constant<int, 3> I3;
+    typedef std::integral_constant<int, TM + TN> INext;
+    static_assert(KS == 4, "k-steps per stage");
+    fetch(I0{}, I0{});
+    fetch(I1{}, I1{});
+    mfma(I0{}, INext{});
+    fetch(I0{}, I2{});
+    mfma(I1{}, INext{});
+    fetch(I1{}, I3{});
+    mfma(I0{}, INext{});
+    mfma(I1{}, I0{});
   }
   if constexpr (EPI == EPI_PARTIAL) {
 #pragma unroll
