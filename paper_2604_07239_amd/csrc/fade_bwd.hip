@@ -4,6 +4,7 @@
 // All reductions run in a fixed order (no atomics): encoder and decoder must reproduce the same weights bit for bit.
 #include "fade_dev.h"
 #include "fade_kernels.h"
+#include <cstdlib>
 
 namespace {
 
@@ -270,10 +271,21 @@ __global__ __launch_bounds__(256) void embed_t_kernel(WinSrc ws, int B, int Bp, 
 // workgroup while the batch is small (more workgroups to hide the two dependent rounds of loads), four for large batches
 // (fewer partial sums to write and add up). B = 1024: the three kernels 15.5 / 20.0 / 26.7 us with four rows, 13.7 / 14.8 /
 // 21.3 with two (one row: 13.3 / 14.4 / 20.1, but 8 us more in the reduction of twice as many partial sums).
-inline int rows_per_block(int B) { return B <= 2048 ? 2 : 4; }
+inline int env_int(const char *name) { const char *e = getenv(name); return e ? atoi(e) : 0; }
+// Rows a workgroup of a row kernel takes through each phase together. Small batches: 2 (few workgroups, latency-bound);
+// up to 4096 rows: 4; large batches: 1, where the lower register count (two more wavefronts per SIMD) is worth more than
+// the shared reductions (B = 16384, with 16 row groups per workgroup: Eq. 10 / Eq. 8 / Eq. 5-6 backward 116 / 178 / 244 us
+// with 4 rows, 95 / 136 / 213 with 1).
+inline int rows_per_block(int B) {
+  static const int r = env_int("FADE_ROWS_R");  // tuning override: 1, 2 or 4
+  return (r == 1 || r == 2 || r == 4) ? r : (B <= 2048 ? 2 : B < 8192 ? 4 : 1);
+}
 // Row groups one workgroup of a row kernel walks through, adding the LayerNorm-gain partials of all of them in registers:
 // at large batches this keeps the first-stage partial buffers (one row of 2 D_h floats per workgroup) small.
-__host__ __device__ inline int row_groups(int B) { return B >= 8192 ? 4 : 1; }
+inline int row_groups(int B) {
+  static const int g = env_int("FADE_ROWS_G");  // tuning override
+  return g > 0 ? g : (B >= 8192 ? 16 : 1);
+}
 
 // Several row sums at once over a 256-thread workgroup (same fixed order as block_sum); red holds 4 * N floats.
 template <int N>
@@ -308,7 +320,7 @@ __global__ __launch_bounds__(256) void bwd_out_kernel(BwdOutArgs a) {
   for (int i = 0; i < 8; ++i) { ga[i] = be[i] = pg[i] = pb[i] = 0.0f; }
   if (mine) { ld8<float>(a.gamma + tid * 8, ga); ld8<float>(a.beta + tid * 8, be); }
   float dh[R][8], xh[R][8], rstd[R], sums[3 * R];
-  const int G = row_groups(a.B);
+  const int G = a.groups;
   for (int rb = blockIdx.x * G; rb < (int)blockIdx.x * G + G; ++rb) {
 #pragma unroll
   for (int r = 0; r < R; ++r) {
@@ -396,7 +408,7 @@ __global__ __launch_bounds__(256) void bwd_gate_kernel(BwdGateArgs a) {
   for (int i = 0; i < 8; ++i) { ga[i] = pg[i] = pb[i] = 0.0f; }
   if (mine) ld8<float>(a.gamma + tid * 8, ga);
   float dh[R][8], xh[R][8], rstd[R], sums[2 * R], sl[R];
-  const int G = row_groups(a.B);
+  const int G = a.groups;
   for (int rb = blockIdx.x * G; rb < (int)blockIdx.x * G + G; ++rb) {
 #pragma unroll
   for (int r = 0; r < R; ++r) {
@@ -494,7 +506,7 @@ __global__ __launch_bounds__(256) void bwd_mix_kernel(BwdMixArgs a) {
   for (int i = 0; i < 8; ++i) { ga[i] = pg[i] = pb[i] = 0.0f; }
   if (mine) ld8<float>(a.gamma + tid * 8, ga);
   float dh[R][8], xh[R][8], rstd[R], sums[2 * R], sl[R];
-  const int G = row_groups(a.B);
+  const int G = a.groups;
   for (int rb = blockIdx.x * G; rb < (int)blockIdx.x * G + G; ++rb) {
 #pragma unroll
   for (int r = 0; r < R; ++r) {
@@ -1338,15 +1350,17 @@ hipError_t fade_embed_t(const WinSrc &ws, int B, int Bp, int T, int D, const voi
 #define DISPATCH_ROWS(bf16, KERNEL, B, stream, args)                                                                             \
   do {                                                                                                                            \
     const int R_ = rows_per_block(B), RG_ = R_ * row_groups(B);                                                                   \
+    auto args_ = args;                                                                                                            \
+    args_.groups = row_groups(B);                                                                                                 \
     const dim3 grid_((B + RG_ - 1) / RG_);                                                                                        \
     if (bf16) {                                                                                                                   \
-      if (R_ == 1) hipLaunchKernelGGL((KERNEL<bf16_t, 1>), grid_, dim3(256), 0, stream, args);                                    \
-      else if (R_ == 2) hipLaunchKernelGGL((KERNEL<bf16_t, 2>), grid_, dim3(256), 0, stream, args);                               \
-      else hipLaunchKernelGGL((KERNEL<bf16_t, 4>), grid_, dim3(256), 0, stream, args);                                            \
+      if (R_ == 1) hipLaunchKernelGGL((KERNEL<bf16_t, 1>), grid_, dim3(256), 0, stream, args_);                                    \
+      else if (R_ == 2) hipLaunchKernelGGL((KERNEL<bf16_t, 2>), grid_, dim3(256), 0, stream, args_);                               \
+      else hipLaunchKernelGGL((KERNEL<bf16_t, 4>), grid_, dim3(256), 0, stream, args_);                                            \
     } else {                                                                                                                      \
-      if (R_ == 1) hipLaunchKernelGGL((KERNEL<float, 1>), grid_, dim3(256), 0, stream, args);                                     \
-      else if (R_ == 2) hipLaunchKernelGGL((KERNEL<float, 2>), grid_, dim3(256), 0, stream, args);                                \
-      else hipLaunchKernelGGL((KERNEL<float, 4>), grid_, dim3(256), 0, stream, args);                                             \
+      if (R_ == 1) hipLaunchKernelGGL((KERNEL<float, 1>), grid_, dim3(256), 0, stream, args_);                                     \
+      else if (R_ == 2) hipLaunchKernelGGL((KERNEL<float, 2>), grid_, dim3(256), 0, stream, args_);                                \
+      else hipLaunchKernelGGL((KERNEL<float, 4>), grid_, dim3(256), 0, stream, args_);                                             \
     }                                                                                                                             \
     return hipGetLastError();                                                                                                     \
   } while (0)

@@ -186,6 +186,7 @@ struct TransposeBatch {
 };
 struct BwdOutArgs {
   int B, Dh, stats_n;
+  int groups;  // row groups per workgroup (set by the launcher)
   float *ln_part;  // [blocks][2][Dh] partial sums of d gamma, d beta over this workgroup's rows
   const void *dH, *V, *Hc;
   const float *stats, *gamma, *beta, *lam;
@@ -194,6 +195,7 @@ struct BwdOutArgs {
 };
 struct BwdGateArgs {
   int B, Dh, stats_n;
+  int groups;  // row groups per workgroup (set by the launcher)
   float *ln_part;
   const void *du, *Hc, *dHc, *sg, *Ha, *Hmix;
   const float *stats, *gamma, *lam;
@@ -204,6 +206,7 @@ struct BwdGateArgs {
 };
 struct BwdMixArgs {
   int B, Dh, stats_n;
+  int groups;  // row groups per workgroup (set by the launcher)
   float *ln_part;
   const void *dnc, *Hmix, *dHmix1, *dHmix2, *alpha, *Hg, *Hl, *hm, *cv, *X;
   const float *stats, *gamma, *lam;
