@@ -1213,9 +1213,13 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g) {
 // fp32 products of very small batches (the 16-stream configuration): 16 rows x 16 columns per workgroup, the whole
 // contraction inside it. With 16 rows a 128-column tile leaves four workgroups on a 256-unit chip walking K in lock step
 // (50 us for a 16 x 512 x 512 product); here N / 16 workgroups each keep the 16 operand rows in LDS (prologue applied
-// once) and split K sixteen ways across lanes: thread (r, q) adds row r's terms k = q, q + 16, ... for the tile's 16
-// columns, reading W's 64-byte row pieces straight from L2, and a fixed butterfly over q finishes the sums. The weights
-// (4 MB for that configuration) stay L2-resident across steps, so a step streams them once from L2.
+// once) and split K 64 ways: thread (q, cg) owns the terms k = q, q + 64, ... of all 16 rows for 4 of the tile's columns,
+// so every weight element is loaded once per workgroup (a lane's row pieces are requested up front, before the operand
+// rows are staged: one round trip for K <= 512), the operand values come from LDS (a wavefront reads 16 consecutive k of
+// one row: conflict-free, each value broadcast to the 4 column groups). The 64 K slices are added in a fixed tree: inside
+// a wavefront a butterfly over the slice bits of the lane index that halves the rows a lane keeps at every level (lane
+// bit 5 decides rows 0-7 / 8-15, bit 4 the half of those, ...: 32 + 16 + 8 + 4 exchanges instead of 4 x 64), then the four
+// wavefronts' sums in wavefront order through LDS. A step streams the weights (4 MB for that configuration) once.
 // GeGLU tiles take 8 gate and the matching 8 value columns of a 128-column group (columns c and c + 64).
 // Row statistics are left per 16-column tile: consumers must be told stats_n = N / 16.
 // ---------------------------------------------------------------------------------------------------
@@ -1225,12 +1229,26 @@ __global__ __launch_bounds__(256) void gemm_f32_rows_kernel(GemmArgs g) {
   constexpr int BM = 16, BN = 16, LDC = BN + 4;
   constexpr bool kGeglu = EPI == EPI_GEGLU;
   extern __shared__ __align__(16) unsigned char smem[];
-  const int LDA = g.K + 16;  // rows 16 banks apart: the four rows a wavefront reads at one k do not collide
+  const int LDA = g.K + 16;  // rows 16 banks apart
   float *As = reinterpret_cast<float *>(smem);   // [16][LDA]
   float *Cs = As + BM * LDA;                     // [16][LDC]
   float *mom = Cs + BM * LDC;                    // [16][2]
+  float *red = mom + 2 * BM;                     // [4 wavefronts][16][16]
   const int tid = threadIdx.x, nt = blockIdx.x, m0 = blockIdx.y * BM;
   const int n0 = kGeglu ? (nt / 8) * 128 + (nt % 8) * 8 : nt * BN;   // first (gate) column of the tile in W
+  const int q = tid >> 2, cg = tid & 3, lane = tid & 63, wave = tid >> 6;
+  // this thread's 4 columns of W: gate columns 0-7 then value columns 64-71 for a GeGLU tile
+  const float *W = static_cast<const float *>(g.W) + n0 + (kGeglu ? (cg >> 1) * 64 + (cg & 1) * 4 : cg * 4);
+  constexpr int U = 8;  // k values of a lane per batch (K <= 512: all of them)
+  f32x4 w[U];
+  auto load_w = [&](int k0) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int k = k0 + 64 * u;
+      w[u] = *reinterpret_cast<const f32x4 *>(W + (size_t)(k < g.K ? k : 0) * g.N);  // past K: any row, its term is dropped
+    }
+  };
+  load_w(q);
   float lam = 0.0f;
   if (PRO == PRO_FINAL) lam = g.lam[0];
   if (PRO == PRO_LN || PRO == PRO_FINAL) {
@@ -1252,45 +1270,73 @@ __global__ __launch_bounds__(256) void gemm_f32_rows_kernel(GemmArgs g) {
     store8(As + row * LDA + kc, v);
   }
   __syncthreads();
-  const int r = tid >> 4, q = tid & 15;
-  const float *W = static_cast<const float *>(g.W) + n0;
-  const float *Ar = As + r * LDA;
-  float acc[16];
+  float acc[16][4];
 #pragma unroll
-  for (int j = 0; j < 16; ++j) acc[j] = 0.0f;
-  // eight of a lane's k values at a time: their 32 row pieces of W are requested together (one L2 latency per batch,
-  // not per k); rows past K are clamped and their terms dropped
-  for (int k0 = q; k0 < g.K; k0 += 128) {
-    f32x4 w[8][4];
-    float av[8];
+  for (int r = 0; r < 16; ++r)
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const int k = k0 + 16 * u, kk = k < g.K ? k : q;
-      const float *wr = W + (size_t)kk * g.N;
-      w[u][0] = *reinterpret_cast<const f32x4 *>(wr); w[u][1] = *reinterpret_cast<const f32x4 *>(wr + 4);
-      w[u][2] = *reinterpret_cast<const f32x4 *>(wr + (kGeglu ? 64 : 8)); w[u][3] = *reinterpret_cast<const f32x4 *>(wr + (kGeglu ? 68 : 12));
-      av[u] = k < g.K ? Ar[kk] : 0.0f;
-    }
+    for (int j = 0; j < 4; ++j) acc[r][j] = 0.0f;
+  for (int k0 = q; k0 < g.K; k0 += 64 * U) {
+    if (k0 != q) load_w(k0);
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      if (k0 + 16 * u < g.K) {  // in k order, so that the sum does not depend on the batching
+    for (int u = 0; u < U; ++u) {  // in k order
+      const int k = k0 + 64 * u;
+      if (k < g.K) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          acc[i] = fmaf(av[u], w[u][0][i], acc[i]); acc[4 + i] = fmaf(av[u], w[u][1][i], acc[4 + i]);
-          acc[8 + i] = fmaf(av[u], w[u][2][i], acc[8 + i]); acc[12 + i] = fmaf(av[u], w[u][3][i], acc[12 + i]);
+        for (int r = 0; r < 16; ++r) {
+          const float a = As[r * LDA + k];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc[r][j] = fmaf(a, w[u][j], acc[r][j]);
         }
       }
     }
   }
-  // the sixteen K slices of a row sit in sixteen neighbouring lanes: fixed butterfly, then lane q keeps column q
-  float mine = 0.0f;
+  // butterfly over the 16 K slices of a wavefront (lane bits 2-5), keeping half of the rows at every level
+  float h8[8][4], h4[4][4], h2[2][4], h1[4];
+  {
+    const bool up = lane & 32;
 #pragma unroll
-  for (int j = 0; j < 16; ++j) {
-    float t = acc[j];
-    t += __shfl_xor(t, 1, 64); t += __shfl_xor(t, 2, 64); t += __shfl_xor(t, 4, 64); t += __shfl_xor(t, 8, 64);
-    if (q == j) mine = t;
+    for (int r = 0; r < 8; ++r)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float keep = up ? acc[8 + r][j] : acc[r][j], send = up ? acc[r][j] : acc[8 + r][j];
+        h8[r][j] = keep + __shfl_xor(send, 32, 64);
+      }
   }
-  Cs[r * LDC + q] = mine;
+  {
+    const bool up = lane & 16;
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float keep = up ? h8[4 + r][j] : h8[r][j], send = up ? h8[r][j] : h8[4 + r][j];
+        h4[r][j] = keep + __shfl_xor(send, 16, 64);
+      }
+  }
+  {
+    const bool up = lane & 8;
+#pragma unroll
+    for (int r = 0; r < 2; ++r)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float keep = up ? h4[2 + r][j] : h4[r][j], send = up ? h4[r][j] : h4[2 + r][j];
+        h2[r][j] = keep + __shfl_xor(send, 8, 64);
+      }
+  }
+  {
+    const bool up = lane & 4;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float keep = up ? h2[1][j] : h2[0][j], send = up ? h2[0][j] : h2[1][j];
+      h1[j] = keep + __shfl_xor(send, 4, 64);
+    }
+  }
+  {  // the lane now holds row (bits 5, 4, 3, 2 of the lane index), its 4 columns, summed over the wavefront's 16 slices
+    const int row = ((lane >> 5) & 1) * 8 + ((lane >> 4) & 1) * 4 + ((lane >> 3) & 1) * 2 + ((lane >> 2) & 1);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) red[(wave * 16 + row) * 16 + cg * 4 + j] = h1[j];
+  }
+  __syncthreads();
+  Cs[(tid >> 4) * LDC + (tid & 15)] = (red[tid] + red[256 + tid]) + (red[512 + tid] + red[768 + tid]);
   __syncthreads();
   epilogue<EPI, AT, BM, BN>(g, Cs, m0, kGeglu ? 0 : n0, nt, tid);
 }
@@ -1299,7 +1345,7 @@ template <int PRO, int EPI>
 hipError_t launch_f32_rows(const GemmArgs &g, hipStream_t s) {
   constexpr bool kGeglu = EPI == EPI_GEGLU;
   if (g.M <= 0 || g.K % 16 || g.K > 2048 || g.N % (kGeglu ? 128 : 16) || g.wt) return hipErrorInvalidValue;
-  const size_t lds = ((size_t)16 * (g.K + 16) + 16 * 20 + 32) * sizeof(float);
+  const size_t lds = ((size_t)16 * (g.K + 16) + 16 * 20 + 32 + 4 * 256) * sizeof(float);
   static size_t attr = 0;
   auto kern = gemm_f32_rows_kernel<PRO, EPI>;
   if (lds > attr) {
