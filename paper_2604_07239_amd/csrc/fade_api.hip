@@ -686,7 +686,7 @@ GemmArgs args_x(fade_ctx *c, const void *dY, int Kred, int Nout, const void *wt_
   GemmArgs g{};
   g.M = (int)c->d.B; g.N = Nout; g.K = Kred; g.A = dY; g.lda = Kred; g.C = out; g.ldc = Nout;
   if (c->bf16) g.W = wt_frag;
-  else { g.W = w_f32; g.wt = 1; g.ldb = ld_w; }
+  else { g.W = w_f32; g.wt = 1; g.ldb = ld_w; g.rows16 = c->rows16 && Kred % 16 == 0 && Kred <= 2048 && Nout % 16 == 0; }
   return g;
 }
 // dW[Kw][N] = L^T R over the batch. bf16 path: both operands row-major as the forward / backward kernels left them
@@ -855,7 +855,7 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     GemmArgs g{};
     g.M = B; g.N = dl; g.K = Dh; g.splits = c->sp_dz; g.A = c->dHa; g.lda = Dh; g.C = c->dz_part; g.ldc = dl;
     if (bf) g.W = c->WT_up;
-    else { g.W = c->P(P_WUP); g.wt = 1; g.ldb = Dh; }
+    else { g.W = c->P(P_WUP); g.wt = 1; g.ldb = Dh; g.rows16 = c->rows16 && c->sp_dz <= 1 && dl % 16 == 0; }
     ph.add(GEMM_PARTIAL, g);
     if ((rc = run_phase(c, "gemms_gate_up", ph))) return rc;
   }

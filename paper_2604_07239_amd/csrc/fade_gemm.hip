@@ -1241,11 +1241,19 @@ __global__ __launch_bounds__(256) void gemm_f32_rows_kernel(GemmArgs g) {
   const float *W = static_cast<const float *>(g.W) + n0 + (kGeglu ? (cg >> 1) * 64 + (cg & 1) * 4 : cg * 4);
   constexpr int U = 8;  // k values of a lane per batch (K <= 512: all of them)
   f32x4 w[U];
+  // W given transposed ([N][ldb], K contiguous: the activation gradients of the update): the 16 slices of a wavefront
+  // read 64 contiguous bytes of each of the tile's columns
+  const float *Wt = static_cast<const float *>(g.W) + (size_t)(n0 + cg * 4) * g.ldb;
   auto load_w = [&](int k0) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int k = k0 + 64 * u;
-      w[u] = *reinterpret_cast<const f32x4 *>(W + (size_t)(k < g.K ? k : 0) * g.N);  // past K: any row, its term is dropped
+      const int k = k0 + 64 * u, kk = k < g.K ? k : 0;  // past K: any row, its term is dropped
+      if (g.wt) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) w[u][j] = Wt[(size_t)j * g.ldb + kk];
+      } else {
+        w[u] = *reinterpret_cast<const f32x4 *>(W + (size_t)kk * g.N);
+      }
     }
   };
   load_w(q);
@@ -1344,7 +1352,7 @@ __global__ __launch_bounds__(256) void gemm_f32_rows_kernel(GemmArgs g) {
 template <int PRO, int EPI>
 hipError_t launch_f32_rows(const GemmArgs &g, hipStream_t s) {
   constexpr bool kGeglu = EPI == EPI_GEGLU;
-  if (g.M <= 0 || g.K % 16 || g.K > 2048 || g.N % (kGeglu ? 128 : 16) || g.wt) return hipErrorInvalidValue;
+  if (g.M <= 0 || g.K % 16 || g.K > 2048 || g.N % (kGeglu ? 128 : 16) || (g.wt && (kGeglu || g.ldb < g.K))) return hipErrorInvalidValue;
   const size_t lds = ((size_t)16 * (g.K + 16) + 16 * 20 + 32 + 4 * 256) * sizeof(float);
   static size_t attr = 0;
   auto kern = gemm_f32_rows_kernel<PRO, EPI>;
@@ -1677,6 +1685,10 @@ hipError_t fade_gemm(int op, bool bf16, const GemmArgs &g, hipStream_t s) {
       case GEMM_FNR_IN:   return launch_f32_rows<PRO_LN, EPI_GEGLU>(g, s);
       case GEMM_FNR_OUT:  return launch_f32_rows<PRO_PLAIN, EPI_STORE>(g, s);
       case GEMM_HEAD:     return launch_f32_rows<PRO_FINAL, EPI_STORE_F32>(g, s);
+      case GEMM_X_STORE:  return launch_f32_rows<PRO_PLAIN, EPI_STORE>(g, s);  // W passed transposed (wt = 1)
+      case GEMM_PARTIAL:  // one range only: a plain fp32 store
+        if (g.splits > 1 || g.sum_splits) return hipErrorInvalidValue;
+        return launch_f32_rows<PRO_PLAIN, EPI_PARTIAL>(g, s);
       default: return hipErrorInvalidValue;
     }
   }
