@@ -273,18 +273,18 @@ __global__ __launch_bounds__(256) void embed_t_kernel(WinSrc ws, int B, int Bp, 
 // 21.3 with two (one row: 13.3 / 14.4 / 20.1, but 8 us more in the reduction of twice as many partial sums).
 inline int env_int(const char *name) { const char *e = getenv(name); return e ? atoi(e) : 0; }
 // Rows a workgroup of a row kernel takes through each phase together. Small batches: 2 (few workgroups, latency-bound);
-// up to 4096 rows: 4; large batches: 1, where the lower register count (two more wavefronts per SIMD) is worth more than
+// below 4096 rows: 4; from 4096 on: 1, where the lower register count (two more wavefronts per SIMD) is worth more than
 // the shared reductions (B = 16384, with 16 row groups per workgroup: Eq. 10 / Eq. 8 / Eq. 5-6 backward 116 / 178 / 244 us
-// with 4 rows, 95 / 136 / 213 with 1).
+// with 4 rows, 95 / 136 / 213 with 1; B = 4096, 4 groups of 1 row against 1 group of 4: 26 / 44 / 78 against 30 / 47 / 82).
 inline int rows_per_block(int B) {
   static const int r = env_int("FADE_ROWS_R");  // tuning override: 1, 2 or 4
-  return (r == 1 || r == 2 || r == 4) ? r : (B <= 2048 ? 2 : B < 8192 ? 4 : 1);
+  return (r == 1 || r == 2 || r == 4) ? r : (B <= 2048 ? 2 : B < 4096 ? 4 : 1);
 }
 // Row groups one workgroup of a row kernel walks through, adding the LayerNorm-gain partials of all of them in registers:
 // at large batches this keeps the first-stage partial buffers (one row of 2 D_h floats per workgroup) small.
 inline int row_groups(int B) {
   static const int g = env_int("FADE_ROWS_G");  // tuning override
-  return g > 0 ? g : (B >= 8192 ? 16 : 1);
+  return g > 0 ? g : (B >= 8192 ? 16 : B >= 4096 ? 4 : 1);
 }
 
 // Several row sums at once over a 256-thread workgroup (same fixed order as block_sum); red holds 4 * N floats.
