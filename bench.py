@@ -43,10 +43,10 @@ ROUTER_GATE_TRAFFIC_BYTES = {
     (1024, 2048, "online"): int(0.5 * (56.4 + 53.5) * MiB),                    # profiles/cfg2_online_kernel_trace_and_hbm.md
 }
 # the same for the fp32 small-batch product (gemm_f32_rows_kernel) by (B, D_h, mode): profiles/cfg1_kernel_trace_and_hbm.md
-F32_ROUTER_GATE_TRAFFIC_BYTES = {}
+F32_ROUTER_GATE_TRAFFIC_BYTES = {(16, 512, "frozen"): int(0.5 * (2.46 + 0.05 + 2.40 + 0.05) * MiB), (16, 512, "online"): int(0.5 * (2.46 + 0.08 + 2.40 + 0.08) * MiB)}
 # adam_refresh_kernel by (parameters of the nine big matrices, mode), same counter runs
 ADAM_TRAFFIC_BYTES = {(11272192, "online"): int((171.59 + 167.46) * MiB),      # profiles/cfg2_online_kernel_trace_and_hbm.md
-                      (13369344, "online"): int((269.41 + 253.27) * MiB)}      # profiles/cfg5_online_kernel_trace_and_hbm.md
+                      (13369344, "online"): int((493.64 + 253.27) * MiB)}      # profiles/cfg5_online_kernel_trace_and_hbm.md
 
 
 def parse():
