@@ -1,20 +1,26 @@
 // fade_gemm.hip — the dense products of the model step with fused prologues and epilogues (gfx950).
 //
-// bf16 path: C[M][N] = A'[M][K] * W[K][N] on the matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulate).
-//   * 256 threads = 4 wavefronts arranged WM x WN; each wavefront owns TM x TN tiles of 32 x 32.
-//   * A' is formed on the fly (LayerNorm, the Eq. 10 tail, the causal-conv row gather), converted to bf16 and
-//     staged through LDS in blocks of 64 along K, double buffered.
-//   * W never touches LDS: at load time it is rearranged into MFMA fragment order (one contiguous 1 KiB
-//     read per wavefront and 32 x 16 fragment), so each wavefront streams its own columns straight from
-//     L2 into registers, one K block ahead.
-//   * The accumulators are parked in LDS (fp32) and re-read row-wise, so that every side input and every
-//     output moves in 16-byte pieces and per-row statistics for the next LayerNorm fall out of a 16-lane
-//     butterfly. Partial statistics are stored per 128-column tile and summed by the consumer in index
-//     order: no atomics, so the result is reproducible bit for bit.
-//   * blockIdx -> tile: the chip dispatches consecutive workgroups round-robin over its 8 XCDs, each with
-//     a private L2. Tiles are numbered so that one XCD owns a contiguous range of column tiles for all
-//     row tiles: each XCD then pulls only its 1/8 of W through its L2.
-// fp32 path (small-batch configuration): same prologues/epilogues around a plain FMA core.
+// bf16 path: C[M][N] = A[M][K] * W[K][N] on the matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulate).
+//   * Both operands stream global -> LDS by LDS-DMA (global_load_lds_dwordx4) through a ring of stages synchronised by
+//     hand (s_waitcnt vmcnt + a bare s_barrier); A is row-major with its 16-byte pieces XOR-permuted in LDS, W was
+//     rearranged at load time into MFMA fragment order (1 KiB per 32 columns x 16 k, contiguous along K).
+//     pipe_body: 4 wavefronts, tiles of 64 / 128 rows x 64 / 128 columns, stages of 64 along K (small and medium batches,
+//     grouped launches, split-K partials). pipe2_body: 8 wavefronts on a 256 x 256 tile, ring of four 32-wide stages with
+//     the stage hand-over between the two k-steps of a stage (large batches). Fragment reads go through inline assembly
+//     with hand-placed lgkmcnt waits, so that the next k-step's reads stay in flight under the matrix instructions.
+//   * gemm_bf16_kernel forms A on the fly instead (the causal-conv row gather; Eq. 10's tail for the head product) and
+//     stages it through LDS from registers; its W fragments go straight from L2 into registers.
+//   * Weight gradients dW = L^T R contract over the batch: tn_body stages both row-major operands as they lie in memory
+//     and turns them on the way out of LDS with the transposing read (ds_read_b64_tr_b16); 4 wavefronts on up to
+//     128 x 128 inside grouped launches, 8 wavefronts on 256 x 256 as a launch of its own at large batches.
+//   * The accumulators are parked in LDS (fp32; 64-row slabs for the 256-row tiles) and re-read row-wise, so that every
+//     side input and every output moves in 16-byte pieces and per-row statistics for the next LayerNorm fall out of a
+//     16-lane butterfly. Partial statistics are stored per 128-column tile and summed by the consumer in index order: no
+//     atomics, so the result is reproducible bit for bit, and the same for every tile shape.
+//   * blockIdx -> tile: the chip dispatches consecutive workgroups round-robin over its 8 XCDs, each with a private L2;
+//     tile_of_block gives an XCD a range of column tiles (its share of W stays in its L2) and walks its tiles row by row.
+// fp32 path: the same prologues / epilogues around a plain FMA core (gemm_f32_kernel), and 16 x 16 tiles with the
+// contraction split over the workgroup's threads for batches of up to 256 rows (gemm_f32_rows_kernel).
 #include <cstdlib>
 #include <type_traits>
 
