@@ -130,11 +130,21 @@ def main():
         dst_dev = torch.zeros(n, dtype=torch.uint8, device="cuda")
         torch.cuda.synchronize()
 
+        def pieces(call):
+            """the whole job in pieces of about 20 s, with a progress line after each (a long silent run reads as hung)"""
+            per = max(1, L // 16)
+            torch.cuda.synchronize(); t0 = time.perf_counter()
+            done = 0
+            while done < L:
+                cnt = min(per, L - done)
+                call(done, cnt)
+                done += cnt
+                print(f"[bench] {mode}: {done}/{L} steps, {time.perf_counter() - t0:.1f} s", file=sys.stderr, flush=True)
+            torch.cuda.synchronize(); return time.perf_counter() - t0
+
         def timed_encode():
             if a.full:
-                torch.cuda.synchronize(); t0 = time.perf_counter()
-                g.encode_device(src_dev, n, 0, 0)
-                torch.cuda.synchronize(); return time.perf_counter() - t0
+                return pieces(lambda first, cnt: g.encode_device(src_dev, n, first, cnt))
             g.encode_device(src_dev, n, 0, first)          # uniform warm-up symbols + W untimed model steps
             torch.cuda.synchronize(); t0 = time.perf_counter()
             g.encode_device(src_dev, n, first, count)      # exactly K timed steps (and the termination of each stream)
@@ -142,9 +152,7 @@ def main():
 
         def timed_decode(lens, data):
             if a.full:
-                torch.cuda.synchronize(); t0 = time.perf_counter()
-                g.decode_device(lens, data, dst_dev, n, 0, 0)
-                torch.cuda.synchronize(); return time.perf_counter() - t0
+                return pieces(lambda first, cnt: g.decode_device(lens, data, dst_dev, n, first, cnt))
             g.decode_device(lens, data, dst_dev, n, 0, first)
             torch.cuda.synchronize(); t0 = time.perf_counter()
             g.decode_device(None, None, dst_dev, n, first, count)
