@@ -996,11 +996,12 @@ __global__ __launch_bounds__(256) void conv_grad_mfma_kernel(ConvGradArgs a) {
   conv_grad_mfma_body(a, (int)blockIdx.x, (int)gridDim.x);
 }
 // The newest-slot backward and the conv backward both start from what the mix backward left and feed the embedding
-// backward: independent, so one launch carries both (the first pslot workgroups take the slot part).
+// backward: independent, so one launch carries both. The first pconv workgroups take the conv part: each of them walks
+// many 128-token chunks, so they start first and the short slot workgroups fill in around them.
 template <int SPW, int KCH>
-__global__ __launch_bounds__(256) void slot_conv_kernel(BwdSlotArgs sa, ConvGradArgs ca, int pslot) {
-  if ((int)blockIdx.x < pslot) bwd_slot_body<bf16_t, SPW, KCH>(sa, (int)blockIdx.x);
-  else conv_grad_mfma_body(ca, (int)blockIdx.x - pslot, (int)gridDim.x - pslot);
+__global__ __launch_bounds__(256) void slot_conv_kernel(BwdSlotArgs sa, ConvGradArgs ca, int pconv) {
+  if ((int)blockIdx.x < pconv) conv_grad_mfma_body(ca, (int)blockIdx.x, pconv);
+  else bwd_slot_body<bf16_t, SPW, KCH>(sa, (int)blockIdx.x - pconv);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -1406,8 +1407,8 @@ hipError_t fade_bwd_slot_conv(const BwdSlotArgs &sa, float *dWgv, const ConvGrad
   const int Ps = narrow ? (sa.B + 15) / 16 : (sa.B + 3) / 4;
   const long long nchunks = ((long long)ca.B * ca.T + 127) / 128;
   const int Pc = (int)(nchunks < 512 ? nchunks : 512);
-  if (narrow) hipLaunchKernelGGL((slot_conv_kernel<4, 1>), dim3(Ps + Pc), dim3(256), 0, s, sa, ca, Ps);
-  else hipLaunchKernelGGL((slot_conv_kernel<1, 4>), dim3(Ps + Pc), dim3(256), 0, s, sa, ca, Ps);
+  if (narrow) hipLaunchKernelGGL((slot_conv_kernel<4, 1>), dim3(Ps + Pc), dim3(256), 0, s, sa, ca, Pc);
+  else hipLaunchKernelGGL((slot_conv_kernel<1, 4>), dim3(Ps + Pc), dim3(256), 0, s, sa, ca, Pc);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (!rb.push(Ps, 2 * sa.D * sa.c, sa.part, dWgv) || !rb.push(Pc, (ca.taps * ca.D + 1) * ca.D, ca.part, dWb)) return hipErrorInvalidValue;
