@@ -852,8 +852,9 @@ __device__ __forceinline__ void pipe2_body(const GemmArgs &g, int bid, int split
         for (int h = 0; h < BN / 128; ++h)
 #pragma unroll
           for (int u = 0; u < SP; ++u) {
-            const int m = m0 + p * 64 + u * (NT / 16) + tid / 16;
-            epi_side_load<EPI, AT>(g, (size_t)m * g.ldc + n0 + h * 128 + (tid % 16) * 8, m < g.M, sd[buf][h][u]);
+            int m = m0 + p * 64 + u * (NT / 16) + tid / 16;
+            m = m < g.M ? m : g.M - 1;  // past the last row: any row (the epilogue drops it); no branch around the loads
+            epi_side_load<EPI, AT>(g, (size_t)m * g.ldc + n0 + h * 128 + (tid % 16) * 8, true, sd[buf][h][u]);
           }
       }
     };
