@@ -121,7 +121,9 @@ __device__ __forceinline__ void fade_row_moments(const float *stats, int stats_n
   }
   const float inv = 1.0f / (float)width;
   mean = s * inv;
-  rstd = 1.0f / sqrtf(fmaxf(q * inv - mean * mean, 0.0f) + 1e-5f);
+  // explicit product and fused multiply-add: this function is inlined into many kernels whose results must agree bit for
+  // bit, which must not depend on which of the two products the compiler fuses with the subtraction
+  rstd = 1.0f / sqrtf(fmaxf(fmaf(q, inv, -__fmul_rn(mean, mean)), 0.0f) + 1e-5f);
 }
 
 // Row-wise element kernels: thread t = blockIdx.x * 256 + tid owns the 8-wide chunk t % chunks of the RPT rows of row

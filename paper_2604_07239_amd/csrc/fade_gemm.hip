@@ -118,12 +118,12 @@ __device__ __forceinline__ void stage_transform(const GemmArgs &g, int k, const 
     load8(g.gamma + k, ga);
     load8(g.beta + k, be);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] = (v[i] - mean) * rstd * ga[i] + be[i];
+    for (int i = 0; i < 8; ++i) v[i] = fmaf(__fmul_rn(v[i] - mean, rstd), ga[i], be[i]);
     if (PRO == PRO_FINAL) {
       float r[8];
       raw_to_float(a2, r);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) v[i] = gelu_f(v[i]) + lam * r[i];
+      for (int i = 0; i < 8; ++i) v[i] = fmaf(lam, r[i], gelu_f(v[i]));
     }
   }
 }
@@ -149,6 +149,9 @@ __device__ __forceinline__ void epi_side_load(const GemmArgs &g, size_t o, bool 
   if (EpiSides<EPI>::n >= 2) raw_load(sd[1], static_cast<const AT *>(g.S2) + o);
 }
 
+// The arithmetic below is written with explicit fused multiply-adds and unfusable products (fmaf, __fmul_rn): instances of
+// this function for different tile shapes must give the same bits (a pass over many steps and a single step use different
+// ones), which must not depend on where the compiler chooses to contract a * b + c.
 // A thread walks rows r0, r0 + RP, ... of its 8-wide column chunk. The side inputs (and the row moments of the folded
 // form) of U consecutive passes are requested together before the first of them is used, so that one memory latency
 // covers U rows; with PRE the caller has requested them even earlier (`pre`: [pass][input], all BM / RP passes).
@@ -183,7 +186,8 @@ __device__ __forceinline__ void epilogue(const GemmArgs &g, const float *Cs, int
       for (int u = 0; u < U; ++u) {
         const int m = m0 + rb + u * RP;
         if (kRagged && rb + u * RP >= BM) continue;
-        epi_side_load<EPI, AT>(g, (size_t)m * g.ldc + nout0 + c8, m < g.M, own[u]);
+        // past the last row: any row (dropped below); a branch around the loads would cost the exact vmcnt waits
+        epi_side_load<EPI, AT>(g, (size_t)(m < g.M ? m : g.M - 1) * g.ldc + nout0 + c8, true, own[u]);
         if (EPI == EPI_GEGLU_FOLD) row_moments(g, m, mean[u], rstd[u]);
       }
     }
@@ -212,7 +216,7 @@ __device__ __forceinline__ void epilogue(const GemmArgs &g, const float *Cs, int
         float s1[8];
         raw_to_float(sd[0], s1);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) out[i] = gelu_f(x[i]) + lam * s1[i];
+        for (int i = 0; i < 8; ++i) out[i] = fmaf(lam, s1[i], gelu_f(x[i]));
         store8(static_cast<AT *>(g.C) + o, out);
         if (g.C2) store8(static_cast<AT *>(g.C2) + o, x);
       } else if (EPI == EPI_MIX) {
@@ -220,7 +224,7 @@ __device__ __forceinline__ void epilogue(const GemmArgs &g, const float *Cs, int
         raw_to_float(sd[0], s1);
         raw_to_float(sd[1], s2);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) { al[i] = sigmoid_f(x[i]); out[i] = al[i] * s1[i] + (1.0f - al[i]) * s2[i]; }
+        for (int i = 0; i < 8; ++i) { al[i] = sigmoid_f(x[i]); out[i] = fmaf(al[i], s1[i], __fmul_rn(1.0f - al[i], s2[i])); }
         store8(static_cast<AT *>(g.C) + o, out);
         if (g.C2) store8(static_cast<AT *>(g.C2) + o, al);
       } else if (EPI == EPI_GATE) {
@@ -228,7 +232,7 @@ __device__ __forceinline__ void epilogue(const GemmArgs &g, const float *Cs, int
         raw_to_float(sd[0], s1);
         raw_to_float(sd[1], s2);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) { sgm[i] = sigmoid_f(x[i]); out[i] = s1[i] * sgm[i] + lam * s2[i]; }
+        for (int i = 0; i < 8; ++i) { sgm[i] = sigmoid_f(x[i]); out[i] = fmaf(lam, s2[i], __fmul_rn(s1[i], sgm[i])); }
         store8(static_cast<AT *>(g.C) + o, out);
         if (g.C2) store8(static_cast<AT *>(g.C2) + o, sgm);
       } else if (EPI == EPI_GEGLU) {
@@ -276,7 +280,7 @@ __device__ __forceinline__ void epilogue(const GemmArgs &g, const float *Cs, int
     if (g.stats_out && (EPI == EPI_STORE || EPI == EPI_MIX || EPI == EPI_GATE)) {
       float s = 0.0f, q = 0.0f;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) { s += out[i]; q += out[i] * out[i]; }
+      for (int i = 0; i < 8; ++i) { s += out[i]; q = fmaf(out[i], out[i], q); }
 #pragma unroll
       for (int off = CH / 2; off > 0; off >>= 1) { s += __shfl_xor(s, off, 64); q += __shfl_xor(q, off, 64); }
       if (live && (tid % CH) == 0) {
