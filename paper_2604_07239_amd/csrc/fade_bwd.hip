@@ -330,12 +330,13 @@ __global__ __launch_bounds__(256) void bwd_out_kernel(BwdOutArgs a) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) { dh[r][i] = 0.0f; xh[r][i] = 0.0f; }
     if (b < a.B && mine) {  // b < B is uniform over the workgroup
-      moments(a.stats + (size_t)b * a.stats_n * 2, a.stats_n, a.Dh, mean, rstd[r]);
+      // the row pieces are requested before the row's statistics are summed: one round trip, not two
       const size_t base = (size_t)b * a.Dh + tid * 8;
       float dH[8], v[8], hc[8], dhc[8];
       ld8<AT>(static_cast<const AT *>(a.dH) + base, dH);
       ld8<AT>(static_cast<const AT *>(a.V) + base, v);
       ld8<AT>(static_cast<const AT *>(a.Hc) + base, hc);
+      moments(a.stats + (size_t)b * a.stats_n * 2, a.stats_n, a.Dh, mean, rstd[r]);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         xh[r][i] = (v[i] - mean) * rstd[r];
@@ -418,11 +419,15 @@ __global__ __launch_bounds__(256) void bwd_gate_kernel(BwdGateArgs a) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) { dh[r][i] = 0.0f; xh[r][i] = 0.0f; }
     if (b < a.B && mine) {
-      moments(a.stats + (size_t)b * a.stats_n * 2, a.stats_n, a.Dh, mean, rstd[r]);
       const size_t base = (size_t)b * a.Dh + tid * 8;
       float du[8], hc[8];
+      ld8<AT>(static_cast<const AT *>(a.Hc) + base, hc);  // requested before the statistics are summed
+      if (!a.du_part && a.du) ld8<AT>(static_cast<const AT *>(a.du) + base, du);
+      moments(a.stats + (size_t)b * a.stats_n * 2, a.stats_n, a.Dh, mean, rstd[r]);
+      if (a.du_part || !a.du) {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) du[i] = 0.0f;
+        for (int i = 0; i < 8; ++i) du[i] = 0.0f;
+      }
       if (a.du_part) {
         for (int sp = 0; sp < a.du_splits; ++sp) {
           float pv[8];
@@ -432,10 +437,7 @@ __global__ __launch_bounds__(256) void bwd_gate_kernel(BwdGateArgs a) {
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i) du[i] = (float)(AT)du[i];  // the value the unsplit product would have stored
-      } else if (a.du) {
-        ld8<AT>(static_cast<const AT *>(a.du) + base, du);
       }
-      ld8<AT>(static_cast<const AT *>(a.Hc) + base, hc);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         xh[r][i] = (hc[i] - mean) * rstd[r];
@@ -516,15 +518,15 @@ __global__ __launch_bounds__(256) void bwd_mix_kernel(BwdMixArgs a) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) { dh[r][i] = 0.0f; xh[r][i] = 0.0f; }
     if (b < a.B && mine) {
-      moments(a.stats + (size_t)b * a.stats_n * 2, a.stats_n, a.Dh, mean, rstd[r]);
       const size_t base = (size_t)b * a.Dh + tid * 8;
       float dn[8], hm[8];
 #pragma unroll
       for (int i = 0; i < 8; ++i) { dn[i] = 0.0f; hm[i] = 0.0f; }
-      if (a.dnc) {
+      if (a.dnc) {  // requested before the statistics are summed
         ld8<AT>(static_cast<const AT *>(a.dnc) + base, dn);
         ld8<AT>(static_cast<const AT *>(a.Hmix) + base, hm);
       }
+      moments(a.stats + (size_t)b * a.stats_n * 2, a.stats_n, a.Dh, mean, rstd[r]);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         xh[r][i] = (hm[i] - mean) * rstd[r];
