@@ -1049,29 +1049,16 @@ __global__ __launch_bounds__(256) void symbol_sums_mfma_kernel(BwdTokenArgs a, i
   for (int j = 0; j < NT; ++j) b_off[j] = r0 * PITCH + (((j * 4 + 2 * mh + ((s16 & 3) >> 1)) ^ swz(r0)) << 4) + (s16 & 1) * 8;
   const bf16_t one = (bf16_t)1.0f, zero = (bf16_t)0.0f;
 
-  // global loads of chunk c + 1 are issued before the matrix work on chunk c (values wait in registers)
+  // global loads of chunk c + 1 are issued before the matrix work on chunk c (values wait in registers). The two big loads
+  // of an item are issued without a branch (addresses clamped into the arrays, values masked when they are used): with the
+  // loads inside `if (t < t_end)` the compiler waits for each item's loads before it issues the next item's.
   constexpr int ITEMS = CH * PPR / 256;
   Raw8B<AT> ra[ITEMS], rb[ITEMS];
   Raw8B<float> rc[ITEMS];
   unsigned short psym = 0xFFFF;
   auto fetch = [&](long long c0) {
-#pragma unroll
-    for (int it = 0; it < ITEMS; ++it) {
-      const int item = tid + 256 * it, tl = item / PPR, col = (item % PPR) * 8;
-      const long long t = c0 + tl;
-      ra[it].zero(); rb[it].zero(); rc[it].zero();
-      if (t < t_end) {
-        if (col < D) {
-          const size_t g = (size_t)t * D + col;
-          ra[it].load(static_cast<const AT *>(a.dX1) + g);
-          rb[it].load(static_cast<const AT *>(a.dX2) + g);
-          // newest token of its stream: the cache-slot path ends here too
-          if ((int)(t & Tm1) == Tm1) rc[it].load(a.dxt + (size_t)(t >> lgT) * D + col);
-        } else {
-          ra[it].load(static_cast<const AT *>(a.dxl) + (size_t)t * D + (col - D));
-        }
-      }
-    }
+    // the symbol first: its address depends on loaded values (active flag, window position), and waiting for that chain
+    // must not wait for the big loads behind it
     psym = 0xFFFF;  // matches no symbol: tokens past the range and inactive streams contribute nothing
     if (tid < CH) {
       const long long t = c0 + tid;
@@ -1079,6 +1066,23 @@ __global__ __launch_bounds__(256) void symbol_sums_mfma_kernel(BwdTokenArgs a, i
         const int b = (int)(t >> lgT), j = (int)(t & Tm1);
         if (stream_active(a.ws, b)) psym = stream_window(a.ws, b, a.T)[j];
       }
+    }
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it) {
+      const int item = tid + 256 * it, tl = item / PPR, col = (item % PPR) * 8;
+      const long long t = c0 + tl < tokens ? c0 + tl : tokens - 1;
+      const bool first = col < D;  // columns [0, D): dX1 + dX2 (+ dxt at the newest token); [D, 2 D): dxl
+      const size_t g = (size_t)t * D + (first ? col : col - D);
+      ra[it].load(first ? static_cast<const AT *>(a.dX1) + g : static_cast<const AT *>(a.dxl) + g);
+      rb[it].load(static_cast<const AT *>(a.dX2) + g);  // used by the first half only
+    }
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it) {
+      const int item = tid + 256 * it, tl = item / PPR, col = (item % PPR) * 8;
+      const long long t = c0 + tl;
+      rc[it].zero();
+      // newest token of its stream: the cache-slot path ends here too
+      if (t < t_end && col < D && (int)(t & Tm1) == Tm1) rc[it].load(a.dxt + (size_t)(t >> lgT) * D + col);
     }
   };
   if (t_begin < t_end) fetch(t_begin);
@@ -1089,10 +1093,11 @@ __global__ __launch_bounds__(256) void symbol_sums_mfma_kernel(BwdTokenArgs a, i
       const int item = tid + 256 * it, tl = item / PPR, pc = item % PPR;
       float v[8], w[8], x[8];
       ra[it].cvt(v); rb[it].cvt(w); rc[it].cvt(x);
+      const bool live = c0 + tl < t_end, both = live && pc * 8 < D;
       bf16x8 hi, mid, lo;
 #pragma unroll
       for (int q = 0; q < 8; ++q) {
-        const float val = (v[q] + w[q]) + x[q];
+        const float val = ((live ? v[q] : 0.0f) + (both ? w[q] : 0.0f)) + x[q];
         hi[q] = (bf16_t)val;
         const float r1 = val - (float)hi[q];
         mid[q] = (bf16_t)r1;
