@@ -730,11 +730,19 @@ __device__ __forceinline__ void bwd_slot_body(const BwdSlotArgs &a, int block) {
   for (int u = 0; u < SPW; ++u)
 #pragma unroll
     for (int k = 0; k < KCH; ++k) {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) dh[u][k][i] = 0.0f;
-      const int ch = lane + 64 * k;
-      if (b0 + u < a.B && ch < nch) ld8<AT>(static_cast<const AT *>(a.dhm) + (size_t)(b0 + u) * a.Dh + ch * 8, dh[u][k]);
+      // no branch around the loads (a branch makes the compiler wait for each load before it issues the next): addresses
+      // are clamped into the array, values of streams / chunks that do not exist are zeroed afterwards
+      const int ch = lane + 64 * k, bc = b0 + u < a.B ? b0 + u : a.B - 1, cc = ch < nch ? ch : nch - 1;
+      ld8<AT>(static_cast<const AT *>(a.dhm) + (size_t)bc * a.Dh + cc * 8, dh[u][k]);
     }
+#pragma unroll
+  for (int u = 0; u < SPW; ++u)
+#pragma unroll
+    for (int k = 0; k < KCH; ++k)
+      if (!(b0 + u < a.B && lane + 64 * k < nch)) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) dh[u][k][i] = 0.0f;
+      }
   for (int q0 = 0; q0 < a.c; q0 += 64) {  // 64 slot columns at a time: lane ql ends up with dg[q0 + ql] of each stream
     const int qn = a.c - q0 < 64 ? a.c - q0 : 64;
     float mine[SPW];
@@ -748,18 +756,19 @@ __device__ __forceinline__ void bwd_slot_body(const BwdSlotArgs &a, int block) {
       float sacc[SPW];
 #pragma unroll
       for (int u = 0; u < SPW; ++u) sacc[u] = 0.0f;
+      float w[KCH][8];
+#pragma unroll
+      for (int k = 0; k < KCH; ++k) {  // all of the row's pieces requested together; a chunk past the row meets dh = 0
+        const int ch = lane + 64 * k;
+        ld8<float>(wrow + (ch < nch ? ch : nch - 1) * 8, w[k]);
+      }
 #pragma unroll
       for (int k = 0; k < KCH; ++k) {
-        const int ch = lane + 64 * k;
-        if (ch < nch) {
-          float w[8];
-          ld8<float>(wrow + ch * 8, w);
 #pragma unroll
-          for (int i = 0; i < 8; ++i) {
-            const float wi = a.round_bf16 ? (float)(bf16_t)w[i] : w[i];
+        for (int i = 0; i < 8; ++i) {
+          const float wi = a.round_bf16 ? (float)(bf16_t)w[k][i] : w[k][i];
 #pragma unroll
-            for (int u = 0; u < SPW; ++u) sacc[u] = fmaf(dh[u][k][i], wi, sacc[u]);
-          }
+          for (int u = 0; u < SPW; ++u) sacc[u] = fmaf(dh[u][k][i], wi, sacc[u]);
         }
       }
 #pragma unroll
