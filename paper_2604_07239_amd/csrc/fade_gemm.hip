@@ -128,6 +128,23 @@ __device__ __forceinline__ void stage_transform(const GemmArgs &g, int k, const 
   }
 }
 
+// The same with the LayerNorm gain / shift of the chunk already in registers (requested together with the chunk itself).
+template <int PRO, typename AT>
+__device__ __forceinline__ void stage_transform_gb(const Raw8<AT> &a, const Raw8<AT> &a2, float mean, float rstd, float lam,
+                                                   const float ga[8], const float be[8], float v[8]) {
+  raw_to_float(a, v);
+  if (PRO == PRO_LN || PRO == PRO_FINAL) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = fmaf(__fmul_rn(v[i] - mean, rstd), ga[i], be[i]);
+    if (PRO == PRO_FINAL) {
+      float r[8];
+      raw_to_float(a2, r);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = fmaf(lam, r[i], gelu_f(v[i]));
+    }
+  }
+}
+
 // mean / rstd of row m from the partial sums its producer left behind (fixed summation order).
 __device__ __forceinline__ void row_moments(const GemmArgs &g, int m, float &mean, float &rstd) {
   mean = 0.0f; rstd = 1.0f;
@@ -359,10 +376,17 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
 
   Raw8<AT> ra[PASSES], ra2[PASSES];
   bf16x8 bcur[4][TN], bnext[4][TN];
+  // LayerNorm gain / shift of this thread's 8 columns of the block: requested with the block's rows, not when they are used
+  constexpr bool kGB = PRO == PRO_LN || PRO == PRO_FINAL;
+  float ga[kGB ? 8 : 1], be[kGB ? 8 : 1];
+  auto load_gb = [&](int k) {
+    if constexpr (kGB) { load8(g.gamma + k, ga); load8(g.beta + k, be); }
+  };
 
   // preamble: the range's first K block
 #pragma unroll
   for (int p = 0; p < PASSES; ++p) stage_load<PRO, AT>(g, m0 + p * 32 + srow, kb0 * BK + skc, ra[p], ra2[p]);
+  load_gb(kb0 * BK + skc);
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
@@ -375,7 +399,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
       *reinterpret_cast<bf16x8 *>(dst) = ra[p].v;
     } else {
       float v[8];
-      stage_transform<PRO, AT>(g, kb0 * BK + skc, ra[p], ra2[p], mean[p], rstd[p], lam, v);
+      if constexpr (kGB) stage_transform_gb<PRO, AT>(ra[p], ra2[p], mean[p], rstd[p], lam, ga, be, v);
+      else stage_transform<PRO, AT>(g, kb0 * BK + skc, ra[p], ra2[p], mean[p], rstd[p], lam, v);
       store8(dst, v);
     }
   }
@@ -386,6 +411,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
       const int k1 = (kb0 + kb + 1) * BK;
 #pragma unroll
       for (int p = 0; p < PASSES; ++p) stage_load<PRO, AT>(g, m0 + p * 32 + srow, k1 + skc, ra[p], ra2[p]);
+      load_gb(k1 + skc);
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
@@ -415,7 +441,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
           *reinterpret_cast<bf16x8 *>(dst) = ra[p].v;
         } else {
           float v[8];
-          stage_transform<PRO, AT>(g, k1 + skc, ra[p], ra2[p], mean[p], rstd[p], lam, v);
+          if constexpr (kGB) stage_transform_gb<PRO, AT>(ra[p], ra2[p], mean[p], rstd[p], lam, ga, be, v);
+          else stage_transform<PRO, AT>(g, k1 + skc, ra[p], ra2[p], mean[p], rstd[p], lam, v);
           store8(dst, v);
         }
       }
