@@ -340,6 +340,12 @@ __device__ __forceinline__ void moments_from_partials(const float *stats, int st
 __global__ __launch_bounds__(256) void cci_kernel(CciArgs a) {
   const int b = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (b >= a.B) return;
+  // the stream's W_U (8 KiB, contiguous) as eight 16-byte pieces per lane, requested before anything else: piece
+  // lane + 64 i holds row k = lane / 8 + 8 i, columns 8 (lane % 8) .. + 7
+  const bf16x8 *Wp = reinterpret_cast<const bf16x8 *>(a.WU + (size_t)(b % a.streams) * 4096) + lane;
+  bf16x8 w[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) w[i] = Wp[64 * i];
   float raw = 0.0f;
   for (int s0 = 0; s0 < a.splits; s0 += 8) {  // 8 partials in flight, added in split order
     float pv[8];
@@ -352,11 +358,28 @@ __global__ __launch_bounds__(256) void cci_kernel(CciArgs a) {
   moments_from_partials(a.stats + (size_t)b * a.stats_n * 2, a.stats_n, a.Dh, mean, rstd);
   const float yv = rstd * (raw - mean * a.s_fold[lane]) + a.t_fold[lane];
   a.y[(size_t)b * 64 + lane] = yv;
-  const bf16_t *W = a.WU + (size_t)(b % a.streams) * 4096;
-  float acc = 0.0f;
-#pragma unroll 8
-  for (int k = 0; k < 64; ++k) acc = fmaf(__shfl(yv, k, 64), (float)W[k * 64 + lane], acc);
-  a.z[(size_t)b * 64 + lane] = (bf16_t)acc;
+  // z[n] = sum_k y[k] W_U[k][n]: a lane adds its eight rows for its eight columns (k = lane / 8, + 8, ... in order), then the
+  // eight lanes that share the columns are added in a fixed tree; lanes 0..7 store 16 bytes each
+  const int m = lane >> 3;
+  float acc[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const float yk = __shfl(yv, m + 8 * i, 64);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = fmaf(yk, (float)w[i][j], acc[j]);
+  }
+#pragma unroll
+  for (int off = 8; off < 64; off <<= 1)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] += __shfl_xor(acc[j], off, 64);
+  if (m == 0) {
+    bf16x8 zv;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) zv[j] = (bf16_t)acc[j];
+    *reinterpret_cast<bf16x8 *>(a.z + (size_t)b * 64 + lane * 8) = zv;
+  }
 }
 
 // Eq. 9 (bf16 path): reduce the split-K partials of H_coarse [W'_fg | W'_fv] (gate and value interleaved per 128
