@@ -130,122 +130,180 @@ __device__ __forceinline__ void slot_pair(const float *xt, const float *Wg, cons
   }
 }
 // Eq. 4 for one window on the matrix cores (bf16, D = 32): H_local[j][o] = psi(b[o] + sum_{r,i} xl[j - (taps-1) + r][i] W[r][i][o]).
-// Wavefront w owns tokens 32 w .. 32 w + 31 (T <= 128). A lane's operand piece, 8 consecutive channels of one tap of one
+// A wavefront takes the 32 tokens of one tile (T <= 128). A lane's operand piece, 8 consecutive channels of one tap of one
 // token, is one 16-byte read of the per-symbol table; the W fragments are read as they lie. One accumulator takes the K
 // steps in order and the tail is the product kernel's conv epilogue, so the result is bit for bit that kernel's.
-__device__ __forceinline__ void conv_window_mfma(const EmbedArgs &a, const uint8_t *win, const bf16_t *tabXl, size_t row, int wave) {
-  const int lane = threadIdx.x & 63;  // `wave`: which 32 tokens of the window the calling wavefront takes
-  if (wave * 32 >= a.T) return;
-  const int j = wave * 32 + (lane & 31), ksteps = a.Kc / 16;  // K_c <= 128: at most 8 K steps, 2 per tap
-  const bf16x8 *Wf = static_cast<const bf16x8 *>(a.conv_W) + lane;
-  // all operand reads are requested before the first matrix instruction: the symbols of the taps, then the table pieces
+// Three stages, so that the caller can put its own loads of the same depth beside each: the window's symbols, the operand
+// pieces they address, then the arithmetic. No load sits behind a branch (the compiler ends such a branch by waiting for
+// every load in flight): indices are clamped into the arrays and pieces that do not exist are zeroed afterwards.
+template <int KS>  // K steps held in registers: K_c / 16 <= KS <= 8
+struct ConvWindow {
   int sym[4];
+  bool ok[4];
+  bf16x8 af[KS], bf[KS];
+  float bias;
+  __device__ __forceinline__ void symbols(const EmbedArgs &a, const uint8_t *win, int tile) {
+    const int j = tile * 32 + (threadIdx.x & 31);
 #pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const int tok = j - (a.taps - 1) + r;
-    sym[r] = (r < a.taps && tok >= 0 && j < a.T) ? (int)win[tok] : -1;
-  }
-  bf16x8 af[8], bf[8];
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) {
-    const int i = (ks & 1) * 16 + (lane >> 5) * 8, sy = sym[ks >> 1];  // k = 16 ks + 8 (lane / 32) = 32 tap + i
-#pragma unroll
-    for (int q = 0; q < 8; ++q) { af[ks][q] = (bf16_t)0.0f; bf[ks][q] = (bf16_t)0.0f; }
-    if (ks < ksteps) {
-      if (sy >= 0) af[ks] = *reinterpret_cast<const bf16x8 *>(tabXl + (size_t)sy * 32 + i);
-      bf[ks] = Wf[(size_t)ks * 64];
+    for (int r = 0; r < 4; ++r) {
+      const int tok = j - (a.taps - 1) + r;
+      ok[r] = r < a.taps && tok >= 0 && j < a.T;
+      sym[r] = win[ok[r] ? tok : 0];
     }
   }
-  f32x16 acc;
+  __device__ __forceinline__ void operands(const EmbedArgs &a, const bf16_t *tabXl) {
+    const int lane = threadIdx.x & 63, ksteps = a.Kc / 16;  // K_c <= 128: at most 8 K steps, 2 per tap
+    const bf16x8 *Wf = static_cast<const bf16x8 *>(a.conv_W) + lane;
 #pragma unroll
-  for (int e = 0; e < 16; ++e) acc[e] = 0.0f;
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks)
-    if (ks < ksteps) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks], bf[ks], acc, 0, 0, 0);
-  // The tile leaves through LDS (this wavefront's own 32 x 32 patch: no workgroup barrier) so that a lane stores 16
-  // consecutive channels of one token, 2 x 16 bytes per output, instead of 16 scattered 2-byte values.
-  __shared__ float patch[4][32][33];
-  float (*pt)[33] = patch[(threadIdx.x >> 6) & 3];
-  const int o = lane & 31;
-  const float bias = a.conv_b[o];
-#pragma unroll
-  for (int e = 0; e < 16; ++e) pt[(e >> 2) * 8 + (lane >> 5) * 4 + (e & 3)][o] = acc[e] + bias;
-  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the wavefront's LDS writes have landed before its lanes read each other's
-  const int tr = lane >> 1, c0 = (lane & 1) * 16, t = wave * 32 + tr;
-  if (t < a.T) {
-    bf16x8 h[2], p[2];
-#pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      const float pre = pt[tr][c0 + q];
-      h[q >> 3][q & 7] = (bf16_t)gelu_f(pre);
-      p[q >> 3][q & 7] = (bf16_t)pre;
+    for (int ks = 0; ks < KS; ++ks) {
+      const int i = (ks & 1) * 16 + (lane >> 5) * 8;  // k = 16 ks + 8 (lane / 32) = 32 tap + i
+      af[ks] = *reinterpret_cast<const bf16x8 *>(tabXl + (size_t)sym[ks >> 1] * 32 + i);
+      bf[ks] = Wf[(size_t)(ks < ksteps ? ks : 0) * 64];
     }
-    bf16_t *Hl = static_cast<bf16_t *>(a.Hl) + row * a.Dh + t * 32 + c0;
-    *reinterpret_cast<bf16x8 *>(Hl) = h[0];
-    *reinterpret_cast<bf16x8 *>(Hl + 8) = h[1];
-    if (a.cv) {
-      bf16_t *cv = static_cast<bf16_t *>(a.cv) + row * a.Dh + t * 32 + c0;
-      *reinterpret_cast<bf16x8 *>(cv) = p[0];
-      *reinterpret_cast<bf16x8 *>(cv + 8) = p[1];
+    bias = a.conv_b[lane & 31];
+  }
+  // tile: which 32 tokens; the 32 x 32 result leaves through this wavefront's own LDS patch (no workgroup barrier) so that a
+  // lane stores 16 consecutive channels of one token, 2 x 16 bytes per output, instead of 16 scattered 2-byte values
+  __device__ __forceinline__ void finish(const EmbedArgs &a, size_t row, int tile) {
+    const int lane = threadIdx.x & 63, ksteps = a.Kc / 16;
+    f32x16 acc;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = 0.0f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      bf16x8 av = af[ks];
+      if (!ok[ks >> 1]) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) av[q] = (bf16_t)0.0f;
+      }
+      if (ks < ksteps) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bf[ks], acc, 0, 0, 0);
+    }
+    __shared__ float patch[4][32][33];
+    float (*pt)[33] = patch[(threadIdx.x >> 6) & 3];
+    const int o = lane & 31;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) pt[(e >> 2) * 8 + (lane >> 5) * 4 + (e & 3)][o] = acc[e] + bias;
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the wavefront's LDS writes have landed before its lanes read each other's
+    const int tr = lane >> 1, c0 = (lane & 1) * 16, t = tile * 32 + tr;
+    if (t < a.T) {
+      bf16x8 h[2], p[2];
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const float pre = pt[tr][c0 + q];
+        h[q >> 3][q & 7] = (bf16_t)gelu_f(pre);
+        p[q >> 3][q & 7] = (bf16_t)pre;
+      }
+      bf16_t *Hl = static_cast<bf16_t *>(a.Hl) + row * a.Dh + t * 32 + c0;
+      *reinterpret_cast<bf16x8 *>(Hl) = h[0];
+      *reinterpret_cast<bf16x8 *>(Hl + 8) = h[1];
+      if (a.cv) {
+        bf16_t *cv = static_cast<bf16_t *>(a.cv) + row * a.Dh + t * 32 + c0;
+        *reinterpret_cast<bf16x8 *>(cv) = p[0];
+        *reinterpret_cast<bf16x8 *>(cv + 8) = p[1];
+      }
     }
   }
+};
+__device__ __forceinline__ void conv_window_mfma(const EmbedArgs &a, const uint8_t *win, const bf16_t *tabXl, size_t row, int tile) {
+  if (tile * 32 >= a.T) return;
+  ConvWindow<8> cw;
+  cw.symbols(a, win, tile);
+  cw.operands(a, tabXl);
+  cw.finish(a, row, tile);
 }
 
-template <typename AT>
+// One workgroup per stream, in rounds of loads of equal depth: first what depends on nothing (the window's symbols, the
+// cache row), then what a symbol addresses (table pieces for X, X_l and Eq. 4, the newest symbol's slot), then stores and
+// arithmetic. nt threads: 256, or 64 per 32-token tile of Eq. 4 (see the launcher). KS: K steps of Eq. 4 held in registers
+// (>= K_c / 16); NKP: 16-byte pieces of the cache row per thread (>= D_cache / (nt V), wide slots).
+template <typename AT, int KS, int NKP>
 __global__ __launch_bounds__(256) void embed_cache_kernel(EmbedArgs a) {
-  const int b = blockIdx.x, tid = threadIdx.x;
+  const int b = blockIdx.x, tid = threadIdx.x, nt = blockDim.x;
   if (!stream_active(a.ws, b)) return;
   const uint8_t *win = stream_window(a.ws, b, a.T);
   const AT *tabXe = static_cast<const AT *>(a.tabXe), *tabXl = static_cast<const AT *>(a.tabXl);
   AT *X = static_cast<AT *>(a.X) + (size_t)b * a.Dh, *XL = a.XL ? static_cast<AT *>(a.XL) + (size_t)b * a.Dh : nullptr;
+  AT *M = static_cast<AT *>(a.M) + (size_t)b * a.Dc;
   constexpr int V = 16 / sizeof(AT);  // elements per 16-byte piece
   typedef f32x4 piece_t;              // 16 bytes, whatever the element type
-  for (int ch = tid; ch < a.Dh / V; ch += 256) {
-    const int e0 = ch * V, j = e0 / a.D, i = e0 - j * a.D;
+  const bool wide = a.c % V == 0;     // wide slots: the shift of Eq. 2 is a whole number of 16-byte pieces
+  const int np = a.Dc / V, sh = a.c / V, nx = a.Dh / V;
+  const bool conv_live = sizeof(AT) == 2 && a.conv_W && (tid >> 6) * 32 < a.T;
+  const int tile = conv_live ? tid >> 6 : 0;
+  // round 1
+  const bool two = tid + nt < nx;  // the first two pieces of X of this thread (all of them when D_h <= 2 nt V)
+  const int e0 = (tid < nx ? tid : 0) * V, j0 = e0 / a.D, i0 = e0 - j0 * a.D;
+  const int e1 = (two ? tid + nt : 0) * V, j1 = e1 / a.D, i1 = e1 - j1 * a.D;
+  const int s0 = win[j0], s1 = win[j1], slast = win[a.T - 1];
+  piece_t kp[NKP];
+  if (wide) {
+#pragma unroll
+    for (int q = 0; q < NKP; ++q) {
+      const int idx = q * nt + tid;
+      kp[q] = reinterpret_cast<const piece_t *>(M)[idx < np ? idx : np - 1];
+    }
+  }
+  ConvWindow<KS> cw;
+  if constexpr (sizeof(AT) == 2) {
+    if (a.conv_W) cw.symbols(a, win, tile);
+  }
+  // round 2
+  const piece_t xe0 = *reinterpret_cast<const piece_t *>(tabXe + (size_t)s0 * a.D + i0);
+  const piece_t xe1 = *reinterpret_cast<const piece_t *>(tabXe + (size_t)s1 * a.D + i1);
+  const piece_t xl0 = *reinterpret_cast<const piece_t *>(tabXl + (size_t)s0 * a.D + i0);
+  const piece_t xl1 = *reinterpret_cast<const piece_t *>(tabXl + (size_t)s1 * a.D + i1);
+  // frozen weights: the slot depends on the symbol alone (without the table: a read of X's table that nothing uses)
+  const AT slot = static_cast<const AT *>(a.slot_tab ? a.slot_tab : a.tabXe)[a.slot_tab ? (size_t)slast * a.c + (tid < a.c ? tid : 0) : 0];
+  if constexpr (sizeof(AT) == 2) {
+    if (a.conv_W) cw.operands(a, reinterpret_cast<const bf16_t *>(tabXl));
+  }
+  float gg = 0.0f, gv = 0.0f;  // adapting weights: Eq. 1's two pre-activations of the newest symbol, in the same round
+  if (!a.slot_tab && tid < a.c) slot_pair(a.tabXe32 + (size_t)slast * a.D, a.Wg, a.Wv, a.D, a.c, tid, gg, gv);
+  // stores and arithmetic
+  if (tid < nx) {
+    *reinterpret_cast<piece_t *>(X + e0) = xe0;
+    if (a.XL) *reinterpret_cast<piece_t *>(XL + e0) = xl0;
+  }
+  if (two) {
+    *reinterpret_cast<piece_t *>(X + e1) = xe1;
+    if (a.XL) *reinterpret_cast<piece_t *>(XL + e1) = xl1;
+  }
+  for (int ch = tid + 2 * nt; ch < nx; ch += nt) {  // rows of more than 2 nt pieces
+    const int e = ch * V, j = e / a.D, i = e - j * a.D;
     const int s = win[j];
-    *reinterpret_cast<piece_t *>(X + e0) = *reinterpret_cast<const piece_t *>(tabXe + (size_t)s * a.D + i);
-    if (a.XL) *reinterpret_cast<piece_t *>(XL + e0) = *reinterpret_cast<const piece_t *>(tabXl + (size_t)s * a.D + i);
+    *reinterpret_cast<piece_t *>(X + e) = *reinterpret_cast<const piece_t *>(tabXe + (size_t)s * a.D + i);
+    if (a.XL) *reinterpret_cast<piece_t *>(XL + e) = *reinterpret_cast<const piece_t *>(tabXl + (size_t)s * a.D + i);
   }
   if constexpr (sizeof(AT) == 2) {
-    if (a.conv_W) conv_window_mfma(a, win, reinterpret_cast<const bf16_t *>(tabXl), (size_t)b, tid >> 6);
+    if (conv_live) cw.finish(a, (size_t)b, tile);
   }
   // Eq. 2: shift the cache left by one slot (through registers, so the move is safe in place) ...
-  AT *M = static_cast<AT *>(a.M) + (size_t)b * a.Dc;
-  if (a.c % V == 0) {  // wide slots: the shift is a whole number of 16-byte pieces
-    const int np = a.Dc / V, sh = a.c / V;
-    piece_t kp[4];  // D_cache <= 4096: at most 1024 pieces
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int idx = q * 256 + tid;
-      if (idx < np) kp[q] = reinterpret_cast<const piece_t *>(M)[idx];
-    }
+  if (wide) {
     __syncthreads();
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int idx = q * 256 + tid;
+    for (int q = 0; q < NKP; ++q) {
+      const int idx = q * nt + tid;
       if (idx < np && idx >= sh) reinterpret_cast<piece_t *>(M)[idx - sh] = kp[q];
     }
   } else {
-    AT keep[16];  // D_cache <= 4096
+    AT keep[16];  // D_cache <= 16 nt
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
-      const int idx = q * 256 + tid;
+      const int idx = q * nt + tid;
       if (idx < a.Dc) keep[q] = M[idx];
     }
     __syncthreads();
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
-      const int idx = q * 256 + tid;
+      const int idx = q * nt + tid;
       if (idx < a.Dc && idx >= a.c) M[idx - a.c] = keep[q];
     }
   }
   // ... and append Eq. 1's GeGLU of the newest symbol: psi(x_t W_g) * (x_t W_v)
   if (tid < a.c) {
-    if (a.slot_tab) {  // frozen weights: the slot depends on the symbol alone
-      M[a.Dc - a.c + tid] = static_cast<const AT *>(a.slot_tab)[(size_t)win[a.T - 1] * a.c + tid];
+    if (a.slot_tab) {
+      M[a.Dc - a.c + tid] = slot;
     } else {
-      float gg, gv;
-      slot_pair(a.tabXe32 + (size_t)win[a.T - 1] * a.D, a.Wg, a.Wv, a.D, a.c, tid, gg, gv);
       M[a.Dc - a.c + tid] = (AT)(gelu_f(gg) * gv);
       if (a.GG) { a.GG[(size_t)b * a.c + tid] = gg; a.GV[(size_t)b * a.c + tid] = gv; }
     }
@@ -1006,8 +1064,14 @@ hipError_t fade_tables(const float *E, const float *ge, const float *be, const f
 hipError_t fade_embed_cache(const EmbedArgs &a, int B, bool bf16, hipStream_t s) {
   if (a.Dc > 4096 || a.c > 256 || a.c <= 0) return hipErrorInvalidValue;  // the kernel's register file holds one cache row
   if (a.conv_W && (!bf16 || a.D != 32 || a.T > 128 || a.Kc % 16 || a.Kc > 128 || a.taps * 32 > a.Kc || !a.Hl || !a.conv_b)) return hipErrorInvalidValue;
-  if (bf16) hipLaunchKernelGGL(embed_cache_kernel<bf16_t>, dim3(B), dim3(256), 0, s, a);
-  else hipLaunchKernelGGL(embed_cache_kernel<float>, dim3(B), dim3(256), 0, s, a);
+  // One wavefront per 32-token tile of Eq. 4 when that is fewer than four: every wavefront then carries the same work (on
+  // 256 threads the tiles' matrix work and activations sit on T / 32 of the four SIMDs), and a compute unit holds twice as
+  // many streams, each a chain of dependent round trips (window byte -> table piece -> store).
+  int nt = 256;
+  if (a.conv_W && a.T % 32 == 0 && a.T < 128 && a.c % 8 == 0 && a.Dc / 8 <= 4 * 2 * a.T && a.c <= 2 * a.T) nt = 2 * a.T;
+  if (!bf16) hipLaunchKernelGGL((embed_cache_kernel<float, 8, 4>), dim3(B), dim3(nt), 0, s, a);
+  else if (a.conv_W && a.Kc <= 96 && a.c % 8 == 0 && a.Dc / 8 <= nt) hipLaunchKernelGGL((embed_cache_kernel<bf16_t, 6, 1>), dim3(B), dim3(nt), 0, s, a);
+  else hipLaunchKernelGGL((embed_cache_kernel<bf16_t, 8, 4>), dim3(B), dim3(nt), 0, s, a);
   return hipGetLastError();
 }
 hipError_t fade_embed_steps(const EmbedArgs &a, hipStream_t s) {
