@@ -167,6 +167,7 @@ struct fade_ctx {
   // frozen bf16 encode: up to `steps_max` consecutive steps share one pass (rows = B * steps); buffers hold B * steps_max rows
   int steps_max = 1;
   void *slot_tab = nullptr;   // [256][c] Eq. 1 per symbol
+  float *gg_tab = nullptr, *gv_tab = nullptr;  // [256][c] its two pre-activations per symbol (adapting weights)
   uint2 *ranges = nullptr;    // [B * steps_max] coding intervals of one pass
   // kept for the backward pass (online mode only)
   void *hm = nullptr, *alpha = nullptr, *sg = nullptr, *eg = nullptr, *ev = nullptr, *cv = nullptr;
@@ -345,7 +346,7 @@ int refresh_small(fade_ctx *c, ReduceBatch *pending = nullptr) {
   pb.tab = TablesArgs{c->P(P_E), c->P(P_GAMMA_E), c->P(P_BETA_E), c->P(P_GAMMA_L), c->P(P_BETA_L), (int)d.D, 1, c->tabXe, c->tabXl, c->tabXe32,
                       c->tabXhat, c->tabRstd};
   HIP_TRY(c, fade_prep_batch(pb, s));
-  if (c->slot_tab) HIP_TRY(c, fade_slot_table(c->tabXe32, c->Wg_c, c->Wv_c, (int)d.D, (int)d.c, c->slot_tab, s));
+  if (c->slot_tab || c->gg_tab) HIP_TRY(c, fade_slot_table(c->tabXe32, c->Wg_c, c->Wv_c, (int)d.D, (int)d.c, c->slot_tab, c->gg_tab, c->gv_tab, s));
   return FADE_OK;
 }
 
@@ -533,7 +534,7 @@ int forward_bf16(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uin
     EmbedArgs a{};
     a.ws = ws; a.T = (int)d.T; a.D = (int)d.D; a.Dh = Dh; a.Dc = (int)d.Dc; a.c = (int)d.c;
     a.tabXe = c->tabXe; a.tabXl = c->tabXl; a.tabXe32 = c->tabXe32; a.Wg = c->Wg_c; a.Wv = c->Wv_c;
-    a.X = c->X; a.XL = c->XL; a.M = c->M; a.GG = c->GG; a.GV = c->GV; a.slot_tab = c->slot_tab; a.B = streams; a.S = steps;
+    a.X = c->X; a.XL = c->XL; a.M = c->M; a.GG = c->GG; a.GV = c->GV; a.slot_tab = c->slot_tab; a.gg_tab = c->gg_tab; a.gv_tab = c->gv_tab; a.B = streams; a.S = steps;
     if (conv_fused) {  // Eq. 4 rides along: one launch less, and the per-token rows XL only exist for the backward pass
       a.conv_W = c->Wconv_c; a.conv_b = c->P(P_BCONV); a.Hl = c->Hl; a.cv = c->online ? c->cv : nullptr; a.taps = (int)d.k; a.Kc = (int)d.Kc;
       if (!c->online) a.XL = nullptr;
@@ -1145,9 +1146,12 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
     TRY_ALLOC(dev_alloc(c, &c->part_down, part_rows(c->sp_down) * d.dl));
     if (c->sp_fnr > 1) TRY_ALLOC(dev_alloc(c, &c->part_fnr, part_rows(c->sp_fnr) * 2 * d.De));  // one K range: no partials (folded epilogue)
     TRY_ALLOC(dev_alloc(c, &c->part_head, part_rows(c->sp_head) * 256));
-    if (c->steps_max > 1) {
+    if (c->steps_max > 1) TRY_ALLOC(dev_alloc(c, &c->ranges, R));
+    if (!c->online) {
       TRY_ALLOC(A(&c->slot_tab, 256 * d.c));
-      TRY_ALLOC(dev_alloc(c, &c->ranges, R));
+    } else {
+      TRY_ALLOC(dev_alloc(c, &c->gg_tab, 256 * d.c));
+      TRY_ALLOC(dev_alloc(c, &c->gv_tab, 256 * d.c));
     }
     TRY_ALLOC(dev_alloc(c, &c->s_down, 2 * d.dl));
     c->t_down = c->s_down + d.dl;

@@ -42,6 +42,7 @@ struct EmbedArgs {
   void *M;                    // [B][Dc]
   float *GG, *GV;             // optional [B][c]: pre-activations of Eq. 1 for the backward pass
   const void *slot_tab;       // optional [256][c] activation type: Eq. 1's slot of every symbol (frozen weights only)
+  const float *gg_tab, *gv_tab;  // optional [256][c]: Eq. 1's two pre-activations of every symbol (adapting weights)
   int B, S;                   // several steps per launch (slot_tab required): row s * B + b is stream b at step ws.i + s
   // Eq. 4 in the same launch (bf16, D = 32; conv_W == NULL: a separate product does it): W_conv as MFMA fragments
   // [K_c / 16][64][8], bias [D], outputs H_local [rows][T][D] and, optionally, the pre-activations for the backward pass.
@@ -134,7 +135,7 @@ hipError_t fade_tables(const float *E, const float *ge, const float *be, const f
                        void *tabXl, float *tabXe32, float *tabXhat, float *tabRstd, bool bf16, hipStream_t s);
 hipError_t fade_embed_cache(const EmbedArgs &a, int B, bool bf16, hipStream_t s);
 hipError_t fade_embed_steps(const EmbedArgs &a, hipStream_t s);  // bf16, a.B * a.S rows, cache rebuilt from the window
-hipError_t fade_slot_table(const float *tabXe32, const float *Wg, const float *Wv, int D, int c, void *tab_bf16, hipStream_t s);
+hipError_t fade_slot_table(const float *tabXe32, const float *Wg, const float *Wv, int D, int c, void *tab_bf16, float *gg_tab, float *gv_tab, hipStream_t s);
 hipError_t fade_encode_ranges(const WinSrc &ws, const uint2 *ranges, int B, int S, const CoderBufs &cb, hipStream_t s);
 hipError_t fade_bmm(const float *y, const void *WU, void *z, int B, bool bf16, hipStream_t s);
 hipError_t fade_softmax_quant_code(const SqcArgs &a, int mode, hipStream_t s);

@@ -1,6 +1,8 @@
 // fade_misc.hip — everything of the step that is not a dense product: weight preparation, the embedding /
 // window gather with the rolling-cache update (Eq. 1-2), the per-stream memory product of Eq. 7, and the
 // fused softmax -> frequency table -> arithmetic coder kernel (one wavefront per stream).
+#include <cstdlib>
+
 #include "fade_dev.h"
 #include "fade_kernels.h"
 
@@ -136,6 +138,58 @@ __device__ __forceinline__ void slot_pair(const float *xt, const float *Wg, cons
 // Three stages, so that the caller can put its own loads of the same depth beside each: the window's symbols, the operand
 // pieces they address, then the arithmetic. No load sits behind a branch (the compiler ends such a branch by waiting for
 // every load in flight): indices are clamped into the arrays and pieces that do not exist are zeroed afterwards.
+// tile: which 32 tokens; af / bf: the K steps' operand pieces (ok[tap]: that tap's token exists); the 32 x 32 result passes
+// through the wavefront's own LDS patch (no workgroup barrier) so that a lane ends up with 16 consecutive channels of one
+// token (h: psi of the pre-activations p), 2 x 16 bytes per output, instead of 16 scattered 2-byte values
+template <int KS>
+__device__ __forceinline__ void conv_tile_compute(const EmbedArgs &a, const bf16x8 *af, const bool *ok, const bf16x8 *bf, float bias, bf16x8 *h, bf16x8 *p) {
+  const int lane = threadIdx.x & 63, ksteps = a.Kc / 16;
+  f32x16 acc;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[e] = 0.0f;
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    bf16x8 av = af[ks];
+    if (!ok[ks >> 1]) {
+#pragma unroll
+      for (int q = 0; q < 8; ++q) av[q] = (bf16_t)0.0f;
+    }
+    if (ks < ksteps) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bf[ks], acc, 0, 0, 0);
+  }
+  __shared__ float patch[4][32][33];
+  float (*pt)[33] = patch[(threadIdx.x >> 6) & 3];
+  const int o = lane & 31;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) pt[(e >> 2) * 8 + (lane >> 5) * 4 + (e & 3)][o] = acc[e] + bias;
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the wavefront's LDS writes have landed before its lanes read each other's
+  const int tr = lane >> 1, c0 = (lane & 1) * 16;
+#pragma unroll
+  for (int q = 0; q < 16; ++q) {
+    const float pre = pt[tr][c0 + q];
+    h[q >> 3][q & 7] = (bf16_t)gelu_f(pre);
+    p[q >> 3][q & 7] = (bf16_t)pre;
+  }
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // ... and read before a later tile of this wavefront overwrites the patch
+}
+__device__ __forceinline__ void conv_tile_store(const EmbedArgs &a, size_t row, int tile, const bf16x8 *h, const bf16x8 *p) {
+  const int lane = threadIdx.x & 63, tr = lane >> 1, c0 = (lane & 1) * 16, t = tile * 32 + tr;
+  if (t < a.T) {
+    bf16_t *Hl = static_cast<bf16_t *>(a.Hl) + row * a.Dh + t * 32 + c0;
+    *reinterpret_cast<bf16x8 *>(Hl) = h[0];
+    *reinterpret_cast<bf16x8 *>(Hl + 8) = h[1];
+    if (a.cv) {
+      bf16_t *cv = static_cast<bf16_t *>(a.cv) + row * a.Dh + t * 32 + c0;
+      *reinterpret_cast<bf16x8 *>(cv) = p[0];
+      *reinterpret_cast<bf16x8 *>(cv + 8) = p[1];
+    }
+  }
+}
+template <int KS>
+__device__ __forceinline__ void conv_tile_finish(const EmbedArgs &a, const bf16x8 *af, const bool *ok, const bf16x8 *bf, float bias, size_t row, int tile) {
+  bf16x8 h[2], p[2];
+  conv_tile_compute<KS>(a, af, ok, bf, bias, h, p);
+  conv_tile_store(a, row, tile, h, p);
+}
 template <int KS>  // K steps held in registers: K_c / 16 <= KS <= 8
 struct ConvWindow {
   int sym[4];
@@ -162,47 +216,7 @@ struct ConvWindow {
     }
     bias = a.conv_b[lane & 31];
   }
-  // tile: which 32 tokens; the 32 x 32 result leaves through this wavefront's own LDS patch (no workgroup barrier) so that a
-  // lane stores 16 consecutive channels of one token, 2 x 16 bytes per output, instead of 16 scattered 2-byte values
-  __device__ __forceinline__ void finish(const EmbedArgs &a, size_t row, int tile) {
-    const int lane = threadIdx.x & 63, ksteps = a.Kc / 16;
-    f32x16 acc;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) acc[e] = 0.0f;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      bf16x8 av = af[ks];
-      if (!ok[ks >> 1]) {
-#pragma unroll
-        for (int q = 0; q < 8; ++q) av[q] = (bf16_t)0.0f;
-      }
-      if (ks < ksteps) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bf[ks], acc, 0, 0, 0);
-    }
-    __shared__ float patch[4][32][33];
-    float (*pt)[33] = patch[(threadIdx.x >> 6) & 3];
-    const int o = lane & 31;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) pt[(e >> 2) * 8 + (lane >> 5) * 4 + (e & 3)][o] = acc[e] + bias;
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the wavefront's LDS writes have landed before its lanes read each other's
-    const int tr = lane >> 1, c0 = (lane & 1) * 16, t = tile * 32 + tr;
-    if (t < a.T) {
-      bf16x8 h[2], p[2];
-#pragma unroll
-      for (int q = 0; q < 16; ++q) {
-        const float pre = pt[tr][c0 + q];
-        h[q >> 3][q & 7] = (bf16_t)gelu_f(pre);
-        p[q >> 3][q & 7] = (bf16_t)pre;
-      }
-      bf16_t *Hl = static_cast<bf16_t *>(a.Hl) + row * a.Dh + t * 32 + c0;
-      *reinterpret_cast<bf16x8 *>(Hl) = h[0];
-      *reinterpret_cast<bf16x8 *>(Hl + 8) = h[1];
-      if (a.cv) {
-        bf16_t *cv = static_cast<bf16_t *>(a.cv) + row * a.Dh + t * 32 + c0;
-        *reinterpret_cast<bf16x8 *>(cv) = p[0];
-        *reinterpret_cast<bf16x8 *>(cv + 8) = p[1];
-      }
-    }
-  }
+  __device__ __forceinline__ void finish(const EmbedArgs &a, size_t row, int tile) { conv_tile_finish<KS>(a, af, ok, bf, bias, row, tile); }
 };
 __device__ __forceinline__ void conv_window_mfma(const EmbedArgs &a, const uint8_t *win, const bf16_t *tabXl, size_t row, int tile) {
   if (tile * 32 >= a.T) return;
@@ -310,13 +324,153 @@ __global__ __launch_bounds__(256) void embed_cache_kernel(EmbedArgs a) {
   }
 }
 
-// Eq. 1 for every symbol (frozen weights): tab[sym][q] = psi(x W_g)[q] * (x W_v)[q], x = the symbol's embedded row.
-__global__ void slot_table_kernel(const float *tabXe32, const float *Wg, const float *Wv, int D, int c, bf16_t *tab) {
+// The same step with the two per-symbol tables in LDS (bf16, Eq. 4 in the launch, T = 32, 64 or 128, a cache row of at
+// most 64 pieces). In the kernel above every wavefront issues some 25 gathering loads per stream (symbols, table pieces,
+// the weights of Eq. 4), and the vector memory path of the compute unit, not HBM, sets its pace. Here a workgroup of
+// four wavefronts copies both tables to LDS once (32 KiB), keeps the weights of Eq. 4 in registers, and then walks over
+// streams: T / 32 wavefronts per stream, 4 / (T / 32) streams side by side. Per stream a wavefront reads the window once
+// from memory (lane l: bytes l and 64 + l, parked in its own LDS row); everything a symbol addresses comes from LDS
+// except Eq. 1's entry of the newest symbol (its table: `slot_tab`, or with adapting weights the two pre-activations
+// `gg_tab` / `gv_tab`).
+// One wait for memory per turn, placed after the arithmetic and before the turn's stores: the counter of outstanding
+// memory operations is in order and covers stores, and behind stores that sit in branches the compiler's count for an
+// older load is the pessimistic one, so a wait anywhere after the stores would expose their whole round trip. The loads it
+// covers (window and cache row two streams ahead, the slot entry one stream ahead) and the stores before them are then
+// a turn's arithmetic old. Streams past the end or inactive are read at clamped addresses and store nothing.
+// UPD: the weights adapt (X_l, the pre-activations of Eq. 4 and of Eq. 1 are kept for the update).
+template <int KS, bool UPD>
+__global__ __launch_bounds__(256) void embed_cache_lds_kernel(EmbedArgs a) {
+  __shared__ __align__(16) bf16_t sXe[256 * 32], sXl[256 * 32];
+  __shared__ uint8_t sWin[4][128];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, B = a.B;
+  const int wps = a.T / 32, grp = wave / wps, tile = wave - grp * wps, ngrp = 4 / wps;  // wavefronts per stream, streams per workgroup
+  const int nt = wps * 64, vt = tid - grp * nt;                                          // threads per stream, this one's index
+  const int np = a.Dc / 8, sh = a.c / 8, ksteps = a.Kc / 16;
+  for (int i = tid; i < 1024; i += 256) {
+    reinterpret_cast<f32x4 *>(sXe)[i] = static_cast<const f32x4 *>(a.tabXe)[i];
+    reinterpret_cast<f32x4 *>(sXl)[i] = static_cast<const f32x4 *>(a.tabXl)[i];
+  }
+  bf16x8 bf[KS];
+  {
+    const bf16x8 *Wf = static_cast<const bf16x8 *>(a.conv_W) + lane;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) bf[ks] = Wf[(size_t)(ks < ksteps ? ks : 0) * 64];
+  }
+  const float bias = a.conv_b[lane & 31];
+  int toff[4];
+  bool ok[4];
+  {
+    const int j = tile * 32 + (lane & 31);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int tok = j - (a.taps - 1) + r;
+      ok[r] = r < a.taps && tok >= 0 && j < a.T;
+      toff[r] = ok[r] ? tok : 0;
+    }
+  }
+  const int j0 = vt >> 2, j1 = (vt + nt) >> 2, i0 = (vt & 3) * 8;  // D = 32: four pieces per token, 2 nt pieces per row
+  const int pk = vt < np ? vt : np - 1, l1 = 64 + lane < a.T ? 64 + lane : a.T - 1, vc = vt < a.c ? vt : 0;
+  uint8_t *myWin = sWin[wave];
+  struct Ahead { int w0, w1, act; f32x4 kp; };  // the window (lane l: bytes l and 64 + l), the mask byte, this thread's piece of the cache row
+  struct Slot { uint32_t tab; float gg, gv; };  // tab: the bf16 entry's bits
+  auto request = [&](int b, Ahead &y) {
+    const int bc = b < B ? b : B - 1;
+    long long off = (long long)bc * a.ws.stride + (a.ws.i - a.T);
+    if (!a.ws.active) { const long long hi = a.ws.n - a.T; off = off < hi ? off : hi; }
+    const uint8_t *win = a.ws.base + off;
+    y.w0 = win[lane < a.T ? lane : a.T - 1];
+    y.w1 = win[l1];
+    y.act = *(a.ws.active ? a.ws.active + bc : win);
+    y.kp = reinterpret_cast<const f32x4 *>(static_cast<const bf16_t *>(a.M) + (size_t)bc * a.Dc)[pk];
+  };
+  auto request_slot = [&](const Ahead &y, Slot &e) {  // the newest symbol: byte T - 1 of the window
+    const int slast = __builtin_amdgcn_readlane(a.T > 64 ? y.w1 : y.w0, (a.T - 1) & 63);
+    if constexpr (UPD) {
+      e.gg = a.gg_tab[(size_t)slast * a.c + vc];
+      e.gv = a.gv_tab[(size_t)slast * a.c + vc];
+    } else {
+      e.tab = static_cast<const uint16_t *>(a.slot_tab)[(size_t)slast * a.c + vc];
+    }
+  };
+  const int step = gridDim.x * ngrp;
+  int b = blockIdx.x * ngrp + grp;
+  Ahead cur, nx, n2;
+  Slot cs{0u, 0.0f, 0.0f}, ns{0u, 0.0f, 0.0f};
+  request(b, cur);
+  request(b + step, nx);
+  request_slot(cur, cs);
+  __syncthreads();  // the tables are in LDS
+  for (; b < B; b += step) {  // a wavefront's trip count depends on its group only: no workgroup barrier inside
+    myWin[lane] = (uint8_t)cur.w0;
+    myWin[64 + lane] = (uint8_t)cur.w1;
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the wavefront's own window row is written before its lanes read it
+    const int s0 = myWin[j0], s1 = myWin[j1];
+    int sym[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) sym[r] = myWin[toff[r]];
+    const f32x4 xe0 = *reinterpret_cast<const f32x4 *>(sXe + s0 * 32 + i0), xe1 = *reinterpret_cast<const f32x4 *>(sXe + s1 * 32 + i0);
+    f32x4 xl0 = xe0, xl1 = xe1;
+    if constexpr (UPD) {
+      xl0 = *reinterpret_cast<const f32x4 *>(sXl + s0 * 32 + i0);
+      xl1 = *reinterpret_cast<const f32x4 *>(sXl + s1 * 32 + i0);
+    }
+    bf16x8 af[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) af[ks] = *reinterpret_cast<const bf16x8 *>(sXl + sym[ks >> 1] * 32 + (ks & 1) * 16 + (lane >> 5) * 8);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // every read of the window row is done before the next turn overwrites it
+    bf16x8 h[2], p[2];
+    conv_tile_compute<KS>(a, af, ok, bf, bias, h, p);
+    // the turn's one wait for memory (see above). Its operands tie the arithmetic above to this side of it and tell the
+    // compiler that the loaded values used below are in their registers from here on.
+    {
+      f32x4 h0 = __builtin_bit_cast(f32x4, h[0]), h1 = __builtin_bit_cast(f32x4, h[1]), p0 = __builtin_bit_cast(f32x4, p[0]), p1 = __builtin_bit_cast(f32x4, p[1]);
+      asm volatile("s_waitcnt vmcnt(0)"
+                   : "+v"(h0), "+v"(h1), "+v"(p0), "+v"(p1), "+v"(cur.kp), "+v"(cs.tab), "+v"(cs.gg), "+v"(cs.gv), "+v"(nx.w0), "+v"(nx.w1), "+v"(cur.act)
+                   :
+                   : "memory");
+      h[0] = __builtin_bit_cast(bf16x8, h0); h[1] = __builtin_bit_cast(bf16x8, h1);
+      p[0] = __builtin_bit_cast(bf16x8, p0); p[1] = __builtin_bit_cast(bf16x8, p1);
+    }
+    request(b + 2 * step, n2);
+    request_slot(nx, ns);
+    const bool alive = a.ws.active ? cur.act != 0 : (a.ws.i < a.ws.stride && (long long)b * a.ws.stride + a.ws.i < a.ws.n);
+    if (alive) {
+      bf16_t *X = static_cast<bf16_t *>(a.X) + (size_t)b * a.Dh;
+      *reinterpret_cast<f32x4 *>(X + vt * 8) = xe0;
+      *reinterpret_cast<f32x4 *>(X + (vt + nt) * 8) = xe1;
+      if constexpr (UPD) {
+        if (a.XL) {
+          bf16_t *XL = static_cast<bf16_t *>(a.XL) + (size_t)b * a.Dh;
+          *reinterpret_cast<f32x4 *>(XL + vt * 8) = xl0;
+          *reinterpret_cast<f32x4 *>(XL + (vt + nt) * 8) = xl1;
+        }
+      }
+      conv_tile_store(a, (size_t)b, tile, h, p);
+      // Eq. 2: the row shifted left by one slot; all of its pieces sit in one wavefront, read two turns ago
+      bf16_t *M = static_cast<bf16_t *>(a.M) + (size_t)b * a.Dc;
+      if (vt < np && vt >= sh) reinterpret_cast<f32x4 *>(M)[vt - sh] = cur.kp;
+      if (vt < a.c) {  // ... and Eq. 1's GeGLU of the newest symbol appended
+        if constexpr (UPD) {
+          M[a.Dc - a.c + vt] = (bf16_t)(gelu_f(cs.gg) * cs.gv);
+          if (a.GG) { a.GG[(size_t)b * a.c + vt] = cs.gg; a.GV[(size_t)b * a.c + vt] = cs.gv; }
+        } else {
+          reinterpret_cast<uint16_t *>(M)[a.Dc - a.c + vt] = (uint16_t)cs.tab;
+        }
+      }
+    }
+    cur = nx; nx = n2; cs = ns;
+  }
+}
+
+// Eq. 1 for every symbol: tab[sym][q] = psi(x W_g)[q] * (x W_v)[q], x = the symbol's embedded row (frozen weights), and / or
+// the two pre-activations themselves (adapting weights: the update needs them per stream). Outputs that are NULL are skipped.
+__global__ void slot_table_kernel(const float *tabXe32, const float *Wg, const float *Wv, int D, int c, bf16_t *tab, float *gg_tab, float *gv_tab) {
   const int sym = blockIdx.x;
   for (int q = threadIdx.x; q < c; q += blockDim.x) {
     float gg, gv;
     slot_pair(tabXe32 + (size_t)sym * D, Wg, Wv, D, c, q, gg, gv);
-    tab[(size_t)sym * c + q] = (bf16_t)(gelu_f(gg) * gv);
+    if (tab) tab[(size_t)sym * c + q] = (bf16_t)(gelu_f(gg) * gv);
+    if (gg_tab) { gg_tab[(size_t)sym * c + q] = gg; gv_tab[(size_t)sym * c + q] = gv; }
   }
 }
 
@@ -1069,6 +1223,25 @@ hipError_t fade_embed_cache(const EmbedArgs &a, int B, bool bf16, hipStream_t s)
   // many streams, each a chain of dependent round trips (window byte -> table piece -> store).
   int nt = 256;
   if (a.conv_W && a.T % 32 == 0 && a.T < 128 && a.c % 8 == 0 && a.Dc / 8 <= 4 * 2 * a.T && a.c <= 2 * a.T) nt = 2 * a.T;
+  const bool frozen_shape = a.slot_tab && !a.XL && !a.cv, adapting_shape = !a.slot_tab && a.gg_tab && a.gv_tab;
+  if (bf16 && a.conv_W && (a.T == 32 || a.T == 64 || a.T == 128) && a.c % 8 == 0 && a.Dc / 8 <= 64 && a.c <= 64 && a.Dh == a.T * 32 && a.ws.i >= a.T &&
+      (a.ws.active || a.ws.n >= a.T) && (frozen_shape || adapting_shape) && B >= 1) {
+    static const int per_cu = getenv("FADE_EMBED_WGS") ? atoi(getenv("FADE_EMBED_WGS")) : 3;
+    EmbedArgs p = a;
+    p.B = B;
+    const int ngrp = 4 / (a.T / 32), want = (B + ngrp - 1) / ngrp;
+    const int G = want < 256 * per_cu ? want : 256 * per_cu;
+    if (per_cu > 0) {
+      if (a.Kc <= 96) {
+        if (frozen_shape) hipLaunchKernelGGL((embed_cache_lds_kernel<6, false>), dim3(G), dim3(256), 0, s, p);
+        else hipLaunchKernelGGL((embed_cache_lds_kernel<6, true>), dim3(G), dim3(256), 0, s, p);
+      } else {
+        if (frozen_shape) hipLaunchKernelGGL((embed_cache_lds_kernel<8, false>), dim3(G), dim3(256), 0, s, p);
+        else hipLaunchKernelGGL((embed_cache_lds_kernel<8, true>), dim3(G), dim3(256), 0, s, p);
+      }
+      return hipGetLastError();
+    }
+  }
   if (!bf16) hipLaunchKernelGGL((embed_cache_kernel<float, 8, 4>), dim3(B), dim3(nt), 0, s, a);
   else if (a.conv_W && a.Kc <= 96 && a.c % 8 == 0 && a.Dc / 8 <= nt) hipLaunchKernelGGL((embed_cache_kernel<bf16_t, 6, 1>), dim3(B), dim3(nt), 0, s, a);
   else hipLaunchKernelGGL((embed_cache_kernel<bf16_t, 8, 4>), dim3(B), dim3(nt), 0, s, a);
@@ -1090,8 +1263,9 @@ hipError_t fade_fill_u32(uint32_t *dst, uint32_t value, size_t n, hipStream_t s)
   hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, dst, value, n);
   return hipGetLastError();
 }
-hipError_t fade_slot_table(const float *tabXe32, const float *Wg, const float *Wv, int D, int c, void *tab_bf16, hipStream_t s) {
-  hipLaunchKernelGGL(slot_table_kernel, dim3(256), dim3(64), 0, s, tabXe32, Wg, Wv, D, c, static_cast<bf16_t *>(tab_bf16));
+hipError_t fade_slot_table(const float *tabXe32, const float *Wg, const float *Wv, int D, int c, void *tab_bf16, float *gg_tab, float *gv_tab, hipStream_t s) {
+  if (!gg_tab != !gv_tab) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(slot_table_kernel, dim3(256), dim3(64), 0, s, tabXe32, Wg, Wv, D, c, static_cast<bf16_t *>(tab_bf16), gg_tab, gv_tab);
   return hipGetLastError();
 }
 hipError_t fade_encode_ranges(const WinSrc &ws, const uint2 *ranges, int B, int S, const CoderBufs &cb, hipStream_t s) {
