@@ -172,7 +172,11 @@ __device__ __forceinline__ void epi_side_load(const GemmArgs &g, size_t o, bool 
 // A thread walks rows r0, r0 + RP, ... of its 8-wide column chunk. The side inputs (and the row moments of the folded
 // form) of U consecutive passes are requested together before the first of them is used, so that one memory latency
 // covers U rows; with PRE the caller has requested them even earlier (`pre`: [pass][input], all BM / RP passes).
-template <int EPI, typename AT, int BM, int BN, int LDC = BN + 4, int NT = 256, bool PRE = false>
+// ALL: every row of the tile exists (M is a multiple of the tile height): the stores then sit behind no branch. The counter
+// of outstanding memory operations is in order and covers stores; for a load older than stores that sit in branches the
+// compiler's wait count assumes the branches not taken, so the wait for the next slab's side inputs would also wait for
+// this slab's stores to be acknowledged.
+template <int EPI, typename AT, int BM, int BN, int LDC = BN + 4, int NT = 256, bool PRE = false, bool ALL = false>
 __device__ __forceinline__ void epilogue(const GemmArgs &g, const float *Cs, int m0, int n0, int nt, int tid, int split = 0,
                                          const Raw8<AT> (*pre)[2] = nullptr) {
   constexpr bool kGeglu = EPI == EPI_GEGLU || EPI == EPI_GEGLU_FOLD;
@@ -214,7 +218,7 @@ __device__ __forceinline__ void epilogue(const GemmArgs &g, const float *Cs, int
     const int r = rb + u * RP;
     if (kRagged && r >= BM) continue;
     const int m = m0 + r;
-    const bool live = m < g.M;
+    const bool live = ALL || m < g.M;
     float x[8], out[8];
     load8(Cs + r * LDC + c8, x);
     const size_t o = (size_t)m * g.ldc + nout0 + c8;
@@ -300,7 +304,10 @@ __device__ __forceinline__ void epilogue(const GemmArgs &g, const float *Cs, int
       for (int i = 0; i < 8; ++i) { s += out[i]; q = fmaf(out[i], out[i], q); }
 #pragma unroll
       for (int off = CH / 2; off > 0; off >>= 1) { s += __shfl_xor(s, off, 64); q += __shfl_xor(q, off, 64); }
-      if (live && (tid % CH) == 0) {
+      if (ALL) {  // every lane of the row's group holds the sums: all store them (same value, same address), no branch
+        float *p = g.stats_out + ((size_t)m * (g.N / BN) + nt) * 2;
+        *reinterpret_cast<float2 *>(p) = make_float2(s, q);
+      } else if (live && (tid % CH) == 0) {
         float *p = g.stats_out + ((size_t)m * (g.N / BN) + nt) * 2;
         p[0] = s; p[1] = q;
       }
@@ -911,7 +918,7 @@ __device__ __forceinline__ void pipe2_body(const GemmArgs &g, int bid, int split
       __syncthreads();
 #pragma unroll
       for (int h = 0; h < BN / 128; ++h)
-        epilogue<EPI, AT, 64, 128, LDC, NT, PRE>(g, Cs + h * 128, m0 + p * 64, n0 + h * 128, nt * (BN / 128) + h, tid, 0, sd[PRE ? (p & 1) : 0][h]);
+        epilogue<EPI, AT, 64, 128, LDC, NT, PRE, NW == 8>(g, Cs + h * 128, m0 + p * 64, n0 + h * 128, nt * (BN / 128) + h, tid, 0, sd[PRE ? (p & 1) : 0][h]);
     }
   } else {
     __syncthreads();
@@ -1508,6 +1515,7 @@ hipError_t launch_pipe2(const GemmArgs &g, hipStream_t s) {
   const int splits = g.splits > 1 ? g.splits : 1;
   if (g.N % BN || g.M <= 0 || g.K % (splits * 32) || (EPI != EPI_PARTIAL && splits != 1) || g.lda % 8) return hipErrorInvalidValue;
   if (g.sum_splits && EPI != EPI_PARTIAL) return hipErrorInvalidValue;
+  if (BM > 128 && NW == 8 && g.M % BM) return hipErrorInvalidValue;  // the slab epilogue of the eight-wavefront tile assumes whole tiles
   GemmArgs ga = g;
   const int ntm = (g.M + BM - 1) / BM, ntn = g.N / BN;
   if (ga.col_groups == 0) ga.col_groups = fade_gemm_col_groups(g.M, g.K, g.N, BN >= 256 ? (size_t)4 << 20 : (size_t)2 << 20);
@@ -1532,7 +1540,7 @@ hipError_t launch_pipe_auto(const GemmArgs &g, hipStream_t s) {
   const int tune = fade_gemm_tune();
   if constexpr (EPI != EPI_PARTIAL) {
     const int tiles256 = ((g.M + 255) / 256) * (g.N / 256);
-    if (g.N % 256 == 0 && (tune == 20 || (tune == 0 && tiles256 >= 256 && g.K >= 256))) return launch_pipe2<256, 256, 4, EPI, 8, 1>(g, s);
+    if (g.N % 256 == 0 && g.M % 256 == 0 && (tune == 20 || (tune == 0 && tiles256 >= 256 && g.K >= 256))) return launch_pipe2<256, 256, 4, EPI, 8, 1>(g, s);
     if (tune == 21) return launch_pipe2<256, 128, 3, EPI, 4, 2>(g, s);
   }
   if (tune == 23) return launch_pipe2<128, 128, 4, EPI, 4, 2>(g, s);
