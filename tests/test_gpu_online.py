@@ -171,7 +171,8 @@ def test_online_gradients_bf16_two_tiles():
     _grad_check("bf16", 130, 16, 32, 128, seed=6, tol=3e-2)
 
 
-@pytest.mark.parametrize("dtype,B,T,D,H,n", [("f32", 5, 8, 16, 64, 5 * 60 + 3), ("bf16", 9, 8, 32, 64, 9 * 70), ("bf16", 70, 8, 32, 64, 70 * 40 + 11)])
+@pytest.mark.parametrize("dtype,B,T,D,H,n", [("f32", 5, 8, 16, 64, 5 * 60 + 3), ("bf16", 9, 8, 32, 64, 9 * 70), ("bf16", 70, 8, 32, 64, 70 * 40 + 11),
+                                            ("bf16", 7, 32, 32, 64, 7 * 80 + 3)])  # T = 32: the tables-in-LDS window kernel with adapting weights
 def test_online_round_trip_and_size(dtype, B, T, D, H, n):
     need_gpu()
     g, o, _ = make_pair(B, T, D, H, dtype, seed=8, update_mode=1, std=0.05, lr=2e-3)

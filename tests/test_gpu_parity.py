@@ -149,6 +149,14 @@ def test_step_parity_bf16_small(B):
     _step_parity(B, 8, 32, 64, "bf16", steps=11, randomize=True, seed=B)
 
 
+@pytest.mark.parametrize("B,T", [(5, 32), (7, 64), (67, 32)])
+def test_step_parity_bf16_window_kernel_with_tables_in_lds(B, T):
+    """T = 32 / 64 at D = 32: the window / cache / conv step runs as the kernel that keeps the per-symbol tables in LDS and
+    walks over streams (4 or 2 streams side by side per workgroup), here with a stream count that is no multiple of that
+    and, at step 1, masked streams that must not advance."""
+    _step_parity(B, T, 32, 64, "bf16", steps=4, randomize=True, seed=B + T)
+
+
 def test_step_parity_bf16_wide_cache():
     _step_parity(33, 16, 32, 128, "bf16", steps=4, randomize=True, seed=3)
 
@@ -293,6 +301,7 @@ def test_step_parity_config5_full_batch_sampled():
 @pytest.mark.parametrize("dtype,B,T,D,H,n", [
     ("bf16", 5, 8, 32, 64, 0), ("bf16", 5, 8, 32, 64, 3), ("bf16", 5, 8, 32, 64, 37), ("bf16", 5, 8, 32, 64, 1001),
     ("bf16", 70, 8, 32, 64, 70 * 40), ("f32", 16, 32, 16, 128, 16 * 50 + 5),
+    ("bf16", 7, 32, 32, 64, 7 * 90 + 5),   # T = 32: tables-in-LDS window kernel, a last stream that ends early
 ])
 def test_round_trip_and_size_vs_oracle(dtype, B, T, D, H, n):
     need_gpu()
