@@ -138,12 +138,15 @@ __device__ __forceinline__ void slot_pair(const float *xt, const float *Wg, cons
 // Three stages, so that the caller can put its own loads of the same depth beside each: the window's symbols, the operand
 // pieces they address, then the arithmetic. No load sits behind a branch (the compiler ends such a branch by waiting for
 // every load in flight): indices are clamped into the arrays and pieces that do not exist are zeroed afterwards.
+// K steps of Eq. 4 that carry data: two per tap (D = 32); K_c may be padded beyond that with zero rows, whose steps every
+// kernel here skips alike (they would add exact zeros)
+__device__ __forceinline__ int conv_ksteps(const EmbedArgs &a) { return a.Kc / 16 < 2 * a.taps ? a.Kc / 16 : 2 * a.taps; }
 // tile: which 32 tokens; af / bf: the K steps' operand pieces (ok[tap]: that tap's token exists); the 32 x 32 result passes
 // through the wavefront's own LDS patch (no workgroup barrier) so that a lane ends up with 16 consecutive channels of one
 // token (h: psi of the pre-activations p), 2 x 16 bytes per output, instead of 16 scattered 2-byte values
 template <int KS>
 __device__ __forceinline__ void conv_tile_compute(const EmbedArgs &a, const bf16x8 *af, const bool *ok, const bf16x8 *bf, float bias, bf16x8 *h, bf16x8 *p) {
-  const int lane = threadIdx.x & 63, ksteps = a.Kc / 16;
+  const int lane = threadIdx.x & 63, ksteps = conv_ksteps(a);
   f32x16 acc;
 #pragma unroll
   for (int e = 0; e < 16; ++e) acc[e] = 0.0f;
@@ -206,7 +209,7 @@ struct ConvWindow {
     }
   }
   __device__ __forceinline__ void operands(const EmbedArgs &a, const bf16_t *tabXl) {
-    const int lane = threadIdx.x & 63, ksteps = a.Kc / 16;  // K_c <= 128: at most 8 K steps, 2 per tap
+    const int lane = threadIdx.x & 63, ksteps = conv_ksteps(a);  // K_c <= 128: at most 8 K steps, 2 per tap
     const bf16x8 *Wf = static_cast<const bf16x8 *>(a.conv_W) + lane;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
@@ -345,7 +348,7 @@ __global__ __launch_bounds__(256) void embed_cache_lds_kernel(EmbedArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, B = a.B;
   const int wps = a.T / 32, grp = wave / wps, tile = wave - grp * wps, ngrp = 4 / wps;  // wavefronts per stream, streams per workgroup
   const int nt = wps * 64, vt = tid - grp * nt;                                          // threads per stream, this one's index
-  const int np = a.Dc / 8, sh = a.c / 8, ksteps = a.Kc / 16;
+  const int np = a.Dc / 8, sh = a.c / 8, ksteps = conv_ksteps(a);
   for (int i = tid; i < 1024; i += 256) {
     reinterpret_cast<f32x4 *>(sXe)[i] = static_cast<const f32x4 *>(a.tabXe)[i];
     reinterpret_cast<f32x4 *>(sXl)[i] = static_cast<const f32x4 *>(a.tabXl)[i];
@@ -1232,7 +1235,7 @@ hipError_t fade_embed_cache(const EmbedArgs &a, int B, bool bf16, hipStream_t s)
     const int ngrp = 4 / (a.T / 32), want = (B + ngrp - 1) / ngrp;
     const int G = want < 256 * per_cu ? want : 256 * per_cu;
     if (per_cu > 0) {
-      if (a.Kc <= 96) {
+      if (a.Kc <= 96 || a.taps <= 3) {
         if (frozen_shape) hipLaunchKernelGGL((embed_cache_lds_kernel<6, false>), dim3(G), dim3(256), 0, s, p);
         else hipLaunchKernelGGL((embed_cache_lds_kernel<6, true>), dim3(G), dim3(256), 0, s, p);
       } else {
@@ -1243,7 +1246,7 @@ hipError_t fade_embed_cache(const EmbedArgs &a, int B, bool bf16, hipStream_t s)
     }
   }
   if (!bf16) hipLaunchKernelGGL((embed_cache_kernel<float, 8, 4>), dim3(B), dim3(nt), 0, s, a);
-  else if (a.conv_W && a.Kc <= 96 && a.c % 8 == 0 && a.Dc / 8 <= nt) hipLaunchKernelGGL((embed_cache_kernel<bf16_t, 6, 1>), dim3(B), dim3(nt), 0, s, a);
+  else if (a.conv_W && (a.Kc <= 96 || a.taps <= 3) && a.c % 8 == 0 && a.Dc / 8 <= nt) hipLaunchKernelGGL((embed_cache_kernel<bf16_t, 6, 1>), dim3(B), dim3(nt), 0, s, a);
   else hipLaunchKernelGGL((embed_cache_kernel<bf16_t, 8, 4>), dim3(B), dim3(nt), 0, s, a);
   return hipGetLastError();
 }
