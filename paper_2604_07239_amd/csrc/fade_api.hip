@@ -344,9 +344,9 @@ int refresh_small(fade_ctx *c, ReduceBatch *pending = nullptr) {
   if (c->WT_mslot) padd(PREP_FRAG_T, c->P(P_WM) + (d.Dc - d.c) * d.Dh, d.c, d.c, d.Dh, c->WT_mslot);
   pb.has_tables = 1;  // same launch: the tables read the master embedding and round it as the copy above does
   pb.tab = TablesArgs{c->P(P_E), c->P(P_GAMMA_E), c->P(P_BETA_E), c->P(P_GAMMA_L), c->P(P_BETA_L), (int)d.D, 1, c->tabXe, c->tabXl, c->tabXe32,
-                      c->tabXhat, c->tabRstd};
+                      c->tabXhat, c->tabRstd, nullptr, nullptr, (int)d.c, c->slot_tab, c->gg_tab, c->gv_tab};
+  if (c->slot_tab || c->gg_tab) { pb.tab.Wg = c->P(P_WG); pb.tab.Wv = c->P(P_WV); }  // Eq. 1 per symbol rides along
   HIP_TRY(c, fade_prep_batch(pb, s));
-  if (c->slot_tab || c->gg_tab) HIP_TRY(c, fade_slot_table(c->tabXe32, c->Wg_c, c->Wv_c, (int)d.D, (int)d.c, c->slot_tab, c->gg_tab, c->gv_tab, s));
   return FADE_OK;
 }
 

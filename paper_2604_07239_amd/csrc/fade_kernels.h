@@ -115,6 +115,12 @@ struct TablesArgs {
   int D, round_bf16;       // round_bf16: E counts as its bf16 rounding (what the bf16 path's embedding copy holds)
   void *tabXe, *tabXl;     // bf16
   float *tabXe32, *tabXhat, *tabRstd;
+  // optional, same launch: Eq. 1 per symbol from the masters W_g, W_v [D][c] (rounded to bf16 as their compute copies are):
+  // slot_tab [256][c] bf16 entries (frozen weights) and / or gg_tab, gv_tab [256][c] fp32 pre-activations (adapting weights)
+  const float *Wg, *Wv;
+  int c;
+  void *slot_tab;
+  float *gg_tab, *gv_tab;
 };
 struct PrepBatch {
   PrepDesc d[20];
@@ -135,7 +141,6 @@ hipError_t fade_tables(const float *E, const float *ge, const float *be, const f
                        void *tabXl, float *tabXe32, float *tabXhat, float *tabRstd, bool bf16, hipStream_t s);
 hipError_t fade_embed_cache(const EmbedArgs &a, int B, bool bf16, hipStream_t s);
 hipError_t fade_embed_steps(const EmbedArgs &a, hipStream_t s);  // bf16, a.B * a.S rows, cache rebuilt from the window
-hipError_t fade_slot_table(const float *tabXe32, const float *Wg, const float *Wv, int D, int c, void *tab_bf16, float *gg_tab, float *gv_tab, hipStream_t s);
 hipError_t fade_encode_ranges(const WinSrc &ws, const uint2 *ranges, int B, int S, const CoderBufs &cb, hipStream_t s);
 hipError_t fade_bmm(const float *y, const void *WU, void *z, int B, bool bf16, hipStream_t s);
 hipError_t fade_softmax_quant_code(const SqcArgs &a, int mode, hipStream_t s);

@@ -114,6 +114,24 @@ __device__ __forceinline__ void tables_body(int s, const float *E, bool round_bf
   }
   if (i == 0 && tabRstd) tabRstd[s] = rstd;
 }
+// Eq. 1 for symbol s in the same workgroup: x = the row just formed (fp32, as tabXe32 holds it), W_g / W_v rounded to bf16 as
+// their compute copies are; slot_pair's order of operations, so the values are those that function gives from the copies.
+__device__ __forceinline__ void tables_slot_body(int s, const TablesArgs &t) {
+  __shared__ float xrow[256];
+  const int i = threadIdx.x;
+  __syncthreads();  // tabXe32's row of this symbol was written by this workgroup just above
+  if (i < t.D) xrow[i] = t.tabXe32[(size_t)s * t.D + i];
+  __syncthreads();
+  for (int q = i; q < t.c; q += 256) {
+    float gg = 0.0f, gv = 0.0f;
+    for (int k = 0; k < t.D; ++k) {
+      gg = fmaf(xrow[k], (float)(bf16_t)t.Wg[k * t.c + q], gg);
+      gv = fmaf(xrow[k], (float)(bf16_t)t.Wv[k * t.c + q], gv);
+    }
+    if (t.slot_tab) static_cast<bf16_t *>(t.slot_tab)[(size_t)s * t.c + q] = (bf16_t)(gelu_f(gg) * gv);
+    if (t.gg_tab) { t.gg_tab[(size_t)s * t.c + q] = gg; t.gv_tab[(size_t)s * t.c + q] = gv; }
+  }
+}
 template <typename AT>
 __global__ __launch_bounds__(256) void tables_kernel(const float *E, const float *ge, const float *be, const float *gl, const float *bl, int D,
                                                      AT *tabXe, AT *tabXl, float *tabXe32, float *tabXhat, float *tabRstd) {
@@ -465,18 +483,6 @@ __global__ __launch_bounds__(256) void embed_cache_lds_kernel(EmbedArgs a) {
   }
 }
 
-// Eq. 1 for every symbol: tab[sym][q] = psi(x W_g)[q] * (x W_v)[q], x = the symbol's embedded row (frozen weights), and / or
-// the two pre-activations themselves (adapting weights: the update needs them per stream). Outputs that are NULL are skipped.
-__global__ void slot_table_kernel(const float *tabXe32, const float *Wg, const float *Wv, int D, int c, bf16_t *tab, float *gg_tab, float *gv_tab) {
-  const int sym = blockIdx.x;
-  for (int q = threadIdx.x; q < c; q += blockDim.x) {
-    float gg, gv;
-    slot_pair(tabXe32 + (size_t)sym * D, Wg, Wv, D, c, q, gg, gv);
-    if (tab) tab[(size_t)sym * c + q] = (bf16_t)(gelu_f(gg) * gv);
-    if (gg_tab) { gg_tab[(size_t)sym * c + q] = gg; gv_tab[(size_t)sym * c + q] = gv; }
-  }
-}
-
 // Several steps of every stream in one launch (frozen weights, coding a known input): row r = s * B + b is stream b at
 // step i + s. The cache of Eq. 2 is rebuilt from the window instead of rolled: after step i, slot j holds the symbol
 // window[j]'s entry of Eq. 1, provided the model already ran at the step that appended it (steps before T code under the
@@ -712,9 +718,11 @@ __global__ __launch_bounds__(256) void residual_add_kernel(const bf16_t *x, cons
 __global__ __launch_bounds__(256) void prep_batch_kernel(PrepBatch pb) {
   if ((int)blockIdx.y == pb.count) {  // the per-symbol tables: workgroup x = symbol x
     const TablesArgs &t = pb.tab;
-    if (blockIdx.x < 256)
+    if (blockIdx.x < 256) {
       tables_body<bf16_t>(blockIdx.x, t.E, t.round_bf16 != 0, t.ge, t.be, t.gl, t.bl, t.D, static_cast<bf16_t *>(t.tabXe), static_cast<bf16_t *>(t.tabXl),
                           t.tabXe32, t.tabXhat, t.tabRstd);
+      if (t.Wg) tables_slot_body(blockIdx.x, t);
+    }
     return;
   }
   const PrepDesc &d = pb.d[blockIdx.y];
@@ -1264,11 +1272,6 @@ __global__ void fill_u32_kernel(uint32_t *dst, uint32_t value, size_t n) {
 hipError_t fade_fill_u32(uint32_t *dst, uint32_t value, size_t n, hipStream_t s) {
   if (!n) return hipSuccess;
   hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, dst, value, n);
-  return hipGetLastError();
-}
-hipError_t fade_slot_table(const float *tabXe32, const float *Wg, const float *Wv, int D, int c, void *tab_bf16, float *gg_tab, float *gv_tab, hipStream_t s) {
-  if (!gg_tab != !gv_tab) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(slot_table_kernel, dim3(256), dim3(64), 0, s, tabXe32, Wg, Wv, D, c, static_cast<bf16_t *>(tab_bf16), gg_tab, gv_tab);
   return hipGetLastError();
 }
 hipError_t fade_encode_ranges(const WinSrc &ws, const uint2 *ranges, int B, int S, const CoderBufs &cb, hipStream_t s) {
