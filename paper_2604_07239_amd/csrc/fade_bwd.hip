@@ -1028,14 +1028,17 @@ __global__ __launch_bounds__(256) void slot_conv_kernel(BwdSlotArgs sa, ConvGrad
 // terms are enough for bf16 inputs), so the result is an fp32-accurate sum in a fixed order. One workgroup owns a contiguous token range and leaves a
 // partial table [2][256][D]; wavefront w owns symbols 64 w .. 64 w + 63. V is staged row-major (16-byte pieces, permuted as
 // in the weight-gradient kernel) and read with the transposing LDS load.
-template <typename AT, int D>
-__global__ __launch_bounds__(256) void symbol_sums_mfma_kernel(BwdTokenArgs a, int per_block) {
+// NTH threads: wavefront w owns the 256 / (NTH / 64) symbols from 256 w / (NTH / 64) on (RT = 1 or 2 row tiles of 32).
+template <typename AT, int D, int NTH>
+__global__ __launch_bounds__(NTH) void symbol_sums_mfma_kernel(BwdTokenArgs a, int per_block) {
   typedef __attribute__((ext_vector_type(4))) short i16x4;
   typedef __attribute__((ext_vector_type(8))) short i16x8;
   typedef __attribute__((ext_vector_type(8))) unsigned short u16x8;
   constexpr int W2 = 2 * D, PITCH = W2 * 2, NT = W2 / 32, PPR = W2 / 8, CH = 128;
   // bf16 inputs: a sum of two bf16 values (plus, for one token in T, an fp32 term) is carried by two terms to 2^-17
   constexpr int NS = sizeof(AT) == 2 ? 2 : 3;
+  constexpr int RT = 8 / (NTH / 64);  // 32-symbol row tiles per wavefront
+  static_assert(NTH == 256 || NTH == 512, "threads");
   __shared__ __attribute__((aligned(16))) unsigned char vs[NS][CH * PITCH];
   __shared__ __attribute__((aligned(16))) unsigned short sym[CH];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -1044,9 +1047,9 @@ __global__ __launch_bounds__(256) void symbol_sums_mfma_kernel(BwdTokenArgs a, i
   long long t_end = t_begin + per_block;
   if (t_end > tokens) t_end = tokens;
   auto swz = [](int r) { return PITCH == 128 ? (((r >> 1) & 1) << 2) : 0; };
-  f32x16 acc[2][NT];
+  f32x16 acc[RT][NT];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < RT; ++i)
 #pragma unroll
     for (int j = 0; j < NT; ++j)
 #pragma unroll
@@ -1061,7 +1064,7 @@ __global__ __launch_bounds__(256) void symbol_sums_mfma_kernel(BwdTokenArgs a, i
   // global loads of chunk c + 1 are issued before the matrix work on chunk c (values wait in registers). The two big loads
   // of an item are issued without a branch (addresses clamped into the arrays, values masked when they are used): with the
   // loads inside `if (t < t_end)` the compiler waits for each item's loads before it issues the next item's.
-  constexpr int ITEMS = CH * PPR / 256;
+  constexpr int ITEMS = CH * PPR / NTH;
   Raw8B<AT> ra[ITEMS], rb[ITEMS];
   Raw8B<float> rc[ITEMS];
   unsigned short psym = 0xFFFF;
@@ -1078,7 +1081,7 @@ __global__ __launch_bounds__(256) void symbol_sums_mfma_kernel(BwdTokenArgs a, i
     }
 #pragma unroll
     for (int it = 0; it < ITEMS; ++it) {
-      const int item = tid + 256 * it, tl = item / PPR, col = (item % PPR) * 8;
+      const int item = tid + NTH * it, tl = item / PPR, col = (item % PPR) * 8;
       const long long t = c0 + tl < tokens ? c0 + tl : tokens - 1;
       const bool first = col < D;  // columns [0, D): dX1 + dX2 (+ dxt at the newest token); [D, 2 D): dxl
       const size_t g = (size_t)t * D + (first ? col : col - D);
@@ -1087,7 +1090,7 @@ __global__ __launch_bounds__(256) void symbol_sums_mfma_kernel(BwdTokenArgs a, i
     }
 #pragma unroll
     for (int it = 0; it < ITEMS; ++it) {
-      const int item = tid + 256 * it, tl = item / PPR, col = (item % PPR) * 8;
+      const int item = tid + NTH * it, tl = item / PPR, col = (item % PPR) * 8;
       const long long t = c0 + tl;
       rc[it].zero();
       // newest token of its stream: the cache-slot path ends here too
@@ -1099,7 +1102,7 @@ __global__ __launch_bounds__(256) void symbol_sums_mfma_kernel(BwdTokenArgs a, i
     __syncthreads();  // the previous chunk has been consumed
 #pragma unroll
     for (int it = 0; it < ITEMS; ++it) {
-      const int item = tid + 256 * it, tl = item / PPR, pc = item % PPR;
+      const int item = tid + NTH * it, tl = item / PPR, pc = item % PPR;
       float v[8], w[8], x[8];
       ra[it].cvt(v); rb[it].cvt(w); rc[it].cvt(x);
       const bool live = c0 + tl < t_end, both = live && pc * 8 < D;
@@ -1123,10 +1126,10 @@ __global__ __launch_bounds__(256) void symbol_sums_mfma_kernel(BwdTokenArgs a, i
 #pragma unroll 2
     for (int ks = 0; ks < CH / 16; ++ks) {
       const u16x8 sy = *reinterpret_cast<const u16x8 *>(sym + ks * 16 + (lane >> 5) * 8);
-      bf16x8 af[2];
+      bf16x8 af[RT];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const unsigned short s = (unsigned short)((wave * 2 + i) * 32 + (lane & 31));
+      for (int i = 0; i < RT; ++i) {
+        const unsigned short s = (unsigned short)((wave * RT + i) * 32 + (lane & 31));
 #pragma unroll
         for (int q = 0; q < 8; ++q) af[i][q] = sy[q] == s ? one : zero;
       }
@@ -1139,18 +1142,18 @@ __global__ __launch_bounds__(256) void symbol_sums_mfma_kernel(BwdTokenArgs a, i
           const i16x4 h4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)(p + 4 * PITCH));
           const bf16x8 bfr = __builtin_bit_cast(bf16x8, (i16x8)__builtin_shufflevector(l4, h4, 0, 1, 2, 3, 4, 5, 6, 7));
 #pragma unroll
-          for (int i = 0; i < 2; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr, acc[i][j], 0, 0, 0);
+          for (int i = 0; i < RT; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr, acc[i][j], 0, 0, 0);
         }
     }
   }
   float *out = a.part + (size_t)blockIdx.x * 2 * 256 * D;
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < RT; ++i)
 #pragma unroll
     for (int j = 0; j < NT; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const int s = (wave * 2 + i) * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3), n = j * 32 + (lane & 31);
+        const int s = (wave * RT + i) * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3), n = j * 32 + (lane & 31);
         out[((size_t)(n / D) * 256 + s) * D + (n % D)] = acc[i][j][e];
       }
 }
@@ -1451,12 +1454,14 @@ hipError_t fade_bwd_embed(const BwdTokenArgs &a, int nblocks, float *contrib, fl
   if (a.D != 16 && a.D != 32) return hipErrorInvalidValue;
   const long long tokens = (long long)a.B * a.T;
   const int per = (int)(((tokens + nblocks - 1) / nblocks + 127) / 128 * 128);  // whole 128-token chunks per workgroup
+  // D = 32 in bf16: eight wavefronts of one 32-symbol row tile each (twice the wavefronts per compute unit for the same
+  // number of partial tables; B = 16384: 96 -> 89 us)
   if (bf16) {
-    if (a.D == 32) hipLaunchKernelGGL((symbol_sums_mfma_kernel<bf16_t, 32>), dim3(nblocks), dim3(256), 0, s, a, per);
-    else hipLaunchKernelGGL((symbol_sums_mfma_kernel<bf16_t, 16>), dim3(nblocks), dim3(256), 0, s, a, per);
+    if (a.D == 32) hipLaunchKernelGGL((symbol_sums_mfma_kernel<bf16_t, 32, 512>), dim3(nblocks), dim3(512), 0, s, a, per);
+    else hipLaunchKernelGGL((symbol_sums_mfma_kernel<bf16_t, 16, 256>), dim3(nblocks), dim3(256), 0, s, a, per);
   } else {
-    if (a.D == 32) hipLaunchKernelGGL((symbol_sums_mfma_kernel<float, 32>), dim3(nblocks), dim3(256), 0, s, a, per);
-    else hipLaunchKernelGGL((symbol_sums_mfma_kernel<float, 16>), dim3(nblocks), dim3(256), 0, s, a, per);
+    if (a.D == 32) hipLaunchKernelGGL((symbol_sums_mfma_kernel<float, 32, 256>), dim3(nblocks), dim3(256), 0, s, a, per);
+    else hipLaunchKernelGGL((symbol_sums_mfma_kernel<float, 16, 256>), dim3(nblocks), dim3(256), 0, s, a, per);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
