@@ -941,21 +941,34 @@ __device__ __forceinline__ void conv_grad_mfma_body(const ConvGradArgs &a, int b
     for (int q = 0; q < 8; ++q) wt[ks][q] = (bf16_t)0.0f;
     if (ks < xsteps) wt[ks] = static_cast<const bf16x8 *>(a.WT)[(size_t)ks * 64 + lane];
   }
+  // The pieces of chunk c + 1 are requested before the matrix work on chunk c and waited for after it, BEFORE chunk c's
+  // stores: the counter of outstanding memory operations is in order and covers stores, and behind stores that sit in a
+  // branch the compiler's count for an older load is the pessimistic one, so a wait placed after the stores would also
+  // wait for them to be acknowledged. No branch around the loads: addresses clamped, tokens past the end zeroed at use.
+  f32x4 pxv[2], pdv[2];
+  auto request = [&](long long t0) {
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {  // 128 tokens x 4 pieces of 16 bytes, for each operand
+      const int e = tid + 256 * it, tl = e >> 2, pc = e & 3;
+      const long long t = t0 + tl < tokens ? t0 + tl : tokens - 1;
+      pxv[it] = *reinterpret_cast<const f32x4 *>(XL + (size_t)t * D + pc * 8);
+      pdv[it] = *reinterpret_cast<const f32x4 *>(dcv + (size_t)t * D + pc * 8);
+    }
+  };
+  if (block < nchunks) request((long long)block * 128);
   for (long long chunk = block; chunk < nchunks; chunk += nblocks) {
     const long long t0 = chunk * 128;
     __syncthreads();  // the zero fill, or the previous chunk's reads, are done
 #pragma unroll
-    for (int it = 0; it < 2; ++it) {  // 128 tokens x 4 pieces of 16 bytes, for each operand
+    for (int it = 0; it < 2; ++it) {
       const int e = tid + 256 * it, tl = e >> 2, pc = e & 3;
-      f32x4 xv = {0.0f, 0.0f, 0.0f, 0.0f}, dv = xv;
-      if (t0 + tl < tokens) {
-        xv = *reinterpret_cast<const f32x4 *>(XL + (size_t)(t0 + tl) * D + pc * 8);
-        dv = *reinterpret_cast<const f32x4 *>(dcv + (size_t)(t0 + tl) * D + pc * 8);
-      }
-      *reinterpret_cast<f32x4 *>(xs + (prow(tl) + pad) * PITCH + pc * 16) = xv;
-      *reinterpret_cast<f32x4 *>(ds + tl * PITCH + pc * 16) = dv;
+      const f32x4 zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+      const bool live = t0 + tl < tokens;
+      *reinterpret_cast<f32x4 *>(xs + (prow(tl) + pad) * PITCH + pc * 16) = live ? pxv[it] : zero4;
+      *reinterpret_cast<f32x4 *>(ds + tl * PITCH + pc * 16) = live ? pdv[it] : zero4;
     }
     __syncthreads();
+    request(chunk + nblocks < nchunks ? (chunk + nblocks) * 128 : t0);  // the last turn asks for its own chunk again
     if (wave < a.taps) {
 #pragma unroll 2
       for (int ks = 0; ks < 8; ++ks) {
@@ -984,6 +997,7 @@ __device__ __forceinline__ void conv_grad_mfma_body(const ConvGradArgs &a, int b
           accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, wt[ks], accx, 0, 0, 0);
         }
       }
+      asm volatile("s_waitcnt vmcnt(0)" : "+v"(pxv[0]), "+v"(pxv[1]), "+v"(pdv[0]), "+v"(pdv[1]), "+v"(accx) : : "memory");  // see above
       bf16_t *dxl = static_cast<bf16_t *>(a.dxl);
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
@@ -1009,8 +1023,10 @@ __global__ __launch_bounds__(256) void conv_grad_mfma_kernel(ConvGradArgs a) {
 // The newest-slot backward and the conv backward both start from what the mix backward left and feed the embedding
 // backward: independent, so one launch carries both. The first pconv workgroups take the conv part: each of them walks
 // many 128-token chunks, so they start first and the short slot workgroups fill in around them.
+// Three wavefronts per SIMD: the slot half's streams are one wavefront each and need the occupancy; without the bound the
+// conv half's prefetch registers take the kernel to two (136 us against 101-107; a bound of four spills and gives 108).
 template <int SPW, int KCH>
-__global__ __launch_bounds__(256) void slot_conv_kernel(BwdSlotArgs sa, ConvGradArgs ca, int pconv) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void slot_conv_kernel(BwdSlotArgs sa, ConvGradArgs ca, int pconv) {
   if ((int)blockIdx.x < pconv) conv_grad_mfma_body(ca, (int)blockIdx.x, pconv);
   else bwd_slot_body<bf16_t, SPW, KCH>(sa, (int)blockIdx.x - pconv);
 }
