@@ -38,8 +38,8 @@ MiB = 1 << 20
 # (FETCH x 2.0, WRITE x 1.0 against a plain 256 MiB copy, see profiles/cfg2_frozen_pmc_counters.md). A shape that
 # was not profiled reports null.
 ROUTER_GATE_TRAFFIC_BYTES = {
-    (16384, 2048, "frozen"): int(0.5 * (320.5 + 66.0 + 314.0 + 66.1) * MiB),   # profiles/cfg5_frozen_kernel_trace_and_hbm.md (cfg 2's 16-step passes have the same shape)
-    (16384, 2048, "online"): int(0.5 * (320.4 + 130.2 + 314.2 + 130.3) * MiB), # profiles/cfg5_online_kernel_trace_and_hbm.md
+    (16384, 2048, "frozen"): int(0.5 * (320.5 + 66.2 + 314.4 + 66.2) * MiB),   # profiles/cfg5_frozen_kernel_trace_and_hbm.md (cfg 2's 16-step passes have the same shape)
+    (16384, 2048, "online"): int(0.5 * (320.6 + 130.5 + 314.3 + 130.2) * MiB), # profiles/cfg5_online_kernel_trace_and_hbm.md
     (1024, 2048, "online"): int(0.5 * (56.4 + 53.5) * MiB),                    # profiles/cfg2_online_kernel_trace_and_hbm.md
 }
 # the same for the fp32 small-batch product (gemm_f32_rows_kernel) by (B, D_h, mode): profiles/cfg1_kernel_trace_and_hbm.md
