@@ -635,7 +635,8 @@ int forward_bf16(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uin
   // Frozen weights: nothing but the head reads H, so Eq. 10's tail is formed in the head product's operand load
   // (FADE_FUSE_HEAD=0 keeps the separate kernel; the update needs H itself for the head's weight gradient).
   static const bool fuse_head_env = !(getenv("FADE_FUSE_HEAD") && getenv("FADE_FUSE_HEAD")[0] == '0');
-  const bool fuse_head = level >= 5 && !c->online && fuse_head_env;
+  // with adapting weights the product also writes H (the head's weight gradient reads it); needs whole 32-row tiles
+  const bool fuse_head = level >= 5 && fuse_head_env && (!c->online || B % 32 == 0);
   if (level >= 5 && !fuse_head) {  // Eq. 10's tail
     feat = c->Hout;
     Prof p(c, "hout");
@@ -651,6 +652,7 @@ int forward_bf16(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uin
     g.A = feat; g.lda = Dh; g.W = c->Wo_c; g.C = c->part_head; g.ldc = 256;
     if (fuse_head) {
       g.A = c->V; g.A2 = c->Hc; g.stats = c->stats_o; g.stats_n = SN; g.gamma = c->P(P_GAMMA_O); g.beta = c->P(P_BETA_O); g.lam = c->P(P_LAMBDA_O);
+      if (c->online) g.C2 = c->Hout;
       HIP_TRY(c, fade_gemm(GEMM_HEAD, true, g, s));
     } else {
       HIP_TRY(c, fade_gemm(GEMM_PARTIAL, true, g, s));

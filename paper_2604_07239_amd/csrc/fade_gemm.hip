@@ -337,7 +337,10 @@ __device__ __forceinline__ bool tile_of_block(int bid, int ntm, int ntn, int cg,
 // ---------------------------------------------------------------------------------------------------
 // bf16 MFMA core
 // ---------------------------------------------------------------------------------------------------
-template <int WM, int WN, int TM, int TN, int PRO, int EPI>
+// KEEP (PRO_FINAL, M a multiple of the tile height): the operand formed on the fly, H of Eq. 10, is also written to C2
+// ([M][lda], the update needs it for the head's weight gradient). Its stores are unconditional and sit behind the request
+// for the block after next, so that no load ever waits for them (the memory counter is in order and covers stores).
+template <int WM, int WN, int TM, int TN, int PRO, int EPI, bool KEEP = false>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
   typedef bf16_t AT;
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = 64, LDA = BK + 8, PASSES = BM / 32, LDC = BN + 4;
@@ -383,6 +386,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
 
   Raw8<AT> ra[PASSES], ra2[PASSES];
   bf16x8 bcur[4][TN], bnext[4][TN];
+  bf16x8 hkeep[KEEP ? PASSES : 1];  // KEEP: the block's transformed values as they went to LDS
   // LayerNorm gain / shift of this thread's 8 columns of the block: requested with the block's rows, not when they are used
   constexpr bool kGB = PRO == PRO_LN || PRO == PRO_FINAL;
   float ga[kGB ? 8 : 1], be[kGB ? 8 : 1];
@@ -409,12 +413,37 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
       if constexpr (kGB) stage_transform_gb<PRO, AT>(ra[p], ra2[p], mean[p], rstd[p], lam, ga, be, v);
       else stage_transform<PRO, AT>(g, kb0 * BK + skc, ra[p], ra2[p], mean[p], rstd[p], lam, v);
       store8(dst, v);
+      if constexpr (KEEP) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) hkeep[p][q] = (bf16_t)v[q];
+      }
     }
+  }
+  auto request = [&](int kb_abs) {  // rows, gain / shift and W fragments of K block kb_abs
+    const int k1 = kb_abs * BK;
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) stage_load<PRO, AT>(g, m0 + p * 32 + srow, k1 + skc, ra[p], ra2[p]);
+    load_gb(k1 + skc);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) bnext[ks][j] = Wf[((size_t)j * ksteps + kb_abs * 4 + ks) * 64];
+  };
+  auto keep_store = [&](int kb_abs) {
+    if constexpr (KEEP) {
+#pragma unroll
+      for (int p = 0; p < PASSES; ++p)
+        *reinterpret_cast<bf16x8 *>(static_cast<AT *>(g.C2) + (size_t)(m0 + p * 32 + srow) * g.lda + kb_abs * BK + skc) = hkeep[p];
+    }
+  };
+  if constexpr (KEEP) {
+    if (nkb > 1) request(kb0 + 1);
+    keep_store(kb0);
   }
 
   for (int kb = 0; kb < nkb; ++kb) {
     const bool more = kb + 1 < nkb;
-    if (more) {
+    if (more && !KEEP) {
       const int k1 = (kb0 + kb + 1) * BK;
 #pragma unroll
       for (int p = 0; p < PASSES; ++p) stage_load<PRO, AT>(g, m0 + p * 32 + srow, k1 + skc, ra[p], ra2[p]);
@@ -451,12 +480,20 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
           if constexpr (kGB) stage_transform_gb<PRO, AT>(ra[p], ra2[p], mean[p], rstd[p], lam, ga, be, v);
           else stage_transform<PRO, AT>(g, k1 + skc, ra[p], ra2[p], mean[p], rstd[p], lam, v);
           store8(dst, v);
+          if constexpr (KEEP) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) hkeep[p][q] = (bf16_t)v[q];
+      }
         }
       }
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
         for (int j = 0; j < TN; ++j) bcur[ks][j] = bnext[ks][j];
+      if constexpr (KEEP) {
+        if (kb + 2 < nkb) request(kb0 + kb + 2);
+        keep_store(kb0 + kb + 1);
+      }
     }
   }
   if constexpr (EPI == EPI_PARTIAL) {
@@ -1410,13 +1447,14 @@ hipError_t launch_f32_rows(const GemmArgs &g, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <int WM, int WN, int TM, int TN, int PRO, int EPI>
+template <int WM, int WN, int TM, int TN, int PRO, int EPI, bool KEEP = false>
 hipError_t launch_bf16(const GemmArgs &g, hipStream_t s) {
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
   constexpr size_t lds_a = 2 * BM * (64 + 8) * sizeof(bf16_t), lds_c = (size_t)BM * (BN + 4) * sizeof(float);
   constexpr size_t lds = lds_a > lds_c ? lds_a : lds_c;
   static bool attr_done = false;
-  auto kern = gemm_bf16_kernel<WM, WN, TM, TN, PRO, EPI>;
+  auto kern = gemm_bf16_kernel<WM, WN, TM, TN, PRO, EPI, KEEP>;
+  if (KEEP && (g.M % BM || !g.C2)) return hipErrorInvalidValue;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
@@ -1717,6 +1755,7 @@ hipError_t fade_gemm(int op, bool bf16, const GemmArgs &g, hipStream_t s) {
       case GEMM_HEAD:     // head on H = psi(LN(V)) + lam * H_coarse formed in the operand load (Eq. 10's tail never goes to memory):
         // 32 rows x all 256 columns per workgroup (two workgroups per unit), so every row is transformed once; split-K partials as GEMM_PARTIAL leaves them
         if (!g.stats || !g.A2 || !g.gamma || !g.beta || !g.lam || g.N != 256) return hipErrorInvalidValue;
+        if (g.C2) return launch_bf16<1, 4, 1, 2, PRO_FINAL, EPI_PARTIAL, true>(g, s);  // H itself kept for the update
         return launch_bf16<1, 4, 1, 2, PRO_FINAL, EPI_PARTIAL>(g, s);
       default: return hipErrorInvalidValue;
     }
