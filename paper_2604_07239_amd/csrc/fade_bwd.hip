@@ -660,24 +660,28 @@ __global__ __launch_bounds__(256) void bwd_cci_kernel(BwdCciArgs a) {
   }
   __syncthreads();
   AT *Wc = static_cast<AT *>(a.WU_c) + (size_t)b * 4096;
-  {  // dy[k] = row k of W_U[b] dot dz: four threads per row, 16 columns each, combined in a fixed butterfly
-    const int k = tid >> 2, q = tid & 3;
-    float s = 0.0f;
-    float wr[16];
-    ld8<AT>(Wc + k * 64 + q * 16, wr);
-    ld8<AT>(Wc + k * 64 + q * 16 + 8, wr + 8);
+  {  // dy[k] = row k of W_U[b] dot dz. The compute copy W_U[b] is the master rounded to the activation type, and the master
+     // is in registers already (thread: rows 16 e + tid / 16, columns 4 (tid % 16) .. + 3): no second read of the matrix.
+     // 16 threads share a row: their partial sums are combined in a fixed butterfly.
+    const int n0 = (tid & 15) * 4;
 #pragma unroll
-    for (int n = 0; n < 16; ++n) s = fmaf(wr[n], dz_s[q * 16 + n], s);
-    s += __shfl_xor(s, 1, 64);
-    s += __shfl_xor(s, 2, 64);
-    if (q == 0) {
-      a.dy[(size_t)b * 64 + k] = s;
-      static_cast<AT *>(a.dy_at)[(size_t)b * 64 + k] = (AT)s;
+    for (int e = 0; e < 4; ++e) {
+      float s = 0.0f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) s = fmaf((float)(AT)w4[e][i], dz_s[n0 + i], s);
+      s += __shfl_xor(s, 1, 64);
+      s += __shfl_xor(s, 2, 64);
+      s += __shfl_xor(s, 4, 64);
+      s += __shfl_xor(s, 8, 64);
+      if ((tid & 15) == 0) {
+        const int k = e * 16 + (tid >> 4);
+        a.dy[(size_t)b * 64 + k] = s;
+        static_cast<AT *>(a.dy_at)[(size_t)b * 64 + k] = (AT)s;
+      }
     }
   }
   const UpdateState u = *a.u;
   if (u.na == 0) return;
-  __syncthreads();  // every read of the old W_U[b] is done before it is rewritten
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
     const int idx = (e * 256 + tid) * 4, k = idx >> 6, n = idx & 63;
