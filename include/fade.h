@@ -129,7 +129,10 @@ size_t fade_encode_bound(const fade_ctx *ctx, size_t n);
  * Frozen bf16 contexts take several consecutive steps of every stream per pass here and in fade_encode_device (the
  * model's steps are independent once the input is known); the container is byte for byte the one single steps write.
  * The steps per pass are fixed at fade_create (about 16384 / B, at most 256; environment variable
- * FADE_STEPS_PER_PASS overrides, 1 = single steps only) and size the context's activation buffers. */
+ * FADE_STEPS_PER_PASS overrides, 1 = single steps only) and size the context's activation buffers.
+ * The host-buffer calls (fade_encode, fade_decode, fade_payloads, fade_decode_device's payload upload) stage the job and
+ * the flat payloads in device buffers that belong to the context: allocated at the first call, grown when a later job is
+ * larger, released by fade_destroy; a context that codes job after job of one size allocates once. */
 int fade_encode(fade_ctx *ctx, const uint8_t *src_host, size_t n, uint8_t *dst_host, size_t dst_cap, size_t *dst_len);
 
 /* Inverse of fade_encode with the same configuration and weights (checked against the header). */

@@ -141,6 +141,10 @@ struct fade_ctx {
   bool own_stream = false;
   std::string err;
   std::vector<void *> allocs;
+  // staging of the host-buffer entry points (job bytes, flat payloads, payload offsets): grown on demand, kept until
+  // fade_destroy, so a context that codes job after job allocates once
+  void *stage[3] = {nullptr, nullptr, nullptr};
+  size_t stage_cap[3] = {0, 0, 0};
 
   bool have_weights = false;
   std::vector<float> loaded;
@@ -258,6 +262,26 @@ int dev_alloc_bytes(fade_ctx *c, void **p, size_t bytes) {
   int rc = dev_alloc(c, &q, bytes);
   *p = q;
   return rc;
+}
+
+// Staging buffer `slot` of at least `bytes` bytes (STAGE_*). A buffer that is too small is replaced (the stream is idle
+// between calls of the host-buffer entry points, which are the only users); contents are not kept.
+enum { STAGE_JOB = 0, STAGE_FLAT = 1, STAGE_OFF = 2 };
+int stage_buf(fade_ctx *c, int slot, size_t bytes, void **p) {
+  if (bytes == 0) bytes = 1;
+  if (c->stage_cap[slot] < bytes) {
+    if (c->stage[slot]) {
+      hipError_t e = hipStreamSynchronize(c->stream);
+      if (e != hipSuccess) return hip_fail(c, e, "hipStreamSynchronize");
+      (void)hipFree(c->stage[slot]);
+      c->stage[slot] = nullptr; c->stage_cap[slot] = 0;
+    }
+    hipError_t e = hipMalloc(&c->stage[slot], bytes);
+    if (e != hipSuccess) { c->stage[slot] = nullptr; return hip_fail(c, e, "hipMalloc(staging)"); }
+    c->stage_cap[slot] = bytes;
+  }
+  *p = c->stage[slot];
+  return FADE_OK;
 }
 
 // profiling: bracket a launch with two events on the context's stream
@@ -993,12 +1017,14 @@ int move_payloads(fade_ctx *c, uint32_t *lens_host, uint8_t *bytes_host, size_t 
   std::vector<unsigned long long> off(B);
   unsigned long long o = 0;
   for (size_t b = 0; b < B; ++b) { off[b] = o; o += lens_host[b]; }
-  unsigned long long *off_dev = nullptr;
-  uint8_t *flat = nullptr;
-  hipError_t e = hipMalloc(reinterpret_cast<void **>(&off_dev), B * sizeof(unsigned long long));
-  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&flat), total ? total : 1);
+  void *off_p = nullptr, *flat_p = nullptr;
+  int rc = stage_buf(c, STAGE_OFF, B * sizeof(unsigned long long), &off_p);
+  if (!rc) rc = stage_buf(c, STAGE_FLAT, total, &flat_p);
+  if (rc) return rc;
+  unsigned long long *off_dev = static_cast<unsigned long long *>(off_p);
+  uint8_t *flat = static_cast<uint8_t *>(flat_p);
   hipStream_t s = c->stream;
-  if (e == hipSuccess) e = hipMemcpyAsync(off_dev, off.data(), B * sizeof(unsigned long long), hipMemcpyHostToDevice, s);
+  hipError_t e = hipMemcpyAsync(off_dev, off.data(), B * sizeof(unsigned long long), hipMemcpyHostToDevice, s);
   if (e == hipSuccess && !gather) {
     e = hipMemcpyAsync(c->in_len, lens_host, B * sizeof(uint32_t), hipMemcpyHostToDevice, s);
     if (e == hipSuccess && total) e = hipMemcpyAsync(flat, bytes_host, total, hipMemcpyHostToDevice, s);
@@ -1006,8 +1032,6 @@ int move_payloads(fade_ctx *c, uint32_t *lens_host, uint8_t *bytes_host, size_t 
   if (e == hipSuccess) e = fade_payload_move(c->payload, c->payload_cap, flat, off_dev, gather ? c->cb.pos : c->in_len, (int)B, gather, s);
   if (e == hipSuccess && gather && total) e = hipMemcpyAsync(bytes_host, flat, total, hipMemcpyDeviceToHost, s);
   if (e == hipSuccess) e = hipStreamSynchronize(s);
-  (void)hipFree(off_dev);
-  (void)hipFree(flat);
   if (e != hipSuccess) return hip_fail(c, e, "payload transfer");
   return FADE_OK;
 }
@@ -1071,6 +1095,7 @@ void fade_destroy(fade_ctx *c) {
   if (c->stream) (void)hipStreamSynchronize(c->stream);
   for (auto &ev : c->events) { (void)hipEventDestroy(ev.a); (void)hipEventDestroy(ev.b); }
   for (void *p : c->allocs) (void)hipFree(p);
+  for (void *p : c->stage) if (p) (void)hipFree(p);
   if (c->own_stream && c->stream) (void)hipStreamDestroy(c->stream);
   delete c;
 }
@@ -1432,10 +1457,11 @@ int fade_encode(fade_ctx *c, const uint8_t *src_host, size_t n, uint8_t *dst_hos
   if (!c || (!src_host && n) || !dst_host || !dst_len) return FADE_E_INVALID_ARG;
   if (!c->have_weights) return fail(c, FADE_E_NO_WEIGHTS, "no weights loaded");
   const size_t B = c->d.B;
-  uint8_t *src_dev = nullptr;
-  hipError_t e = hipMalloc(reinterpret_cast<void **>(&src_dev), n ? n : 1);
-  if (e != hipSuccess) return hip_fail(c, e, "hipMalloc(src)");
-  int rc = FADE_OK;
+  void *src_p = nullptr;
+  int rc = stage_buf(c, STAGE_JOB, n, &src_p);
+  if (rc) return rc;
+  uint8_t *src_dev = static_cast<uint8_t *>(src_p);
+  hipError_t e = hipSuccess;
   std::vector<uint32_t> lens(B);
   size_t total = 0;
   do {
@@ -1461,7 +1487,6 @@ int fade_encode(fade_ctx *c, const uint8_t *src_host, size_t n, uint8_t *dst_hos
     size_t got = 0;
     rc = fade_payloads(c, lens.data(), dst_host + kHeaderBytes + 4 * B, dst_cap - kHeaderBytes - 4 * B, &got);
   } while (0);
-  (void)hipFree(src_dev);
   return rc;
 }
 
@@ -1492,12 +1517,13 @@ int fade_decode(fade_ctx *c, const uint8_t *src_host, size_t src_len, uint8_t *d
     total += lens[b];
   }
   if (total != body) return fail(c, FADE_E_CORRUPT_STREAM, "trailing bytes");
-  uint8_t *dst_dev = nullptr;
-  hipError_t e = hipMalloc(reinterpret_cast<void **>(&dst_dev), n ? n : 1);
-  if (e != hipSuccess) return hip_fail(c, e, "hipMalloc(dst)");
-  int rc = fade_decode_device(c, lens.data(), src_host + kHeaderBytes + 4 * B, total, dst_dev, n, 0, 0);
+  void *dst_p = nullptr;
+  int rc = stage_buf(c, STAGE_JOB, n, &dst_p);
+  if (rc) return rc;
+  uint8_t *dst_dev = static_cast<uint8_t *>(dst_p);
+  hipError_t e = hipSuccess;
+  rc = fade_decode_device(c, lens.data(), src_host + kHeaderBytes + 4 * B, total, dst_dev, n, 0, 0);
   if (!rc && n && (e = hipMemcpy(dst_host, dst_dev, n, hipMemcpyDeviceToHost)) != hipSuccess) rc = hip_fail(c, e, "download");
-  (void)hipFree(dst_dev);
   return rc;
 }
 

@@ -447,6 +447,21 @@ def test_round_trip_separate_cache_and_refiner_widths():
         g2.decode(c, n)                                    # another refiner width: refused
 
 
+def test_one_context_codes_jobs_of_different_sizes():
+    """The host-buffer calls stage jobs in buffers the context keeps and grows: a small, a larger and again a smaller job
+    on one context give the containers fresh contexts give, and every one round-trips."""
+    need_gpu()
+    B = 9
+    g, _, _ = make_pair(B, 8, 32, 64, "bf16", seed=5, std=0.05)
+    for n in (B * 20 + 1, B * 140 + 5, 0, B * 33):
+        src = fi.text(79 + n, n) if n else np.zeros(0, np.uint8)
+        c = g.encode(src)
+        fresh, _, _ = make_pair(B, 8, 32, 64, "bf16", seed=5, std=0.05)
+        assert c.tobytes() == fresh.encode(src).tobytes(), n
+        np.testing.assert_array_equal(g.decode(c, n), src)
+        np.testing.assert_array_equal(fresh.decode(c, n), src)
+
+
 def test_uniform_model_container_is_exact():
     """Zero head -> every table is f = 256: payload = the bytes + 0x40 per stream, identical to the oracle's."""
     need_gpu()
