@@ -197,6 +197,9 @@ struct fade_ctx {
   // weight gradients with few output tiles are left as partial sums over ranges of the batch (bf16 path): per parameter
   // tensor the number of ranges (1: none) and the slices [ranges][K][N]; the Adam pass adds them up
   int gsp[P_COUNT] = {};
+  // weight gradients on 256 x 256 tiles wait here until the end of the backward pass and run as one launch (defer_tn2)
+  Tn2Group tn2q{};
+  bool defer_tn2 = false;
   float *gpart[P_COUNT] = {};
   int sp_du = 1;            // ranges of K = 2 D_e in du = dE [W_fg W_fv]^T (bf16 path, wide refiners)
   float *du_part = nullptr;
@@ -761,7 +764,8 @@ int run_phase(fade_ctx *c, const char *name, const PhaseGemms &ph) {
       const GemmArgs &g = ph.g[i];
       const bool alone = (ph.op[i] == GEMM_X_STORE && g.N % 256 == 0 && g.K >= 1024 && ((g.M + 255) / 256) * (g.N / 256) >= 256) ||
                          (ph.op[i] == GEMM_W_TN && fade_gemm_tn2_ok(g.M, g.N, g.K));
-      if (alone) HIP_TRY(c, fade_gemm(ph.op[i], true, g, c->stream));
+      if (alone && ph.op[i] == GEMM_W_TN && c->defer_tn2) HIP_TRY(c, fade_gemm_tn2_group_add(c->tn2q, g));  // launched at the end of the pass
+      else if (alone) HIP_TRY(c, fade_gemm(ph.op[i], true, g, c->stream));
       else HIP_TRY(c, fade_gemm_group_add(gg, ph.op[i], g));
     }
     HIP_TRY(c, fade_gemm_group_launch(gg, c->stream));
@@ -787,6 +791,7 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
   auto Gp = [&](int id) { return G + c->lay.off[id]; };
   const int RB = (B + fade_rows_per_block(B) - 1) / fade_rows_per_block(B);
   ReduceBatch rq{};  // second-stage reductions nothing in here waits for: one launch before Adam
+  c->tn2q.count = 0;
   int rc;
   // ablation level: the head's gradient enters the chain at the level's feature vector; the stages behind it do not run
   // and their parameters keep a zero gradient (their Adam step is then exactly zero)
@@ -966,6 +971,11 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
   // pass leaves the partial sums of the folded-LayerNorm vectors), then one launch for every pending column sum (vectors,
   // scalars, biases and the small tensors get their Adam step right where their gradient sums are finished), then the small
   // operand copies and the per-symbol tables
+  if (c->tn2q.count > 0) {  // the weight gradients that waited: their operands are activations and gradients of this pass, all still in place
+    Prof p(c, "gemms_weights");
+    HIP_TRY(c, fade_gemm_tn2_group_launch(c->tn2q, s));
+    c->tn2q.count = 0;
+  }
   {
     Prof p(c, "adam_matrices");
     if ((rc = refresh_matrices(c, true))) return rc;
@@ -1273,11 +1283,33 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
       const struct { int id, pair, M, N; } gw[] = {{P_WO, -1, (int)d.Dh, 256}, {P_WF, -1, (int)d.De, (int)d.Dh}, {P_WFG, P_WFV, (int)d.Dh, (int)(2 * d.De)},
                                                     {P_WDOWN, -1, (int)d.Dh, (int)d.dl}, {P_WUP, -1, (int)d.dl, (int)d.Dh}, {P_WM, -1, (int)d.Dc, (int)d.Dh},
                                                     {P_WC, -1, (int)d.Dh, (int)d.Dh}, {P_WR, -1, (int)d.Dh, (int)d.Dh}};
+      // Weight gradients on 256 x 256 tiles feed nothing but the optimiser: with two or more of them they wait for the end
+      // of the backward pass and run as ONE launch with the same number of ranges of the batch for every matrix, so that
+      // all workgroups are equally long; the count is the smallest that gives at least two workgroups per compute unit
+      // and wastes least of the last round (D_h = 2048, D_e = D_cache = 512, B = 16384: 192 tiles x 4 ranges = 3 rounds of
+      // 256, 192 MiB of slices for the Adam pass to add up; launched one by one, with 4 / 8 / 16 ranges until each launch
+      // had 256 workgroups: 320 MiB). FADE_TN2_DEFER=0 keeps the launches apart.
+      int tn2_total = 0, tn2_count = 0, tn2_sp = 0;
+      for (const auto &w : gw)
+        if (fade_gemm_tn2_ok(w.M, w.N, (int)Bp)) { tn2_total += (w.M / 256) * (w.N / 256); ++tn2_count; }
+      const char *defer_env = getenv("FADE_TN2_DEFER");
+      if (tn2_count >= 2 && tn2_count <= 8 && !(defer_env && defer_env[0] == '0')) {
+        const int nkb = (int)(Bp / 64);
+        double best = 0.0;
+        for (int sp = 1; sp <= 16; sp *= 2) {
+          if (nkb % sp || nkb / sp < 8 || tn2_total * sp < 512) continue;
+          const int blocks = tn2_total * sp;
+          const double fill = (double)blocks / (((blocks + 255) / 256) * 256);
+          if (fill > best + 1e-9) { best = fill; tn2_sp = sp; }
+        }
+        c->defer_tn2 = tn2_sp > 0;
+      }
       for (const auto &w : gw) {
         if (fade_gemm_tn2_ok(w.M, w.N, (int)Bp)) {  // 256 x 256 tiles, one workgroup per compute unit: ranges until every unit has one
           const int tiles256 = (w.M / 256) * (w.N / 256), nkb = (int)(Bp / 64);
           int sp = 1;
-          while (sp < 16 && tiles256 * sp * 2 <= 256 && nkb % (sp * 2) == 0 && nkb / (sp * 2) >= 8) sp *= 2;
+          if (c->defer_tn2) sp = tn2_sp;
+          else while (sp < 16 && tiles256 * sp * 2 <= 256 && nkb % (sp * 2) == 0 && nkb / (sp * 2) >= 8) sp *= 2;
           if (sp > 1) {
             c->gsp[w.id] = sp;
             TRY_ALLOC(dev_alloc(c, &c->gpart[w.id], (size_t)sp * c->lay.len[w.id]));

@@ -96,6 +96,16 @@ struct GemmGroup {
   GemmArgs g[4];
 };
 
+// Weight gradients on 256 x 256 tiles (gemm_tn2_kernel's body) of several matrices in ONE launch: blocks [first_block[p],
+// first_block[p + 1]) are the tiles[p] x splits[p] workgroups of product p. A weight gradient feeds nothing but the
+// optimiser, so the products of a whole backward pass can wait for its end; with one range count for all of them the
+// workgroups are equally long and fill whole rounds of the chip.
+struct Tn2Group {
+  int count;
+  int splits[8], first_block[9];
+  GemmArgs g[8];
+};
+
 // Row statistics are accumulated per block tile of BN columns; consumers add the partials in index order.
 #define FADE_STATS_BN 128
 

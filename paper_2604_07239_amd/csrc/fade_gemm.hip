@@ -1184,14 +1184,22 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmArgs g) {
 // Workgroups go to the eight XCDs round-robin and each XCD has its own L2: an XCD takes whole units of eight workgroups,
 // a unit being a block of 2 x 4 tiles of one range of the batch (2 + 4 operand panels for 8 tiles; one row or column of
 // tiles would need 1 + 8).
-__global__ __launch_bounds__(512, 1) void gemm_tn2_kernel(GemmArgs g, int nsplit) {
-  const int ntm = g.M / 256, ntn = g.N / 256, tiles = ntm * ntn, bid = (int)blockIdx.x;
+__device__ __forceinline__ void tn2_block(const GemmArgs &g, int bid, int nsplit) {
+  const int ntm = g.M / 256, ntn = g.N / 256, tiles = ntm * ntn;
   if (ntm % 2 == 0 && ntn % 4 == 0 && (tiles / 8 * nsplit) % 8 == 0) {
     const int x = bid & 7, r = bid >> 3, u = x + 8 * (r >> 3), w = r & 7, U = tiles / 8, b = u % U, split = u / U;
     tn_body<256, 256, 2, 8>(g, 0, split, nsplit, (b / (ntn / 4)) * 2 + (w >> 2), (b % (ntn / 4)) * 4 + (w & 3));
   } else {
     tn_body<256, 256, 2, 8>(g, bid % tiles, bid / tiles, nsplit);
   }
+}
+__global__ __launch_bounds__(512, 1) void gemm_tn2_kernel(GemmArgs g, int nsplit) { tn2_block(g, (int)blockIdx.x, nsplit); }
+// The same for several matrices in one launch (Tn2Group): every product's first block is a multiple of 8, so a block's
+// position within its product goes to the same XCD as in a launch of its own.
+__global__ __launch_bounds__(512, 1) void gemm_tn2_group_kernel(Tn2Group tg) {
+  int p = 0;
+  while (p + 1 < tg.count && (int)blockIdx.x >= tg.first_block[p + 1]) ++p;
+  tn2_block(tg.g[p], (int)blockIdx.x - tg.first_block[p], tg.splits[p]);
 }
 
 // Several independent products in ONE launch (a block-uniform switch picks the problem and its kernel body): the products
@@ -1536,6 +1544,32 @@ hipError_t launch_tn2(const GemmArgs &g, hipStream_t s) {
   hipLaunchKernelGGL(gemm_tn2_kernel, dim3((g.M / 256) * (g.N / 256) * splits), dim3(512), lds, s, g, splits);
   return hipGetLastError();
 }
+
+}  // namespace
+hipError_t fade_gemm_tn2_group_add(Tn2Group &tg, const GemmArgs &g) {
+  const int splits = g.splits > 1 ? g.splits : 1;
+  if (tg.count >= 8 || !fade_gemm_tn2_ok(g.M, g.N, g.K) || g.K % (splits * 64) || g.a_rows <= 0 || g.a_rows > g.K || g.lda % 8 || g.ldb % 8)
+    return hipErrorInvalidValue;
+  const int p = tg.count, blocks = (g.M / 256) * (g.N / 256) * splits;
+  if (p == 0) tg.first_block[0] = 0;
+  if (tg.first_block[p] % 8) return hipErrorInvalidValue;  // keeps every product's blocks on the XCDs a launch of its own would use
+  tg.g[p] = g; tg.splits[p] = splits; tg.first_block[p + 1] = tg.first_block[p] + blocks;
+  tg.count = p + 1;
+  return hipSuccess;
+}
+hipError_t fade_gemm_tn2_group_launch(const Tn2Group &tg, hipStream_t s) {
+  if (tg.count <= 0) return hipSuccess;
+  constexpr size_t lds = (size_t)2 * 64 * (256 + 256) * 2;
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_tn2_group_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  hipLaunchKernelGGL(gemm_tn2_group_kernel, dim3(tg.first_block[tg.count]), dim3(512), lds, s, tg);
+  return hipGetLastError();
+}
+namespace {
 
 template <int BM, int BN, int STAGES, int EPI, int NW, int WPU>
 hipError_t launch_pipe2(const GemmArgs &g, hipStream_t s) {

@@ -18,6 +18,8 @@ bool fade_gemm_tn2_ok(int M, int N, int K);  // dW[M][N] over a batch of K rows 
 int fade_gemm_tn_tiles(int M, int N);  // workgroups per batch range of a grouped weight-gradient product dW[M][N]; 0: shape not supported
 hipError_t fade_gemm_group_add(GemmGroup &gg, int op, const GemmArgs &g);
 hipError_t fade_gemm_group_launch(const GemmGroup &gg, hipStream_t s);
+hipError_t fade_gemm_tn2_group_add(Tn2Group &tg, const GemmArgs &g);  // g as for GEMM_W_TN with fade_gemm_tn2_ok(g.M, g.N, g.K)
+hipError_t fade_gemm_tn2_group_launch(const Tn2Group &tg, hipStream_t s);
 
 enum { CODE_NONE = 0, CODE_ENCODE = 1, CODE_DECODE = 2, CODE_RANGES = 3 };  // CODE_RANGES: leave each row's coding interval for a later pass
 
