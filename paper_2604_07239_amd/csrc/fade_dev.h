@@ -102,6 +102,7 @@ struct GemmGroup {
 // workgroups are equally long and fill whole rounds of the chip.
 struct Tn2Group {
   int count;
+  int near;  // an XCD's units are consecutive ones (see tn2_block)
   int splits[8], first_block[9];
   GemmArgs g[8];
 };

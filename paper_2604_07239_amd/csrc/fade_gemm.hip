@@ -1184,22 +1184,27 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmArgs g) {
 // Workgroups go to the eight XCDs round-robin and each XCD has its own L2: an XCD takes whole units of eight workgroups,
 // a unit being a block of 2 x 4 tiles of one range of the batch (2 + 4 operand panels for 8 tiles; one row or column of
 // tiles would need 1 + 8).
-__device__ __forceinline__ void tn2_block(const GemmArgs &g, int bid, int nsplit) {
+// near: an XCD's units are consecutive ones (unit = tile block within a range, ranges outermost), so the units it runs
+// side by side are neighbouring tile blocks of one range and share operand panels in its L2 (D_h x D_h over four ranges:
+// an XCD's four units are 4 x 8 tiles of one range, 4 + 8 panels for 32 tiles instead of 4 x (2 + 4)).
+__device__ __forceinline__ void tn2_block(const GemmArgs &g, int bid, int nsplit, bool near) {
   const int ntm = g.M / 256, ntn = g.N / 256, tiles = ntm * ntn;
   if (ntm % 2 == 0 && ntn % 4 == 0 && (tiles / 8 * nsplit) % 8 == 0) {
-    const int x = bid & 7, r = bid >> 3, u = x + 8 * (r >> 3), w = r & 7, U = tiles / 8, b = u % U, split = u / U;
+    const int x = bid & 7, r = bid >> 3, w = r & 7, U = tiles / 8;
+    const int u = near ? x * (U * nsplit / 8) + (r >> 3) : x + 8 * (r >> 3), b = u % U, split = u / U;
     tn_body<256, 256, 2, 8>(g, 0, split, nsplit, (b / (ntn / 4)) * 2 + (w >> 2), (b % (ntn / 4)) * 4 + (w & 3));
   } else {
     tn_body<256, 256, 2, 8>(g, bid % tiles, bid / tiles, nsplit);
   }
 }
-__global__ __launch_bounds__(512, 1) void gemm_tn2_kernel(GemmArgs g, int nsplit) { tn2_block(g, (int)blockIdx.x, nsplit); }
-// The same for several matrices in one launch (Tn2Group): every product's first block is a multiple of 8, so a block's
-// position within its product goes to the same XCD as in a launch of its own.
+__global__ __launch_bounds__(512, 1) void gemm_tn2_kernel(GemmArgs g, int nsplit) { tn2_block(g, (int)blockIdx.x, nsplit, false); }
+// The same for several matrices in one launch (Tn2Group). Where every product's block count is a multiple of 8 (all the
+// shapes of the benchmark configurations), a block's position within its product goes to the same XCD as in a launch of
+// its own; otherwise only the L2 reuse of the later products suffers.
 __global__ __launch_bounds__(512, 1) void gemm_tn2_group_kernel(Tn2Group tg) {
   int p = 0;
   while (p + 1 < tg.count && (int)blockIdx.x >= tg.first_block[p + 1]) ++p;
-  tn2_block(tg.g[p], (int)blockIdx.x - tg.first_block[p], tg.splits[p]);
+  tn2_block(tg.g[p], (int)blockIdx.x - tg.first_block[p], tg.splits[p], tg.near != 0);
 }
 
 // Several independent products in ONE launch (a block-uniform switch picks the problem and its kernel body): the products
@@ -1552,7 +1557,6 @@ hipError_t fade_gemm_tn2_group_add(Tn2Group &tg, const GemmArgs &g) {
     return hipErrorInvalidValue;
   const int p = tg.count, blocks = (g.M / 256) * (g.N / 256) * splits;
   if (p == 0) tg.first_block[0] = 0;
-  if (tg.first_block[p] % 8) return hipErrorInvalidValue;  // keeps every product's blocks on the XCDs a launch of its own would use
   tg.g[p] = g; tg.splits[p] = splits; tg.first_block[p + 1] = tg.first_block[p] + blocks;
   tg.count = p + 1;
   return hipSuccess;
@@ -1566,7 +1570,28 @@ hipError_t fade_gemm_tn2_group_launch(const Tn2Group &tg, hipStream_t s) {
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL(gemm_tn2_group_kernel, dim3(tg.first_block[tg.count]), dim3(512), lds, s, tg);
+  // the products with the most workgroups first: their blocks then start on a multiple of 256, and the units an XCD runs
+  // side by side belong to one product
+  Tn2Group o{};
+  o.count = tg.count;
+  int idx[8];
+  for (int p = 0; p < tg.count; ++p) idx[p] = p;
+  for (int i = 1; i < tg.count; ++i)
+    for (int j = i; j > 0; --j) {
+      const int a = idx[j - 1], b = idx[j];
+      if (tg.first_block[b + 1] - tg.first_block[b] <= tg.first_block[a + 1] - tg.first_block[a]) break;
+      idx[j - 1] = b; idx[j] = a;
+    }
+  o.first_block[0] = 0;
+  for (int p = 0; p < tg.count; ++p) {
+    const int q = idx[p];
+    o.g[p] = tg.g[q]; o.splits[p] = tg.splits[q];
+    o.first_block[p + 1] = o.first_block[p] + (tg.first_block[q + 1] - tg.first_block[q]);
+  }
+  static int near = -1;
+  if (near < 0) { const char *e = getenv("FADE_TN2_NEAR"); near = (e && e[0] == '0') ? 0 : 1; }
+  o.near = near;
+  hipLaunchKernelGGL(gemm_tn2_group_kernel, dim3(o.first_block[o.count]), dim3(512), lds, s, o);
   return hipGetLastError();
 }
 namespace {
