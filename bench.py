@@ -16,8 +16,7 @@ default run also measures the same steps with frozen weights (inference only) an
 
 Prints ONE JSON line (see the keys below); `roofline` describes the dominant kernel (the D_h x D_h router /
 gate product), timed with HIP events on the library's stream in a second pass over the same steps;
-`update_roofline` (online mode) does the same for the longest single launch of the update, the HBM-bound Adam pass over
-the nine big matrices; `cpu_baseline` times the CPU oracle on a bounded sample of the same workload.
+`update_roofline` (online mode) does the same for the HBM-bound Adam pass over the nine big matrices; `cpu_baseline` times the CPU oracle on a bounded sample of the same workload.
 """
 import argparse
 import json
@@ -38,15 +37,15 @@ MiB = 1 << 20
 # (FETCH x 2.0, WRITE x 1.0 against a plain 256 MiB copy, see profiles/cfg2_frozen_pmc_counters.md). A shape that
 # was not profiled reports null.
 ROUTER_GATE_TRAFFIC_BYTES = {
-    (16384, 2048, "frozen"): int(0.5 * (320.5 + 66.2 + 314.4 + 66.2) * MiB),   # profiles/cfg5_frozen_kernel_trace_and_hbm.md (cfg 2's 16-step passes have the same shape)
-    (16384, 2048, "online"): int(0.5 * (320.6 + 130.5 + 314.3 + 130.2) * MiB), # profiles/cfg5_online_kernel_trace_and_hbm.md
+    (16384, 2048, "frozen"): int(0.5 * (320.4 + 66.2 + 314.4 + 66.1) * MiB),   # profiles/cfg5_frozen_kernel_trace_and_hbm.md (cfg 2's 16-step passes have the same shape)
+    (16384, 2048, "online"): int(0.5 * (320.4 + 130.4 + 314.2 + 130.3) * MiB), # profiles/cfg5_online_kernel_trace_and_hbm.md
     (1024, 2048, "online"): int(0.5 * (56.4 + 53.5) * MiB),                    # profiles/cfg2_online_kernel_trace_and_hbm.md
 }
 # the same for the fp32 small-batch product (gemm_f32_rows_kernel) by (B, D_h, mode): profiles/cfg1_kernel_trace_and_hbm.md
 F32_ROUTER_GATE_TRAFFIC_BYTES = {(16, 512, "frozen"): int(0.5 * (2.46 + 0.05 + 2.40 + 0.05) * MiB), (16, 512, "online"): int(0.5 * (2.46 + 0.08 + 2.40 + 0.08) * MiB)}
 # adam_refresh_kernel by (parameters of the nine big matrices, mode), same counter runs
 ADAM_TRAFFIC_BYTES = {(11272192, "online"): int((171.59 + 167.46) * MiB),      # profiles/cfg2_online_kernel_trace_and_hbm.md
-                      (13369344, "online"): int((493.64 + 253.27) * MiB)}      # profiles/cfg5_online_kernel_trace_and_hbm.md
+                      (13369344, "online"): int((349.5 + 242.9) * MiB)}        # profiles/cfg5_online_kernel_trace_and_hbm.md
 
 
 def parse():
@@ -231,7 +230,7 @@ def main():
                         "traffic": F32_ROUTER_GATE_TRAFFIC_BYTES.get((B, Dh, mode)), "avg_us": round(us, 2), "algorithmic_bytes_per_launch": nbytes}
         update_roofline = None
         if "adam_matrices" in kern and spec["dtype"] == "bf16":
-            # the longest single launch of an online step: Adam on the nine big matrices fused with the refresh of their bf16
+            # the HBM-bound pass of the update over the shared weights: Adam on the nine big matrices fused with the refresh of their bf16
             # operand copies. Per parameter: gradient, both moments and the master weight read (16 B), moments and weight
             # written (12 B), one bf16 copy per orientation the products use (2 B each; W_m has one orientation only).
             P = 2 * Dh * Dh + 3 * Dh * De + Dc * Dh + 256 * Dh + 2 * dl * Dh
