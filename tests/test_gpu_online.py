@@ -247,40 +247,53 @@ def test_online_update_large_batch_launch_shapes(cfg):
     active; the oracle runs exactly those streams on their own W_U slices (the loss is the mean over the active streams on
     both sides, and masked streams contribute nothing), so every shared gradient, the active W_U gradients, the weights'
     effect on the next step's probabilities and the masked streams' untouched state can be compared."""
+    spec = fi.CONFIGS[cfg]
+    _large_batch_online_step(f"cfg{cfg}", cfg, spec["B"], spec["T"], spec["D"], spec["H"], fi.config_blob(cfg))
+
+
+def test_online_update_paper_default_shape_8192_streams():
+    """The same step for the paper's default model shape (T = 16, D = 32, cache 4096, refiner 8192) at B = 8192, the batch
+    the paper quotes its peak throughput at: from 8192 rows on the weight gradients on 256 x 256 tiles wait for the end of
+    the backward pass and run as one launch, here with another mix of matrices than configuration 5 has (W_f 32 x 2 tiles,
+    W_fg | W_fv 2 x 64, W_m 16 x 2; the D_h x D_h ones are too small for that tile) and another range count."""
+    spec = fi.CONFIGS[6]
+    B = 8192
+    blob = fi.init_blob(B, spec["T"], spec["D"], spec["H"], 1234, d_cache=spec["d_cache"], d_e=spec["d_e"])
+    _large_batch_online_step("paper-default shape", 6, B, spec["T"], spec["D"], spec["H"], blob, d_cache=spec["d_cache"], d_e=spec["d_e"])
+
+
+def _large_batch_online_step(label, cfg, B, T, D, H, blob, **widths):
     torch = need_gpu()
     import os
     import paper_2604_07239_amd as fa
-    spec = fi.CONFIGS[cfg]
-    B, T, D, H = spec["B"], spec["T"], spec["D"], spec["H"]
-    blob = fi.config_blob(cfg)
     idx = np.unique(np.linspace(0, B - 1, 256).astype(np.int64))
     act = np.zeros(B, np.uint8); act[idx] = 1
     os.environ["FADE_DEBUG_WU_GRAD"] = "1"
     try:
-        g = fa.Fade(fa.make_config(B, T, D, H, dtype=fa.BF16, update_mode=fa.ONLINE_ADAM))
+        g = fa.Fade(fa.make_config(B, T, D, H, dtype=fa.BF16, update_mode=fa.ONLINE_ADAM, **widths))
     finally:
         os.environ.pop("FADE_DEBUG_WU_GRAD", None)
     g.load_weights(blob.data)
-    sub = fi.Blob(len(idx), T, D, H)
+    sub = fi.Blob(len(idx), T, D, H, **widths)
     for name, _, _ in sub.specs:
         sub[name] = blob[name][idx] if name == "W_U" else blob[name]
-    o = orc.Oracle(orc.make_config(len(idx), T, D, H, dtype=orc.BF16, update_mode=orc.ONLINE_ADAM))
+    o = orc.Oracle(orc.make_config(len(idx), T, D, H, dtype=orc.BF16, update_mode=orc.ONLINE_ADAM, **widths))
     o.load_weights(sub.data)
     # the configuration's own kind of bytes (a 16 MiB prefix of its generator; for the mixed source that is text), one row per stream
     data = fi.config_bytes(cfg, 16 << 20)[:B * 1024].reshape(B, 1024)[:, 512:512 + T + 2]
     win = np.ascontiguousarray(data[:, :T]); tgt = np.ascontiguousarray(data[:, T])
     probs_d = torch.zeros((B, 256), dtype=torch.float32, device="cuda")
     ad = torch.from_numpy(act).cuda()
-    _log(f"cfg{cfg} online, B={B}, {len(idx)} active streams: forward")
+    _log(f"{label} online, B={B}, {len(idx)} active streams: forward")
     g.step_probs(torch.from_numpy(win).cuda(), ad, None, probs_d)
     _, po = o.step_probs(np.ascontiguousarray(win[idx]), None)
     assert np.abs(probs_d.cpu().numpy()[idx] - po).max() <= 1e-3
-    _log(f"cfg{cfg} online: oracle backward")
+    _log(f"{label} online: oracle backward")
     go = o.backward(np.ascontiguousarray(tgt[idx]), None)
-    _log(f"cfg{cfg} online: GPU update")
+    _log(f"{label} online: GPU update")
     g.step_update(torch.from_numpy(tgt).cuda(), ad)
     gg = g.debug_grad()
-    _compare_gradients(sub, _sub_view(blob, sub, gg, idx), go, 3e-2, f"cfg{cfg} full batch")
+    _compare_gradients(sub, _sub_view(blob, sub, gg, idx), go, 3e-2, f"{label} full batch")
     wu = blob.view(gg, "W_U")
     mask = np.ones(B, bool); mask[idx] = False
     assert not wu[mask].any()                                    # masked streams: no gradient
@@ -297,7 +310,7 @@ def test_online_update_large_batch_launch_shapes(cfg):
         if big.any():
             assert np.abs(a[big] - r[big]).max() <= 0.3e-3 + 1e-6, name
     win2 = np.ascontiguousarray(data[:, 1:T + 1])
-    _log(f"cfg{cfg} online: step after the update")
+    _log(f"{label} online: step after the update")
     g.step_probs(torch.from_numpy(win2).cuda(), ad, None, probs_d)
     _, po2 = o.step_probs(np.ascontiguousarray(win2[idx]), None)
     # After that step the two states differ wherever a gradient's sign lies within the path's error (2 lr apart), and on
@@ -305,7 +318,7 @@ def test_online_update_large_batch_launch_shapes(cfg):
     # probabilities by factors: the next step's probabilities agree within 1e-3 plus 5 % of the probability (the relative
     # bar the forward parity tests use), not within 1e-3 alone as from identical states (checked above).
     dp = np.abs(probs_d.cpu().numpy()[idx] - po2)
-    _log(f"cfg{cfg} online: after the update max |dp| {dp.max():.2e}, max p {po2.max():.3f}, max |dp| / (1e-3 + 0.05 p) {(dp / (1e-3 + 0.05 * po2)).max():.2f}")
+    _log(f"{label} online: after the update max |dp| {dp.max():.2e}, max p {po2.max():.3f}, max |dp| / (1e-3 + 0.05 p) {(dp / (1e-3 + 0.05 * po2)).max():.2f}")
     assert np.all(dp <= 1e-3 + 0.05 * po2)
     g.close()
 
