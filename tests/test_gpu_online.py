@@ -196,6 +196,27 @@ def test_online_is_deterministic():
     assert a.tobytes() == b.tobytes()
 
 
+def test_online_round_trip_8192_streams_is_exact_and_deterministic():
+    """Encoder and decoder must reach the same weights step by step: 8192 streams of configuration 5's model shape, where
+    the weight gradients on 256 x 256 tiles run as one launch at the end of the backward pass. Twelve updates each way;
+    the container is the same on a second encode and decodes to the input."""
+    need_gpu()
+    import paper_2604_07239_amd as fa
+    spec = fi.CONFIGS[5]
+    B, T, D, H = 8192, spec["T"], spec["D"], spec["H"]
+    blob = fi.config_blob(5, B)
+    g = fa.Fade(fa.make_config(B, T, D, H, dtype=fa.BF16, update_mode=fa.ONLINE_ADAM))
+    g.load_weights(blob.data)
+    n = B * (T + 12) - 5                                   # a last stream that ends early
+    src = fi.config_bytes(5, 16 << 20)[:n]
+    _log(f"online round trip B={B} n={n}")
+    a = g.encode(src)
+    np.testing.assert_array_equal(g.decode(a, n), src)
+    b = g.encode(src)                                      # every encode starts from the loaded weights and a zero optimiser state
+    assert a.tobytes() == b.tobytes()
+    g.close()
+
+
 def test_online_update_config2_full_batch():
     """Configuration 2 at its full B = 1024 (the launch shapes bench.py times): one online step from identical states.
     The shared-weight gradient couples all streams, so the oracle runs the whole batch once (about half a minute on one
