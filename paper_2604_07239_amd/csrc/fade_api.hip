@@ -913,7 +913,7 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     BwdMixArgs a{};
     a.B = B; a.Dh = Dh; a.stats_n = SN; a.ln_part = c->ln_part + (size_t)RB * 4 * Dh; a.dnc = level >= 3 ? c->dnc : nullptr; a.Hmix = c->Hmix; a.dHmix1 = c->dHmix1;
     a.dHmix2 = level >= 4 ? c->dHmix2 : nullptr; a.alpha = level >= 2 ? c->alpha : nullptr;
-    a.Hg = c->Hg; a.Hl = c->Hl; a.hm = c->hm; a.cv = c->cv; a.X = c->X; a.stats = c->stats_c; a.gamma = c->P(P_GAMMA_C);
+    a.hm = c->hm; a.cv = c->cv; a.X = c->X; a.stats = c->stats_c; a.gamma = c->P(P_GAMMA_C);
     a.lam = c->P(P_LAMBDA_M); a.dar = c->dar; a.dhm = c->dhm; a.dcv = c->dcv; a.dX = c->dX1; a.row_dlam = c->row_dlam + 2 * B;
     HIP_TRY(c, fade_bwd_mix(a, bf, s));
     if (level >= 3) rq.push(RB, 2 * Dh, c->ln_part + (size_t)RB * 4 * Dh, Gp(P_GAMMA_C));

@@ -492,6 +492,8 @@ __global__ __launch_bounds__(256) void bwd_gate_kernel(BwdGateArgs a) {
   }
 }
 
+// The two branch outputs are not read back: H_g = psi(hm) + lambda_m X and H_l = psi(cv) follow from the pre-activations
+// and X, which the kernel reads anyway, and psi shares Phi and the Gaussian with psi' (two of ten row reads less).
 // LN (Eq. 7) backward into dH_mix (+ the gate path's contribution), then Eq. 5-6 and the branch activations:
 // dHg = dmix a, dHl = dmix (1-a), d(router logits) = dmix (Hg - Hl) a (1-a), d(global pre-act) = dHg psi'(hm),
 // d(conv pre-act) = dHl psi'(cv), dX = lambda_m dHg, row part of d lambda_m.
@@ -547,15 +549,13 @@ __global__ __launch_bounds__(256) void bwd_mix_kernel(BwdMixArgs a) {
     if (b < a.B && mine) {
       const size_t base = (size_t)b * a.Dh + tid * 8;
       const float m1 = sums[r] / (float)a.Dh, m2 = sums[R + r] / (float)a.Dh;
-      float d1[8], d2[8], al[8], hg[8], hl[8], pre_g[8], pre_c[8], x[8], dar[8], dhm[8], dcv[8], dX[8];
+      float d1[8], d2[8], al[8], pre_g[8], pre_c[8], x[8], dar[8], dhm[8], dcv[8], dX[8];
       ld8<AT>(static_cast<const AT *>(a.dHmix1) + base, d1);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) { d2[i] = 0.0f; al[i] = 1.0f; hg[i] = 0.0f; hl[i] = 0.0f; pre_c[i] = 0.0f; }
+      for (int i = 0; i < 8; ++i) { d2[i] = 0.0f; al[i] = 1.0f; pre_c[i] = 0.0f; }
       if (a.dHmix2) ld8<AT>(static_cast<const AT *>(a.dHmix2) + base, d2);
       if (a.alpha) {
         ld8<AT>(static_cast<const AT *>(a.alpha) + base, al);
-        ld8<AT>(static_cast<const AT *>(a.Hg) + base, hg);
-        ld8<AT>(static_cast<const AT *>(a.Hl) + base, hl);
         ld8<AT>(static_cast<const AT *>(a.cv) + base, pre_c);
       }
       ld8<AT>(static_cast<const AT *>(a.hm) + base, pre_g);
@@ -564,9 +564,11 @@ __global__ __launch_bounds__(256) void bwd_mix_kernel(BwdMixArgs a) {
       for (int i = 0; i < 8; ++i) {
         const float d = d1[i] + d2[i] + rstd[r] * (dh[r][i] - m1 - xh[r][i] * m2);
         const float dHg = d * al[i], dHl = d * (1.0f - al[i]);
-        dar[i] = d * (hg[i] - hl[i]) * al[i] * (1.0f - al[i]);
-        dhm[i] = dHg * gelu_grad_f(pre_g[i]);
-        dcv[i] = dHl * gelu_grad_f(pre_c[i]);
+        float grad_g, grad_c;
+        const float hg = fmaf(lam, x[i], fade_gelu_both(pre_g[i], grad_g)), hl = fade_gelu_both(pre_c[i], grad_c);
+        dar[i] = d * (hg - hl) * al[i] * (1.0f - al[i]);
+        dhm[i] = dHg * grad_g;
+        dcv[i] = dHl * grad_c;
         dX[i] = lam * dHg;
         sl[r] += dHg * x[i];
       }

@@ -187,4 +187,11 @@ __device__ __forceinline__ float fade_gelu_grad(float x) {  // psi'(x) = Phi(x) 
   const float cdf = fade_norm_cdf(x, g);
   return fmaf(x * 0.3989422804014327f, g, cdf);
 }
+// psi(x) and psi'(x) from one evaluation of Phi and the Gaussian
+__device__ __forceinline__ float fade_gelu_both(float x, float &grad) {
+  float g;
+  const float cdf = fade_norm_cdf(x, g);
+  grad = fmaf(x * 0.3989422804014327f, g, cdf);
+  return x * cdf;
+}
 __device__ __forceinline__ float fade_sigmoid(float x) { return __builtin_amdgcn_rcpf(1.0f + fade_exp(-x)); }

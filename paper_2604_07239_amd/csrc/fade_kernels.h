@@ -216,7 +216,7 @@ struct BwdMixArgs {
   int B, Dh, stats_n;
   int groups;  // row groups per workgroup (set by the launcher)
   float *ln_part;
-  const void *dnc, *Hmix, *dHmix1, *dHmix2, *alpha, *Hg, *Hl, *hm, *cv, *X;
+  const void *dnc, *Hmix, *dHmix1, *dHmix2, *alpha, *hm, *cv, *X;  // hm, cv: pre-activations of the global / local stream
   const float *stats, *gamma, *lam;
   void *dar, *dhm, *dcv, *dX;
   float *row_dlam;

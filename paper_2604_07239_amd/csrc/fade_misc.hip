@@ -265,7 +265,7 @@ __global__ __launch_bounds__(256) void embed_cache_kernel(EmbedArgs a) {
   const int np = a.Dc / V, sh = a.c / V, nx = a.Dh / V;
   const bool conv_live = sizeof(AT) == 2 && a.conv_W && (tid >> 6) * 32 < a.T;
   const int tile = conv_live ? tid >> 6 : 0;
-  // round 1
+  // first batch of loads: window symbols and the cache row
   const bool two = tid + nt < nx;  // the first two pieces of X of this thread (all of them when D_h <= 2 nt V)
   const int e0 = (tid < nx ? tid : 0) * V, j0 = e0 / a.D, i0 = e0 - j0 * a.D;
   const int e1 = (two ? tid + nt : 0) * V, j1 = e1 / a.D, i1 = e1 - j1 * a.D;
@@ -282,7 +282,7 @@ __global__ __launch_bounds__(256) void embed_cache_kernel(EmbedArgs a) {
   if constexpr (sizeof(AT) == 2) {
     if (a.conv_W) cw.symbols(a, win, tile);
   }
-  // round 2
+  // second batch of loads: the table pieces the symbols address
   const piece_t xe0 = *reinterpret_cast<const piece_t *>(tabXe + (size_t)s0 * a.D + i0);
   const piece_t xe1 = *reinterpret_cast<const piece_t *>(tabXe + (size_t)s1 * a.D + i1);
   const piece_t xl0 = *reinterpret_cast<const piece_t *>(tabXl + (size_t)s0 * a.D + i0);
