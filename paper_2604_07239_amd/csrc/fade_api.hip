@@ -186,7 +186,7 @@ struct fade_ctx {
   void *WT_o = nullptr, *WT_f = nullptr, *WT_fgv = nullptr, *WT_c = nullptr, *WT_up = nullptr, *WT_down = nullptr, *WT_r = nullptr,
        *WT_conv = nullptr;
   void *WT_mslot = nullptr, *dg_slot = nullptr;  // wide cache slots (c % 64 == 0): W_m's last slot transposed (fragments [Dh][c]), dg [B][c]
-  void *dl = nullptr, *dHout = nullptr, *dnv = nullptr, *dV = nullptr, *dHc = nullptr, *dHexp = nullptr, *dE = nullptr, *du = nullptr,
+  void *dl = nullptr, *dHout = nullptr, *dV = nullptr, *dHc = nullptr, *dHexp = nullptr, *dE = nullptr, *du = nullptr,
        *dHa = nullptr, *dac = nullptr, *dHmix1 = nullptr, *dHmix2 = nullptr, *dy_at = nullptr, *dnc = nullptr, *dar = nullptr,
        *dhm = nullptr, *dcv = nullptr, *dX1 = nullptr, *dX2 = nullptr, *dxl = nullptr;
   void *LT[8] = {};  // left operands of the weight gradients that need a copy: LN(H_coarse), LN(H_mix) row-major (bf16 path); feature-major copies [width][Bp] of all eight (fp32 path)
@@ -841,7 +841,7 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
     Prof p(c, "bwd_out");
     BwdOutArgs a{};
     a.B = B; a.Dh = Dh; a.stats_n = SN; a.ln_part = c->ln_part; a.dH = c->dHout; a.V = c->V; a.Hc = c->Hc; a.stats = c->stats_o; a.gamma = c->P(P_GAMMA_O);
-    a.beta = c->P(P_BETA_O); a.lam = c->P(P_LAMBDA_O); a.dnv = c->dnv; a.dV = c->dV; a.dHc = c->dHc; a.row_dlam = c->row_dlam;
+    a.beta = c->P(P_BETA_O); a.lam = c->P(P_LAMBDA_O); a.dV = c->dV; a.dHc = c->dHc; a.row_dlam = c->row_dlam;
     HIP_TRY(c, fade_bwd_out(a, bf, s));
     rq.push(RB, 2 * Dh, c->ln_part, Gp(P_GAMMA_O));  // gamma_o then beta_o, adjacent in the blob
   }
@@ -1254,7 +1254,7 @@ int fade_create(const fade_config *cfg, fade_ctx **out) {
     if (d.c % 64 == 0) TRY_ALLOC(A(&c->dg_slot, Bp * d.c));
     // gradients that serve as the right operand of a weight-gradient product have Bp rows (padding rows stay zero)
     struct { void **p; size_t n; } bufs[] = {
-        {&c->dl, Bp * 256}, {&c->dHout, BDh}, {&c->dnv, BDh}, {&c->dV, BpDh}, {&c->dHc, BDh}, {&c->dHexp, d.B * d.De},
+        {&c->dl, Bp * 256}, {&c->dHout, BDh}, {&c->dV, BpDh}, {&c->dHc, BDh}, {&c->dHexp, d.B * d.De},
         {&c->dE, Bp * 2 * d.De}, {&c->du, BDh}, {&c->dHa, BpDh}, {&c->dac, BpDh}, {&c->dHmix1, BDh}, {&c->dHmix2, BDh},
         {&c->dy_at, Bp * d.dl}, {&c->dnc, BDh}, {&c->dar, BpDh}, {&c->dhm, BpDh}, {&c->dcv, BDh}, {&c->dX1, BDh}, {&c->dX2, BDh},
         {&c->dxl, BDh},

@@ -198,7 +198,7 @@ struct BwdOutArgs {
   float *ln_part;  // [blocks][2][Dh] partial sums of d gamma, d beta over this workgroup's rows
   const void *dH, *V, *Hc;
   const float *stats, *gamma, *beta, *lam;
-  void *dnv, *dV, *dHc;
+  void *dV, *dHc;
   float *row_dlam;
 };
 struct BwdGateArgs {
