@@ -194,8 +194,9 @@ size_t fade_tap(fade_ctx *ctx, int which, float *out_host, size_t cap_floats);
 int fade_get_weights(fade_ctx *ctx, void *blob_host, size_t nbytes);
 
 /* Debug/test: the gradient of the mean NLL computed by the most recent fade_step_update, in blob layout (fp32).
- * The W_U range is only filled in contexts created with FADE_DEBUG_WU_GRAD=1 in the environment: normally those
- * gradients are consumed inside the kernel that applies them and never reach memory. */
+ * Complete only in contexts created with FADE_DEBUG_WU_GRAD=1 in the environment: normally the W_U gradients, and from
+ * 2048 streams on the sums of the weight gradients that are formed in ranges of the batch, are consumed inside the kernel
+ * that applies them and never reach memory (those ranges of the blob then hold zeros or an older step's values). */
 int fade_debug_grad(fade_ctx *ctx, void *blob_host, size_t nbytes);
 
 /* Per-kernel device time of the most recent fade_encode_device / fade_decode_device, measured with HIP

@@ -214,7 +214,7 @@ struct fade_ctx {
   int *dev_err = nullptr;
   bool rows16 = false;               // fp32 path at very small batches: 16 x 16 product tiles, row statistics per 16 columns
   size_t stats_n = 0;                // partial (sum, sum of squares) pairs per row the statistics buffers hold
-  bool debug_wu_grad = false;        // FADE_DEBUG_WU_GRAD=1 at fade_create: the per-stream gradient is also written to the gradient array
+  bool debug_wu_grad = false;        // FADE_DEBUG_WU_GRAD=1 at fade_create: gradients consumed where they are formed (W_U's, the sums of sliced weight gradients) are also written to the gradient array
   uint32_t *scratch_dev = nullptr;   // this device's copy of the file-scope scratch array (see scratch_for_device)
   size_t loop_n = 0, loop_next = 0;  // job size and next step of the device-resident loop in progress
   int loop_mode = 0;
@@ -323,6 +323,7 @@ int refresh_matrices(fade_ctx *c, bool adam) {
   const bool bf = c->bf16;
   AdamRefreshBatch ab{};
   ab.refresh_only = adam ? 0 : 1;
+  ab.keep_sum = c->debug_wu_grad ? 1 : 0;
   ab.opt = AdamArrays{c->grad, c->master, c->adam_m, c->adam_v, c->ustate, c->cfg.lr, c->cfg.beta1, c->cfg.beta2, c->cfg.eps};
   auto add = [&](int id, size_t K, size_t N, int vcol0, int vstride, size_t VN, void *frag, void *fragT, const float *ga, const float *be, float *fp) {
     AdamMat &m = ab.m[ab.count++];

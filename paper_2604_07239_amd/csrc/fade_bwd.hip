@@ -1244,8 +1244,9 @@ __global__ __launch_bounds__(256) void adam_refresh_kernel(AdamRefreshBatch ab) 
     size_t idx[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) idx[q] = M.off + (size_t)(k0 + (tid >> 4) + 16 * q) * M.N + n0 + c4;
-    // a gradient that arrives as partial sums over ranges of the batch: add them in range order and keep the sum (done
-    // before the other operands are fetched, so that it needs no registers of its own)
+    // a gradient that arrives as partial sums over ranges of the batch: add them in range order (done before the other
+    // operands are fetched, so that it needs no registers of its own); the sum itself only goes to memory in a debug
+    // context, nothing but this step uses it
     const bool parts = !ab.refresh_only && M.gpart != nullptr;
     if (parts) {
       const size_t mat = (size_t)M.K * M.N;
@@ -1255,8 +1256,10 @@ __global__ __launch_bounds__(256) void adam_refresh_kernel(AdamRefreshBatch ab) 
       for (int sp = 1; sp < M.gsplits; ++sp)
 #pragma unroll
         for (int q = 0; q < 4; ++q) g[q] += *reinterpret_cast<const f32x4 *>(M.gpart + sp * mat + (idx[q] - M.off));
+      if (ab.keep_sum) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) *reinterpret_cast<f32x4 *>(const_cast<float *>(ab.opt.grad_base) + idx[q]) = g[q];
+        for (int q = 0; q < 4; ++q) *reinterpret_cast<f32x4 *>(const_cast<float *>(ab.opt.grad_base) + idx[q]) = g[q];
+      }
     }
 #pragma unroll
     for (int q = 0; q < 4; ++q) {

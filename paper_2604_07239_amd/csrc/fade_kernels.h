@@ -324,6 +324,7 @@ struct AdamMat {
 struct AdamRefreshBatch {
   int count, total_blocks;
   int refresh_only;        // no Adam step: rebuild the copies from the master weights as they are (load / reset)
+  int keep_sum;            // a gradient that arrives as slices over ranges of the batch: also store the sum in the gradient array (debug contexts)
   AdamMat m[10];
   AdamArrays opt;
 };
