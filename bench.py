@@ -37,15 +37,15 @@ MiB = 1 << 20
 # (FETCH x 2.0, WRITE x 1.0 against a plain 256 MiB copy, see profiles/cfg2_frozen_pmc_counters.md). A shape that
 # was not profiled reports null.
 ROUTER_GATE_TRAFFIC_BYTES = {
-    (16384, 2048, "frozen"): int(0.5 * (320.4 + 66.2 + 314.4 + 66.1) * MiB),   # profiles/cfg5_frozen_kernel_trace_and_hbm.md (cfg 2's 16-step passes have the same shape)
-    (16384, 2048, "online"): int(0.5 * (320.4 + 130.4 + 314.2 + 130.3) * MiB), # profiles/cfg5_online_kernel_trace_and_hbm.md
+    (16384, 2048, "frozen"): int(0.5 * (320.4 + 66.2 + 314.1 + 66.1) * MiB),   # profiles/cfg5_frozen_kernel_trace_and_hbm.md (cfg 2's 16-step passes have the same shape)
+    (16384, 2048, "online"): int(0.5 * (320.4 + 130.4 + 314.1 + 130.3) * MiB), # profiles/cfg5_online_kernel_trace_and_hbm.md
     (1024, 2048, "online"): int(0.5 * (56.4 + 53.5) * MiB),                    # profiles/cfg2_online_kernel_trace_and_hbm.md
 }
 # the same for the fp32 small-batch product (gemm_f32_rows_kernel) by (B, D_h, mode): profiles/cfg1_kernel_trace_and_hbm.md
 F32_ROUTER_GATE_TRAFFIC_BYTES = {(16, 512, "frozen"): int(0.5 * (2.46 + 0.05 + 2.40 + 0.05) * MiB), (16, 512, "online"): int(0.5 * (2.46 + 0.08 + 2.40 + 0.08) * MiB)}
 # adam_refresh_kernel by (parameters of the nine big matrices, mode), same counter runs
 ADAM_TRAFFIC_BYTES = {(11272192, "online"): int((171.59 + 167.46) * MiB),      # profiles/cfg2_online_kernel_trace_and_hbm.md
-                      (13369344, "online"): int((349.5 + 242.9) * MiB)}        # profiles/cfg5_online_kernel_trace_and_hbm.md
+                      (13369344, "online"): int((349.5 + 194.5) * MiB)}        # profiles/cfg5_online_kernel_trace_and_hbm.md
 
 
 def parse():
