@@ -1701,7 +1701,9 @@ static bool tn_shape(int M, int N, int &kind, int &bm, int &bn) {
 // more (fewer would need ranges of the batch shorter than the pipeline is worth). At B = 4096 the grouped 128 x 128 tiles
 // are faster (gate and router phases 104 / 106 us against 138 / 138, and 31 us less in the Adam pass).
 bool fade_gemm_tn2_ok(int M, int N, int K) {
-  return M > 0 && M % 256 == 0 && N % 256 == 0 && K >= 8192 && (M / 256) * (N / 256) >= 16 && fade_gemm_tune() != 26;
+  static int mink = -1;  // rows of the batch from which the 256 x 256 weight-gradient tiles are used (sweeps: FADE_TN2_MINK)
+  if (mink < 0) { const char *e = getenv("FADE_TN2_MINK"); mink = e ? atoi(e) : 8192; }
+  return M > 0 && M % 256 == 0 && N % 256 == 0 && K >= mink && (M / 256) * (N / 256) >= 16 && fade_gemm_tune() != 26;
 }
 int fade_gemm_tn_tiles(int M, int N) {
   int kind, bm, bn;
