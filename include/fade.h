@@ -52,8 +52,8 @@ typedef struct {
   uint32_t ablation;     /* which prefix of the model feeds the output head (the paper's progressive ablation):
                           * 0 or 5 the full model; 1 the global stream alone (H_global, Eq. 3); 2 the decoupler (H_mix,
                           * Eq. 6); 3 channel interaction without its gate (H_a + lambda_c H_mix); 4 with the gate
-                          * (H_coarse, Eq. 8). Levels 1-4: FADE_BF16 only; with FADE_ONLINE_ADAM the stages behind the cut get no
-                          * gradient and stay as loaded. The weight blob is the same. */
+                          * (H_coarse, Eq. 8). With FADE_ONLINE_ADAM the stages behind the cut get no gradient and stay as
+                          * loaded. The weight blob is the same. */
   uint32_t dtype;        /* FADE_F32 | FADE_BF16 */
   uint32_t update_mode;  /* FADE_FROZEN | FADE_ONLINE_ADAM */
   float lr, beta1, beta2, eps; /* Adam; 0 => 1e-3, 0.9, 0.999, 1e-8 */

@@ -72,7 +72,6 @@ int resolve_dims(const fade_config &cfg, Dims &d, std::string *why) {
 int check_kernel_limits(const fade_config &cfg, const Dims &d, std::string *why) {
   auto bad = [&](const char *m) { if (why) *why = m; return FADE_E_BAD_CONFIG; };
   if (d.dl != 64) return bad("kernels need d_low == 64");
-  if (cfg.ablation >= 1 && cfg.ablation <= 4 && cfg.dtype != FADE_BF16) return bad("ablation levels 1-4 are built for the bf16 path only");
   if (d.Dh % 128) return bad("kernels need T*D to be a multiple of 128");
   if (d.Dc % 64 || d.Dc > 4096) return bad("kernels need D_cache to be a multiple of 64, at most 4096");
   if (d.De % 64 || d.De > 8192) return bad("kernels need D_e to be a multiple of 64, at most 8192");
@@ -426,6 +425,9 @@ int forward_f32(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint
   const bool bf = false;
   const int B = (int)d.B, Dh = (int)d.Dh, SN = (int)c->stats_n;
   const int r16 = c->rows16 ? 1 : 0;
+  // progressive ablation (the paper's component table): the head reads the last stage that is switched on
+  const int level = c->cfg.ablation == 0 ? 5 : (int)c->cfg.ablation;
+  const void *feat = c->Hg;
   {
     Prof p(c, "embed_cache");
     EmbedArgs a{};
@@ -434,7 +436,7 @@ int forward_f32(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint
     a.X = c->X; a.XL = c->XL; a.M = c->M; a.GG = c->GG; a.GV = c->GV;
     HIP_TRY(c, fade_embed_cache(a, B, bf, s));
   }
-  {  // Eq. 4
+  if (level >= 2) {  // Eq. 4
     Prof p(c, "gemm_conv");
     GemmArgs g{};
     g.M = (int)(d.B * d.T); g.N = (int)d.D; g.K = (int)d.Kc;
@@ -451,7 +453,8 @@ int forward_f32(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint
     g.rows16 = r16;
     HIP_TRY(c, fade_gemm(GEMM_GLOBAL, bf, g, s));
   }
-  {  // Eq. 5-6
+  if (level >= 2) {  // Eq. 5-6
+    feat = c->Hmix;
     Prof p(c, "gemm_router");
     GemmArgs g{};
     g.M = B; g.N = Dh; g.K = Dh;
@@ -460,7 +463,7 @@ int forward_f32(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint
     g.rows16 = r16;
     HIP_TRY(c, fade_gemm(GEMM_ROUTER, bf, g, s));
   }
-  {  // Eq. 7: Down(LN(H_mix))
+  if (level >= 3) {  // Eq. 7: Down(LN(H_mix))
     Prof p(c, "gemm_down");
     GemmArgs g{};
     g.M = B; g.N = (int)d.dl; g.K = Dh;
@@ -469,11 +472,12 @@ int forward_f32(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint
     g.rows16 = r16;
     HIP_TRY(c, fade_gemm(GEMM_DOWN, bf, g, s));
   }
-  {  // Eq. 7: the per-stream memory
+  if (level >= 3) {  // Eq. 7: the per-stream memory
     Prof p(c, "bmm_wu");
     HIP_TRY(c, fade_bmm(c->y, c->WU_c, c->z, B, bf, s));
   }
-  {  // Eq. 7: Up
+  if (level >= 3) {  // Eq. 7: Up
+    feat = c->Hc;
     Prof p(c, "gemm_up");
     GemmArgs g{};
     g.M = B; g.N = Dh; g.K = (int)d.dl;
@@ -481,7 +485,11 @@ int forward_f32(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint
     g.rows16 = r16;
     HIP_TRY(c, fade_gemm(GEMM_UP, bf, g, s));
   }
-  {  // Eq. 8
+  if (level == 3) {  // Eq. 8 without its gate
+    Prof p(c, "residual_add");
+    HIP_TRY(c, fade_residual_add(c->Ha, c->Hmix, c->P(P_LAMBDA_C), c->Hc, (size_t)B * Dh, false, s));
+  }
+  if (level >= 4) {  // Eq. 8
     Prof p(c, "gemm_gate");
     GemmArgs g{};
     g.M = B; g.N = Dh; g.K = Dh;
@@ -490,7 +498,7 @@ int forward_f32(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint
     g.rows16 = r16;
     HIP_TRY(c, fade_gemm(GEMM_GATE, bf, g, s));
   }
-  {  // Eq. 9
+  if (level >= 5) {  // Eq. 9
     Prof p(c, "gemm_fnr_in");
     GemmArgs g{};
     g.M = B; g.N = (int)(2 * d.De); g.K = Dh;
@@ -499,7 +507,7 @@ int forward_f32(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint
     g.rows16 = r16;
     HIP_TRY(c, fade_gemm(GEMM_FNR_IN, bf, g, s));
   }
-  {  // Eq. 10: H_expand W_f (+ statistics for its LayerNorm)
+  if (level >= 5) {  // Eq. 10: H_expand W_f (+ statistics for its LayerNorm)
     Prof p(c, "gemm_fnr_out");
     GemmArgs g{};
     g.M = B; g.N = Dh; g.K = (int)d.De;
@@ -507,14 +515,21 @@ int forward_f32(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uint
     g.rows16 = r16;
     HIP_TRY(c, fade_gemm(GEMM_FNR_OUT, bf, g, s));
   }
-  if (c->online) {  // the update needs H itself (for dW_o); frozen mode forms it only inside the head's operand load
+  if (c->online && level >= 5) {  // the update needs H itself (for dW_o); frozen mode forms it only inside the head's operand load
     Prof p(c, "hout");
     HoutArgs a{};
     a.B = B; a.Dh = Dh; a.stats_n = SN; a.V = c->V; a.Hc = c->Hc; a.stats = c->stats_o; a.gamma = c->P(P_GAMMA_O);
     a.beta = c->P(P_BETA_O); a.lam = c->P(P_LAMBDA_O); a.Hout = c->Hout;
     HIP_TRY(c, fade_hout(a, false, s));
   }
-  {  // Eq. 10's tail fused into the head's operand load; logits = H W_o + b_o
+  if (level < 5) {  // the head on the last stage that is switched on: logits = feat W_o + b_o
+    Prof p(c, "gemm_head");
+    GemmArgs g{};
+    g.M = B; g.N = 256; g.K = Dh;
+    g.A = feat; g.lda = Dh; g.W = c->Wo_c; g.C = c->logits; g.ldc = 256; g.bias = c->P(P_BO);
+    g.rows16 = r16;
+    HIP_TRY(c, fade_gemm(GEMM_HEAD_PLAIN, bf, g, s));
+  } else {  // Eq. 10's tail fused into the head's operand load; logits = H W_o + b_o
     Prof p(c, "gemm_head");
     GemmArgs g{};
     g.M = B; g.N = 256; g.K = Dh;
@@ -618,7 +633,7 @@ int forward_bf16(fade_ctx *c, const WinSrc &ws, int mode, uint8_t *sym_base, uin
   }
   if (level == 3) {  // Eq. 8 without its gate
     Prof p(c, "residual_add");
-    HIP_TRY(c, fade_residual_add(c->Ha, c->Hmix, c->P(P_LAMBDA_C), c->Hc, (size_t)B * Dh, s));
+    HIP_TRY(c, fade_residual_add(c->Ha, c->Hmix, c->P(P_LAMBDA_C), c->Hc, (size_t)B * Dh, true, s));
   }
   if (level >= 4) {  // Eq. 8
     Prof p(c, "gemm_gate");
@@ -820,7 +835,7 @@ int backward(fade_ctx *c, const WinSrc &ws, const uint8_t *targets, long long ts
       tb.t[tb.count] = tr_desc(c, src, width, dst, st, ga, be);
       tb.N[tb.count++] = width;
     };
-    add(c->Hout, Dh, c->LT[0], nullptr, nullptr, nullptr);
+    add(feat, Dh, c->LT[0], nullptr, nullptr, nullptr);  // the stage the head reads (H of Eq. 10 with every stage on)
     add(c->Hexp, De, c->LT[1], nullptr, nullptr, nullptr);
     add(c->Hc, Dh, c->LT[2], c->stats_f, c->P(P_GAMMA_F), c->P(P_BETA_F));   // u = LN(H_coarse)
     add(c->Hmix, Dh, c->LT[3], nullptr, nullptr, nullptr);

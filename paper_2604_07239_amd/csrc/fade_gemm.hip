@@ -1832,6 +1832,7 @@ hipError_t fade_gemm(int op, bool bf16, const GemmArgs &g, hipStream_t s) {
       case GEMM_FNR_IN:   return launch_f32_rows<PRO_LN, EPI_GEGLU>(g, s);
       case GEMM_FNR_OUT:  return launch_f32_rows<PRO_PLAIN, EPI_STORE>(g, s);
       case GEMM_HEAD:     return launch_f32_rows<PRO_FINAL, EPI_STORE_F32>(g, s);
+      case GEMM_HEAD_PLAIN: return launch_f32_rows<PRO_PLAIN, EPI_STORE_F32>(g, s);
       case GEMM_X_STORE:  return launch_f32_rows<PRO_PLAIN, EPI_STORE>(g, s);  // W passed transposed (wt = 1)
       case GEMM_PARTIAL:  // one range only: a plain fp32 store
         if (g.splits > 1 || g.sum_splits) return hipErrorInvalidValue;
@@ -1849,6 +1850,7 @@ hipError_t fade_gemm(int op, bool bf16, const GemmArgs &g, hipStream_t s) {
     case GEMM_FNR_IN:   return launch_f32<PRO_LN, EPI_GEGLU, true>(g, s);
     case GEMM_FNR_OUT:  return launch_f32<PRO_PLAIN, EPI_STORE, true>(g, s);
     case GEMM_HEAD:     return launch_f32<PRO_FINAL, EPI_STORE_F32, true>(g, s);
+    case GEMM_HEAD_PLAIN: return launch_f32<PRO_PLAIN, EPI_STORE_F32, true>(g, s);
     case GEMM_X_STORE:  // W passed transposed (wt = 1)
       if (g.N % 128 == 0) return launch_f32<PRO_PLAIN, EPI_STORE, true>(g, s);
       return launch_f32<PRO_PLAIN, EPI_STORE, false>(g, s);

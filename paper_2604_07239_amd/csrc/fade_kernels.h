@@ -9,6 +9,7 @@ enum {
   GEMM_W,        // backward: dW = L^T R, reduction over the batch, fp32 gradient out
   GEMM_W_TN,     // the same from row-major operands (bf16 path): A = L [a_rows][lda], W = R [K][ldb], K = padded batch
   GEMM_CONVT,    // backward of Eq. 4 w.r.t. its input
+  GEMM_HEAD_PLAIN,  // fp32 path, ablation levels below 5: logits = A W_o + b_o on the stage the head reads (no Eq. 10 tail)
   GEMM_OP_COUNT
 };
 // Launch one of the model step's products (see fade_gemm.hip). bf16 selects the MFMA path (activations
@@ -133,7 +134,7 @@ struct PrepBatch {
 hipError_t fade_prep_batch(const PrepBatch &pb, hipStream_t s);
 hipError_t fade_convt_build(const float *Wconv, int taps, int D, int Kc, float *V, hipStream_t s);
 hipError_t fade_cci(const CciArgs &a, hipStream_t s);
-hipError_t fade_residual_add(const void *x, const void *y, const float *lam, void *out, size_t n, hipStream_t s);  // bf16: out = x + lam[0] * y
+hipError_t fade_residual_add(const void *x, const void *y, const float *lam, void *out, size_t n, bool bf16, hipStream_t s);  // out = x + lam[0] * y
 hipError_t fade_geglu(const GegluArgs &a, hipStream_t s);
 hipError_t fade_hout(const HoutArgs &a, bool bf16, hipStream_t s);
 hipError_t fade_virtual_copy(const float *W0, const float *W1, int k_real, int K, int N, int interleave, float *out, hipStream_t s);

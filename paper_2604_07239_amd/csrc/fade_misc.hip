@@ -702,6 +702,18 @@ __global__ __launch_bounds__(256) void hout_kernel(HoutArgs a) {
   }
 }
 
+// The same in fp32, 4 elements per thread.
+__global__ __launch_bounds__(256) void residual_add_f32_kernel(const float *x, const float *y, const float *lam, float *out, size_t n4) {
+  const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (t >= n4) return;
+  const f32x4 xv = reinterpret_cast<const f32x4 *>(x)[t], yv = reinterpret_cast<const f32x4 *>(y)[t];
+  const float l = lam[0];
+  f32x4 o;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) o[i] = fmaf(l, yv[i], xv[i]);
+  reinterpret_cast<f32x4 *>(out)[t] = o;
+}
+
 // Eq. 8 with its gate switched off (ablation level 3): out = x + lam * y, 8 bf16 per thread.
 __global__ __launch_bounds__(256) void residual_add_kernel(const bf16_t *x, const bf16_t *y, const float *lam, bf16_t *out, size_t n8) {
   const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -1294,8 +1306,13 @@ hipError_t fade_geglu(const GegluArgs &a, hipStream_t s) {
   hipLaunchKernelGGL(geglu_kernel, dim3(blocks_for((size_t)a.B * (a.De / 8), 256)), dim3(256), 0, s, a);
   return hipGetLastError();
 }
-hipError_t fade_residual_add(const void *x, const void *y, const float *lam, void *out, size_t n, hipStream_t s) {
+hipError_t fade_residual_add(const void *x, const void *y, const float *lam, void *out, size_t n, bool bf16, hipStream_t s) {
   if (n % 8) return hipErrorInvalidValue;
+  if (!bf16) {
+    hipLaunchKernelGGL(residual_add_f32_kernel, dim3(blocks_for(n / 4, 256)), dim3(256), 0, s, static_cast<const float *>(x), static_cast<const float *>(y),
+                       lam, static_cast<float *>(out), n / 4);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(residual_add_kernel, dim3(blocks_for(n / 8, 256)), dim3(256), 0, s, static_cast<const bf16_t *>(x), static_cast<const bf16_t *>(y),
                      lam, static_cast<bf16_t *>(out), n / 8);
   return hipGetLastError();

@@ -143,6 +143,12 @@ def test_online_gradients_ablation_levels(level):
     _grad_check("bf16", 37, 8, 32, 64, seed=30 + level, tol=5e-2, ablation=level)
 
 
+@pytest.mark.parametrize("level", [1, 2, 3, 4])
+def test_online_gradients_ablation_levels_fp32(level):
+    """The same on the fp32 path at the fp32 bar."""
+    _grad_check("f32", 7, 8, 16, 64, seed=60 + level, tol=2e-4, ablation=level)
+
+
 @pytest.mark.parametrize("level", [1, 3])
 def test_online_round_trip_ablation_levels(level):
     need_gpu()
