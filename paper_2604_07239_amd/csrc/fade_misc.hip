@@ -367,6 +367,7 @@ __global__ __launch_bounds__(256) void embed_cache_lds_kernel(EmbedArgs a) {
   const int wps = a.T / 32, grp = wave / wps, tile = wave - grp * wps, ngrp = 4 / wps;  // wavefronts per stream, streams per workgroup
   const int nt = wps * 64, vt = tid - grp * nt;                                          // threads per stream, this one's index
   const int np = a.Dc / 8, sh = a.c / 8, ksteps = conv_ksteps(a);
+  const bool half_shift = a.c == 4;  // slots of four elements: Eq. 2 shifts the row by half a 16-byte piece
   for (int i = tid; i < 1024; i += 256) {
     reinterpret_cast<f32x4 *>(sXe)[i] = static_cast<const f32x4 *>(a.tabXe)[i];
     reinterpret_cast<f32x4 *>(sXl)[i] = static_cast<const f32x4 *>(a.tabXl)[i];
@@ -469,7 +470,22 @@ __global__ __launch_bounds__(256) void embed_cache_lds_kernel(EmbedArgs a) {
       conv_tile_store(a, (size_t)b, tile, h, p);
       // Eq. 2: the row shifted left by one slot; all of its pieces sit in one wavefront, read two turns ago
       bf16_t *M = static_cast<bf16_t *>(a.M) + (size_t)b * a.Dc;
-      if (vt < np && vt >= sh) reinterpret_cast<f32x4 *>(M)[vt - sh] = cur.kp;
+      if (half_shift) {
+        // new piece q = upper half of old piece q, lower half of old piece q + 1 (the row's pieces sit in consecutive lanes
+        // of one wavefront); the last piece keeps its lower half for the slot appended below
+        const float n0 = __shfl_down(cur.kp[0], 1, 64), n1 = __shfl_down(cur.kp[1], 1, 64);
+        if (vt < np - 1) {
+          f32x4 v;
+          v[0] = cur.kp[2]; v[1] = cur.kp[3]; v[2] = n0; v[3] = n1;
+          reinterpret_cast<f32x4 *>(M)[vt] = v;
+        } else if (vt == np - 1) {
+          float2 v;
+          v.x = cur.kp[2]; v.y = cur.kp[3];
+          *reinterpret_cast<float2 *>(M + a.Dc - 8) = v;
+        }
+      } else if (vt < np && vt >= sh) {
+        reinterpret_cast<f32x4 *>(M)[vt - sh] = cur.kp;
+      }
       if (vt < a.c) {  // ... and Eq. 1's GeGLU of the newest symbol appended
         if constexpr (UPD) {
           M[a.Dc - a.c + vt] = (bf16_t)(gelu_f(cs.gg) * cs.gv);
@@ -1247,7 +1263,7 @@ hipError_t fade_embed_cache(const EmbedArgs &a, int B, bool bf16, hipStream_t s)
   int nt = 256;
   if (a.conv_W && a.T % 32 == 0 && a.T < 128 && a.c % 8 == 0 && a.Dc / 8 <= 4 * 2 * a.T && a.c <= 2 * a.T) nt = 2 * a.T;
   const bool frozen_shape = a.slot_tab && !a.XL && !a.cv, adapting_shape = !a.slot_tab && a.gg_tab && a.gv_tab;
-  if (bf16 && a.conv_W && (a.T == 32 || a.T == 64 || a.T == 128) && a.c % 8 == 0 && a.Dc / 8 <= 64 && a.c <= 64 && a.Dh == a.T * 32 && a.ws.i >= a.T &&
+  if (bf16 && a.conv_W && (a.T == 32 || a.T == 64 || a.T == 128) && (a.c % 8 == 0 || a.c == 4) && a.Dc % 8 == 0 && a.Dc / 8 <= 64 && a.c <= 64 && a.Dh == a.T * 32 && a.ws.i >= a.T &&
       (a.ws.active || a.ws.n >= a.T) && (frozen_shape || adapting_shape) && B >= 1) {
     static const int per_cu = getenv("FADE_EMBED_WGS") ? atoi(getenv("FADE_EMBED_WGS")) : 3;
     EmbedArgs p = a;

@@ -149,12 +149,13 @@ def test_step_parity_bf16_small(B):
     _step_parity(B, 8, 32, 64, "bf16", steps=11, randomize=True, seed=B)
 
 
-@pytest.mark.parametrize("B,T", [(5, 32), (7, 64), (67, 32)])
-def test_step_parity_bf16_window_kernel_with_tables_in_lds(B, T):
-    """T = 32 / 64 at D = 32: the window / cache / conv step runs as the kernel that keeps the per-symbol tables in LDS and
+@pytest.mark.parametrize("B,T,c", [(5, 32, 8), (7, 64, 8), (67, 32, 8), (5, 32, 4), (7, 64, 4), (67, 64, 4), (9, 32, 16)])
+def test_step_parity_bf16_window_kernel_with_tables_in_lds(B, T, c):
+    """T = 32 / 64 at D = 32 with cache slots of 8, 16 or 4 elements (4: the benchmark configurations 2-4, whose roll of Eq. 2
+    is half a 16-byte piece): the window / cache / conv step runs as the kernel that keeps the per-symbol tables in LDS and
     walks over streams (4 or 2 streams side by side per workgroup), here with a stream count that is no multiple of that
-    and, at step 1, masked streams that must not advance."""
-    _step_parity(B, T, 32, 64, "bf16", steps=4, randomize=True, seed=B + T)
+    and, at step 1, masked streams that must not advance. Ten steps: the rolled cache holds entries of several steps."""
+    _step_parity(B, T, 32, 64, "bf16", steps=10, randomize=True, seed=B + T + c, d_cache=c * T)
 
 
 def test_step_parity_bf16_wide_cache():
