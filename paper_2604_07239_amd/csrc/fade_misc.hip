@@ -293,7 +293,11 @@ __global__ __launch_bounds__(256) void embed_cache_kernel(EmbedArgs a) {
     if (a.conv_W) cw.operands(a, reinterpret_cast<const bf16_t *>(tabXl));
   }
   float gg = 0.0f, gv = 0.0f;  // adapting weights: Eq. 1's two pre-activations of the newest symbol, in the same round
-  if (!a.slot_tab && tid < a.c) slot_pair(a.tabXe32 + (size_t)slast * a.D, a.Wg, a.Wv, a.D, a.c, tid, gg, gv);
+  if (!a.slot_tab && tid < a.c) {
+    // per symbol they are a table too where the refresh builds it (same operations in the same order, so the same bits)
+    if (a.gg_tab) { gg = a.gg_tab[(size_t)slast * a.c + tid]; gv = a.gv_tab[(size_t)slast * a.c + tid]; }
+    else slot_pair(a.tabXe32 + (size_t)slast * a.D, a.Wg, a.Wv, a.D, a.c, tid, gg, gv);
+  }
   // stores and arithmetic
   if (tid < nx) {
     *reinterpret_cast<piece_t *>(X + e0) = xe0;
