@@ -39,12 +39,12 @@ MiB = 1 << 20
 ROUTER_GATE_TRAFFIC_BYTES = {
     (16384, 2048, "frozen"): int(0.5 * (320.4 + 66.2 + 314.1 + 66.1) * MiB),   # profiles/cfg5_frozen_kernel_trace_and_hbm.md (cfg 2's 16-step passes have the same shape)
     (16384, 2048, "online"): int(0.5 * (320.4 + 130.4 + 314.1 + 130.3) * MiB), # profiles/cfg5_online_kernel_trace_and_hbm.md
-    (1024, 2048, "online"): int(0.5 * (56.4 + 53.5) * MiB),                    # profiles/cfg2_online_kernel_trace_and_hbm.md
+    (1024, 2048, "online"): int(0.5 * (48.1 + 8.2 + 45.2 + 8.2) * MiB),                    # profiles/cfg2_online_kernel_trace_and_hbm.md
 }
 # the same for the fp32 small-batch product (gemm_f32_rows_kernel) by (B, D_h, mode): profiles/cfg1_kernel_trace_and_hbm.md
 F32_ROUTER_GATE_TRAFFIC_BYTES = {(16, 512, "frozen"): int(0.5 * (2.46 + 0.05 + 2.40 + 0.05) * MiB), (16, 512, "online"): int(0.5 * (2.46 + 0.08 + 2.40 + 0.08) * MiB)}
 # adam_refresh_kernel by (parameters of the nine big matrices, mode), same counter runs
-ADAM_TRAFFIC_BYTES = {(11272192, "online"): int((171.59 + 167.46) * MiB),      # profiles/cfg2_online_kernel_trace_and_hbm.md
+ADAM_TRAFFIC_BYTES = {(11272192, "online"): int((174.6 + 170.0) * MiB),      # profiles/cfg2_online_kernel_trace_and_hbm.md
                       (13369344, "online"): int((349.5 + 194.5) * MiB)}        # profiles/cfg5_online_kernel_trace_and_hbm.md
 
 
