@@ -363,7 +363,9 @@ __global__ __launch_bounds__(256) void embed_cache_kernel(EmbedArgs a) {
 // covers (window and cache row two streams ahead, the slot entry one stream ahead) and the stores before them are then
 // a turn's arithmetic old. Streams past the end or inactive are read at clamped addresses and store nothing.
 // UPD: the weights adapt (X_l, the pre-activations of Eq. 4 and of Eq. 1 are kept for the update).
-template <int KS, bool UPD>
+// HALF: cache slots of four elements (Eq. 2 shifts the row by half a 16-byte piece); a template argument so that the
+// kernel for whole-piece shifts keeps its instruction schedule.
+template <int KS, bool UPD, bool HALF = false>
 __global__ __launch_bounds__(256) void embed_cache_lds_kernel(EmbedArgs a) {
   __shared__ __align__(16) bf16_t sXe[256 * 32], sXl[256 * 32];
   __shared__ uint8_t sWin[4][128];
@@ -371,7 +373,6 @@ __global__ __launch_bounds__(256) void embed_cache_lds_kernel(EmbedArgs a) {
   const int wps = a.T / 32, grp = wave / wps, tile = wave - grp * wps, ngrp = 4 / wps;  // wavefronts per stream, streams per workgroup
   const int nt = wps * 64, vt = tid - grp * nt;                                          // threads per stream, this one's index
   const int np = a.Dc / 8, sh = a.c / 8, ksteps = conv_ksteps(a);
-  const bool half_shift = a.c == 4;  // slots of four elements: Eq. 2 shifts the row by half a 16-byte piece
   for (int i = tid; i < 1024; i += 256) {
     reinterpret_cast<f32x4 *>(sXe)[i] = static_cast<const f32x4 *>(a.tabXe)[i];
     reinterpret_cast<f32x4 *>(sXl)[i] = static_cast<const f32x4 *>(a.tabXl)[i];
@@ -474,7 +475,7 @@ __global__ __launch_bounds__(256) void embed_cache_lds_kernel(EmbedArgs a) {
       conv_tile_store(a, (size_t)b, tile, h, p);
       // Eq. 2: the row shifted left by one slot; all of its pieces sit in one wavefront, read two turns ago
       bf16_t *M = static_cast<bf16_t *>(a.M) + (size_t)b * a.Dc;
-      if (half_shift) {
+      if constexpr (HALF) {
         // new piece q = upper half of old piece q, lower half of old piece q + 1 (the row's pieces sit in consecutive lanes
         // of one wavefront); the last piece keeps its lower half for the slot appended below
         const float n0 = __shfl_down(cur.kp[0], 1, 64), n1 = __shfl_down(cur.kp[1], 1, 64);
@@ -487,8 +488,8 @@ __global__ __launch_bounds__(256) void embed_cache_lds_kernel(EmbedArgs a) {
           v.x = cur.kp[2]; v.y = cur.kp[3];
           *reinterpret_cast<float2 *>(M + a.Dc - 8) = v;
         }
-      } else if (vt < np && vt >= sh) {
-        reinterpret_cast<f32x4 *>(M)[vt - sh] = cur.kp;
+      } else {
+        if (vt < np && vt >= sh) reinterpret_cast<f32x4 *>(M)[vt - sh] = cur.kp;
       }
       if (vt < a.c) {  // ... and Eq. 1's GeGLU of the newest symbol appended
         if constexpr (UPD) {
@@ -1275,11 +1276,16 @@ hipError_t fade_embed_cache(const EmbedArgs &a, int B, bool bf16, hipStream_t s)
     const int ngrp = 4 / (a.T / 32), want = (B + ngrp - 1) / ngrp;
     const int G = want < 256 * per_cu ? want : 256 * per_cu;
     if (per_cu > 0) {
+      const bool half = a.c == 4;
       if (a.Kc <= 96 || a.taps <= 3) {
-        if (frozen_shape) hipLaunchKernelGGL((embed_cache_lds_kernel<6, false>), dim3(G), dim3(256), 0, s, p);
+        if (half && frozen_shape) hipLaunchKernelGGL((embed_cache_lds_kernel<6, false, true>), dim3(G), dim3(256), 0, s, p);
+        else if (half) hipLaunchKernelGGL((embed_cache_lds_kernel<6, true, true>), dim3(G), dim3(256), 0, s, p);
+        else if (frozen_shape) hipLaunchKernelGGL((embed_cache_lds_kernel<6, false>), dim3(G), dim3(256), 0, s, p);
         else hipLaunchKernelGGL((embed_cache_lds_kernel<6, true>), dim3(G), dim3(256), 0, s, p);
       } else {
-        if (frozen_shape) hipLaunchKernelGGL((embed_cache_lds_kernel<8, false>), dim3(G), dim3(256), 0, s, p);
+        if (half && frozen_shape) hipLaunchKernelGGL((embed_cache_lds_kernel<8, false, true>), dim3(G), dim3(256), 0, s, p);
+        else if (half) hipLaunchKernelGGL((embed_cache_lds_kernel<8, true, true>), dim3(G), dim3(256), 0, s, p);
+        else if (frozen_shape) hipLaunchKernelGGL((embed_cache_lds_kernel<8, false>), dim3(G), dim3(256), 0, s, p);
         else hipLaunchKernelGGL((embed_cache_lds_kernel<8, true>), dim3(G), dim3(256), 0, s, p);
       }
       return hipGetLastError();
