@@ -810,13 +810,39 @@ __device__ __forceinline__ void bwd_slot_body(const BwdSlotArgs &a, int block) {
   __syncthreads();
   // one thread per (stream, channel): the stream's x_t row goes to LDS (zero for an inactive stream: it then adds
   // nothing below), and dxt[channel] = sum_q W_g[channel][q] d gg[q] + W_v[channel][q] d gv[q]
+  const bool wide = a.c >= 64;
   for (int t = tid; t < NS * a.D; t += 256) {
     const int k = t / a.D, i = t - k * a.D, b = block * NS + k;
     xt_s[k][i] = sym_s[k] >= 0 ? a.tabXe32[(size_t)sym_s[k] * a.D + i] : 0.0f;
-    if (b < a.B) {
+    if (b < a.B && !wide) {
       float sv = 0.0f;
       for (int q = 0; q < a.c; ++q) sv += a.Wg[i * a.c + q] * dg_s[k][0][q] + a.Wv[i * a.c + q] * dg_s[k][1][q];
       a.dxt[(size_t)b * a.D + i] = sv;
+    }
+  }
+  if (wide) {
+    // wide slots: a thread walking all c columns of its channel's rows of W_g, W_v reads them with a stride of a whole row
+    // between neighbouring threads. Here a wavefront takes channels wave, wave + 4, ... and its lanes run along the slot
+    // columns (coalesced rows, read once for all of the workgroup's streams); each stream's sum is folded over the lanes in
+    // a fixed butterfly and lane k keeps stream k's.
+    for (int i = wave; i < a.D; i += 4) {
+      float acc[NS];
+#pragma unroll
+      for (int k = 0; k < NS; ++k) acc[k] = 0.0f;
+      for (int q = lane; q < a.c; q += 64) {
+        const float wg = a.Wg[i * a.c + q], wv = a.Wv[i * a.c + q];
+#pragma unroll
+        for (int k = 0; k < NS; ++k) acc[k] = fmaf(wg, dg_s[k][0][q], fmaf(wv, dg_s[k][1][q], acc[k]));
+      }
+      float keep = 0.0f;
+#pragma unroll
+      for (int k = 0; k < NS; ++k) {
+        float sv = acc[k];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) sv += __shfl_xor(sv, off, 64);
+        if (lane == k) keep = sv;
+      }
+      if (lane < NS && block * NS + lane < a.B) a.dxt[(size_t)(block * NS + lane) * a.D + i] = keep;
     }
   }
   __syncthreads();
