@@ -1474,10 +1474,15 @@ hipError_t fade_bwd_slot_conv(const BwdSlotArgs &sa, float *dWgv, const ConvGrad
   if (sa.Dh > 2048 || sa.Dh % 8 || sa.c > 256 || sa.D > 64) return hipErrorInvalidValue;
   if (ca.D != 32 || 128 % ca.T || ca.T < 4 || ca.taps > 4 || !ca.WT || !ca.dxl || ca.Kc % 16 || ca.Kc > 128 || ca.taps * 32 > ca.Kc) return hipErrorInvalidValue;
   const bool narrow = sa.Dh <= 512;
-  const int Ps = narrow ? (sa.B + 15) / 16 : (sa.B + 3) / 4;
+  // narrow rows with wide slots (the paper-default shape: D_h = 512, c = 256): a stream's element-wise part and its share of
+  // the partial sums are long, so two streams per wavefront instead of four (twice the workgroups)
+  static const int spw_env = env_int("FADE_SLOT_SPW");
+  const int spw = narrow ? ((spw_env == 2 || spw_env == 4) ? spw_env : (sa.c >= 64 ? 2 : 4)) : 1;
+  const int Ps = (sa.B + 4 * spw - 1) / (4 * spw);
   const long long nchunks = ((long long)ca.B * ca.T + 127) / 128;
   const int Pc = (int)(nchunks < 512 ? nchunks : 512);
-  if (narrow) hipLaunchKernelGGL((slot_conv_kernel<4, 1>), dim3(Ps + Pc), dim3(256), 0, s, sa, ca, Pc);
+  if (spw == 4) hipLaunchKernelGGL((slot_conv_kernel<4, 1>), dim3(Ps + Pc), dim3(256), 0, s, sa, ca, Pc);
+  else if (spw == 2) hipLaunchKernelGGL((slot_conv_kernel<2, 1>), dim3(Ps + Pc), dim3(256), 0, s, sa, ca, Pc);
   else hipLaunchKernelGGL((slot_conv_kernel<1, 4>), dim3(Ps + Pc), dim3(256), 0, s, sa, ca, Pc);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
